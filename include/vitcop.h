@@ -1,0 +1,209 @@
+/*
+ * libvitcop — MI355X (gfx950) kernels for the pruned-prefill hot path of ViTCoP
+ * (arXiv 2601.17818): the [CLS]-attention filter over vision-encoder tokens
+ * (Sec. 3.1), K-vector-norm saliency with top-k selection (Sec. 3.2.2, Sec. 3.3),
+ * compaction of the survivors, and causal attention over them.
+ *
+ * Conventions for every entry point
+ *  - Plain C ABI.  bf16 tensors are passed as uint16_t bit patterns.
+ *  - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte
+ *    aligned unless stated otherwise, rows contiguous, token-major.
+ *  - The library allocates no device memory and keeps no state between calls.
+ *    Scratch memory comes from the caller through `ws` / `ws_bytes`; the size
+ *    needed is returned by the matching *_workspace_bytes query.  The contents
+ *    of `ws` need not be initialised and are undefined afterwards.
+ *  - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *    Calls enqueue work on it and return without synchronising.
+ *  - Return value: VITCOP_OK or a negative status.  All argument validation
+ *    happens on the host before any HIP call, so invalid arguments are
+ *    reported even on a machine without a GPU.  No exception crosses the ABI.
+ *    vitcop_last_error() returns a thread-local description of the last failure.
+ *  - Outputs are fully overwritten.  Inputs must be finite.
+ */
+#ifndef VITCOP_H
+#define VITCOP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define VITCOP_OK            0
+#define VITCOP_EINVAL      (-1)  /* null/misaligned pointer, negative size, keep > n_vis, Hq % Hkv != 0 ... */
+#define VITCOP_EUNSUPPORTED (-2) /* shape outside what the kernels are built for */
+#define VITCOP_EWORKSPACE  (-3)  /* ws is NULL or smaller than *_workspace_bytes */
+#define VITCOP_EHIP        (-4)  /* a HIP call or launch failed */
+
+/* Largest candidate count the selection kernel ranks per sample. */
+#define VITCOP_MAX_CANDIDATES 16384
+
+/* flags of vitcop_knorm_select */
+#define VITCOP_NORMS_PRECOMPUTED 1u /* `norms` is an input holding the scores to rank */
+#define VITCOP_NORMS_SQUARED     2u /* with PRECOMPUTED: `norms` holds squared norms; it is
+                                       overwritten with their square roots before ranking */
+
+const char* vitcop_last_error(void);
+int vitcop_version(void);
+
+/* ------------------------------------------------------------------------
+ * Stage I filter (Sec. 3.1, Eq. 1; Alg. 1 Stage I).
+ * For each image b and head h, softmax over the N+1 keys of the logits
+ * scale * <q_cls[b,h], k[b,i,h]>; the score of patch i (token i+1) is the
+ * sum over heads of its softmax weight.  [CLS] (token 0) takes part in the
+ * normalisation but is neither scored nor a candidate.  The `keep` highest
+ * scores survive, ties going to the lower index.
+ *   q_cls      [B,H,d]      bf16, query of the [CLS] token
+ *   k          [B,N+1,H,d]  bf16, keys, [CLS] at token 0
+ *   scale      softmax scale; 0 selects 1/sqrt(d)
+ *   scores_out [B,N] fp32, may be NULL
+ *   idx_out    [B,keep] int32, ascending patch indices in [0,N)
+ * d in {64,128}; N <= VITCOP_MAX_CANDIDATES; 0 <= keep <= N.
+ */
+size_t vitcop_filter_visual_workspace_bytes(int B, int N, int H, int d);
+int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k,
+                         int B, int N, int H, int d, int keep, float scale,
+                         float* scores_out, int32_t* idx_out,
+                         void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * K-norm saliency and selection (Sec. 3.2.2, Eq. 4; Alg. 1 Stage III; "a
+ * smaller norm corresponds to higher importance", Sec. 2.2).
+ * norm_i = sqrt(sum over the Hkv heads and d channels of K[b,i,h,c]^2) for the
+ * visual tokens i in [vis_start, vis_start+n_vis).  The `keep` smallest norms
+ * survive, ties going to the lower index.  The output list holds, ascending,
+ * every text position plus the surviving visual positions.
+ *   k              [B,T,Hkv,d] bf16; token rows k_row_stride elements apart,
+ *                  samples k_batch_stride elements apart (so K may sit inside
+ *                  a fused QKV buffer); strides are multiples of 8 elements.
+ *                  May be NULL with VITCOP_NORMS_PRECOMPUTED.
+ *   norms          [B,n_vis] fp32: output, or input when PRECOMPUTED
+ *                  (with SQUARED it is replaced by its square root).
+ *                  Ranking uses exactly the fp32 values left in `norms`.
+ *   keep_idx_out   [B,T'] int32 positions in [0,T), T' = T - n_vis + keep
+ * Hkv*d % 8 == 0; n_vis <= VITCOP_MAX_CANDIDATES; 0 <= keep <= n_vis.
+ */
+size_t vitcop_knorm_select_workspace_bytes(int B, int n_vis);
+int vitcop_knorm_select(const uint16_t* k, int64_t k_row_stride, int64_t k_batch_stride,
+                        int B, int T, int Hkv, int d, int vis_start, int n_vis, int keep,
+                        float* norms, int32_t* keep_idx_out, unsigned flags,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Compaction: the token removal implied by TopK(V_current, ...) in Alg. 1.
+ * dst[b,j,:] = src[b, idx[b,j], :] for up to 8 tensors in one launch.
+ * Out of place only; dst is dense [B,T_out,row_bytes].  row_bytes and the
+ * strides are multiples of 4; a multiple of 16 (with 16-byte aligned
+ * pointers) takes the fast path.  Indices must lie in [0,T_in): this is the
+ * caller's contract and is not checked on the device.
+ */
+typedef struct {
+    const void* src;
+    void*       dst;
+    int64_t     row_bytes;
+    int64_t     src_row_stride_bytes;
+    int64_t     src_batch_stride_bytes;
+} vitcop_gather_t;
+#define VITCOP_MAX_GATHER 8
+int vitcop_compact(const vitcop_gather_t* tensors /* host array */, int n_tensors,
+                   const int32_t* idx /* [B,T_out] device */, int B, int T_in, int T_out,
+                   void* stream);
+
+/* ------------------------------------------------------------------------
+ * Attention over the surviving tokens: exact softmax(scale Q K^T [+ causal]) V,
+ * the computation a FlashAttention kernel performs (Sec. 1, Sec. 2.2; the
+ * 4 N^2 d term of Eq. 7).  Causal order is the order of the rows given, which
+ * is the original order because keep lists ascend.  Query head h reads KV head
+ * h / (Hq/Hkv).  No positional encoding is applied.
+ *   q [B,N,Hq,d], k,v [B,N,Hkv,d] bf16, dense
+ *   out [B,N,Hq,d] bf16;  lse_out [B,Hq,N] fp32 natural-log-sum-exp, may be NULL
+ *   scale 0 selects 1/sqrt(d);  causal 0 or 1
+ * d == 128 (d == 64 is rejected with VITCOP_EUNSUPPORTED in this build).
+ */
+size_t vitcop_prefill_attn_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
+int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
+                        uint16_t* out, float* lse_out,
+                        int B, int N, int Hq, int Hkv, int d, float scale, int causal,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Supporting step: linear projection with the K-norm as a side output
+ * ("K vectors from the LLM's attention module", Sec. 3.2.2).
+ *   y[m, n] = bf16( sum_k x[m,k] * w[n,k] (+ residual[m,n]) ), fp32 accumulate.
+ *   x [M,K] bf16 rows x_row_stride elements apart; w [N,K] bf16 dense
+ *   (out_features x in_features); y [M,N] bf16 rows y_row_stride apart.
+ *   residual: NULL, or [M,N] bf16 with rows res_row_stride apart (added in fp32
+ *   before rounding).
+ *   sumsq_parts: NULL, or fp32 [P][M] with P = vitcop_project_sumsq_parts(N):
+ *   part p holds, per row, the sum of squares of the ROUNDED outputs of a
+ *   fixed group of columns; the P parts added in index order give
+ *   sum_n y[m,n]^2, i.e. the squared K-norm of Eq. 4 without re-reading K.
+ * K % 32 == 0, N % 16 == 0, strides multiples of 8.
+ */
+int vitcop_project_sumsq_parts(int N);
+int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w,
+                   uint16_t* y, int64_t y_row_stride,
+                   const uint16_t* residual, int64_t res_row_stride,
+                   int M, int N, int K, float* sumsq_parts, void* stream);
+
+/* Selection from the projection's side output: adds the P parts in index
+ * order, takes the square root, writes norms_out (may be NULL) and ranks as
+ * vitcop_knorm_select does.  sumsq_parts is [P][part_stride]; the value of
+ * sample b, visual token i is at index b*T + vis_start + i of each part.
+ */
+int vitcop_select_from_sumsq(const float* sumsq_parts, int n_parts, int64_t part_stride,
+                             int B, int T, int vis_start, int n_vis, int keep,
+                             float* norms_out, int32_t* keep_idx_out, void* stream);
+
+/* ------------------------------------------------------------------------
+ * One attention layer of the prefill with pruning on entry (body of the layer
+ * loop of Alg. 1): K projection of all T tokens with the norm side output,
+ * selection, compaction of hidden states and K, Q/V projection of survivors,
+ * causal attention, output projection (+ residual).  keep == n_vis skips the
+ * pruning steps and gives the vanilla layer it is compared with.
+ * All weights are [out_features, in_features] bf16.
+ */
+typedef struct {
+    int B, T, D, Hq, Hkv, d;
+    int vis_start, n_vis, keep;
+    int residual;                 /* 1: y = x_kept + attn_out W_o^T */
+    const uint16_t* x;            /* [B,T,D] */
+    const uint16_t *wq, *wk, *wv, *wo;
+    uint16_t* y;                  /* [B,T',D], T' = T - n_vis + keep */
+    int32_t*  keep_idx;           /* [B,T'] out (may be NULL when keep == n_vis) */
+    float*    norms;              /* [B,n_vis] out, may be NULL */
+    const int32_t* positions_in;  /* [B,T] original positions, may be NULL */
+    int32_t*  positions_out;      /* [B,T'] gathered positions, may be NULL */
+} vitcop_layer_t;
+size_t vitcop_layer_workspace_bytes(const vitcop_layer_t* L);
+int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, void* stream);
+
+/* ------------------------------------------------------------------------
+ * Step-wise schedule (Alg. 1 layer loop, Eq. 8): runs n_layers attention
+ * layers on one batch, pruning on entry to layer prune_layer[s] (0-indexed)
+ * down to prune_keep[s] visual tokens using that layer's own K.
+ * Weights of layer l: wq[l], wk[l], wv[l], wo[l] (host arrays of device
+ * pointers).  h <- h + attention block output; no MLP, no normalisation.
+ *   x [B,T,D] in;  y_out [B,T_final,D];  positions_out [B,T_final] (may be NULL)
+ */
+typedef struct {
+    int B, T, D, Hq, Hkv, d, vis_start, n_vis;
+    int n_layers, n_stages;
+    const int* prune_layer;       /* host, ascending */
+    const int* prune_keep;        /* host, non-increasing, <= n_vis */
+    const uint16_t* x;
+    const uint16_t* const* wq;    /* host arrays, n_layers device pointers each */
+    const uint16_t* const* wk;
+    const uint16_t* const* wv;
+    const uint16_t* const* wo;
+    uint16_t* y_out;
+    int32_t*  positions_out;
+} vitcop_schedule_t;
+size_t vitcop_schedule_workspace_bytes(const vitcop_schedule_t* S);
+int vitcop_schedule_prefill(const vitcop_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* VITCOP_H */

@@ -1,0 +1,320 @@
+"""ctypes binding of libvitcop.so: argument marshalling only.
+
+Every function has the name of the C entry point it calls (include/vitcop.h).
+Tensors are torch CUDA tensors (PyTorch is used for device memory and streams
+only); bf16 tensors may be torch.bfloat16 or 16-bit integer bit patterns.
+Calls enqueue on torch's current stream and do not synchronise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libvitcop.so")
+
+VITCOP_OK = 0
+VITCOP_EINVAL = -1
+VITCOP_EUNSUPPORTED = -2
+VITCOP_EWORKSPACE = -3
+VITCOP_EHIP = -4
+VITCOP_NORMS_PRECOMPUTED = 1
+VITCOP_NORMS_SQUARED = 2
+VITCOP_MAX_CANDIDATES = 16384
+
+EXPORTS = (
+    "vitcop_last_error", "vitcop_version",
+    "vitcop_filter_visual_workspace_bytes", "vitcop_filter_visual",
+    "vitcop_knorm_select_workspace_bytes", "vitcop_knorm_select",
+    "vitcop_compact",
+    "vitcop_prefill_attn_workspace_bytes", "vitcop_prefill_attn",
+    "vitcop_project_sumsq_parts", "vitcop_project", "vitcop_select_from_sumsq",
+    "vitcop_layer_workspace_bytes", "vitcop_layer_prefill",
+    "vitcop_schedule_workspace_bytes", "vitcop_schedule_prefill",
+)
+
+
+class VitcopError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libvitcop error {code}: {msg}")
+        self.code = code
+
+
+class GatherT(C.Structure):
+    _fields_ = [("src", C.c_void_p), ("dst", C.c_void_p), ("row_bytes", C.c_int64),
+                ("src_row_stride_bytes", C.c_int64), ("src_batch_stride_bytes", C.c_int64)]
+
+
+class LayerT(C.Structure):
+    _fields_ = [("B", C.c_int), ("T", C.c_int), ("D", C.c_int), ("Hq", C.c_int), ("Hkv", C.c_int),
+                ("d", C.c_int), ("vis_start", C.c_int), ("n_vis", C.c_int), ("keep", C.c_int),
+                ("residual", C.c_int),
+                ("x", C.c_void_p), ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p),
+                ("wo", C.c_void_p), ("y", C.c_void_p), ("keep_idx", C.c_void_p),
+                ("norms", C.c_void_p), ("positions_in", C.c_void_p), ("positions_out", C.c_void_p)]
+
+
+class ScheduleT(C.Structure):
+    _fields_ = [("B", C.c_int), ("T", C.c_int), ("D", C.c_int), ("Hq", C.c_int), ("Hkv", C.c_int),
+                ("d", C.c_int), ("vis_start", C.c_int), ("n_vis", C.c_int),
+                ("n_layers", C.c_int), ("n_stages", C.c_int),
+                ("prune_layer", C.POINTER(C.c_int)), ("prune_keep", C.POINTER(C.c_int)),
+                ("x", C.c_void_p),
+                ("wq", C.POINTER(C.c_void_p)), ("wk", C.POINTER(C.c_void_p)),
+                ("wv", C.POINTER(C.c_void_p)), ("wo", C.POINTER(C.c_void_p)),
+                ("y_out", C.c_void_p), ("positions_out", C.c_void_p)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it with `python -m paper_2601_17818_amd.build` "
+            "(there is no fallback path)")
+    lib = C.CDLL(_LIB_PATH)
+    vp, i32, i64, f32, sz, u32 = C.c_void_p, C.c_int, C.c_int64, C.c_float, C.c_size_t, C.c_uint
+    lib.vitcop_last_error.restype = C.c_char_p
+    lib.vitcop_last_error.argtypes = []
+    lib.vitcop_version.restype = i32
+    lib.vitcop_filter_visual_workspace_bytes.restype = sz
+    lib.vitcop_filter_visual_workspace_bytes.argtypes = [i32] * 4
+    lib.vitcop_filter_visual.restype = i32
+    lib.vitcop_filter_visual.argtypes = [vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.vitcop_knorm_select_workspace_bytes.restype = sz
+    lib.vitcop_knorm_select_workspace_bytes.argtypes = [i32, i32]
+    lib.vitcop_knorm_select.restype = i32
+    lib.vitcop_knorm_select.argtypes = [vp, i64, i64, i32, i32, i32, i32, i32, i32, i32, vp, vp, u32,
+                                        vp, sz, vp]
+    lib.vitcop_compact.restype = i32
+    lib.vitcop_compact.argtypes = [C.POINTER(GatherT), i32, vp, i32, i32, i32, vp]
+    lib.vitcop_prefill_attn_workspace_bytes.restype = sz
+    lib.vitcop_prefill_attn_workspace_bytes.argtypes = [i32] * 5
+    lib.vitcop_prefill_attn.restype = i32
+    lib.vitcop_prefill_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, i32, vp, sz, vp]
+    lib.vitcop_project_sumsq_parts.restype = i32
+    lib.vitcop_project_sumsq_parts.argtypes = [i32]
+    lib.vitcop_project.restype = i32
+    lib.vitcop_project.argtypes = [vp, i64, vp, vp, i64, vp, i64, i32, i32, i32, vp, vp]
+    lib.vitcop_select_from_sumsq.restype = i32
+    lib.vitcop_select_from_sumsq.argtypes = [vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp]
+    lib.vitcop_layer_workspace_bytes.restype = sz
+    lib.vitcop_layer_workspace_bytes.argtypes = [C.POINTER(LayerT)]
+    lib.vitcop_layer_prefill.restype = i32
+    lib.vitcop_layer_prefill.argtypes = [C.POINTER(LayerT), vp, sz, vp]
+    lib.vitcop_schedule_workspace_bytes.restype = sz
+    lib.vitcop_schedule_workspace_bytes.argtypes = [C.POINTER(ScheduleT)]
+    lib.vitcop_schedule_prefill.restype = i32
+    lib.vitcop_schedule_prefill.argtypes = [C.POINTER(ScheduleT), vp, sz, vp]
+    return lib
+
+
+lib = _load()
+
+
+def vitcop_last_error() -> str:
+    return lib.vitcop_last_error().decode()
+
+
+def _check(rc: int) -> None:
+    if rc != VITCOP_OK:
+        raise VitcopError(rc, vitcop_last_error())
+
+
+def _ptr(t) -> int | None:
+    return None if t is None else t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dense(t: torch.Tensor, name: str) -> torch.Tensor:
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a CUDA tensor")
+    if not t.is_contiguous():
+        raise ValueError(f"{name} must be contiguous")
+    if t.element_size() != 2:
+        raise ValueError(f"{name} must be a 16-bit (bf16) tensor")
+    return t
+
+
+def _ws(nbytes: int, like: torch.Tensor) -> torch.Tensor | None:
+    return torch.empty(max(int(nbytes), 16), dtype=torch.uint8, device=like.device)
+
+
+# --------------------------------------------------------------------------
+
+
+def vitcop_filter_visual(q_cls, k, keep: int, scale: float = 0.0, want_scores: bool = True):
+    """q_cls [B,H,d], k [B,N+1,H,d] -> (scores [B,N] fp32 or None, idx [B,keep] int32)."""
+    _dense(q_cls, "q_cls"); _dense(k, "k")
+    B, N1, H, d = k.shape
+    N = N1 - 1
+    scores = torch.empty((B, N), dtype=torch.float32, device=k.device) if want_scores else None
+    idx = torch.empty((B, max(keep, 0)), dtype=torch.int32, device=k.device)
+    nb = lib.vitcop_filter_visual_workspace_bytes(B, N, H, d)
+    ws = _ws(nb, k)
+    _check(lib.vitcop_filter_visual(_ptr(q_cls), _ptr(k), B, N, H, d, keep, scale, _ptr(scores),
+                                    _ptr(idx), _ptr(ws), ws.numel(), _stream()))
+    return scores, idx
+
+
+def vitcop_knorm_select(k, vis_start: int, n_vis: int, keep: int, *, norms=None, flags: int = 0,
+                        k_row_stride: int | None = None, k_batch_stride: int | None = None,
+                        shape=None):
+    """k [B,T,Hkv,d] -> (norms [B,n_vis] fp32, keep_idx [B,T'] int32).
+
+    With ``flags & VITCOP_NORMS_PRECOMPUTED`` pass ``norms`` (and ``shape`` =
+    (B,T,Hkv,d) when k is None).  Strides default to the dense layout.
+    """
+    if k is not None:
+        B, T, Hkv, d = shape if shape is not None else k.shape
+        if not k.is_cuda or k.element_size() != 2:
+            raise ValueError("k must be a 16-bit CUDA tensor")
+        dev = k.device
+    else:
+        B, T, Hkv, d = shape
+        dev = norms.device
+    rs = Hkv * d if k_row_stride is None else k_row_stride
+    bs = T * rs if k_batch_stride is None else k_batch_stride
+    if norms is None:
+        norms = torch.empty((B, n_vis), dtype=torch.float32, device=dev)
+    idx = torch.empty((B, max(T - n_vis + keep, 0)), dtype=torch.int32, device=dev)
+    _check(lib.vitcop_knorm_select(_ptr(k), rs, bs, B, T, Hkv, d, vis_start, n_vis, keep,
+                                   _ptr(norms), _ptr(idx), flags, None, 0, _stream()))
+    return norms, idx
+
+
+def vitcop_compact(srcs, idx, T_in: int | None = None):
+    """Each src [B,T_in,...] -> dst [B,T_out,...] gathered by idx [B,T_out] (int32)."""
+    srcs = list(srcs)
+    B, T_out = idx.shape
+    arr = (GatherT * max(len(srcs), 1))()
+    outs = []
+    for i, s in enumerate(srcs):
+        if not s.is_cuda or not s.is_contiguous():
+            raise ValueError("sources must be contiguous CUDA tensors")
+        row_bytes = s[0, 0].numel() * s.element_size() if s.dim() > 2 else s.element_size()
+        dst = torch.empty((B, T_out) + tuple(s.shape[2:]), dtype=s.dtype, device=s.device)
+        arr[i] = GatherT(s.data_ptr(), dst.data_ptr(), row_bytes, row_bytes, s.shape[1] * row_bytes)
+        outs.append(dst)
+    t_in = srcs[0].shape[1] if (T_in is None and srcs) else (T_in or 0)
+    _check(lib.vitcop_compact(arr, len(srcs), _ptr(idx), B, t_in, T_out, _stream()))
+    return outs
+
+
+def vitcop_prefill_attn(q, k, v, scale: float = 0.0, causal: bool = True, want_lse: bool = False):
+    """q [B,N,Hq,d], k,v [B,N,Hkv,d] -> (out [B,N,Hq,d] same dtype as q, lse [B,Hq,N] or None)."""
+    _dense(q, "q"); _dense(k, "k"); _dense(v, "v")
+    B, N, Hq, d = q.shape
+    Hkv = k.shape[2]
+    out = torch.empty_like(q)
+    lse = torch.empty((B, Hq, N), dtype=torch.float32, device=q.device) if want_lse else None
+    _check(lib.vitcop_prefill_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, N, Hq, Hkv, d,
+                                   scale, 1 if causal else 0, None, 0, _stream()))
+    return out, lse
+
+
+def vitcop_project_sumsq_parts(N: int) -> int:
+    return lib.vitcop_project_sumsq_parts(N)
+
+
+def vitcop_project(x, w, residual=None, want_sumsq: bool = False):
+    """x [M,K], w [N,K] -> (y [M,N], sumsq_parts [P,M] fp32 or None)."""
+    _dense(x, "x"); _dense(w, "w")
+    M, K = x.shape
+    N = w.shape[0]
+    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+    parts = None
+    if want_sumsq:
+        parts = torch.empty((vitcop_project_sumsq_parts(N), M), dtype=torch.float32, device=x.device)
+    if residual is not None:
+        _dense(residual, "residual")
+    _check(lib.vitcop_project(_ptr(x), K, _ptr(w), _ptr(y), N, _ptr(residual), N, M, N, K,
+                              _ptr(parts), _stream()))
+    return y, parts
+
+
+def vitcop_select_from_sumsq(parts, B: int, T: int, vis_start: int, n_vis: int, keep: int):
+    """parts [P, B*T] fp32 -> (norms [B,n_vis], keep_idx [B,T'])."""
+    P = parts.shape[0]
+    norms = torch.empty((B, n_vis), dtype=torch.float32, device=parts.device)
+    idx = torch.empty((B, T - n_vis + keep), dtype=torch.int32, device=parts.device)
+    _check(lib.vitcop_select_from_sumsq(_ptr(parts), P, parts.shape[1], B, T, vis_start, n_vis, keep,
+                                        _ptr(norms), _ptr(idx), _stream()))
+    return norms, idx
+
+
+class LayerPlan:
+    """Pre-marshalled vitcop_layer_prefill call (descriptor, outputs and workspace
+    are created once; ``run`` only enqueues)."""
+
+    def __init__(self, x, wq, wk, wv, wo, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int,
+                 keep: int, residual: bool = False, want_idx: bool = True, want_norms: bool = True,
+                 positions=None):
+        B, T, D = x.shape
+        Tp = T - n_vis + keep
+        dev = x.device
+        self.tensors = (x, wq, wk, wv, wo, positions)
+        self.y = torch.empty((B, Tp, D), dtype=x.dtype, device=dev)
+        self.keep_idx = torch.empty((B, Tp), dtype=torch.int32, device=dev) if want_idx else None
+        self.norms = torch.empty((B, n_vis), dtype=torch.float32, device=dev) if want_norms else None
+        self.positions_out = (torch.empty((B, Tp), dtype=torch.int32, device=dev)
+                              if positions is not None else None)
+        self.desc = LayerT(B, T, D, Hq, Hkv, d, vis_start, n_vis, keep, 1 if residual else 0,
+                           _ptr(x), _ptr(wq), _ptr(wk), _ptr(wv), _ptr(wo), _ptr(self.y),
+                           _ptr(self.keep_idx), _ptr(self.norms), _ptr(positions),
+                           _ptr(self.positions_out))
+        nb = lib.vitcop_layer_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, x)
+
+    def run(self):
+        _check(lib.vitcop_layer_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        return self.y
+
+
+def vitcop_layer_prefill(x, wq, wk, wv, wo, Hq, Hkv, d, vis_start, n_vis, keep, residual=False,
+                         positions=None):
+    """One pruned attention layer.  Returns dict(y, keep_idx, norms, positions)."""
+    plan = LayerPlan(x, wq, wk, wv, wo, Hq, Hkv, d, vis_start, n_vis, keep, residual,
+                     positions=positions)
+    plan.run()
+    return {"y": plan.y, "keep_idx": plan.keep_idx, "norms": plan.norms,
+            "positions": plan.positions_out}
+
+
+class SchedulePlan:
+    """Pre-marshalled vitcop_schedule_prefill call."""
+
+    def __init__(self, x, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, schedule):
+        B, T, D = x.shape
+        n_layers = len(weights)
+        self.keepalive = (x, weights)
+        layers = [int(s[0]) for s in schedule]
+        keeps = [int(s[1]) for s in schedule]
+        self._pl = (C.c_int * max(len(layers), 1))(*layers)
+        self._pk = (C.c_int * max(len(keeps), 1))(*keeps)
+        self._w = {n: (C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights])
+                   for n in ("wq", "wk", "wv", "wo")}
+        T_final = T - n_vis + (keeps[-1] if keeps else n_vis)
+        self.y = torch.empty((B, T_final, D), dtype=x.dtype, device=x.device)
+        self.positions = torch.empty((B, T_final), dtype=torch.int32, device=x.device)
+        self.desc = ScheduleT(B, T, D, Hq, Hkv, d, vis_start, n_vis, n_layers, len(layers),
+                              self._pl, self._pk, _ptr(x), self._w["wq"], self._w["wk"],
+                              self._w["wv"], self._w["wo"], _ptr(self.y), _ptr(self.positions))
+        nb = lib.vitcop_schedule_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, x)
+
+    def run(self):
+        _check(lib.vitcop_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        return self.y
+
+
+def vitcop_schedule_prefill(x, weights, Hq, Hkv, d, vis_start, n_vis, schedule):
+    plan = SchedulePlan(x, weights, Hq, Hkv, d, vis_start, n_vis, schedule)
+    plan.run()
+    return plan.y, plan.positions

@@ -1,0 +1,420 @@
+// C ABI of libvitcop: argument validation on the host (before any HIP call),
+// then kernel launches on the caller's stream.  See include/vitcop.h for the
+// contract of each entry point.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+
+#include "vitcop_internal.h"
+
+namespace vitcop {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+int hip_status(hipError_t e, const char* what) {
+    if (e == hipSuccess) return VITCOP_OK;
+    return fail(VITCOP_EHIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+int launch_status(const char* kernel_name) { return hip_status(hipGetLastError(), kernel_name); }
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
+struct Carver {   // hands out 256-byte aligned pieces of the caller's workspace
+    char* base;
+    size_t used = 0;
+    explicit Carver(void* p) : base(static_cast<char*>(p)) {}
+    template <typename T>
+    T* take(size_t bytes) {
+        T* r = reinterpret_cast<T*>(base + used);
+        used += up256(bytes);
+        return r;
+    }
+};
+
+}  // namespace vitcop
+
+using namespace vitcop;
+
+#define REQUIRE(cond, code, ...)                     \
+    do {                                             \
+        if (!(cond)) return fail(code, __VA_ARGS__); \
+    } while (0)
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+const char* vitcop_last_error(void) { return g_err; }
+int vitcop_version(void) { return 1; }
+
+/* ---------------------------------------------------------------- filter */
+
+size_t vitcop_filter_visual_workspace_bytes(int B, int N, int H, int d) {
+    if (B < 0 || N < 0 || H < 0 || d < 0) return 0;
+    return up256((size_t)B * H * ((size_t)N + 1) * sizeof(float));
+}
+
+int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
+                         int keep, float scale, float* scores_out, int32_t* idx_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+    REQUIRE(B >= 0 && N >= 1 && H >= 1, VITCOP_EINVAL, "filter_visual: B=%d N=%d H=%d", B, N, H);
+    REQUIRE(keep >= 0 && keep <= N, VITCOP_EINVAL, "filter_visual: keep=%d outside [0,%d]", keep, N);
+    REQUIRE(d == 64 || d == 128, VITCOP_EUNSUPPORTED, "filter_visual: d=%d (64 or 128)", d);
+    REQUIRE(N <= VITCOP_MAX_CANDIDATES, VITCOP_EUNSUPPORTED, "filter_visual: N=%d > %d", N,
+            VITCOP_MAX_CANDIDATES);
+    REQUIRE(H <= 256 && (long)H * d <= 2048, VITCOP_EUNSUPPORTED, "filter_visual: H*d=%ld > 2048",
+            (long)H * d);
+    REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "filter_visual: scale");
+    if (B == 0) return VITCOP_OK;
+    REQUIRE(q_cls && k && (idx_out || keep == 0), VITCOP_EINVAL, "filter_visual: null pointer");
+    REQUIRE(aligned16(q_cls) && aligned16(k), VITCOP_EINVAL, "filter_visual: q_cls/k not 16-byte aligned");
+    REQUIRE(ws && ws_bytes >= vitcop_filter_visual_workspace_bytes(B, N, H, d), VITCOP_EWORKSPACE,
+            "filter_visual: workspace needs %zu bytes", vitcop_filter_visual_workspace_bytes(B, N, H, d));
+    if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
+    return launch_filter(q_cls, k, B, N, H, d, keep, scale, scores_out, idx_out,
+                         static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+}
+
+/* --------------------------------------------------------- knorm + select */
+
+size_t vitcop_knorm_select_workspace_bytes(int B, int n_vis) {
+    (void)B; (void)n_vis;
+    return 0;   // norms are written straight to the caller's `norms`
+}
+
+int vitcop_knorm_select(const uint16_t* k, int64_t k_row_stride, int64_t k_batch_stride, int B,
+                        int T, int Hkv, int d, int vis_start, int n_vis, int keep, float* norms,
+                        int32_t* keep_idx_out, unsigned flags, void* ws, size_t ws_bytes,
+                        void* stream) {
+    (void)ws; (void)ws_bytes;
+    REQUIRE(B >= 0 && T >= 0 && Hkv >= 1 && d >= 1, VITCOP_EINVAL, "knorm_select: B=%d T=%d Hkv=%d d=%d",
+            B, T, Hkv, d);
+    REQUIRE(vis_start >= 0 && n_vis >= 0 && (long)vis_start + n_vis <= T, VITCOP_EINVAL,
+            "knorm_select: visual span [%d,%d) outside [0,%d)", vis_start, vis_start + n_vis, T);
+    REQUIRE(keep >= 0 && keep <= n_vis, VITCOP_EINVAL, "knorm_select: keep=%d outside [0,%d]", keep, n_vis);
+    REQUIRE((flags & ~(VITCOP_NORMS_PRECOMPUTED | VITCOP_NORMS_SQUARED)) == 0, VITCOP_EINVAL,
+            "knorm_select: unknown flags 0x%x", flags);
+    REQUIRE(!(flags & VITCOP_NORMS_SQUARED) || (flags & VITCOP_NORMS_PRECOMPUTED), VITCOP_EINVAL,
+            "knorm_select: SQUARED needs PRECOMPUTED");
+    REQUIRE(n_vis <= VITCOP_MAX_CANDIDATES, VITCOP_EUNSUPPORTED, "knorm_select: n_vis=%d > %d", n_vis,
+            VITCOP_MAX_CANDIDATES);
+    const long row = (long)Hkv * d;
+    const bool pre = flags & VITCOP_NORMS_PRECOMPUTED;
+    if (!pre) {
+        REQUIRE(row % 8 == 0, VITCOP_EUNSUPPORTED, "knorm_select: Hkv*d=%ld not a multiple of 8", row);
+        REQUIRE(k_row_stride >= row && k_row_stride % 8 == 0 && k_batch_stride % 8 == 0 &&
+                    k_batch_stride >= 0,
+                VITCOP_EINVAL, "knorm_select: strides (%lld, %lld)", (long long)k_row_stride,
+                (long long)k_batch_stride);
+    }
+    if (B == 0 || T == 0) return VITCOP_OK;
+    REQUIRE(keep_idx_out, VITCOP_EINVAL, "knorm_select: keep_idx_out is null");
+    REQUIRE(norms || n_vis == 0, VITCOP_EINVAL, "knorm_select: norms is null");
+    if (!pre) {
+        REQUIRE(k && aligned16(k), VITCOP_EINVAL, "knorm_select: k null or not 16-byte aligned");
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!pre) {
+        int rc = launch_knorm(k, k_row_stride, k_batch_stride, B, (int)row, vis_start, n_vis, norms, s);
+        if (rc) return rc;
+    }
+    const bool sq = flags & VITCOP_NORMS_SQUARED;
+    return launch_select_smallest(norms, 1, 0, n_vis, 0, sq ? 1 : 0, sq ? norms : nullptr, B, T,
+                                  vis_start, n_vis, keep, keep_idx_out, s);
+}
+
+int vitcop_select_from_sumsq(const float* sumsq_parts, int n_parts, int64_t part_stride, int B,
+                             int T, int vis_start, int n_vis, int keep, float* norms_out,
+                             int32_t* keep_idx_out, void* stream) {
+    REQUIRE(B >= 0 && T >= 0 && n_parts >= 1, VITCOP_EINVAL, "select_from_sumsq: B=%d T=%d parts=%d", B, T,
+            n_parts);
+    REQUIRE(vis_start >= 0 && n_vis >= 0 && (long)vis_start + n_vis <= T, VITCOP_EINVAL,
+            "select_from_sumsq: visual span [%d,%d) outside [0,%d)", vis_start, vis_start + n_vis, T);
+    REQUIRE(keep >= 0 && keep <= n_vis, VITCOP_EINVAL, "select_from_sumsq: keep=%d outside [0,%d]", keep,
+            n_vis);
+    REQUIRE(part_stride >= (int64_t)B * T, VITCOP_EINVAL, "select_from_sumsq: part_stride=%lld < B*T",
+            (long long)part_stride);
+    REQUIRE(n_vis <= VITCOP_MAX_CANDIDATES, VITCOP_EUNSUPPORTED, "select_from_sumsq: n_vis=%d > %d", n_vis,
+            VITCOP_MAX_CANDIDATES);
+    if (B == 0 || T == 0) return VITCOP_OK;
+    REQUIRE(sumsq_parts && keep_idx_out, VITCOP_EINVAL, "select_from_sumsq: null pointer");
+    return launch_select_smallest(sumsq_parts, n_parts, part_stride, T, vis_start, 1, norms_out, B, T,
+                                  vis_start, n_vis, keep, keep_idx_out, static_cast<hipStream_t>(stream));
+}
+
+/* ---------------------------------------------------------------- compact */
+
+int vitcop_compact(const vitcop_gather_t* tensors, int n_tensors, const int32_t* idx, int B, int T_in,
+                   int T_out, void* stream) {
+    REQUIRE(n_tensors >= 0 && n_tensors <= VITCOP_MAX_GATHER, VITCOP_EINVAL, "compact: n_tensors=%d", n_tensors);
+    REQUIRE(B >= 0 && T_in >= 0 && T_out >= 0, VITCOP_EINVAL, "compact: B=%d T_in=%d T_out=%d", B, T_in, T_out);
+    REQUIRE(T_out == 0 || T_in > 0, VITCOP_EINVAL, "compact: T_out=%d rows from an empty source", T_out);
+    REQUIRE(n_tensors == 0 || tensors, VITCOP_EINVAL, "compact: tensors is null");
+    if (n_tensors == 0 || B == 0 || T_out == 0) return VITCOP_OK;
+    REQUIRE(idx, VITCOP_EINVAL, "compact: idx is null");
+    for (int i = 0; i < n_tensors; ++i) {
+        const vitcop_gather_t& g = tensors[i];
+        REQUIRE(g.src && g.dst, VITCOP_EINVAL, "compact: tensor %d has a null pointer", i);
+        REQUIRE(g.src != g.dst, VITCOP_EINVAL, "compact: tensor %d is in place", i);
+        REQUIRE(g.row_bytes > 0 && g.row_bytes % 4 == 0 && g.src_row_stride_bytes >= g.row_bytes &&
+                    g.src_row_stride_bytes % 4 == 0 && g.src_batch_stride_bytes >= 0 &&
+                    g.src_batch_stride_bytes % 4 == 0,
+                VITCOP_EINVAL, "compact: tensor %d row_bytes/strides (%lld, %lld, %lld)", i,
+                (long long)g.row_bytes, (long long)g.src_row_stride_bytes,
+                (long long)g.src_batch_stride_bytes);
+        REQUIRE((reinterpret_cast<uintptr_t>(g.src) & 3) == 0 && (reinterpret_cast<uintptr_t>(g.dst) & 3) == 0,
+                VITCOP_EINVAL, "compact: tensor %d not 4-byte aligned", i);
+    }
+    return launch_compact(tensors, n_tensors, idx, B, T_out, static_cast<hipStream_t>(stream));
+}
+
+/* -------------------------------------------------------------- attention */
+
+size_t vitcop_prefill_attn_workspace_bytes(int B, int N, int Hq, int Hkv, int d) {
+    (void)B; (void)N; (void)Hq; (void)Hkv; (void)d;
+    return 0;
+}
+
+int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                        float* lse_out, int B, int N, int Hq, int Hkv, int d, float scale, int causal,
+                        void* ws, size_t ws_bytes, void* stream) {
+    (void)ws; (void)ws_bytes;
+    REQUIRE(B >= 0 && N >= 0 && Hq >= 1 && Hkv >= 1, VITCOP_EINVAL, "prefill_attn: B=%d N=%d Hq=%d Hkv=%d", B,
+            N, Hq, Hkv);
+    REQUIRE(Hq % Hkv == 0, VITCOP_EINVAL, "prefill_attn: Hq=%d not a multiple of Hkv=%d", Hq, Hkv);
+    REQUIRE(causal == 0 || causal == 1, VITCOP_EINVAL, "prefill_attn: causal=%d", causal);
+    REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "prefill_attn: scale");
+    REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "prefill_attn: d=%d", d);
+    REQUIRE(d == 128, VITCOP_EUNSUPPORTED, "prefill_attn: d=%d (this build has d=128 only)", d);
+    REQUIRE(Hq <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "prefill_attn: Hq or B above 65535");
+    if (B == 0 || N == 0) return VITCOP_OK;
+    REQUIRE(q && k && v && out, VITCOP_EINVAL, "prefill_attn: null pointer");
+    REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), VITCOP_EINVAL,
+            "prefill_attn: pointers must be 16-byte aligned");
+    if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
+    return launch_attn(q, k, v, out, lse_out, B, N, Hq, Hkv, scale, causal, static_cast<hipStream_t>(stream));
+}
+
+/* ------------------------------------------------------------- projection */
+
+int vitcop_project_sumsq_parts(int N) { return N > 0 ? gemm_sumsq_parts(N) : 0; }
+
+int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w, uint16_t* y,
+                   int64_t y_row_stride, const uint16_t* residual, int64_t res_row_stride, int M, int N,
+                   int K, float* sumsq_parts, void* stream) {
+    REQUIRE(M >= 0 && N >= 0 && K >= 1, VITCOP_EINVAL, "project: M=%d N=%d K=%d", M, N, K);
+    REQUIRE(K % 32 == 0 && N % 16 == 0, VITCOP_EUNSUPPORTED, "project: K=%d %% 32, N=%d %% 16", K, N);
+    REQUIRE(x_row_stride >= K && x_row_stride % 8 == 0 && y_row_stride >= N && y_row_stride % 8 == 0,
+            VITCOP_EINVAL, "project: strides (%lld, %lld)", (long long)x_row_stride, (long long)y_row_stride);
+    REQUIRE(!residual || (res_row_stride >= N && res_row_stride % 8 == 0), VITCOP_EINVAL,
+            "project: residual stride %lld", (long long)res_row_stride);
+    if (M == 0 || N == 0) return VITCOP_OK;
+    REQUIRE(x && w && y, VITCOP_EINVAL, "project: null pointer");
+    REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(residual), VITCOP_EINVAL,
+            "project: pointers must be 16-byte aligned");
+    return launch_gemm(x, x_row_stride, w, y, y_row_stride, residual, res_row_stride, M, N, K, sumsq_parts,
+                       static_cast<hipStream_t>(stream));
+}
+
+/* ------------------------------------------------------------------ layer */
+
+static int check_layer(const vitcop_layer_t* L) {
+    REQUIRE(L, VITCOP_EINVAL, "layer: descriptor is null");
+    REQUIRE(L->B >= 1 && L->T >= 1 && L->D >= 32 && L->Hq >= 1 && L->Hkv >= 1, VITCOP_EINVAL,
+            "layer: B=%d T=%d D=%d Hq=%d Hkv=%d", L->B, L->T, L->D, L->Hq, L->Hkv);
+    REQUIRE(L->Hq % L->Hkv == 0, VITCOP_EINVAL, "layer: Hq=%d not a multiple of Hkv=%d", L->Hq, L->Hkv);
+    REQUIRE(L->d == 128, VITCOP_EUNSUPPORTED, "layer: d=%d (this build has d=128 only)", L->d);
+    REQUIRE(L->D % 32 == 0, VITCOP_EUNSUPPORTED, "layer: D=%d not a multiple of 32", L->D);
+    REQUIRE(L->vis_start >= 0 && L->n_vis >= 0 && (long)L->vis_start + L->n_vis <= L->T, VITCOP_EINVAL,
+            "layer: visual span [%d,%d) outside [0,%d)", L->vis_start, L->vis_start + L->n_vis, L->T);
+    REQUIRE(L->keep >= 0 && L->keep <= L->n_vis, VITCOP_EINVAL, "layer: keep=%d outside [0,%d]", L->keep,
+            L->n_vis);
+    REQUIRE(L->n_vis <= VITCOP_MAX_CANDIDATES, VITCOP_EUNSUPPORTED, "layer: n_vis=%d > %d", L->n_vis,
+            VITCOP_MAX_CANDIDATES);
+    REQUIRE(L->T - L->n_vis + L->keep >= 1, VITCOP_EINVAL, "layer: nothing survives");
+    return VITCOP_OK;
+}
+
+size_t vitcop_layer_workspace_bytes(const vitcop_layer_t* L) {
+    if (check_layer(L) != VITCOP_OK) return 0;
+    const size_t B = L->B, T = L->T, Tp = L->T - L->n_vis + L->keep, D = L->D;
+    const size_t qd = (size_t)L->Hq * L->d, kd = (size_t)L->Hkv * L->d;
+    size_t n = 0;
+    n += up256(B * T * kd * 2);                                         // K of every token
+    n += up256((size_t)gemm_sumsq_parts((int)kd) * B * T * 4);          // squared-norm partials
+    n += up256(B * Tp * 4);                                             // keep list
+    n += up256(B * Tp * D * 2);                                         // compacted hidden states
+    n += up256(B * Tp * kd * 2);                                        // compacted K
+    n += up256(B * Tp * qd * 2);                                        // Q
+    n += up256(B * Tp * kd * 2);                                        // V
+    n += up256(B * Tp * qd * 2);                                        // attention output
+    return n;
+}
+
+int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_layer(L);
+    if (rc) return rc;
+    REQUIRE(L->x && L->wq && L->wk && L->wv && L->wo && L->y, VITCOP_EINVAL, "layer: null pointer");
+    REQUIRE(aligned16(L->x) && aligned16(L->wq) && aligned16(L->wk) && aligned16(L->wv) &&
+                aligned16(L->wo) && aligned16(L->y),
+            VITCOP_EINVAL, "layer: pointers must be 16-byte aligned");
+    REQUIRE(!L->positions_out || L->positions_in, VITCOP_EINVAL, "layer: positions_out without positions_in");
+    REQUIRE(ws && ws_bytes >= vitcop_layer_workspace_bytes(L), VITCOP_EWORKSPACE,
+            "layer: workspace needs %zu bytes", vitcop_layer_workspace_bytes(L));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int B = L->B, T = L->T, D = L->D, Tp = L->T - L->n_vis + L->keep;
+    const int qd = L->Hq * L->d, kd = L->Hkv * L->d;
+    const bool prune = L->keep < L->n_vis;
+    const bool want_sel = prune || L->keep_idx || L->norms;
+    const int P = gemm_sumsq_parts(kd);
+
+    Carver c(ws);
+    uint16_t* k_all = c.take<uint16_t>((size_t)B * T * kd * 2);
+    float* parts = c.take<float>((size_t)P * B * T * 4);
+    int32_t* idx_ws = c.take<int32_t>((size_t)B * Tp * 4);
+    uint16_t* x_kept = c.take<uint16_t>((size_t)B * Tp * D * 2);
+    uint16_t* k_kept = c.take<uint16_t>((size_t)B * Tp * kd * 2);
+    uint16_t* qb = c.take<uint16_t>((size_t)B * Tp * qd * 2);
+    uint16_t* vb = c.take<uint16_t>((size_t)B * Tp * kd * 2);
+    uint16_t* ob = c.take<uint16_t>((size_t)B * Tp * qd * 2);
+    int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
+
+    // K of every token of the layer input, squared norms as a side output
+    rc = launch_gemm(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, s);
+    if (rc) return rc;
+    if (want_sel) {
+        rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T,
+                                    L->vis_start, L->n_vis, L->keep, idx, s);
+        if (rc) return rc;
+    }
+    const uint16_t* xs = L->x;
+    const uint16_t* ks = k_all;
+    if (prune) {
+        vitcop_gather_t g[3];
+        int ng = 0;
+        g[ng++] = {L->x, x_kept, (int64_t)D * 2, (int64_t)D * 2, (int64_t)T * D * 2};
+        g[ng++] = {k_all, k_kept, (int64_t)kd * 2, (int64_t)kd * 2, (int64_t)T * kd * 2};
+        if (L->positions_out) g[ng++] = {L->positions_in, L->positions_out, 4, 4, (int64_t)T * 4};
+        rc = launch_compact(g, ng, idx, B, Tp, s);
+        if (rc) return rc;
+        xs = x_kept;
+        ks = k_kept;
+    } else if (L->positions_out) {
+        rc = hip_status(hipMemcpyAsync(L->positions_out, L->positions_in, (size_t)B * T * 4,
+                                       hipMemcpyDeviceToDevice, s),
+                        "copy positions");
+        if (rc) return rc;
+    }
+    // Q and V of the survivors only
+    rc = launch_gemm(xs, D, L->wq, qb, qd, nullptr, 0, B * Tp, qd, D, nullptr, s);
+    if (rc) return rc;
+    rc = launch_gemm(xs, D, L->wv, vb, kd, nullptr, 0, B * Tp, kd, D, nullptr, s);
+    if (rc) return rc;
+    rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, 1.0f / std::sqrt((float)L->d), 1, s);
+    if (rc) return rc;
+    return launch_gemm(ob, qd, L->wo, L->y, D, L->residual ? xs : nullptr, D, B * Tp, D, qd, nullptr, s);
+}
+
+/* --------------------------------------------------------------- schedule */
+
+static int check_schedule(const vitcop_schedule_t* S) {
+    REQUIRE(S, VITCOP_EINVAL, "schedule: descriptor is null");
+    REQUIRE(S->n_layers >= 1 && S->n_stages >= 0, VITCOP_EINVAL, "schedule: n_layers=%d n_stages=%d",
+            S->n_layers, S->n_stages);
+    REQUIRE(S->n_stages == 0 || (S->prune_layer && S->prune_keep), VITCOP_EINVAL, "schedule: null stage arrays");
+    int prev_layer = -1, prev_keep = S->n_vis;
+    for (int i = 0; i < S->n_stages; ++i) {
+        REQUIRE(S->prune_layer[i] > prev_layer && S->prune_layer[i] < S->n_layers, VITCOP_EINVAL,
+                "schedule: stage %d at layer %d (must ascend within [0,%d))", i, S->prune_layer[i],
+                S->n_layers);
+        REQUIRE(S->prune_keep[i] >= 0 && S->prune_keep[i] <= prev_keep, VITCOP_EINVAL,
+                "schedule: stage %d keeps %d of %d", i, S->prune_keep[i], prev_keep);
+        prev_layer = S->prune_layer[i];
+        prev_keep = S->prune_keep[i];
+    }
+    vitcop_layer_t L{};
+    L.B = S->B; L.T = S->T; L.D = S->D; L.Hq = S->Hq; L.Hkv = S->Hkv; L.d = S->d;
+    L.vis_start = S->vis_start; L.n_vis = S->n_vis; L.keep = S->n_vis;
+    return check_layer(&L);
+}
+
+size_t vitcop_schedule_workspace_bytes(const vitcop_schedule_t* S) {
+    if (check_schedule(S) != VITCOP_OK) return 0;
+    vitcop_layer_t L{};
+    L.B = S->B; L.T = S->T; L.D = S->D; L.Hq = S->Hq; L.Hkv = S->Hkv; L.d = S->d;
+    L.vis_start = S->vis_start; L.n_vis = S->n_vis; L.keep = S->n_vis;
+    const size_t B = S->B, T = S->T, D = S->D;
+    return vitcop_layer_workspace_bytes(&L) + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
+}
+
+__global__ void iota_kernel(int32_t* p, int T, int64_t n) {
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = (int32_t)(i % T);
+}
+
+int vitcop_schedule_prefill(const vitcop_schedule_t* S, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_schedule(S);
+    if (rc) return rc;
+    REQUIRE(S->x && S->y_out && S->wq && S->wk && S->wv && S->wo, VITCOP_EINVAL, "schedule: null pointer");
+    for (int l = 0; l < S->n_layers; ++l)
+        REQUIRE(S->wq[l] && S->wk[l] && S->wv[l] && S->wo[l], VITCOP_EINVAL, "schedule: layer %d has a null weight", l);
+    REQUIRE(ws && ws_bytes >= vitcop_schedule_workspace_bytes(S), VITCOP_EWORKSPACE,
+            "schedule: workspace needs %zu bytes", vitcop_schedule_workspace_bytes(S));
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t B = S->B, T = S->T, D = S->D;
+    Carver c(ws);
+    uint16_t* hbuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
+    int32_t* pbuf[2] = {c.take<int32_t>(B * T * 4), c.take<int32_t>(B * T * 4)};
+    void* lws = c.base + c.used;
+    const size_t lws_bytes = ws_bytes - c.used;
+
+    const int64_t npos = (int64_t)B * T;
+    hipLaunchKernelGGL(iota_kernel, dim3((unsigned)((npos + 255) / 256)), dim3(256), 0, s, pbuf[0], S->T, npos);
+    rc = launch_status("iota");
+    if (rc) return rc;
+
+    const uint16_t* h = S->x;
+    int cur_T = S->T, cur_vis = S->n_vis, stage = 0, pp = 0;
+    for (int l = 0; l < S->n_layers; ++l) {
+        vitcop_layer_t L{};
+        L.B = S->B; L.T = cur_T; L.D = S->D; L.Hq = S->Hq; L.Hkv = S->Hkv; L.d = S->d;
+        L.vis_start = S->vis_start; L.n_vis = cur_vis; L.keep = cur_vis; L.residual = 1;
+        L.x = h; L.wq = S->wq[l]; L.wk = S->wk[l]; L.wv = S->wv[l]; L.wo = S->wo[l];
+        const bool last = l + 1 == S->n_layers;
+        const bool prune_here = stage < S->n_stages && S->prune_layer[stage] == l;
+        if (prune_here) {
+            L.keep = S->prune_keep[stage++];
+            L.positions_in = pbuf[pp];
+            L.positions_out = pbuf[pp ^ 1];
+        }
+        uint16_t* dst = last ? S->y_out : hbuf[l & 1];
+        L.y = dst;
+        rc = vitcop_layer_prefill(&L, lws, lws_bytes, stream);
+        if (rc) return rc;
+        if (prune_here) {
+            pp ^= 1;
+            cur_T = cur_T - cur_vis + L.keep;
+            cur_vis = L.keep;
+        }
+        h = dst;
+    }
+    if (S->positions_out) {
+        rc = hip_status(hipMemcpyAsync(S->positions_out, pbuf[pp], (size_t)B * cur_T * 4,
+                                       hipMemcpyDeviceToDevice, s),
+                        "copy positions");
+    }
+    return rc;
+}
+
+#pragma GCC visibility pop
+}  // extern "C"

@@ -1,0 +1,212 @@
+// Causal prefill attention over the surviving tokens: exact
+// softmax(scale Q K^T + causal) V with an online softmax, i.e. what a
+// FlashAttention kernel computes (Sec. 1 and Sec. 2.2 rely on that
+// compatibility; this is the 4 N^2 d term of Eq. 7).  Head dimension 128.
+//
+// Layout of the computation (wave64, v_mfma_f32_32x32x16_bf16):
+//  * a workgroup of 4 wavefronts owns 128 consecutive queries of one
+//    (sample, head); each wavefront owns 32 of them;
+//  * keys/values stream through LDS in tiles of 64 keys;
+//  * scores are computed TRANSPOSED, S^T = K Q^T, so that every lane holds
+//    scores of a single query (its column): the running max / sum are
+//    per-lane scalars plus one exchange with lane^32, and the probabilities
+//    are already laid out as the B operand of the second product
+//    O^T += V^T P^T — they never leave registers;
+//  * V is written to LDS transposed (channel-major) with the keys of each
+//    group of 32 permuted so that the 8 keys a lane needs are contiguous.
+#include "vitcop_internal.h"
+#include "device_utils.h"
+
+namespace vitcop {
+
+constexpr int AT_D = 128;
+constexpr int AT_BM = 128;
+constexpr int AT_BN = 64;
+constexpr int AT_THREADS = 256;
+constexpr int AT_KLD = AT_D + 8;     // bf16 per K row in LDS (272 B: conflict-free 16 B reads)
+constexpr int AT_VLD = AT_BN + 8;    // bf16 per V^T row in LDS (144 B)
+
+__global__ __launch_bounds__(AT_THREADS) void attn_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, uint16_t* __restrict__ out, float* __restrict__ lse,
+    int N, int Hq, int Hkv, float scale_log2e, int causal) {
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[AT_BN * AT_KLD];
+    __shared__ __attribute__((aligned(16))) uint16_t Vt[AT_D * AT_VLD];
+
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int l32 = lane & 31, g = lane >> 5;
+    // late query blocks carry the most keys under the causal mask: start them first
+    const int qb = causal ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (Hq / Hkv);
+    const int q0 = qb * AT_BM, wq0 = q0 + 32 * wv;
+    const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
+    const int query = wq0 + l32;
+
+    // Q^T fragments (B operand): lane holds 8 channels of its query per 16-channel step
+    bf16x8 qf[8];
+    {
+        const uint16_t* qp = q + ((int64_t)b * N + min(query, N - 1)) * q_rs + h * AT_D + 8 * g;
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
+    }
+
+    f32x16 o[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
+    float m_run = -INFINITY, l_run = 0.f;
+
+    const int kend = causal ? min(N, q0 + AT_BM) : N;
+    const int ntiles = (kend + AT_BN - 1) / AT_BN;
+    const int wave_kend = causal ? min(N, wq0 + 32) : N;
+    const uint16_t* kbase = k + (int64_t)b * N * kv_rs + hk * AT_D;
+    const uint16_t* vbase = v + (int64_t)b * N * kv_rs + hk * AT_D;
+
+    const int vkq = tid & 15, vc = tid >> 4;      // V: key quad, channel chunk
+    // position of the key quad inside its row of V^T: swap the two low bits of the quad index
+    const int vpq = (vkq & ~3) | ((vkq & 1) << 1) | ((vkq >> 1) & 1);
+    uint4 kr[4], vr[4];
+    auto load_tile = [&](int t) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int id = tid + AT_THREADS * j;
+            const int key = min(t * AT_BN + (id >> 4), N - 1);
+            kr[j] = *reinterpret_cast<const uint4*>(kbase + key * kv_rs + (id & 15) * 8);
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int key = min(t * AT_BN + 4 * vkq + j, N - 1);
+            vr[j] = *reinterpret_cast<const uint4*>(vbase + key * kv_rs + vc * 8);
+        }
+    };
+    load_tile(0);
+
+    for (int t = 0; t < ntiles; ++t) {
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int id = tid + AT_THREADS * j;
+            *reinterpret_cast<uint4*>(&Ks[(id >> 4) * AT_KLD + (id & 15) * 8]) = kr[j];
+        }
+        {
+            const uint32_t w0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
+            const uint32_t w1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
+            const uint32_t w2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
+            const uint32_t w3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint2 ev, od;
+                ev.x = (w0[p] & 0xFFFFu) | (w1[p] << 16);
+                ev.y = (w2[p] & 0xFFFFu) | (w3[p] << 16);
+                od.x = (w0[p] >> 16) | (w1[p] & 0xFFFF0000u);
+                od.y = (w2[p] >> 16) | (w3[p] & 0xFFFF0000u);
+                *reinterpret_cast<uint2*>(&Vt[(vc * 8 + 2 * p) * AT_VLD + vpq * 4]) = ev;
+                *reinterpret_cast<uint2*>(&Vt[(vc * 8 + 2 * p + 1) * AT_VLD + vpq * 4]) = od;
+            }
+        }
+        __syncthreads();
+        if (t + 1 < ntiles) load_tile(t + 1);
+        if (t * AT_BN >= wave_kend) continue;     // every key of this tile is masked for this wave
+
+        // S^T = K Q^T for the two 32-key halves of the tile
+        f32x16 s[2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
+#pragma unroll
+            for (int dc = 0; dc < 8; ++dc) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+                    &Ks[(kt * 32 + l32) * AT_KLD + dc * 16 + g * 8]);
+                s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[dc], s[kt], 0, 0, 0);
+            }
+        }
+        // lane holds, for its query, keys  t*64 + kt*32 + 8*(r/4) + 4*g + r%4
+        const int kb0 = t * AT_BN;
+        const bool need_mask = (kb0 + AT_BN > N) || (causal && kb0 + AT_BN - 1 > wq0);
+        float mx = -INFINITY;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                float val = s[kt][r] * scale_log2e;
+                if (need_mask) {
+                    const int key = kb0 + kt * 32 + 8 * (r >> 2) + 4 * g + (r & 3);
+                    if (key >= N || (causal && key > query)) val = -INFINITY;
+                }
+                s[kt][r] = val;
+                mx = fmaxf(mx, val);
+            }
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);          // finite: key 0 is visible to every query
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
+        m_run = m_new;
+        float psum = 0.f;
+        bf16x8 pf[2][2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                float e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    e[i] = __builtin_amdgcn_exp2f(s[kt][8 * tt + i] - m_new);
+                    psum += e[i];
+                }
+                uint4 pk;
+                pk.x = pack_bf16(e[0], e[1]);
+                pk.y = pack_bf16(e[2], e[3]);
+                pk.z = pack_bf16(e[4], e[5]);
+                pk.w = pack_bf16(e[6], e[7]);
+                pf[kt][tt] = __builtin_bit_cast(bf16x8, pk);
+            }
+        l_run = l_run * alpha + psum;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
+        // O^T += V^T P^T
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+                        &Vt[(db * 32 + l32) * AT_VLD + kt * 32 + tt * 16 + g * 8]);
+                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[kt][tt], o[db], 0, 0, 0);
+                }
+    }
+
+    const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
+    if (query < N) {
+        const float inv = 1.0f / l_tot;
+        uint16_t* op = out + ((int64_t)b * N + query) * q_rs + h * AT_D;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                uint2 pk;
+                pk.x = pack_bf16(o[db][4 * r4] * inv, o[db][4 * r4 + 1] * inv);
+                pk.y = pack_bf16(o[db][4 * r4 + 2] * inv, o[db][4 * r4 + 3] * inv);
+                *reinterpret_cast<uint2*>(op + db * 32 + 8 * r4 + 4 * g) = pk;
+            }
+        if (lse && g == 0)
+            lse[((int64_t)b * Hq + h) * N + query] =
+                (m_run + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+    }
+}
+
+int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                float* lse, int B, int N, int Hq, int Hkv, float scale, int causal,
+                hipStream_t s) {
+    if (B == 0 || N == 0) return VITCOP_OK;
+    dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
+    hipLaunchKernelGGL(attn_kernel, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv,
+                       scale * 1.4426950408889634f, causal);
+    return launch_status("attn");
+}
+
+}  // namespace vitcop

@@ -1,0 +1,51 @@
+// Internal declarations shared by the translation units of libvitcop.
+// Host-side argument checking lives in api.cpp; each *.hip file owns its
+// kernels and exposes one or two launch functions declared here.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "vitcop.h"
+
+namespace vitcop {
+
+// Records a thread-local message and returns `code` (a VITCOP_E* value).
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+// VITCOP_OK, or records the HIP error text and returns VITCOP_EHIP.
+int hip_status(hipError_t e, const char* what);
+int launch_status(const char* kernel_name);
+
+// ---- K-norm + selection (knorm_select.hip) -------------------------------
+int launch_knorm(const uint16_t* k, int64_t row_stride, int64_t batch_stride, int B,
+                 int row_elems, int vis_start, int n_vis, float* norms, hipStream_t s);
+// Ranks the n_vis candidates of each sample and writes the keep list.
+// value(b,i) = sum_{p<n_parts} parts[p*part_stride + b*sample_stride + offset + i];
+// do_sqrt: rank sqrt(value); norms_out (nullable) receives the ranked values.
+int launch_select_smallest(const float* parts, int n_parts, int64_t part_stride,
+                           int64_t sample_stride, int64_t offset, int do_sqrt,
+                           float* norms_out, int B, int T, int vis_start, int n_vis,
+                           int keep, int32_t* keep_idx, hipStream_t s);
+
+// ---- compaction (compact.hip) --------------------------------------------
+int launch_compact(const vitcop_gather_t* t, int n, const int32_t* idx, int B, int T_out,
+                   hipStream_t s);
+
+// ---- Stage I filter (filter.hip) -----------------------------------------
+int launch_filter(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
+                  int keep, float scale, float* scores_out, int32_t* idx_out,
+                  float* logits_ws, hipStream_t s);
+
+// ---- attention (attn.hip) -------------------------------------------------
+int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                float* lse, int B, int N, int Hq, int Hkv, float scale, int causal,
+                hipStream_t s);
+
+// ---- projection GEMM (gemm.hip) -------------------------------------------
+int gemm_sumsq_parts(int N);
+int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
+                int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
+                int K, float* sumsq_parts, hipStream_t s);
+
+}  // namespace vitcop

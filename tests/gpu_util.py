@@ -1,0 +1,59 @@
+"""Helpers shared by the GPU parity tests (device transfer and comparison)."""
+import numpy as np
+import torch
+
+import vitcop_inputs as I
+from oracle import vitcop_oracle as O
+
+ATTN_MAX_ABS = 2e-2      # bf16 attention output vs the fp64 oracle (stated tolerance)
+ATTN_MEAN_REL = 1e-2
+BAND_REL = 1e-3          # relative score gap below which the selection may differ
+
+
+def dev(bits: np.ndarray) -> torch.Tensor:
+    """uint16 bf16 bit pattern -> torch.bfloat16 CUDA tensor (same bits)."""
+    t = torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda()
+    return t.view(torch.bfloat16)
+
+
+def host_bits(t: torch.Tensor) -> np.ndarray:
+    """bf16 CUDA tensor -> uint16 bit pattern."""
+    return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+def host_f64(t: torch.Tensor) -> np.ndarray:
+    if t.dtype == torch.bfloat16:
+        return I.bf16_bits_to_f32(host_bits(t)).astype(np.float64)
+    return t.cpu().numpy().astype(np.float64)
+
+
+def assert_attention_close(got_f64: np.ndarray, ref_f64: np.ndarray, what=""):
+    scale = max(1.0, float(np.abs(ref_f64).max()))
+    err = np.abs(got_f64 - ref_f64)
+    assert err.max() <= ATTN_MAX_ABS * scale, f"{what}: max-abs {err.max():.4g} (scale {scale:.3g})"
+    denom = max(float(np.abs(ref_f64).mean()), 1e-30)
+    assert err.mean() / denom <= ATTN_MEAN_REL, f"{what}: mean-rel {err.mean() / denom:.4g}"
+
+
+def assert_selection_matches(gpu_idx: np.ndarray, gpu_scores: np.ndarray, ref_scores: np.ndarray,
+                             keep: int, largest: bool, what=""):
+    """gpu_idx: ascending candidate indices chosen by the GPU for one sample.
+
+    (1) exactly `keep` distinct ascending members;
+    (2) bit-exact against the tie rule applied to the GPU's own fp32 scores;
+    (3) equal to the oracle's set outside the band of near-ties around the k-th score.
+    """
+    n = len(ref_scores)
+    assert gpu_idx.shape == (keep,), f"{what}: {gpu_idx.shape} vs keep {keep}"
+    if keep:
+        assert np.all(np.diff(gpu_idx) > 0) and gpu_idx[0] >= 0 and gpu_idx[-1] < n, what
+    g32 = np.asarray(gpu_scores, dtype=np.float32)
+    key = -g32 if largest else g32
+    own = np.sort(np.lexsort((np.arange(n), key))[:keep])
+    assert np.array_equal(gpu_idx, own), f"{what}: not the top-k of the GPU's own scores"
+    ref = (O.topk_largest if largest else O.topk_smallest)(ref_scores, keep)
+    band = O.tie_band(ref_scores, keep, largest, BAND_REL)
+    outside = ~band
+    a = np.zeros(n, bool); a[gpu_idx] = True
+    b = np.zeros(n, bool); b[ref] = True
+    assert np.array_equal(a[outside], b[outside]), f"{what}: differs from the oracle outside the tie band"

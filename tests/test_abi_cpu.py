@@ -1,0 +1,186 @@
+"""The C-ABI library: loads, exports every declared symbol, validates on the host.
+
+No compute call is made here; every call below must be rejected by the
+argument checks that run before any HIP call.
+"""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "vitcop.h")
+
+binding = pytest.importorskip("paper_2601_17818_amd.binding")
+lib = binding.lib
+
+A16 = 0x1000   # a fake, 16-byte aligned, non-null "device pointer" (never dereferenced)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(vitcop_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported():
+    names = declared_functions()
+    assert set(names) == set(binding.EXPORTS)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_codes_match_header():
+    text = open(HEADER).read()
+    for name in ("VITCOP_OK", "VITCOP_EINVAL", "VITCOP_EUNSUPPORTED", "VITCOP_EWORKSPACE", "VITCOP_EHIP"):
+        m = re.search(rf"#define\s+{name}\s+\(?(-?\d+)\)?", text)
+        assert m and int(m.group(1)) == getattr(binding, name)
+    m = re.search(r"#define\s+VITCOP_MAX_CANDIDATES\s+(\d+)", text)
+    assert int(m.group(1)) == binding.VITCOP_MAX_CANDIDATES
+
+
+def test_struct_sizes_match_c_layout():
+    assert C.sizeof(binding.GatherT) == 40
+    assert C.sizeof(binding.LayerT) == 10 * 4 + 10 * 8
+    assert C.sizeof(binding.ScheduleT) == 10 * 4 + 9 * 8
+
+
+def test_filter_validation():
+    f = lib.vitcop_filter_visual
+    assert f(A16, A16, 1, 10, 2, 64, 11, 0.0, None, A16, A16, 1 << 20, None) == binding.VITCOP_EINVAL
+    assert "keep" in binding.vitcop_last_error()
+    assert f(A16, A16, 1, 10, 2, 32, 5, 0.0, None, A16, A16, 1 << 20, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(None, A16, 1, 10, 2, 64, 5, 0.0, None, A16, A16, 1 << 20, None) == binding.VITCOP_EINVAL
+    assert f(A16 + 2, A16, 1, 10, 2, 64, 5, 0.0, None, A16, A16, 1 << 20, None) == binding.VITCOP_EINVAL
+    assert f(A16, A16, 1, 10, 2, 64, 5, 0.0, None, A16, A16, 8, None) == binding.VITCOP_EWORKSPACE
+    assert f(A16, A16, 1, 10, 2, 64, 5, 0.0, None, A16, None, 0, None) == binding.VITCOP_EWORKSPACE
+    assert f(A16, A16, 1, 20000, 2, 64, 5, 0.0, None, A16, A16, 1 << 30, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(A16, A16, -1, 10, 2, 64, 5, 0.0, None, A16, A16, 1 << 20, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_filter_visual_workspace_bytes(8, 576, 16, 64) >= 8 * 16 * 577 * 4
+    # an empty batch is a no-op, not an error
+    assert f(None, None, 0, 10, 2, 64, 5, 0.0, None, None, None, 0, None) == binding.VITCOP_OK
+
+
+def test_knorm_select_validation():
+    f = lib.vitcop_knorm_select
+
+    def call(k=A16, rs=4096, bs=640 * 4096, B=1, T=640, Hkv=32, d=128, vs=35, nv=576, keep=64,
+             norms=A16, idx=A16, flags=0):
+        return f(k, rs, bs, B, T, Hkv, d, vs, nv, keep, norms, idx, flags, None, 0, None)
+
+    assert call(keep=577) == binding.VITCOP_EINVAL
+    assert call(vs=100, nv=576) == binding.VITCOP_EINVAL          # span leaves the sequence
+    assert call(k=None) == binding.VITCOP_EINVAL
+    assert call(k=A16 + 8) == binding.VITCOP_EINVAL
+    assert call(rs=4095) == binding.VITCOP_EINVAL
+    assert call(rs=2048) == binding.VITCOP_EINVAL                 # stride shorter than a row
+    assert call(idx=None) == binding.VITCOP_EINVAL
+    assert call(norms=None) == binding.VITCOP_EINVAL
+    assert call(flags=8) == binding.VITCOP_EINVAL
+    assert call(flags=binding.VITCOP_NORMS_SQUARED) == binding.VITCOP_EINVAL
+    assert call(T=40000, nv=20000, vs=0, bs=40000 * 4096) == binding.VITCOP_EUNSUPPORTED
+    assert call(Hkv=1, d=12, rs=16) == binding.VITCOP_EUNSUPPORTED  # row not a multiple of 8
+    assert call(B=0) == binding.VITCOP_OK
+
+
+def test_compact_validation():
+    f = lib.vitcop_compact
+    g = (binding.GatherT * 2)()
+    g[0] = binding.GatherT(A16, A16 + 4096, 64, 64, 6400)
+    g[1] = binding.GatherT(A16, A16, 64, 64, 6400)
+    assert f(g, 2, A16, 1, 100, 10, None) == binding.VITCOP_EINVAL           # in place
+    assert f(g, 9, A16, 1, 100, 10, None) == binding.VITCOP_EINVAL
+    assert f(g, 1, None, 1, 100, 10, None) == binding.VITCOP_EINVAL
+    g[0] = binding.GatherT(A16, A16 + 4096, 6, 64, 6400)
+    assert f(g, 1, A16, 1, 100, 10, None) == binding.VITCOP_EINVAL           # row_bytes % 4
+    g[0] = binding.GatherT(A16, A16 + 4096, 64, 32, 6400)
+    assert f(g, 1, A16, 1, 100, 10, None) == binding.VITCOP_EINVAL           # stride < row
+    g[0] = binding.GatherT(A16, A16 + 4096, 64, 64, 6400)
+    assert f(g, 1, A16, 1, 0, 10, None) == binding.VITCOP_EINVAL             # rows from nothing
+    assert f(g, 1, A16, 1, 100, 0, None) == binding.VITCOP_OK
+    assert f(g, 0, None, 1, 100, 10, None) == binding.VITCOP_OK
+
+
+def test_attn_validation():
+    f = lib.vitcop_prefill_attn
+
+    def call(q=A16, k=A16, v=A16, out=A16, B=1, N=128, Hq=32, Hkv=32, d=128, scale=0.0, causal=1):
+        return f(q, k, v, out, None, B, N, Hq, Hkv, d, scale, causal, None, 0, None)
+
+    assert call(Hq=28, Hkv=5) == binding.VITCOP_EINVAL
+    assert call(d=96) == binding.VITCOP_EINVAL
+    assert call(d=64) == binding.VITCOP_EUNSUPPORTED
+    assert call(causal=2) == binding.VITCOP_EINVAL
+    assert call(scale=-1.0) == binding.VITCOP_EINVAL
+    assert call(q=None) == binding.VITCOP_EINVAL
+    assert call(out=A16 + 4) == binding.VITCOP_EINVAL
+    assert call(N=0) == binding.VITCOP_OK and call(B=0) == binding.VITCOP_OK
+
+
+def test_project_and_select_from_sumsq_validation():
+    f = lib.vitcop_project
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4096, 4008, None, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4100, 4096, None, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(A16, 1024, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
+    assert f(None, 4096, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
+    assert f(A16, 4096, A16, A16, 4096, A16, 8, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 0, 4096, 4096, None, None) == binding.VITCOP_OK
+    assert lib.vitcop_project_sumsq_parts(4096) == 32 and lib.vitcop_project_sumsq_parts(512) == 4
+    s = lib.vitcop_select_from_sumsq
+    assert s(A16, 32, 640, 1, 640, 35, 576, 600, None, A16, None) == binding.VITCOP_EINVAL
+    assert s(A16, 32, 100, 1, 640, 35, 576, 64, None, A16, None) == binding.VITCOP_EINVAL   # stride < B*T
+    assert s(None, 32, 640, 1, 640, 35, 576, 64, None, A16, None) == binding.VITCOP_EINVAL
+    assert s(A16, 0, 640, 1, 640, 35, 576, 64, None, A16, None) == binding.VITCOP_EINVAL
+
+
+def layer_desc(**kw):
+    base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, vis_start=35, n_vis=576, keep=64, residual=0,
+                x=A16, wq=A16, wk=A16, wv=A16, wo=A16, y=A16, keep_idx=None, norms=None,
+                positions_in=None, positions_out=None)
+    base.update(kw)
+    return binding.LayerT(**base)
+
+
+def test_layer_validation_and_workspace():
+    ws = lib.vitcop_layer_workspace_bytes
+    run = lib.vitcop_layer_prefill
+    good = layer_desc()
+    need = ws(C.byref(good))
+    # K of all tokens + partials + survivors' x/K/Q/V/O
+    assert need >= 640 * 4096 * 2 + 32 * 640 * 4 + 128 * 4096 * 2 * 5
+    assert run(C.byref(good), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    assert run(C.byref(good), None, need, None) == binding.VITCOP_EWORKSPACE
+    for bad in (layer_desc(keep=600), layer_desc(Hq=30), layer_desc(vis_start=100),
+                layer_desc(x=None), layer_desc(positions_out=A16)):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    assert ws(C.byref(layer_desc(d=64))) == 0
+    assert run(C.byref(layer_desc(d=64)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
+    assert run(C.byref(layer_desc(D=4100)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
+
+
+def test_schedule_validation():
+    n_layers = 4
+    w = (C.c_void_p * n_layers)(*[A16] * n_layers)
+
+    def desc(layers, keeps, **kw):
+        pl = (C.c_int * max(1, len(layers)))(*layers)
+        pk = (C.c_int * max(1, len(keeps)))(*keeps)
+        base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, vis_start=35, n_vis=576,
+                    n_layers=n_layers, n_stages=len(layers), prune_layer=pl, prune_keep=pk, x=A16,
+                    wq=w, wk=w, wv=w, wo=w, y_out=A16, positions_out=None)
+        base.update(kw)
+        d = binding.ScheduleT(**base)
+        d._keep = (pl, pk)
+        return d
+
+    run = lib.vitcop_schedule_prefill
+    good = desc([1, 2], [192, 64])
+    need = lib.vitcop_schedule_workspace_bytes(C.byref(good))
+    assert need > 2 * 640 * 4096 * 2
+    assert run(C.byref(good), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    assert run(C.byref(desc([2, 1], [192, 64])), A16, 1 << 40, None) == binding.VITCOP_EINVAL   # not ascending
+    assert run(C.byref(desc([1, 2], [64, 192])), A16, 1 << 40, None) == binding.VITCOP_EINVAL   # budget grows
+    assert run(C.byref(desc([1, 4], [192, 64])), A16, 1 << 40, None) == binding.VITCOP_EINVAL   # layer out of range
+    assert run(C.byref(desc([1], [600])), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    assert run(C.byref(desc([1], [64], x=None)), A16, 1 << 40, None) == binding.VITCOP_EINVAL

@@ -1,0 +1,90 @@
+"""GPU parity: causal prefill attention vs the oracle's exact softmax(QK^T)V."""
+import numpy as np
+import pytest
+import torch
+
+import vitcop_inputs as I
+from oracle import vitcop_oracle as O
+from gpu_util import assert_attention_close, dev, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vc():
+    from paper_2601_17818_amd import binding
+    return binding
+
+
+def run(vc, t, causal=True, scale=0.0, lse=True):
+    out, l = vc.vitcop_prefill_attn(dev(t["q"]), dev(t["k"]), dev(t["v"]), scale, causal, lse)
+    torch.cuda.synchronize()
+    return host_f64(out), (l.cpu().numpy().astype(np.float64) if lse else None)
+
+
+# N spans: single row, inside one 32-row wavefront tile, exactly one key tile, ragged
+# tails, several query blocks
+@pytest.mark.parametrize("N", [1, 2, 31, 32, 33, 64, 65, 100, 127, 128, 129, 191, 300, 517])
+def test_causal_sizes(vc, N):
+    t = I.qkv_tensors(100 + N, 2, N, 3, 3, 128)
+    out, lse = run(vc, t)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+    assert_attention_close(out, ref, f"N={N}")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+@pytest.mark.parametrize("N", [5, 64, 130, 257])
+def test_non_causal(vc, N):
+    t = I.qkv_tensors(200 + N, 1, N, 2, 2, 128)
+    out, lse = run(vc, t, causal=False)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], None, False)
+    assert_attention_close(out, ref, f"non-causal N={N}")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+@pytest.mark.parametrize("Hq,Hkv", [(28, 4), (8, 2), (6, 1)])
+def test_gqa(vc, Hq, Hkv):
+    t = I.qkv_tensors(300 + Hq, 1, 150, Hq, Hkv, 128)
+    out, _ = run(vc, t)
+    ref, _ = O.attention(t["q"], t["k"], t["v"])
+    assert_attention_close(out, ref, f"GQA {Hq}/{Hkv}")
+
+
+def test_explicit_scale_and_large_logits(vc):
+    t = I.qkv_tensors(400, 1, 140, 2, 2, 128, std=3.0)       # logits of order +-100
+    out, lse = run(vc, t, scale=0.11)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], 0.11)
+    assert_attention_close(out, ref, "large logits")
+    assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
+def test_structure_pins(vc):
+    t = I.qkv_tensors(500, 1, 200, 2, 2, 128)
+    ones = I.f32_to_bf16_bits(np.ones((1, 200, 2, 128), np.float32))
+    out, _ = run(vc, dict(t, v=ones))
+    assert np.abs(out - 1.0).max() < 1e-2                       # rows of softmax sum to 1
+    out, _ = run(vc, t)
+    v = I.bf16_bits_to_f32(t["v"]).astype(np.float64)
+    assert np.array_equal(out[0, 0], v[0, 0])                   # row 0 sees key 0 only
+    kk = np.tile(t["k"][:, :1], (1, 200, 1, 1))
+    out, _ = run(vc, dict(t, k=kk))
+    run_mean = np.cumsum(v[0], axis=0) / np.arange(1, 201)[:, None, None]
+    assert np.abs(out[0] - run_mean).max() < 2e-2
+
+
+def test_config0_pruned_shape_and_unpruned_shape(vc):
+    for N in (128, 640):
+        t = I.qkv_tensors(600 + N, 1, N, 32, 32, 128)
+        out, lse = run(vc, t)
+        ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+        assert_attention_close(out, ref, f"config0 N={N}")
+        assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+def test_deterministic(vc):
+    t = I.qkv_tensors(700, 2, 300, 4, 2, 128)
+    q, k, v = dev(t["q"]), dev(t["k"]), dev(t["v"])
+    a, _ = vc.vitcop_prefill_attn(q, k, v)
+    for _ in range(5):
+        b, _ = vc.vitcop_prefill_attn(q, k, v)
+        assert torch.equal(a, b)

@@ -1,0 +1,164 @@
+"""GPU parity: projection with the norm side output, the pruned layer and the schedule."""
+import numpy as np
+import pytest
+import torch
+
+import vitcop_inputs as I
+from oracle import vitcop_oracle as O
+from gpu_util import assert_attention_close, assert_selection_matches, dev, host_bits, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vc():
+    from paper_2601_17818_amd import binding
+    return binding
+
+
+def assert_bf16_of(got_bits, ref_f64, what, ulps=1.0):
+    """got is the bf16 rounding of an fp32 accumulation of ref: within `ulps` bf16 ulp."""
+    got = I.bf16_bits_to_f32(got_bits).astype(np.float64)
+    ulp = 2.0 ** (np.floor(np.log2(np.maximum(np.abs(ref_f64), 1e-30))) - 7)
+    err = np.abs(got - ref_f64)
+    assert np.all(err <= ulps * 0.5 * ulp * 1.02 + 1e-6 * np.abs(ref_f64).max()), \
+        f"{what}: worst {np.max(err / ulp):.3f} ulp"
+
+
+@pytest.mark.parametrize("M,N,K", [(640, 4096, 4096), (128, 512, 3584), (300, 1024, 256),
+                                   (1, 128, 32), (257, 144, 96), (1500, 4096, 512)])
+def test_project_matches_oracle(vc, M, N, K):
+    x = I.normal_bf16(M + N, 0, (M, K))
+    w = I.normal_bf16(M + N, 1, (N, K), 0.05)
+    y, parts = vc.vitcop_project(dev(x), dev(w), want_sumsq=True)
+    torch.cuda.synchronize()
+    ref = O.project(x, w)
+    yb = host_bits(y)
+    assert_bf16_of(yb, ref, f"project {M}x{N}x{K}")
+    # side output: squared norm of the rounded row, parts added in order
+    ss = parts.cpu().numpy().astype(np.float64).sum(axis=0)
+    ref_ss = (I.bf16_bits_to_f32(yb).astype(np.float64) ** 2).sum(axis=1)
+    assert parts.shape[0] == vc.vitcop_project_sumsq_parts(N)
+    assert np.allclose(ss, ref_ss, rtol=1e-5)
+
+
+def test_project_residual_and_strides(vc):
+    M, N, K = 200, 256, 128
+    x = I.normal_bf16(1, 0, (M, K)); w = I.normal_bf16(1, 1, (N, K), 0.1); r = I.normal_bf16(1, 2, (M, N))
+    y, _ = vc.vitcop_project(dev(x), dev(w), residual=dev(r))
+    ref = O.project(x, w) + O.bf16_to_f64(r)
+    assert_bf16_of(host_bits(y), ref, "residual")
+
+
+def small_layer(seed, B=2, T=200, D=256, Hq=4, Hkv=2, d=128, vs=20, nv=150):
+    return I.layer_inputs(seed, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.06)
+
+
+def gap_free(c, keep):
+    """True if the oracle's ranking has no near-tie at the cut (so both sides must agree exactly)."""
+    kb = O.f64_to_bf16_bits(O.project(c["x"], c["wk"])).reshape(c["B"], c["T"], c["Hkv"], c["d"])
+    n = O.k_norms(kb, c["vis_start"], c["n_vis"])
+    return all(O.tie_band(n[b], keep, False, 4e-3).sum() <= 1 for b in range(c["B"]))
+
+
+def run_layer(vc, c, keep, residual=False):
+    B, T = c["B"], c["T"]
+    pos = torch.arange(T, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+    r = vc.vitcop_layer_prefill(dev(c["x"]), dev(c["wq"]), dev(c["wk"]), dev(c["wv"]), dev(c["wo"]),
+                                c["Hq"], c["Hkv"], c["d"], c["vis_start"], c["n_vis"], keep,
+                                residual=residual, positions=pos)
+    torch.cuda.synchronize()
+    return r
+
+
+def check_layer(vc, c, keep, residual, what):
+    r = run_layer(vc, c, keep, residual)
+    ref = O.pruned_layer(c["x"], c["wq"], c["wk"], c["wv"], c["wo"], c["Hq"], c["Hkv"], c["d"],
+                         c["vis_start"], c["n_vis"], keep, residual)
+    idx = r["keep_idx"].cpu().numpy()
+    norms = r["norms"].cpu().numpy()
+    vs = c["vis_start"]
+    assert np.allclose(norms, ref["norms"], rtol=2e-3), what      # K differs by bf16 double rounding only
+    for b in range(c["B"]):
+        assert_selection_matches(idx[b, vs:vs + keep] - vs, norms[b], ref["norms"][b], keep, False, what)
+    assert np.array_equal(r["positions"].cpu().numpy(), idx)
+    assert np.array_equal(idx, ref["keep_idx"]), f"{what}: seed chosen gap-free, lists must agree"
+    assert_attention_close(host_f64(r["y"]), ref["y"], what)
+
+
+@pytest.mark.parametrize("keep", [0, 17, 75, 150])
+def test_small_layer_matches_oracle(vc, keep):
+    seed = 900
+    while not gap_free(small_layer(seed), keep):
+        seed += 1
+    check_layer(vc, small_layer(seed), keep, False, f"small layer keep={keep}")
+
+
+def test_small_layer_residual_gqa(vc):
+    seed = 950
+    while not gap_free(small_layer(seed, B=1, T=333, D=512, Hq=8, Hkv=2, vs=0, nv=300), 100):
+        seed += 1
+    check_layer(vc, small_layer(seed, B=1, T=333, D=512, Hq=8, Hkv=2, vs=0, nv=300), 100, True, "gqa+res")
+
+
+def test_config0_layer(vc):
+    trial = 0
+    while not gap_free(I.config0(trial), 64):
+        trial += 1
+    c = I.config0(trial)
+    check_layer(vc, c, 64, False, f"config 0 trial {trial}")
+    # unpruned limit of the same call
+    r = run_layer(vc, c, 576)
+    u = O.unpruned_layer(c["x"], c["wq"], c["wk"], c["wv"], c["wo"], 32, 32, 128)
+    assert_attention_close(host_f64(r["y"]), u["y"], "config 0 unpruned")
+    assert np.array_equal(r["keep_idx"].cpu().numpy(), np.arange(640)[None])
+
+
+def test_schedule_small(vc):
+    B, T, D, Hq, Hkv, d, vs, nv = 1, 180, 256, 4, 2, 128, 10, 150
+    sched = ((1, 90), (3, 40), (4, 12))
+    n_layers = 6
+    cfg = I.layer_inputs(1234, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.02)
+    gain, _ = I.lognormal_gains(1234, B, nv)
+    xf = I.bf16_bits_to_f32(cfg["x"]).copy()
+    xf[:, vs:vs + nv] *= gain[:, :, None]
+    x = I.f32_to_bf16_bits(xf)
+    ws = [I.layer_inputs(5000 + l, 1, 1, D, Hq, Hkv, d, 0, 0, w_std=0.02) for l in range(n_layers)]
+    for w in ws:
+        w["wo"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w["wo"]) * np.float32(0.125))
+    ref = O.schedule_prefill(x, lambda l: ws[l], n_layers, sched, Hq, Hkv, d, vs, nv)
+    dws = [{n: dev(w[n]) for n in ("wq", "wk", "wv", "wo")} for w in ws]
+
+    # (1) teacher-forced: every layer run on the oracle's input for that layer
+    budgets = dict(sched)
+    cur_vis = nv
+    for l, lay in enumerate(ref["layers"]):
+        xin = lay["x_in"]
+        keep = budgets.get(l, cur_vis)
+        r = vc.vitcop_layer_prefill(dev(xin), dws[l]["wq"], dws[l]["wk"], dws[l]["wv"], dws[l]["wo"],
+                                    Hq, Hkv, d, vs, cur_vis, keep, residual=True)
+        nxt = ref["layers"][l + 1]["x_in"] if l + 1 < n_layers else ref["h"]
+        if lay["keep_idx"] is not None:
+            idx = r["keep_idx"].cpu().numpy()
+            nr = r["norms"].cpu().numpy()
+            for b in range(B):
+                assert_selection_matches(idx[b, vs:vs + keep] - vs, nr[b], lay["norms"][b], keep, False,
+                                         f"layer {l}")
+            if not np.array_equal(idx, lay["keep_idx"]):
+                cur_vis = keep
+                continue            # a near-tie at the cut: outputs are for a different, equally valid set
+        assert_attention_close(host_f64(r["y"]), O.bf16_to_f64(nxt), f"schedule layer {l}")
+        cur_vis = keep
+
+    # (2) free-running schedule through the one C call
+    y, pos = vc.vitcop_schedule_prefill(dev(x), dws, Hq, Hkv, d, vs, nv, sched)
+    torch.cuda.synchronize()
+    pos = pos.cpu().numpy()
+    assert y.shape == (B, T - nv + 12, D) and np.all(np.diff(pos, axis=1) > 0)
+    assert np.array_equal(pos[:, :vs], np.arange(vs)[None]) and np.array_equal(pos[:, vs + 12:], np.arange(vs + nv, T)[None])
+    if np.array_equal(pos, ref["positions"]):
+        assert_attention_close(host_f64(y), O.bf16_to_f64(ref["h"]), "schedule end to end")
+    else:
+        # survivors may differ only by near-ties; most must agree
+        common = len(set(pos[0].tolist()) & set(ref["positions"][0].tolist()))
+        assert common >= pos.shape[1] - 3
