@@ -145,23 +145,29 @@ def _ws(nbytes: int, like: torch.Tensor) -> torch.Tensor | None:
 # --------------------------------------------------------------------------
 
 
-def vitcop_filter_visual(q_cls, k, keep: int, scale: float = 0.0, want_scores: bool = True):
-    """q_cls [B,H,d], k [B,N+1,H,d] -> (scores [B,N] fp32 or None, idx [B,keep] int32)."""
+def vitcop_filter_visual(q_cls, k, keep: int, scale: float = 0.0, want_scores: bool = True,
+                         out=None):
+    """q_cls [B,H,d], k [B,N+1,H,d] -> (scores [B,N] fp32 or None, idx [B,keep] int32).
+
+    ``out`` = (scores, idx, ws) reuses buffers from an earlier call (no allocation).
+    """
     _dense(q_cls, "q_cls"); _dense(k, "k")
     B, N1, H, d = k.shape
     N = N1 - 1
-    scores = torch.empty((B, N), dtype=torch.float32, device=k.device) if want_scores else None
-    idx = torch.empty((B, max(keep, 0)), dtype=torch.int32, device=k.device)
-    nb = lib.vitcop_filter_visual_workspace_bytes(B, N, H, d)
-    ws = _ws(nb, k)
+    if out is not None:
+        scores, idx, ws = out
+    else:
+        scores = torch.empty((B, N), dtype=torch.float32, device=k.device) if want_scores else None
+        idx = torch.empty((B, max(keep, 0)), dtype=torch.int32, device=k.device)
+        ws = _ws(lib.vitcop_filter_visual_workspace_bytes(B, N, H, d), k)
     _check(lib.vitcop_filter_visual(_ptr(q_cls), _ptr(k), B, N, H, d, keep, scale, _ptr(scores),
                                     _ptr(idx), _ptr(ws), ws.numel(), _stream()))
-    return scores, idx
+    return (scores, idx, ws) if out is not None else (scores, idx)
 
 
 def vitcop_knorm_select(k, vis_start: int, n_vis: int, keep: int, *, norms=None, flags: int = 0,
                         k_row_stride: int | None = None, k_batch_stride: int | None = None,
-                        shape=None):
+                        shape=None, idx_out=None):
     """k [B,T,Hkv,d] -> (norms [B,n_vis] fp32, keep_idx [B,T'] int32).
 
     With ``flags & VITCOP_NORMS_PRECOMPUTED`` pass ``norms`` (and ``shape`` =
@@ -179,13 +185,14 @@ def vitcop_knorm_select(k, vis_start: int, n_vis: int, keep: int, *, norms=None,
     bs = T * rs if k_batch_stride is None else k_batch_stride
     if norms is None:
         norms = torch.empty((B, n_vis), dtype=torch.float32, device=dev)
-    idx = torch.empty((B, max(T - n_vis + keep, 0)), dtype=torch.int32, device=dev)
+    idx = idx_out if idx_out is not None else torch.empty(
+        (B, max(T - n_vis + keep, 0)), dtype=torch.int32, device=dev)
     _check(lib.vitcop_knorm_select(_ptr(k), rs, bs, B, T, Hkv, d, vis_start, n_vis, keep,
                                    _ptr(norms), _ptr(idx), flags, None, 0, _stream()))
     return norms, idx
 
 
-def vitcop_compact(srcs, idx, T_in: int | None = None):
+def vitcop_compact(srcs, idx, T_in: int | None = None, outs_in=None):
     """Each src [B,T_in,...] -> dst [B,T_out,...] gathered by idx [B,T_out] (int32)."""
     srcs = list(srcs)
     B, T_out = idx.shape
@@ -195,7 +202,8 @@ def vitcop_compact(srcs, idx, T_in: int | None = None):
         if not s.is_cuda or not s.is_contiguous():
             raise ValueError("sources must be contiguous CUDA tensors")
         row_bytes = s[0, 0].numel() * s.element_size() if s.dim() > 2 else s.element_size()
-        dst = torch.empty((B, T_out) + tuple(s.shape[2:]), dtype=s.dtype, device=s.device)
+        dst = outs_in[i] if outs_in is not None else torch.empty(
+            (B, T_out) + tuple(s.shape[2:]), dtype=s.dtype, device=s.device)
         arr[i] = GatherT(s.data_ptr(), dst.data_ptr(), row_bytes, row_bytes, s.shape[1] * row_bytes)
         outs.append(dst)
     t_in = srcs[0].shape[1] if (T_in is None and srcs) else (T_in or 0)
@@ -203,12 +211,13 @@ def vitcop_compact(srcs, idx, T_in: int | None = None):
     return outs
 
 
-def vitcop_prefill_attn(q, k, v, scale: float = 0.0, causal: bool = True, want_lse: bool = False):
+def vitcop_prefill_attn(q, k, v, scale: float = 0.0, causal: bool = True, want_lse: bool = False,
+                        out=None):
     """q [B,N,Hq,d], k,v [B,N,Hkv,d] -> (out [B,N,Hq,d] same dtype as q, lse [B,Hq,N] or None)."""
     _dense(q, "q"); _dense(k, "k"); _dense(v, "v")
     B, N, Hq, d = q.shape
     Hkv = k.shape[2]
-    out = torch.empty_like(q)
+    out = torch.empty_like(q) if out is None else out
     lse = torch.empty((B, Hq, N), dtype=torch.float32, device=q.device) if want_lse else None
     _check(lib.vitcop_prefill_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, N, Hq, Hkv, d,
                                    scale, 1 if causal else 0, None, 0, _stream()))
@@ -219,15 +228,21 @@ def vitcop_project_sumsq_parts(N: int) -> int:
     return lib.vitcop_project_sumsq_parts(N)
 
 
-def vitcop_project(x, w, residual=None, want_sumsq: bool = False):
-    """x [M,K], w [N,K] -> (y [M,N], sumsq_parts [P,M] fp32 or None)."""
+def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None):
+    """x [M,K], w [N,K] -> (y [M,N], sumsq_parts [P,M] fp32 or None).
+
+    ``out`` = (y, parts) reuses buffers from an earlier call.
+    """
     _dense(x, "x"); _dense(w, "w")
     M, K = x.shape
     N = w.shape[0]
-    y = torch.empty((M, N), dtype=x.dtype, device=x.device)
-    parts = None
-    if want_sumsq:
-        parts = torch.empty((vitcop_project_sumsq_parts(N), M), dtype=torch.float32, device=x.device)
+    if out is not None:
+        y, parts = out
+    else:
+        y = torch.empty((M, N), dtype=x.dtype, device=x.device)
+        parts = None
+        if want_sumsq:
+            parts = torch.empty((vitcop_project_sumsq_parts(N), M), dtype=torch.float32, device=x.device)
     if residual is not None:
         _dense(residual, "residual")
     _check(lib.vitcop_project(_ptr(x), K, _ptr(w), _ptr(y), N, _ptr(residual), N, M, N, K,
@@ -235,11 +250,14 @@ def vitcop_project(x, w, residual=None, want_sumsq: bool = False):
     return y, parts
 
 
-def vitcop_select_from_sumsq(parts, B: int, T: int, vis_start: int, n_vis: int, keep: int):
+def vitcop_select_from_sumsq(parts, B: int, T: int, vis_start: int, n_vis: int, keep: int, out=None):
     """parts [P, B*T] fp32 -> (norms [B,n_vis], keep_idx [B,T'])."""
     P = parts.shape[0]
-    norms = torch.empty((B, n_vis), dtype=torch.float32, device=parts.device)
-    idx = torch.empty((B, T - n_vis + keep), dtype=torch.int32, device=parts.device)
+    if out is not None:
+        norms, idx = out
+    else:
+        norms = torch.empty((B, n_vis), dtype=torch.float32, device=parts.device)
+        idx = torch.empty((B, T - n_vis + keep), dtype=torch.int32, device=parts.device)
     _check(lib.vitcop_select_from_sumsq(_ptr(parts), P, parts.shape[1], B, T, vis_start, n_vis, keep,
                                         _ptr(norms), _ptr(idx), _stream()))
     return norms, idx

@@ -51,14 +51,25 @@ def test_project_residual_and_strides(vc):
 
 
 def small_layer(seed, B=2, T=200, D=256, Hq=4, Hkv=2, d=128, vs=20, nv=150):
-    return I.layer_inputs(seed, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.06)
+    # log-normal row gains spread the K-norms the way real LVLM layers do; plain N(0,1)
+    # rows would all have nearly the same norm and every cut would fall among near-ties
+    gain, _ = I.lognormal_gains(seed, B, nv, outlier_frac=0.0)
+    return I.layer_inputs(seed, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.06, row_gain=gain)
 
 
 def gap_free(c, keep):
-    """True if the oracle's ranking has no near-tie at the cut (so both sides must agree exactly)."""
+    """True if the oracle's ranking has no near-tie at the cut (then both sides must agree exactly)."""
     kb = O.f64_to_bf16_bits(O.project(c["x"], c["wk"])).reshape(c["B"], c["T"], c["Hkv"], c["d"])
     n = O.k_norms(kb, c["vis_start"], c["n_vis"])
     return all(O.tie_band(n[b], keep, False, 4e-3).sum() <= 1 for b in range(c["B"]))
+
+
+def first_gap_free(make, keep, seed):
+    for s in range(seed, seed + 200):
+        c = make(s)
+        if gap_free(c, keep):
+            return c
+    raise AssertionError("no gap-free seed found")
 
 
 def run_layer(vc, c, keep, residual=False):
@@ -69,6 +80,23 @@ def run_layer(vc, c, keep, residual=False):
                                 residual=residual, positions=pos)
     torch.cuda.synchronize()
     return r
+
+
+def staged_layer(vc, c, idx, residual=False):
+    """The same layer through the separate entry points, with a GIVEN keep list."""
+    B, T, D, Hq, Hkv, d = c["B"], c["T"], c["D"], c["Hq"], c["Hkv"], c["d"]
+    x = dev(c["x"])
+    k_all, _ = vc.vitcop_project(x.reshape(B * T, D), dev(c["wk"]))
+    idx_t = torch.from_numpy(np.ascontiguousarray(idx)).cuda()
+    xs, ks = vc.vitcop_compact([x, k_all.reshape(B, T, Hkv, d)], idx_t)
+    Tp = idx.shape[1]
+    q, _ = vc.vitcop_project(xs.reshape(B * Tp, D), dev(c["wq"]))
+    v, _ = vc.vitcop_project(xs.reshape(B * Tp, D), dev(c["wv"]))
+    o, _ = vc.vitcop_prefill_attn(q.reshape(B, Tp, Hq, d), ks, v.reshape(B, Tp, Hkv, d))
+    y, _ = vc.vitcop_project(o.reshape(B * Tp, Hq * d), dev(c["wo"]),
+                             residual=xs.reshape(B * Tp, D) if residual else None)
+    torch.cuda.synchronize()
+    return {"y": y.reshape(B, Tp, D), "k": k_all, "q": q, "v": v, "o": o}
 
 
 def check_layer(vc, c, keep, residual, what):
@@ -82,32 +110,36 @@ def check_layer(vc, c, keep, residual, what):
     for b in range(c["B"]):
         assert_selection_matches(idx[b, vs:vs + keep] - vs, norms[b], ref["norms"][b], keep, False, what)
     assert np.array_equal(r["positions"].cpu().numpy(), idx)
-    assert np.array_equal(idx, ref["keep_idx"]), f"{what}: seed chosen gap-free, lists must agree"
-    assert_attention_close(host_f64(r["y"]), ref["y"], what)
+    # the separate entry points, driven by the ORACLE's keep list, reproduce the oracle's layer
+    st = staged_layer(vc, c, ref["keep_idx"], residual)
+    assert_bf16_of(host_bits(st["k"]).reshape(ref["k"].shape), O.project(c["x"], c["wk"]).reshape(ref["k"].shape), what)
+    assert_attention_close(host_f64(st["o"]).reshape(ref["attn"].shape), ref["attn"], what + " attn")
+    assert_attention_close(host_f64(st["y"]), ref["y"], what + " staged y")
+    # the one-call layer is the composition of those entry points on its own keep list
+    st_own = st if np.array_equal(idx, ref["keep_idx"]) else staged_layer(vc, c, idx, residual)
+    assert torch.equal(r["y"], st_own["y"]), what + ": fused call differs from the staged calls"
+    return np.array_equal(idx, ref["keep_idx"])
 
 
 @pytest.mark.parametrize("keep", [0, 17, 75, 150])
 def test_small_layer_matches_oracle(vc, keep):
-    seed = 900
-    while not gap_free(small_layer(seed), keep):
-        seed += 1
-    check_layer(vc, small_layer(seed), keep, False, f"small layer keep={keep}")
+    c = first_gap_free(small_layer, keep, 900)
+    same = check_layer(vc, c, keep, False, f"small layer keep={keep}")
+    assert same, "gap-free seed: the keep lists must agree exactly"
 
 
 def test_small_layer_residual_gqa(vc):
-    seed = 950
-    while not gap_free(small_layer(seed, B=1, T=333, D=512, Hq=8, Hkv=2, vs=0, nv=300), 100):
-        seed += 1
-    check_layer(vc, small_layer(seed, B=1, T=333, D=512, Hq=8, Hkv=2, vs=0, nv=300), 100, True, "gqa+res")
+    make = lambda s: small_layer(s, B=1, T=333, D=512, Hq=8, Hkv=2, vs=0, nv=300)
+    c = first_gap_free(make, 100, 950)
+    assert check_layer(vc, c, 100, True, "gqa+res")
 
 
 def test_config0_layer(vc):
-    trial = 0
-    while not gap_free(I.config0(trial), 64):
-        trial += 1
-    c = I.config0(trial)
-    check_layer(vc, c, 64, False, f"config 0 trial {trial}")
-    # unpruned limit of the same call
+    # N(0,1) hidden states give tightly concentrated K-norms: the cut falls among near-ties,
+    # so the GPU's list may differ from the oracle's inside the tie band (checked), and the
+    # outputs are then compared through the staged path
+    c = I.config0()
+    check_layer(vc, c, 64, False, "config 0")
     r = run_layer(vc, c, 576)
     u = O.unpruned_layer(c["x"], c["wq"], c["wk"], c["wv"], c["wo"], 32, 32, 128)
     assert_attention_close(host_f64(r["y"]), u["y"], "config 0 unpruned")
