@@ -1,0 +1,231 @@
+#!/usr/bin/env python3
+"""Benchmark of the pruned-prefill hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--keep 320] [--no-schedule] [--no-cpu]
+
+One step = one pass of the whole hot path over one batch of synthetic input:
+  Stage I filter on the batch's 20 CLIP-shaped image tiles (scores, top-k, feature compaction)
+  + one LLaVA-NeXT-7B-shaped attention layer with pruning on entry (batch 4, 2880 visual + 64
+  text tokens): K projection of all tokens with the norm side output, selection, compaction of
+  hidden states and K, Q/V projection of survivors, causal attention, output projection.
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=30)
+    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--keep", type=int, default=320, help="visual budget of the timed layer (of 2880)")
+    p.add_argument("--no-schedule", action="store_true", help="skip the 32-layer step-wise schedule leg")
+    p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    p.add_argument("--no-extras", action="store_true", help="only the headline step and its roofline")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+              "(no collectives or sharding are part of it).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    import vitcop_inputs as I
+    from paper_2601_17818_amd import binding as vc
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    def dev(bits):
+        return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).cuda().view(torch.bfloat16)
+
+    def ev_time(fn, reps, warm=3):
+        """Average milliseconds per call, HIP events on the stream the kernels are launched on."""
+        for _ in range(warm):
+            fn()
+        a = torch.cuda.Event(enable_timing=True)
+        b = torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            fn()
+        b.record()
+        b.synchronize()
+        return a.elapsed_time(b) / reps
+
+    # ------------------------------------------------------------------ inputs
+    c3 = I.config3()
+    B, T, D, Hq, Hkv, d = c3["B"], c3["T"], c3["D"], c3["Hq"], c3["Hkv"], c3["d"]
+    vs, nv = c3["vis_start"], c3["n_vis"]
+    x = dev(c3["x"])
+    wq, wk, wv, wo = (dev(c3[n]) for n in ("wq", "wk", "wv", "wo"))
+    tiles = I.config1(B=5 * B)                       # 5 tiles per image, CLIP ViT-L/14-336 shape
+    f_q, f_k, f_feat = dev(tiles["q_cls"]), dev(tiles["k"]), dev(tiles["feats"][:, 1:, :])
+    f_keep = tiles["keep"]
+    f_out = vc.vitcop_filter_visual(f_q, f_k, f_keep)
+    f_bufs = (f_out[0], f_out[1], torch.empty(vc.lib.vitcop_filter_visual_workspace_bytes(
+        5 * B, tiles["N"], tiles["H"], tiles["d"]), dtype=torch.uint8, device="cuda"))
+    f_cmp = vc.vitcop_compact([f_feat], f_bufs[1])
+
+    plans = {k: vc.LayerPlan(x, wq, wk, wv, wo, Hq, Hkv, d, vs, nv, k, want_norms=False)
+             for k in sorted(set(c3["keeps"]) | {args.keep, nv})}
+    plan = plans[args.keep]
+    Tp = T - nv + args.keep
+
+    def step():
+        vc.vitcop_filter_visual(f_q, f_k, f_keep, out=f_bufs)
+        vc.vitcop_compact([f_feat], f_bufs[1], outs_in=f_cmp)
+        plan.run()
+
+    # ------------------------------------------------------------ timed region
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tokens_per_s = B * T / (ms_per_step * 1e-3)
+
+    # ------------------------------------------- per-kernel durations (HIP events)
+    reps = max(5, args.steps)
+    kd, qd = Hkv * d, Hq * d
+    kbuf = vc.vitcop_project(x.reshape(B * T, D), wk, want_sumsq=True)
+    t_kproj = ev_time(lambda: vc.vitcop_project(x.reshape(B * T, D), wk, want_sumsq=True, out=kbuf), reps)
+    kproj_flops = 2.0 * B * T * kd * D
+    roofline = {
+        "kernel": "gemm_kernel<256,256> (K projection with squared-norm epilogue)",
+        "bound": "mfma", "achieved": kproj_flops / (t_kproj * 1e-3) / 1e12,
+        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "traffic": None,
+    }
+    roofline["frac"] = roofline["achieved"] / roofline["peak"]
+
+    out = {
+        "metric": "pruned_prefill_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": f"config3: LLaVA-NeXT-7B-shaped layer, B={B}, T={T} (2880 visual + 64 text), "
+                               f"keep {args.keep} of {nv} visual (T'={Tp}), D={D}, {Hq}x{d} MHA; "
+                               f"plus Stage I filter on {5 * B} CLIP tiles (577x16x64, keep {f_keep})",
+                   "seed": I.seed_for(3)},
+        "roofline": roofline,
+    }
+
+    if not args.no_extras:
+        kern = {}
+        kern["kproj_gemm_ms"] = t_kproj
+        # K-norm + select as its own call on the projected K (algorithmic bytes: K rows + norms + list)
+        k_all = kbuf[0].reshape(B, T, Hkv, d)
+        nbuf = torch.empty((B, nv), dtype=torch.float32, device="cuda")
+        ibuf = torch.empty((B, Tp), dtype=torch.int32, device="cuda")
+        t_ks = ev_time(lambda: vc.vitcop_knorm_select(k_all, vs, nv, args.keep, norms=nbuf, idx_out=ibuf), reps)
+        ks_bytes = B * nv * (2 * kd + 4) + B * Tp * 4
+        kern["knorm_select_ms"] = t_ks
+        kern["knorm_select_GBps"] = ks_bytes / (t_ks * 1e-3) / 1e9
+        # streaming measurement: many independent config-0-shaped samples, > 1 GiB of K
+        R = 288
+        kbig = torch.randn((R, 640, 32, 128), dtype=torch.bfloat16, device="cuda")
+        nb2 = torch.empty((R, 576), dtype=torch.float32, device="cuda")
+        ib2 = torch.empty((R, 128), dtype=torch.int32, device="cuda")
+        t_s = ev_time(lambda: vc.vitcop_knorm_select(kbig, 35, 576, 64, norms=nb2, idx_out=ib2), 10)
+        s_bytes = R * 576 * (2 * 4096 + 4) + R * 128 * 4
+        kern["knorm_select_stream_GBps"] = s_bytes / (t_s * 1e-3) / 1e9
+        kern["knorm_select_stream_frac_hbm"] = kern["knorm_select_stream_GBps"] / HBM_PEAK_GBPS
+        idx_big = ib2
+        cbig = torch.empty((R, 128, 32, 128), dtype=torch.bfloat16, device="cuda")
+        t_c = ev_time(lambda: vc.vitcop_compact([kbig], idx_big, outs_in=[cbig]), 10)
+        kern["compact_stream_GBps"] = (R * 128 * (2 * 8192 + 4)) / (t_c * 1e-3) / 1e9
+        del kbig, cbig
+        # filter (config 1 shape x 20 tiles)
+        t_f = ev_time(lambda: vc.vitcop_filter_visual(f_q, f_k, f_keep, out=f_bufs), reps)
+        f_bytes = 5 * B * (577 * 1024 * 2 + f_keep * 4)
+        kern["filter_ms"] = t_f
+        kern["filter_GBps"] = f_bytes / (t_f * 1e-3) / 1e9
+        # attention: pruned shape and the unpruned shape
+        for name, n_att in (("attn_pruned", Tp), ("attn_unpruned", T)):
+            qq = torch.randn((B, n_att, Hq, d), dtype=torch.bfloat16, device="cuda")
+            kk = torch.randn((B, n_att, Hkv, d), dtype=torch.bfloat16, device="cuda")
+            vv = torch.randn((B, n_att, Hkv, d), dtype=torch.bfloat16, device="cuda")
+            oo = torch.empty_like(qq)
+            t_a = ev_time(lambda: vc.vitcop_prefill_attn(qq, kk, vv, out=oo), max(3, reps // 3))
+            fl = 4.0 * d * Hq * B * n_att * (n_att + 1) / 2
+            kern[name + "_ms"] = t_a
+            kern[name + "_TFLOPs"] = fl / (t_a * 1e-3) / 1e12
+            kern[name + "_frac_mfma"] = kern[name + "_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
+            del qq, kk, vv, oo
+        # the layer alone at each keep ratio, and the unpruned layer
+        layer_ms = {}
+        for k_, p_ in plans.items():
+            layer_ms[k_] = ev_time(p_.run, max(3, reps // 3))
+        kern["layer_ms"] = {("unpruned" if k_ == nv else f"keep{k_}"): v_ for k_, v_ in layer_ms.items()}
+        out["speedup_vs_unpruned"] = {f"keep{k_}": layer_ms[nv] / v_ for k_, v_ in layer_ms.items() if k_ != nv}
+        out["layer_tokens_per_s"] = {("unpruned" if k_ == nv else f"keep{k_}"): B * T / (v_ * 1e-3)
+                                     for k_, v_ in layer_ms.items()}
+        out["knorm_select_GBps"] = kern["knorm_select_stream_GBps"]
+        out["attn_bf16_TFLOPs"] = kern["attn_unpruned_TFLOPs"]
+        out["attn_frac_of_peak"] = kern["attn_unpruned_frac_mfma"]
+        out["kernels"] = kern
+
+    # -------------------------------------- step-wise schedule (config 2, 32 layers)
+    if not args.no_schedule and not args.no_extras:
+        from concurrent.futures import ThreadPoolExecutor
+        h2 = I.config2_hidden()
+        with ThreadPoolExecutor(max_workers=8) as ex:
+            w_host = list(ex.map(I.config2_layer_weights, range(I.CONFIG2_LAYERS)))
+        for w in w_host:      # small output projection keeps the residual stream bounded without a norm
+            w["wo"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w["wo"]) * np.float32(0.125))
+        w_dev = [{n: dev(w[n]) for n in ("wq", "wk", "wv", "wo")} for w in w_host]
+        del w_host
+        x2 = dev(h2["x"])
+        sp = vc.SchedulePlan(x2, w_dev, 32, 32, 128, 35, 576, I.CONFIG2_SCHEDULE)
+        up = vc.SchedulePlan(x2, w_dev, 32, 32, 128, 35, 576, ())
+        t_sched = ev_time(sp.run, 5, warm=2)
+        t_unpr = ev_time(up.run, 5, warm=2)
+        out["schedule_config2"] = {"ms_pruned": t_sched, "ms_unpruned": t_unpr,
+                                   "speedup": t_unpr / t_sched, "tokens_per_s": 640 / (t_sched * 1e-3),
+                                   "layers": 32, "schedule": list(map(list, I.CONFIG2_SCHEDULE))}
+        del w_dev, sp, up
+
+    # ------------------------------------------------------ CPU oracle baseline
+    if not args.no_cpu:
+        from oracle import vitcop_oracle as O
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        t0 = time.perf_counter()
+        O.pruned_layer(c3["x"], c3["wq"], c3["wk"], c3["wv"], c3["wo"], Hq, Hkv, d, vs, nv, args.keep)
+        O.filter_visual(tiles["q_cls"], tiles["k"], f_keep)
+        t_cpu = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": B * T / t_cpu, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
+                               "sample": f"one full step of the same workload ({B} samples x {T} tokens, fp64 "
+                                         f"pruned layer + filter on {5 * B} tiles), {t_cpu:.1f} s"}
+
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
