@@ -67,18 +67,18 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     const int vkq = tid & 15, vc = tid >> 4;      // V: key quad, channel chunk
     // position of the key quad inside its row of V^T: swap the two low bits of the quad index
     const int vpq = (vkq & ~3) | ((vkq & 1) << 1) | ((vkq >> 1) & 1);
-    uint4 kr[4], vr[4];
+    u32x4 kr[4], vr[4];
     auto load_tile = [&](int t) {
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int id = tid + AT_THREADS * j;
             const int key = min(t * AT_BN + (id >> 4), N - 1);
-            kr[j] = *reinterpret_cast<const uint4*>(kbase + key * kv_rs + (id & 15) * 8);
+            kr[j] = *reinterpret_cast<const u32x4*>(kbase + key * kv_rs + (id & 15) * 8);
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int key = min(t * AT_BN + 4 * vkq + j, N - 1);
-            vr[j] = *reinterpret_cast<const uint4*>(vbase + key * kv_rs + vc * 8);
+            vr[j] = *reinterpret_cast<const u32x4*>(vbase + key * kv_rs + vc * 8);
         }
     };
     load_tile(0);
@@ -88,20 +88,17 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int id = tid + AT_THREADS * j;
-            *reinterpret_cast<uint4*>(&Ks[(id >> 4) * AT_KLD + (id & 15) * 8]) = kr[j];
+            *reinterpret_cast<u32x4*>(&Ks[(id >> 4) * AT_KLD + (id & 15) * 8]) = kr[j];
         }
         {
-            const uint32_t w0[4] = {vr[0].x, vr[0].y, vr[0].z, vr[0].w};
-            const uint32_t w1[4] = {vr[1].x, vr[1].y, vr[1].z, vr[1].w};
-            const uint32_t w2[4] = {vr[2].x, vr[2].y, vr[2].z, vr[2].w};
-            const uint32_t w3[4] = {vr[3].x, vr[3].y, vr[3].z, vr[3].w};
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
+                const uint32_t w0 = vr[0][p], w1 = vr[1][p], w2 = vr[2][p], w3 = vr[3][p];
                 uint2 ev, od;
-                ev.x = (w0[p] & 0xFFFFu) | (w1[p] << 16);
-                ev.y = (w2[p] & 0xFFFFu) | (w3[p] << 16);
-                od.x = (w0[p] >> 16) | (w1[p] & 0xFFFF0000u);
-                od.y = (w2[p] >> 16) | (w3[p] & 0xFFFF0000u);
+                ev.x = (w0 & 0xFFFFu) | (w1 << 16);
+                ev.y = (w2 & 0xFFFFu) | (w3 << 16);
+                od.x = (w0 >> 16) | (w1 & 0xFFFF0000u);
+                od.y = (w2 >> 16) | (w3 & 0xFFFF0000u);
                 *reinterpret_cast<uint2*>(&Vt[(vc * 8 + 2 * p) * AT_VLD + vpq * 4]) = ev;
                 *reinterpret_cast<uint2*>(&Vt[(vc * 8 + 2 * p + 1) * AT_VLD + vpq * 4]) = od;
             }

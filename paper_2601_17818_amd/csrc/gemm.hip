@@ -47,19 +47,19 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    uint4 xr[XCH], wr[WCH];
+    u32x4 xr[XCH], wr[WCH];
     auto load_tile = [&](int k0) {
 #pragma unroll
         for (int j = 0; j < XCH; ++j) {
             const int id = tid + GM_THREADS * j;
             const int row = min(m0 + (id >> 2), M - 1);
-            xr[j] = *reinterpret_cast<const uint4*>(x + (int64_t)row * x_stride + k0 + (id & 3) * 8);
+            xr[j] = *reinterpret_cast<const u32x4*>(x + (int64_t)row * x_stride + k0 + (id & 3) * 8);
         }
 #pragma unroll
         for (int j = 0; j < WCH; ++j) {
             const int id = tid + GM_THREADS * j;
             const int row = min(n0 + (id >> 2), N - 1);
-            wr[j] = *reinterpret_cast<const uint4*>(w + (int64_t)row * K + k0 + (id & 3) * 8);
+            wr[j] = *reinterpret_cast<const u32x4*>(w + (int64_t)row * K + k0 + (id & 3) * 8);
         }
     };
     load_tile(0);
@@ -69,12 +69,12 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < XCH; ++j) {
             const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<uint4*>(&Xs[(id >> 2) * GM_LD + (id & 3) * 8]) = xr[j];
+            *reinterpret_cast<u32x4*>(&Xs[(id >> 2) * GM_LD + (id & 3) * 8]) = xr[j];
         }
 #pragma unroll
         for (int j = 0; j < WCH; ++j) {
             const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<uint4*>(&Ws[(id >> 2) * GM_LD + (id & 3) * 8]) = wr[j];
+            *reinterpret_cast<u32x4*>(&Ws[(id >> 2) * GM_LD + (id & 3) * 8]) = wr[j];
         }
         __syncthreads();
         if (k0 + GM_BK < K) load_tile(k0 + GM_BK);
