@@ -9,35 +9,65 @@
 // operand, x tile as the B operand): a lane then owns one output row m and
 // 4-element runs of consecutive columns n, which gives 8-byte stores and
 // in-lane row sums for the norm epilogue.
+//
+// Pipeline: k-steps of 64; two LDS stages; global -> registers -> LDS with the
+// loads for step t+2 in flight while step t is multiplied; one barrier per
+// k-step; MFMA fragments of the next 16-wide slice are read while the current
+// slice is multiplied.  Workgroups are renumbered so that each XCD (own L2)
+// works on a compact patch of output tiles.
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
-constexpr int GM_BK = 32;
-constexpr int GM_LD = GM_BK + 8;     // bf16 per LDS row (80 B: conflict-free 16 B reads)
+constexpr int GM_BK = 64;
+constexpr int GM_LD = GM_BK + 8;     // bf16 per LDS row (144 B: conflict-free 16-byte reads)
 constexpr int GM_PART = 128;         // columns per sum-of-squares partial
+constexpr int GM_XCDS = 8;
+
+template <int BM, int BN>
+constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * GM_LD * sizeof(uint16_t); }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w,
     uint16_t* __restrict__ y, int64_t y_stride, const uint16_t* __restrict__ res,
-    int64_t res_stride, int M, int N, int K, float* __restrict__ sumsq_parts) {
+    int64_t res_stride, int M, int N, int K, float* __restrict__ sumsq_parts, int tiles_m,
+    int tiles_n, int group_m) {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts");
     constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
     constexpr int MI = TM / 32, NI = TN / 32;
     static_assert(TN == GM_PART, "one sum-of-squares partial per wavefront");
-    constexpr int XCH = BM * GM_BK / 8 / GM_THREADS;   // 16-byte chunks per thread
+    constexpr int XCH = BM * GM_BK / 8 / GM_THREADS;   // 16-byte chunks per thread per stage
     constexpr int WCH = BN * GM_BK / 8 / GM_THREADS;
+    constexpr int STAGE = (BM + BN) * GM_LD;           // elements per LDS stage
 
-    __shared__ __attribute__((aligned(16))) uint16_t Xs[BM * GM_LD];
-    __shared__ __attribute__((aligned(16))) uint16_t Ws[BN * GM_LD];
+    extern __shared__ __attribute__((aligned(16))) uint16_t gemm_lds[];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
     const int wm = wv % WAVES_M, wn = wv / WAVES_M;
-    const int m0 = blockIdx.y * BM, n0 = blockIdx.x * BN;
+
+    // Workgroup -> tile.  Consecutive workgroup ids go to different XCDs, so id % 8 picks the
+    // XCD and id / 8 the slot inside it; each XCD walks a contiguous range of a grouped
+    // ordering (group_m tile rows by all tile columns, column-major inside the group).
+    int tile_m, tile_n;
+    {
+        const int nt = tiles_m * tiles_n;
+        const int pid = blockIdx.x;
+        const int per = (nt + GM_XCDS - 1) / GM_XCDS;
+        int lin = (pid % GM_XCDS) * per + pid / GM_XCDS;
+        if (nt % GM_XCDS != 0) lin = pid;             // ragged: plain order
+        const int width = group_m * tiles_n;
+        const int grp = lin / width;
+        const int first = grp * group_m;
+        const int gsz = min(tiles_m - first, group_m);
+        const int in = lin - grp * width;
+        tile_m = first + in % gsz;
+        tile_n = in / gsz;
+    }
+    const int m0 = tile_m * BM, n0 = tile_n * BN;
 
     f32x16 acc[NI][MI];
 #pragma unroll
@@ -47,55 +77,113 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+    // global -> register staging: chunk id -> (row = id / 8, 16-byte column = id % 8);
+    // 32-bit element offsets from a base that advances with k (the host checks the range)
+    int xo[XCH], wo[WCH];
+#pragma unroll
+    for (int j = 0; j < XCH; ++j) {
+        const int id = tid + GM_THREADS * j;
+        xo[j] = min(m0 + (id >> 3), M - 1) * (int)x_stride + (id & 7) * 8;
+    }
+#pragma unroll
+    for (int j = 0; j < WCH; ++j) {
+        const int id = tid + GM_THREADS * j;
+        wo[j] = min(n0 + (id >> 3), N - 1) * K + (id & 7) * 8;
+    }
     u32x4 xr[XCH], wr[WCH];
     auto load_tile = [&](int k0) {
+        const uint16_t* xb = x + k0;
+        const uint16_t* wb = w + k0;
+#pragma unroll
+        for (int j = 0; j < XCH; ++j) xr[j] = *reinterpret_cast<const u32x4*>(xb + xo[j]);
+#pragma unroll
+        for (int j = 0; j < WCH; ++j) wr[j] = *reinterpret_cast<const u32x4*>(wb + wo[j]);
+    };
+    auto store_tile = [&](int stage) {
+        uint16_t* Xs = gemm_lds + stage * STAGE;
+        uint16_t* Ws = Xs + BM * GM_LD;
 #pragma unroll
         for (int j = 0; j < XCH; ++j) {
             const int id = tid + GM_THREADS * j;
-            const int row = min(m0 + (id >> 2), M - 1);
-            xr[j] = *reinterpret_cast<const u32x4*>(x + (int64_t)row * x_stride + k0 + (id & 3) * 8);
+            *reinterpret_cast<u32x4*>(&Xs[(id >> 3) * GM_LD + (id & 7) * 8]) = xr[j];
         }
 #pragma unroll
         for (int j = 0; j < WCH; ++j) {
             const int id = tid + GM_THREADS * j;
-            const int row = min(n0 + (id >> 2), N - 1);
-            wr[j] = *reinterpret_cast<const u32x4*>(w + (int64_t)row * K + k0 + (id & 3) * 8);
+            *reinterpret_cast<u32x4*>(&Ws[(id >> 3) * GM_LD + (id & 7) * 8]) = wr[j];
         }
     };
-    load_tile(0);
 
-    for (int k0 = 0; k0 < K; k0 += GM_BK) {
-        __syncthreads();
+    const int xoff = (wm * TM + l32) * GM_LD + g * 8;
+    const int woff = BM * GM_LD + (wn * TN + l32) * GM_LD + g * 8;
+    bf16x8 xf[2][MI], wf[2][NI];
+    auto read_frags = [&](int buf, int stage, int kc) {
+        const uint16_t* S = gemm_lds + stage * STAGE + kc * 16;
 #pragma unroll
-        for (int j = 0; j < XCH; ++j) {
-            const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<u32x4*>(&Xs[(id >> 2) * GM_LD + (id & 3) * 8]) = xr[j];
-        }
+        for (int j = 0; j < MI; ++j)
+            xf[buf][j] = *reinterpret_cast<const bf16x8*>(&S[xoff + j * 32 * GM_LD]);
 #pragma unroll
-        for (int j = 0; j < WCH; ++j) {
-            const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<u32x4*>(&Ws[(id >> 2) * GM_LD + (id & 3) * 8]) = wr[j];
-        }
-        __syncthreads();
-        if (k0 + GM_BK < K) load_tile(k0 + GM_BK);
+        for (int i = 0; i < NI; ++i)
+            wf[buf][i] = *reinterpret_cast<const bf16x8*>(&S[woff + i * 32 * GM_LD]);
+    };
+    auto multiply = [&](int buf) {
 #pragma unroll
-        for (int kc = 0; kc < GM_BK / 16; ++kc) {
-            bf16x8 xf[MI], wf[NI];
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
             for (int j = 0; j < MI; ++j)
-                xf[j] = *reinterpret_cast<const bf16x8*>(
-                    &Xs[(wm * TM + j * 32 + l32) * GM_LD + kc * 16 + g * 8]);
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-                wf[i] = *reinterpret_cast<const bf16x8*>(
-                    &Ws[(wn * TN + i * 32 + l32) * GM_LD + kc * 16 + g * 8]);
-#pragma unroll
-            for (int i = 0; i < NI; ++i)
-#pragma unroll
-                for (int j = 0; j < MI; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i], xf[j], acc[i][j], 0, 0, 0);
-        }
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][i], xf[buf][j], acc[i][j], 0, 0, 0);
+    };
+    // scheduling hints: alternate one MFMA with `per` memory instructions of class `mask`
+    // (0x100 LDS read, 0x200 LDS write, 0x020 global read), `n` times
+#define VITCOP_INTERLEAVE(mask, per, n)                              \
+    _Pragma("unroll") for (int q_ = 0; q_ < (n); ++q_) {             \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           \
+        __builtin_amdgcn_sched_group_barrier((mask), (per), 0);      \
     }
+    constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
+    constexpr int REST = NMFMA - NFRAG;
+
+    // Software pipeline over k-steps.  Stage s = t & 1 holds tile t.  Within step t:
+    //   slice 0: multiply slice 0, read slice 1
+    //   slice 1: multiply slice 1, read slice 2, write tile t+1 (in registers) to stage s^1
+    //   slice 2: multiply slice 2, read slice 3, start the global loads of tile t+2
+    //   barrier (stage s^1 is complete; every wave is past its last read of ... see below)
+    //   slice 3: multiply slice 3, read slice 0 of tile t+1 from stage s^1
+    // Stage s^1 was last read before the barrier of step t-1, so the writes in slice 1 are safe.
+    // Past the end the loads repeat the last tile and the extra LDS traffic is never consumed.
+    const int nk = K / GM_BK;
+    load_tile(0);
+    store_tile(0);
+    load_tile(min(1, nk - 1) * GM_BK);
+    __syncthreads();
+    read_frags(0, 0, 0);
+
+    for (int t = 0; t < nk; ++t) {
+        const int s = t & 1;
+        read_frags(1, s, 1);
+        multiply(0);
+        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
+        __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+
+        read_frags(0, s, 2);
+        store_tile(s ^ 1);
+        multiply(1);
+        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
+        VITCOP_INTERLEAVE(0x200, (XCH + WCH + REST - 1) / REST, REST)
+
+        read_frags(1, s, 3);
+        load_tile(min(t + 2, nk - 1) * GM_BK);
+        multiply(0);
+        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
+        VITCOP_INTERLEAVE(0x020, (XCH + WCH + REST - 1) / REST, REST)
+
+        __syncthreads();
+        read_frags(0, s ^ 1, 0);
+        multiply(1);
+        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
+        __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+    }
+#undef VITCOP_INTERLEAVE
 
     // epilogue: lane owns row m = .. + l32 and columns n = .. + 8*(r/4) + 4*g + r%4
 #pragma unroll
@@ -140,22 +228,40 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 
 int gemm_sumsq_parts(int N) { return (N + GM_PART - 1) / GM_PART; }
 
+template <int BM, int BN, int WAVES_M, int WAVES_N>
+static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
+                           int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
+                           int K, float* sumsq_parts, hipStream_t s) {
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+    static bool attr_set = false;        // per kernel instantiation; setting it twice is harmless
+    if (!attr_set) {
+        int rc = hip_status(hipFuncSetAttribute((const void*)kern,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
+                            "hipFuncSetAttribute(gemm)");
+        if (rc) return rc;
+        attr_set = true;
+    }
+    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    // tile rows per group: a patch of about 32 tiles (one XCD's worth of workgroups) near square
+    int group_m = 1;
+    while (group_m * 2 <= tiles_m && group_m * group_m * 2 <= 32) group_m *= 2;
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(GM_THREADS), lds, s, x, x_stride, w, y,
+                       y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m);
+    return launch_status("gemm");
+}
+
 int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                 int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                 int K, float* sumsq_parts, hipStream_t s) {
     if (M == 0 || N == 0) return VITCOP_OK;
     // large problems: 256x256 tiles (each wavefront 128x128); otherwise 128x128 tiles
     const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big_tiles >= 192) {
-        dim3 grid((N + 255) / 256, (M + 255) / 256);
-        hipLaunchKernelGGL((gemm_kernel<256, 256, 2, 2>), grid, dim3(GM_THREADS), 0, s, x, x_stride,
-                           w, y, y_stride, res, res_stride, M, N, K, sumsq_parts);
-    } else {
-        dim3 grid((N + 127) / 128, (M + 127) / 128);
-        hipLaunchKernelGGL((gemm_kernel<128, 128, 4, 1>), grid, dim3(GM_THREADS), 0, s, x, x_stride,
-                           w, y, y_stride, res, res_stride, M, N, K, sumsq_parts);
-    }
-    return launch_status("gemm");
+    if (big_tiles >= 192)
+        return launch_gemm_cfg<256, 256, 2, 2>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                               sumsq_parts, s);
+    return launch_gemm_cfg<128, 128, 4, 1>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                           sumsq_parts, s);
 }
 
 }  // namespace vitcop
