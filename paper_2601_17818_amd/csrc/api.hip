@@ -219,7 +219,7 @@ int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w, u
     REQUIRE(!residual || (res_row_stride >= N && res_row_stride % 8 == 0), VITCOP_EINVAL,
             "project: residual stride %lld", (long long)res_row_stride);
     REQUIRE((int64_t)M * x_row_stride < ((int64_t)1 << 31) && (int64_t)N * K < ((int64_t)1 << 31),
-            VITCOP_EUNSUPPORTED, "project: operand larger than 2^31 elements");
+            VITCOP_EUNSUPPORTED, "project: operand larger than 2^31 elements (4 GiB)");
     if (M == 0 || N == 0) return VITCOP_OK;
     REQUIRE(x && w && y, VITCOP_EINVAL, "project: null pointer");
     REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(residual), VITCOP_EINVAL,

@@ -79,38 +79,36 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 
     // global -> register staging: chunk id -> (row = id / 8, 16-byte column = id % 8);
     // 32-bit element offsets from a base that advances with k (the host checks the range)
-    int xo[XCH], wo[WCH];
+    // (unsigned byte offsets: base in scalar registers + one 32-bit register per chunk)
+    const int srow = tid >> 3, scol = (tid & 7) * 8;      // chunk j sits 32*j rows further down
+    unsigned xo[XCH], wo[WCH];
 #pragma unroll
-    for (int j = 0; j < XCH; ++j) {
-        const int id = tid + GM_THREADS * j;
-        xo[j] = min(m0 + (id >> 3), M - 1) * (int)x_stride + (id & 7) * 8;
-    }
+    for (int j = 0; j < XCH; ++j)
+        xo[j] = 2u * (unsigned)(min(m0 + srow + 32 * j, M - 1) * (int)x_stride + scol);
 #pragma unroll
-    for (int j = 0; j < WCH; ++j) {
-        const int id = tid + GM_THREADS * j;
-        wo[j] = min(n0 + (id >> 3), N - 1) * K + (id & 7) * 8;
-    }
-    u32x4 xr[XCH], wr[WCH];
-    auto load_tile = [&](int k0) {
-        const uint16_t* xb = x + k0;
-        const uint16_t* wb = w + k0;
+    for (int j = 0; j < WCH; ++j)
+        wo[j] = 2u * (unsigned)(min(n0 + srow + 32 * j, N - 1) * K + scol);
+    // Two register staging sets; a tile is fetched two k-steps before it is written to LDS.
+    // The 16-byte chunks of a tile (XCH of x, then WCH of W) are handled one quarter per
+    // 16-wide slice, so the LDS writes and the global loads are spread over the whole k-step.
+    constexpr int NCH = XCH + WCH, QCH = NCH / 4;
+    static_assert(NCH % 4 == 0, "chunks split evenly over the four slices");
+    u32x4 st[2][NCH];
+    auto load_chunks = [&](int set, int k0, int c0, int c1) {
+        const char* xb = reinterpret_cast<const char*>(x + k0);
+        const char* wb = reinterpret_cast<const char*>(w + k0);
 #pragma unroll
-        for (int j = 0; j < XCH; ++j) xr[j] = *reinterpret_cast<const u32x4*>(xb + xo[j]);
-#pragma unroll
-        for (int j = 0; j < WCH; ++j) wr[j] = *reinterpret_cast<const u32x4*>(wb + wo[j]);
+        for (int c = c0; c < c1; ++c)
+            st[set][c] = c < XCH ? *reinterpret_cast<const u32x4*>(xb + xo[c < XCH ? c : 0])
+                                 : *reinterpret_cast<const u32x4*>(wb + wo[c < XCH ? 0 : c - XCH]);
     };
-    auto store_tile = [&](int stage) {
-        uint16_t* Xs = gemm_lds + stage * STAGE;
+    auto store_chunks = [&](int set, int stage, int c0, int c1) {
+        uint16_t* Xs = gemm_lds + stage * STAGE + srow * GM_LD + scol;
         uint16_t* Ws = Xs + BM * GM_LD;
 #pragma unroll
-        for (int j = 0; j < XCH; ++j) {
-            const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<u32x4*>(&Xs[(id >> 3) * GM_LD + (id & 7) * 8]) = xr[j];
-        }
-#pragma unroll
-        for (int j = 0; j < WCH; ++j) {
-            const int id = tid + GM_THREADS * j;
-            *reinterpret_cast<u32x4*>(&Ws[(id >> 3) * GM_LD + (id & 7) * 8]) = wr[j];
+        for (int c = c0; c < c1; ++c) {
+            if (c < XCH) *reinterpret_cast<u32x4*>(Xs + c * 32 * GM_LD) = st[set][c];
+            else *reinterpret_cast<u32x4*>(Ws + (c - XCH) * 32 * GM_LD) = st[set][c];
         }
     };
 
@@ -141,48 +139,68 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         __builtin_amdgcn_sched_group_barrier((mask), (per), 0);      \
     }
     constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
-    constexpr int REST = NMFMA - NFRAG;
 
-    // Software pipeline over k-steps.  Stage s = t & 1 holds tile t.  Within step t:
-    //   slice 0: multiply slice 0, read slice 1
-    //   slice 1: multiply slice 1, read slice 2, write tile t+1 (in registers) to stage s^1
-    //   slice 2: multiply slice 2, read slice 3, start the global loads of tile t+2
-    //   barrier (stage s^1 is complete; every wave is past its last read of ... see below)
-    //   slice 3: multiply slice 3, read slice 0 of tile t+1 from stage s^1
-    // Stage s^1 was last read before the barrier of step t-1, so the writes in slice 1 are safe.
+    // Software pipeline over k-steps.  LDS stage s = t & 1 holds tile t; on entry to step t
+    // register set s holds tile t+1 (its first quarter already in LDS and refilled with tile
+    // t+3) and set s^1 holds tile t+2.  Step t, slice by slice (each slice: 16 MFMAs, the
+    // fragment reads of the next slice, a quarter of the LDS writes and of the global loads):
+    //   slices 0..2: quarters 1..3 of tile t+1 go from set s to stage s^1; each register is
+    //                refilled with tile t+3 right after it is written
+    //   barrier     (stage s^1 complete; nobody reads stage s any more: slice 3 was fetched)
+    //   slice 3:     reads slice 0 of tile t+1 from stage s^1; quarter 0 of tile t+2 goes
+    //                from set s^1 to stage s, refilled with tile t+4
     // Past the end the loads repeat the last tile and the extra LDS traffic is never consumed.
     const int nk = K / GM_BK;
-    load_tile(0);
-    store_tile(0);
-    load_tile(min(1, nk - 1) * GM_BK);
-    __syncthreads();
-    read_frags(0, 0, 0);
-
-    for (int t = 0; t < nk; ++t) {
-        const int s = t & 1;
+    auto tile_k = [&](int tile) { return min(tile, nk - 1) * GM_BK; };
+#define VITCOP_SLICE_HINTS()                                                         \
+    if constexpr (NMFMA >= NFRAG + 2 * QCH) {                                        \
+        VITCOP_INTERLEAVE(0x100, 1, NFRAG)                                           \
+        VITCOP_INTERLEAVE(0x200, 1, QCH)                                             \
+        VITCOP_INTERLEAVE(0x020, 1, QCH)                                             \
+        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG - 2 * QCH, 0);     \
+    }
+    auto step = [&](int t, int set) {
+        const int s = set;             // == t & 1, kept a compile-time constant after inlining
         read_frags(1, s, 1);
+        store_chunks(set, s ^ 1, QCH, 2 * QCH);
+        load_chunks(set, tile_k(t + 3), QCH, 2 * QCH);
         multiply(0);
-        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
-        __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+        VITCOP_SLICE_HINTS()
 
         read_frags(0, s, 2);
-        store_tile(s ^ 1);
+        store_chunks(set, s ^ 1, 2 * QCH, 3 * QCH);
+        load_chunks(set, tile_k(t + 3), 2 * QCH, 3 * QCH);
         multiply(1);
-        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
-        VITCOP_INTERLEAVE(0x200, (XCH + WCH + REST - 1) / REST, REST)
+        VITCOP_SLICE_HINTS()
 
         read_frags(1, s, 3);
-        load_tile(min(t + 2, nk - 1) * GM_BK);
+        store_chunks(set, s ^ 1, 3 * QCH, NCH);
+        load_chunks(set, tile_k(t + 3), 3 * QCH, NCH);
         multiply(0);
-        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
-        VITCOP_INTERLEAVE(0x020, (XCH + WCH + REST - 1) / REST, REST)
+        VITCOP_SLICE_HINTS()
 
         __syncthreads();
         read_frags(0, s ^ 1, 0);
+        store_chunks(set ^ 1, s, 0, QCH);
+        load_chunks(set ^ 1, tile_k(t + 4), 0, QCH);
         multiply(1);
-        VITCOP_INTERLEAVE(0x100, 1, NFRAG)
-        __builtin_amdgcn_sched_group_barrier(0x008, REST, 0);
+        VITCOP_SLICE_HINTS()
+    };
+    load_chunks(0, 0, 0, NCH);
+    store_chunks(0, 0, 0, NCH);
+    load_chunks(0, tile_k(1), 0, NCH);
+    load_chunks(1, tile_k(2), 0, NCH);
+    store_chunks(0, 1, 0, QCH);
+    load_chunks(0, tile_k(3), 0, QCH);
+    __syncthreads();
+    read_frags(0, 0, 0);
+    int t = 0;
+    for (; t + 1 < nk; t += 2) {
+        step(t, 0);
+        step(t + 1, 1);
     }
+    if (t < nk) step(t, 0);
+#undef VITCOP_SLICE_HINTS
 #undef VITCOP_INTERLEAVE
 
     // epilogue: lane owns row m = .. + l32 and columns n = .. + 8*(r/4) + 4*g + r%4
