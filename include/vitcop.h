@@ -139,7 +139,7 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
  *   part p holds, per row, the sum of squares of the ROUNDED outputs of a
  *   fixed group of columns; the P parts added in index order give
  *   sum_n y[m,n]^2, i.e. the squared K-norm of Eq. 4 without re-reading K.
- * K % 64 == 0, N % 16 == 0, strides multiples of 8.
+ * K % 32 == 0, N % 16 == 0, strides multiples of 8; each operand below 2^31 elements.
  */
 int vitcop_project_sumsq_parts(int N);
 int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w,

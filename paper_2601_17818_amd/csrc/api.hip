@@ -213,7 +213,7 @@ int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w, u
                    int64_t y_row_stride, const uint16_t* residual, int64_t res_row_stride, int M, int N,
                    int K, float* sumsq_parts, void* stream) {
     REQUIRE(M >= 0 && N >= 0 && K >= 1, VITCOP_EINVAL, "project: M=%d N=%d K=%d", M, N, K);
-    REQUIRE(K % 64 == 0 && N % 16 == 0, VITCOP_EUNSUPPORTED, "project: K=%d %% 64, N=%d %% 16", K, N);
+    REQUIRE(K % 32 == 0 && N % 16 == 0, VITCOP_EUNSUPPORTED, "project: K=%d %% 32, N=%d %% 16", K, N);
     REQUIRE(x_row_stride >= K && x_row_stride % 8 == 0 && y_row_stride >= N && y_row_stride % 8 == 0,
             VITCOP_EINVAL, "project: strides (%lld, %lld)", (long long)x_row_stride, (long long)y_row_stride);
     REQUIRE(!residual || (res_row_stride >= N && res_row_stride % 8 == 0), VITCOP_EINVAL,
@@ -236,7 +236,7 @@ static int check_layer(const vitcop_layer_t* L) {
             "layer: B=%d T=%d D=%d Hq=%d Hkv=%d", L->B, L->T, L->D, L->Hq, L->Hkv);
     REQUIRE(L->Hq % L->Hkv == 0, VITCOP_EINVAL, "layer: Hq=%d not a multiple of Hkv=%d", L->Hq, L->Hkv);
     REQUIRE(L->d == 128, VITCOP_EUNSUPPORTED, "layer: d=%d (this build has d=128 only)", L->d);
-    REQUIRE(L->D % 64 == 0, VITCOP_EUNSUPPORTED, "layer: D=%d not a multiple of 64", L->D);
+    REQUIRE(L->D % 32 == 0, VITCOP_EUNSUPPORTED, "layer: D=%d not a multiple of 32", L->D);
     REQUIRE(L->vis_start >= 0 && L->n_vis >= 0 && (long)L->vis_start + L->n_vis <= L->T, VITCOP_EINVAL,
             "layer: visual span [%d,%d) outside [0,%d)", L->vis_start, L->vis_start + L->n_vis, L->T);
     REQUIRE(L->keep >= 0 && L->keep <= L->n_vis, VITCOP_EINVAL, "layer: keep=%d outside [0,%d]", L->keep,

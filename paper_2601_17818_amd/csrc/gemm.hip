@@ -10,8 +10,8 @@
 // 4-element runs of consecutive columns n, which gives 8-byte stores and
 // in-lane row sums for the norm epilogue.
 //
-// Pipeline: k-steps of 64; two LDS stages; global -> registers -> LDS with the
-// loads for step t+2 in flight while step t is multiplied; one barrier per
+// Pipeline: k-steps of 32 held in a ring of four LDS slabs that are filled by direct
+// global -> LDS loads (no register staging), three k-steps in flight; one barrier per
 // k-step; MFMA fragments of the next 16-wide slice are read while the current
 // slice is multiplied.  Workgroups are renumbered so that each XCD (own L2)
 // works on a compact patch of output tiles.
@@ -21,13 +21,18 @@
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
-constexpr int GM_BK = 64;
-constexpr int GM_LD = GM_BK + 8;     // bf16 per LDS row (144 B: conflict-free 16-byte reads)
+constexpr int GM_BK = 32;            // k-extent of one LDS slab
+constexpr int GM_SLABS = 4;          // ring of slabs: three k-steps of loads in flight
+constexpr int GM_ROWB = GM_BK * 2;   // bytes per slab row (64): unpadded, chunks XOR-swizzled
 constexpr int GM_PART = 128;         // columns per sum-of-squares partial
 constexpr int GM_XCDS = 8;
 
 template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return (size_t)2 * (BM + BN) * GM_LD * sizeof(uint16_t); }
+constexpr size_t gemm_lds_bytes() { return (size_t)GM_SLABS * (BM + BN) * GM_ROWB; }
+
+// 16-byte chunk c (0..3) of slab row r lives at chunk position c ^ swz(r): with 64-byte rows
+// this makes the MFMA fragment reads (32 consecutive rows, same chunk) bank-conflict free.
+__device__ __forceinline__ int gm_swz(int row) { return (row >> 2) & 3; }
 
 template <int BM, int BN, int WAVES_M, int WAVES_N>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
@@ -39,13 +44,14 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
     constexpr int MI = TM / 32, NI = TN / 32;
     static_assert(TN == GM_PART, "one sum-of-squares partial per wavefront");
-    constexpr int XCH = BM * GM_BK / 8 / GM_THREADS;   // 16-byte chunks per thread per stage
-    constexpr int WCH = BN * GM_BK / 8 / GM_THREADS;
-    constexpr int STAGE = (BM + BN) * GM_LD;           // elements per LDS stage
+    constexpr int SLAB = (BM + BN) * GM_ROWB;           // bytes per slab
+    constexpr int NDMA = SLAB / 1024 / 4;               // 1 KiB direct-to-LDS loads per wavefront per slab
+    static_assert(SLAB % 4096 == 0, "slab splits evenly over four wavefronts");
 
-    extern __shared__ __attribute__((aligned(16))) uint16_t gemm_lds[];
+    extern __shared__ __attribute__((aligned(1024))) char gemm_lds[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront index, kept scalar
     const int l32 = lane & 31, g = lane >> 5;
     const int wm = wv % WAVES_M, wn = wv / WAVES_M;
 
@@ -77,52 +83,50 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
-    // global -> register staging: chunk id -> (row = id / 8, 16-byte column = id % 8);
-    // 32-bit element offsets from a base that advances with k (the host checks the range)
-    // (unsigned byte offsets: base in scalar registers + one 32-bit register per chunk)
-    const int srow = tid >> 3, scol = (tid & 7) * 8;      // chunk j sits 32*j rows further down
-    unsigned xo[XCH], wo[WCH];
+    // Direct global -> LDS loads.  Load q of wavefront wv fills slab bytes [(wv*NDMA+q)*1024, +1024):
+    // 16 rows of 64 bytes; lane L lands at row L/4, chunk position L%4, so it must fetch the
+    // chunk that the swizzle assigns to that position.  Rows [0,BM) are x, [BM,BM+BN) are W.
+    unsigned goff[NDMA];             // byte offset of this lane's chunk from x (or W) at k = 0
 #pragma unroll
-    for (int j = 0; j < XCH; ++j)
-        xo[j] = 2u * (unsigned)(min(m0 + srow + 32 * j, M - 1) * (int)x_stride + scol);
-#pragma unroll
-    for (int j = 0; j < WCH; ++j)
-        wo[j] = 2u * (unsigned)(min(n0 + srow + 32 * j, N - 1) * K + scol);
-    // Two register staging sets; a tile is fetched two k-steps before it is written to LDS.
-    // The 16-byte chunks of a tile (XCH of x, then WCH of W) are handled one quarter per
-    // 16-wide slice, so the LDS writes and the global loads are spread over the whole k-step.
-    constexpr int NCH = XCH + WCH, QCH = NCH / 4;
-    static_assert(NCH % 4 == 0, "chunks split evenly over the four slices");
-    u32x4 st[2][NCH];
-    auto load_chunks = [&](int set, int k0, int c0, int c1) {
+    for (int q = 0; q < NDMA; ++q) {
+        const int row = (wv * NDMA + q) * 16 + (lane >> 2);        // slab row
+        const int chunk = (lane & 3) ^ gm_swz(row);
+        if (row < BM)
+            goff[q] = 2u * (unsigned)(min(m0 + row, M - 1) * (int)x_stride + chunk * 8);
+        else
+            goff[q] = 2u * (unsigned)(min(n0 + row - BM, N - 1) * K + chunk * 8);
+    }
+    auto issue_loads = [&](int slab, int k0, int q0, int q1) {
         const char* xb = reinterpret_cast<const char*>(x + k0);
         const char* wb = reinterpret_cast<const char*>(w + k0);
 #pragma unroll
-        for (int c = c0; c < c1; ++c)
-            st[set][c] = c < XCH ? *reinterpret_cast<const u32x4*>(xb + xo[c < XCH ? c : 0])
-                                 : *reinterpret_cast<const u32x4*>(wb + wo[c < XCH ? 0 : c - XCH]);
-    };
-    auto store_chunks = [&](int set, int stage, int c0, int c1) {
-        uint16_t* Xs = gemm_lds + stage * STAGE + srow * GM_LD + scol;
-        uint16_t* Ws = Xs + BM * GM_LD;
-#pragma unroll
-        for (int c = c0; c < c1; ++c) {
-            if (c < XCH) *reinterpret_cast<u32x4*>(Xs + c * 32 * GM_LD) = st[set][c];
-            else *reinterpret_cast<u32x4*>(Ws + (c - XCH) * 32 * GM_LD) = st[set][c];
+        for (int q = q0; q < q1; ++q) {
+            const bool is_x = (wv * NDMA + q) * 16 < BM;            // wave-uniform
+            const char* src = (is_x ? xb : wb) + goff[q];
+            char* dst = gemm_lds + slab * SLAB + (wv * NDMA + q) * 1024;
+            __builtin_amdgcn_global_load_lds(
+                (const __attribute__((address_space(1))) void*)src,
+                (__attribute__((address_space(3))) void*)dst, 16, 0, 0);
         }
     };
 
-    const int xoff = (wm * TM + l32) * GM_LD + g * 8;
-    const int woff = BM * GM_LD + (wn * TN + l32) * GM_LD + g * 8;
+    // MFMA fragments: lane (l32, g) reads 8 consecutive k of row l32: chunk 2*kc + g
+    int xrow[MI], wrow[NI];
+#pragma unroll
+    for (int j = 0; j < MI; ++j) xrow[j] = wm * TM + j * 32 + l32;
+#pragma unroll
+    for (int i = 0; i < NI; ++i) wrow[i] = BM + wn * TN + i * 32 + l32;
     bf16x8 xf[2][MI], wf[2][NI];
-    auto read_frags = [&](int buf, int stage, int kc) {
-        const uint16_t* S = gemm_lds + stage * STAGE + kc * 16;
+    auto read_frags = [&](int buf, int slab, int kc) {
+        const char* S = gemm_lds + slab * SLAB;
 #pragma unroll
         for (int j = 0; j < MI; ++j)
-            xf[buf][j] = *reinterpret_cast<const bf16x8*>(&S[xoff + j * 32 * GM_LD]);
+            xf[buf][j] = *reinterpret_cast<const bf16x8*>(
+                S + xrow[j] * GM_ROWB + (((2 * kc + g) ^ gm_swz(xrow[j])) << 4));
 #pragma unroll
         for (int i = 0; i < NI; ++i)
-            wf[buf][i] = *reinterpret_cast<const bf16x8*>(&S[woff + i * 32 * GM_LD]);
+            wf[buf][i] = *reinterpret_cast<const bf16x8*>(
+                S + wrow[i] * GM_ROWB + (((2 * kc + g) ^ gm_swz(wrow[i])) << 4));
     };
     auto multiply = [&](int buf) {
 #pragma unroll
@@ -131,76 +135,63 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
             for (int j = 0; j < MI; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][i], xf[buf][j], acc[i][j], 0, 0, 0);
     };
-    // scheduling hints: alternate one MFMA with `per` memory instructions of class `mask`
-    // (0x100 LDS read, 0x200 LDS write, 0x020 global read), `n` times
-#define VITCOP_INTERLEAVE(mask, per, n)                              \
+    // scheduling hints: alternate one MFMA with one memory instruction of class `mask`, n times
+    // (0x100 LDS read, 0x020 global read)
+#define VITCOP_INTERLEAVE(mask, n)                                   \
     _Pragma("unroll") for (int q_ = 0; q_ < (n); ++q_) {             \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);           \
-        __builtin_amdgcn_sched_group_barrier((mask), (per), 0);      \
+        __builtin_amdgcn_sched_group_barrier((mask), 1, 0);          \
     }
     constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
 
-    // Software pipeline over k-steps.  LDS stage s = t & 1 holds tile t; on entry to step t
-    // register set s holds tile t+1 (its first quarter already in LDS and refilled with tile
-    // t+3) and set s^1 holds tile t+2.  Step t, slice by slice (each slice: 16 MFMAs, the
-    // fragment reads of the next slice, a quarter of the LDS writes and of the global loads):
-    //   slices 0..2: quarters 1..3 of tile t+1 go from set s to stage s^1; each register is
-    //                refilled with tile t+3 right after it is written
-    //   barrier     (stage s^1 complete; nobody reads stage s any more: slice 3 was fetched)
-    //   slice 3:     reads slice 0 of tile t+1 from stage s^1; quarter 0 of tile t+2 goes
-    //                from set s^1 to stage s, refilled with tile t+4
-    // Past the end the loads repeat the last tile and the extra LDS traffic is never consumed.
+    // Pipeline over k-steps of 32.  Slab t % 4 holds k-step t; the loads of k-step t+3 are
+    // issued during step t into the slab that step t-1 used (every wavefront left it before
+    // the barrier of step t-1).  Step t:
+    //   slice 0: multiply slice 0; read the fragments of slice 1; issue the loads of step t+3
+    //   wait until this wavefront's loads of step t+1 have landed (two younger steps may
+    //   still be in flight); barrier
+    //   slice 1: multiply slice 1; read the fragments of slice 0 of step t+1
+    // Past the end the loads repeat the last k-step into slabs nobody reads again.
     const int nk = K / GM_BK;
-    auto tile_k = [&](int tile) { return min(tile, nk - 1) * GM_BK; };
-#define VITCOP_SLICE_HINTS()                                                         \
-    if constexpr (NMFMA >= NFRAG + 2 * QCH) {                                        \
-        VITCOP_INTERLEAVE(0x100, 1, NFRAG)                                           \
-        VITCOP_INTERLEAVE(0x200, 1, QCH)                                             \
-        VITCOP_INTERLEAVE(0x020, 1, QCH)                                             \
-        __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG - 2 * QCH, 0);     \
-    }
-    auto step = [&](int t, int set) {
-        const int s = set;             // == t & 1, kept a compile-time constant after inlining
-        read_frags(1, s, 1);
-        store_chunks(set, s ^ 1, QCH, 2 * QCH);
-        load_chunks(set, tile_k(t + 3), QCH, 2 * QCH);
+    auto k_of = [&](int step) { return min(step, nk - 1) * GM_BK; };
+    auto step = [&](int t, int slab) {
+        read_frags(1, slab, 1);
+        issue_loads((slab + 3) & 3, k_of(t + 3), 0, NDMA);
         multiply(0);
-        VITCOP_SLICE_HINTS()
-
-        read_frags(0, s, 2);
-        store_chunks(set, s ^ 1, 2 * QCH, 3 * QCH);
-        load_chunks(set, tile_k(t + 3), 2 * QCH, 3 * QCH);
+        if constexpr (NMFMA >= NFRAG + NDMA) {
+            VITCOP_INTERLEAVE(0x100, NFRAG)
+            VITCOP_INTERLEAVE(0x020, NDMA)
+            __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG - NDMA, 0);
+        }
+        // (a plain s_barrier: __syncthreads would also drain the two younger steps' loads)
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        read_frags(0, (slab + 1) & 3, 0);
         multiply(1);
-        VITCOP_SLICE_HINTS()
-
-        read_frags(1, s, 3);
-        store_chunks(set, s ^ 1, 3 * QCH, NCH);
-        load_chunks(set, tile_k(t + 3), 3 * QCH, NCH);
-        multiply(0);
-        VITCOP_SLICE_HINTS()
-
-        __syncthreads();
-        read_frags(0, s ^ 1, 0);
-        store_chunks(set ^ 1, s, 0, QCH);
-        load_chunks(set ^ 1, tile_k(t + 4), 0, QCH);
-        multiply(1);
-        VITCOP_SLICE_HINTS()
+        if constexpr (NMFMA >= NFRAG) {
+            VITCOP_INTERLEAVE(0x100, NFRAG)
+            __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
+        }
     };
-    load_chunks(0, 0, 0, NCH);
-    store_chunks(0, 0, 0, NCH);
-    load_chunks(0, tile_k(1), 0, NCH);
-    load_chunks(1, tile_k(2), 0, NCH);
-    store_chunks(0, 1, 0, QCH);
-    load_chunks(0, tile_k(3), 0, QCH);
-    __syncthreads();
+    issue_loads(0, k_of(0), 0, NDMA);
+    issue_loads(1, k_of(1), 0, NDMA);
+    issue_loads(2, k_of(2), 0, NDMA);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
     read_frags(0, 0, 0);
     int t = 0;
-    for (; t + 1 < nk; t += 2) {
+    for (; t + 3 < nk; t += 4) {
         step(t, 0);
         step(t + 1, 1);
+        step(t + 2, 2);
+        step(t + 3, 3);
     }
     if (t < nk) step(t, 0);
-#undef VITCOP_SLICE_HINTS
+    if (t + 1 < nk) step(t + 1, 1);
+    if (t + 2 < nk) step(t + 2, 2);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no load may outlive the workgroup's LDS
 #undef VITCOP_INTERLEAVE
 
     // epilogue: lane owns row m = .. + l32 and columns n = .. + 8*(r/4) + 4*g + r%4
