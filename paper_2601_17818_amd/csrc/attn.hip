@@ -196,13 +196,250 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     }
 }
 
+// ---------------------------------------------------------------------------
+// Wide variant for long sequences: a workgroup owns 256 queries, each of its 4
+// wavefronts 64 of them (two 32-query blocks), so every K and V^T fragment read
+// from LDS feeds two MFMAs.  K and V tiles (64 keys) arrive by direct
+// global -> LDS loads into two stages; both stay row-major in LDS with their
+// 16-byte chunks XOR-swizzled; V^T fragments come from the transposing LDS read
+// (ds_read_b64_tr_b16), so nothing is staged in or shuffled through registers.
+// The running maximum is only refreshed when it grew by more than 2^8 (the
+// accumulators are rescaled then); the normalisation at the end makes the
+// result independent of which reference maximum was used.
+// ---------------------------------------------------------------------------
+constexpr int AW_BM = 256;
+constexpr int AW_BN = 64;
+constexpr int AW_TILE = AW_BN * AT_D * 2;        // bytes of one K (or V) tile: 16 KiB
+constexpr int AW_STAGE = 2 * AW_TILE;            // K then V
+constexpr int AW_STAGES = 2;
+constexpr float AW_RESCALE_GAP = 8.0f;
+
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+__device__ __forceinline__ int aw_kswz(int row) { return row & 15; }            // K: 16-byte reads
+__device__ __forceinline__ int aw_vswz(int row) { return (row & 7) << 1; }      // V: 8-byte transposed reads
+
+template <bool CAUSAL>
+__global__ __launch_bounds__(256) void attn_wide_kernel(
+    const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
+    const uint16_t* __restrict__ v, uint16_t* __restrict__ out, float* __restrict__ lse,
+    int N, int Hq, int Hkv, float scale_log2e) {
+    extern __shared__ __attribute__((aligned(1024))) char aw_lds[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    const int qb = CAUSAL ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
+    const int h = blockIdx.y, b = blockIdx.z;
+    const int hk = h / (Hq / Hkv);
+    const int q0 = qb * AW_BM, wq0 = q0 + 64 * wv;
+    const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
+
+    // Q^T fragments of the two query blocks
+    bf16x8 qf[2][8];
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int query = min(wq0 + 32 * u + l32, N - 1);
+        const uint16_t* qp = q + ((int64_t)b * N + query) * q_rs + h * AT_D + 8 * g;
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc) qf[u][dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
+    }
+
+    f32x16 o[2][4];
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[u][i][r] = 0.f;
+    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+
+    const int kend = CAUSAL ? min(N, q0 + AW_BM) : N;
+    const int ntiles = (kend + AW_BN - 1) / AW_BN;
+    const int wave_kend = CAUSAL ? min(N, wq0 + 64) : N;
+    const char* kbase = reinterpret_cast<const char*>(k + (int64_t)b * N * kv_rs + hk * AT_D);
+    const char* vbase = reinterpret_cast<const char*>(v + (int64_t)b * N * kv_rs + hk * AT_D);
+
+    // direct-to-LDS loads: load i (0..3) of this wavefront fills rows 4*(4*wv+i) .. +3 of the K
+    // tile and of the V tile; lane L lands at row L/16, chunk position L%16
+    auto issue_tile = [&](int t, int stage) {
+        char* dstK = aw_lds + stage * AW_STAGE + wv * 4096;
+        char* dstV = dstK + AW_TILE;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int row = 16 * wv + 4 * i + (lane >> 4);
+            const int64_t key = min(t * AW_BN + row, N - 1);
+            const int cp = lane & 15;
+            const char* sk = kbase + key * kv_rs * 2 + ((cp ^ aw_kswz(row)) << 4);
+            const char* sv = vbase + key * kv_rs * 2 + ((cp ^ aw_vswz(row)) << 4);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sk,
+                                             (__attribute__((address_space(3))) void*)(dstK + i * 1024), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sv,
+                                             (__attribute__((address_space(3))) void*)(dstV + i * 1024), 16, 0, 0);
+        }
+    };
+
+    // lane roles for the transposing V^T read: lane = 16*h16 + 4*e + a supplies the address of
+    // key (.. + e), channels 16*(h16&1) + 4*a .. +3; it receives channel (lane & 31), 4 keys
+    const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_h = lane >> 4;
+
+    issue_tile(0, 0);
+    for (int t = 0; t < ntiles; ++t) {
+        // tile t has landed for every wavefront, and every wavefront is done with tile t-1
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        if (t + 1 < ntiles) issue_tile(t + 1, (t + 1) & 1);
+        if (t * AW_BN >= wave_kend) continue;
+
+        const char* Ks = aw_lds + (t & 1) * AW_STAGE;
+        const char* Vs = Ks + AW_TILE;
+        const int kb0 = t * AW_BN;
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            if (CAUSAL && kb0 + kt * 32 >= wave_kend) break;
+            // S^T = K Q^T for 32 keys x (2 x 32) queries
+            f32x16 s[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[u][r] = 0.f;
+            const int krow = kt * 32 + l32;
+#pragma unroll
+            for (int dc = 0; dc < 8; ++dc) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(
+                    Ks + krow * 256 + (((2 * dc + g) ^ aw_kswz(krow)) << 4));
+                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][dc], s[0], 0, 0, 0);
+                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[1], 0, 0, 0);
+            }
+            // online softmax; lane holds keys kb0 + kt*32 + 8*(r/4) + 4*g + r%4 of its query
+            const int kbase_i = kb0 + kt * 32 + 4 * g;
+            const bool need_mask = (kb0 + kt * 32 + 32 > N) || (CAUSAL && kb0 + kt * 32 + 31 > wq0);
+            bf16x8 pf[2][2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const int query = wq0 + 32 * u + l32;
+                if (need_mask) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int key = kbase_i + 8 * (r >> 2) + (r & 3);
+                        if (key >= N || (CAUSAL && key > query)) s[u][r] = -INFINITY;
+                    }
+                }
+                float mx = fmaxf(s[u][0], s[u][1]);
+#pragma unroll
+                for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[u][r], s[u][r + 1]));
+                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
+                if (__builtin_amdgcn_ballot_w64(m_new > m_ref[u] + AW_RESCALE_GAP) != 0) {
+                    const float alpha = __builtin_amdgcn_exp2f(m_ref[u] - m_new);   // exp2(-inf) = 0 at the start
+                    m_ref[u] = m_new;
+                    l_run[u] *= alpha;
+#pragma unroll
+                    for (int db = 0; db < 4; ++db)
+#pragma unroll
+                        for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha;
+                }
+                const float mr = m_ref[u];
+                float psum = 0.f;
+#pragma unroll
+                for (int tt = 0; tt < 2; ++tt) {
+                    float e[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        e[i] = __builtin_amdgcn_exp2f(fmaf(s[u][8 * tt + i], scale_log2e, -mr));
+                        psum += e[i];
+                    }
+                    u32x4 pk;
+                    pk.x = pack_bf16(e[0], e[1]);
+                    pk.y = pack_bf16(e[2], e[3]);
+                    pk.z = pack_bf16(e[4], e[5]);
+                    pk.w = pack_bf16(e[6], e[7]);
+                    pf[u][tt] = __builtin_bit_cast(bf16x8, pk);
+                }
+                l_run[u] += psum;
+            }
+            // O^T += V^T P^T : V^T fragment = channel (lane & 31) x 8 keys, via two transposing reads
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+                for (int db = 0; db < 4; ++db) {
+                    s16x4 lo, hi;
+                    {
+                        const int vrow0 = kt * 32 + 16 * tt + 4 * g + tr_e;           // keys of slots 0..3
+                        const int vrow1 = vrow0 + 8;                                   // keys of slots 4..7
+                        const int col = db * 32 + 16 * (tr_h & 1) + 4 * tr_a;          // channel of this address
+                        const char* p0 = Vs + vrow0 * 256 + ((((col >> 3) ^ aw_vswz(vrow0)) << 4) | ((col & 4) << 1));
+                        const char* p1 = Vs + vrow1 * 256 + ((((col >> 3) ^ aw_vswz(vrow1)) << 4) | ((col & 4) << 1));
+                        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+                        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+                    }
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+                    o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][tt], o[0][db], 0, 0, 0);
+                    o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][tt], o[1][db], 0, 0, 0);
+                }
+        }
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+
+#pragma unroll
+    for (int u = 0; u < 2; ++u) {
+        const int query = wq0 + 32 * u + l32;
+        const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
+        if (query < N) {
+            const float inv = 1.0f / l_tot;
+            uint16_t* op = out + ((int64_t)b * N + query) * q_rs + h * AT_D;
+#pragma unroll
+            for (int db = 0; db < 4; ++db)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    uint2 pk;
+                    pk.x = pack_bf16(o[u][db][4 * r4] * inv, o[u][db][4 * r4 + 1] * inv);
+                    pk.y = pack_bf16(o[u][db][4 * r4 + 2] * inv, o[u][db][4 * r4 + 3] * inv);
+                    *reinterpret_cast<uint2*>(op + db * 32 + 8 * r4 + 4 * g) = pk;
+                }
+            if (lse && g == 0)
+                lse[((int64_t)b * Hq + h) * N + query] =
+                    (m_ref[u] + __builtin_amdgcn_logf(l_tot)) * 0.6931471805599453f;
+        }
+    }
+}
+
+constexpr int AW_MIN_N = 1024;     // below this the 128-query kernel fills the chip better
+
 int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                 float* lse, int B, int N, int Hq, int Hkv, float scale, int causal,
                 hipStream_t s) {
     if (B == 0 || N == 0) return VITCOP_OK;
+    const float sl2 = scale * 1.4426950408889634f;
+    if (N >= AW_MIN_N) {
+        static bool attr_set = false;
+        constexpr int lds = AW_STAGES * AW_STAGE;
+        if (!attr_set) {
+            int rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<true>,
+                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+                                "hipFuncSetAttribute(attn_wide)");
+            if (rc) return rc;
+            rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<false>,
+                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+                            "hipFuncSetAttribute(attn_wide)");
+            if (rc) return rc;
+            attr_set = true;
+        }
+        dim3 grid((N + AW_BM - 1) / AW_BM, Hq, B);
+        if (causal)
+            hipLaunchKernelGGL(attn_wide_kernel<true>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
+                               Hkv, sl2);
+        else
+            hipLaunchKernelGGL(attn_wide_kernel<false>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
+                               Hkv, sl2);
+        return launch_status("attn_wide");
+    }
     dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
-    hipLaunchKernelGGL(attn_kernel, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv,
-                       scale * 1.4426950408889634f, causal);
+    hipLaunchKernelGGL(attn_kernel, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
+                       causal);
     return launch_status("attn");
 }
 

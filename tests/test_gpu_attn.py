@@ -33,6 +33,38 @@ def test_causal_sizes(vc, N):
     assert np.abs(lse - ref_lse).max() < 1e-3
 
 
+# the 256-query kernel takes over at N >= 1024: block edges, ragged tails, several blocks
+@pytest.mark.parametrize("N", [1024, 1025, 1087, 1280, 1500, 2100])
+def test_causal_long(vc, N):
+    t = I.qkv_tensors(150 + N, 1, N, 2, 2, 128)
+    out, lse = run(vc, t)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+    assert_attention_close(out, ref, f"N={N}")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+def test_long_gqa_batch_and_non_causal(vc):
+    t = I.qkv_tensors(160, 2, 1111, 8, 2, 128)
+    out, lse = run(vc, t)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+    assert_attention_close(out, ref, "long GQA")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+    t = I.qkv_tensors(161, 1, 1300, 2, 1, 128)
+    out, lse = run(vc, t, causal=False)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], None, False)
+    assert_attention_close(out, ref, "long non-causal")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+def test_long_large_logits(vc):
+    # logits of order +-100 with outliers: exercises the deferred rescaling of the accumulators
+    t = I.qkv_tensors(162, 1, 1200, 2, 2, 128, std=3.0)
+    out, lse = run(vc, t, scale=0.11)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], 0.11)
+    assert_attention_close(out, ref, "long large logits")
+    assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
 @pytest.mark.parametrize("N", [5, 64, 130, 257])
 def test_non_causal(vc, N):
     t = I.qkv_tensors(200 + N, 1, N, 2, 2, 128)
