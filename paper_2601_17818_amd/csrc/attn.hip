@@ -209,15 +209,20 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 // ---------------------------------------------------------------------------
 constexpr int AW_BM = 256;
 constexpr int AW_BN = 64;
-constexpr int AW_TILE = AW_BN * AT_D * 2;        // bytes of one K (or V) tile: 16 KiB
-constexpr int AW_STAGE = 2 * AW_TILE;            // K then V
-constexpr int AW_STAGES = 2;
+// LDS layout of a 64-key tile (rows of 256 B): one direct-to-LDS load writes 1 KiB = the four
+// rows {i, i+16, i+32, i+48}, so row r sits at (r % 16) * (1024 + pad) + (r / 16) * 256.
+// The pad after every KiB shifts consecutive keys across the banks: 16 B for K (16-byte
+// fragment reads of 16 consecutive keys), 64 B for V (8-byte transposing reads: 32 lanes = 4 consecutive
+// keys x 64 B).  Every fragment address is then one per-lane base + a constant.
+constexpr int AW_KGRP = 1024 + 16;
+constexpr int AW_VGRP = 1024 + 64;
+constexpr int AW_KTILE = 16 * AW_KGRP;           // 16640 B
+constexpr int AW_VTILE = 16 * AW_VGRP;           // 16896 B
+constexpr int AW_STAGE = AW_KTILE + AW_VTILE;    // K then V
+constexpr int AW_STAGES = 3;
 constexpr float AW_RESCALE_GAP = 8.0f;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
-
-__device__ __forceinline__ int aw_kswz(int row) { return row & 15; }            // K: 16-byte reads
-__device__ __forceinline__ int aw_vswz(int row) { return (row & 7) << 1; }      // V: 8-byte transposed reads
 
 template <bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
@@ -255,133 +260,171 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
 
     const int kend = CAUSAL ? min(N, q0 + AW_BM) : N;
-    const int ntiles = (kend + AW_BN - 1) / AW_BN;
-    const int wave_kend = CAUSAL ? min(N, wq0 + 64) : N;
+    const int ntiles = (kend + AW_BN - 1) / AW_BN;                 // tiles the workgroup streams
+    const int wave_kend = CAUSAL ? min(N, wq0 + 64) : N;           // keys this wavefront needs
+    const int my_tiles = wq0 < N ? (wave_kend + AW_BN - 1) / AW_BN : 0;
+    // tiles whose 64 keys are visible to all 64 queries and lie inside the sequence: no masking
+    const int full_tiles = min(CAUSAL ? wq0 / AW_BN : N / AW_BN, min(N / AW_BN, my_tiles));
     const char* kbase = reinterpret_cast<const char*>(k + (int64_t)b * N * kv_rs + hk * AT_D);
     const char* vbase = reinterpret_cast<const char*>(v + (int64_t)b * N * kv_rs + hk * AT_D);
 
-    // direct-to-LDS loads: load i (0..3) of this wavefront fills rows 4*(4*wv+i) .. +3 of the K
-    // tile and of the V tile; lane L lands at row L/16, chunk position L%16
-    auto issue_tile = [&](int t, int stage) {
-        char* dstK = aw_lds + stage * AW_STAGE + wv * 4096;
-        char* dstV = dstK + AW_TILE;
+    // direct-to-LDS loads: load i (0..3) of this wavefront is KiB group 4*wv+i of the K tile and
+    // of the V tile: rows {grp, grp+16, grp+32, grp+48}; lane L carries row grp + 16*(L/16),
+    // 16-byte chunk L%16
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+        char* stage = aw_lds + (t % AW_STAGES) * AW_STAGE;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int row = 16 * wv + 4 * i + (lane >> 4);
-            const int64_t key = min(t * AW_BN + row, N - 1);
-            const int cp = lane & 15;
-            const char* sk = kbase + key * kv_rs * 2 + ((cp ^ aw_kswz(row)) << 4);
-            const char* sv = vbase + key * kv_rs * 2 + ((cp ^ aw_vswz(row)) << 4);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sk,
-                                             (__attribute__((address_space(3))) void*)(dstK + i * 1024), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)sv,
-                                             (__attribute__((address_space(3))) void*)(dstV + i * 1024), 16, 0, 0);
+            const int grp = 4 * wv + i;
+            const int64_t key = min(t * AW_BN + grp + 16 * (lane >> 4), N - 1);
+            const int64_t off = key * kv_rs * 2 + ((lane & 15) << 4);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + off),
+                                             (__attribute__((address_space(3))) void*)(stage + grp * AW_KGRP), 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + off),
+                                             (__attribute__((address_space(3))) void*)(stage + AW_KTILE + grp * AW_VGRP), 16, 0, 0);
         }
     };
+
+    // Software pipeline over "stages" of 32 keys (two per tile).  For stage c, with both query
+    // blocks: S(c) = 16 MFMAs, softmax(c) = vector work, PV(c) = 16 MFMAs.  Program order:
+    //     ... | PV(c-1) + max(c) | S(c+1) + exp(c) | PV(c) + max(c+1) | ...
+    // so the vector work of stage c always sits beside MFMAs that do not depend on it.
+    // Score accumulators and probability fragments are double buffered by stage parity.
+    f32x16 s[2][2];                  // [parity][query block]
+    bf16x8 pf[2][2][2];              // [parity][query block][16-key half]
 
     // lane roles for the transposing V^T read: lane = 16*h16 + 4*e + a supplies the address of
     // key (.. + e), channels 16*(h16&1) + 4*a .. +3; it receives channel (lane & 31), 4 keys
     const int tr_e = (lane >> 2) & 3, tr_a = lane & 3, tr_h = lane >> 4;
+    // per-lane parts of the fragment addresses (the rest are compile-time constants)
+    //   K row kt*32 + l32, bytes 32*dc + 16*g           V row kt*32 + 16*tt + 8*u + 4*g + e,
+    //                                                     channels db*32 + 16*(h16&1) + 4*a
+    const int k_lane = (l32 & 15) * AW_KGRP + (l32 >> 4) * 256 + g * 16;
+    const int v_lane = AW_KTILE + (4 * g + tr_e) * AW_VGRP + (16 * (tr_h & 1) + 4 * tr_a) * 2;
 
-    issue_tile(0, 0);
-    for (int t = 0; t < ntiles; ++t) {
-        // tile t has landed for every wavefront, and every wavefront is done with tile t-1
+    auto scores = [&](int par, int t, int kt) __attribute__((always_inline)) {           // S^T = K Q^T, 32 keys x (2 x 32) queries
+        const char* Ks = aw_lds + (t % AW_STAGES) * AW_STAGE + k_lane + kt * 512;
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[par][u][r] = 0.f;
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc) {
+            const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + dc * 32);
+            s[par][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][dc], s[par][0], 0, 0, 0);
+            s[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[par][1], 0, 0, 0);
+        }
+    };
+    auto weighted_values = [&](int par, int t, int kt) __attribute__((always_inline)) {  // O^T += V^T P^T for that stage
+        const char* Vs = aw_lds + (t % AW_STAGES) * AW_STAGE + v_lane + kt * 512;
+#pragma unroll
+        for (int tt = 0; tt < 2; ++tt)
+#pragma unroll
+            for (int db = 0; db < 4; ++db) {
+                const char* p0 = Vs + tt * 256 + db * 64;                      // keys of slots 0..3
+                const char* p1 = p0 + 8 * AW_VGRP;                             // keys of slots 4..7
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+                o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][0][tt], o[0][db], 0, 0, 0);
+                o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
+            }
+    };
+    // softmax, first part: mask (edge stages only), stage maximum, and - rarely - a new reference
+    // maximum with rescaling of the accumulators.  Must run after PV of the previous stage was
+    // issued: that product still belongs to the old reference.
+    auto stage_max = [&](int par, int key0, bool masked) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            if (masked) {
+                const int query = wq0 + 32 * u + l32;
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int key = key0 + 4 * g + 8 * (r >> 2) + (r & 3);
+                    if (key >= N || (CAUSAL && key > query)) s[par][u][r] = -INFINITY;
+                }
+            }
+            float mx = fmaxf(s[par][u][0], s[par][u][1]);
+#pragma unroll
+            for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[par][u][r], s[par][u][r + 1]));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
+            if (__builtin_amdgcn_ballot_w64(m_new > m_ref[u] + AW_RESCALE_GAP) != 0) {
+                const float alpha = __builtin_amdgcn_exp2f(m_ref[u] - m_new);   // exp2(-inf) = 0 at the start
+                m_ref[u] = m_new;
+                l_run[u] *= alpha;
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha;
+            }
+        }
+    };
+    // softmax, second part: probabilities relative to the reference maximum, row sums, bf16 packing
+    auto stage_exp = [&](int par) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const float mr = m_ref[u];
+            float psum = 0.f;
+#pragma unroll
+            for (int tt = 0; tt < 2; ++tt) {
+                float e[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    e[i] = __builtin_amdgcn_exp2f(fmaf(s[par][u][8 * tt + i], scale_log2e, -mr));
+                    psum += e[i];
+                }
+                u32x4 pk;
+                pk.x = pack_bf16(e[0], e[1]);
+                pk.y = pack_bf16(e[2], e[3]);
+                pk.z = pack_bf16(e[4], e[5]);
+                pk.w = pack_bf16(e[6], e[7]);
+                pf[par][u][tt] = __builtin_bit_cast(bf16x8, pk);
+            }
+            l_run[u] += psum;
+        }
+    };
+    // tile t+1 has landed everywhere and tile t-1 is dead everywhere: start fetching tile t+2
+    auto tile_sync = [&](int t) __attribute__((always_inline)) {
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (t + 1 < ntiles) issue_tile(t + 1, (t + 1) & 1);
-        if (t * AW_BN >= wave_kend) continue;
+        if (t + 2 < ntiles) issue_tile(t + 2);
+    };
+    auto tile_body = [&](int t, bool masked, bool first) __attribute__((always_inline)) {
+        // even stage c = 2t (parity 0)
+        if (!first) weighted_values(1, t - 1, 1);                     // PV(c-1)
+        stage_max(0, t * AW_BN, masked);
+        scores(1, t, 1);                                              // S(c+1)
+        stage_exp(0);
+        // odd stage c = 2t+1 (parity 1)
+        weighted_values(0, t, 0);                                     // PV(c-1)
+        stage_max(1, t * AW_BN + 32, masked);
+        tile_sync(t);
+        scores(0, t + 1, 0);                                          // S(c+1): first stage of the next tile
+        stage_exp(1);
+    };
 
-        const char* Ks = aw_lds + (t & 1) * AW_STAGE;
-        const char* Vs = Ks + AW_TILE;
-        const int kb0 = t * AW_BN;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            if (CAUSAL && kb0 + kt * 32 >= wave_kend) break;
-            // S^T = K Q^T for 32 keys x (2 x 32) queries
-            f32x16 s[2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[u][r] = 0.f;
-            const int krow = kt * 32 + l32;
-#pragma unroll
-            for (int dc = 0; dc < 8; ++dc) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-                    Ks + krow * 256 + (((2 * dc + g) ^ aw_kswz(krow)) << 4));
-                s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][dc], s[0], 0, 0, 0);
-                s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[1], 0, 0, 0);
-            }
-            // online softmax; lane holds keys kb0 + kt*32 + 8*(r/4) + 4*g + r%4 of its query
-            const int kbase_i = kb0 + kt * 32 + 4 * g;
-            const bool need_mask = (kb0 + kt * 32 + 32 > N) || (CAUSAL && kb0 + kt * 32 + 31 > wq0);
-            bf16x8 pf[2][2];
-#pragma unroll
-            for (int u = 0; u < 2; ++u) {
-                const int query = wq0 + 32 * u + l32;
-                if (need_mask) {
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int key = kbase_i + 8 * (r >> 2) + (r & 3);
-                        if (key >= N || (CAUSAL && key > query)) s[u][r] = -INFINITY;
-                    }
-                }
-                float mx = fmaxf(s[u][0], s[u][1]);
-#pragma unroll
-                for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[u][r], s[u][r + 1]));
-                mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
-                if (__builtin_amdgcn_ballot_w64(m_new > m_ref[u] + AW_RESCALE_GAP) != 0) {
-                    const float alpha = __builtin_amdgcn_exp2f(m_ref[u] - m_new);   // exp2(-inf) = 0 at the start
-                    m_ref[u] = m_new;
-                    l_run[u] *= alpha;
-#pragma unroll
-                    for (int db = 0; db < 4; ++db)
-#pragma unroll
-                        for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha;
-                }
-                const float mr = m_ref[u];
-                float psum = 0.f;
-#pragma unroll
-                for (int tt = 0; tt < 2; ++tt) {
-                    float e[8];
-#pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        e[i] = __builtin_amdgcn_exp2f(fmaf(s[u][8 * tt + i], scale_log2e, -mr));
-                        psum += e[i];
-                    }
-                    u32x4 pk;
-                    pk.x = pack_bf16(e[0], e[1]);
-                    pk.y = pack_bf16(e[2], e[3]);
-                    pk.z = pack_bf16(e[4], e[5]);
-                    pk.w = pack_bf16(e[6], e[7]);
-                    pf[u][tt] = __builtin_bit_cast(bf16x8, pk);
-                }
-                l_run[u] += psum;
-            }
-            // O^T += V^T P^T : V^T fragment = channel (lane & 31) x 8 keys, via two transposing reads
-#pragma unroll
-            for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-                for (int db = 0; db < 4; ++db) {
-                    s16x4 lo, hi;
-                    {
-                        const int vrow0 = kt * 32 + 16 * tt + 4 * g + tr_e;           // keys of slots 0..3
-                        const int vrow1 = vrow0 + 8;                                   // keys of slots 4..7
-                        const int col = db * 32 + 16 * (tr_h & 1) + 4 * tr_a;          // channel of this address
-                        const char* p0 = Vs + vrow0 * 256 + ((((col >> 3) ^ aw_vswz(vrow0)) << 4) | ((col & 4) << 1));
-                        const char* p1 = Vs + vrow1 * 256 + ((((col >> 3) ^ aw_vswz(vrow1)) << 4) | ((col & 4) << 1));
-                        lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
-                        hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
-                    }
-                    typedef __attribute__((ext_vector_type(8))) short s16x8;
-                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-                    o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[0][tt], o[0][db], 0, 0, 0);
-                    o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[1][tt], o[1][db], 0, 0, 0);
-                }
+    issue_tile(0);
+    if (ntiles > 1) issue_tile(1);
+    if (ntiles > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // tile 0 (8 loads) done, tile 1 may fly
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+
+    int t = 0;
+    if (my_tiles > 0) {
+        scores(0, 0, 0);
+        if (full_tiles > 0) {
+            tile_body(0, false, true);
+            for (t = 1; t < full_tiles; ++t) tile_body(t, false, false);
         }
+        for (; t < my_tiles; ++t) tile_body(t, true, t == 0);
+        weighted_values(1, my_tiles - 1, 1);                           // drain: PV of the last stage
     }
+    for (; t < ntiles; ++t) tile_sync(t);                              // keep feeding the other wavefronts
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
