@@ -14,6 +14,8 @@
 //    O^T += V^T P^T — they never leave registers;
 //  * V is written to LDS transposed (channel-major) with the keys of each
 //    group of 32 permuted so that the 8 keys a lane needs are contiguous.
+#include <type_traits>
+
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -224,6 +226,31 @@ constexpr float AW_RESCALE_GAP = 8.0f;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
+// Transposing LDS read (ds_read_b64_tr_b16) with the constant part of the address in the
+// instruction's offset field.  Written as inline assembly because the compiler materialises a
+// separate address register per read for the corresponding builtin.  The result is only valid
+// after lds_wait<K>() has been applied to it: LDS reads return in order, so "at most K LDS
+// operations outstanding" implies every read older than the last K has landed.
+template <int OFF>
+__device__ __forceinline__ s16x4 lds_read_tr16(unsigned addr) {
+    static_assert(OFF >= 0 && OFF < 65536 && OFF % 8 == 0, "DS offset field");
+    s16x4 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
+    return v;
+}
+template <int K>
+__device__ __forceinline__ void lds_wait(s16x4& a, s16x4& b) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(K));
+}
+
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 template <bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -299,38 +326,43 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // per-lane parts of the fragment addresses (the rest are compile-time constants)
     //   K row kt*32 + l32, bytes 32*dc + 16*g           V row kt*32 + 16*tt + 8*u + 4*g + e,
     //                                                     channels db*32 + 16*(h16&1) + 4*a
-    const int k_lane = (l32 & 15) * AW_KGRP + (l32 >> 4) * 256 + g * 16;
-    const int v_lane = AW_KTILE + (4 * g + tr_e) * AW_VGRP + (16 * (tr_h & 1) + 4 * tr_a) * 2;
+    // (kept as 32-bit LDS byte addresses so that the constants fold into the instruction offsets)
+    typedef __attribute__((address_space(3))) char lds_char;
+    const unsigned lds0 = (unsigned)(uintptr_t)(lds_char*)aw_lds;
+    const unsigned k_lane = lds0 + (l32 & 15) * AW_KGRP + (l32 >> 4) * 256 + g * 16;
+    const unsigned v_lane = lds0 + AW_KTILE + (4 * g + tr_e) * AW_VGRP + (16 * (tr_h & 1) + 4 * tr_a) * 2;
 
     auto scores = [&](int par, int t, int kt) __attribute__((always_inline)) {           // S^T = K Q^T, 32 keys x (2 x 32) queries
-        const char* Ks = aw_lds + (t % AW_STAGES) * AW_STAGE + k_lane + kt * 512;
+        const unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[par][u][r] = 0.f;
 #pragma unroll
         for (int dc = 0; dc < 8; ++dc) {
-            const bf16x8 a = *reinterpret_cast<const bf16x8*>(Ks + dc * 32);
+            const bf16x8 a = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
             s[par][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][dc], s[par][0], 0, 0, 0);
             s[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[par][1], 0, 0, 0);
         }
     };
-    auto weighted_values = [&](int par, int t, int kt) __attribute__((always_inline)) {  // O^T += V^T P^T for that stage
-        const char* Vs = aw_lds + (t % AW_STAGES) * AW_STAGE + v_lane + kt * 512;
-#pragma unroll
-        for (int tt = 0; tt < 2; ++tt)
-#pragma unroll
-            for (int db = 0; db < 4; ++db) {
-                const char* p0 = Vs + tt * 256 + db * 64;                      // keys of slots 0..3
-                const char* p1 = p0 + 8 * AW_VGRP;                             // keys of slots 4..7
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p0);
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)p1);
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-                o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][0][tt], o[0][db], 0, 0, 0);
-                o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
-            }
+    auto weighted_values = [&](int par, int t, int kt) __attribute__((always_inline)) {  // O^T += V^T P^T
+        const unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
+        // fragment n = 4*tt + db: keys 16*tt + (slots 0..3 | slots 4..7), channels 32*db ..
+        s16x4 lo[8], hi[8];
+        static_for<0, 8>([&](auto n) {
+            constexpr int off = (n.value >> 2) * 256 + (n.value & 3) * 64;
+            lo[n.value] = lds_read_tr16<off>(Vs);
+            hi[n.value] = lds_read_tr16<off + 8 * AW_VGRP>(Vs);
+        });
+        static_for<0, 8>([&](auto n) {
+            constexpr int tt = n.value >> 2, db = n.value & 3;
+            lds_wait<14 - 2 * n.value>(lo[n.value], hi[n.value]);
+            typedef __attribute__((ext_vector_type(8))) short s16x8;
+            const s16x8 both = __builtin_shufflevector(lo[n.value], hi[n.value], 0, 1, 2, 3, 4, 5, 6, 7);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, both);
+            o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][0][tt], o[0][db], 0, 0, 0);
+            o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
+        });
     };
     // softmax, first part: mask (edge stages only), stage maximum, and - rarely - a new reference
     // maximum with rescaling of the accumulators.  Must run after PV of the previous stage was
