@@ -226,21 +226,23 @@ constexpr float AW_RESCALE_GAP = 8.0f;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
 
-// Transposing LDS read (ds_read_b64_tr_b16) with the constant part of the address in the
-// instruction's offset field.  Written as inline assembly because the compiler materialises a
-// separate address register per read for the corresponding builtin.  The result is only valid
-// after lds_wait<K>() has been applied to it: LDS reads return in order, so "at most K LDS
-// operations outstanding" implies every read older than the last K has landed.
-template <int OFF>
+// Transposing LDS read (ds_read_b64_tr_b16): lane 16*h + 4*e + a passes the address of 4
+// consecutive 16-bit values; it receives, for j = 0..3, element (lane & 3) of the quadruple
+// addressed by lane 16*h + 4*j + ((lane >> 2) & 3).
 __device__ __forceinline__ s16x4 lds_read_tr16(unsigned addr) {
-    static_assert(OFF >= 0 && OFF < 65536 && OFF % 8 == 0, "DS offset field");
-    s16x4 v;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF));
-    return v;
+    return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr);
 }
-template <int K>
-__device__ __forceinline__ void lds_wait(s16x4& a, s16x4& b) {
-    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(a), "+v"(b) : "n"(K));
+
+// 16 bytes per lane, global -> LDS, without passing through registers: lane L's data lands at
+// lds_base + 16*L (lds_base is wave-uniform and travels in M0).  Written as inline assembly on
+// purpose: for the builtin the compiler makes every later LDS read wait for ALL such loads in
+// flight, which would undo the prefetch; completion is tracked here by explicit vmcnt waits
+// before the barrier that publishes a tile.
+__device__ __forceinline__ void load_to_lds_16(const void* gptr, unsigned lds_base) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
+                 :
+                 : "s"(lds_base), "v"(gptr)
+                 : "memory");
 }
 
 template <int I, int N, typename F>
@@ -297,26 +299,45 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 
     // direct-to-LDS loads: load i (0..3) of this wavefront is KiB group 4*wv+i of the K tile and
     // of the V tile: rows {grp, grp+16, grp+32, grp+48}; lane L carries row grp + 16*(L/16),
-    // 16-byte chunk L%16
-    auto issue_tile = [&](int t) __attribute__((always_inline)) {
-        char* stage = aw_lds + (t % AW_STAGES) * AW_STAGE;
+    // 16-byte chunk L%16.  Byte offsets of tile 0 are kept per lane; a tile further on adds a
+    // uniform stride.  Only the last tile of a ragged sequence needs its rows clamped.
+    const unsigned lds_base0 = __builtin_amdgcn_readfirstlane(
+        (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)aw_lds);
+    const int64_t tile_stride = (int64_t)AW_BN * kv_rs * 2;
+    const int last_full_tile = N / AW_BN;                 // tiles [0, last_full_tile) lie inside the sequence
+    int64_t src_off[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int grp = 4 * wv + i;
-            const int64_t key = min(t * AW_BN + grp + 16 * (lane >> 4), N - 1);
-            const int64_t off = key * kv_rs * 2 + ((lane & 15) << 4);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(kbase + off),
-                                             (__attribute__((address_space(3))) void*)(stage + grp * AW_KGRP), 16, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(vbase + off),
-                                             (__attribute__((address_space(3))) void*)(stage + AW_KTILE + grp * AW_VGRP), 16, 0, 0);
+    for (int i = 0; i < 4; ++i)
+        src_off[i] = (int64_t)(4 * wv + i + 16 * (lane >> 4)) * kv_rs * 2 + ((lane & 15) << 4);
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+        const unsigned stage = lds_base0 + (t % AW_STAGES) * AW_STAGE;
+        const char* kt_base = kbase + t * tile_stride;
+        const char* vt_base = vbase + t * tile_stride;
+        if (t < last_full_tile) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int grp = 4 * wv + i;
+                load_to_lds_16(kt_base + src_off[i], stage + grp * AW_KGRP);
+                load_to_lds_16(vt_base + src_off[i], stage + AW_KTILE + grp * AW_VGRP);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int grp = 4 * wv + i;
+                const int64_t key = min(t * AW_BN + grp + 16 * (lane >> 4), N - 1);
+                const int64_t off = key * kv_rs * 2 + ((lane & 15) << 4);
+                load_to_lds_16(kbase + off, stage + grp * AW_KGRP);
+                load_to_lds_16(vbase + off, stage + AW_KTILE + grp * AW_VGRP);
+            }
         }
     };
 
     // Software pipeline over "stages" of 32 keys (two per tile).  For stage c, with both query
-    // blocks: S(c) = 16 MFMAs, softmax(c) = vector work, PV(c) = 16 MFMAs.  Program order:
-    //     ... | PV(c-1) + max(c) | S(c+1) + exp(c) | PV(c) + max(c+1) | ...
-    // so the vector work of stage c always sits beside MFMAs that do not depend on it.
-    // Score accumulators and probability fragments are double buffered by stage parity.
+    // blocks: S(c) = 16 MFMAs, softmax(c) = vector work, PV(c) = 16 MFMAs.  One straight-line
+    // block per stage holds softmax(c) next to the MFMAs of PV(c-1) and S(c+1), which do not
+    // depend on it; the two MFMA streams are interleaved so that no accumulator is touched
+    // twice in a row.  Score accumulators and probability fragments are double buffered by
+    // stage parity.
     f32x16 s[2][2];                  // [parity][query block]
     bf16x8 pf[2][2][2];              // [parity][query block][16-key half]
 
@@ -332,7 +353,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     const unsigned k_lane = lds0 + (l32 & 15) * AW_KGRP + (l32 >> 4) * 256 + g * 16;
     const unsigned v_lane = lds0 + AW_KTILE + (4 * g + tr_e) * AW_VGRP + (16 * (tr_h & 1) + 4 * tr_a) * 2;
 
-    auto scores = [&](int par, int t, int kt) __attribute__((always_inline)) {           // S^T = K Q^T, 32 keys x (2 x 32) queries
+    auto scores_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // prologue: S of the first stage
         const unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -345,18 +366,16 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             s[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[par][1], 0, 0, 0);
         }
     };
-    auto weighted_values = [&](int par, int t, int kt) __attribute__((always_inline)) {  // O^T += V^T P^T
+    auto values_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // drain: PV of the last stage
         const unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
-        // fragment n = 4*tt + db: keys 16*tt + (slots 0..3 | slots 4..7), channels 32*db ..
         s16x4 lo[8], hi[8];
         static_for<0, 8>([&](auto n) {
             constexpr int off = (n.value >> 2) * 256 + (n.value & 3) * 64;
-            lo[n.value] = lds_read_tr16<off>(Vs);
-            hi[n.value] = lds_read_tr16<off + 8 * AW_VGRP>(Vs);
+            lo[n.value] = lds_read_tr16(Vs + off);
+            hi[n.value] = lds_read_tr16(Vs + off + 8 * AW_VGRP);
         });
         static_for<0, 8>([&](auto n) {
             constexpr int tt = n.value >> 2, db = n.value & 3;
-            lds_wait<14 - 2 * n.value>(lo[n.value], hi[n.value]);
             typedef __attribute__((ext_vector_type(8))) short s16x8;
             const s16x8 both = __builtin_shufflevector(lo[n.value], hi[n.value], 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 a = __builtin_bit_cast(bf16x8, both);
@@ -364,10 +383,34 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
         });
     };
-    // softmax, first part: mask (edge stages only), stage maximum, and - rarely - a new reference
-    // maximum with rescaling of the accumulators.  Must run after PV of the previous stage was
-    // issued: that product still belongs to the old reference.
-    auto stage_max = [&](int par, int key0, bool masked) __attribute__((always_inline)) {
+
+    // One pipeline block: softmax of stage c (scores in s[par]) -> pf[par];
+    // PV(c-1) with pf[par^1] and the V rows (tv, ktv); S(c+1) -> s[par^1] from the K rows (ts, kts).
+    auto stage_block = [&](int par, int key0, bool masked, bool has_prev, int tv, int ktv, int ts,
+                           int kts) __attribute__((always_inline)) {
+        unsigned Vs = v_lane + (tv % AW_STAGES) * AW_STAGE + ktv * 512;
+        unsigned Ks = k_lane + (ts % AW_STAGES) * AW_STAGE + kts * 512;
+        // keep the two bases as the values the fragment addresses are formed from (base + constant)
+        asm("" : "+v"(Vs));
+        asm("" : "+v"(Ks));
+        // every fragment this block multiplies is requested up front: the vector work of the
+        // stage maximum runs while they arrive
+        bf16x8 kfr[8];
+        s16x4 lo[8], hi[8];
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc)
+            kfr[dc] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
+        if (has_prev) {
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const int off = (n >> 2) * 256 + (n & 3) * 64;
+                lo[n] = lds_read_tr16(Vs + off);                               // keys of slots 0..3
+                hi[n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);                 // keys of slots 4..7
+            }
+        }
+        // softmax(c), part 1: stage maximum per query; the reference maximum of a query moves
+        // only when it is exceeded by more than the gap, and alpha = exp2(old - new) (1 if kept)
+        float alpha[2];
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             if (masked) {
@@ -381,21 +424,33 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             float mx = fmaxf(s[par][u][0], s[par][u][1]);
 #pragma unroll
             for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[par][u][r], s[par][u][r + 1]));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));       // both halves of the wavefront
             const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
-            if (__builtin_amdgcn_ballot_w64(m_new > m_ref[u] + AW_RESCALE_GAP) != 0) {
-                const float alpha = __builtin_amdgcn_exp2f(m_ref[u] - m_new);   // exp2(-inf) = 0 at the start
-                m_ref[u] = m_new;
-                l_run[u] *= alpha;
-#pragma unroll
-                for (int db = 0; db < 4; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha;
-            }
+            const float m_use = (m_new > m_ref[u] + AW_RESCALE_GAP) ? m_new : m_ref[u];
+            alpha[u] = __builtin_amdgcn_exp2f(m_ref[u] - m_use);               // exp2(-inf) = 0 at the start
+            m_ref[u] = m_use;
         }
-    };
-    // softmax, second part: probabilities relative to the reference maximum, row sums, bf16 packing
-    auto stage_exp = [&](int par) __attribute__((always_inline)) {
+        // S(c+1) accumulators
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s[par ^ 1][u][r] = 0.f;
+        // the two MFMA streams, interleaved
+        static_for<0, 8>([&](auto n) {
+            constexpr int dc = n.value;
+            s[par ^ 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[dc], qf[0][dc], s[par ^ 1][0], 0, 0, 0);
+            s[par ^ 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[dc], qf[1][dc], s[par ^ 1][1], 0, 0, 0);
+            if (has_prev) {
+                constexpr int tt = n.value >> 2, db = n.value & 3;
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const s16x8 both = __builtin_shufflevector(lo[n.value], hi[n.value], 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 va = __builtin_bit_cast(bf16x8, both);
+                o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][0][tt], o[0][db], 0, 0, 0);
+                o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][1][tt], o[1][db], 0, 0, 0);
+            }
+        });
+        // softmax(c), part 2: probabilities relative to the reference maximum, row sums, bf16 packing
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
             const float mr = m_ref[u];
@@ -415,7 +470,32 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                 pk.w = pack_bf16(e[6], e[7]);
                 pf[par][u][tt] = __builtin_bit_cast(bf16x8, pk);
             }
-            l_run[u] += psum;
+            l_run[u] = fmaf(l_run[u], alpha[u], psum);
+        }
+        // the probabilities are consumed in the next block; without this pin the compiler sinks
+        // the whole exponential part past the end of this block, away from the MFMAs it must hide
+        asm volatile("" ::"v"(pf[par][0][0]), "v"(pf[par][0][1]), "v"(pf[par][1][0]), "v"(pf[par][1][1]),
+                     "v"(l_run[0]), "v"(l_run[1]));
+        // scheduling hints for this block: after every MFMA one LDS read (while there are any)
+        // and a share of the vector work
+        if (has_prev) {
+            __builtin_amdgcn_sched_group_barrier(0x100, 24, 0);      // all LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);      // stage maximum while they fly
+#pragma unroll
+            for (int i = 0; i < 32; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+            }
+        }
+        // rare: some query moved its reference.  PV(c-1) above still belongs to the old one and
+        // has been issued; PV(c) comes in the next block.
+        if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha[u];
         }
     };
     // tile t+1 has landed everywhere and tile t-1 is dead everywhere: start fetching tile t+2
@@ -426,17 +506,11 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         if (t + 2 < ntiles) issue_tile(t + 2);
     };
     auto tile_body = [&](int t, bool masked, bool first) __attribute__((always_inline)) {
-        // even stage c = 2t (parity 0)
-        if (!first) weighted_values(1, t - 1, 1);                     // PV(c-1)
-        stage_max(0, t * AW_BN, masked);
-        scores(1, t, 1);                                              // S(c+1)
-        stage_exp(0);
-        // odd stage c = 2t+1 (parity 1)
-        weighted_values(0, t, 0);                                     // PV(c-1)
-        stage_max(1, t * AW_BN + 32, masked);
+        // even stage c = 2t: PV(c-1) = second half of tile t-1, S(c+1) = second half of tile t
+        stage_block(0, t * AW_BN, masked, !first, t - 1, 1, t, 1);
         tile_sync(t);
-        scores(0, t + 1, 0);                                          // S(c+1): first stage of the next tile
-        stage_exp(1);
+        // odd stage c = 2t+1: PV(c-1) = first half of tile t, S(c+1) = first half of tile t+1
+        stage_block(1, t * AW_BN + 32, masked, true, t, 0, t + 1, 0);
     };
 
     issue_tile(0);
@@ -448,13 +522,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 
     int t = 0;
     if (my_tiles > 0) {
-        scores(0, 0, 0);
+        scores_only(0, 0, 0);
         if (full_tiles > 0) {
             tile_body(0, false, true);
             for (t = 1; t < full_tiles; ++t) tile_body(t, false, false);
         }
         for (; t < my_tiles; ++t) tile_body(t, true, t == 0);
-        weighted_values(1, my_tiles - 1, 1);                           // drain: PV of the last stage
+        values_only(1, my_tiles - 1, 1);                               // drain: PV of the last stage
     }
     for (; t < ntiles; ++t) tile_sync(t);                              // keep feeding the other wavefronts
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
