@@ -221,7 +221,7 @@ constexpr int AW_VGRP = 1024 + 64;
 constexpr int AW_KTILE = 16 * AW_KGRP;           // 16640 B
 constexpr int AW_VTILE = 16 * AW_VGRP;           // 16896 B
 constexpr int AW_STAGE = AW_KTILE + AW_VTILE;    // K then V
-constexpr int AW_STAGES = 3;
+constexpr int AW_STAGES = 4;
 constexpr float AW_RESCALE_GAP = 8.0f;
 
 typedef __attribute__((ext_vector_type(4))) short s16x4;
@@ -480,11 +480,11 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         // and a share of the vector work
         if (has_prev) {
             __builtin_amdgcn_sched_group_barrier(0x100, 24, 0);      // all LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x002, 40, 0);      // stage maximum while they fly
+            __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);      // start of the stage maximum while they fly
 #pragma unroll
             for (int i = 0; i < 32; ++i) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 6, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
             }
         }
         // rare: some query moved its reference.  PV(c-1) above still belongs to the old one and
@@ -498,12 +498,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                     for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha[u];
         }
     };
-    // tile t+1 has landed everywhere and tile t-1 is dead everywhere: start fetching tile t+2
+    // Tile t+1 has landed everywhere (the 8 loads of tile t+2 may still be in flight) and tile
+    // t-1 is dead everywhere: start fetching tile t+3 into its stage.
     auto tile_sync = [&](int t) __attribute__((always_inline)) {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        if (t + 2 < ntiles) issue_tile(t + 2);
+        if (t + 3 < ntiles) issue_tile(t + 3);
     };
     auto tile_body = [&](int t, bool masked, bool first) __attribute__((always_inline)) {
         // even stage c = 2t: PV(c-1) = second half of tile t-1, S(c+1) = second half of tile t
@@ -515,7 +517,10 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
-    if (ntiles > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");   // tile 0 (8 loads) done, tile 1 may fly
+    if (ntiles > 2) issue_tile(2);
+    // tile 0 (the oldest 8 loads, after the Q fragments) must have landed; younger tiles may fly
+    if (ntiles > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
+    else if (ntiles > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
