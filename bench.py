@@ -24,6 +24,9 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
+# HBM-side bytes per launch of the K-projection GEMM at the bench shape, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy: profiles/gemm_kproj_config3_hbm_traffic.txt
+KPROJ_MEASURED_TRAFFIC_BYTES = 819.8e6
 
 
 def parse():
@@ -35,6 +38,12 @@ def parse():
     p.add_argument("--no-schedule", action="store_true", help="skip the 32-layer step-wise schedule leg")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--no-extras", action="store_true", help="only the headline step and its roofline")
+    p.add_argument("--calib-copy", action="store_true",
+                   help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's "
+                        "FETCH_SIZE / WRITE_SIZE counters)")
+    p.add_argument("--traffic", type=float, default=None,
+                   help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs), "
+                        "echoed in roofline.traffic")
     return p.parse_args()
 
 
@@ -117,9 +126,20 @@ def main():
     roofline = {
         "kernel": "gemm_kernel<256,256> (K projection with squared-norm epilogue)",
         "bound": "mfma", "achieved": kproj_flops / (t_kproj * 1e-3) / 1e12,
-        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "traffic": None,
+        "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "traffic": KPROJ_MEASURED_TRAFFIC_BYTES if args.keep == 320 else None,
     }
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
+    roofline["algorithmic_flops_per_launch"] = kproj_flops
+    roofline["algorithmic_bytes_per_launch"] = 2.0 * (B * T * D + kd * D + B * T * kd)
+    if args.traffic is not None:
+        roofline["traffic"] = args.traffic
+    if args.calib_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     out = {
         "metric": "pruned_prefill_layer_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
