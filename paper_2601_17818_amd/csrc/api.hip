@@ -318,9 +318,7 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
         if (rc) return rc;
     }
     // Q and V of the survivors only
-    rc = launch_gemm(xs, D, L->wq, qb, qd, nullptr, 0, B * Tp, qd, D, nullptr, s);
-    if (rc) return rc;
-    rc = launch_gemm(xs, D, L->wv, vb, kd, nullptr, 0, B * Tp, kd, D, nullptr, s);
+    rc = launch_gemm_pair(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, s);
     if (rc) return rc;
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;

@@ -21,32 +21,41 @@
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
-constexpr int GM_BK = 32;            // k-extent of one LDS slab
-constexpr int GM_SLABS = 4;          // ring of slabs: three k-steps of loads in flight
-constexpr int GM_ROWB = GM_BK * 2;   // bytes per slab row (64): unpadded, chunks XOR-swizzled
+constexpr int GM_SLABS = 4;          // ring of k-slabs in LDS: three k-steps of loads in flight
 constexpr int GM_PART = 128;         // columns per sum-of-squares partial
 constexpr int GM_XCDS = 8;
 
-template <int BM, int BN>
-constexpr size_t gemm_lds_bytes() { return (size_t)GM_SLABS * (BM + BN) * GM_ROWB; }
+template <int BM, int BN, int BK>
+constexpr size_t gemm_lds_bytes() { return (size_t)GM_SLABS * (BM + BN) * BK * 2; }
 
-// 16-byte chunk c (0..3) of slab row r lives at chunk position c ^ swz(r): with 64-byte rows
-// this makes the MFMA fragment reads (32 consecutive rows, same chunk) bank-conflict free.
-__device__ __forceinline__ int gm_swz(int row) { return (row >> 2) & 3; }
+// A slab row holds BK bf16 (64 or 128 bytes, unpadded because direct loads write 1 KiB runs).
+// 16-byte chunk c of row r lives at chunk position c ^ swz(r), which makes the MFMA fragment
+// reads (32 consecutive rows, same chunk) bank-conflict free.
+template <int BK>
+__device__ __forceinline__ int gm_swz(int row) {
+    return BK == 32 ? (row >> 2) & 3 : row & 7;
+}
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+// y = x W^T (+ residual).  With w2 != nullptr the columns [n_split, N) come from a second weight
+// matrix and go to a second output (two projections of the same input in one launch).
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w,
     uint16_t* __restrict__ y, int64_t y_stride, const uint16_t* __restrict__ res,
     int64_t res_stride, int M, int N, int K, float* __restrict__ sumsq_parts, int tiles_m,
-    int tiles_n, int group_m) {
+    int tiles_n, int group_m, const uint16_t* __restrict__ w2, uint16_t* __restrict__ y2,
+    int n_split) {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts");
+    static_assert(BK == 32 || BK == 64, "slab rows of 64 or 128 bytes");
     constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
     constexpr int MI = TM / 32, NI = TN / 32;
-    static_assert(TN == GM_PART, "one sum-of-squares partial per wavefront");
-    constexpr int SLAB = (BM + BN) * GM_ROWB;           // bytes per slab
-    constexpr int NDMA = SLAB / 1024 / 4;               // 1 KiB direct-to-LDS loads per wavefront per slab
-    static_assert(SLAB % 4096 == 0, "slab splits evenly over four wavefronts");
+    constexpr int ROWB = BK * 2;                         // bytes per slab row
+    constexpr int CHUNKS = BK / 8;                       // 16-byte chunks per row
+    constexpr int ROWS_PER_LOAD = 64 / CHUNKS;           // rows covered by one 1 KiB direct load
+    constexpr int KC = BK / 16;                          // 16-wide MFMA slices per k-step
+    constexpr int SLAB = (BM + BN) * ROWB;               // bytes per slab
+    constexpr int NDMA = SLAB / 1024 / 4;                // direct loads per wavefront per slab
+    static_assert(SLAB % 4096 == 0 && (BM * ROWB) % 1024 == 0, "slab splits evenly over loads");
 
     extern __shared__ __attribute__((aligned(1024))) char gemm_lds[];
 
@@ -73,7 +82,16 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         tile_m = first + in % gsz;
         tile_n = in / gsz;
     }
-    const int m0 = tile_m * BM, n0 = tile_n * BN;
+    const int m0 = tile_m * BM;
+    int n0 = tile_n * BN;
+    if (w2 != nullptr && n0 >= n_split) {                // second projection (uniform per workgroup)
+        w = w2;
+        y = y2;
+        n0 -= n_split;
+        N -= n_split;
+    } else if (w2 != nullptr) {
+        N = n_split;
+    }
 
     f32x16 acc[NI][MI];
 #pragma unroll
@@ -84,24 +102,24 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
     // Direct global -> LDS loads.  Load q of wavefront wv fills slab bytes [(wv*NDMA+q)*1024, +1024):
-    // 16 rows of 64 bytes; lane L lands at row L/4, chunk position L%4, so it must fetch the
-    // chunk that the swizzle assigns to that position.  Rows [0,BM) are x, [BM,BM+BN) are W.
+    // ROWS_PER_LOAD rows; lane L lands at row L / CHUNKS, chunk position L % CHUNKS, so it must
+    // fetch the chunk that the swizzle assigns to that position.  Rows [0,BM) are x, then W.
     unsigned goff[NDMA];             // byte offset of this lane's chunk from x (or W) at k = 0
 #pragma unroll
     for (int q = 0; q < NDMA; ++q) {
-        const int row = (wv * NDMA + q) * 16 + (lane >> 2);        // slab row
-        const int chunk = (lane & 3) ^ gm_swz(row);
+        const int row = (wv * NDMA + q) * ROWS_PER_LOAD + lane / CHUNKS;        // slab row
+        const int chunk = (lane % CHUNKS) ^ gm_swz<BK>(row);
         if (row < BM)
             goff[q] = 2u * (unsigned)(min(m0 + row, M - 1) * (int)x_stride + chunk * 8);
         else
             goff[q] = 2u * (unsigned)(min(n0 + row - BM, N - 1) * K + chunk * 8);
     }
-    auto issue_loads = [&](int slab, int k0, int q0, int q1) {
+    auto issue_loads = [&](int slab, int k0) {
         const char* xb = reinterpret_cast<const char*>(x + k0);
         const char* wb = reinterpret_cast<const char*>(w + k0);
 #pragma unroll
-        for (int q = q0; q < q1; ++q) {
-            const bool is_x = (wv * NDMA + q) * 16 < BM;            // wave-uniform
+        for (int q = 0; q < NDMA; ++q) {
+            const bool is_x = (wv * NDMA + q) * ROWS_PER_LOAD < BM;            // wave-uniform
             const char* src = (is_x ? xb : wb) + goff[q];
             char* dst = gemm_lds + slab * SLAB + (wv * NDMA + q) * 1024;
             __builtin_amdgcn_global_load_lds(
@@ -122,11 +140,11 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
         for (int j = 0; j < MI; ++j)
             xf[buf][j] = *reinterpret_cast<const bf16x8*>(
-                S + xrow[j] * GM_ROWB + (((2 * kc + g) ^ gm_swz(xrow[j])) << 4));
+                S + xrow[j] * ROWB + (((2 * kc + g) ^ gm_swz<BK>(xrow[j])) << 4));
 #pragma unroll
         for (int i = 0; i < NI; ++i)
             wf[buf][i] = *reinterpret_cast<const bf16x8*>(
-                S + wrow[i] * GM_ROWB + (((2 * kc + g) ^ gm_swz(wrow[i])) << 4));
+                S + wrow[i] * ROWB + (((2 * kc + g) ^ gm_swz<BK>(wrow[i])) << 4));
     };
     auto multiply = [&](int buf) {
 #pragma unroll
@@ -144,39 +162,47 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     }
     constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
 
-    // Pipeline over k-steps of 32.  Slab t % 4 holds k-step t; the loads of k-step t+3 are
+    // Pipeline over k-steps of BK.  Slab t % 4 holds k-step t; the loads of k-step t+3 are
     // issued during step t into the slab that step t-1 used (every wavefront left it before
-    // the barrier of step t-1).  Step t:
-    //   slice 0: multiply slice 0; read the fragments of slice 1; issue the loads of step t+3
+    // the barrier of step t-1).  Step t, slice by slice (a slice = 16 of k):
+    //   slice 0: multiply; read the fragments of slice 1; issue the loads of step t+3
+    //   slices 1 .. KC-2: multiply; read the fragments of the next slice
     //   wait until this wavefront's loads of step t+1 have landed (two younger steps may
     //   still be in flight); barrier
-    //   slice 1: multiply slice 1; read the fragments of slice 0 of step t+1
+    //   slice KC-1: multiply; read the fragments of slice 0 of step t+1
     // Past the end the loads repeat the last k-step into slabs nobody reads again.
-    const int nk = K / GM_BK;
-    auto k_of = [&](int step) { return min(step, nk - 1) * GM_BK; };
+    const int nk = K / BK;
+    auto k_of = [&](int step) { return min(step, nk - 1) * BK; };
     auto step = [&](int t, int slab) {
-        read_frags(1, slab, 1);
-        issue_loads((slab + 3) & 3, k_of(t + 3), 0, NDMA);
-        multiply(0);
-        if constexpr (NMFMA >= NFRAG + NDMA) {
-            VITCOP_INTERLEAVE(0x100, NFRAG)
-            VITCOP_INTERLEAVE(0x020, NDMA)
-            __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG - NDMA, 0);
+#pragma unroll
+        for (int kc = 0; kc < KC - 1; ++kc) {
+            read_frags((kc + 1) & 1, slab, kc + 1);
+            if (kc == 0) issue_loads((slab + 3) & 3, k_of(t + 3));
+            multiply(kc & 1);
+            if constexpr (NMFMA >= NFRAG + NDMA) {
+                VITCOP_INTERLEAVE(0x100, NFRAG)
+                if (kc == 0) {
+                    VITCOP_INTERLEAVE(0x020, NDMA)
+                    __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG - NDMA, 0);
+                } else {
+                    __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
+                }
+            }
         }
         // (a plain s_barrier: __syncthreads would also drain the two younger steps' loads)
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        read_frags(0, (slab + 1) & 3, 0);
-        multiply(1);
+        read_frags(KC & 1, (slab + 1) & 3, 0);
+        multiply((KC - 1) & 1);
         if constexpr (NMFMA >= NFRAG) {
             VITCOP_INTERLEAVE(0x100, NFRAG)
             __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
         }
     };
-    issue_loads(0, k_of(0), 0, NDMA);
-    issue_loads(1, k_of(1), 0, NDMA);
-    issue_loads(2, k_of(2), 0, NDMA);
+    issue_loads(0, k_of(0));
+    issue_loads(1, k_of(1));
+    issue_loads(2, k_of(2));
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -217,32 +243,37 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
                         pk.x = pack_bf16(c0, c1);
                         pk.y = pack_bf16(c2, c3);
                         *reinterpret_cast<uint2*>(y + (int64_t)m * y_stride + n) = pk;
-                        if (sumsq_parts) {
-                            float a;
-                            a = bf16_lo(pk.x); ss = fmaf(a, a, ss);
-                            a = bf16_hi(pk.x); ss = fmaf(a, a, ss);
-                            a = bf16_lo(pk.y); ss = fmaf(a, a, ss);
-                            a = bf16_hi(pk.y); ss = fmaf(a, a, ss);
+                        if constexpr (TN == GM_PART) {
+                            if (sumsq_parts) {
+                                float a;
+                                a = bf16_lo(pk.x); ss = fmaf(a, a, ss);
+                                a = bf16_hi(pk.x); ss = fmaf(a, a, ss);
+                                a = bf16_lo(pk.y); ss = fmaf(a, a, ss);
+                                a = bf16_hi(pk.y); ss = fmaf(a, a, ss);
+                            }
                         }
                     }
                 }
         }
-        if (sumsq_parts) {
-            ss += __shfl_xor(ss, 32, 64);
-            const int part = (n0 + wn * TN) / GM_PART;
-            if (g == 0 && m < M && n0 + wn * TN < N) sumsq_parts[(int64_t)part * M + m] = ss;
+        if constexpr (TN == GM_PART) {           // one partial per wavefront; other layouts never get sumsq_parts
+            if (sumsq_parts) {
+                ss += __shfl_xor(ss, 32, 64);
+                const int part = (n0 + wn * TN) / GM_PART;
+                if (g == 0 && m < M && n0 + wn * TN < N) sumsq_parts[(int64_t)part * M + m] = ss;
+            }
         }
     }
 }
 
 int gemm_sumsq_parts(int N) { return (N + GM_PART - 1) / GM_PART; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
 static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                            int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
-                           int K, float* sumsq_parts, hipStream_t s) {
-    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N>;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN>();
+                           int K, float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split,
+                           hipStream_t s) {
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
     static bool attr_set = false;        // per kernel instantiation; setting it twice is harmless
     if (!attr_set) {
         int rc = hip_status(hipFuncSetAttribute((const void*)kern,
@@ -256,21 +287,71 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
     int group_m = 1;
     while (group_m * 2 <= tiles_m && group_m * group_m * 2 <= 32) group_m *= 2;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(GM_THREADS), lds, s, x, x_stride, w, y,
-                       y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m);
+                       y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m, w2,
+                       y2, n_split);
     return launch_status("gemm");
+}
+
+// Tile choice: 256x256 tiles (each wavefront 128x128) are the efficient ones, 128x128 tiles fill
+// the chip when there are few rows.  A 256x256 tile costs about three 128x128 tiles (measured);
+// pick the cheaper number of rounds over 256 CUs.
+static bool prefer_big_tiles(int M, int N) {
+    const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
+    const long mid = (long)((M + 127) / 128) * ((N + 127) / 128);
+    const long cost_big = 3 * ((big + 255) / 256), cost_mid = (mid + 255) / 256;
+    return cost_big < cost_mid;
+}
+
+// Few rows and no norm output: the weight matrix dominates the traffic and one CU cannot pull
+// its share fast enough, so the columns are cut into 32-wide tiles to put every CU to work.
+static bool prefer_skinny_tiles(int M, int N, int K) {
+    const long mid = (long)((M + 127) / 128) * ((N + 127) / 128);
+    return mid <= 64 && K % 64 == 0 && N % 32 == 0;
 }
 
 int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                 int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                 int K, float* sumsq_parts, hipStream_t s) {
     if (M == 0 || N == 0) return VITCOP_OK;
-    // large problems: 256x256 tiles (each wavefront 128x128); otherwise 128x128 tiles
-    const long big_tiles = (long)((M + 255) / 256) * ((N + 255) / 256);
-    if (big_tiles >= 192)
-        return launch_gemm_cfg<256, 256, 2, 2>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                               sumsq_parts, s);
-    return launch_gemm_cfg<128, 128, 4, 1>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                           sumsq_parts, s);
+    if (prefer_big_tiles(M, N))
+        return launch_gemm_cfg<256, 256, 2, 2, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                                   sumsq_parts, nullptr, nullptr, 0, s);
+    if (sumsq_parts)       // one norm partial per wavefront needs the 32x128 wavefront tile
+        return launch_gemm_cfg<128, 128, 4, 1, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                                   sumsq_parts, nullptr, nullptr, 0, s);
+    if (prefer_skinny_tiles(M, N, K))
+        return launch_gemm_cfg<128, 32, 4, 1, 64>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                                  nullptr, nullptr, nullptr, 0, s);
+    return launch_gemm_cfg<128, 128, 2, 2, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
+                                               nullptr, nullptr, nullptr, 0, s);
+}
+
+// Two projections of the same input in one launch: y1 = x W1^T [M,N1], y2 = x W2^T [M,N2].
+// N1 must be a multiple of 256 (so no tile straddles the two outputs).
+int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
+                     const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s) {
+    if (M == 0) return VITCOP_OK;
+    if (N1 % 256 != 0) {
+        int rc = launch_gemm(x, x_stride, w1, y1, N1, nullptr, 0, M, N1, K, nullptr, s);
+        if (rc) return rc;
+        return launch_gemm(x, x_stride, w2, y2, N2, nullptr, 0, M, N2, K, nullptr, s);
+    }
+    // both outputs are dense with their own row stride: the kernel takes one y_stride, so the
+    // fused launch needs N1 == N2; otherwise fall back to two launches
+    if (N1 != N2) {
+        int rc = launch_gemm(x, x_stride, w1, y1, N1, nullptr, 0, M, N1, K, nullptr, s);
+        if (rc) return rc;
+        return launch_gemm(x, x_stride, w2, y2, N2, nullptr, 0, M, N2, K, nullptr, s);
+    }
+    const int N = N1 + N2;
+    if (prefer_big_tiles(M, N))
+        return launch_gemm_cfg<256, 256, 2, 2, 32>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2,
+                                                   y2, N1, s);
+    if (prefer_skinny_tiles(M, N, K))
+        return launch_gemm_cfg<128, 32, 4, 1, 64>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2, y2,
+                                                  N1, s);
+    return launch_gemm_cfg<128, 128, 2, 2, 32>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2, y2,
+                                               N1, s);
 }
 
 }  // namespace vitcop

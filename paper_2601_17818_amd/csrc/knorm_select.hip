@@ -77,7 +77,15 @@ __global__ __launch_bounds__(SEL_THREADS) void select_smallest_kernel(
     const float* src = parts + (int64_t)b * sample_stride + offset;
     for (int i = tid; i < n_vis; i += SEL_THREADS) {
         float v = src[i];
-        for (int p = 1; p < n_parts; ++p) v += src[(int64_t)p * part_stride + i];
+        int p = 1;
+        for (; p + 8 <= n_parts; p += 8) {           // eight independent loads in flight, summed in order
+            float w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] = src[(int64_t)(p + j) * part_stride + i];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) v += w[j];
+        }
+        for (; p < n_parts; ++p) v += src[(int64_t)p * part_stride + i];
         if (do_sqrt) v = sqrtf(v);
         if (norms_out) norms_out[(int64_t)b * n_vis + i] = v;
         sel_keys[i] = __float_as_uint(v);          // v >= 0: bit order = value order

@@ -32,9 +32,22 @@ __device__ inline void block_select_emit(const unsigned* keys, int n, int keep, 
         for (int shift = 24; shift >= 0; shift -= 8) {
             if (tid < 256) sh.hist[tid] = 0;
             __syncthreads();
-            for (int i = tid; i < n; i += SEL_THREADS) {
-                unsigned k = keys[i];
-                if ((k & mask) == prefix) atomicAdd(&sh.hist[(k >> shift) & 255u], 1u);
+            for (int i0 = 0; i0 < n; i0 += SEL_THREADS) {        // uniform trip count: ballots below
+                const int i = i0 + tid;
+                const unsigned k = i < n ? keys[i] : 0u;
+                const bool live = i < n && (k & mask) == prefix;
+                const unsigned dgt = (k >> shift) & 255u;
+                // Scores of one sample share their high bits, so in the early passes most lanes
+                // of a wavefront hit the same bin: the lanes that agree with the first live lane
+                // are counted with one atomic, the others add individually.
+                const unsigned long long live_mask = __builtin_amdgcn_ballot_w64(live);
+                if (live_mask != 0) {
+                    const int leader = __builtin_ctzll(live_mask);
+                    const unsigned d0 = __builtin_amdgcn_readlane(dgt, leader);
+                    const unsigned long long same = __builtin_amdgcn_ballot_w64(live && dgt == d0);
+                    if ((tid & 63) == leader) atomicAdd(&sh.hist[d0], (unsigned)__builtin_popcountll(same));
+                    else if (live && dgt != d0) atomicAdd(&sh.hist[dgt], 1u);
+                }
             }
             __syncthreads();
             if (tid < 64) {

@@ -47,5 +47,8 @@ int gemm_sumsq_parts(int N);
 int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                 int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                 int K, float* sumsq_parts, hipStream_t s);
+// y1 = x W1^T [M,N1] and y2 = x W2^T [M,N2] (dense outputs), one launch when the shapes allow
+int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
+                     const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s);
 
 }  // namespace vitcop
