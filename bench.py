@@ -237,12 +237,15 @@ def main():
         except Exception:
             cores = os.cpu_count() or 1
         t0 = time.perf_counter()
-        O.pruned_layer(c3["x"], c3["wq"], c3["wk"], c3["wv"], c3["wo"], Hq, Hkv, d, vs, nv, args.keep)
-        O.filter_visual(tiles["q_cls"], tiles["k"], f_keep)
-        t_cpu = time.perf_counter() - t0
+        n_cpu = 0
+        while n_cpu == 0 or time.perf_counter() - t0 < 10.0:     # about 10 s of CPU work
+            O.pruned_layer(c3["x"], c3["wq"], c3["wk"], c3["wv"], c3["wo"], Hq, Hkv, d, vs, nv, args.keep)
+            O.filter_visual(tiles["q_cls"], tiles["k"], f_keep)
+            n_cpu += 1
+        t_cpu = (time.perf_counter() - t0) / n_cpu
         out["cpu_baseline"] = {"value": B * T / t_cpu, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
-                               "sample": f"one full step of the same workload ({B} samples x {T} tokens, fp64 "
-                                         f"pruned layer + filter on {5 * B} tiles), {t_cpu:.1f} s"}
+                               "sample": f"{n_cpu} full steps of the same workload ({B} samples x {T} tokens, fp64 "
+                                         f"pruned layer + filter on {5 * B} tiles), {t_cpu:.2f} s per step"}
 
     print(json.dumps(out))
 
