@@ -39,7 +39,7 @@ def hipcc() -> str:
 
 # per-file extras: the attention kernels never produce NaNs (masked scores are -inf and the
 # reference maximum is finite from the first key on), so fmax needs no NaN-quieting moves
-EXTRA = {"attn.hip": ["-fno-honor-nans"]}
+EXTRA = {"attn.hip": ["-fno-honor-nans", "-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def _compile(src: str) -> str:

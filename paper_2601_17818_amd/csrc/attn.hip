@@ -421,9 +421,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                     if (key >= N || (CAUSAL && key > query)) s[par][u][r] = -INFINITY;
                 }
             }
-            float mx = fmaxf(s[par][u][0], s[par][u][1]);
-#pragma unroll
-            for (int r = 2; r < 16; r += 2) mx = fmaxf(mx, fmaxf(s[par][u][r], s[par][u][r + 1]));
+            // (reductions are written as trees: a dependent vector instruction waits about
+            // twice as long as an independent one)
+            const f32x16& sv = s[par][u];
+            const float m0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), m1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
+            const float m2 = fmaxf(fmaxf(sv[6], sv[7]), sv[8]), m3 = fmaxf(fmaxf(sv[9], sv[10]), sv[11]);
+            const float m4 = fmaxf(fmaxf(sv[12], sv[13]), sv[14]);
+            float mx = fmaxf(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3)), fmaxf(m4, sv[15]));
             const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
             mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));       // both halves of the wavefront
             const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
@@ -450,24 +454,31 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                 o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][1][tt], o[1][db], 0, 0, 0);
             }
         });
-        // softmax(c), part 2: probabilities relative to the reference maximum, row sums, bf16 packing
+        // softmax(c), part 2: probabilities relative to the reference maximum, row sums, bf16
+        // packing.  All arguments first, then all exponentials, then tree sums: no instruction
+        // waits on its immediate predecessor.
+        float e[2][16];
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) e[u][i] = fmaf(s[par][u][i], scale_log2e, -m_ref[u]);
+#pragma unroll
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) e[u][i] = __builtin_amdgcn_exp2f(e[u][i]);
 #pragma unroll
         for (int u = 0; u < 2; ++u) {
-            const float mr = m_ref[u];
-            float psum = 0.f;
+            float p[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) p[i] = e[u][2 * i] + e[u][2 * i + 1];
+            const float psum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-                float e[8];
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    e[i] = __builtin_amdgcn_exp2f(fmaf(s[par][u][8 * tt + i], scale_log2e, -mr));
-                    psum += e[i];
-                }
                 u32x4 pk;
-                pk.x = pack_bf16(e[0], e[1]);
-                pk.y = pack_bf16(e[2], e[3]);
-                pk.z = pack_bf16(e[4], e[5]);
-                pk.w = pack_bf16(e[6], e[7]);
+                pk.x = pack_bf16(e[u][8 * tt + 0], e[u][8 * tt + 1]);
+                pk.y = pack_bf16(e[u][8 * tt + 2], e[u][8 * tt + 3]);
+                pk.z = pack_bf16(e[u][8 * tt + 4], e[u][8 * tt + 5]);
+                pk.w = pack_bf16(e[u][8 * tt + 6], e[u][8 * tt + 7]);
                 pf[par][u][tt] = __builtin_bit_cast(bf16x8, pk);
             }
             l_run[u] = fmaf(l_run[u], alpha[u], psum);
