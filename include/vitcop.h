@@ -119,7 +119,7 @@ int vitcop_compact(const vitcop_gather_t* tensors /* host array */, int n_tensor
  *   q [B,N,Hq,d], k,v [B,N,Hkv,d] bf16, dense
  *   out [B,N,Hq,d] bf16;  lse_out [B,Hq,N] fp32 natural-log-sum-exp, may be NULL
  *   scale 0 selects 1/sqrt(d);  causal 0 or 1
- * d == 128 (d == 64 is rejected with VITCOP_EUNSUPPORTED in this build).
+ * d in {64, 128}.
  */
 size_t vitcop_prefill_attn_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
 int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,

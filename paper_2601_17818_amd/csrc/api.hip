@@ -195,14 +195,13 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
     REQUIRE(causal == 0 || causal == 1, VITCOP_EINVAL, "prefill_attn: causal=%d", causal);
     REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "prefill_attn: scale");
     REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "prefill_attn: d=%d", d);
-    REQUIRE(d == 128, VITCOP_EUNSUPPORTED, "prefill_attn: d=%d (this build has d=128 only)", d);
     REQUIRE(Hq <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "prefill_attn: Hq or B above 65535");
     if (B == 0 || N == 0) return VITCOP_OK;
     REQUIRE(q && k && v && out, VITCOP_EINVAL, "prefill_attn: null pointer");
     REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), VITCOP_EINVAL,
             "prefill_attn: pointers must be 16-byte aligned");
     if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
-    return launch_attn(q, k, v, out, lse_out, B, N, Hq, Hkv, scale, causal, static_cast<hipStream_t>(stream));
+    return launch_attn(q, k, v, out, lse_out, B, N, Hq, Hkv, d, scale, causal, static_cast<hipStream_t>(stream));
 }
 
 /* ------------------------------------------------------------- projection */
@@ -235,7 +234,7 @@ static int check_layer(const vitcop_layer_t* L) {
     REQUIRE(L->B >= 1 && L->T >= 1 && L->D >= 32 && L->Hq >= 1 && L->Hkv >= 1, VITCOP_EINVAL,
             "layer: B=%d T=%d D=%d Hq=%d Hkv=%d", L->B, L->T, L->D, L->Hq, L->Hkv);
     REQUIRE(L->Hq % L->Hkv == 0, VITCOP_EINVAL, "layer: Hq=%d not a multiple of Hkv=%d", L->Hq, L->Hkv);
-    REQUIRE(L->d == 128, VITCOP_EUNSUPPORTED, "layer: d=%d (this build has d=128 only)", L->d);
+    REQUIRE(L->d == 64 || L->d == 128, VITCOP_EUNSUPPORTED, "layer: d=%d (64 or 128)", L->d);
     REQUIRE(L->D % 32 == 0, VITCOP_EUNSUPPORTED, "layer: D=%d not a multiple of 32", L->D);
     REQUIRE(L->vis_start >= 0 && L->n_vis >= 0 && (long)L->vis_start + L->n_vis <= L->T, VITCOP_EINVAL,
             "layer: visual span [%d,%d) outside [0,%d)", L->vis_start, L->vis_start + L->n_vis, L->T);
@@ -320,7 +319,7 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
     // Q and V of the survivors only
     rc = launch_gemm_pair(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, s);
     if (rc) return rc;
-    rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, 1.0f / std::sqrt((float)L->d), 1, s);
+    rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
     return launch_gemm(ob, qd, L->wo, L->y, D, L->residual ? xs : nullptr, D, B * Tp, D, qd, nullptr, s);
 }

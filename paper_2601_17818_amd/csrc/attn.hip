@@ -25,15 +25,21 @@ constexpr int AT_D = 128;
 constexpr int AT_BM = 128;
 constexpr int AT_BN = 64;
 constexpr int AT_THREADS = 256;
-constexpr int AT_KLD = AT_D + 8;     // bf16 per K row in LDS (272 B: conflict-free 16 B reads)
 constexpr int AT_VLD = AT_BN + 8;    // bf16 per V^T row in LDS (144 B)
 
+template <int D>
 __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, uint16_t* __restrict__ out, float* __restrict__ lse,
     int N, int Hq, int Hkv, float scale_log2e, int causal) {
-    __shared__ __attribute__((aligned(16))) uint16_t Ks[AT_BN * AT_KLD];
-    __shared__ __attribute__((aligned(16))) uint16_t Vt[AT_D * AT_VLD];
+    static_assert(D == 64 || D == 128, "head dimension");
+    constexpr int KLD = D + 8;            // bf16 per K row in LDS (odd multiple of 16 B: conflict-free reads)
+    constexpr int DC = D / 16;            // 16-channel MFMA steps of Q K^T
+    constexpr int DB = D / 32;            // 32-channel blocks of the output
+    constexpr int KCH = D / 8;            // 16-byte chunks per K/V row
+    constexpr int KLOADS = AT_BN * KCH / AT_THREADS;   // K chunks per thread per tile (4 or 2)
+    __shared__ __attribute__((aligned(16))) uint16_t Ks[AT_BN * KLD];
+    __shared__ __attribute__((aligned(16))) uint16_t Vt[D * AT_VLD];
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
@@ -42,20 +48,20 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     const int h = blockIdx.y, b = blockIdx.z;
     const int hk = h / (Hq / Hkv);
     const int q0 = qb * AT_BM, wq0 = q0 + 32 * wv;
-    const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
+    const int64_t q_rs = (int64_t)Hq * D, kv_rs = (int64_t)Hkv * D;
     const int query = wq0 + l32;
 
     // Q^T fragments (B operand): lane holds 8 channels of its query per 16-channel step
-    bf16x8 qf[8];
+    bf16x8 qf[DC];
     {
-        const uint16_t* qp = q + ((int64_t)b * N + min(query, N - 1)) * q_rs + h * AT_D + 8 * g;
+        const uint16_t* qp = q + ((int64_t)b * N + min(query, N - 1)) * q_rs + h * D + 8 * g;
 #pragma unroll
-        for (int dc = 0; dc < 8; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
+        for (int dc = 0; dc < DC; ++dc) qf[dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
     }
 
-    f32x16 o[4];
+    f32x16 o[DB];
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < DB; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[i][r] = 0.f;
     float m_run = -INFINITY, l_run = 0.f;
@@ -63,24 +69,27 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     const int kend = causal ? min(N, q0 + AT_BM) : N;
     const int ntiles = (kend + AT_BN - 1) / AT_BN;
     const int wave_kend = causal ? min(N, wq0 + 32) : N;
-    const uint16_t* kbase = k + (int64_t)b * N * kv_rs + hk * AT_D;
-    const uint16_t* vbase = v + (int64_t)b * N * kv_rs + hk * AT_D;
+    const uint16_t* kbase = k + (int64_t)b * N * kv_rs + hk * D;
+    const uint16_t* vbase = v + (int64_t)b * N * kv_rs + hk * D;
 
-    const int vkq = tid & 15, vc = tid >> 4;      // V: key quad, channel chunk
+    const int vkq = tid & 15, vc = tid >> 4;      // V: key quad, channel chunk (threads with vc >= KCH idle)
+    const bool v_active = vc < KCH;
     // position of the key quad inside its row of V^T: swap the two low bits of the quad index
     const int vpq = (vkq & ~3) | ((vkq & 1) << 1) | ((vkq >> 1) & 1);
-    u32x4 kr[4], vr[4];
+    u32x4 kr[KLOADS], vr[4];
     auto load_tile = [&](int t) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KLOADS; ++j) {
             const int id = tid + AT_THREADS * j;
-            const int key = min(t * AT_BN + (id >> 4), N - 1);
-            kr[j] = *reinterpret_cast<const u32x4*>(kbase + key * kv_rs + (id & 15) * 8);
+            const int key = min(t * AT_BN + id / KCH, N - 1);
+            kr[j] = *reinterpret_cast<const u32x4*>(kbase + key * kv_rs + (id % KCH) * 8);
         }
+        if (v_active) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int key = min(t * AT_BN + 4 * vkq + j, N - 1);
-            vr[j] = *reinterpret_cast<const u32x4*>(vbase + key * kv_rs + vc * 8);
+            for (int j = 0; j < 4; ++j) {
+                const int key = min(t * AT_BN + 4 * vkq + j, N - 1);
+                vr[j] = *reinterpret_cast<const u32x4*>(vbase + key * kv_rs + vc * 8);
+            }
         }
     };
     load_tile(0);
@@ -88,11 +97,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     for (int t = 0; t < ntiles; ++t) {
         __syncthreads();
 #pragma unroll
-        for (int j = 0; j < 4; ++j) {
+        for (int j = 0; j < KLOADS; ++j) {
             const int id = tid + AT_THREADS * j;
-            *reinterpret_cast<u32x4*>(&Ks[(id >> 4) * AT_KLD + (id & 15) * 8]) = kr[j];
+            *reinterpret_cast<u32x4*>(&Ks[(id / KCH) * KLD + (id % KCH) * 8]) = kr[j];
         }
-        {
+        if (v_active) {
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
                 const uint32_t w0 = vr[0][p], w1 = vr[1][p], w2 = vr[2][p], w3 = vr[3][p];
@@ -116,9 +125,9 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[kt][r] = 0.f;
 #pragma unroll
-            for (int dc = 0; dc < 8; ++dc) {
+            for (int dc = 0; dc < DC; ++dc) {
                 const bf16x8 a = *reinterpret_cast<const bf16x8*>(
-                    &Ks[(kt * 32 + l32) * AT_KLD + dc * 16 + g * 8]);
+                    &Ks[(kt * 32 + l32) * KLD + dc * 16 + g * 8]);
                 s[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[dc], s[kt], 0, 0, 0);
             }
         }
@@ -163,12 +172,12 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
             }
         l_run = l_run * alpha + psum;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
         // O^T += V^T P^T
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
@@ -182,9 +191,9 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
     const float l_tot = l_run + __shfl_xor(l_run, 32, 64);
     if (query < N) {
         const float inv = 1.0f / l_tot;
-        uint16_t* op = out + ((int64_t)b * N + query) * q_rs + h * AT_D;
+        uint16_t* op = out + ((int64_t)b * N + query) * q_rs + h * D;
 #pragma unroll
-        for (int db = 0; db < 4; ++db)
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
             for (int r4 = 0; r4 < 4; ++r4) {
                 uint2 pk;
@@ -575,10 +584,16 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 constexpr int AW_MIN_N = 320;      // below this the 128-query kernel is faster (measured)
 
 int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
-                float* lse, int B, int N, int Hq, int Hkv, float scale, int causal,
+                float* lse, int B, int N, int Hq, int Hkv, int d, float scale, int causal,
                 hipStream_t s) {
     if (B == 0 || N == 0) return VITCOP_OK;
     const float sl2 = scale * 1.4426950408889634f;
+    if (d == 64) {
+        dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
+        hipLaunchKernelGGL(attn_kernel<64>, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
+                           causal);
+        return launch_status("attn<64>");
+    }
     if (N >= AW_MIN_N) {
         static bool attr_set = false;
         constexpr int lds = AW_STAGES * AW_STAGE;
@@ -603,7 +618,7 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
         return launch_status("attn_wide");
     }
     dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
-    hipLaunchKernelGGL(attn_kernel, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
+    hipLaunchKernelGGL(attn_kernel<128>, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
                        causal);
     return launch_status("attn");
 }

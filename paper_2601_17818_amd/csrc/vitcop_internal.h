@@ -39,7 +39,7 @@ int launch_filter(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H,
 
 // ---- attention (attn.hip) -------------------------------------------------
 int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
-                float* lse, int B, int N, int Hq, int Hkv, float scale, int causal,
+                float* lse, int B, int N, int Hq, int Hkv, int d, float scale, int causal,
                 hipStream_t s);
 
 // ---- projection GEMM (gemm.hip) -------------------------------------------

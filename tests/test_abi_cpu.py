@@ -110,7 +110,7 @@ def test_attn_validation():
 
     assert call(Hq=28, Hkv=5) == binding.VITCOP_EINVAL
     assert call(d=96) == binding.VITCOP_EINVAL
-    assert call(d=64) == binding.VITCOP_EUNSUPPORTED
+    assert call(d=64, N=0) == binding.VITCOP_OK                  # d = 64 passes validation
     assert call(causal=2) == binding.VITCOP_EINVAL
     assert call(scale=-1.0) == binding.VITCOP_EINVAL
     assert call(q=None) == binding.VITCOP_EINVAL
@@ -154,8 +154,9 @@ def test_layer_validation_and_workspace():
     for bad in (layer_desc(keep=600), layer_desc(Hq=30), layer_desc(vis_start=100),
                 layer_desc(x=None), layer_desc(positions_out=A16)):
         assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
-    assert ws(C.byref(layer_desc(d=64))) == 0
-    assert run(C.byref(layer_desc(d=64)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
+    assert ws(C.byref(layer_desc(d=64, Hq=64, Hkv=64))) > 0
+    assert ws(C.byref(layer_desc(d=96))) == 0
+    assert run(C.byref(layer_desc(d=96)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
     assert run(C.byref(layer_desc(D=4100)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
 
 

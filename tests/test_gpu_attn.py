@@ -113,6 +113,29 @@ def test_config0_pruned_shape_and_unpruned_shape(vc):
         assert np.abs(lse - ref_lse).max() < 1e-3
 
 
+# head dimension 64 (the vision encoder's, and small language models')
+@pytest.mark.parametrize("N", [1, 33, 64, 65, 129, 300, 577, 1111])
+def test_head_dim_64_causal(vc, N):
+    t = I.qkv_tensors(800 + N, 2, N, 4, 2, 64)
+    out, lse = run(vc, t)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+    assert_attention_close(out, ref, f"d=64 N={N}")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+def test_head_dim_64_non_causal_and_scale(vc):
+    t = I.qkv_tensors(850, 1, 577, 16, 16, 64)                  # one CLIP-L image: 576 patches + [CLS]
+    out, lse = run(vc, t, causal=False)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], None, False)
+    assert_attention_close(out, ref, "d=64 non-causal")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+    t = I.qkv_tensors(851, 1, 200, 2, 2, 64, std=3.0)
+    out, lse = run(vc, t, scale=0.2)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], 0.2)
+    assert_attention_close(out, ref, "d=64 large logits")
+    assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
 def test_deterministic(vc):
     t = I.qkv_tensors(700, 2, 300, 4, 2, 128)
     q, k, v = dev(t["q"]), dev(t["k"]), dev(t["v"])

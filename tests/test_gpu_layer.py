@@ -134,6 +134,12 @@ def test_small_layer_residual_gqa(vc):
     assert check_layer(vc, c, 100, True, "gqa+res")
 
 
+def test_small_layer_head_dim_64(vc):
+    make = lambda s: small_layer(s, B=2, T=420, D=256, Hq=4, Hkv=4, d=64, vs=10, nv=390)
+    c = first_gap_free(make, 120, 970)
+    assert check_layer(vc, c, 120, True, "d=64")
+
+
 def test_config0_layer(vc):
     # N(0,1) hidden states give tightly concentrated K-norms: the cut falls among near-ties,
     # so the GPU's list may differ from the oracle's inside the tie band (checked), and the
