@@ -292,14 +292,26 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
     return launch_status("gemm");
 }
 
-// Tile choice: 256x256 tiles (each wavefront 128x128) are the efficient ones, 128x128 tiles fill
-// the chip when there are few rows.  A 256x256 tile costs about three 128x128 tiles (measured);
-// pick the cheaper number of rounds over 256 CUs.
-static bool prefer_big_tiles(int M, int N) {
-    const long big = (long)((M + 255) / 256) * ((N + 255) / 256);
-    const long mid = (long)((M + 127) / 128) * ((N + 127) / 128);
-    const long cost_big = 3 * ((big + 255) / 256), cost_mid = (mid + 255) / 256;
-    return cost_big < cost_mid;
+// Tile shapes.  The wavefront tile sets the LDS bytes read per MFMA, so big tiles are the
+// efficient ones; smaller ones exist to fill all 256 CUs when there are few rows.  `rate` is
+// the measured throughput of a CU on that shape relative to 256x256 (K = 4096, full rounds).
+struct TileShape {
+    int bm, bn;
+    float rate;
+    bool sumsq;        // wavefront tile is 128 columns wide: can emit the norm partials
+};
+enum TileId { T256x256, T192x256, T256x128, T192x128, T128x128, T128x128R, T128x32, T_COUNT };
+static const TileShape kTiles[T_COUNT] = {
+    {256, 256, 1.00f, true},  {192, 256, 0.80f, true},  {256, 128, 0.74f, false}, {192, 128, 0.64f, false},
+    {128, 128, 0.71f, false}, {128, 128, 0.69f, true},  {128, 32, 0.0f, false},
+};
+
+// Estimated time of the launch in units of (one 256x256 tile at full rate): rounds over the
+// 256 CUs times the time of one tile.
+static float tile_cost(const TileShape& t, int M, int N) {
+    const long tiles = (long)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn);
+    const long rounds = (tiles + 255) / 256;
+    return (float)rounds * (float)(t.bm * t.bn) / (65536.0f * t.rate);
 }
 
 // Few rows and no norm output: the weight matrix dominates the traffic and one CU cannot pull
@@ -309,49 +321,64 @@ static bool prefer_skinny_tiles(int M, int N, int K) {
     return mid <= 64 && K % 64 == 0 && N % 32 == 0;
 }
 
+static TileId choose_tile(int M, int N, int K, bool need_sumsq, int align_n) {
+    if (!need_sumsq && prefer_skinny_tiles(M, N, K)) return T128x32;
+    TileId best = need_sumsq ? T128x128R : T128x128;
+    float best_cost = tile_cost(kTiles[best], M, N);
+    for (int i = 0; i < T128x32; ++i) {
+        const TileShape& t = kTiles[i];
+        if (need_sumsq && !t.sumsq) continue;
+        if (align_n % t.bn != 0) continue;           // a tile must not straddle the two outputs of a pair
+        const float c = tile_cost(t, M, N);
+        if (c < best_cost) {
+            best_cost = c;
+            best = (TileId)i;
+        }
+    }
+    return best;
+}
+
+static int launch_tile(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
+                       int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N, int K,
+                       float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split, hipStream_t s) {
+#define VITCOP_TILE(BM, BN, WM, WN, BK) \
+    return launch_gemm_cfg<BM, BN, WM, WN, BK>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, \
+                                               sumsq_parts, w2, y2, n_split, s)
+    switch (id) {
+        case T256x256: VITCOP_TILE(256, 256, 2, 2, 32);
+        case T192x256: VITCOP_TILE(192, 256, 2, 2, 32);
+        case T256x128: VITCOP_TILE(256, 128, 2, 2, 32);
+        case T192x128: VITCOP_TILE(192, 128, 2, 2, 32);
+        case T128x128: VITCOP_TILE(128, 128, 2, 2, 32);
+        case T128x128R: VITCOP_TILE(128, 128, 4, 1, 32);
+        default: VITCOP_TILE(128, 32, 4, 1, 64);
+    }
+#undef VITCOP_TILE
+}
+
 int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                 int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                 int K, float* sumsq_parts, hipStream_t s) {
     if (M == 0 || N == 0) return VITCOP_OK;
-    if (prefer_big_tiles(M, N))
-        return launch_gemm_cfg<256, 256, 2, 2, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                                   sumsq_parts, nullptr, nullptr, 0, s);
-    if (sumsq_parts)       // one norm partial per wavefront needs the 32x128 wavefront tile
-        return launch_gemm_cfg<128, 128, 4, 1, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                                   sumsq_parts, nullptr, nullptr, 0, s);
-    if (prefer_skinny_tiles(M, N, K))
-        return launch_gemm_cfg<128, 32, 4, 1, 64>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                                  nullptr, nullptr, nullptr, 0, s);
-    return launch_gemm_cfg<128, 128, 2, 2, 32>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K,
-                                               nullptr, nullptr, nullptr, 0, s);
+    const TileId id = choose_tile(M, N, K, sumsq_parts != nullptr, 768 /* any tile width divides it */);
+    return launch_tile(id, x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, nullptr,
+                       nullptr, 0, s);
 }
 
 // Two projections of the same input in one launch: y1 = x W1^T [M,N1], y2 = x W2^T [M,N2].
-// N1 must be a multiple of 256 (so no tile straddles the two outputs).
+// Both outputs are dense and the kernel takes one output row stride, so the fused launch needs
+// N1 == N2, and N1 a multiple of the tile width so that no tile straddles the two outputs;
+// otherwise two launches.
 int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                      const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s) {
     if (M == 0) return VITCOP_OK;
-    if (N1 % 256 != 0) {
+    if (N1 != N2 || N1 % 128 != 0) {
         int rc = launch_gemm(x, x_stride, w1, y1, N1, nullptr, 0, M, N1, K, nullptr, s);
         if (rc) return rc;
         return launch_gemm(x, x_stride, w2, y2, N2, nullptr, 0, M, N2, K, nullptr, s);
     }
-    // both outputs are dense with their own row stride: the kernel takes one y_stride, so the
-    // fused launch needs N1 == N2; otherwise fall back to two launches
-    if (N1 != N2) {
-        int rc = launch_gemm(x, x_stride, w1, y1, N1, nullptr, 0, M, N1, K, nullptr, s);
-        if (rc) return rc;
-        return launch_gemm(x, x_stride, w2, y2, N2, nullptr, 0, M, N2, K, nullptr, s);
-    }
-    const int N = N1 + N2;
-    if (prefer_big_tiles(M, N))
-        return launch_gemm_cfg<256, 256, 2, 2, 32>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2,
-                                                   y2, N1, s);
-    if (prefer_skinny_tiles(M, N, K))
-        return launch_gemm_cfg<128, 32, 4, 1, 64>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2, y2,
-                                                  N1, s);
-    return launch_gemm_cfg<128, 128, 2, 2, 32>(x, x_stride, w1, y1, N1, nullptr, 0, M, N, K, nullptr, w2, y2,
-                                               N1, s);
+    const TileId id = choose_tile(M, N1 + N2, K, false, N1);
+    return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
 }
 
 }  // namespace vitcop
