@@ -196,6 +196,7 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
     REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "prefill_attn: scale");
     REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "prefill_attn: d=%d", d);
     REQUIRE(Hq <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "prefill_attn: Hq or B above 65535");
+    REQUIRE(N <= (1 << 22), VITCOP_EUNSUPPORTED, "prefill_attn: N=%d above 2^22", N);
     if (B == 0 || N == 0) return VITCOP_OK;
     REQUIRE(q && k && v && out, VITCOP_EINVAL, "prefill_attn: null pointer");
     REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), VITCOP_EINVAL,

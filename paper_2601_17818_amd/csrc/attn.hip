@@ -18,6 +18,7 @@
 
 #include "vitcop_internal.h"
 #include "device_utils.h"
+#include <algorithm>
 
 namespace vitcop {
 
@@ -43,9 +44,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int l32 = lane & 31, g = lane >> 5;
-    // late query blocks carry the most keys under the causal mask: start them first
-    const int qb = causal ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Late query blocks carry the most keys under the causal mask.  The query block is the
+    // slowest grid index and is reversed, so workgroups start in order of decreasing work over
+    // all heads and samples (longest first keeps the CUs evenly loaded to the end).
+    const int qb = causal ? (int)gridDim.z - 1 - (int)blockIdx.z : (int)blockIdx.z;
+    const int h = blockIdx.x, b = blockIdx.y;
     const int hk = h / (Hq / Hkv);
     const int q0 = qb * AT_BM, wq0 = q0 + 32 * wv;
     const int64_t q_rs = (int64_t)Hq * D, kv_rs = (int64_t)Hkv * D;
@@ -266,14 +269,32 @@ template <bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, uint16_t* __restrict__ out, float* __restrict__ lse,
-    int N, int Hq, int Hkv, float scale_log2e) {
+    int N, int Hq, int Hkv, float scale_log2e, int n_qb, int n_heads, int group) {
     extern __shared__ __attribute__((aligned(1024))) char aw_lds[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
-    const int qb = CAUSAL ? (int)gridDim.x - 1 - (int)blockIdx.x : (int)blockIdx.x;
-    const int h = blockIdx.y, b = blockIdx.z;
+    // Workgroup -> (sample*head, query block).  The (sample, head) pairs are taken in groups of
+    // `group`; inside a group the query blocks go from the last (most keys under the causal
+    // mask) to the first, all heads of the group for each.  So at any time the chip works on
+    // few heads and many of their query blocks, which stream the same K and V rows at the
+    // same pace and share them in L2, while work still starts in order of decreasing length.
+    // Consecutive workgroup ids go to different XCDs (each with its own L2): with a group size
+    // that is a multiple of 8 a head keeps its XCD for all its query blocks, and the heads
+    // of one XCD are consecutive, i.e. they share their K/V head under grouped-query attention.
+    int qb, hb;
+    {
+        const int id = blockIdx.x;
+        const int grp = id / (n_qb * group);
+        const int first = grp * group;
+        const int gsz = min(group, n_heads - first);
+        const int rem = id - first * n_qb;
+        const int r = rem / gsz, j = rem - r * gsz;
+        hb = first + ((gsz & 7) == 0 ? (j & 7) * (gsz >> 3) + (j >> 3) : j);
+        qb = CAUSAL ? n_qb - 1 - r : r;
+    }
+    const int h = hb % Hq, b = hb / Hq;
     const int hk = h / (Hq / Hkv);
     const int q0 = qb * AW_BM, wq0 = q0 + 64 * wv;
     const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
@@ -287,6 +308,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 #pragma unroll
         for (int dc = 0; dc < 8; ++dc) qf[u][dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
     }
+    // The Q fragments are only ever MFMA operands, which may come from the accumulation
+    // registers: keep them there, so the 64 of them do not compete with the accumulators and
+    // the softmax for the 256 vector registers (they would be evicted and copied back before
+    // every use).
+#pragma unroll
+    for (int u = 0; u < 2; ++u)
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc) asm volatile("" : "+a"(qf[u][dc]));
 
     f32x16 o[2][4];
 #pragma unroll
@@ -587,9 +616,10 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
                 float* lse, int B, int N, int Hq, int Hkv, int d, float scale, int causal,
                 hipStream_t s) {
     if (B == 0 || N == 0) return VITCOP_OK;
+    if (N > (1 << 22)) return fail(VITCOP_EUNSUPPORTED, "attention: N=%d above 2^22", N);   // grid.z limit
     const float sl2 = scale * 1.4426950408889634f;
     if (d == 64) {
-        dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
+        dim3 grid(Hq, B, (N + AT_BM - 1) / AT_BM);
         hipLaunchKernelGGL(attn_kernel<64>, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
                            causal);
         return launch_status("attn<64>");
@@ -608,16 +638,22 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
             if (rc) return rc;
             attr_set = true;
         }
-        dim3 grid((N + AW_BM - 1) / AW_BM, Hq, B);
+        const int n_qb = (N + AW_BM - 1) / AW_BM;
+        const long n_heads = (long)Hq * B;
+        if (n_heads * n_qb > 0x7fffffffL) return fail(VITCOP_EUNSUPPORTED, "attention: grid too large");
+        // (sample, head) pairs in flight together: few, so that their query blocks share K/V
+        // in L2, but enough to fill the 256 CUs twice over (measured: 32 from N = 2048 up)
+        const int group = std::max(32, (512 / n_qb + 7) / 8 * 8);
+        dim3 grid((unsigned)(n_heads * n_qb));
         if (causal)
             hipLaunchKernelGGL(attn_wide_kernel<true>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
-                               Hkv, sl2);
+                               Hkv, sl2, n_qb, (int)n_heads, group);
         else
             hipLaunchKernelGGL(attn_wide_kernel<false>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
-                               Hkv, sl2);
+                               Hkv, sl2, n_qb, (int)n_heads, group);
         return launch_status("attn_wide");
     }
-    dim3 grid((N + AT_BM - 1) / AT_BM, Hq, B);
+    dim3 grid(Hq, B, (N + AT_BM - 1) / AT_BM);
     hipLaunchKernelGGL(attn_kernel<128>, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,
                        causal);
     return launch_status("attn");
