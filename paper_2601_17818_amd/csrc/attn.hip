@@ -391,6 +391,29 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     const unsigned k_lane = lds0 + (l32 & 15) * AW_KGRP + (l32 >> 4) * 256 + g * 16;
     const unsigned v_lane = lds0 + AW_KTILE + (4 * g + tr_e) * AW_VGRP + (16 * (tr_h & 1) + 4 * tr_a) * 2;
 
+    // MFMA fragments are read from LDS one pipeline block ahead of their use, into two register
+    // sets that alternate with the stage parity (the spare accumulation registers hold them),
+    // so no block waits for LDS.
+    bf16x8 kfr[2][8];                // K rows of the stage whose scores the block forms
+    s16x4 vlo[2][8], vhi[2][8];      // V^T of the stage whose probabilities the block multiplies
+    auto load_k_frags = [&](int set, int t, int kt) __attribute__((always_inline)) {
+        unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
+        asm("" : "+v"(Ks));          // keep base + constant addressing
+#pragma unroll
+        for (int dc = 0; dc < 8; ++dc)
+            kfr[set][dc] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
+    };
+    auto load_v_frags = [&](int set, int t, int kt) __attribute__((always_inline)) {
+        unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
+        asm("" : "+v"(Vs));
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int off = (n >> 2) * 256 + (n & 3) * 64;
+            vlo[set][n] = lds_read_tr16(Vs + off);                             // keys of slots 0..3
+            vhi[set][n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);               // keys of slots 4..7
+        }
+    };
+
     auto scores_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // prologue: S of the first stage
         const unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
 #pragma unroll
@@ -404,48 +427,29 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             s[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[par][1], 0, 0, 0);
         }
     };
-    auto values_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // drain: PV of the last stage
-        const unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
-        s16x4 lo[8], hi[8];
-        static_for<0, 8>([&](auto n) {
-            constexpr int off = (n.value >> 2) * 256 + (n.value & 3) * 64;
-            lo[n.value] = lds_read_tr16(Vs + off);
-            hi[n.value] = lds_read_tr16(Vs + off + 8 * AW_VGRP);
-        });
+    auto values_only = [&](int par, int set) __attribute__((always_inline)) {   // drain: PV of the last stage
         static_for<0, 8>([&](auto n) {
             constexpr int tt = n.value >> 2, db = n.value & 3;
             typedef __attribute__((ext_vector_type(8))) short s16x8;
-            const s16x8 both = __builtin_shufflevector(lo[n.value], hi[n.value], 0, 1, 2, 3, 4, 5, 6, 7);
+            const s16x8 both = __builtin_shufflevector(vlo[set][n.value], vhi[set][n.value], 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 a = __builtin_bit_cast(bf16x8, both);
             o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][0][tt], o[0][db], 0, 0, 0);
             o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
         });
     };
 
-    // One pipeline block: softmax of stage c (scores in s[par]) -> pf[par];
-    // PV(c-1) with pf[par^1] and the V rows (tv, ktv); S(c+1) -> s[par^1] from the K rows (ts, kts).
-    auto stage_block = [&](int par, int key0, bool masked, bool has_prev, int tv, int ktv, int ts,
-                           int kts) __attribute__((always_inline)) {
-        unsigned Vs = v_lane + (tv % AW_STAGES) * AW_STAGE + ktv * 512;
-        unsigned Ks = k_lane + (ts % AW_STAGES) * AW_STAGE + kts * 512;
-        // keep the two bases as the values the fragment addresses are formed from (base + constant)
-        asm("" : "+v"(Vs));
-        asm("" : "+v"(Ks));
-        // every fragment this block multiplies is requested up front: the vector work of the
-        // stage maximum runs while they arrive
-        bf16x8 kfr[8];
-        s16x4 lo[8], hi[8];
-#pragma unroll
-        for (int dc = 0; dc < 8; ++dc)
-            kfr[dc] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
-        if (has_prev) {
-#pragma unroll
-            for (int n = 0; n < 8; ++n) {
-                const int off = (n >> 2) * 256 + (n & 3) * 64;
-                lo[n] = lds_read_tr16(Vs + off);                               // keys of slots 0..3
-                hi[n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);                 // keys of slots 4..7
-            }
-        }
+    // One pipeline block, stage c = 2t + par: softmax of stage c (scores in s[par]) -> pf[par];
+    // PV(c-1) with pf[par^1] and S(c+1) -> s[par^1], both from fragment set `par`, which the
+    // previous block requested; this block requests set par^1 for the next one: the K rows of
+    // stage c+2 = (tile t+1, half par) and the V rows of stage c = (tile t, half par).
+    auto stage_block = [&](int par, int t, bool masked, bool has_prev) __attribute__((always_inline)) {
+        const int key0 = t * AW_BN + 32 * par;
+        // The fragments requested a whole block ago have long arrived; saying so here (a wait on
+        // the LDS counter alone) spares the block partial waits: with its own 24 requests queued
+        // behind them the 4-bit counter could not express "only the older ones".
+        __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0), other counters untouched
+        load_k_frags(par ^ 1, t + 1, par);
+        load_v_frags(par ^ 1, t, par);
         // softmax(c), part 1: stage maximum per query; the reference maximum of a query moves
         // only when it is exceeded by more than the gap, and alpha = exp2(old - new) (1 if kept)
         float alpha[2];
@@ -481,12 +485,12 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         // the two MFMA streams, interleaved
         static_for<0, 8>([&](auto n) {
             constexpr int dc = n.value;
-            s[par ^ 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[dc], qf[0][dc], s[par ^ 1][0], 0, 0, 0);
-            s[par ^ 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[dc], qf[1][dc], s[par ^ 1][1], 0, 0, 0);
+            s[par ^ 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[0][dc], s[par ^ 1][0], 0, 0, 0);
+            s[par ^ 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[1][dc], s[par ^ 1][1], 0, 0, 0);
             if (has_prev) {
                 constexpr int tt = n.value >> 2, db = n.value & 3;
                 typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 both = __builtin_shufflevector(lo[n.value], hi[n.value], 0, 1, 2, 3, 4, 5, 6, 7);
+                const s16x8 both = __builtin_shufflevector(vlo[par][n.value], vhi[par][n.value], 0, 1, 2, 3, 4, 5, 6, 7);
                 const bf16x8 va = __builtin_bit_cast(bf16x8, both);
                 o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][0][tt], o[0][db], 0, 0, 0);
                 o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][1][tt], o[1][db], 0, 0, 0);
@@ -547,42 +551,46 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                     for (int r = 0; r < 16; ++r) o[u][db][r] *= alpha[u];
         }
     };
-    // Tile t+1 has landed everywhere (the 8 loads of tile t+2 may still be in flight) and tile
-    // t-1 is dead everywhere: start fetching tile t+3 into its stage.
+    // Start of tile t.  After the wait and the barrier, tile t+1 has landed everywhere (the 8
+    // loads of tile t+2 may still be in flight) and tile t-1 is dead everywhere: its last
+    // fragments were requested in the previous block and have arrived (lgkmcnt), so the fetch
+    // of tile t+3 may overwrite its stage.
     auto tile_sync = [&](int t) __attribute__((always_inline)) {
-        if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-        else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
+        else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         if (t + 3 < ntiles) issue_tile(t + 3);
     };
     auto tile_body = [&](int t, bool masked, bool first) __attribute__((always_inline)) {
         // even stage c = 2t: PV(c-1) = second half of tile t-1, S(c+1) = second half of tile t
-        stage_block(0, t * AW_BN, masked, !first, t - 1, 1, t, 1);
-        tile_sync(t);
+        stage_block(0, t, masked, !first);
         // odd stage c = 2t+1: PV(c-1) = first half of tile t, S(c+1) = first half of tile t+1
-        stage_block(1, t * AW_BN + 32, masked, true, t, 0, t + 1, 0);
+        stage_block(1, t, masked, true);
     };
 
     issue_tile(0);
     if (ntiles > 1) issue_tile(1);
     if (ntiles > 2) issue_tile(2);
-    // tile 0 (the oldest 8 loads, after the Q fragments) must have landed; younger tiles may fly
-    if (ntiles > 2) asm volatile("s_waitcnt vmcnt(16)" ::: "memory");
-    else if (ntiles > 1) asm volatile("s_waitcnt vmcnt(8)" ::: "memory");
-    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
+    tile_sync(0);                    // also covers the Q fragments, which were requested first
 
-    int t = 0;
+    int t = 1;
     if (my_tiles > 0) {
         scores_only(0, 0, 0);
+        load_k_frags(0, 0, 1);                                          // for S(1) in the first block
+        t = 0;
         if (full_tiles > 0) {
             tile_body(0, false, true);
-            for (t = 1; t < full_tiles; ++t) tile_body(t, false, false);
+            for (t = 1; t < full_tiles; ++t) {
+                tile_sync(t);
+                tile_body(t, false, false);
+            }
         }
-        for (; t < my_tiles; ++t) tile_body(t, true, t == 0);
-        values_only(1, my_tiles - 1, 1);                               // drain: PV of the last stage
+        for (; t < my_tiles; ++t) {
+            if (t > 0) tile_sync(t);
+            tile_body(t, true, t == 0);
+        }
+        values_only(1, 0);                                              // drain: PV of the last stage
     }
     for (; t < ntiles; ++t) tile_sync(t);                              // keep feeding the other wavefronts
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
