@@ -265,6 +265,59 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+// Vector work of the softmax of one 32-key stage (both query blocks), as a list of single
+// instructions in issue order.  The pipeline block below cuts the list into 32 runs and puts
+// one run behind each of its 32 MFMAs, with scheduling barriers in between, so that the
+// matrix pipe and the vector pipe stay busy together; the order keeps every instruction a
+// few issue slots away from the producer of its operands.
+//   kinds: MAX5 five 3-input maxima of the 16 scores; MAX3 their reduction to one; SWAP exchange
+//   between the two wavefront halves (they hold different keys of the same query); REF0..REF6
+//   new reference maximum and alpha = exp2(old - new); FMA argument of an exponential; EXP;
+//   ADD2 sum of two neighbours; CVT pack two probabilities to bf16; TREE reduction of the
+//   eight pair sums and update of the running denominator.
+enum SmKind : int { SM_MAX5, SM_MAX3, SM_SWAP, SM_REF, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
+struct SmOp {
+    int kind, u, i;
+};
+constexpr int SM_NOPS = 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 8);
+struct SmTable {
+    SmOp op[SM_NOPS];
+    int start[33];       // run r is op[start[r]] .. op[start[r+1]-1]
+};
+constexpr SmTable make_sm_table() {
+    SmTable t{};
+    int n = 0;
+    // part 1, the two query blocks interleaved
+    for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 0, i};
+    for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 1, i};
+    for (int i = 0; i < 3; ++i) { t.op[n++] = {SM_MAX3, 0, i}; t.op[n++] = {SM_MAX3, 1, i}; }
+    t.op[n++] = {SM_SWAP, 0, 0};
+    t.op[n++] = {SM_SWAP, 1, 0};
+    for (int i = 0; i < 7; ++i) { t.op[n++] = {SM_REF, 0, i}; t.op[n++] = {SM_REF, 1, i}; }
+    // part 2 in groups of four scores (group g: query block g / 4, scores 4 (g % 4) ..+3),
+    // software pipelined: arguments of group ph, exponentials of group ph-1, sums and packing
+    // of group ph-2; the tree of a query block follows two phases after its last pair sums
+    for (int ph = 0; ph < 13; ++ph) {
+        if (ph < 8)
+            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_FMA, ph / 4, 4 * (ph % 4) + i};
+        if (ph >= 1 && ph < 9)
+            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_EXP, (ph - 1) / 4, 4 * ((ph - 1) % 4) + i};
+        if (ph >= 2 && ph < 10) {
+            const int g = ph - 2;
+            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_ADD2, g / 4, 2 * (g % 4) + i};
+            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_CVT, g / 4, 2 * (g % 4) + i};
+        }
+        if (ph == 7 || ph == 8)                     // query block 0: pair sums done in phase 5
+            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_TREE, 0, 4 * (ph - 7) + i};
+        if (ph == 11 || ph == 12)                   // query block 1: pair sums done in phase 9
+            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_TREE, 1, 4 * (ph - 11) + i};
+    }
+    // even split over the 32 runs
+    for (int r = 0; r <= 32; ++r) t.start[r] = (int)((long)r * n / 32);
+    return t;
+}
+constexpr SmTable SM_TABLE = make_sm_table();
+
 template <bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
@@ -403,16 +456,6 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         for (int dc = 0; dc < 8; ++dc)
             kfr[set][dc] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
     };
-    auto load_v_frags = [&](int set, int t, int kt) __attribute__((always_inline)) {
-        unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
-        asm("" : "+v"(Vs));
-#pragma unroll
-        for (int n = 0; n < 8; ++n) {
-            const int off = (n >> 2) * 256 + (n & 3) * 64;
-            vlo[set][n] = lds_read_tr16(Vs + off);                             // keys of slots 0..3
-            vhi[set][n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);               // keys of slots 4..7
-        }
-    };
 
     auto scores_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // prologue: S of the first stage
         const unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
@@ -448,14 +491,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         // the LDS counter alone) spares the block partial waits: with its own 24 requests queued
         // behind them the 4-bit counter could not express "only the older ones".
         __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0), other counters untouched
-        load_k_frags(par ^ 1, t + 1, par);
-        load_v_frags(par ^ 1, t, par);
-        // softmax(c), part 1: stage maximum per query; the reference maximum of a query moves
-        // only when it is exceeded by more than the gap, and alpha = exp2(old - new) (1 if kept)
-        float alpha[2];
+        unsigned Ks = k_lane + ((t + 1) % AW_STAGES) * AW_STAGE + par * 512;
+        unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + par * 512;
+        asm("" : "+v"(Ks));          // keep base + constant addressing
+        asm("" : "+v"(Vs));
+        if (masked) {
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            if (masked) {
+            for (int u = 0; u < 2; ++u) {
                 const int query = wq0 + 32 * u + l32;
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
@@ -463,83 +505,98 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                     if (key >= N || (CAUSAL && key > query)) s[par][u][r] = -INFINITY;
                 }
             }
-            // (reductions are written as trees: a dependent vector instruction waits about
-            // twice as long as an independent one)
-            const f32x16& sv = s[par][u];
-            const float m0 = fmaxf(fmaxf(sv[0], sv[1]), sv[2]), m1 = fmaxf(fmaxf(sv[3], sv[4]), sv[5]);
-            const float m2 = fmaxf(fmaxf(sv[6], sv[7]), sv[8]), m3 = fmaxf(fmaxf(sv[9], sv[10]), sv[11]);
-            const float m4 = fmaxf(fmaxf(sv[12], sv[13]), sv[14]);
-            float mx = fmaxf(fmaxf(fmaxf(m0, m1), fmaxf(m2, m3)), fmaxf(m4, sv[15]));
-            const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-            mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));       // both halves of the wavefront
-            const float m_new = fmaxf(m_ref[u], mx * scale_log2e);
-            const float m_use = (m_new > m_ref[u] + AW_RESCALE_GAP) ? m_new : m_ref[u];
-            alpha[u] = __builtin_amdgcn_exp2f(m_ref[u] - m_use);               // exp2(-inf) = 0 at the start
-            m_ref[u] = m_use;
         }
+        // state of the vector work (see SmKind)
+        float m5[2][5], m3[2][3], mx[2], ref[2][4], alpha[2] = {1.f, 1.f};
+        float e[2][16], p2[2][8], tr[2][7];
+        uint32_t pk[2][8];
+        auto vector_op = [&](auto kc, auto uc, auto ic) __attribute__((always_inline)) {
+            constexpr int kind = kc.value, u = uc.value, i = ic.value;
+            const f32x16& sv = s[par][u];
+            if constexpr (kind == SM_MAX5) {
+                m5[u][i] = fmaxf(fmaxf(sv[3 * i], sv[3 * i + 1]), sv[3 * i + 2]);
+            } else if constexpr (kind == SM_MAX3) {
+                if constexpr (i == 0) m3[u][0] = fmaxf(fmaxf(m5[u][0], m5[u][1]), m5[u][2]);
+                if constexpr (i == 1) m3[u][1] = fmaxf(fmaxf(m5[u][3], m5[u][4]), sv[15]);
+                if constexpr (i == 2) m3[u][2] = fmaxf(m3[u][0], m3[u][1]);
+            } else if constexpr (kind == SM_SWAP) {
+                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(m3[u][2]),
+                                                                 __float_as_uint(m3[u][2]), false, false);
+                mx[u] = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+            } else if constexpr (kind == SM_REF) {
+                // the reference maximum of a query moves only when it is exceeded by more than
+                // the gap; alpha = exp2(old - new) (1 if kept; exp2(-inf) = 0 at the start)
+                if constexpr (i == 0) ref[u][0] = mx[u] * scale_log2e;
+                if constexpr (i == 1) ref[u][1] = fmaxf(m_ref[u], ref[u][0]);
+                if constexpr (i == 2) ref[u][2] = m_ref[u] + AW_RESCALE_GAP;
+                if constexpr (i == 3) ref[u][3] = (ref[u][1] > ref[u][2]) ? ref[u][1] : m_ref[u];
+                if constexpr (i == 4) ref[u][0] = m_ref[u] - ref[u][3];
+                if constexpr (i == 5) alpha[u] = __builtin_amdgcn_exp2f(ref[u][0]);
+                if constexpr (i == 6) m_ref[u] = ref[u][3];
+            } else if constexpr (kind == SM_FMA) {
+                e[u][i] = fmaf(sv[i], scale_log2e, -m_ref[u]);
+            } else if constexpr (kind == SM_EXP) {
+                e[u][i] = __builtin_amdgcn_exp2f(e[u][i]);
+            } else if constexpr (kind == SM_ADD2) {
+                p2[u][i] = e[u][2 * i] + e[u][2 * i + 1];
+            } else if constexpr (kind == SM_CVT) {
+                pk[u][i] = pack_bf16(e[u][2 * i], e[u][2 * i + 1]);
+            } else {
+                if constexpr (i < 4) tr[u][i] = p2[u][2 * i] + p2[u][2 * i + 1];
+                if constexpr (i == 4) tr[u][4] = tr[u][0] + tr[u][1];
+                if constexpr (i == 5) tr[u][5] = tr[u][2] + tr[u][3];
+                if constexpr (i == 6) tr[u][6] = tr[u][4] + tr[u][5];
+                if constexpr (i == 7) l_run[u] = fmaf(l_run[u], alpha[u], tr[u][6]);
+            }
+        };
         // S(c+1) accumulators
 #pragma unroll
         for (int u = 0; u < 2; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[par ^ 1][u][r] = 0.f;
-        // the two MFMA streams, interleaved
-        static_for<0, 8>([&](auto n) {
-            constexpr int dc = n.value;
-            s[par ^ 1][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[0][dc], s[par ^ 1][0], 0, 0, 0);
-            s[par ^ 1][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[1][dc], s[par ^ 1][1], 0, 0, 0);
-            if (has_prev) {
-                constexpr int tt = n.value >> 2, db = n.value & 3;
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 both = __builtin_shufflevector(vlo[par][n.value], vhi[par][n.value], 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 va = __builtin_bit_cast(bf16x8, both);
-                o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][0][tt], o[0][db], 0, 0, 0);
-                o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[par ^ 1][1][tt], o[1][db], 0, 0, 0);
+        // 32 slots: one MFMA (the 16 of S(c+1) first, so that they are complete when the next
+        // block reads them, then the 16 of PV(c-1)), one fragment request, one run of vector work
+        static_for<0, 32>([&](auto slot) {
+            constexpr int i = slot.value;
+            if constexpr (i < 16) {
+                constexpr int dc = i >> 1, u = i & 1;
+                s[par ^ 1][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[u][dc], s[par ^ 1][u], 0, 0, 0);
+            } else {
+                if (has_prev) {
+                    constexpr int n = (i - 16) >> 1, u = i & 1, tt = n >> 2, db = n & 3;
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    const s16x8 both = __builtin_shufflevector(vlo[par][n], vhi[par][n], 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[u][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both),
+                                                                       pf[par ^ 1][u][tt], o[u][db], 0, 0, 0);
+                }
             }
+            if constexpr (i < 8) {
+                kfr[par ^ 1][i] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + i * 32);
+            } else if constexpr (i < 24) {
+                constexpr int n = (i - 8) >> 1, off = (n >> 2) * 256 + (n & 3) * 64;
+                if constexpr ((i & 1) == 0) vlo[par ^ 1][n] = lds_read_tr16(Vs + off);                 // keys of slots 0..3
+                else vhi[par ^ 1][n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);                          // keys of slots 4..7
+            }
+            static_for<SM_TABLE.start[i], SM_TABLE.start[i + 1]>([&](auto k) {
+                constexpr SmOp op = SM_TABLE.op[k.value];
+                vector_op(std::integral_constant<int, op.kind>{}, std::integral_constant<int, op.u>{},
+                          std::integral_constant<int, op.i>{});
+            });
+            __builtin_amdgcn_sched_barrier(0);
         });
-        // softmax(c), part 2: probabilities relative to the reference maximum, row sums, bf16
-        // packing.  All arguments first, then all exponentials, then tree sums: no instruction
-        // waits on its immediate predecessor.
-        float e[2][16];
+        // the probabilities are consumed in the next block; without this pin the compiler sinks
+        // their computation past the end of this block, away from the MFMAs it must hide behind
+        asm volatile("" ::"v"(pk[0][0]), "v"(pk[0][1]), "v"(pk[0][2]), "v"(pk[0][3]), "v"(pk[0][4]), "v"(pk[0][5]),
+                     "v"(pk[0][6]), "v"(pk[0][7]), "v"(pk[1][0]), "v"(pk[1][1]), "v"(pk[1][2]), "v"(pk[1][3]),
+                     "v"(pk[1][4]), "v"(pk[1][5]), "v"(pk[1][6]), "v"(pk[1][7]), "v"(l_run[0]), "v"(l_run[1]));
 #pragma unroll
         for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) e[u][i] = fmaf(s[par][u][i], scale_log2e, -m_ref[u]);
-#pragma unroll
-        for (int u = 0; u < 2; ++u)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) e[u][i] = __builtin_amdgcn_exp2f(e[u][i]);
-#pragma unroll
-        for (int u = 0; u < 2; ++u) {
-            float p[8];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) p[i] = e[u][2 * i] + e[u][2 * i + 1];
-            const float psum = ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
-                u32x4 pk;
-                pk.x = pack_bf16(e[u][8 * tt + 0], e[u][8 * tt + 1]);
-                pk.y = pack_bf16(e[u][8 * tt + 2], e[u][8 * tt + 3]);
-                pk.z = pack_bf16(e[u][8 * tt + 4], e[u][8 * tt + 5]);
-                pk.w = pack_bf16(e[u][8 * tt + 6], e[u][8 * tt + 7]);
-                pf[par][u][tt] = __builtin_bit_cast(bf16x8, pk);
+                u32x4 w;
+                w.x = pk[u][4 * tt]; w.y = pk[u][4 * tt + 1]; w.z = pk[u][4 * tt + 2]; w.w = pk[u][4 * tt + 3];
+                pf[par][u][tt] = __builtin_bit_cast(bf16x8, w);
             }
-            l_run[u] = fmaf(l_run[u], alpha[u], psum);
-        }
-        // the probabilities are consumed in the next block; without this pin the compiler sinks
-        // the whole exponential part past the end of this block, away from the MFMAs it must hide
-        asm volatile("" ::"v"(pf[par][0][0]), "v"(pf[par][0][1]), "v"(pf[par][1][0]), "v"(pf[par][1][1]),
-                     "v"(l_run[0]), "v"(l_run[1]));
-        // scheduling hints for this block: after every MFMA one LDS read (while there are any)
-        // and a share of the vector work
-        if (has_prev) {
-            __builtin_amdgcn_sched_group_barrier(0x100, 24, 0);      // all LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x002, 16, 0);      // start of the stage maximum while they fly
-#pragma unroll
-            for (int i = 0; i < 32; ++i) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
-            }
-        }
         // rare: some query moved its reference.  PV(c-1) above still belongs to the old one and
         // has been issued; PV(c) comes in the next block.
         if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
