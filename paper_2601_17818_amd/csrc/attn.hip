@@ -270,23 +270,26 @@ __device__ __forceinline__ void static_for(F&& f) {
 // one run behind each of its 32 MFMAs, with scheduling barriers in between, so that the
 // matrix pipe and the vector pipe stay busy together; the order keeps every instruction a
 // few issue slots away from the producer of its operands.
-//   kinds: MAX5 five 3-input maxima of the 16 scores; MAX3 their reduction to one; SWAP exchange
+//   kinds: MASK (diagonal and ragged tiles only) score := -inf where the key is not visible;
+//   MAX5 five 3-input maxima of the 16 scores; MAX3 their reduction to one; SWAP exchange
 //   between the two wavefront halves (they hold different keys of the same query); REF0..REF6
 //   new reference maximum and alpha = exp2(old - new); FMA argument of an exponential; EXP;
 //   ADD2 sum of two neighbours; CVT pack two probabilities to bf16; TREE reduction of the
 //   eight pair sums and update of the running denominator.
-enum SmKind : int { SM_MAX5, SM_MAX3, SM_SWAP, SM_REF, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
+enum SmKind : int { SM_MASK, SM_MAX5, SM_MAX3, SM_SWAP, SM_REF, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
 struct SmOp {
     int kind, u, i;
 };
-constexpr int SM_NOPS = 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 8);
+constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 8);
 struct SmTable {
     SmOp op[SM_NOPS];
     int start[33];       // run r is op[start[r]] .. op[start[r+1]-1]
 };
-constexpr SmTable make_sm_table() {
+constexpr SmTable make_sm_table(bool masked) {
     SmTable t{};
     int n = 0;
+    if (masked)
+        for (int i = 0; i < 16; ++i) { t.op[n++] = {SM_MASK, 0, i}; t.op[n++] = {SM_MASK, 1, i}; }
     // part 1, the two query blocks interleaved
     for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 0, i};
     for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 1, i};
@@ -312,11 +315,21 @@ constexpr SmTable make_sm_table() {
         if (ph == 11 || ph == 12)                   // query block 1: pair sums done in phase 9
             for (int i = 0; i < 4; ++i) t.op[n++] = {SM_TREE, 1, 4 * (ph - 11) + i};
     }
-    // even split over the 32 runs
-    for (int r = 0; r <= 32; ++r) t.start[r] = (int)((long)r * n / 32);
+    // split into 32 runs of about equal issue time (a mask is a compare and a select, an
+    // exponential takes twice as long as a plain instruction)
+    int total = 0;
+    for (int k = 0; k < n; ++k) total += (t.op[k].kind == SM_MASK || t.op[k].kind == SM_EXP) ? 2 : 1;
+    int acc = 0, r = 0;
+    t.start[0] = 0;
+    for (int k = 0; k < n; ++k) {
+        acc += (t.op[k].kind == SM_MASK || t.op[k].kind == SM_EXP) ? 2 : 1;
+        while (r < 31 && acc * 32 >= total * (r + 1)) t.start[++r] = k + 1;
+    }
+    while (r < 32) t.start[++r] = n;
     return t;
 }
-constexpr SmTable SM_TABLE = make_sm_table();
+constexpr SmTable SM_TABLE_PLAIN = make_sm_table(false);
+constexpr SmTable SM_TABLE_MASKED = make_sm_table(true);
 
 template <bool CAUSAL>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
@@ -349,14 +362,16 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     }
     const int h = hb % Hq, b = hb / Hq;
     const int hk = h / (Hq / Hkv);
-    const int q0 = qb * AW_BM, wq0 = q0 + 64 * wv;
+    // Query blocks are aligned to the END of the sequence: a ragged block is then the first one,
+    // which has the fewest keys to waste wavefronts on (query indices below 0 do not exist).
+    const int q0 = N - (n_qb - qb) * AW_BM, wq0 = q0 + 64 * wv;
     const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
 
     // Q^T fragments of the two query blocks
     bf16x8 qf[2][8];
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-        const int query = min(wq0 + 32 * u + l32, N - 1);
+        const int query = max(wq0 + 32 * u + l32, 0);
         const uint16_t* qp = q + ((int64_t)b * N + query) * q_rs + h * AT_D + 8 * g;
 #pragma unroll
         for (int dc = 0; dc < 8; ++dc) qf[u][dc] = *reinterpret_cast<const bf16x8*>(qp + 16 * dc);
@@ -381,10 +396,10 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 
     const int kend = CAUSAL ? min(N, q0 + AW_BM) : N;
     const int ntiles = (kend + AW_BN - 1) / AW_BN;                 // tiles the workgroup streams
-    const int wave_kend = CAUSAL ? min(N, wq0 + 64) : N;           // keys this wavefront needs
-    const int my_tiles = wq0 < N ? (wave_kend + AW_BN - 1) / AW_BN : 0;
+    const int wave_kend = CAUSAL ? wq0 + 64 : N;                   // keys this wavefront needs
+    const int my_tiles = wq0 + 64 > 0 ? (wave_kend + AW_BN - 1) / AW_BN : 0;
     // tiles whose 64 keys are visible to all 64 queries and lie inside the sequence: no masking
-    const int full_tiles = min(CAUSAL ? wq0 / AW_BN : N / AW_BN, min(N / AW_BN, my_tiles));
+    const int full_tiles = min(CAUSAL ? max(wq0, 0) / AW_BN : N / AW_BN, min(N / AW_BN, my_tiles));
     const char* kbase = reinterpret_cast<const char*>(k + (int64_t)b * N * kv_rs + hk * AT_D);
     const char* vbase = reinterpret_cast<const char*>(v + (int64_t)b * N * kv_rs + hk * AT_D);
 
@@ -485,7 +500,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // PV(c-1) with pf[par^1] and S(c+1) -> s[par^1], both from fragment set `par`, which the
     // previous block requested; this block requests set par^1 for the next one: the K rows of
     // stage c+2 = (tile t+1, half par) and the V rows of stage c = (tile t, half par).
-    auto stage_block = [&](int par, int t, bool masked, bool has_prev) __attribute__((always_inline)) {
+    auto stage_block = [&](int par, int t, auto masked_c, bool has_prev) __attribute__((always_inline)) {
+        constexpr bool MASKED = decltype(masked_c)::value;
+        constexpr const SmTable& SM_TABLE = MASKED ? SM_TABLE_MASKED : SM_TABLE_PLAIN;
         const int key0 = t * AW_BN + 32 * par;
         // The fragments requested a whole block ago have long arrived; saying so here (a wait on
         // the LDS counter alone) spares the block partial waits: with its own 24 requests queued
@@ -495,15 +512,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         unsigned Vs = v_lane + (t % AW_STAGES) * AW_STAGE + par * 512;
         asm("" : "+v"(Ks));          // keep base + constant addressing
         asm("" : "+v"(Vs));
-        if (masked) {
+        // diagonal and ragged tiles: key key0 + 4g + 8(r/4) + r%4 of register r is visible to
+        // the lane's query iff it is <= min(query, N-1), i.e. iff 8(r/4) + r%4 <= lim
+        int lim[2] = {0, 0};
+        if constexpr (MASKED) {
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
-                const int query = wq0 + 32 * u + l32;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int key = key0 + 4 * g + 8 * (r >> 2) + (r & 3);
-                    if (key >= N || (CAUSAL && key > query)) s[par][u][r] = -INFINITY;
-                }
+                const int query = max(wq0 + 32 * u + l32, 0);      // rows below 0 are never stored
+                lim[u] = (CAUSAL ? min(query, N - 1) : N - 1) - key0 - 4 * g;
             }
         }
         // state of the vector work (see SmKind)
@@ -513,7 +529,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         auto vector_op = [&](auto kc, auto uc, auto ic) __attribute__((always_inline)) {
             constexpr int kind = kc.value, u = uc.value, i = ic.value;
             const f32x16& sv = s[par][u];
-            if constexpr (kind == SM_MAX5) {
+            if constexpr (kind == SM_MASK) {
+                if (8 * (i >> 2) + (i & 3) > lim[u]) s[par][u][i] = -INFINITY;
+            } else if constexpr (kind == SM_MAX5) {
                 m5[u][i] = fmaxf(fmaxf(sv[3 * i], sv[3 * i + 1]), sv[3 * i + 2]);
             } else if constexpr (kind == SM_MAX3) {
                 if constexpr (i == 0) m3[u][0] = fmaxf(fmaxf(m5[u][0], m5[u][1]), m5[u][2]);
@@ -619,11 +637,11 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         asm volatile("" ::: "memory");
         if (t + 3 < ntiles) issue_tile(t + 3);
     };
-    auto tile_body = [&](int t, bool masked, bool first) __attribute__((always_inline)) {
+    auto tile_body = [&](int t, auto masked_c, bool first) __attribute__((always_inline)) {
         // even stage c = 2t: PV(c-1) = second half of tile t-1, S(c+1) = second half of tile t
-        stage_block(0, t, masked, !first);
+        stage_block(0, t, masked_c, !first);
         // odd stage c = 2t+1: PV(c-1) = first half of tile t, S(c+1) = first half of tile t+1
-        stage_block(1, t, masked, true);
+        stage_block(1, t, masked_c, true);
     };
 
     issue_tile(0);
@@ -637,15 +655,15 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         load_k_frags(0, 0, 1);                                          // for S(1) in the first block
         t = 0;
         if (full_tiles > 0) {
-            tile_body(0, false, true);
+            tile_body(0, std::false_type{}, true);
             for (t = 1; t < full_tiles; ++t) {
                 tile_sync(t);
-                tile_body(t, false, false);
+                tile_body(t, std::false_type{}, false);
             }
         }
         for (; t < my_tiles; ++t) {
             if (t > 0) tile_sync(t);
-            tile_body(t, true, t == 0);
+            tile_body(t, std::true_type{}, t == 0);
         }
         values_only(1, 0);                                              // drain: PV of the last stage
     }
@@ -654,9 +672,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
 
 #pragma unroll
     for (int u = 0; u < 2; ++u) {
-        const int query = wq0 + 32 * u + l32;
+        const int query = wq0 + 32 * u + l32;                          // < N by construction
         const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
-        if (query < N) {
+        if (query >= 0) {
             const float inv = 1.0f / l_tot;
             uint16_t* op = out + ((int64_t)b * N + query) * q_rs + h * AT_D;
 #pragma unroll
