@@ -25,8 +25,14 @@ constexpr int GM_SLABS = 4;          // ring of k-slabs in LDS: three k-steps of
 constexpr int GM_PART = 128;         // columns per sum-of-squares partial
 constexpr int GM_XCDS = 8;
 
-template <int BM, int BN, int BK>
-constexpr size_t gemm_lds_bytes() { return (size_t)GM_SLABS * (BM + BN) * BK * 2; }
+// LDS: the slab ring, reused by the epilogue as one staging region per wavefront of
+// (BM / WAVES_M) rows of (BN / WAVES_N) bf16 + 16 bytes of padding.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
+constexpr size_t gemm_lds_bytes() {
+    constexpr size_t ring = (size_t)GM_SLABS * (BM + BN) * BK * 2;
+    constexpr size_t stage = (size_t)4 * (BM / WAVES_M) * ((BN / WAVES_N) * 2 + 16);
+    return ring > stage ? ring : stage;
+}
 
 // A slab row holds BK bf16 (64 or 128 bytes, unpadded because direct loads write 1 KiB runs).
 // 16-byte chunk c of row r lives at chunk position c ^ swz(r), which makes the MFMA fragment
@@ -220,47 +226,66 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no load may outlive the workgroup's LDS
 #undef VITCOP_INTERLEAVE
 
-    // epilogue: lane owns row m = .. + l32 and columns n = .. + 8*(r/4) + 4*g + r%4
+    // Epilogue.  In the accumulators a lane owns row m = .. + l32 and 4-element runs of columns
+    // n = .. + 8*(r/4) + 4*g + r%4: stored directly, every store instruction would touch 32
+    // rows with 16 bytes each, and the L2 request rate of all CUs finishing a round together
+    // becomes the bottleneck.  So the rounded tile goes through LDS (the slab ring is free now):
+    // each wavefront stages its own TM x TN block, rows padded by 16 bytes, and writes it out
+    // with 16 bytes per lane, consecutive lanes along a row.  The residual is added and the
+    // norm partial is formed on the way in, in the accumulator layout.
+    constexpr int STAGE_ROW = TN * 2 + 16;                // bytes; the pad spreads the rows over the banks
+    __builtin_amdgcn_s_barrier();                         // every wavefront is done reading the slabs
+    char* stage = gemm_lds + wv * (TM * STAGE_ROW);
 #pragma unroll
     for (int j = 0; j < MI; ++j) {
         const int m = m0 + wm * TM + j * 32 + l32;
         float ss = 0.f;
-        if (m < M) {
 #pragma unroll
-            for (int i = 0; i < NI; ++i)
+        for (int i = 0; i < NI; ++i)
 #pragma unroll
-                for (int r4 = 0; r4 < 4; ++r4) {
-                    const int n = n0 + wn * TN + i * 32 + 8 * r4 + 4 * g;
-                    if (n < N) {                     // N % 4 == 0: the run of 4 is all in or all out
-                        float c0 = acc[i][j][4 * r4], c1 = acc[i][j][4 * r4 + 1];
-                        float c2 = acc[i][j][4 * r4 + 2], c3 = acc[i][j][4 * r4 + 3];
-                        if (res) {
-                            const uint2 rr = *reinterpret_cast<const uint2*>(res + (int64_t)m * res_stride + n);
-                            c0 += bf16_lo(rr.x); c1 += bf16_hi(rr.x);
-                            c2 += bf16_lo(rr.y); c3 += bf16_hi(rr.y);
-                        }
-                        uint2 pk;
-                        pk.x = pack_bf16(c0, c1);
-                        pk.y = pack_bf16(c2, c3);
-                        *reinterpret_cast<uint2*>(y + (int64_t)m * y_stride + n) = pk;
-                        if constexpr (TN == GM_PART) {
-                            if (sumsq_parts) {
-                                float a;
-                                a = bf16_lo(pk.x); ss = fmaf(a, a, ss);
-                                a = bf16_hi(pk.x); ss = fmaf(a, a, ss);
-                                a = bf16_lo(pk.y); ss = fmaf(a, a, ss);
-                                a = bf16_hi(pk.y); ss = fmaf(a, a, ss);
-                            }
-                        }
+            for (int r4 = 0; r4 < 4; ++r4) {
+                const int n = n0 + wn * TN + i * 32 + 8 * r4 + 4 * g;
+                float c0 = acc[i][j][4 * r4], c1 = acc[i][j][4 * r4 + 1];
+                float c2 = acc[i][j][4 * r4 + 2], c3 = acc[i][j][4 * r4 + 3];
+                if (res) {
+                    if (m < M && n < N) {            // N % 4 == 0: the run of 4 is all in or all out
+                        const uint2 rr = *reinterpret_cast<const uint2*>(res + (int64_t)m * res_stride + n);
+                        c0 += bf16_lo(rr.x); c1 += bf16_hi(rr.x);
+                        c2 += bf16_lo(rr.y); c3 += bf16_hi(rr.y);
                     }
                 }
-        }
+                uint2 pk;
+                pk.x = pack_bf16(c0, c1);
+                pk.y = pack_bf16(c2, c3);
+                *reinterpret_cast<uint2*>(stage + (j * 32 + l32) * STAGE_ROW + (i * 32 + 8 * r4 + 4 * g) * 2) = pk;
+                if constexpr (TN == GM_PART) {
+                    if (sumsq_parts && n < N) {      // squares of the ROUNDED outputs, two per instruction
+                        const bf16x2 lo = __builtin_bit_cast(bf16x2, pk.x), hi = __builtin_bit_cast(bf16x2, pk.y);
+                        ss = __builtin_amdgcn_fdot2_f32_bf16(lo, lo, ss, false);
+                        ss = __builtin_amdgcn_fdot2_f32_bf16(hi, hi, ss, false);
+                    }
+                }
+            }
         if constexpr (TN == GM_PART) {           // one partial per wavefront; other layouts never get sumsq_parts
             if (sumsq_parts) {
                 ss += __shfl_xor(ss, 32, 64);
                 const int part = (n0 + wn * TN) / GM_PART;
                 if (g == 0 && m < M && n0 + wn * TN < N) sumsq_parts[(int64_t)part * M + m] = ss;
             }
+        }
+    }
+    // (a wavefront reads back only what it wrote itself: no barrier, the LDS counter suffices)
+    constexpr int LANES_PER_ROW = TN / 8;                 // 16-byte chunks per staged row
+    constexpr int ROWS_PER_STORE = 64 / LANES_PER_ROW;
+    const int srow = lane / LANES_PER_ROW, schunk = lane % LANES_PER_ROW;
+    const int n = n0 + wn * TN + schunk * 8;
+    if (n < N) {                                          // N % 8 == 0: the chunk is all in or all out
+#pragma unroll
+        for (int r0 = 0; r0 < TM; r0 += ROWS_PER_STORE) {
+            const int row = r0 + srow;
+            const int m = m0 + wm * TM + row;
+            const u32x4 val = *reinterpret_cast<const u32x4*>(stage + row * STAGE_ROW + schunk * 16);
+            if (m < M) *reinterpret_cast<u32x4*>(y + (int64_t)m * y_stride + n) = val;
         }
     }
 }
@@ -273,7 +298,7 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
                            int K, float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split,
                            hipStream_t s) {
     auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK>;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, BK>();
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK>();
     static bool attr_set = false;        // per kernel instantiation; setting it twice is harmless
     if (!attr_set) {
         int rc = hip_status(hipFuncSetAttribute((const void*)kern,
