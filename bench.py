@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
 # HBM-side bytes per launch of the K-projection GEMM at the bench shape, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy: profiles/gemm_kproj_config3_hbm_traffic.txt
-KPROJ_MEASURED_TRAFFIC_BYTES = 819.8e6
+KPROJ_MEASURED_TRAFFIC_BYTES = 790.1e6
 
 
 def parse():
@@ -183,14 +183,19 @@ def main():
         f_bytes = 5 * B * (577 * 1024 * 2 + f_keep * 4)
         kern["filter_ms"] = t_f
         kern["filter_GBps"] = f_bytes / (t_f * 1e-3) / 1e9
-        # attention: pruned shape and the unpruned shape
-        for name, n_att in (("attn_pruned", Tp), ("attn_unpruned", T)):
-            qq = torch.randn((B, n_att, Hq, d), dtype=torch.bfloat16, device="cuda")
-            kk = torch.randn((B, n_att, Hkv, d), dtype=torch.bfloat16, device="cuda")
-            vv = torch.randn((B, n_att, Hkv, d), dtype=torch.bfloat16, device="cuda")
+        # attention (causal-useful FLOPs): the pruned and the unpruned shape of this layer, the same
+        # unpruned shape with the batch raised to 24 workgroups per CU, and the video shape
+        # (28 query heads on 4 KV heads) unpruned and at its pruned length
+        for name, b_att, n_att, hq_att, hkv_att in (
+                ("attn_pruned", B, Tp, Hq, Hkv), ("attn_unpruned", B, T, Hq, Hkv),
+                ("attn_unpruned_batch16", 16, T, Hq, Hkv), ("attn_video_unpruned", 1, 6400, 28, 4),
+                ("attn_video_pruned", 1, 755, 28, 4)):
+            qq = torch.randn((b_att, n_att, hq_att, d), dtype=torch.bfloat16, device="cuda")
+            kk = torch.randn((b_att, n_att, hkv_att, d), dtype=torch.bfloat16, device="cuda")
+            vv = torch.randn((b_att, n_att, hkv_att, d), dtype=torch.bfloat16, device="cuda")
             oo = torch.empty_like(qq)
-            t_a = ev_time(lambda: vc.vitcop_prefill_attn(qq, kk, vv, out=oo), max(3, reps // 3))
-            fl = 4.0 * d * Hq * B * n_att * (n_att + 1) / 2
+            t_a = ev_time(lambda: vc.vitcop_prefill_attn(qq, kk, vv, out=oo), 20, warm=10)
+            fl = 4.0 * d * hq_att * b_att * n_att * (n_att + 1) / 2
             kern[name + "_ms"] = t_a
             kern[name + "_TFLOPs"] = fl / (t_a * 1e-3) / 1e12
             kern[name + "_frac_mfma"] = kern[name + "_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
@@ -206,6 +211,7 @@ def main():
         out["knorm_select_GBps"] = kern["knorm_select_stream_GBps"]
         out["attn_bf16_TFLOPs"] = kern["attn_unpruned_TFLOPs"]
         out["attn_frac_of_peak"] = kern["attn_unpruned_frac_mfma"]
+        out["attn_bf16_TFLOPs_batch16"] = kern["attn_unpruned_batch16_TFLOPs"]
         out["kernels"] = kern
 
     # -------------------------------------- step-wise schedule (config 2, 32 layers)
@@ -246,6 +252,19 @@ def main():
         out["cpu_baseline"] = {"value": B * T / t_cpu, "unit": "tokens/s", "cores": int(cores), "kind": "oracle",
                                "sample": f"{n_cpu} full steps of the same workload ({B} samples x {T} tokens, fp64 "
                                          f"pruned layer + filter on {5 * B} tiles), {t_cpu:.2f} s per step"}
+        # the same oracle held to one thread, on one sample of the batch (a quarter of the step)
+        try:
+            from threadpoolctl import threadpool_limits
+            with threadpool_limits(limits=1):
+                t0 = time.perf_counter()
+                O.pruned_layer(c3["x"][:1], c3["wq"], c3["wk"], c3["wv"], c3["wo"], Hq, Hkv, d, vs, nv, args.keep)
+                O.filter_visual(tiles["q_cls"][:5], tiles["k"][:5], f_keep)
+                t_one = time.perf_counter() - t0
+            out["cpu_baseline"]["single_thread"] = {
+                "value": T / t_one, "unit": "tokens/s", "cores": 1,
+                "sample": f"one sample ({T} tokens) + 5 tiles, {t_one:.2f} s"}
+        except ImportError:
+            pass
 
     print(json.dumps(out))
 
