@@ -1,0 +1,157 @@
+"""CPU oracle for Visual Information Clustering (VIC).  TEST INFRASTRUCTURE ONLY.
+
+Plain NumPy float64 on the exact bf16 feature bits, written from Sec. 3.2.1
+(Eq. 2, Eq. 3) and Alg. 2 of arXiv 2601.17818, step by step in the paper's
+order and notation.  It imports only NumPy and shares nothing with the GPU
+library.  Only tests, the smoke check and the bench's CPU leg may import it.
+
+Steps and readings
+------------------
+* ``feature_distances``  D_feat[i,j] = ||f_i - f_j||_2 (Alg. 2, Step 1), from the
+                         differences themselves (no Gram-matrix shortcut).
+* ``spatial_distances``  D_spatial[i,j] = ||p_i - p_j||_2; positions are grid
+                         coordinates normalised to [0,1]^2 (reading: the paper
+                         gives tau = 0.6 without units).
+* ``density``            Eq. 2: rho_i = sum_{j != i} exp(-(D_feat[i,j]/d_c)^2).
+* ``parents``            Eq. 3 / Alg. 2 Step 2: delta_i = min D_feat[i,j] over
+                         j with rho_j > rho_i (strictly) and D_spatial[i,j] <=
+                         tau; N_i = the first j reaching that minimum (strict
+                         "<" in the listing: ties -> lower index); none ->
+                         delta_i = inf, N_i = -1.
+* ``centers``            Step 3: gamma_i = rho_i * delta_i, the ``n_centers``
+                         highest are centres (ties -> lower index).  Readings:
+                         n_centers = ceil(n * alpha) is an argument (alpha is
+                         never given); gamma_i = inf whenever delta_i = inf,
+                         also for rho_i = 0.
+* ``labels``             Step 4: centres get their own label; every other
+                         token, in order of decreasing rho, takes the label of
+                         its parent N_i.  Readings: a token that is not a
+                         centre and has no parent (N_i = -1; the listing would
+                         read L[-1]) becomes the root of its own cluster;
+                         cluster labels are numbered 0..R-1 by the root's token
+                         index (the listing numbers centres by gamma rank;
+                         labels are names of sets, any numbering gives the
+                         same partition).
+
+Comparisons that decide integers (rho_j > rho_i, D <= tau, the minimum, the
+TopK of gamma) are taken on the values handed in: callers that check a GPU
+result pass the GPU's own float32 arrays, so both sides decide on identical
+numbers.
+"""
+from __future__ import annotations
+
+import math
+
+import numpy as np
+
+
+def _bf16_to_f64(bits) -> np.ndarray:
+    b = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return b.view(np.float32).astype(np.float64)
+
+
+def feature_distances(feat_bits) -> np.ndarray:
+    """feat_bits [n, D] bf16 bits -> D_feat [n, n] float64 (Alg. 2, Step 1)."""
+    f = _bf16_to_f64(feat_bits)
+    n = f.shape[0]
+    out = np.zeros((n, n), dtype=np.float64)
+    for i in range(n):
+        diff = f - f[i]
+        out[i] = np.sqrt(np.sum(diff * diff, axis=1))
+    return out
+
+
+def spatial_distances(pos) -> np.ndarray:
+    """pos [n, 2] -> D_spatial [n, n] float64."""
+    p = np.asarray(pos, dtype=np.float64)
+    diff = p[:, None, :] - p[None, :, :]
+    return np.sqrt(np.sum(diff * diff, axis=2))
+
+
+def density(d_feat, d_c: float) -> np.ndarray:
+    """Eq. 2: rho_i = sum over j != i of exp(-(D_feat[i,j] / d_c)^2)."""
+    d = np.asarray(d_feat, dtype=np.float64)
+    n = d.shape[0]
+    rho = np.zeros(n, dtype=np.float64)
+    for i in range(n):
+        acc = 0.0
+        for j in range(n):
+            if j != i:
+                acc += math.exp(-((d[i, j] / d_c) ** 2))
+        rho[i] = acc
+    return rho
+
+
+def parents(d_feat, d_spatial, rho, tau: float):
+    """Eq. 3 / Alg. 2 Step 2.  Returns (delta [n] with inf where no candidate, N [n] int32 with -1)."""
+    n = len(rho)
+    delta = np.full(n, np.inf, dtype=np.float64)
+    parent = np.full(n, -1, dtype=np.int32)
+    for i in range(n):
+        for j in range(n):
+            if rho[j] > rho[i] and d_spatial[i][j] <= tau:
+                if d_feat[i][j] < delta[i]:
+                    delta[i] = d_feat[i][j]
+                    parent[i] = j
+    return delta, parent
+
+
+def importance(rho, delta) -> np.ndarray:
+    """gamma = rho * delta (Step 3), inf wherever delta is inf."""
+    rho = np.asarray(rho, dtype=np.float64)
+    delta = np.asarray(delta, dtype=np.float64)
+    gamma = np.empty_like(rho)
+    for i in range(len(rho)):
+        gamma[i] = np.inf if np.isinf(delta[i]) else rho[i] * delta[i]
+    return gamma
+
+
+def centers(gamma, n_centers: int) -> np.ndarray:
+    """Indices of the n_centers highest gamma, ascending; ties -> lower index."""
+    n = len(gamma)
+    assert 0 <= n_centers <= n
+    order = sorted(range(n), key=lambda i: (-gamma[i], i))      # inf sorts first; stable on index
+    return np.array(sorted(order[:n_centers]), dtype=np.int32)
+
+
+def labels(rho, parent, center_idx):
+    """Step 4.  Returns (L [n] int32 in [0,R), roots [R] int32 ascending)."""
+    n = len(rho)
+    is_center = np.zeros(n, dtype=bool)
+    is_center[np.asarray(center_idx, dtype=np.int64)] = True
+    roots = [i for i in range(n) if is_center[i] or parent[i] < 0]
+    L = np.full(n, -1, dtype=np.int32)
+    for k, i in enumerate(roots):
+        L[i] = k
+    order = sorted(range(n), key=lambda i: (-rho[i], i))          # decreasing density
+    for i in order:
+        if L[i] == -1:
+            assert L[parent[i]] != -1, "a parent is strictly denser, so it was labelled before"
+            L[i] = L[parent[i]]
+    return L, np.array(roots, dtype=np.int32)
+
+
+def vic_cluster(feat_bits, pos, d_c: float, tau: float, n_centers: int):
+    """Alg. 2 end to end for one image.  Returns a dict of every intermediate."""
+    d_feat = feature_distances(feat_bits)
+    d_sp = spatial_distances(pos)
+    rho = density(d_feat, d_c)
+    delta, parent = parents(d_feat, d_sp, rho, tau)
+    gamma = importance(rho, delta)
+    c = centers(gamma, n_centers)
+    L, roots = labels(rho, parent, c)
+    return {"d_feat": d_feat, "d_spatial": d_sp, "rho": rho, "delta": delta, "parent": parent,
+            "gamma": gamma, "centers": c, "labels": L, "roots": roots}
+
+
+def same_partition(a, b) -> bool:
+    """True if two label arrays describe the same partition (labels are names)."""
+    a = np.asarray(a)
+    b = np.asarray(b)
+    if a.shape != b.shape:
+        return False
+    fwd, bwd = {}, {}
+    for x, y in zip(a.tolist(), b.tolist()):
+        if fwd.setdefault(x, y) != y or bwd.setdefault(y, x) != x:
+            return False
+    return True

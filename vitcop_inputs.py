@@ -264,3 +264,25 @@ def k_tensor_lognormal(seed: int, B: int, T: int, Hkv: int, d: int, vis_start: i
     k = _rng(seed, 42).standard_normal((B, T, Hkv * d), dtype=np.float32)
     k[:, vis_start:vis_start + n_vis, :] *= gain[:, :, None]
     return {"k": f32_to_bf16_bits(k.reshape(B, T, Hkv, d)), "gain": gain, "outlier": mask}
+
+
+def vic_inputs(seed: int, n: int, D: int, grid: int = 24, n_regions: int = 12,
+               noise: float = 0.1) -> dict:
+    """Input of Visual Information Clustering (Sec. 3.2.1): the ``n`` patches that survived
+    Stage I out of a ``grid`` x ``grid`` image, with features that are piecewise constant
+    over spatial regions (the nearest of ``n_regions`` seeded sites) plus N(0, noise^2), and
+    their positions as patch centres normalised to [0,1]^2.  With D = 1024 and noise 0.1,
+    tokens of one region are about 4.5 apart and regions about 45 (the cutoff d_c is 8).
+    Returns feature bits [n, D], pos float32 [n, 2], the region of every token and the
+    ascending patch indices that were kept.
+    """
+    g = _rng(seed, 0)
+    keep = np.sort(g.choice(grid * grid, size=n, replace=False))
+    rows, cols = keep // grid, keep % grid
+    pos = np.stack([(rows + 0.5) / grid, (cols + 0.5) / grid], axis=1).astype(np.float32)
+    sites = g.random((n_regions, 2))
+    region = np.argmin(((pos[:, None, :].astype(np.float64) - sites[None]) ** 2).sum(-1), axis=1)
+    cent = g.standard_normal((n_regions, D), dtype=np.float32)
+    feats = cent[region] + np.float32(noise) * g.standard_normal((n, D), dtype=np.float32)
+    return {"n": n, "D": D, "feats": f32_to_bf16_bits(feats), "pos": pos,
+            "region": region.astype(np.int64), "patch": keep.astype(np.int64)}
