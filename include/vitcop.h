@@ -203,6 +203,42 @@ typedef struct {
 size_t vitcop_schedule_workspace_bytes(const vitcop_schedule_t* S);
 int vitcop_schedule_prefill(const vitcop_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Visual Information Clustering (Sec. 3.2.1, Eq. 2-3; Alg. 2): density-peak
+ * clustering of the visual tokens that survived Stage I, under a spatial
+ * neighbourhood constraint.  Per image, with D_feat[i,j] = ||f_i - f_j||_2 and
+ * D_spatial[i,j] = ||p_i - p_j||_2:
+ *   rho_i   = sum_{j != i} exp(-(D_feat[i,j] / d_c)^2)                      (Eq. 2)
+ *   delta_i = min D_feat[i,j] over j with rho_j > rho_i and D_spatial[i,j] <= tau,
+ *             N_i the first such j reaching it (lower index on ties);
+ *             none: delta_i = +inf, N_i = -1                                (Eq. 3)
+ *   gamma_i = rho_i * delta_i (+inf when delta_i is); the n_centers highest gamma
+ *             are centres (lower index on ties)
+ *   labels: a token follows its parents N_i until it reaches a root, i.e. a centre
+ *             or a token without parent; clusters are numbered 0..R-1 by the token
+ *             index of their root (Alg. 2 Step 4 gives the same partition; a
+ *             non-centre without parent, which the listing leaves undefined, is
+ *             the root of its own cluster, so R >= n_centers).
+ * All comparisons are made on the fp32 values written to rho_out / delta_out /
+ * dist_out, so the labels are a deterministic function of those arrays.
+ *   feats  [B,n,D] bf16, rows feat_row_stride elements apart, images
+ *          feat_batch_stride apart (multiples of 8); D % 32 == 0
+ *   pos    [B,n,2] fp32 positions (the paper's tau = 0.6 assumes coordinates
+ *          normalised to the unit square)
+ *   n_centers = ceil(n * alpha) is the caller's choice (alpha is not published)
+ *   labels_out [B,n] int32;  n_clusters_out [B] int32 (= R)
+ *   rho_out, delta_out [B,n] fp32, parent_out [B,n] int32: optional (NULL)
+ *   dist_out: optional [B,n,n4] fp32 with n4 = n rounded up to a multiple of 4
+ *          (row stride n4, pad undefined), receives D_feat with a zero diagonal
+ * n <= VITCOP_VIC_MAX_TOKENS.  One image's features must stay below 2^31 elements.
+ */
+#define VITCOP_VIC_MAX_TOKENS 8192
+size_t vitcop_vic_cluster_workspace_bytes(int B, int n, int D);
+int vitcop_vic_cluster(const uint16_t* feats, int64_t feat_row_stride, int64_t feat_batch_stride,
+                       const float* pos, int B, int n, int D, float d_c, float tau, int n_centers,
+                       int32_t* labels_out, int32_t* n_clusters_out, float* rho_out, float* delta_out,
+                       int32_t* parent_out, float* dist_out, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

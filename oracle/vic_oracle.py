@@ -50,14 +50,16 @@ def _bf16_to_f64(bits) -> np.ndarray:
     return b.view(np.float32).astype(np.float64)
 
 
-def feature_distances(feat_bits) -> np.ndarray:
-    """feat_bits [n, D] bf16 bits -> D_feat [n, n] float64 (Alg. 2, Step 1)."""
+def feature_distances(feat_bits, rows=None) -> np.ndarray:
+    """feat_bits [n, D] bf16 bits -> D_feat [n, n] float64 (Alg. 2, Step 1); with ``rows`` only
+    those rows of the matrix, [len(rows), n]."""
     f = _bf16_to_f64(feat_bits)
     n = f.shape[0]
-    out = np.zeros((n, n), dtype=np.float64)
-    for i in range(n):
+    rows = range(n) if rows is None else list(rows)
+    out = np.zeros((len(rows), n), dtype=np.float64)
+    for r, i in enumerate(rows):
         diff = f - f[i]
-        out[i] = np.sqrt(np.sum(diff * diff, axis=1))
+        out[r] = np.sqrt(np.sum(diff * diff, axis=1))
     return out
 
 

@@ -32,6 +32,7 @@ EXPORTS = (
     "vitcop_project_sumsq_parts", "vitcop_project", "vitcop_select_from_sumsq",
     "vitcop_layer_workspace_bytes", "vitcop_layer_prefill",
     "vitcop_schedule_workspace_bytes", "vitcop_schedule_prefill",
+    "vitcop_vic_cluster_workspace_bytes", "vitcop_vic_cluster",
 )
 
 
@@ -105,6 +106,11 @@ def _load() -> C.CDLL:
     lib.vitcop_schedule_workspace_bytes.argtypes = [C.POINTER(ScheduleT)]
     lib.vitcop_schedule_prefill.restype = i32
     lib.vitcop_schedule_prefill.argtypes = [C.POINTER(ScheduleT), vp, sz, vp]
+    lib.vitcop_vic_cluster_workspace_bytes.restype = sz
+    lib.vitcop_vic_cluster_workspace_bytes.argtypes = [i32, i32, i32]
+    lib.vitcop_vic_cluster.restype = i32
+    lib.vitcop_vic_cluster.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp,
+                                       vp, sz, vp]
     return lib
 
 
@@ -261,6 +267,29 @@ def vitcop_select_from_sumsq(parts, B: int, T: int, vis_start: int, n_vis: int, 
     _check(lib.vitcop_select_from_sumsq(_ptr(parts), P, parts.shape[1], B, T, vis_start, n_vis, keep,
                                         _ptr(norms), _ptr(idx), _stream()))
     return norms, idx
+
+
+def vitcop_vic_cluster(feats, pos, d_c: float, tau: float, n_centers: int, want_dist: bool = False):
+    """feats [B,n,D] bf16, pos [B,n,2] fp32 -> dict(labels [B,n], n_clusters [B], rho, delta, parent
+    [B,n], and with ``want_dist`` the distance matrix [B,n,n4], n4 = n rounded up to 4)."""
+    _dense(feats, "feats")
+    B, n, D = feats.shape
+    if not (pos.is_cuda and pos.is_contiguous() and pos.dtype == torch.float32 and tuple(pos.shape) == (B, n, 2)):
+        raise ValueError("pos must be a contiguous CUDA float32 tensor [B,n,2]")
+    dev = feats.device
+    labels = torch.empty((B, n), dtype=torch.int32, device=dev)
+    n_clusters = torch.empty((B,), dtype=torch.int32, device=dev)
+    rho = torch.empty((B, n), dtype=torch.float32, device=dev)
+    delta = torch.empty((B, n), dtype=torch.float32, device=dev)
+    parent = torch.empty((B, n), dtype=torch.int32, device=dev)
+    dist = torch.empty((B, n, (n + 3) // 4 * 4), dtype=torch.float32, device=dev) if want_dist else None
+    need = lib.vitcop_vic_cluster_workspace_bytes(B, n, D)
+    ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.vitcop_vic_cluster(_ptr(feats), D, n * D, _ptr(pos), B, n, D, d_c, tau, n_centers, _ptr(labels),
+                                  _ptr(n_clusters), _ptr(rho), _ptr(delta), _ptr(parent), _ptr(dist), _ptr(ws),
+                                  need, _stream()))
+    return {"labels": labels, "n_clusters": n_clusters, "rho": rho, "delta": delta, "parent": parent,
+            "dist": dist}
 
 
 class LayerPlan:

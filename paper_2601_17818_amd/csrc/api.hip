@@ -28,7 +28,6 @@ int hip_status(hipError_t e, const char* what) {
 int launch_status(const char* kernel_name) { return hip_status(hipGetLastError(), kernel_name); }
 
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
-static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
 
 struct Carver {   // hands out 256-byte aligned pieces of the caller's workspace
     char* base;
@@ -414,6 +413,48 @@ int vitcop_schedule_prefill(const vitcop_schedule_t* S, void* ws, size_t ws_byte
                         "copy positions");
     }
     return rc;
+}
+
+/* ------------------------------------------------ Visual Information Clustering */
+
+static int check_vic(int B, int n, int D, float d_c, float tau, int n_centers) {
+    REQUIRE(B >= 0 && n >= 0 && D >= 8, VITCOP_EINVAL, "vic_cluster: B=%d n=%d D=%d", B, n, D);
+    REQUIRE(n <= VITCOP_VIC_MAX_TOKENS, VITCOP_EUNSUPPORTED, "vic_cluster: n=%d above %d", n, VITCOP_VIC_MAX_TOKENS);
+    REQUIRE(D % 32 == 0, VITCOP_EUNSUPPORTED, "vic_cluster: D=%d not a multiple of 32", D);
+    REQUIRE(std::isfinite(d_c) && d_c > 0.f, VITCOP_EINVAL, "vic_cluster: d_c must be positive");
+    REQUIRE(std::isfinite(tau) && tau >= 0.f, VITCOP_EINVAL, "vic_cluster: tau must be non-negative");
+    REQUIRE(n_centers >= 0 && n_centers <= n, VITCOP_EINVAL, "vic_cluster: n_centers=%d outside [0,%d]", n_centers, n);
+    return VITCOP_OK;
+}
+
+size_t vitcop_vic_cluster_workspace_bytes(int B, int n, int D) {
+    if (B < 0 || n < 0 || n > VITCOP_VIC_MAX_TOKENS || D < 8) return 0;
+    return vic_workspace_bytes(B, n);
+}
+
+int vitcop_vic_cluster(const uint16_t* feats, int64_t feat_row_stride, int64_t feat_batch_stride,
+                       const float* pos, int B, int n, int D, float d_c, float tau, int n_centers,
+                       int32_t* labels_out, int32_t* n_clusters_out, float* rho_out, float* delta_out,
+                       int32_t* parent_out, float* dist_out, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_vic(B, n, D, d_c, tau, n_centers);
+    if (rc) return rc;
+    if (B == 0) return VITCOP_OK;
+    REQUIRE(n_clusters_out, VITCOP_EINVAL, "vic_cluster: null pointer");
+    if (n > 0) {
+        REQUIRE(feats && pos && labels_out, VITCOP_EINVAL, "vic_cluster: null pointer");
+        REQUIRE(aligned16(feats) && aligned16(pos) && aligned16(dist_out), VITCOP_EINVAL,
+                "vic_cluster: feats, pos and dist_out must be 16-byte aligned");
+        REQUIRE(feat_row_stride >= D && feat_row_stride % 8 == 0 && feat_batch_stride % 8 == 0 &&
+                    (B == 1 || feat_batch_stride >= (int64_t)n * feat_row_stride),
+                VITCOP_EINVAL, "vic_cluster: strides");
+        REQUIRE((int64_t)n * feat_row_stride < (1LL << 31), VITCOP_EUNSUPPORTED,
+                "vic_cluster: one image's features must stay below 2^31 elements");
+        const size_t need = vic_workspace_bytes(B, n);
+        REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "vic_cluster: workspace %zu < %zu", ws_bytes, need);
+        REQUIRE(aligned16(ws), VITCOP_EINVAL, "vic_cluster: workspace must be 16-byte aligned");
+    }
+    return launch_vic(feats, feat_row_stride, feat_batch_stride, pos, B, n, D, d_c, tau, n_centers, labels_out,
+                      n_clusters_out, rho_out, delta_out, parent_out, dist_out, ws, static_cast<hipStream_t>(stream));
 }
 
 #pragma GCC visibility pop

@@ -44,13 +44,19 @@ __device__ __forceinline__ int gm_swz(int row) {
 
 // y = x W^T (+ residual).  With w2 != nullptr the columns [n_split, N) come from a second weight
 // matrix and go to a second output (two projections of the same input in one launch).
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
+// EPI selects the epilogue: GM_EPI_BF16 the projection described above; GM_EPI_DIST writes,
+// in fp32, the Euclidean distance between row m of x and row n of w from their inner product
+// and the two squared row norms: dist[m,n] = sqrt(max(0, xsq[m] + wsq[n] - 2 <x_m, w_n>)).
+constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1;
+
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w,
     uint16_t* __restrict__ y, int64_t y_stride, const uint16_t* __restrict__ res,
     int64_t res_stride, int M, int N, int K, float* __restrict__ sumsq_parts, int tiles_m,
     int tiles_n, int group_m, const uint16_t* __restrict__ w2, uint16_t* __restrict__ y2,
-    int n_split) {
+    int n_split, int64_t w_stride, const float* __restrict__ xsq, const float* __restrict__ wsq,
+    float* __restrict__ dist, int64_t dist_stride) {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts");
     static_assert(BK == 32 || BK == 64, "slab rows of 64 or 128 bytes");
     constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
@@ -118,7 +124,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         if (row < BM)
             goff[q] = 2u * (unsigned)(min(m0 + row, M - 1) * (int)x_stride + chunk * 8);
         else
-            goff[q] = 2u * (unsigned)(min(n0 + row - BM, N - 1) * K + chunk * 8);
+            goff[q] = 2u * (unsigned)(min(n0 + row - BM, N - 1) * (int)w_stride + chunk * 8);
     }
     auto issue_loads = [&](int slab, int k0) {
         const char* xb = reinterpret_cast<const char*>(x + k0);
@@ -226,6 +232,32 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no load may outlive the workgroup's LDS
 #undef VITCOP_INTERLEAVE
 
+    if constexpr (EPI == GM_EPI_DIST) {
+        // lane owns row m = .. + l32 and the 4-element column runs n = .. + 8*(r/4) + 4*g + r%4
+#pragma unroll
+        for (int j = 0; j < MI; ++j) {
+            const int m = m0 + wm * TM + j * 32 + l32;
+            if (m >= M) continue;
+            const float sm = xsq[m];
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int n = n0 + wn * TN + i * 32 + 8 * r4 + 4 * g;
+                    if (n >= N) continue;
+                    // wsq and the rows of dist are padded to a multiple of 4 entries, so the run
+                    // of 4 may be read and written whole even when N cuts it
+                    const float4 sn = *reinterpret_cast<const float4*>(wsq + n);
+                    float4 o;
+                    o.x = __builtin_sqrtf(fmaxf(0.f, fmaf(-2.f, acc[i][j][4 * r4], sm + sn.x)));
+                    o.y = __builtin_sqrtf(fmaxf(0.f, fmaf(-2.f, acc[i][j][4 * r4 + 1], sm + sn.y)));
+                    o.z = __builtin_sqrtf(fmaxf(0.f, fmaf(-2.f, acc[i][j][4 * r4 + 2], sm + sn.z)));
+                    o.w = __builtin_sqrtf(fmaxf(0.f, fmaf(-2.f, acc[i][j][4 * r4 + 3], sm + sn.w)));
+                    *reinterpret_cast<float4*>(dist + (int64_t)m * dist_stride + n) = o;
+                }
+        }
+        return;
+    }
     // Epilogue.  In the accumulators a lane owns row m = .. + l32 and 4-element runs of columns
     // n = .. + 8*(r/4) + 4*g + r%4: stored directly, every store instruction would touch 32
     // rows with 16 bytes each, and the L2 request rate of all CUs finishing a round together
@@ -292,12 +324,14 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 
 int gemm_sumsq_parts(int N) { return (N + GM_PART - 1) / GM_PART; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
 static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                            int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                            int K, float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split,
-                           hipStream_t s) {
-    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK>;
+                           hipStream_t s, int64_t w_stride = 0, const float* xsq = nullptr,
+                           const float* wsq = nullptr, float* dist = nullptr, int64_t dist_stride = 0) {
+    if (w_stride == 0) w_stride = K;
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, EPI>;
     constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK>();
     static bool attr_set = false;        // per kernel instantiation; setting it twice is harmless
     if (!attr_set) {
@@ -313,7 +347,7 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
     while (group_m * 2 <= tiles_m && group_m * group_m * 2 <= 32) group_m *= 2;
     hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(GM_THREADS), lds, s, x, x_stride, w, y,
                        y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m, w2,
-                       y2, n_split);
+                       y2, n_split, w_stride, xsq, wsq, dist, dist_stride);
     return launch_status("gemm");
 }
 
@@ -404,6 +438,18 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
     }
     const TileId id = choose_tile(M, N1 + N2, K, false, N1);
     return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
+}
+
+// dist[m,n] = ||x_m - w_n||_2 in fp32 for bf16 rows x [M,K], w [N,K] (row strides in elements)
+// with their squared norms xsq [M], wsq [N] given.  wsq must be readable, and the rows of dist
+// writable, up to the next multiple of 4 entries (dist_stride % 4 == 0; the pad holds garbage).
+int launch_pairwise_dist(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
+                         const float* xsq, const float* wsq, float* dist, int64_t dist_stride, int M,
+                         int N, int K, hipStream_t s) {
+    if (M == 0 || N == 0) return VITCOP_OK;
+    return launch_gemm_cfg<128, 128, 2, 2, 32, GM_EPI_DIST>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K,
+                                                            nullptr, nullptr, nullptr, 0, s, w_stride, xsq, wsq,
+                                                            dist, dist_stride);
 }
 
 }  // namespace vitcop

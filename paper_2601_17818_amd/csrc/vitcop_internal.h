@@ -11,6 +11,8 @@
 
 namespace vitcop {
 
+static inline size_t up256(size_t n) { return (n + 255) & ~(size_t)255; }
+
 // Records a thread-local message and returns `code` (a VITCOP_E* value).
 int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
 // VITCOP_OK, or records the HIP error text and returns VITCOP_EHIP.
@@ -50,5 +52,18 @@ int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t
 // y1 = x W1^T [M,N1] and y2 = x W2^T [M,N2] (dense outputs), one launch when the shapes allow
 int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                      const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s);
+
+// dist[m,n] = ||x_m - w_n||_2 (fp32) from the MFMA inner products and given squared row norms;
+// wsq readable and dist rows writable up to the next multiple of 4 entries, dist_stride % 4 == 0
+int launch_pairwise_dist(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
+                         const float* xsq, const float* wsq, float* dist, int64_t dist_stride, int M,
+                         int N, int K, hipStream_t s);
+
+// ---- Visual Information Clustering (vic.hip) --------------------------------
+size_t vic_workspace_bytes(int B, int n);
+int launch_vic(const uint16_t* feats, int64_t row_stride, int64_t batch_stride, const float* pos, int B,
+               int n, int D, float d_c, float tau, int n_centers, int32_t* labels, int32_t* n_clusters,
+               float* rho_out, float* delta_out, int32_t* parent_out, float* dist_out, void* ws,
+               hipStream_t s);
 
 }  // namespace vitcop

@@ -185,3 +185,26 @@ def test_schedule_validation():
     assert run(C.byref(desc([1, 4], [192, 64])), A16, 1 << 40, None) == binding.VITCOP_EINVAL   # layer out of range
     assert run(C.byref(desc([1], [600])), A16, 1 << 40, None) == binding.VITCOP_EINVAL
     assert run(C.byref(desc([1], [64], x=None)), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+
+
+def test_vic_validation():
+    f = lib.vitcop_vic_cluster
+    wsb = lib.vitcop_vic_cluster_workspace_bytes
+
+    def call(feats=A16, rs=1024, bs=288 * 1024, pos=A16, B=1, n=288, D=1024, d_c=8.0, tau=0.6, nc=29,
+             labels=A16, ncl=A16, ws=A16, ws_bytes=1 << 30):
+        return f(feats, rs, bs, pos, B, n, D, d_c, tau, nc, labels, ncl, None, None, None, None, ws, ws_bytes, None)
+
+    need = wsb(1, 288, 1024)
+    assert need >= 288 * 288 * 4 + 5 * 288 * 4
+    assert call(ws_bytes=need - 1) == binding.VITCOP_EWORKSPACE
+    assert call(ws=None) == binding.VITCOP_EWORKSPACE
+    assert call(n=8193, bs=8193 * 1024) == binding.VITCOP_EUNSUPPORTED and wsb(1, 8193, 1024) == 0
+    assert call(D=1000, rs=1000) == binding.VITCOP_EUNSUPPORTED
+    assert call(d_c=0.0) == binding.VITCOP_EINVAL
+    assert call(tau=-1.0) == binding.VITCOP_EINVAL
+    assert call(nc=289) == binding.VITCOP_EINVAL
+    assert call(feats=None) == binding.VITCOP_EINVAL
+    assert call(rs=1000) == binding.VITCOP_EINVAL
+    assert call(feats=A16 + 2) == binding.VITCOP_EINVAL
+    assert call(B=0) == binding.VITCOP_OK
