@@ -1,4 +1,5 @@
-"""CPU oracle for Visual Information Clustering (VIC).  TEST INFRASTRUCTURE ONLY.
+"""CPU oracle for Stage II: Visual Information Clustering (VIC) and collaborative pruning and
+merging.  TEST INFRASTRUCTURE ONLY.
 
 Plain NumPy float64 on the exact bf16 feature bits, written from Sec. 3.2.1
 (Eq. 2, Eq. 3) and Alg. 2 of arXiv 2601.17818, step by step in the paper's
@@ -37,6 +38,9 @@ Comparisons that decide integers (rho_j > rho_i, D <= tau, the minimum, the
 TopK of gamma) are taken on the values handed in: callers that check a GPU
 result pass the GPU's own float32 arrays, so both sides decide on identical
 numbers.
+
+``collab_prune_merge`` (Sec. 3.2.3, Eq. 5-6, Alg. 3) is described, with its
+readings, above its definition at the end of this file.
 """
 from __future__ import annotations
 
@@ -157,3 +161,54 @@ def same_partition(a, b) -> bool:
         if fwd.setdefault(x, y) != y or bwd.setdefault(y, x) != x:
             return False
     return True
+
+
+# ---------------------------------------------------------------------------
+# Visual-textual collaborative pruning and merging (Sec. 3.2.3, Eq. 5-6; Alg. 3)
+# ---------------------------------------------------------------------------
+# Readings: B - N_c is taken as 0 when the budget is below the number of clusters (the listing
+# would give negative quotas); "sort by K-norm ascending" is stable, so equal norms go to the
+# lower index; the output set is laid out as the elites in ascending token index followed by the
+# merged tokens in cluster-label order; a merged token is represented, for position purposes, by
+# the lowest-index token it absorbed (the paper treats V_out as a set and says nothing of
+# positions).  floor(|C_c| / n * (B - N_c)) is evaluated exactly, as an integer division.
+
+def collab_prune_merge(feat_bits, labels, k_norms, budget: int):
+    """Alg. 3 for one image.  feat_bits [n, D] bf16 bits, labels [n] in [0, N_c), k_norms [n].
+
+    Returns a dict: ``quota`` [N_c], ``elite`` bool [n], ``feats`` float64 [n_out, D] (elites
+    are the input rows, merged rows are the fp64 means of Eq. 6), ``index`` int32 [n_out]
+    (elite: its token; merged: lowest-index absorbed token), ``assign`` int32 [n] (the output
+    row every input token went to), ``n_elite``.
+    """
+    f = _bf16_to_f64(feat_bits)
+    labels = np.asarray(labels, dtype=np.int64)
+    norms = np.asarray(k_norms, dtype=np.float64)
+    n = len(labels)
+    n_c = int(labels.max()) + 1 if n else 0
+    clusters = [[i for i in range(n) if labels[i] == c] for c in range(n_c)]      # GroupTokensByLabel
+    assert all(len(c) > 0 for c in clusters), "labels must be the dense names 0..N_c-1"
+    b_elites = max(0, budget - n_c)
+    quota = np.zeros(n_c, dtype=np.int64)
+    elite = np.zeros(n, dtype=bool)
+    remaining = []
+    for c, members in enumerate(clusters):
+        quota[c] = (len(members) * b_elites) // n                                 # Eq. 5
+        ranked = sorted(members, key=lambda i: (norms[i], i))                     # ascending K-norm
+        for i in ranked[:quota[c]]:
+            elite[i] = True
+        remaining.append(sorted(ranked[quota[c]:]))
+    elite_idx = [i for i in range(n) if elite[i]]
+    rows, index = [f[i] for i in elite_idx], list(elite_idx)
+    assign = np.full(n, -1, dtype=np.int32)
+    for r, i in enumerate(elite_idx):
+        assign[i] = r
+    for c, rem in enumerate(remaining):
+        if rem:
+            rows.append(f[rem].sum(axis=0) / len(rem))                            # Eq. 6
+            for i in rem:
+                assign[i] = len(index)
+            index.append(rem[0])
+    feats = np.stack(rows) if rows else np.zeros((0, f.shape[1]))
+    return {"quota": quota, "elite": elite, "feats": feats, "index": np.array(index, dtype=np.int32),
+            "assign": assign, "n_elite": len(elite_idx)}
