@@ -239,6 +239,33 @@ int vitcop_vic_cluster(const uint16_t* feats, int64_t feat_row_stride, int64_t f
                        int32_t* labels_out, int32_t* n_clusters_out, float* rho_out, float* delta_out,
                        int32_t* parent_out, float* dist_out, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * Visual-textual collaborative pruning and merging (Sec. 3.2.3, Eq. 5-6; Alg. 3).
+ * Per image, given the cluster label of every visual token (vitcop_vic_cluster),
+ * the number of clusters N_c, the tokens' K-vector norms (Eq. 4) and a budget B:
+ *   q_c = floor(|C_c| * max(0, B - N_c) / n)                                 (Eq. 5)
+ *   the q_c tokens of cluster c with the smallest norm are kept as they are
+ *   ("elites", lower index on equal norms); the other tokens of the cluster are
+ *   replaced by their mean (fp32 sums in ascending token order, rounded to bf16) (Eq. 6)
+ * Output rows: the elites in ascending token index, then one merged row per
+ * cluster that has non-elites, in label order; n_out = sum q_c + #merged <= B
+ * whenever B >= N_c (with B < N_c there are no elites and N_c merged rows).
+ * The paper treats the output as a set and does not say which position a merged
+ * token takes: out_index names, for an elite, its token, and for a merged row the
+ * lowest-index token it absorbed.
+ *   feats [B,n,D] bf16 (strides in elements, multiples of 8), D % 8 == 0
+ *   labels [B,n] int32 in [0, n_clusters[b]): the caller's contract;
+ *   n_clusters [B] int32 (device);  k_norms [B,n] fp32
+ *   out_feats [B,n,D] bf16 and out_index [B,n] int32: rows [0, n_out[b]) are written
+ *   n_out [B] int32;  assign_out [B,n] int32, optional (NULL): output row of every token
+ * n <= VITCOP_VIC_MAX_TOKENS.
+ */
+size_t vitcop_collab_prune_merge_workspace_bytes(int B, int n);
+int vitcop_collab_prune_merge(const uint16_t* feats, int64_t feat_row_stride, int64_t feat_batch_stride,
+                              const int32_t* labels, const int32_t* n_clusters, const float* k_norms,
+                              int B, int n, int D, int budget, uint16_t* out_feats, int32_t* out_index,
+                              int32_t* n_out, int32_t* assign_out, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

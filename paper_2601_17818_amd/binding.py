@@ -33,6 +33,7 @@ EXPORTS = (
     "vitcop_layer_workspace_bytes", "vitcop_layer_prefill",
     "vitcop_schedule_workspace_bytes", "vitcop_schedule_prefill",
     "vitcop_vic_cluster_workspace_bytes", "vitcop_vic_cluster",
+    "vitcop_collab_prune_merge_workspace_bytes", "vitcop_collab_prune_merge",
 )
 
 
@@ -111,6 +112,10 @@ def _load() -> C.CDLL:
     lib.vitcop_vic_cluster.restype = i32
     lib.vitcop_vic_cluster.argtypes = [vp, i64, i64, vp, i32, i32, i32, f32, f32, i32, vp, vp, vp, vp, vp, vp,
                                        vp, sz, vp]
+    lib.vitcop_collab_prune_merge_workspace_bytes.restype = sz
+    lib.vitcop_collab_prune_merge_workspace_bytes.argtypes = [i32, i32]
+    lib.vitcop_collab_prune_merge.restype = i32
+    lib.vitcop_collab_prune_merge.argtypes = [vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     return lib
 
 
@@ -290,6 +295,24 @@ def vitcop_vic_cluster(feats, pos, d_c: float, tau: float, n_centers: int, want_
                                   need, _stream()))
     return {"labels": labels, "n_clusters": n_clusters, "rho": rho, "delta": delta, "parent": parent,
             "dist": dist}
+
+
+def vitcop_collab_prune_merge(feats, labels, n_clusters, k_norms, budget: int):
+    """feats [B,n,D] bf16, labels [B,n] int32, n_clusters [B] int32, k_norms [B,n] fp32 ->
+    dict(feats [B,n,D] (rows below n_out valid), index [B,n], n_out [B], assign [B,n])."""
+    _dense(feats, "feats")
+    B, n, D = feats.shape
+    dev = feats.device
+    out = torch.empty_like(feats)
+    index = torch.empty((B, n), dtype=torch.int32, device=dev)
+    n_out = torch.empty((B,), dtype=torch.int32, device=dev)
+    assign = torch.empty((B, n), dtype=torch.int32, device=dev)
+    need = lib.vitcop_collab_prune_merge_workspace_bytes(B, n)
+    ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+    _check(lib.vitcop_collab_prune_merge(_ptr(feats), D, n * D, _ptr(labels), _ptr(n_clusters), _ptr(k_norms),
+                                         B, n, D, budget, _ptr(out), _ptr(index), _ptr(n_out), _ptr(assign),
+                                         _ptr(ws), need, _stream()))
+    return {"feats": out, "index": index, "n_out": n_out, "assign": assign}
 
 
 class LayerPlan:

@@ -457,5 +457,39 @@ int vitcop_vic_cluster(const uint16_t* feats, int64_t feat_row_stride, int64_t f
                       n_clusters_out, rho_out, delta_out, parent_out, dist_out, ws, static_cast<hipStream_t>(stream));
 }
 
+/* ------------------------------------- collaborative pruning and merging */
+
+size_t vitcop_collab_prune_merge_workspace_bytes(int B, int n) {
+    if (B < 0 || n < 0 || n > VITCOP_VIC_MAX_TOKENS) return 0;
+    return collab_workspace_bytes(B, n);
+}
+
+int vitcop_collab_prune_merge(const uint16_t* feats, int64_t feat_row_stride, int64_t feat_batch_stride,
+                              const int32_t* labels, const int32_t* n_clusters, const float* k_norms,
+                              int B, int n, int D, int budget, uint16_t* out_feats, int32_t* out_index,
+                              int32_t* n_out, int32_t* assign_out, void* ws, size_t ws_bytes, void* stream) {
+    REQUIRE(B >= 0 && n >= 0 && D >= 8, VITCOP_EINVAL, "collab_prune_merge: B=%d n=%d D=%d", B, n, D);
+    REQUIRE(n <= VITCOP_VIC_MAX_TOKENS, VITCOP_EUNSUPPORTED, "collab_prune_merge: n=%d above %d", n,
+            VITCOP_VIC_MAX_TOKENS);
+    REQUIRE(D % 8 == 0, VITCOP_EUNSUPPORTED, "collab_prune_merge: D=%d not a multiple of 8", D);
+    REQUIRE(budget >= 0, VITCOP_EINVAL, "collab_prune_merge: budget=%d", budget);
+    REQUIRE(B <= 65535, VITCOP_EUNSUPPORTED, "collab_prune_merge: B above 65535");
+    if (B == 0) return VITCOP_OK;
+    REQUIRE(n_clusters && n_out, VITCOP_EINVAL, "collab_prune_merge: null pointer");
+    if (n > 0) {
+        REQUIRE(feats && labels && k_norms && out_feats && out_index, VITCOP_EINVAL,
+                "collab_prune_merge: null pointer");
+        REQUIRE(aligned16(feats) && aligned16(out_feats), VITCOP_EINVAL,
+                "collab_prune_merge: feats and out_feats must be 16-byte aligned");
+        REQUIRE(feat_row_stride >= D && feat_row_stride % 8 == 0 && feat_batch_stride % 8 == 0 &&
+                    (B == 1 || feat_batch_stride >= (int64_t)n * feat_row_stride),
+                VITCOP_EINVAL, "collab_prune_merge: strides");
+    }
+    const size_t need = collab_workspace_bytes(B, n);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "collab_prune_merge: workspace %zu < %zu", ws_bytes, need);
+    return launch_collab(feats, feat_row_stride, feat_batch_stride, labels, n_clusters, k_norms, B, n, D, budget,
+                         out_feats, out_index, n_out, assign_out, ws, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

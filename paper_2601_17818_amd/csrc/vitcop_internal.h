@@ -66,4 +66,11 @@ int launch_vic(const uint16_t* feats, int64_t row_stride, int64_t batch_stride, 
                float* rho_out, float* delta_out, int32_t* parent_out, float* dist_out, void* ws,
                hipStream_t s);
 
+// ---- collaborative pruning and merging (collab.hip) -------------------------
+size_t collab_workspace_bytes(int B, int n);
+int launch_collab(const uint16_t* feats, int64_t row_stride, int64_t batch_stride, const int32_t* labels,
+                  const int32_t* n_clusters, const float* norms, int B, int n, int D, int budget,
+                  uint16_t* out_feats, int32_t* out_index, int32_t* n_out, int32_t* assign, void* ws,
+                  hipStream_t s);
+
 }  // namespace vitcop

@@ -208,3 +208,22 @@ def test_vic_validation():
     assert call(rs=1000) == binding.VITCOP_EINVAL
     assert call(feats=A16 + 2) == binding.VITCOP_EINVAL
     assert call(B=0) == binding.VITCOP_OK
+
+
+def test_collab_validation():
+    f = lib.vitcop_collab_prune_merge
+    need = lib.vitcop_collab_prune_merge_workspace_bytes(1, 288)
+    assert need >= 2 * 288 * 4
+
+    def call(feats=A16, rs=4096, bs=288 * 4096, labels=A16, ncl=A16, norms=A16, B=1, n=288, D=4096, budget=192,
+             out=A16, index=A16, n_out=A16, ws=A16, ws_bytes=1 << 20):
+        return f(feats, rs, bs, labels, ncl, norms, B, n, D, budget, out, index, n_out, None, ws, ws_bytes, None)
+
+    assert call(ws_bytes=need - 1) == binding.VITCOP_EWORKSPACE
+    assert call(n=8193, bs=8193 * 4096) == binding.VITCOP_EUNSUPPORTED
+    assert call(D=4100, rs=4104) == binding.VITCOP_EUNSUPPORTED
+    assert call(budget=-1) == binding.VITCOP_EINVAL
+    assert call(labels=None) == binding.VITCOP_EINVAL
+    assert call(out=A16 + 8) == binding.VITCOP_EINVAL
+    assert call(rs=4000) == binding.VITCOP_EINVAL
+    assert call(B=0) == binding.VITCOP_OK
