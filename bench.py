@@ -200,6 +200,24 @@ def main():
             kern[name + "_TFLOPs"] = fl / (t_a * 1e-3) / 1e12
             kern[name + "_frac_mfma"] = kern[name + "_TFLOPs"] / MFMA_BF16_PEAK_TFLOPS
             del qq, kk, vv, oo
+        # Stage II (Sec. 3.2.1, 3.2.3): clustering of the Stage I survivors and per-cluster elites +
+        # merging, at the image shape (8 images x 288 tokens, D 4096, 29 centres, budget 253) and at
+        # the video shape (1856 tokens as one set, D 3584, 186 centres, budget 627)
+        stage2 = {}
+        for name, b2, n2, d2, nc2, bud2, grid2 in (("image_8x288", 8, 288, 4096, 29, 253, 24),
+                                                   ("video_1x1856", 1, 1856, 3584, 186, 627, 44)):
+            cases = [I.vic_inputs(I.seed_for(1, 50 + j), n2, d2, grid=grid2, n_regions=max(8, n2 // 40), noise=0.2)
+                     for j in range(b2)]
+            vf = dev(np.stack([c["feats"] for c in cases]))
+            vp = torch.from_numpy(np.stack([c["pos"] for c in cases])).cuda()
+            vnorm = torch.rand((b2, n2), dtype=torch.float32, device="cuda") + 0.5
+            vr = vc.vitcop_vic_cluster(vf, vp, 8.0, 0.6, nc2)
+            t_v = ev_time(lambda: vc.vitcop_vic_cluster(vf, vp, 8.0, 0.6, nc2), 10)
+            t_m = ev_time(lambda: vc.vitcop_collab_prune_merge(vf, vr["labels"], vr["n_clusters"], vnorm, bud2), 10)
+            stage2[name] = {"vic_ms": t_v, "collab_ms": t_m, "clusters": vr["n_clusters"].cpu().tolist(),
+                            "gram_GFLOP": 2.0 * b2 * n2 * n2 * d2 / 1e9}
+            del vf, vp, vr
+        kern["stage2"] = stage2
         # the layer alone at each keep ratio, and the unpruned layer
         layer_ms = {}
         for k_, p_ in plans.items():

@@ -421,6 +421,7 @@ static int check_vic(int B, int n, int D, float d_c, float tau, int n_centers) {
     REQUIRE(B >= 0 && n >= 0 && D >= 8, VITCOP_EINVAL, "vic_cluster: B=%d n=%d D=%d", B, n, D);
     REQUIRE(n <= VITCOP_VIC_MAX_TOKENS, VITCOP_EUNSUPPORTED, "vic_cluster: n=%d above %d", n, VITCOP_VIC_MAX_TOKENS);
     REQUIRE(D % 32 == 0, VITCOP_EUNSUPPORTED, "vic_cluster: D=%d not a multiple of 32", D);
+    REQUIRE(B <= 65535, VITCOP_EUNSUPPORTED, "vic_cluster: B above 65535");
     REQUIRE(std::isfinite(d_c) && d_c > 0.f, VITCOP_EINVAL, "vic_cluster: d_c must be positive");
     REQUIRE(std::isfinite(tau) && tau >= 0.f, VITCOP_EINVAL, "vic_cluster: tau must be non-negative");
     REQUIRE(n_centers >= 0 && n_centers <= n, VITCOP_EINVAL, "vic_cluster: n_centers=%d outside [0,%d]", n_centers, n);

@@ -147,19 +147,46 @@ __global__ __launch_bounds__(256) void collab_emit_kernel(
             *reinterpret_cast<uint4*>(dst + c) = *reinterpret_cast<const uint4*>(src + c);
         return;
     }
-    for (int c = threadIdx.x * 8; c < D; c += 256 * 8) {
+    // a merged row: list the absorbed tokens in ascending order (block-wide ordered compaction of
+    // the tokens assigned to this row), then average them channel by channel
+    __shared__ int members[VITCOP_VIC_MAX_TOKENS];
+    __shared__ int wave_tot[4];
+    __shared__ int total;
+    const int tid = threadIdx.x;
+    int running = 0;
+    for (int i0 = first; i0 < n; i0 += 256) {
+        const int i = i0 + tid;
+        const int f = (i < n && assign[i] == r) ? 1 : 0;
+        int incl = f;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if ((tid & 63) >= o) incl += t;
+        }
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+        __syncthreads();
+        int before = running, chunk = 0;
+        for (int w = 0; w < 4; ++w) {
+            if (w < (tid >> 6)) before += wave_tot[w];
+            chunk += wave_tot[w];
+        }
+        if (f) members[before + incl - 1] = i;
+        running += chunk;
+        __syncthreads();
+    }
+    if (tid == 0) total = running;
+    __syncthreads();
+    const int count = total;
+    const float inv = 1.0f / (float)count;
+    for (int c = tid * 8; c < D; c += 256 * 8) {
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        int count = 0;
-        for (int i = first; i < n; ++i) {                 // the absorbed tokens, ascending
-            if (assign[i] != r) continue;
-            const uint4 u = *reinterpret_cast<const uint4*>(feats + (int64_t)i * row_stride + c);
+        for (int m = 0; m < count; ++m) {
+            const uint4 u = *reinterpret_cast<const uint4*>(feats + (int64_t)members[m] * row_stride + c);
             acc[0] += bf16_lo(u.x); acc[1] += bf16_hi(u.x);
             acc[2] += bf16_lo(u.y); acc[3] += bf16_hi(u.y);
             acc[4] += bf16_lo(u.z); acc[5] += bf16_hi(u.z);
             acc[6] += bf16_lo(u.w); acc[7] += bf16_hi(u.w);
-            ++count;
         }
-        const float inv = 1.0f / (float)count;
         uint4 o;
         o.x = pack_bf16(acc[0] * inv, acc[1] * inv);
         o.y = pack_bf16(acc[2] * inv, acc[3] * inv);

@@ -56,7 +56,8 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     int64_t res_stride, int M, int N, int K, float* __restrict__ sumsq_parts, int tiles_m,
     int tiles_n, int group_m, const uint16_t* __restrict__ w2, uint16_t* __restrict__ y2,
     int n_split, int64_t w_stride, const float* __restrict__ xsq, const float* __restrict__ wsq,
-    float* __restrict__ dist, int64_t dist_stride) {
+    float* __restrict__ dist, int64_t dist_stride, int64_t x_batch, int64_t sq_batch,
+    int64_t dist_batch) {
     static_assert(WAVES_M * WAVES_N == 4, "four wavefronts");
     static_assert(BK == 32 || BK == 64, "slab rows of 64 or 128 bytes");
     constexpr int TM = BM / WAVES_M, TN = BN / WAVES_N;
@@ -70,6 +71,13 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     static_assert(SLAB % 4096 == 0 && (BM * ROWB) % 1024 == 0, "slab splits evenly over loads");
 
     extern __shared__ __attribute__((aligned(1024))) char gemm_lds[];
+    if constexpr (EPI == GM_EPI_DIST) {      // blockIdx.y = image: x and w are the same feature matrix
+        x += blockIdx.y * x_batch;
+        w += blockIdx.y * x_batch;
+        xsq += blockIdx.y * sq_batch;
+        wsq += blockIdx.y * sq_batch;
+        dist += blockIdx.y * dist_batch;
+    }
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);      // wavefront index, kept scalar
@@ -329,7 +337,8 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
                            int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                            int K, float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split,
                            hipStream_t s, int64_t w_stride = 0, const float* xsq = nullptr,
-                           const float* wsq = nullptr, float* dist = nullptr, int64_t dist_stride = 0) {
+                           const float* wsq = nullptr, float* dist = nullptr, int64_t dist_stride = 0,
+                           int batch = 1, int64_t x_batch = 0, int64_t sq_batch = 0, int64_t dist_batch = 0) {
     if (w_stride == 0) w_stride = K;
     auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, EPI>;
     constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK>();
@@ -345,9 +354,9 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
     // tile rows per group: a patch of about 32 tiles (one XCD's worth of workgroups) near square
     int group_m = 1;
     while (group_m * 2 <= tiles_m && group_m * group_m * 2 <= 32) group_m *= 2;
-    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n), dim3(GM_THREADS), lds, s, x, x_stride, w, y,
+    hipLaunchKernelGGL(kern, dim3(tiles_m * tiles_n, batch), dim3(GM_THREADS), lds, s, x, x_stride, w, y,
                        y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m, w2,
-                       y2, n_split, w_stride, xsq, wsq, dist, dist_stride);
+                       y2, n_split, w_stride, xsq, wsq, dist, dist_stride, x_batch, sq_batch, dist_batch);
     return launch_status("gemm");
 }
 
@@ -440,16 +449,17 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
     return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
 }
 
-// dist[m,n] = ||x_m - w_n||_2 in fp32 for bf16 rows x [M,K], w [N,K] (row strides in elements)
-// with their squared norms xsq [M], wsq [N] given.  wsq must be readable, and the rows of dist
-// writable, up to the next multiple of 4 entries (dist_stride % 4 == 0; the pad holds garbage).
-int launch_pairwise_dist(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
-                         const float* xsq, const float* wsq, float* dist, int64_t dist_stride, int M,
-                         int N, int K, hipStream_t s) {
-    if (M == 0 || N == 0) return VITCOP_OK;
-    return launch_gemm_cfg<128, 128, 2, 2, 32, GM_EPI_DIST>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K,
-                                                            nullptr, nullptr, nullptr, 0, s, w_stride, xsq, wsq,
-                                                            dist, dist_stride);
+// dist[b][i,j] = ||f_i - f_j||_2 in fp32 between the rows of each of `batch` bf16 matrices
+// f [n,K] (row stride and batch stride in elements), with their squared row norms sq given.
+// sq must be readable, and the rows of dist writable, up to the next multiple of 4 entries
+// (dist_stride % 4 == 0; the pad holds garbage).
+int launch_pairwise_dist(const uint16_t* f, int64_t row_stride, int64_t batch_stride, const float* sq,
+                         int64_t sq_batch, float* dist, int64_t dist_stride, int64_t dist_batch, int n, int K,
+                         int batch, hipStream_t s) {
+    if (n == 0 || batch == 0) return VITCOP_OK;
+    return launch_gemm_cfg<128, 128, 2, 2, 32, GM_EPI_DIST>(f, row_stride, f, nullptr, 0, nullptr, 0, n, n, K,
+                                                            nullptr, nullptr, nullptr, 0, s, row_stride, sq, sq, dist,
+                                                            dist_stride, batch, batch_stride, sq_batch, dist_batch);
 }
 
 }  // namespace vitcop

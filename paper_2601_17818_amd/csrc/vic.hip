@@ -27,12 +27,14 @@ constexpr int VIC_ROW_THREADS = 256;      // 4 wavefronts, one matrix row each
 
 // sq[i] = sum_c f[i,c]^2 in fp32; D % 8 == 0, rows 16-byte aligned
 __global__ __launch_bounds__(VIC_ROW_THREADS) void rowsq_kernel(const uint16_t* __restrict__ f,
-                                                                int64_t row_stride, int n, int D,
-                                                                float* __restrict__ sq) {
+                                                                int64_t row_stride, int64_t batch_stride,
+                                                                int n, int D, float* __restrict__ sq,
+                                                                int64_t sq_batch) {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * (VIC_ROW_THREADS / 64) + (threadIdx.x >> 6);
     if (i >= n) return;
-    const uint16_t* row = f + (int64_t)i * row_stride;
+    sq += blockIdx.y * sq_batch;
+    const uint16_t* row = f + blockIdx.y * batch_stride + (int64_t)i * row_stride;
     float acc = 0.f;
     for (int c = lane * 8; c < D; c += 64 * 8) acc = sumsq8(*reinterpret_cast<const uint4*>(row + c), acc);
     acc = wave_sum(acc);
@@ -42,13 +44,15 @@ __global__ __launch_bounds__(VIC_ROW_THREADS) void rowsq_kernel(const uint16_t* 
 // Eq. 2.  One wavefront per row; lane l adds the columns l, l+64, ... in order, then the 64
 // lane sums are combined by the fixed xor tree: the result does not depend on scheduling.
 __global__ __launch_bounds__(VIC_ROW_THREADS) void vic_density_kernel(float* __restrict__ dist,
-                                                                      int64_t dist_stride, int n,
+                                                                      int64_t dist_stride,
+                                                                      int64_t dist_batch, int n,
                                                                       float neg_inv_dc2_log2e,
                                                                       float* __restrict__ rho) {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * (VIC_ROW_THREADS / 64) + (threadIdx.x >> 6);
     if (i >= n) return;
-    float* row = dist + (int64_t)i * dist_stride;
+    rho += (int64_t)blockIdx.y * n;
+    float* row = dist + blockIdx.y * dist_batch + (int64_t)i * dist_stride;
     if (lane == 0) row[i] = 0.f;                        // a token is at distance 0 from itself
     float acc = 0.f;
     for (int j = lane; j < n; j += 64) {
@@ -62,13 +66,19 @@ __global__ __launch_bounds__(VIC_ROW_THREADS) void vic_density_kernel(float* __r
 
 // Eq. 3.  One wavefront per row; candidates are ordered by (distance, index).
 __global__ __launch_bounds__(VIC_ROW_THREADS) void vic_parent_kernel(
-    const float* __restrict__ dist, int64_t dist_stride, const float* __restrict__ pos,
-    const float* __restrict__ rho, int n, float tau2, float* __restrict__ delta,
-    int32_t* __restrict__ parent, float* __restrict__ gamma) {
+    const float* __restrict__ dist, int64_t dist_stride, int64_t dist_batch,
+    const float* __restrict__ pos, const float* __restrict__ rho, int n, float tau2,
+    float* __restrict__ delta, int32_t* __restrict__ parent, float* __restrict__ gamma) {
     const int lane = threadIdx.x & 63;
     const int i = blockIdx.x * (VIC_ROW_THREADS / 64) + (threadIdx.x >> 6);
     if (i >= n) return;
-    const float* row = dist + (int64_t)i * dist_stride;
+    const int64_t img = (int64_t)blockIdx.y * n;
+    pos += 2 * img;
+    rho += img;
+    delta += img;
+    parent += img;
+    gamma += img;
+    const float* row = dist + blockIdx.y * dist_batch + (int64_t)i * dist_stride;
     const float rho_i = rho[i], px = pos[2 * i], py = pos[2 * i + 1];
     float best = INFINITY;
     int best_j = 0x7fffffff;
@@ -199,34 +209,29 @@ int launch_vic(const uint16_t* feats, int64_t row_stride, int64_t batch_stride, 
     float* delta = delta_out ? delta_out : delta_ws;
     int32_t* parent = parent_out ? parent_out : parent_ws;
 
-    const unsigned row_blocks = (unsigned)((n + VIC_ROW_THREADS / 64 - 1) / (VIC_ROW_THREADS / 64));
+    const dim3 row_grid((unsigned)((n + VIC_ROW_THREADS / 64 - 1) / (VIC_ROW_THREADS / 64)), B);
     const float c = -1.4426950408889634f / (d_c * d_c);
-    for (int b = 0; b < B; ++b) {
-        const uint16_t* f = feats + b * batch_stride;
-        float* dist_b = dist + (int64_t)b * n * n_pad;
-        hipLaunchKernelGGL(rowsq_kernel, dim3(row_blocks), dim3(VIC_ROW_THREADS), 0, s, f, row_stride, n, D,
-                           sq + b * n_pad);
-        int rc = launch_status("rowsq");
-        if (rc) return rc;
-        rc = launch_pairwise_dist(f, row_stride, f, row_stride, sq + b * n_pad, sq + b * n_pad, dist_b, n_pad, n,
-                                  n, D, s);
-        if (rc) return rc;
-        hipLaunchKernelGGL(vic_density_kernel, dim3(row_blocks), dim3(VIC_ROW_THREADS), 0, s, dist_b, n_pad, n, c,
-                           rho + (int64_t)b * n);
-        rc = launch_status("vic_density");
-        if (rc) return rc;
-        hipLaunchKernelGGL(vic_parent_kernel, dim3(row_blocks), dim3(VIC_ROW_THREADS), 0, s, dist_b, n_pad,
-                           pos + (int64_t)b * n * 2, rho + (int64_t)b * n, n, tau * tau, delta + (int64_t)b * n,
-                           parent + (int64_t)b * n, gamma + (int64_t)b * n);
-        rc = launch_status("vic_parent");
-        if (rc) return rc;
-    }
+    const int64_t dist_batch = (int64_t)n * n_pad;
+    hipLaunchKernelGGL(rowsq_kernel, row_grid, dim3(VIC_ROW_THREADS), 0, s, feats, row_stride, batch_stride, n, D, sq,
+                       n_pad);
+    int rc = launch_status("rowsq");
+    if (rc) return rc;
+    rc = launch_pairwise_dist(feats, row_stride, batch_stride, sq, n_pad, dist, n_pad, dist_batch, n, D, B, s);
+    if (rc) return rc;
+    hipLaunchKernelGGL(vic_density_kernel, row_grid, dim3(VIC_ROW_THREADS), 0, s, dist, n_pad, dist_batch, n, c, rho);
+    rc = launch_status("vic_density");
+    if (rc) return rc;
+    hipLaunchKernelGGL(vic_parent_kernel, row_grid, dim3(VIC_ROW_THREADS), 0, s, dist, n_pad, dist_batch, pos, rho, n,
+                       tau * tau, delta, parent, gamma);
+    rc = launch_status("vic_parent");
+    if (rc) return rc;
     const size_t lds = (size_t)3 * n * 4 + 16;
     static bool attr_set = false;
     if (!attr_set) {
-        int rc = hip_status(hipFuncSetAttribute((const void*)vic_label_kernel,
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, 3 * 8192 * 4 + 16),
-                            "hipFuncSetAttribute(vic_label)");
+        rc = hip_status(hipFuncSetAttribute((const void*)vic_label_kernel,
+                                            hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            3 * VITCOP_VIC_MAX_TOKENS * 4 + 16),
+                        "hipFuncSetAttribute(vic_label)");
         if (rc) return rc;
         attr_set = true;
     }

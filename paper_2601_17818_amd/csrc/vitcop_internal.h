@@ -53,11 +53,12 @@ int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t
 int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                      const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s);
 
-// dist[m,n] = ||x_m - w_n||_2 (fp32) from the MFMA inner products and given squared row norms;
-// wsq readable and dist rows writable up to the next multiple of 4 entries, dist_stride % 4 == 0
-int launch_pairwise_dist(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
-                         const float* xsq, const float* wsq, float* dist, int64_t dist_stride, int M,
-                         int N, int K, hipStream_t s);
+// dist[b][i,j] = ||f_i - f_j||_2 (fp32) between the rows of each of `batch` matrices, from MFMA
+// inner products and given squared row norms; sq readable and dist rows writable up to the next
+// multiple of 4 entries, dist_stride % 4 == 0
+int launch_pairwise_dist(const uint16_t* f, int64_t row_stride, int64_t batch_stride, const float* sq,
+                         int64_t sq_batch, float* dist, int64_t dist_stride, int64_t dist_batch, int n, int K,
+                         int batch, hipStream_t s);
 
 // ---- Visual Information Clustering (vic.hip) --------------------------------
 size_t vic_workspace_bytes(int B, int n);
