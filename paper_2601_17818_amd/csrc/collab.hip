@@ -81,34 +81,9 @@ __global__ __launch_bounds__(CB_PLAN_THREADS) void collab_plan_kernel(
         }
     __syncthreads();
 
-    // block-wide exclusive scan of a 0/1 flag over [0, count), chunk by chunk; returns the total
-    auto scan = [&](int count, auto flag_of, auto store) {
-        int running = 0;
-        for (int i0 = 0; i0 < count; i0 += CB_PLAN_THREADS) {
-            const int i = i0 + tid;
-            const int f = i < count ? flag_of(i) : 0;
-            int incl = f;
-#pragma unroll
-            for (int o = 1; o < 64; o <<= 1) {
-                const int t = __shfl_up(incl, o, 64);
-                if ((tid & 63) >= o) incl += t;
-            }
-            if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
-            __syncthreads();
-            int before = running, chunk = 0;
-            for (int w = 0; w < CB_PLAN_THREADS / 64; ++w) {
-                if (w < (tid >> 6)) before += wave_tot[w];
-                chunk += wave_tot[w];
-            }
-            if (i < count) store(i, f, before + incl - f);
-            running += chunk;
-            __syncthreads();
-        }
-        return running;
-    };
     // elites keep their order: row = number of elites before the token
-    const int n_elite = scan(
-        n, [&](int i) { return elite[i]; },
+    const int n_elite = block_exclusive_scan<CB_PLAN_THREADS>(
+        0, n, wave_tot, [&](int i) { return elite[i]; },
         [&](int i, int f, int pos) {
             if (f) {
                 assign[i] = pos;
@@ -116,8 +91,8 @@ __global__ __launch_bounds__(CB_PLAN_THREADS) void collab_plan_kernel(
             }
         });
     // merged rows follow, one per cluster with non-elites, in cluster order
-    const int n_merged = scan(
-        R, [&](int c) { return merged_row[c]; },
+    const int n_merged = block_exclusive_scan<CB_PLAN_THREADS>(
+        0, R, wave_tot, [&](int c) { return merged_row[c]; },
         [&](int c, int f, int pos) {
             if (f) out_index[n_elite + pos] = first_rest[c];
             merged_row[c] = n_elite + pos;
@@ -153,27 +128,11 @@ __global__ __launch_bounds__(256) void collab_emit_kernel(
     __shared__ int wave_tot[4];
     __shared__ int total;
     const int tid = threadIdx.x;
-    int running = 0;
-    for (int i0 = first; i0 < n; i0 += 256) {
-        const int i = i0 + tid;
-        const int f = (i < n && assign[i] == r) ? 1 : 0;
-        int incl = f;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(incl, o, 64);
-            if ((tid & 63) >= o) incl += t;
-        }
-        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
-        __syncthreads();
-        int before = running, chunk = 0;
-        for (int w = 0; w < 4; ++w) {
-            if (w < (tid >> 6)) before += wave_tot[w];
-            chunk += wave_tot[w];
-        }
-        if (f) members[before + incl - 1] = i;
-        running += chunk;
-        __syncthreads();
-    }
+    const int running = block_exclusive_scan<256>(
+        first, n, wave_tot, [&](int i) { return assign[i] == r ? 1 : 0; },
+        [&](int i, int f, int pos) {
+            if (f) members[pos] = i;
+        });
     if (tid == 0) total = running;
     __syncthreads();
     const int count = total;

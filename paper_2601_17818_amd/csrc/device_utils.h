@@ -59,4 +59,36 @@ __device__ __forceinline__ float sumsq8(const uint4& u, float acc) {
     return acc;
 }
 
+// Workgroup-wide exclusive scan of per-index counts over [first, end), in chunks of THREADS
+// indices: store(i, count_i, exclusive_prefix_i) runs for every index, the total is returned.
+// wave_tot: THREADS/64 ints of LDS.  Must be called by all THREADS threads; the last
+// __syncthreads of the final chunk orders everything `store` wrote to LDS.
+template <int THREADS, typename CountOf, typename Store>
+__device__ inline int block_exclusive_scan(int first, int end, int* wave_tot, CountOf count_of, Store store) {
+    const int tid = threadIdx.x;
+    int running = 0;
+    for (int i0 = first; i0 < end; i0 += THREADS) {
+        const int i = i0 + tid;
+        const int f = i < end ? count_of(i) : 0;
+        int incl = f;
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(incl, o, 64);
+            if ((tid & 63) >= o) incl += t;
+        }
+        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
+        __syncthreads();
+        int before = running, chunk = 0;
+#pragma unroll
+        for (int w = 0; w < THREADS / 64; ++w) {
+            if (w < (tid >> 6)) before += wave_tot[w];
+            chunk += wave_tot[w];
+        }
+        if (i < end) store(i, f, before + incl - f);
+        running += chunk;
+        __syncthreads();
+    }
+    return running;
+}
+
 }  // namespace vitcop

@@ -117,7 +117,7 @@ __global__ __launch_bounds__(SEL_THREADS) void vic_label_kernel(const float* __r
                                                                 int64_t batch_stride) {
     extern __shared__ __attribute__((aligned(16))) unsigned vic_lds[];
     __shared__ SelectShared sh;
-    __shared__ unsigned wave_tot[SEL_THREADS / 64];
+    __shared__ int wave_tot[SEL_THREADS / 64];
     const int tid = threadIdx.x, b = blockIdx.x;
     gamma += b * batch_stride;
     parent += b * batch_stride;
@@ -139,29 +139,12 @@ __global__ __launch_bounds__(SEL_THREADS) void vic_label_kernel(const float* __r
 
     // cluster id of a root = number of roots with a lower index (block-wide exclusive scan over
     // chunks of SEL_THREADS tokens), and the pointer every token starts from
-    unsigned running = 0;
-    for (int i0 = 0; i0 < n; i0 += SEL_THREADS) {
-        const int i = i0 + tid;
-        const unsigned f = i < n ? is_root[i] : 0u;
-        unsigned incl = f;
-#pragma unroll
-        for (int o = 1; o < 64; o <<= 1) {
-            const unsigned t = __shfl_up(incl, o, 64);
-            if ((tid & 63) >= o) incl += t;
-        }
-        if ((tid & 63) == 63) wave_tot[tid >> 6] = incl;
-        __syncthreads();
-        unsigned before = running;
-        for (int w = 0; w < (tid >> 6); ++w) before += wave_tot[w];
-        unsigned chunk_total = 0;
-        for (int w = 0; w < SEL_THREADS / 64; ++w) chunk_total += wave_tot[w];
-        if (i < n) {
-            cid[i] = (int32_t)(before + incl - f);
+    const int running = block_exclusive_scan<SEL_THREADS>(
+        0, n, wave_tot, [&](int i) { return (int)is_root[i]; },
+        [&](int i, int f, int before) {
+            cid[i] = before;
             keys[i] = f ? (unsigned)i : (unsigned)parent[i];
-        }
-        running += chunk_total;
-        __syncthreads();
-    }
+        });
     if (tid == 0) n_clusters[b] = (int32_t)running;
 
     // pointer jumping: after ceil(log2 n) rounds every pointer is a root
