@@ -175,6 +175,10 @@ typedef struct {
     float*    norms;              /* [B,n_vis] out, may be NULL */
     const int32_t* positions_in;  /* [B,T] original positions, may be NULL */
     int32_t*  positions_out;      /* [B,T'] gathered positions, may be NULL */
+    /* profiling hook: hipEvent_t handles (as void*), each NULL or an event the caller created;
+     * recorded on the stream right before and right after the K projection of all tokens */
+    void* ev_kproj_begin;
+    void* ev_kproj_end;
 } vitcop_layer_t;
 size_t vitcop_layer_workspace_bytes(const vitcop_layer_t* L);
 int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, void* stream);

@@ -54,7 +54,8 @@ class LayerT(C.Structure):
                 ("residual", C.c_int),
                 ("x", C.c_void_p), ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p),
                 ("wo", C.c_void_p), ("y", C.c_void_p), ("keep_idx", C.c_void_p),
-                ("norms", C.c_void_p), ("positions_in", C.c_void_p), ("positions_out", C.c_void_p)]
+                ("norms", C.c_void_p), ("positions_in", C.c_void_p), ("positions_out", C.c_void_p),
+                ("ev_kproj_begin", C.c_void_p), ("ev_kproj_end", C.c_void_p)]
 
 
 class ScheduleT(C.Structure):
@@ -340,7 +341,15 @@ class LayerPlan:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
         self.ws = _ws(nb, x)
 
-    def run(self):
+    def run(self, kproj_events=None):
+        """``kproj_events`` = (begin, end): two torch.cuda.Event objects that have been recorded once
+        (so that their handles exist); the library records them around the K projection."""
+        if kproj_events is not None:
+            self.desc.ev_kproj_begin = kproj_events[0].cuda_event
+            self.desc.ev_kproj_end = kproj_events[1].cuda_event
+        else:
+            self.desc.ev_kproj_begin = None
+            self.desc.ev_kproj_end = None
         _check(lib.vitcop_layer_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
         return self.y
 

@@ -291,8 +291,16 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
     int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
 
     // K of every token of the layer input, squared norms as a side output
+    if (L->ev_kproj_begin) {
+        rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_begin), s), "hipEventRecord");
+        if (rc) return rc;
+    }
     rc = launch_gemm(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, s);
     if (rc) return rc;
+    if (L->ev_kproj_end) {
+        rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_end), s), "hipEventRecord");
+        if (rc) return rc;
+    }
     if (want_sel) {
         rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T,
                                     L->vis_start, L->n_vis, L->keep, idx, s);

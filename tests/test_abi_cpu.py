@@ -42,7 +42,7 @@ def test_status_codes_match_header():
 
 def test_struct_sizes_match_c_layout():
     assert C.sizeof(binding.GatherT) == 40
-    assert C.sizeof(binding.LayerT) == 10 * 4 + 10 * 8
+    assert C.sizeof(binding.LayerT) == 10 * 4 + 12 * 8
     assert C.sizeof(binding.ScheduleT) == 10 * 4 + 9 * 8
 
 
@@ -137,7 +137,7 @@ def test_project_and_select_from_sumsq_validation():
 def layer_desc(**kw):
     base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, vis_start=35, n_vis=576, keep=64, residual=0,
                 x=A16, wq=A16, wk=A16, wv=A16, wo=A16, y=A16, keep_idx=None, norms=None,
-                positions_in=None, positions_out=None)
+                positions_in=None, positions_out=None, ev_kproj_begin=None, ev_kproj_end=None)
     base.update(kw)
     return binding.LayerT(**base)
 
