@@ -1,0 +1,74 @@
+"""CPU oracle for one full decoder layer of the prefill with pruning on entry.  TEST INFRASTRUCTURE ONLY.
+
+The paper prunes inside the layers of LLaVA's language model (Sec. 4.1: LLaVA-1.5 / LLaVA-NeXT,
+i.e. a LLaMA-family decoder) but does not restate that architecture.  This module writes out the
+published pre-norm decoder layer (RMSNorm, rotary position embedding in the rotate-half
+convention, grouped-query attention, SiLU-gated MLP, two residual adds) in NumPy float64, with
+the pruning step of Alg. 1 (layer loop body) at its entry, and rounds to bf16 exactly where the
+GPU path stores a bf16 tensor.  It imports only NumPy and the hot-path oracle next to it.
+
+Readings: K-norms are taken before the rotary embedding (a per-pair rotation leaves them
+unchanged, Sec. 3.2.2 / Eq. 4 does not say); survivors keep their original positions (the paper
+is silent); pruning removes a token from the residual stream of this and all later layers.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+from . import vitcop_oracle as O
+
+
+def rmsnorm(x_bits, w_bits, eps: float) -> np.ndarray:
+    """y = x / sqrt(mean(x^2) + eps) * w over the last axis, float64."""
+    x = O.bf16_to_f64(x_bits)
+    w = O.bf16_to_f64(w_bits)
+    ms = np.mean(x * x, axis=-1, keepdims=True)
+    return x / np.sqrt(ms + eps) * w
+
+
+def rope(x_bits, positions, theta: float) -> np.ndarray:
+    """Rotary embedding, rotate-half pairing: channel i < d/2 pairs with i + d/2, angle =
+    position * theta^(-2i/d).  x_bits [B,N,H,d], positions [B,N] -> float64 [B,N,H,d]."""
+    x = O.bf16_to_f64(x_bits)
+    d = x.shape[-1]
+    half = d // 2
+    inv_freq = theta ** (-np.arange(half, dtype=np.float64) * 2.0 / d)
+    ang = np.asarray(positions, dtype=np.float64)[:, :, None, None] * inv_freq        # [B,N,1,half]
+    c, s = np.cos(ang), np.sin(ang)
+    lo, hi = x[..., :half], x[..., half:]
+    return np.concatenate([lo * c - hi * s, hi * c + lo * s], axis=-1)
+
+
+def silu_mul(gate_bits, up_bits) -> np.ndarray:
+    """silu(gate) * up = gate / (1 + exp(-gate)) * up, float64."""
+    g = O.bf16_to_f64(gate_bits)
+    u = O.bf16_to_f64(up_bits)
+    return g / (1.0 + np.exp(-g)) * u
+
+
+def decoder_layer(h_bits, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, keep: int,
+                  positions, eps: float = 1e-5, theta: float = 10000.0):
+    """h [B,T,D] bits; w: bits of ln1, ln2 [D], wq [Hq d, D], wk, wv [Hkv d, D], wo [D, Hq d],
+    wg, wu [F, D], wd [D, F]; positions [B,T].  Returns a dict with the output hidden states
+    (float64 and bf16 bits), the keep list, the norms and the intermediates a staged check needs."""
+    B, T, D = h_bits.shape
+    r16 = O.f64_to_bf16_bits
+    a = r16(rmsnorm(h_bits, w["ln1"], eps))                                    # [B,T,D]
+    k_all = r16(O.project(a, w["wk"])).reshape(B, T, Hkv, d)
+    norms = O.k_norms(k_all, vis_start, n_vis)
+    idx = O.keep_list(norms, T, vis_start, keep)
+    Tp = idx.shape[1]
+    h_kept, a_kept, k_kept = O.compact(h_bits, idx), O.compact(a, idx), O.compact(k_all, idx)
+    pos_kept = np.take_along_axis(np.asarray(positions), idx, axis=1)
+    q = r16(O.project(a_kept, w["wq"])).reshape(B, Tp, Hq, d)
+    v = r16(O.project(a_kept, w["wv"])).reshape(B, Tp, Hkv, d)
+    q_r, k_r = r16(rope(q, pos_kept, theta)), r16(rope(k_kept, pos_kept, theta))
+    attn, _ = O.attention(q_r, k_r, v)
+    o = r16(attn).reshape(B, Tp, Hq * d)
+    h1 = r16(O.bf16_to_f64(h_kept) + O.project(o, w["wo"]))
+    b = r16(rmsnorm(h1, w["ln2"], eps))
+    g, u = r16(O.project(b, w["wg"])), r16(O.project(b, w["wu"]))
+    m = r16(silu_mul(g, u))
+    y = O.bf16_to_f64(h1) + O.project(m, w["wd"])
+    return {"y": y, "y_bits": r16(y), "keep_idx": idx, "norms": norms, "positions": pos_kept,
+            "a": a, "q_rope": q_r, "k_rope": k_r, "h1": h1, "m": m}

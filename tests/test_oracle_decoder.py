@@ -1,0 +1,106 @@
+"""Pins of the decoder-layer oracle against library routines and closed forms."""
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+import vitcop_inputs as I
+from oracle import decoder_oracle as Dc
+from oracle import vitcop_oracle as O
+
+
+def bits(a):
+    return I.f32_to_bf16_bits(np.asarray(a, dtype=np.float32))
+
+
+def f64(b):
+    return O.bf16_to_f64(b)
+
+
+def test_rmsnorm_matches_library():
+    x = I.normal_bf16(1, 0, (5, 7, 96), 2.0)
+    w = I.normal_bf16(1, 1, (96,), 1.0)
+    got = Dc.rmsnorm(x, w, 1e-5)
+    want = F.rms_norm(torch.from_numpy(f64(x)), (96,), torch.from_numpy(f64(w)), 1e-5).numpy()
+    assert np.allclose(got, want, rtol=1e-13, atol=1e-13)
+    # closed form: a constant row c with unit weight maps to c / sqrt(c^2 + eps)
+    c = Dc.rmsnorm(bits(np.full((1, 8), 3.0)), bits(np.ones(8)), 0.25)
+    assert np.allclose(c, 3.0 / np.sqrt(9.25))
+
+
+def test_silu_mul_matches_library():
+    g = I.normal_bf16(2, 0, (33, 40), 3.0)
+    u = I.normal_bf16(2, 1, (33, 40), 1.0)
+    want = (F.silu(torch.from_numpy(f64(g))) * torch.from_numpy(f64(u))).numpy()
+    assert np.allclose(Dc.silu_mul(g, u), want, rtol=1e-13, atol=1e-15)
+
+
+def test_rope_closed_forms_and_invariants():
+    # d = 2: a single pair rotating by `position` radians (theta^0 = 1)
+    x = bits(np.array([1.0, 0.0]).reshape(1, 1, 1, 2).repeat(4, axis=1))
+    pos = np.array([[0, 1, 2, 7]])
+    r = Dc.rope(x, pos, 10000.0)
+    assert np.allclose(r[0, :, 0, 0], np.cos([0, 1, 2, 7])) and np.allclose(r[0, :, 0, 1], np.sin([0, 1, 2, 7]))
+    # d = 4: channel 1 pairs with channel 3 and turns by position * theta^(-1/2)
+    y = bits(np.array([0.0, 2.0, 0.0, 0.0]).reshape(1, 1, 1, 4))
+    r = Dc.rope(y, np.array([[3]]), 100.0)
+    assert np.allclose(r[0, 0, 0], [0.0, 2 * np.cos(0.3), 0.0, 2 * np.sin(0.3)])
+    # position 0 is the identity; norms of pairs are preserved; scores depend on position differences only
+    t = I.qkv_tensors(9, 2, 6, 3, 3, 64)
+    pos = np.array([[0, 3, 4, 10, 11, 40], [5, 6, 7, 8, 9, 10]])
+    q, k = Dc.rope(t["q"], pos, 10000.0), Dc.rope(t["k"], pos, 10000.0)
+    assert np.array_equal(q[0, 0], f64(t["q"])[0, 0])
+    assert np.allclose((q ** 2).sum(-1), (f64(t["q"]) ** 2).sum(-1), rtol=1e-12)
+    q2, k2 = Dc.rope(t["q"], pos + 17, 10000.0), Dc.rope(t["k"], pos + 17, 10000.0)
+    s1 = np.einsum("bnhd,bmhd->bhnm", q, k)
+    s2 = np.einsum("bnhd,bmhd->bhnm", q2, k2)
+    assert np.allclose(s1, s2, rtol=1e-9, atol=1e-9)
+
+
+def torch_reference_layer(h, w, Hq, Hkv, d, positions, eps, theta):
+    """The same layer with library ops in float64 and no intermediate rounding (no pruning)."""
+    t = lambda b: torch.from_numpy(f64(b))
+    B, T, D = h.shape
+    x = t(h)
+    a = F.rms_norm(x, (D,), t(w["ln1"]), eps)
+    q = (a @ t(w["wq"]).T).reshape(B, T, Hq, d).transpose(1, 2)
+    k = (a @ t(w["wk"]).T).reshape(B, T, Hkv, d).transpose(1, 2)
+    v = (a @ t(w["wv"]).T).reshape(B, T, Hkv, d).transpose(1, 2)
+    half = d // 2
+    inv = theta ** (-torch.arange(half, dtype=torch.float64) * 2 / d)
+    ang = torch.from_numpy(np.asarray(positions, dtype=np.float64))[:, None, :, None] * inv
+    cos, sin = torch.cat([ang.cos(), ang.cos()], -1), torch.cat([ang.sin(), ang.sin()], -1)
+    rot = lambda z: torch.cat([-z[..., half:], z[..., :half]], -1)
+    q, k = q * cos + rot(q) * sin, k * cos + rot(k) * sin
+    k = k.repeat_interleave(Hq // Hkv, dim=1)
+    v = v.repeat_interleave(Hq // Hkv, dim=1)
+    o = F.scaled_dot_product_attention(q, k, v, is_causal=True).transpose(1, 2).reshape(B, T, Hq * d)
+    h1 = x + o @ t(w["wo"]).T
+    b = F.rms_norm(h1, (D,), t(w["ln2"]), eps)
+    m = F.silu(b @ t(w["wg"]).T) * (b @ t(w["wu"]).T)
+    return (h1 + m @ t(w["wd"]).T).numpy()
+
+
+def test_unpruned_layer_matches_library_composition():
+    c = I.decoder_inputs(77, 2, 40, 128, 4, 2, 64, 96)
+    pos = np.tile(np.arange(40), (2, 1))
+    r = Dc.decoder_layer(c["h"], c["w"], 4, 2, 64, 5, 30, 30, pos)
+    want = torch_reference_layer(c["h"], c["w"], 4, 2, 64, pos, 1e-5, 10000.0)
+    assert np.array_equal(r["keep_idx"], np.tile(np.arange(40), (2, 1)))
+    # the oracle rounds every stored tensor to bf16 (relative 2^-9 each), the library route does not
+    assert np.abs(r["y"] - want).max() <= 3e-2 * np.abs(want).max()
+    assert np.mean(np.abs(r["y"] - want)) <= 4e-3 * np.mean(np.abs(want))
+
+
+def test_pruned_layer_is_the_library_layer_on_the_survivors_prefix_property():
+    # Pruning only tokens AFTER position p leaves the outputs of tokens <= p unchanged (causality):
+    # compare the pruned layer's first rows with the unpruned layer's
+    c = I.decoder_inputs(78, 1, 48, 128, 4, 4, 64, 96)
+    pos = np.arange(48)[None]
+    full = Dc.decoder_layer(c["h"], c["w"], 4, 4, 64, 20, 28, 28, pos)
+    cut = Dc.decoder_layer(c["h"], c["w"], 4, 4, 64, 20, 28, 9, pos)
+    assert cut["keep_idx"].shape == (1, 29) and np.array_equal(cut["keep_idx"][0, :20], np.arange(20))
+    assert np.array_equal(cut["y_bits"][0, :20], full["y_bits"][0, :20])
+    assert np.array_equal(cut["positions"], cut["keep_idx"])
+    # and the kept visual tokens are the 9 smallest K-norms
+    assert np.array_equal(cut["keep_idx"][0, 20:29] - 20, O.topk_smallest(full["norms"][0], 9))

@@ -286,3 +286,26 @@ def vic_inputs(seed: int, n: int, D: int, grid: int = 24, n_regions: int = 12,
     feats = cent[region] + np.float32(noise) * g.standard_normal((n, D), dtype=np.float32)
     return {"n": n, "D": D, "feats": f32_to_bf16_bits(feats), "pos": pos,
             "region": region.astype(np.int64), "patch": keep.astype(np.int64)}
+
+
+def decoder_inputs(seed: int, B: int, T: int, D: int, Hq: int, Hkv: int, d: int, F: int,
+                   w_std: float | None = None, row_gain: np.ndarray | None = None,
+                   vis_start: int = 0) -> dict:
+    """Hidden states and the nine weight tensors of one pre-norm decoder layer (all bf16 bits):
+    h [B,T,D] ~ N(0,1) (visual rows optionally scaled by ``row_gain`` [B,n]), norm weights
+    ~ N(1, 0.1), projections ~ N(0, w_std) with w_std = 1/sqrt(fan_in) unless given."""
+    g = _rng(seed, 0)
+    h = g.standard_normal((B, T, D), dtype=np.float32)
+    if row_gain is not None:
+        n = row_gain.shape[1]
+        h[:, vis_start:vis_start + n] *= row_gain[:, :, None].astype(np.float32)
+
+    def lin(stream, out_f, in_f):
+        std = w_std if w_std is not None else 1.0 / np.sqrt(in_f)
+        return normal_bf16(seed, stream, (out_f, in_f), std)
+
+    w = {"ln1": f32_to_bf16_bits(1.0 + 0.1 * _rng(seed, 1).standard_normal(D, dtype=np.float32)),
+         "ln2": f32_to_bf16_bits(1.0 + 0.1 * _rng(seed, 2).standard_normal(D, dtype=np.float32)),
+         "wq": lin(3, Hq * d, D), "wk": lin(4, Hkv * d, D), "wv": lin(5, Hkv * d, D),
+         "wo": lin(6, D, Hq * d), "wg": lin(7, F, D), "wu": lin(8, F, D), "wd": lin(9, D, F)}
+    return {"B": B, "T": T, "D": D, "Hq": Hq, "Hkv": Hkv, "d": d, "F": F, "h": f32_to_bf16_bits(h), "w": w}
