@@ -270,6 +270,54 @@ int vitcop_collab_prune_merge(const uint16_t* feats, int64_t feat_row_stride, in
                               int B, int n, int D, int budget, uint16_t* out_feats, int32_t* out_index,
                               int32_t* n_out, int32_t* assign_out, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * A full decoder layer of the language model around the pruned prefill.  The
+ * paper prunes inside the layers of LLaVA's LLaMA-family decoder (Sec. 4.1; the
+ * layer loop of Alg. 1) without restating that architecture; these are its
+ * published pieces: pre-norm RMSNorm, rotary position embedding (rotate-half
+ * pairing: channel i < d/2 pairs with i + d/2, angle = position * theta^(-2i/d)),
+ * grouped-query attention, SiLU-gated MLP, two residual adds.
+ */
+
+/* y[m,:] = x[m,:] / sqrt(mean(x[m,:]^2) + eps) * weight, fp32 arithmetic, bf16 in/out.
+ * x, y [M,D] with row strides in elements (multiples of 8); D % 8 == 0. */
+int vitcop_rmsnorm(const uint16_t* x, int64_t x_row_stride, const uint16_t* weight, float eps,
+                   uint16_t* y, int64_t y_row_stride, int M, int D, void* stream);
+
+/* Rotary embedding IN PLACE on q [B,N,Hq,d] and k [B,N,Hkv,d] (dense; either may be NULL) with
+ * explicit positions [B,N] int32: survivors of pruning keep their original positions.
+ * d % 16 == 0; theta > 1. */
+int vitcop_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int B, int N, int Hq, int Hkv,
+                int d, float theta, void* stream);
+
+/* out = silu(gate) * up element-wise; n_elems % 8 == 0, 16-byte aligned pointers. */
+int vitcop_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, void* stream);
+
+/* One decoder layer with pruning on entry (body of the layer loop of Alg. 1 on a full layer):
+ *   a = RMSNorm(h) ; K = a Wk^T for all T tokens, with the K-norms of Eq. 4 as a side output
+ *   (taken before the rotary embedding, which does not change them) ; keep list by the
+ *   Stage III rule ; gather of h, a, K and the positions ; Q, V of the survivors ; rotary
+ *   embedding of Q, K at the ORIGINAL positions ; causal attention ; h1 = h_kept + O Wo^T ;
+ *   y = h1 + (silu(b Wg^T) * (b Wu^T)) Wd^T with b = RMSNorm(h1).
+ * keep == n_vis gives the vanilla layer.  Weights are [out_features, in_features] bf16.
+ * D % 32 == 0, F % 32 == 0, d in {64,128}.
+ */
+typedef struct {
+    int B, T, D, Hq, Hkv, d, F;      /* F: width of the MLP */
+    int vis_start, n_vis, keep;
+    float eps, theta;                 /* RMSNorm epsilon; rotary base */
+    const uint16_t* h;                /* [B,T,D] */
+    const int32_t* positions;         /* [B,T] */
+    const uint16_t *ln1, *ln2;        /* [D] */
+    const uint16_t *wq, *wk, *wv, *wo, *wg, *wu, *wd;
+    uint16_t* y;                      /* [B,T',D] */
+    int32_t* keep_idx;                /* [B,T'] out, may be NULL */
+    int32_t* positions_out;           /* [B,T'] out, may be NULL */
+    float* norms;                     /* [B,n_vis] out, may be NULL */
+} vitcop_decoder_layer_t;
+size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L);
+int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

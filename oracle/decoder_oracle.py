@@ -47,16 +47,18 @@ def silu_mul(gate_bits, up_bits) -> np.ndarray:
 
 
 def decoder_layer(h_bits, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, keep: int,
-                  positions, eps: float = 1e-5, theta: float = 10000.0):
+                  positions, eps: float = 1e-5, theta: float = 10000.0, keep_idx=None):
     """h [B,T,D] bits; w: bits of ln1, ln2 [D], wq [Hq d, D], wk, wv [Hkv d, D], wo [D, Hq d],
     wg, wu [F, D], wd [D, F]; positions [B,T].  Returns a dict with the output hidden states
-    (float64 and bf16 bits), the keep list, the norms and the intermediates a staged check needs."""
+    (float64 and bf16 bits), the keep list, the norms and the intermediates a staged check needs.
+    ``keep_idx`` [B,T'] replaces the keep list computed here (for checking a pipeline whose own,
+    separately validated, list differs among near-tied norms)."""
     B, T, D = h_bits.shape
     r16 = O.f64_to_bf16_bits
     a = r16(rmsnorm(h_bits, w["ln1"], eps))                                    # [B,T,D]
     k_all = r16(O.project(a, w["wk"])).reshape(B, T, Hkv, d)
     norms = O.k_norms(k_all, vis_start, n_vis)
-    idx = O.keep_list(norms, T, vis_start, keep)
+    idx = O.keep_list(norms, T, vis_start, keep) if keep_idx is None else np.asarray(keep_idx)
     Tp = idx.shape[1]
     h_kept, a_kept, k_kept = O.compact(h_bits, idx), O.compact(a, idx), O.compact(k_all, idx)
     pos_kept = np.take_along_axis(np.asarray(positions), idx, axis=1)

@@ -34,6 +34,8 @@ EXPORTS = (
     "vitcop_schedule_workspace_bytes", "vitcop_schedule_prefill",
     "vitcop_vic_cluster_workspace_bytes", "vitcop_vic_cluster",
     "vitcop_collab_prune_merge_workspace_bytes", "vitcop_collab_prune_merge",
+    "vitcop_rmsnorm", "vitcop_rope", "vitcop_silu_mul",
+    "vitcop_decoder_layer_workspace_bytes", "vitcop_decoder_layer_prefill",
 )
 
 
@@ -56,6 +58,16 @@ class LayerT(C.Structure):
                 ("wo", C.c_void_p), ("y", C.c_void_p), ("keep_idx", C.c_void_p),
                 ("norms", C.c_void_p), ("positions_in", C.c_void_p), ("positions_out", C.c_void_p),
                 ("ev_kproj_begin", C.c_void_p), ("ev_kproj_end", C.c_void_p)]
+
+
+class DecoderLayerT(C.Structure):
+    _fields_ = [("B", C.c_int), ("T", C.c_int), ("D", C.c_int), ("Hq", C.c_int), ("Hkv", C.c_int),
+                ("d", C.c_int), ("F", C.c_int), ("vis_start", C.c_int), ("n_vis", C.c_int), ("keep", C.c_int),
+                ("eps", C.c_float), ("theta", C.c_float),
+                ("h", C.c_void_p), ("positions", C.c_void_p), ("ln1", C.c_void_p), ("ln2", C.c_void_p),
+                ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p), ("wo", C.c_void_p),
+                ("wg", C.c_void_p), ("wu", C.c_void_p), ("wd", C.c_void_p), ("y", C.c_void_p),
+                ("keep_idx", C.c_void_p), ("positions_out", C.c_void_p), ("norms", C.c_void_p)]
 
 
 class ScheduleT(C.Structure):
@@ -117,6 +129,16 @@ def _load() -> C.CDLL:
     lib.vitcop_collab_prune_merge_workspace_bytes.argtypes = [i32, i32]
     lib.vitcop_collab_prune_merge.restype = i32
     lib.vitcop_collab_prune_merge.argtypes = [vp, i64, i64, vp, vp, vp, i32, i32, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.vitcop_rmsnorm.restype = i32
+    lib.vitcop_rmsnorm.argtypes = [vp, i64, vp, f32, vp, i64, i32, i32, vp]
+    lib.vitcop_rope.restype = i32
+    lib.vitcop_rope.argtypes = [vp, vp, vp, i32, i32, i32, i32, i32, f32, vp]
+    lib.vitcop_silu_mul.restype = i32
+    lib.vitcop_silu_mul.argtypes = [vp, vp, vp, i64, vp]
+    lib.vitcop_decoder_layer_workspace_bytes.restype = sz
+    lib.vitcop_decoder_layer_workspace_bytes.argtypes = [C.POINTER(DecoderLayerT)]
+    lib.vitcop_decoder_layer_prefill.restype = i32
+    lib.vitcop_decoder_layer_prefill.argtypes = [C.POINTER(DecoderLayerT), vp, sz, vp]
     return lib
 
 
@@ -314,6 +336,68 @@ def vitcop_collab_prune_merge(feats, labels, n_clusters, k_norms, budget: int):
                                          B, n, D, budget, _ptr(out), _ptr(index), _ptr(n_out), _ptr(assign),
                                          _ptr(ws), need, _stream()))
     return {"feats": out, "index": index, "n_out": n_out, "assign": assign}
+
+
+def vitcop_rmsnorm(x, weight, eps: float = 1e-5):
+    """x [M,D] bf16, weight [D] bf16 -> y [M,D]."""
+    _dense(x, "x"); _dense(weight, "weight")
+    M, D = x.shape
+    y = torch.empty_like(x)
+    _check(lib.vitcop_rmsnorm(_ptr(x), D, _ptr(weight), eps, _ptr(y), D, M, D, _stream()))
+    return y
+
+
+def vitcop_rope(q, k, positions, theta: float = 10000.0):
+    """In place on q [B,N,Hq,d] and k [B,N,Hkv,d] (either may be None) with positions [B,N] int32."""
+    t = q if q is not None else k
+    B, N, _, d = t.shape
+    Hq = q.shape[2] if q is not None else 0
+    Hkv = k.shape[2] if k is not None else 0
+    _check(lib.vitcop_rope(_ptr(q), _ptr(k), _ptr(positions), B, N, Hq, Hkv, d, theta, _stream()))
+    return q, k
+
+
+def vitcop_silu_mul(gate, up):
+    _dense(gate, "gate"); _dense(up, "up")
+    out = torch.empty_like(gate)
+    _check(lib.vitcop_silu_mul(_ptr(gate), _ptr(up), _ptr(out), gate.numel(), _stream()))
+    return out
+
+
+class DecoderLayerPlan:
+    """Pre-marshalled vitcop_decoder_layer_prefill call.  ``w``: dict of device tensors ln1, ln2, wq, wk, wv,
+    wo, wg, wu, wd."""
+
+    def __init__(self, h, positions, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, keep: int,
+                 eps: float = 1e-5, theta: float = 10000.0):
+        B, T, D = h.shape
+        F = w["wg"].shape[0]
+        Tp = T - n_vis + keep
+        dev = h.device
+        self.tensors = (h, positions, w)
+        self.y = torch.empty((B, Tp, D), dtype=h.dtype, device=dev)
+        self.keep_idx = torch.empty((B, Tp), dtype=torch.int32, device=dev)
+        self.positions_out = torch.empty((B, Tp), dtype=torch.int32, device=dev)
+        self.norms = torch.empty((B, n_vis), dtype=torch.float32, device=dev)
+        self.desc = DecoderLayerT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, keep, eps, theta, _ptr(h),
+                                  _ptr(positions), _ptr(w["ln1"]), _ptr(w["ln2"]), _ptr(w["wq"]), _ptr(w["wk"]),
+                                  _ptr(w["wv"]), _ptr(w["wo"]), _ptr(w["wg"]), _ptr(w["wu"]), _ptr(w["wd"]),
+                                  _ptr(self.y), _ptr(self.keep_idx), _ptr(self.positions_out), _ptr(self.norms))
+        nb = lib.vitcop_decoder_layer_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, h)
+
+    def run(self):
+        _check(lib.vitcop_decoder_layer_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        return self.y
+
+
+def vitcop_decoder_layer_prefill(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps=1e-5, theta=10000.0):
+    """One full decoder layer with pruning on entry.  Returns dict(y, keep_idx, positions, norms)."""
+    plan = DecoderLayerPlan(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps, theta)
+    plan.run()
+    return {"y": plan.y, "keep_idx": plan.keep_idx, "positions": plan.positions_out, "norms": plan.norms}
 
 
 class LayerPlan:

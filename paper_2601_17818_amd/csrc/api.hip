@@ -1,6 +1,7 @@
 // C ABI of libvitcop: argument validation on the host (before any HIP call),
 // then kernel launches on the caller's stream.  See include/vitcop.h for the
 // contract of each entry point.
+#include <algorithm>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -498,6 +499,166 @@ int vitcop_collab_prune_merge(const uint16_t* feats, int64_t feat_row_stride, in
     REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "collab_prune_merge: workspace %zu < %zu", ws_bytes, need);
     return launch_collab(feats, feat_row_stride, feat_batch_stride, labels, n_clusters, k_norms, B, n, D, budget,
                          out_feats, out_index, n_out, assign_out, ws, static_cast<hipStream_t>(stream));
+}
+
+/* ------------------------------------------------------------ decoder layer */
+
+int vitcop_rmsnorm(const uint16_t* x, int64_t x_row_stride, const uint16_t* weight, float eps, uint16_t* y,
+                   int64_t y_row_stride, int M, int D, void* stream) {
+    REQUIRE(M >= 0 && D >= 8, VITCOP_EINVAL, "rmsnorm: M=%d D=%d", M, D);
+    REQUIRE(D % 8 == 0, VITCOP_EUNSUPPORTED, "rmsnorm: D=%d not a multiple of 8", D);
+    REQUIRE(std::isfinite(eps) && eps >= 0.f, VITCOP_EINVAL, "rmsnorm: eps");
+    if (M == 0) return VITCOP_OK;
+    REQUIRE(x && weight && y, VITCOP_EINVAL, "rmsnorm: null pointer");
+    REQUIRE(aligned16(x) && aligned16(weight) && aligned16(y), VITCOP_EINVAL, "rmsnorm: pointers must be 16-byte aligned");
+    REQUIRE(x_row_stride >= D && x_row_stride % 8 == 0 && y_row_stride >= D && y_row_stride % 8 == 0, VITCOP_EINVAL,
+            "rmsnorm: strides");
+    return launch_rmsnorm(x, x_row_stride, weight, eps, y, y_row_stride, M, D, static_cast<hipStream_t>(stream));
+}
+
+int vitcop_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int B, int N, int Hq, int Hkv, int d,
+                float theta, void* stream) {
+    REQUIRE(B >= 0 && N >= 0 && Hq >= 0 && Hkv >= 0 && d >= 16, VITCOP_EINVAL, "rope: B=%d N=%d Hq=%d Hkv=%d d=%d", B,
+            N, Hq, Hkv, d);
+    REQUIRE(d % 16 == 0, VITCOP_EUNSUPPORTED, "rope: d=%d not a multiple of 16", d);
+    REQUIRE(std::isfinite(theta) && theta > 1.f, VITCOP_EINVAL, "rope: theta must exceed 1");
+    if (B == 0 || N == 0 || (!q && !k)) return VITCOP_OK;
+    REQUIRE(positions, VITCOP_EINVAL, "rope: null positions");
+    REQUIRE(aligned16(q) && aligned16(k), VITCOP_EINVAL, "rope: pointers must be 16-byte aligned");
+    return launch_rope(q, k, positions, (int64_t)B * N, Hq, Hkv, d, theta, static_cast<hipStream_t>(stream));
+}
+
+int vitcop_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, void* stream) {
+    REQUIRE(n_elems >= 0 && n_elems % 8 == 0, VITCOP_EINVAL, "silu_mul: n_elems=%ld must be a multiple of 8", (long)n_elems);
+    if (n_elems == 0) return VITCOP_OK;
+    REQUIRE(gate && up && out, VITCOP_EINVAL, "silu_mul: null pointer");
+    REQUIRE(aligned16(gate) && aligned16(up) && aligned16(out), VITCOP_EINVAL, "silu_mul: pointers must be 16-byte aligned");
+    return launch_silu_mul(gate, up, out, n_elems, static_cast<hipStream_t>(stream));
+}
+
+static int check_decoder_layer(const vitcop_decoder_layer_t* L) {
+    REQUIRE(L, VITCOP_EINVAL, "decoder_layer: descriptor is null");
+    REQUIRE(L->B >= 1 && L->T >= 1 && L->D >= 32 && L->Hq >= 1 && L->Hkv >= 1 && L->F >= 32, VITCOP_EINVAL,
+            "decoder_layer: B=%d T=%d D=%d Hq=%d Hkv=%d F=%d", L->B, L->T, L->D, L->Hq, L->Hkv, L->F);
+    REQUIRE(L->Hq % L->Hkv == 0, VITCOP_EINVAL, "decoder_layer: Hq=%d not a multiple of Hkv=%d", L->Hq, L->Hkv);
+    REQUIRE(L->d == 64 || L->d == 128, VITCOP_EUNSUPPORTED, "decoder_layer: d=%d (64 or 128)", L->d);
+    REQUIRE(L->D % 32 == 0 && L->F % 32 == 0, VITCOP_EUNSUPPORTED, "decoder_layer: D=%d, F=%d must be multiples of 32",
+            L->D, L->F);
+    REQUIRE(L->vis_start >= 0 && L->n_vis >= 0 && (long)L->vis_start + L->n_vis <= L->T, VITCOP_EINVAL,
+            "decoder_layer: visual span [%d,%d) outside [0,%d)", L->vis_start, L->vis_start + L->n_vis, L->T);
+    REQUIRE(L->keep >= 0 && L->keep <= L->n_vis, VITCOP_EINVAL, "decoder_layer: keep=%d outside [0,%d]", L->keep,
+            L->n_vis);
+    REQUIRE(L->n_vis <= VITCOP_MAX_CANDIDATES, VITCOP_EUNSUPPORTED, "decoder_layer: n_vis=%d > %d", L->n_vis,
+            VITCOP_MAX_CANDIDATES);
+    REQUIRE(L->T - L->n_vis + L->keep >= 1, VITCOP_EINVAL, "decoder_layer: nothing survives");
+    REQUIRE(std::isfinite(L->eps) && L->eps >= 0.f && std::isfinite(L->theta) && L->theta > 1.f, VITCOP_EINVAL,
+            "decoder_layer: eps or theta");
+    REQUIRE((long)L->B * L->T * std::max(L->D, L->F) < (1L << 31), VITCOP_EUNSUPPORTED,
+            "decoder_layer: an activation tensor would reach 2^31 elements");
+    return VITCOP_OK;
+}
+
+size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L) {
+    if (check_decoder_layer(L) != VITCOP_OK) return 0;
+    const size_t B = L->B, T = L->T, Tp = L->T - L->n_vis + L->keep, D = L->D, F = L->F;
+    const size_t qd = (size_t)L->Hq * L->d, kd = (size_t)L->Hkv * L->d;
+    size_t n = 0;
+    n += up256(B * T * D * 2);                                          // a = RMSNorm(h)
+    n += up256(B * T * kd * 2);                                         // K of every token
+    n += up256((size_t)gemm_sumsq_parts((int)kd) * B * T * 4);          // squared-norm partials
+    n += 2 * up256(B * Tp * 4);                                         // keep list, positions
+    n += 2 * up256(B * Tp * D * 2);                                     // gathered h and a
+    n += up256(B * Tp * kd * 2);                                        // gathered K
+    n += up256(B * Tp * qd * 2) + up256(B * Tp * kd * 2);               // Q, V
+    n += up256(B * Tp * qd * 2);                                        // attention output
+    n += 2 * up256(B * Tp * D * 2);                                     // h1, b
+    n += 3 * up256(B * Tp * F * 2);                                     // gate, up, silu(gate) * up
+    return n;
+}
+
+int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_decoder_layer(L);
+    if (rc) return rc;
+    REQUIRE(L->h && L->positions && L->ln1 && L->ln2 && L->wq && L->wk && L->wv && L->wo && L->wg && L->wu &&
+                L->wd && L->y,
+            VITCOP_EINVAL, "decoder_layer: null pointer");
+    REQUIRE(aligned16(L->h) && aligned16(L->ln1) && aligned16(L->ln2) && aligned16(L->wq) && aligned16(L->wk) &&
+                aligned16(L->wv) && aligned16(L->wo) && aligned16(L->wg) && aligned16(L->wu) && aligned16(L->wd) &&
+                aligned16(L->y),
+            VITCOP_EINVAL, "decoder_layer: pointers must be 16-byte aligned");
+    const size_t need = vitcop_decoder_layer_workspace_bytes(L);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "decoder_layer: workspace needs %zu bytes", need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int B = L->B, T = L->T, D = L->D, F = L->F, Tp = L->T - L->n_vis + L->keep;
+    const int qd = L->Hq * L->d, kd = L->Hkv * L->d;
+    const bool prune = L->keep < L->n_vis;
+    const bool want_sel = prune || L->keep_idx || L->norms;
+    const int P = gemm_sumsq_parts(kd);
+
+    Carver c(ws);
+    uint16_t* a_all = c.take<uint16_t>((size_t)B * T * D * 2);
+    uint16_t* k_all = c.take<uint16_t>((size_t)B * T * kd * 2);
+    float* parts = c.take<float>((size_t)P * B * T * 4);
+    int32_t* idx_ws = c.take<int32_t>((size_t)B * Tp * 4);
+    int32_t* pos_ws = c.take<int32_t>((size_t)B * Tp * 4);
+    uint16_t* h_kept = c.take<uint16_t>((size_t)B * Tp * D * 2);
+    uint16_t* a_kept = c.take<uint16_t>((size_t)B * Tp * D * 2);
+    uint16_t* k_kept = c.take<uint16_t>((size_t)B * Tp * kd * 2);
+    uint16_t* qb = c.take<uint16_t>((size_t)B * Tp * qd * 2);
+    uint16_t* vb = c.take<uint16_t>((size_t)B * Tp * kd * 2);
+    uint16_t* ob = c.take<uint16_t>((size_t)B * Tp * qd * 2);
+    uint16_t* h1 = c.take<uint16_t>((size_t)B * Tp * D * 2);
+    uint16_t* bb = c.take<uint16_t>((size_t)B * Tp * D * 2);
+    uint16_t* gate = c.take<uint16_t>((size_t)B * Tp * F * 2);
+    uint16_t* up = c.take<uint16_t>((size_t)B * Tp * F * 2);
+    uint16_t* act = c.take<uint16_t>((size_t)B * Tp * F * 2);
+    int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
+    int32_t* pos = L->positions_out ? L->positions_out : pos_ws;
+
+    rc = launch_rmsnorm(L->h, D, L->ln1, L->eps, a_all, D, B * T, D, s);
+    if (rc) return rc;
+    // K of every token, squared norms (before the rotary embedding) as a side output
+    rc = launch_gemm(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, s);
+    if (rc) return rc;
+    if (want_sel) {
+        rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T, L->vis_start,
+                                    L->n_vis, L->keep, idx, s);
+        if (rc) return rc;
+    }
+    const uint16_t *hs = L->h, *as = a_all;
+    uint16_t* ks = k_all;
+    const int32_t* ps = L->positions;
+    if (prune) {
+        vitcop_gather_t g[4] = {{L->h, h_kept, (int64_t)D * 2, (int64_t)D * 2, (int64_t)T * D * 2},
+                                {a_all, a_kept, (int64_t)D * 2, (int64_t)D * 2, (int64_t)T * D * 2},
+                                {k_all, k_kept, (int64_t)kd * 2, (int64_t)kd * 2, (int64_t)T * kd * 2},
+                                {L->positions, pos, 4, 4, (int64_t)T * 4}};
+        rc = launch_compact(g, 4, idx, B, Tp, s);
+        if (rc) return rc;
+        hs = h_kept;
+        as = a_kept;
+        ks = k_kept;
+        ps = pos;
+    } else if (L->positions_out) {
+        rc = hip_status(hipMemcpyAsync(L->positions_out, L->positions, (size_t)B * T * 4, hipMemcpyDeviceToDevice, s),
+                        "copy positions");
+        if (rc) return rc;
+    }
+    rc = launch_gemm_pair(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, s);
+    if (rc) return rc;
+    rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
+    if (rc) return rc;
+    rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
+    if (rc) return rc;
+    rc = launch_gemm(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, nullptr, s);
+    if (rc) return rc;
+    rc = launch_rmsnorm(h1, D, L->ln2, L->eps, bb, D, B * Tp, D, s);
+    if (rc) return rc;
+    rc = launch_gemm_pair(bb, D, L->wg, gate, F, L->wu, up, F, B * Tp, D, s);
+    if (rc) return rc;
+    rc = launch_silu_mul(gate, up, act, (int64_t)B * Tp * F, s);
+    if (rc) return rc;
+    return launch_gemm(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, s);
 }
 
 #pragma GCC visibility pop

@@ -74,4 +74,12 @@ int launch_collab(const uint16_t* feats, int64_t row_stride, int64_t batch_strid
                   uint16_t* out_feats, int32_t* out_index, int32_t* n_out, int32_t* assign, void* ws,
                   hipStream_t s);
 
+// ---- decoder-layer pieces (decoder.hip) -------------------------------------
+int launch_rmsnorm(const uint16_t* x, int64_t x_stride, const uint16_t* w, float eps, uint16_t* y,
+                   int64_t y_stride, int M, int D, hipStream_t s);
+// in place; q [n_tokens,Hq,d] and k [n_tokens,Hkv,d] (either may be null), positions [n_tokens]
+int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_tokens, int Hq, int Hkv, int d,
+                float theta, hipStream_t s);
+int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, hipStream_t s);
+
 }  // namespace vitcop

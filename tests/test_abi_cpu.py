@@ -227,3 +227,35 @@ def test_collab_validation():
     assert call(out=A16 + 8) == binding.VITCOP_EINVAL
     assert call(rs=4000) == binding.VITCOP_EINVAL
     assert call(B=0) == binding.VITCOP_OK
+
+
+def test_decoder_validation():
+    assert lib.vitcop_rmsnorm(A16, 4096, A16, 1e-5, A16, 4096, 10, 4100, None) == binding.VITCOP_EUNSUPPORTED
+    assert lib.vitcop_rmsnorm(A16, 4000, A16, 1e-5, A16, 4096, 10, 4096, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_rmsnorm(None, 4096, A16, 1e-5, A16, 4096, 10, 4096, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_rmsnorm(None, 4096, None, 1e-5, None, 4096, 0, 4096, None) == binding.VITCOP_OK
+    assert lib.vitcop_rope(A16, A16, A16, 1, 10, 4, 2, 100, 10000.0, None) == binding.VITCOP_EUNSUPPORTED
+    assert lib.vitcop_rope(A16, A16, A16, 1, 10, 4, 2, 128, 1.0, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_rope(A16, A16, None, 1, 10, 4, 2, 128, 10000.0, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_rope(None, None, None, 1, 10, 4, 2, 128, 10000.0, None) == binding.VITCOP_OK
+    assert lib.vitcop_silu_mul(A16, A16, A16, 12, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_silu_mul(A16, A16 + 2, A16, 16, None) == binding.VITCOP_EINVAL
+    assert lib.vitcop_silu_mul(None, None, None, 0, None) == binding.VITCOP_OK
+    assert C.sizeof(binding.DecoderLayerT) == 10 * 4 + 2 * 4 + 15 * 8
+
+    def desc(**kw):
+        base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, F=11008, vis_start=35, n_vis=576, keep=64,
+                    eps=1e-5, theta=10000.0, h=A16, positions=A16, ln1=A16, ln2=A16, wq=A16, wk=A16, wv=A16,
+                    wo=A16, wg=A16, wu=A16, wd=A16, y=A16, keep_idx=None, positions_out=None, norms=None)
+        base.update(kw)
+        return binding.DecoderLayerT(**base)
+
+    ws = lib.vitcop_decoder_layer_workspace_bytes
+    run = lib.vitcop_decoder_layer_prefill
+    need = ws(C.byref(desc()))
+    assert need >= 640 * 4096 * 2 * 2 + 128 * 11008 * 2 * 3
+    assert run(C.byref(desc()), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    for bad in (desc(keep=600), desc(Hq=30), desc(theta=0.5), desc(wg=None), desc(positions=None)):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    assert run(C.byref(desc(F=11000)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
+    assert ws(C.byref(desc(d=96))) == 0
