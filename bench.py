@@ -233,6 +233,25 @@ def main():
                             "gram_GFLOP": 2.0 * b2 * n2 * n2 * d2 / 1e9}
             del vf, vp, vr
         kern["stage2"] = stage2
+        # a full decoder layer (RMSNorm, rotary embedding, gated MLP of width 11008 around the same
+        # attention block) with pruning on entry, at the bench shape
+        Fm = 11008
+        dw = {"ln1": torch.ones(D, dtype=torch.bfloat16, device="cuda"),
+              "ln2": torch.ones(D, dtype=torch.bfloat16, device="cuda"),
+              "wq": wq, "wk": wk, "wv": wv, "wo": wo,
+              "wg": torch.randn((Fm, D), dtype=torch.bfloat16, device="cuda") * 0.02,
+              "wu": torch.randn((Fm, D), dtype=torch.bfloat16, device="cuda") * 0.02,
+              "wd": torch.randn((D, Fm), dtype=torch.bfloat16, device="cuda") * 0.02}
+        dpos = torch.arange(T, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+        dec_ms = {}
+        for k_ in sorted(set(c3["keeps"]) | {args.keep, nv}):
+            dp = vc.DecoderLayerPlan(x, dpos, dw, Hq, Hkv, d, vs, nv, k_)
+            dec_ms["unpruned" if k_ == nv else f"keep{k_}"] = ev_time(dp.run, 10)
+            del dp
+        kern["decoder_layer_ms"] = dec_ms
+        out["decoder_layer_speedup_vs_unpruned"] = {k_: dec_ms["unpruned"] / v_ for k_, v_ in dec_ms.items()
+                                                    if k_ != "unpruned"}
+        del dw
         # the layer alone at each keep ratio, and the unpruned layer
         layer_ms = {}
         for k_, p_ in plans.items():
