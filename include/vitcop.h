@@ -318,6 +318,20 @@ typedef struct {
 size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L);
 int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream);
 
+/* ------------------------------------------------------------------------
+ * One decoding step over the KV cache a (pruned) prefill left behind: for the new
+ * token of every sample, out = softmax(scale * K q) V over ALL N cached keys.  This
+ * is the per-token cost that Table 5 reports after pruning: one pass over K and V
+ * per layer, so it shrinks with the cache.  Query head h reads KV head h / (Hq/Hkv).
+ *   q [B,Hq,d], k, v [B,N,Hkv,d] bf16 dense;  out [B,Hq,d] bf16
+ *   lse_out [B,Hq] fp32 natural-log-sum-exp, may be NULL;  scale 0 selects 1/sqrt(d)
+ * d in {64,128}; N >= 1.
+ */
+size_t vitcop_decode_attn_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
+int vitcop_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
+                       float* lse_out, int B, int N, int Hq, int Hkv, int d, float scale,
+                       void* ws, size_t ws_bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

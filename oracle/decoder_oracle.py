@@ -74,3 +74,26 @@ def decoder_layer(h_bits, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_
     y = O.bf16_to_f64(h1) + O.project(m, w["wd"])
     return {"y": y, "y_bits": r16(y), "keep_idx": idx, "norms": norms, "positions": pos_kept,
             "a": a, "q_rope": q_r, "k_rope": k_r, "h1": h1, "m": m}
+
+
+def decode_attention(q_bits, k_bits, v_bits, scale: float | None = None):
+    """One decoding step over a (compacted) KV cache: for every sample and query head,
+    o = softmax(scale * K q) V over ALL cached keys (the new token sees the whole cache).
+    q [B,Hq,d], k, v [B,N,Hkv,d] bf16 bits -> (o float64 [B,Hq,d], lse float64 [B,Hq]).
+    Query head h reads KV head h // (Hq // Hkv).  This is what the per-token cost of Table 5
+    (decoding after a pruned prefill) is made of: one pass over the cache per layer."""
+    q, k, v = O.bf16_to_f64(q_bits), O.bf16_to_f64(k_bits), O.bf16_to_f64(v_bits)
+    B, Hq, d = q.shape
+    Hkv = k.shape[2]
+    scale = 1.0 / np.sqrt(d) if scale is None else scale
+    out = np.zeros((B, Hq, d))
+    lse = np.zeros((B, Hq))
+    for b in range(B):
+        for h in range(Hq):
+            hk = h // (Hq // Hkv)
+            s = k[b, :, hk, :] @ q[b, h] * scale
+            m = s.max()
+            p = np.exp(s - m)
+            out[b, h] = p @ v[b, :, hk, :] / p.sum()
+            lse[b, h] = m + np.log(p.sum())
+    return out, lse

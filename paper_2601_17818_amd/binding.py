@@ -36,6 +36,7 @@ EXPORTS = (
     "vitcop_collab_prune_merge_workspace_bytes", "vitcop_collab_prune_merge",
     "vitcop_rmsnorm", "vitcop_rope", "vitcop_silu_mul",
     "vitcop_decoder_layer_workspace_bytes", "vitcop_decoder_layer_prefill",
+    "vitcop_decode_attn_workspace_bytes", "vitcop_decode_attn",
 )
 
 
@@ -139,6 +140,10 @@ def _load() -> C.CDLL:
     lib.vitcop_decoder_layer_workspace_bytes.argtypes = [C.POINTER(DecoderLayerT)]
     lib.vitcop_decoder_layer_prefill.restype = i32
     lib.vitcop_decoder_layer_prefill.argtypes = [C.POINTER(DecoderLayerT), vp, sz, vp]
+    lib.vitcop_decode_attn_workspace_bytes.restype = sz
+    lib.vitcop_decode_attn_workspace_bytes.argtypes = [i32] * 5
+    lib.vitcop_decode_attn.restype = i32
+    lib.vitcop_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
     return lib
 
 
@@ -362,6 +367,22 @@ def vitcop_silu_mul(gate, up):
     out = torch.empty_like(gate)
     _check(lib.vitcop_silu_mul(_ptr(gate), _ptr(up), _ptr(out), gate.numel(), _stream()))
     return out
+
+
+def vitcop_decode_attn(q, k, v, scale: float = 0.0, want_lse: bool = True, out=None):
+    """q [B,Hq,d], k, v [B,N,Hkv,d] -> (out [B,Hq,d], lse [B,Hq] or None).  ``out`` = (out, lse, ws) reuses buffers."""
+    _dense(q, "q"); _dense(k, "k"); _dense(v, "v")
+    B, Hq, d = q.shape
+    N, Hkv = k.shape[1], k.shape[2]
+    if out is not None:
+        o, lse, ws = out
+    else:
+        o = torch.empty_like(q)
+        lse = torch.empty((B, Hq), dtype=torch.float32, device=q.device) if want_lse else None
+        ws = _ws(max(lib.vitcop_decode_attn_workspace_bytes(B, N, Hq, Hkv, d), 16), q)
+    _check(lib.vitcop_decode_attn(_ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(lse), B, N, Hq, Hkv, d, scale,
+                                  _ptr(ws), ws.numel(), _stream()))
+    return (o, lse, ws) if out is not None else (o, lse)
 
 
 class DecoderLayerPlan:

@@ -661,5 +661,36 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
     return launch_gemm(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, s);
 }
 
+/* ------------------------------------------------------------- decode step */
+
+static int check_decode(int B, int N, int Hq, int Hkv, int d) {
+    REQUIRE(B >= 0 && N >= 1 && Hq >= 1 && Hkv >= 1, VITCOP_EINVAL, "decode_attn: B=%d N=%d Hq=%d Hkv=%d", B, N, Hq, Hkv);
+    REQUIRE(Hq % Hkv == 0, VITCOP_EINVAL, "decode_attn: Hq=%d not a multiple of Hkv=%d", Hq, Hkv);
+    REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "decode_attn: d=%d", d);
+    REQUIRE(Hkv <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "decode_attn: Hkv or B above 65535");
+    REQUIRE((long)N * Hkv * d < (1L << 31), VITCOP_EUNSUPPORTED, "decode_attn: one sample's cache must stay below 2^31 elements");
+    return VITCOP_OK;
+}
+
+size_t vitcop_decode_attn_workspace_bytes(int B, int N, int Hq, int Hkv, int d) {
+    if (check_decode(B, N, Hq, Hkv, d) != VITCOP_OK) return 0;
+    return decode_workspace_bytes(B, N, Hq, Hkv, d);
+}
+
+int vitcop_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse_out,
+                       int B, int N, int Hq, int Hkv, int d, float scale, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_decode(B, N, Hq, Hkv, d);
+    if (rc) return rc;
+    REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "decode_attn: scale");
+    if (B == 0) return VITCOP_OK;
+    REQUIRE(q && k && v && out, VITCOP_EINVAL, "decode_attn: null pointer");
+    REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), VITCOP_EINVAL,
+            "decode_attn: pointers must be 16-byte aligned");
+    const size_t need = decode_workspace_bytes(B, N, Hq, Hkv, d);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "decode_attn: workspace %zu < %zu", ws_bytes, need);
+    if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
+    return launch_decode_attn(q, k, v, out, lse_out, B, N, Hq, Hkv, d, scale, ws, static_cast<hipStream_t>(stream));
+}
+
 #pragma GCC visibility pop
 }  // extern "C"

@@ -82,4 +82,9 @@ int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_to
                 float theta, hipStream_t s);
 int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, hipStream_t s);
 
+// ---- decoding step over the KV cache (decode.hip) ---------------------------
+size_t decode_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
+int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
+                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s);
+
 }  // namespace vitcop

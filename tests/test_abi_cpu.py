@@ -259,3 +259,22 @@ def test_decoder_validation():
         assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
     assert run(C.byref(desc(F=11000)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
     assert ws(C.byref(desc(d=96))) == 0
+
+
+def test_decode_validation():
+    f = lib.vitcop_decode_attn
+    need = lib.vitcop_decode_attn_workspace_bytes(4, 384, 32, 32, 128)
+    assert need >= 4 * 32 * 128 * 4
+
+    def call(q=A16, k=A16, v=A16, out=A16, B=4, N=384, Hq=32, Hkv=32, d=128, scale=0.0, ws=A16, ws_bytes=1 << 30):
+        return f(q, k, v, out, None, B, N, Hq, Hkv, d, scale, ws, ws_bytes, None)
+
+    assert call(ws_bytes=need - 1) == binding.VITCOP_EWORKSPACE
+    assert call(N=0) == binding.VITCOP_EINVAL
+    assert call(Hq=30) == binding.VITCOP_EINVAL
+    assert call(d=96) == binding.VITCOP_EINVAL
+    assert call(scale=-1.0) == binding.VITCOP_EINVAL
+    assert call(k=None) == binding.VITCOP_EINVAL
+    assert call(out=A16 + 4) == binding.VITCOP_EINVAL
+    assert call(B=0) == binding.VITCOP_OK
+    assert lib.vitcop_decode_attn_workspace_bytes(4, 384, 32, 5, 128) == 0

@@ -104,3 +104,22 @@ def test_pruned_layer_is_the_library_layer_on_the_survivors_prefix_property():
     assert np.array_equal(cut["positions"], cut["keep_idx"])
     # and the kept visual tokens are the 9 smallest K-norms
     assert np.array_equal(cut["keep_idx"][0, 20:29] - 20, O.topk_smallest(full["norms"][0], 9))
+
+
+def test_decode_attention_against_pinned_prefill_and_library():
+    # the last row of a causal prefill IS a decode step over the same keys
+    t = I.qkv_tensors(91, 2, 57, 6, 2, 64)
+    full, full_lse = O.attention(t["q"], t["k"], t["v"])
+    o, lse = Dc.decode_attention(t["q"][:, -1], t["k"], t["v"])
+    assert np.allclose(o, full[:, -1], rtol=1e-12, atol=1e-14)
+    assert np.allclose(lse, full_lse[:, :, -1], rtol=1e-12)
+    q = torch.from_numpy(f64(t["q"][:, -1]))[:, :, None, :]                     # [B,Hq,1,d]
+    k = torch.from_numpy(f64(t["k"])).transpose(1, 2).repeat_interleave(3, dim=1)
+    v = torch.from_numpy(f64(t["v"])).transpose(1, 2).repeat_interleave(3, dim=1)
+    want = F.scaled_dot_product_attention(q, k, v)[:, :, 0].numpy()
+    assert np.allclose(o, want, rtol=1e-12, atol=1e-14)
+    # one cached key: the output is its value row; V == 1 gives 1
+    o1, _ = Dc.decode_attention(t["q"][:, 0], t["k"][:, :1], t["v"][:, :1])
+    assert np.array_equal(o1[:, 0], f64(t["v"])[:, 0, 0])
+    ones = bits(np.ones((2, 57, 2, 64)))
+    assert np.allclose(Dc.decode_attention(t["q"][:, 3], t["k"], ones)[0], 1.0)
