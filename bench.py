@@ -233,6 +233,24 @@ def main():
                             "gram_GFLOP": 2.0 * b2 * n2 * n2 * d2 / 1e9}
             del vf, vp, vr
         kern["stage2"] = stage2
+        # one decoding step over the KV cache the prefill leaves behind (per layer): pruned and
+        # unpruned cache length of this workload, and a streaming case (32 samples x 4096 keys,
+        # 2.1 GB of K and V) for the HBM fraction; algorithmic bytes = K and V read once
+        dec = {}
+        for name, b_d, n_d in (("pruned", B, Tp), ("unpruned", B, T), ("stream", 32, 4096)):
+            kk = torch.randn((b_d, n_d, Hkv, d), dtype=torch.bfloat16, device="cuda")
+            vv = torch.randn((b_d, n_d, Hkv, d), dtype=torch.bfloat16, device="cuda")
+            qq = torch.randn((b_d, Hq, d), dtype=torch.bfloat16, device="cuda")
+            bufs = vc.vitcop_decode_attn(qq, kk, vv)
+            bufs = (bufs[0], bufs[1], torch.empty(vc.lib.vitcop_decode_attn_workspace_bytes(b_d, n_d, Hq, Hkv, d),
+                                                  dtype=torch.uint8, device="cuda"))
+            t_d = ev_time(lambda: vc.vitcop_decode_attn(qq, kk, vv, out=bufs), 20, warm=5)
+            dec[name + "_us"] = t_d * 1e3
+            dec[name + "_GBps"] = 2.0 * b_d * n_d * Hkv * d * 2 / (t_d * 1e-3) / 1e9
+            del kk, vv, qq, bufs
+        dec["stream_frac_hbm"] = dec["stream_GBps"] / HBM_PEAK_GBPS
+        dec["speedup_pruned_cache"] = dec["unpruned_us"] / dec["pruned_us"]
+        kern["decode_step"] = dec
         # a full decoder layer (RMSNorm, rotary embedding, gated MLP of width 11008 around the same
         # attention block) with pruning on entry, at the bench shape
         Fm = 11008
