@@ -274,13 +274,14 @@ __device__ __forceinline__ void static_for(F&& f) {
 //   MAX5 five 3-input maxima of the 16 scores; MAX3 their reduction to one; SWAP exchange
 //   between the two wavefront halves (they hold different keys of the same query); REF0..REF6
 //   new reference maximum and alpha = exp2(old - new); FMA argument of an exponential; EXP;
-//   ADD2 sum of two neighbours; CVT pack two probabilities to bf16; TREE reduction of the
-//   eight pair sums and update of the running denominator.
+//   ADD2 sum of two neighbours, added to one of two running partial sums (few values stay
+//   live); CVT pack two probabilities to bf16; TREE the two partial sums combined and the
+//   update of the running denominator.
 enum SmKind : int { SM_MASK, SM_MAX5, SM_MAX3, SM_SWAP, SM_REF, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
 struct SmOp {
     int kind, u, i;
 };
-constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 8);
+constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 2);
 struct SmTable {
     SmOp op[SM_NOPS];
     int start[33];       // run r is op[start[r]] .. op[start[r+1]-1]
@@ -310,19 +311,22 @@ constexpr SmTable make_sm_table(bool masked) {
             for (int i = 0; i < 2; ++i) t.op[n++] = {SM_ADD2, g / 4, 2 * (g % 4) + i};
             for (int i = 0; i < 2; ++i) t.op[n++] = {SM_CVT, g / 4, 2 * (g % 4) + i};
         }
-        if (ph == 7 || ph == 8)                     // query block 0: pair sums done in phase 5
-            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_TREE, 0, 4 * (ph - 7) + i};
-        if (ph == 11 || ph == 12)                   // query block 1: pair sums done in phase 9
-            for (int i = 0; i < 4; ++i) t.op[n++] = {SM_TREE, 1, 4 * (ph - 11) + i};
+        if (ph == 7)                                // query block 0: pair sums done in phase 5
+            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, 0, i};
+        if (ph == 11)                               // query block 1: pair sums done in phase 9
+            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, 1, i};
     }
     // split into 32 runs of about equal issue time (a mask is a compare and a select, an
-    // exponential takes twice as long as a plain instruction)
+    // exponential takes twice as long as a plain instruction, a pair sum from the third on is two adds)
     int total = 0;
-    for (int k = 0; k < n; ++k) total += (t.op[k].kind == SM_MASK || t.op[k].kind == SM_EXP) ? 2 : 1;
+    auto weight = [](const SmOp& o) {
+        return (o.kind == SM_MASK || o.kind == SM_EXP || (o.kind == SM_ADD2 && o.i >= 2)) ? 2 : 1;
+    };
+    for (int k = 0; k < n; ++k) total += weight(t.op[k]);
     int acc = 0, r = 0;
     t.start[0] = 0;
     for (int k = 0; k < n; ++k) {
-        acc += (t.op[k].kind == SM_MASK || t.op[k].kind == SM_EXP) ? 2 : 1;
+        acc += weight(t.op[k]);
         while (r < 31 && acc * 32 >= total * (r + 1)) t.start[++r] = k + 1;
     }
     while (r < 32) t.start[++r] = n;
@@ -524,7 +528,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         }
         // state of the vector work (see SmKind)
         float m5[2][5], m3[2][3], mx[2], ref[2][4], alpha[2] = {1.f, 1.f};
-        float e[2][16], p2[2][8], tr[2][7];
+        float e[2][16], ps[2][2];
         uint32_t pk[2][8];
         auto vector_op = [&](auto kc, auto uc, auto ic) __attribute__((always_inline)) {
             constexpr int kind = kc.value, u = uc.value, i = ic.value;
@@ -556,15 +560,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             } else if constexpr (kind == SM_EXP) {
                 e[u][i] = __builtin_amdgcn_exp2f(e[u][i]);
             } else if constexpr (kind == SM_ADD2) {
-                p2[u][i] = e[u][2 * i] + e[u][2 * i + 1];
+                const float pair = e[u][2 * i] + e[u][2 * i + 1];
+                if constexpr (i < 2) ps[u][i] = pair;
+                else ps[u][i & 1] += pair;
             } else if constexpr (kind == SM_CVT) {
                 pk[u][i] = pack_bf16(e[u][2 * i], e[u][2 * i + 1]);
             } else {
-                if constexpr (i < 4) tr[u][i] = p2[u][2 * i] + p2[u][2 * i + 1];
-                if constexpr (i == 4) tr[u][4] = tr[u][0] + tr[u][1];
-                if constexpr (i == 5) tr[u][5] = tr[u][2] + tr[u][3];
-                if constexpr (i == 6) tr[u][6] = tr[u][4] + tr[u][5];
-                if constexpr (i == 7) l_run[u] = fmaf(l_run[u], alpha[u], tr[u][6]);
+                if constexpr (i == 0) ps[u][0] += ps[u][1];
+                if constexpr (i == 1) l_run[u] = fmaf(l_run[u], alpha[u], ps[u][0]);
             }
         };
         // S(c+1) accumulators
