@@ -318,6 +318,36 @@ typedef struct {
 size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L);
 int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream);
 
+/* Whole-model prefill over full decoder layers (layer loop of Alg. 1, Eq. 8): n_layers decoder
+ * layers on one batch, pruning on entry to layer prune_layer[s] (0-indexed) down to prune_keep[s]
+ * visual tokens by that layer's own K-norms (the Stage III rule; the paper's own schedule prunes
+ * at layers 2 and 22, Sec. 4.1).  Weights of layer l: ln1[l], ..., wd[l] (host arrays of device
+ * pointers).  The hidden state is carried between layers in bf16.
+ *   h [B,T,D] in, positions [B,T] in;  y_out [B,T_final,D];  positions_out [B,T_final] (may be NULL)
+ */
+typedef struct {
+    int B, T, D, Hq, Hkv, d, F, vis_start, n_vis;
+    int n_layers, n_stages;
+    float eps, theta;
+    const int* prune_layer;           /* host, ascending */
+    const int* prune_keep;            /* host, non-increasing, <= n_vis */
+    const uint16_t* h;
+    const int32_t* positions;
+    const uint16_t* const* ln1;       /* host arrays, n_layers device pointers each */
+    const uint16_t* const* ln2;
+    const uint16_t* const* wq;
+    const uint16_t* const* wk;
+    const uint16_t* const* wv;
+    const uint16_t* const* wo;
+    const uint16_t* const* wg;
+    const uint16_t* const* wu;
+    const uint16_t* const* wd;
+    uint16_t* y_out;
+    int32_t* positions_out;
+} vitcop_decoder_schedule_t;
+size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S);
+int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * One decoding step over the KV cache a (pruned) prefill left behind: for the new
  * token of every sample, out = softmax(scale * K q) V over ALL N cached keys.  This

@@ -97,3 +97,29 @@ def decode_attention(q_bits, k_bits, v_bits, scale: float | None = None):
             out[b, h] = p @ v[b, :, hk, :] / p.sum()
             lse[b, h] = m + np.log(p.sum())
     return out, lse
+
+
+def decoder_schedule(h_bits, layer_weights, schedule, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int,
+                     positions, eps: float = 1e-5, theta: float = 10000.0, keep_lists=None):
+    """Whole-model prefill (layer loop of Alg. 1, Eq. 8): decoder layers in sequence, 0-indexed, pruning on
+    entry to the scheduled layers by that layer's own K-norms; the hidden state is carried in bf16.
+    ``schedule``: ((layer, keep), ...); ``keep_lists``: optional {layer: keep_idx} overriding the lists
+    computed here.  Returns the final hidden state (float64, bits), positions, and per pruning layer the
+    keep list and the norms it was taken from."""
+    h = np.asarray(h_bits)
+    pos = np.asarray(positions)
+    stages = dict(schedule)
+    cur_vis = n_vis
+    kept, norms = {}, {}
+    out = None
+    for l, w in enumerate(layer_weights):
+        keep = stages.get(l, cur_vis)
+        forced = None if keep_lists is None else keep_lists.get(l)
+        out = decoder_layer(h, w, Hq, Hkv, d, vis_start, cur_vis, keep, pos, eps, theta, keep_idx=forced)
+        if l in stages:
+            kept[l] = out["keep_idx"]
+            norms[l] = out["norms"]
+            pos = out["positions"]
+            cur_vis = keep
+        h = out["y_bits"]
+    return {"y": out["y"], "y_bits": h, "positions": pos, "keep_lists": kept, "norms": norms}

@@ -37,6 +37,7 @@ EXPORTS = (
     "vitcop_rmsnorm", "vitcop_rope", "vitcop_silu_mul",
     "vitcop_decoder_layer_workspace_bytes", "vitcop_decoder_layer_prefill",
     "vitcop_decode_attn_workspace_bytes", "vitcop_decode_attn",
+    "vitcop_decoder_schedule_workspace_bytes", "vitcop_decoder_schedule_prefill",
 )
 
 
@@ -69,6 +70,19 @@ class DecoderLayerT(C.Structure):
                 ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p), ("wo", C.c_void_p),
                 ("wg", C.c_void_p), ("wu", C.c_void_p), ("wd", C.c_void_p), ("y", C.c_void_p),
                 ("keep_idx", C.c_void_p), ("positions_out", C.c_void_p), ("norms", C.c_void_p)]
+
+
+_DEC_WEIGHTS = ("ln1", "ln2", "wq", "wk", "wv", "wo", "wg", "wu", "wd")
+
+
+class DecoderScheduleT(C.Structure):
+    _fields_ = ([(n, C.c_int) for n in ("B", "T", "D", "Hq", "Hkv", "d", "F", "vis_start", "n_vis",
+                                         "n_layers", "n_stages")] +
+                [("eps", C.c_float), ("theta", C.c_float),
+                 ("prune_layer", C.POINTER(C.c_int)), ("prune_keep", C.POINTER(C.c_int)),
+                 ("h", C.c_void_p), ("positions", C.c_void_p)] +
+                [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
+                [("y_out", C.c_void_p), ("positions_out", C.c_void_p)])
 
 
 class ScheduleT(C.Structure):
@@ -144,6 +158,10 @@ def _load() -> C.CDLL:
     lib.vitcop_decode_attn_workspace_bytes.argtypes = [i32] * 5
     lib.vitcop_decode_attn.restype = i32
     lib.vitcop_decode_attn.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, i32, f32, vp, sz, vp]
+    lib.vitcop_decoder_schedule_workspace_bytes.restype = sz
+    lib.vitcop_decoder_schedule_workspace_bytes.argtypes = [C.POINTER(DecoderScheduleT)]
+    lib.vitcop_decoder_schedule_prefill.restype = i32
+    lib.vitcop_decoder_schedule_prefill.argtypes = [C.POINTER(DecoderScheduleT), vp, sz, vp]
     return lib
 
 
@@ -467,6 +485,37 @@ def vitcop_layer_prefill(x, wq, wk, wv, wo, Hq, Hkv, d, vis_start, n_vis, keep, 
     plan.run()
     return {"y": plan.y, "keep_idx": plan.keep_idx, "norms": plan.norms,
             "positions": plan.positions_out}
+
+
+class DecoderSchedulePlan:
+    """Pre-marshalled vitcop_decoder_schedule_prefill call.  ``weights``: one dict per layer with the device
+    tensors ln1, ln2, wq, wk, wv, wo, wg, wu, wd; ``schedule``: ((layer, keep), ...)."""
+
+    def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, schedule,
+                 eps: float = 1e-5, theta: float = 10000.0):
+        B, T, D = h.shape
+        n_layers = len(weights)
+        F = weights[0]["wg"].shape[0]
+        self.keepalive = (h, positions, weights)
+        layers = [int(s[0]) for s in schedule]
+        keeps = [int(s[1]) for s in schedule]
+        self._pl = (C.c_int * max(len(layers), 1))(*layers)
+        self._pk = (C.c_int * max(len(keeps), 1))(*keeps)
+        self._w = [(C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights]) for n in _DEC_WEIGHTS]
+        T_final = T - n_vis + (keeps[-1] if keeps else n_vis)
+        self.y = torch.empty((B, T_final, D), dtype=h.dtype, device=h.device)
+        self.positions = torch.empty((B, T_final), dtype=torch.int32, device=h.device)
+        self.desc = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
+                                     self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self.y),
+                                     _ptr(self.positions))
+        nb = lib.vitcop_decoder_schedule_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, h)
+
+    def run(self):
+        _check(lib.vitcop_decoder_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        return self.y
 
 
 class SchedulePlan:

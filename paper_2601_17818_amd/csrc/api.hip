@@ -661,6 +661,89 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
     return launch_gemm(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, s);
 }
 
+static vitcop_decoder_layer_t first_decoder_layer(const vitcop_decoder_schedule_t* S) {
+    vitcop_decoder_layer_t L{};
+    L.B = S->B; L.T = S->T; L.D = S->D; L.Hq = S->Hq; L.Hkv = S->Hkv; L.d = S->d; L.F = S->F;
+    L.vis_start = S->vis_start; L.n_vis = S->n_vis; L.keep = S->n_vis; L.eps = S->eps; L.theta = S->theta;
+    return L;
+}
+
+static int check_decoder_schedule(const vitcop_decoder_schedule_t* S) {
+    REQUIRE(S, VITCOP_EINVAL, "decoder_schedule: descriptor is null");
+    REQUIRE(S->n_layers >= 1 && S->n_stages >= 0, VITCOP_EINVAL, "decoder_schedule: n_layers=%d n_stages=%d",
+            S->n_layers, S->n_stages);
+    REQUIRE(S->n_stages == 0 || (S->prune_layer && S->prune_keep), VITCOP_EINVAL,
+            "decoder_schedule: null stage arrays");
+    int prev_layer = -1, prev_keep = S->n_vis;
+    for (int i = 0; i < S->n_stages; ++i) {
+        REQUIRE(S->prune_layer[i] > prev_layer && S->prune_layer[i] < S->n_layers, VITCOP_EINVAL,
+                "decoder_schedule: stage %d at layer %d (must ascend within [0,%d))", i, S->prune_layer[i],
+                S->n_layers);
+        REQUIRE(S->prune_keep[i] >= 0 && S->prune_keep[i] <= prev_keep, VITCOP_EINVAL,
+                "decoder_schedule: stage %d keeps %d of %d", i, S->prune_keep[i], prev_keep);
+        prev_layer = S->prune_layer[i];
+        prev_keep = S->prune_keep[i];
+    }
+    const vitcop_decoder_layer_t L = first_decoder_layer(S);
+    return check_decoder_layer(&L);
+}
+
+size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S) {
+    if (check_decoder_schedule(S) != VITCOP_OK) return 0;
+    const vitcop_decoder_layer_t L = first_decoder_layer(S);
+    const size_t B = S->B, T = S->T, D = S->D;
+    return vitcop_decoder_layer_workspace_bytes(&L) + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
+}
+
+int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_decoder_schedule(S);
+    if (rc) return rc;
+    REQUIRE(S->h && S->positions && S->y_out && S->ln1 && S->ln2 && S->wq && S->wk && S->wv && S->wo && S->wg &&
+                S->wu && S->wd,
+            VITCOP_EINVAL, "decoder_schedule: null pointer");
+    const size_t need = vitcop_decoder_schedule_workspace_bytes(S);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "decoder_schedule: workspace needs %zu bytes", need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t B = S->B, T = S->T, D = S->D;
+    Carver c(ws);
+    uint16_t* hbuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
+    int32_t* pbuf[2] = {c.take<int32_t>(B * T * 4), c.take<int32_t>(B * T * 4)};
+    void* lws = c.base + c.used;
+    const size_t lws_bytes = ws_bytes - c.used;
+
+    const uint16_t* h = S->h;
+    const int32_t* pos = S->positions;
+    int cur_T = S->T, cur_vis = S->n_vis, stage = 0, pp = 0;
+    for (int l = 0; l < S->n_layers; ++l) {
+        vitcop_decoder_layer_t L = first_decoder_layer(S);
+        L.T = cur_T; L.n_vis = cur_vis; L.keep = cur_vis;
+        L.h = h; L.positions = pos;
+        L.ln1 = S->ln1[l]; L.ln2 = S->ln2[l]; L.wq = S->wq[l]; L.wk = S->wk[l]; L.wv = S->wv[l]; L.wo = S->wo[l];
+        L.wg = S->wg[l]; L.wu = S->wu[l]; L.wd = S->wd[l];
+        const bool last = l + 1 == S->n_layers;
+        const bool prune_here = stage < S->n_stages && S->prune_layer[stage] == l;
+        if (prune_here) {
+            L.keep = S->prune_keep[stage++];
+            L.positions_out = pbuf[pp];
+        }
+        L.y = last ? S->y_out : hbuf[l & 1];
+        rc = vitcop_decoder_layer_prefill(&L, lws, lws_bytes, stream);
+        if (rc) return rc;
+        if (prune_here) {
+            pos = pbuf[pp];
+            pp ^= 1;
+            cur_T = cur_T - cur_vis + L.keep;
+            cur_vis = L.keep;
+        }
+        h = L.y;
+    }
+    if (S->positions_out) {
+        rc = hip_status(hipMemcpyAsync(S->positions_out, pos, (size_t)B * cur_T * 4, hipMemcpyDeviceToDevice, s),
+                        "copy positions");
+    }
+    return rc;
+}
+
 /* ------------------------------------------------------------- decode step */
 
 static int check_decode(int B, int N, int Hq, int Hkv, int d) {

@@ -261,6 +261,31 @@ def test_decoder_validation():
     assert ws(C.byref(desc(d=96))) == 0
 
 
+def test_decoder_schedule_validation():
+    assert C.sizeof(binding.DecoderScheduleT) == 11 * 4 + 2 * 4 + 4 + 15 * 8      # 4 bytes of padding before the pointers
+    ptrs = (C.c_void_p * 4)(*[A16] * 4)
+
+    def desc(layers=(1, 3), keeps=(128, 32), **kw):
+        base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, F=11008, vis_start=35, n_vis=576, n_layers=4,
+                    n_stages=len(layers), eps=1e-5, theta=10000.0,
+                    prune_layer=(C.c_int * len(layers))(*layers), prune_keep=(C.c_int * len(keeps))(*keeps),
+                    h=A16, positions=A16, y_out=A16, positions_out=None)
+        base.update({n: C.cast(ptrs, C.POINTER(C.c_void_p)) for n in binding._DEC_WEIGHTS})
+        base.update(kw)
+        return binding.DecoderScheduleT(**base)
+
+    ws = lib.vitcop_decoder_schedule_workspace_bytes
+    run = lib.vitcop_decoder_schedule_prefill
+    need = ws(C.byref(desc()))
+    assert need >= 2 * 640 * 4096 * 2 + 640 * 4096 * 2 * 2
+    assert run(C.byref(desc()), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    for bad in (desc(layers=(3, 1)), desc(layers=(1, 4)), desc(keeps=(32, 128)), desc(keeps=(600, 32)),
+                desc(n_layers=0), desc(h=None), desc(wq=None), desc(Hq=30)):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    assert ws(C.byref(desc(layers=(3, 1)))) == 0
+    assert ws(C.byref(desc(layers=(), keeps=()))) > 0
+
+
 def test_decode_validation():
     f = lib.vitcop_decode_attn
     need = lib.vitcop_decode_attn_workspace_bytes(4, 384, 32, 32, 128)

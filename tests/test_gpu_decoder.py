@@ -107,3 +107,47 @@ def test_decoder_layer_deterministic_and_prefix(vc):
     again = run_layer(vc, c, pos, 40, 260, 50)
     assert torch.equal(cut["y"], again["y"])
     assert torch.equal(cut["y"][:, :40], full["y"][:, :40])
+
+
+def schedule_case(seed, B, T, D, Hq, Hkv, d, F, vs, nv, n_layers):
+    """Layers whose K projection amplifies the first D/8 input channels, and visual rows that carry a
+    log-normal share of their energy there: after RMSNorm the K-norms are spread, not concentrated."""
+    layers = [I.decoder_inputs(seed + 1 + l, B, T, D, Hq, Hkv, d, F)["w"] for l in range(n_layers)]
+    for w in layers:
+        wk = I.bf16_bits_to_f32(w["wk"])
+        wk[:, : D // 8] *= 4.0
+        w["wk"] = I.f32_to_bf16_bits(wk)
+        for name in ("wo", "wd"):          # small output projections keep the residual stream bounded
+            w[name] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w[name]) * np.float32(0.25))
+    h = I.bf16_bits_to_f32(I.decoder_inputs(seed, B, T, D, Hq, Hkv, d, F)["h"])
+    gain, _ = I.lognormal_gains(seed, B, nv, sigma=1.0, outlier_frac=0.0)
+    h[:, vs:vs + nv, : D // 8] *= gain[:, :, None].astype(np.float32)
+    return I.f32_to_bf16_bits(h), layers
+
+
+def test_decoder_schedule_matches_oracle(vc):
+    # 6 layers, pruning on entry to layers 1 and 4.  Seeds are searched (on the oracle) for cuts
+    # without near-ties at both stages; then positions and outputs must match the oracle's.
+    B, T, D, Hq, Hkv, d, F, vs, nv = 1, 260, 256, 4, 2, 128, 352, 12, 230
+    schedule = ((1, 120), (4, 40))
+    pos = np.arange(T)[None].astype(np.int32)
+    for seed in range(9830, 10000):
+        h, layers = schedule_case(seed, B, T, D, Hq, Hkv, d, F, vs, nv, 6)
+        ref = Dc.decoder_schedule(h, layers, schedule, Hq, Hkv, d, vs, nv, pos)
+        if all(O.tie_band(ref["norms"][l][0], k, False, 4e-3).sum() <= 1 for l, k in schedule):
+            break
+    else:
+        raise AssertionError("no seed with gap-free cuts")
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    plan = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, schedule)
+    plan.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(plan.positions.cpu().numpy(), ref["positions"])
+    assert_attention_close(host_f64(plan.y), ref["y"], "decoder schedule output")
+    # the unpruned schedule has no decisions
+    plan0 = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, ())
+    plan0.run()
+    torch.cuda.synchronize()
+    ref0 = Dc.decoder_schedule(h, layers, (), Hq, Hkv, d, vs, nv, pos)
+    assert_attention_close(host_f64(plan0.y), ref0["y"], "unpruned decoder schedule")
+    assert np.array_equal(plan0.positions.cpu().numpy(), pos)
