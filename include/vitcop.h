@@ -139,13 +139,21 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
  *   part p holds, per row, the sum of squares of the ROUNDED outputs of a
  *   fixed group of columns; the P parts added in index order give
  *   sum_n y[m,n]^2, i.e. the squared K-norm of Eq. 4 without re-reading K.
+ *   ws: NULL, or device scratch of ws_bytes >= vitcop_project_workspace_bytes(M,N,K)
+ *   (16-byte aligned, contents undefined afterwards).  With few rows (M <= 256: the
+ *   sequence after pruning) the weights are nearly all of the traffic; given the
+ *   scratch, such a call streams W once through a split-K kernel whose fp32 partials
+ *   live there and are added in a fixed order.  workspace_bytes is 0 where that path
+ *   does not apply; without scratch, or with too little, the call uses the big tiles.
  * K % 32 == 0, N % 16 == 0, strides multiples of 8; each operand below 2^31 elements.
  */
 int vitcop_project_sumsq_parts(int N);
+size_t vitcop_project_workspace_bytes(int M, int N, int K);
 int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w,
                    uint16_t* y, int64_t y_row_stride,
                    const uint16_t* residual, int64_t res_row_stride,
-                   int M, int N, int K, float* sumsq_parts, void* stream);
+                   int M, int N, int K, float* sumsq_parts,
+                   void* ws, size_t ws_bytes, void* stream);
 
 /* Selection from the projection's side output: adds the P parts in index
  * order, takes the square root, writes norms_out (may be NULL) and ranks as

@@ -29,7 +29,8 @@ EXPORTS = (
     "vitcop_knorm_select_workspace_bytes", "vitcop_knorm_select",
     "vitcop_compact",
     "vitcop_prefill_attn_workspace_bytes", "vitcop_prefill_attn",
-    "vitcop_project_sumsq_parts", "vitcop_project", "vitcop_select_from_sumsq",
+    "vitcop_project_sumsq_parts", "vitcop_project_workspace_bytes", "vitcop_project",
+    "vitcop_select_from_sumsq",
     "vitcop_layer_workspace_bytes", "vitcop_layer_prefill",
     "vitcop_schedule_workspace_bytes", "vitcop_schedule_prefill",
     "vitcop_vic_cluster_workspace_bytes", "vitcop_vic_cluster",
@@ -124,7 +125,9 @@ def _load() -> C.CDLL:
     lib.vitcop_project_sumsq_parts.restype = i32
     lib.vitcop_project_sumsq_parts.argtypes = [i32]
     lib.vitcop_project.restype = i32
-    lib.vitcop_project.argtypes = [vp, i64, vp, vp, i64, vp, i64, i32, i32, i32, vp, vp]
+    lib.vitcop_project.argtypes = [vp, i64, vp, vp, i64, vp, i64, i32, i32, i32, vp, vp, sz, vp]
+    lib.vitcop_project_workspace_bytes.restype = sz
+    lib.vitcop_project_workspace_bytes.argtypes = [i32, i32, i32]
     lib.vitcop_select_from_sumsq.restype = i32
     lib.vitcop_select_from_sumsq.argtypes = [vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp]
     lib.vitcop_layer_workspace_bytes.restype = sz
@@ -285,10 +288,11 @@ def vitcop_project_sumsq_parts(N: int) -> int:
     return lib.vitcop_project_sumsq_parts(N)
 
 
-def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None):
+def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None, scratch: bool = True):
     """x [M,K], w [N,K] -> (y [M,N], sumsq_parts [P,M] fp32 or None).
 
-    ``out`` = (y, parts) reuses buffers from an earlier call.
+    ``out`` = (y, parts) reuses buffers from an earlier call; ``scratch`` = False withholds the
+    workspace, so that a call with few rows also runs on the big tiles.
     """
     _dense(x, "x"); _dense(w, "w")
     M, K = x.shape
@@ -302,8 +306,10 @@ def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None):
             parts = torch.empty((vitcop_project_sumsq_parts(N), M), dtype=torch.float32, device=x.device)
     if residual is not None:
         _dense(residual, "residual")
+    nb = lib.vitcop_project_workspace_bytes(M, N, K) if scratch else 0
+    ws = _ws(nb, x) if nb else None
     _check(lib.vitcop_project(_ptr(x), K, _ptr(w), _ptr(y), N, _ptr(residual), N, M, N, K,
-                              _ptr(parts), _stream()))
+                              _ptr(parts), _ptr(ws), nb, _stream()))
     return y, parts
 
 

@@ -209,9 +209,14 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
 
 int vitcop_project_sumsq_parts(int N) { return N > 0 ? gemm_sumsq_parts(N) : 0; }
 
+size_t vitcop_project_workspace_bytes(int M, int N, int K) {
+    if (M < 1 || N < 1 || K < 1 || K % 32 != 0 || N % 16 != 0) return 0;
+    return gemm_workspace_bytes(M, N, K);
+}
+
 int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w, uint16_t* y,
                    int64_t y_row_stride, const uint16_t* residual, int64_t res_row_stride, int M, int N,
-                   int K, float* sumsq_parts, void* stream) {
+                   int K, float* sumsq_parts, void* ws, size_t ws_bytes, void* stream) {
     REQUIRE(M >= 0 && N >= 0 && K >= 1, VITCOP_EINVAL, "project: M=%d N=%d K=%d", M, N, K);
     REQUIRE(K % 32 == 0 && N % 16 == 0, VITCOP_EUNSUPPORTED, "project: K=%d %% 32, N=%d %% 16", K, N);
     REQUIRE(x_row_stride >= K && x_row_stride % 8 == 0 && y_row_stride >= N && y_row_stride % 8 == 0,
@@ -224,8 +229,9 @@ int vitcop_project(const uint16_t* x, int64_t x_row_stride, const uint16_t* w, u
     REQUIRE(x && w && y, VITCOP_EINVAL, "project: null pointer");
     REQUIRE(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(residual), VITCOP_EINVAL,
             "project: pointers must be 16-byte aligned");
-    return launch_gemm(x, x_row_stride, w, y, y_row_stride, residual, res_row_stride, M, N, K, sumsq_parts,
-                       static_cast<hipStream_t>(stream));
+    REQUIRE(aligned16(ws), VITCOP_EINVAL, "project: workspace must be 16-byte aligned");
+    return launch_gemm_ws(x, x_row_stride, w, y, y_row_stride, residual, res_row_stride, M, N, K, sumsq_parts,
+                          ws, ws_bytes, static_cast<hipStream_t>(stream));
 }
 
 /* ------------------------------------------------------------------ layer */
@@ -247,6 +253,19 @@ static int check_layer(const vitcop_layer_t* L) {
     return VITCOP_OK;
 }
 
+// Scratch of the few-row projection path: the largest need among a layer's projections (rows
+// before and after pruning; F = 0: no MLP).
+static size_t layer_gemm_scratch(int M_all, int M_kept, int D, int qd, int kd, int F) {
+    size_t n = gemm_workspace_bytes(M_all, kd, D);                               // K
+    n = std::max(n, gemm_workspace_bytes(M_kept, qd + kd, D));                   // Q and V
+    n = std::max(n, gemm_workspace_bytes(M_kept, D, qd));                        // O
+    if (F > 0) {
+        n = std::max(n, gemm_workspace_bytes(M_kept, 2 * F, D));                 // gate and up
+        n = std::max(n, gemm_workspace_bytes(M_kept, D, F));                     // down
+    }
+    return n;
+}
+
 size_t vitcop_layer_workspace_bytes(const vitcop_layer_t* L) {
     if (check_layer(L) != VITCOP_OK) return 0;
     const size_t B = L->B, T = L->T, Tp = L->T - L->n_vis + L->keep, D = L->D;
@@ -260,6 +279,7 @@ size_t vitcop_layer_workspace_bytes(const vitcop_layer_t* L) {
     n += up256(B * Tp * qd * 2);                                        // Q
     n += up256(B * Tp * kd * 2);                                        // V
     n += up256(B * Tp * qd * 2);                                        // attention output
+    n += layer_gemm_scratch((int)(B * T), (int)(B * Tp), (int)D, (int)qd, (int)kd, 0);
     return n;
 }
 
@@ -289,6 +309,8 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
     uint16_t* qb = c.take<uint16_t>((size_t)B * Tp * qd * 2);
     uint16_t* vb = c.take<uint16_t>((size_t)B * Tp * kd * 2);
     uint16_t* ob = c.take<uint16_t>((size_t)B * Tp * qd * 2);
+    const size_t gs_bytes = layer_gemm_scratch(B * T, B * Tp, D, qd, kd, 0);
+    void* gs = c.take<char>(gs_bytes);
     int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
 
     // K of every token of the layer input, squared norms as a side output
@@ -296,7 +318,7 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
         rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_begin), s), "hipEventRecord");
         if (rc) return rc;
     }
-    rc = launch_gemm(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, s);
+    rc = launch_gemm_ws(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, gs, gs_bytes, s);
     if (rc) return rc;
     if (L->ev_kproj_end) {
         rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_end), s), "hipEventRecord");
@@ -326,11 +348,11 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
         if (rc) return rc;
     }
     // Q and V of the survivors only
-    rc = launch_gemm_pair(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, s);
+    rc = launch_gemm_pair_ws(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
-    return launch_gemm(ob, qd, L->wo, L->y, D, L->residual ? xs : nullptr, D, B * Tp, D, qd, nullptr, s);
+    return launch_gemm_ws(ob, qd, L->wo, L->y, D, L->residual ? xs : nullptr, D, B * Tp, D, qd, nullptr, gs, gs_bytes, s);
 }
 
 /* --------------------------------------------------------------- schedule */
@@ -361,8 +383,20 @@ size_t vitcop_schedule_workspace_bytes(const vitcop_schedule_t* S) {
     vitcop_layer_t L{};
     L.B = S->B; L.T = S->T; L.D = S->D; L.Hq = S->Hq; L.Hkv = S->Hkv; L.d = S->d;
     L.vis_start = S->vis_start; L.n_vis = S->n_vis; L.keep = S->n_vis;
+    // the largest layer workspace along the schedule (the few-row projection path only needs its
+    // scratch once pruning has cut the sequence)
+    size_t layer_max = 0;
+    int stage = 0;
+    for (int l = 0; l < S->n_layers; ++l) {
+        L.keep = L.n_vis;
+        const bool prune_here = stage < S->n_stages && S->prune_layer[stage] == l;
+        if (prune_here) L.keep = S->prune_keep[stage++];
+        layer_max = std::max(layer_max, vitcop_layer_workspace_bytes(&L));
+        L.T = L.T - L.n_vis + L.keep;
+        L.n_vis = L.keep;
+    }
     const size_t B = S->B, T = S->T, D = S->D;
-    return vitcop_layer_workspace_bytes(&L) + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
+    return layer_max + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
 }
 
 __global__ void iota_kernel(int32_t* p, int T, int64_t n) {
@@ -573,6 +607,7 @@ size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L) {
     n += up256(B * Tp * qd * 2);                                        // attention output
     n += 2 * up256(B * Tp * D * 2);                                     // h1, b
     n += 3 * up256(B * Tp * F * 2);                                     // gate, up, silu(gate) * up
+    n += layer_gemm_scratch((int)(B * T), (int)(B * Tp), (int)D, (int)qd, (int)kd, (int)F);
     return n;
 }
 
@@ -612,13 +647,15 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
     uint16_t* gate = c.take<uint16_t>((size_t)B * Tp * F * 2);
     uint16_t* up = c.take<uint16_t>((size_t)B * Tp * F * 2);
     uint16_t* act = c.take<uint16_t>((size_t)B * Tp * F * 2);
+    const size_t gs_bytes = layer_gemm_scratch(B * T, B * Tp, D, qd, kd, F);
+    void* gs = c.take<char>(gs_bytes);
     int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
     int32_t* pos = L->positions_out ? L->positions_out : pos_ws;
 
     rc = launch_rmsnorm(L->h, D, L->ln1, L->eps, a_all, D, B * T, D, s);
     if (rc) return rc;
     // K of every token, squared norms (before the rotary embedding) as a side output
-    rc = launch_gemm(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, s);
+    rc = launch_gemm_ws(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, gs, gs_bytes, s);
     if (rc) return rc;
     if (want_sel) {
         rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T, L->vis_start,
@@ -644,21 +681,21 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
                         "copy positions");
         if (rc) return rc;
     }
-    rc = launch_gemm_pair(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, s);
+    rc = launch_gemm_pair_ws(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
     if (rc) return rc;
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
-    rc = launch_gemm(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, nullptr, s);
+    rc = launch_gemm_ws(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, nullptr, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_rmsnorm(h1, D, L->ln2, L->eps, bb, D, B * Tp, D, s);
     if (rc) return rc;
-    rc = launch_gemm_pair(bb, D, L->wg, gate, F, L->wu, up, F, B * Tp, D, s);
+    rc = launch_gemm_pair_ws(bb, D, L->wg, gate, F, L->wu, up, F, B * Tp, D, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_silu_mul(gate, up, act, (int64_t)B * Tp * F, s);
     if (rc) return rc;
-    return launch_gemm(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, s);
+    return launch_gemm_ws(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, gs, gs_bytes, s);
 }
 
 static vitcop_decoder_layer_t first_decoder_layer(const vitcop_decoder_schedule_t* S) {
@@ -690,9 +727,19 @@ static int check_decoder_schedule(const vitcop_decoder_schedule_t* S) {
 
 size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S) {
     if (check_decoder_schedule(S) != VITCOP_OK) return 0;
-    const vitcop_decoder_layer_t L = first_decoder_layer(S);
+    vitcop_decoder_layer_t L = first_decoder_layer(S);
+    size_t layer_max = 0;         // the largest layer workspace along the schedule
+    int stage = 0;
+    for (int l = 0; l < S->n_layers; ++l) {
+        L.keep = L.n_vis;
+        const bool prune_here = stage < S->n_stages && S->prune_layer[stage] == l;
+        if (prune_here) L.keep = S->prune_keep[stage++];
+        layer_max = std::max(layer_max, vitcop_decoder_layer_workspace_bytes(&L));
+        L.T = L.T - L.n_vis + L.keep;
+        L.n_vis = L.keep;
+    }
     const size_t B = S->B, T = S->T, D = S->D;
-    return vitcop_decoder_layer_workspace_bytes(&L) + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
+    return layer_max + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
 }
 
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream) {

@@ -449,6 +449,29 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
     return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
 }
 
+size_t gemm_workspace_bytes(int M, int N, int K) { return gemm_skinny_workspace_bytes(M, N, K); }
+
+int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                   const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws,
+                   size_t ws_bytes, hipStream_t s) {
+    if (M == 0 || N == 0) return VITCOP_OK;
+    const size_t need = gemm_skinny_workspace_bytes(M, N, K);
+    if (ws && need && ws_bytes >= need)
+        return launch_gemm_skinny(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, nullptr,
+                                  nullptr, 0, ws, s);
+    return launch_gemm(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, s);
+}
+
+int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
+                        const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
+                        hipStream_t s) {
+    if (M == 0) return VITCOP_OK;
+    const size_t need = gemm_skinny_workspace_bytes(M, N1 + N2, K);
+    if (ws && need && ws_bytes >= need && N1 == N2 && N1 % 128 == 0)
+        return launch_gemm_skinny(x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, ws, s);
+    return launch_gemm_pair(x, x_stride, w1, y1, N1, w2, y2, N2, M, K, s);
+}
+
 // dist[b][i,j] = ||f_i - f_j||_2 in fp32 between the rows of each of `batch` bf16 matrices
 // f [n,K] (row stride and batch stride in elements), with their squared row norms sq given.
 // sq must be readable, and the rows of dist writable, up to the next multiple of 4 entries

@@ -1,0 +1,367 @@
+// Linear projection y = x W^T for FEW rows (M <= 256): what the projections of a decoder layer
+// look like after the pruning of Sec. 3.2.2 has cut the sequence to a few hundred tokens.  The
+// weight matrix is then nearly all of the traffic (one pass over W per launch) and the launch is
+// bound by HBM, not by the matrix cores.  One CU with four wavefronts pulls at most about 50 GB/s
+// from HBM, so the whole chip must take part, whatever N and K are:
+//
+//   * the work is cut into units of (128 output columns) x (64 k-values); the units, ordered
+//     column group by column group, are dealt out evenly to at most 256 workgroups, so a
+//     workgroup's share is a k-range of one column group, or the tail of one group and the head
+//     of the next (two segments);
+//   * both operands are fetched with whole 128-byte lines per 8 lanes (the vector memory path
+//     moves lines, so the MFMA operand layout, 32 rows x 32 bytes per instruction, would cost four
+//     times the cycles) into registers, several units ahead of the multiply, and written to one of
+//     two LDS slabs one unit before their use, with the same swizzle as the big-tile GEMM; all
+//     loads are ordinary ones, so the compiler's own counting of outstanding loads places every
+//     wait;
+//   * every segment writes an fp32 partial tile; a second kernel adds the partials of a column
+//     group in workgroup order (deterministic), adds the residual, rounds to bf16 and, for the
+//     K projection, forms the per-128-column sums of squares of the rounded outputs for the
+//     K-norm of Eq. 4.
+#include "vitcop_internal.h"
+#include "device_utils.h"
+
+namespace vitcop {
+
+constexpr int SK_THREADS = 256;
+constexpr int SK_COLS = 128;          // output columns per unit
+constexpr int SK_UNIT = 64;           // k-values per unit (one 128-byte line per row)
+constexpr int SK_MAX_ROWS = 256;
+constexpr int SK_MAX_WGS = 256;       // one per CU
+
+// units held in registers (one being stored, the others in flight): as many as the register file takes
+template <int MB>
+constexpr int sk_slots() {
+    return 2;
+}
+
+// Workgroup i of P owns the units [i * total / P, (i+1) * total / P) of the group-major order.
+__host__ __device__ __forceinline__ int sk_first_unit(int i, int total, int P) {
+    return (int)((int64_t)i * total / P);
+}
+
+// part[2 * workgroup + segment][m][128] (fp32) = sum over the segment's k-range of x[m,k] W[n,k]
+// for the 128 columns n of the segment's group.  With w2 != nullptr the columns [n_split, N) come
+// from a second weight matrix (n_split a multiple of 128).
+template <int MB>
+__global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
+    const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w, int64_t w_stride,
+    const uint16_t* __restrict__ w2, int n_split, int M, int N, int K, int m_chunk, float* __restrict__ part) {
+    constexpr int NSLOT = sk_slots<MB>();
+    constexpr int XROWS = MB * 32;
+    constexpr int ROWS = XROWS + SK_COLS;                // slab rows: x, then the group's rows of W
+    constexpr int SLAB = ROWS * 128;                     // bytes: 64 k-values per row
+    constexpr int NLD = ROWS / 8 / 4;                    // loads per wavefront per unit (8 rows each)
+    constexpr int STAGE = 32 * (128 + 16);               // epilogue staging per wavefront: 32 rows of 32 fp32, padded
+    static_assert(NSLOT % 2 == 0, "the slab of a unit must be known at compile time");
+    static_assert(2 * SLAB >= 4 * STAGE, "the epilogue reuses the slabs");
+    extern __shared__ __attribute__((aligned(1024))) char sk_lds[];     // 2 * SLAB bytes
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int l32 = lane & 31, g = lane >> 5;
+    const int upg = K / SK_UNIT;                         // units per column group
+    const int total = ((N + SK_COLS - 1) / SK_COLS) * upg;
+    const int first = sk_first_unit(blockIdx.x, total, gridDim.x);
+    const int last = sk_first_unit(blockIdx.x + 1, total, gridDim.x);    // exclusive; last - first <= upg
+    // blockIdx.y picks a chunk of m_chunk <= MB*32 rows (more than 192 rows go in two chunks: the
+    // accumulators of 256 rows leave too few registers for loads in flight)
+    const int m_base = blockIdx.y * m_chunk;
+    const int m_rows = min(M - m_base, m_chunk);
+    x += (int64_t)m_base * x_stride;
+
+    // every wavefront's LDS accesses are done, its writes visible, after this
+    auto lds_barrier = [&]() {
+        __builtin_amdgcn_s_waitcnt(0xC07F);              // lgkmcnt(0) only: the global loads stay in flight
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+    };
+
+    for (int seg = 0, u_begin = first; u_begin < last; ++seg) {
+        const int grp = u_begin / upg;
+        const int u0 = u_begin - grp * upg;                          // first unit inside the group
+        const int nk = min(last, (grp + 1) * upg) - u_begin;         // units of this segment
+        u_begin += nk;
+        int n0 = grp * SK_COLS, n_rows = N;
+        const uint16_t* wm = w;
+        if (w2 != nullptr) {
+            if (n0 >= n_split) {
+                wm = w2;
+                n0 -= n_split;
+                n_rows = N - n_split;
+            } else {
+                n_rows = n_split;
+            }
+        }
+
+        f32x16 acc[MB];
+#pragma unroll
+        for (int j = 0; j < MB; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+
+        // Load q of wavefront wv covers slab rows (wv*NLD+q)*8 .. +8; lane L fetches chunk L%8 (16
+        // bytes) of row L/8 and stores it at chunk position (L%8) ^ (row%8).
+        // (operand base in scalar registers + a 32-bit lane offset: operands are below 2^31 elements)
+        const char* base[NLD];
+        unsigned src[NLD];
+        int dst[NLD];
+#pragma unroll
+        for (int q = 0; q < NLD; ++q) {
+            const int row0 = (wv * NLD + q) * 8, row = row0 + (lane >> 3);
+            const bool is_x = row0 < XROWS;                          // uniform: 8 rows never straddle
+            base[q] = reinterpret_cast<const char*>(is_x ? x : wm);
+            src[q] = 2u * (unsigned)(is_x ? min(row, m_rows - 1) * (int)x_stride
+                                          : min(n0 + row - XROWS, n_rows - 1) * (int)w_stride) + 16 * (lane & 7);
+            dst[q] = row * 128 + (((lane & 7) ^ (row & 7)) << 4);
+        }
+        u32x4 held[NSLOT][NLD];
+        // Past the segment's end every lane reads the operand's first 16 bytes instead (one line per
+        // instruction, never used): the number of loads in flight stays a compile-time fact, which
+        // the compiler's wait counts need, while the memory pipeline carries next to nothing for
+        // them; with a handful of units per segment, full loads that nobody uses would be a large
+        // part of its work.
+        auto issue_loads = [&](int slot, int step) {
+            const bool live = step < nk;
+            const int64_t off = live ? (int64_t)(u0 + step) * (SK_UNIT * 2) : 0;
+#pragma unroll
+            for (int q = 0; q < NLD; ++q)
+                held[slot][q] = *reinterpret_cast<const u32x4*>(base[q] + off + (live ? src[q] : 0u));
+        };
+        auto store_slab = [&](int slot, int slab) {
+#pragma unroll
+            for (int q = 0; q < NLD; ++q) *reinterpret_cast<u32x4*>(sk_lds + slab * SLAB + dst[q]) = held[slot][q];
+        };
+        // MFMA fragments: lane (l32, g) reads the 8 k-values 16*kc + 8*g .. of a row
+        bf16x8 xf[2][MB], wf[2];
+        auto read_frags = [&](int buf, int slab, int kc) {
+            const char* S = sk_lds + slab * SLAB;
+#pragma unroll
+            for (int j = 0; j < MB; ++j) {
+                const int row = j * 32 + l32;
+                xf[buf][j] = *reinterpret_cast<const bf16x8*>(S + row * 128 + (((2 * kc + g) ^ (row & 7)) << 4));
+            }
+            const int row = XROWS + wv * 32 + l32;
+            wf[buf] = *reinterpret_cast<const bf16x8*>(S + row * 128 + (((2 * kc + g) ^ (row & 7)) << 4));
+        };
+        auto multiply = [&](int buf) {
+#pragma unroll
+            for (int j = 0; j < MB; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf], xf[buf][j], acc[j], 0, 0, 0);
+        };
+        // Scheduling hints: a phase is MB multiplies; each is followed by one LDS read of the next
+        // phase's fragments and, if `extra` names a class (0x200 LDS write, 0x020 global load), by
+        // one instruction of that class; what is left of the NLD extras and the last read close it.
+#define VITCOP_PHASE(extra)                                              \
+    _Pragma("unroll") for (int q_ = 0; q_ < MB; ++q_) {                  \
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               \
+        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               \
+        if ((extra) != 0) __builtin_amdgcn_sched_group_barrier((extra), 1, 0); \
+    }                                                                    \
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                   \
+    if ((extra) != 0) __builtin_amdgcn_sched_group_barrier((extra), NLD - MB, 0);
+        // Unit t: slab t % 2, registers slot t % NSLOT.  The operands of unit t+1 go to the other
+        // slab (every wavefront left it at the barrier that ended unit t-1); the loads of unit
+        // t+1+NSLOT take the registers just stored.  The fragments of a 16-wide slice are read
+        // while the slice before it is multiplied.
+        auto unit = [&](int t, int slot) {
+            const int slab = slot & 1, next = (slot + 1) % NSLOT;
+            read_frags(1, slab, 1);               // reads before writes: the compiler keeps LDS accesses in order
+            store_slab(next, slab ^ 1);
+            multiply(0);
+            VITCOP_PHASE(0x200)
+            issue_loads(next, t + 1 + NSLOT);
+            read_frags(0, slab, 2);
+            multiply(1);
+            VITCOP_PHASE(0x020)
+            read_frags(1, slab, 3);
+            multiply(0);
+            VITCOP_PHASE(0)
+            lds_barrier();
+            read_frags(0, slab ^ 1, 0);
+            multiply(1);
+            VITCOP_PHASE(0)
+        };
+        // The wavefronts issue their first loads unit by unit in step (a barrier between units):
+        // left alone, the oldest wavefront queues all of its loads first and the unit-0 data of
+        // the youngest, which the first barrier of the pipeline waits for, arrives last.
+        lds_barrier();                            // the slabs are free (previous segment's epilogue)
+#pragma unroll
+        for (int p = 0; p < NSLOT; ++p) {
+            issue_loads(p, p);
+            __builtin_amdgcn_s_barrier();
+            asm volatile("" ::: "memory");
+        }
+        store_slab(0, 0);
+        issue_loads(0, NSLOT);
+        lds_barrier();
+        read_frags(0, 0, 0);
+        int t = 0;
+        for (; t + NSLOT <= nk; t += NSLOT) {
+#pragma unroll
+            for (int p = 0; p < NSLOT; ++p) unit(t + p, p);
+        }
+#pragma unroll
+        for (int p = 0; p < NSLOT - 1; ++p)
+            if (t + p < nk) unit(t + p, p);
+#undef VITCOP_PHASE
+
+        // Epilogue.  A lane owns row m = 32 j + l32 and the column runs n = 8 (r/4) + 4 g + r%4 of
+        // its wavefront's 32: stored from there, an instruction would touch 32 rows with 32 bytes
+        // each.  Each wavefront stages one 32 x 32 block at a time in LDS (rows padded by 16 bytes)
+        // and writes it with 8 lanes per 128-byte row of the partial tile.
+        lds_barrier();                                       // the last unit's slab reads are done
+        char* stage = sk_lds + wv * STAGE;
+        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base) * SK_COLS;
+        const int srow = lane >> 3, scol = (lane & 7) * 4;   // store side: row within a group of 8, first column
+#pragma unroll
+        for (int j = 0; j < MB; ++j) {
+            if (j * 32 >= m_rows) break;
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) {
+                float4 o;
+                o.x = acc[j][4 * r4];
+                o.y = acc[j][4 * r4 + 1];
+                o.z = acc[j][4 * r4 + 2];
+                o.w = acc[j][4 * r4 + 3];
+                *reinterpret_cast<float4*>(stage + l32 * 144 + (8 * r4 + 4 * g) * 4) = o;
+            }
+            // (a wavefront reads back only what it wrote itself: the LDS counter suffices, no barrier)
+#pragma unroll
+            for (int r0 = 0; r0 < 32; r0 += 8) {
+                const int m = j * 32 + r0 + srow;
+                const float4 o = *reinterpret_cast<const float4*>(stage + (r0 + srow) * 144 + scol * 4);
+                if (m < m_rows) *reinterpret_cast<float4*>(out + (int64_t)m * SK_COLS + wv * 32 + scol) = o;
+            }
+        }
+    }
+}
+
+// y[m, n..n+8) = bf16(sum of the partial tiles of n's column group, in workgroup order, + residual);
+// one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
+// group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
+__global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
+    const float* __restrict__ part, int P, int M, int N, int K, uint16_t* __restrict__ y, int64_t y_stride,
+    uint16_t* __restrict__ y2, int n_split, const uint16_t* __restrict__ res, int64_t res_stride,
+    float* __restrict__ sumsq_parts) {
+    const int groups = (N + SK_COLS - 1) / SK_COLS, chunks = groups * 16;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int m = (int)(id / chunks), c = (int)(id % chunks);
+    const int n = c * 8, grp = c >> 4;
+    float ss = 0.f;
+    if (m < M && n < N) {
+        const int upg = K / SK_UNIT, total = groups * upg;
+        // workgroups whose unit ranges meet [grp * upg, (grp+1) * upg)
+        auto owner = [&](int u) {
+            int i = (int)((int64_t)u * P / total);
+            while (sk_first_unit(i + 1, total, P) <= u) ++i;
+            return i;
+        };
+        const int i_lo = owner(grp * upg), i_hi = owner((grp + 1) * upg - 1);
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (int i = i_lo; i <= i_hi; ++i) {
+            const int seg = sk_first_unit(i, total, P) / upg == grp ? 0 : 1;     // its first or its second group
+            const float* p = part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
+            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+        }
+        uint16_t* dst;
+        if (y2 != nullptr && n >= n_split)
+            dst = y2 + (int64_t)m * y_stride + (n - n_split);
+        else
+            dst = y + (int64_t)m * y_stride + n;
+        if (res) {
+            const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * res_stride + n);
+            v[0] += bf16_lo(r.x); v[1] += bf16_hi(r.x);
+            v[2] += bf16_lo(r.y); v[3] += bf16_hi(r.y);
+            v[4] += bf16_lo(r.z); v[5] += bf16_hi(r.z);
+            v[6] += bf16_lo(r.w); v[7] += bf16_hi(r.w);
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]);
+        o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]);
+        o.w = pack_bf16(v[6], v[7]);
+        *reinterpret_cast<uint4*>(dst) = o;
+        if (sumsq_parts) {
+            float a;
+            a = bf16_lo(o.x); ss = fmaf(a, a, ss);
+            a = bf16_hi(o.x); ss = fmaf(a, a, ss);
+            a = bf16_lo(o.y); ss = fmaf(a, a, ss);
+            a = bf16_hi(o.y); ss = fmaf(a, a, ss);
+            a = bf16_lo(o.z); ss = fmaf(a, a, ss);
+            a = bf16_hi(o.z); ss = fmaf(a, a, ss);
+            a = bf16_lo(o.w); ss = fmaf(a, a, ss);
+            a = bf16_hi(o.w); ss = fmaf(a, a, ss);
+        }
+    }
+    if (sumsq_parts) {                                   // uniform branch: every lane takes part in the shuffles
+#pragma unroll
+        for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);
+        if ((c & 15) == 0 && m < M && n < N) sumsq_parts[(int64_t)grp * M + m] = ss;
+    }
+}
+
+// Workgroups of the first kernel: one per CU if there is work for that many (two units each at
+// least), never fewer than column groups (so that a workgroup's share stays within two groups).
+static int skinny_row_chunks(int M) { return M > 192 ? 2 : 1; }
+static int skinny_workgroups(int M, int N, int K) {
+    const int groups = (N + SK_COLS - 1) / SK_COLS, total = groups * (K / SK_UNIT);
+    return max(groups, min(SK_MAX_WGS / skinny_row_chunks(M), total / 2));
+}
+
+bool gemm_skinny_applies(int M, int N, int K) {
+    return M >= 1 && M <= SK_MAX_ROWS && K % SK_UNIT == 0 && K >= 2 * SK_UNIT && N % 8 == 0;
+}
+
+size_t gemm_skinny_workspace_bytes(int M, int N, int K) {
+    if (!gemm_skinny_applies(M, N, K)) return 0;
+    return up256((size_t)2 * skinny_workgroups(M, N, K) * M * SK_COLS * 4);
+}
+
+template <int MB>
+static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
+                             const uint16_t* w2, int n_split, int M, int N, int K, int wgs, int m_chunk,
+                             float* part, hipStream_t s) {
+    auto kern = gemm_skinny_kernel<MB>;
+    constexpr size_t lds = (size_t)2 * (MB * 32 + SK_COLS) * 128;
+    static bool attr_set = false;
+    if (!attr_set) {
+        int rc = hip_status(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                (int)lds),
+                            "hipFuncSetAttribute(gemm_skinny)");
+        if (rc) return rc;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kern, dim3(wgs, (M + m_chunk - 1) / m_chunk), dim3(SK_THREADS), lds, s, x, x_stride, w,
+                       w_stride, w2, n_split, M, N, K, m_chunk, part);
+    return launch_status("gemm_skinny");
+}
+
+// y = x W^T (+ res) [M,N] for M <= 256 through partial tiles in `ws` (gemm_skinny_workspace_bytes).
+// With w2: columns [n_split, N) use w2 and go to y2 (n_split a multiple of 128); both outputs have
+// row stride y_stride.
+int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                       const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
+                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s) {
+    const int wgs = skinny_workgroups(M, N, K);
+    float* part = static_cast<float*>(ws);
+    const int m_chunk = skinny_row_chunks(M) == 2 ? 128 : M;
+    const int mb = (m_chunk + 31) / 32;
+    int rc;
+    if (mb <= 2)
+        rc = launch_skinny_cfg<2>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
+    else if (mb <= 4)
+        rc = launch_skinny_cfg<4>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
+    else
+        rc = launch_skinny_cfg<6>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
+    if (rc) return rc;
+    const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
+    const int64_t threads = (int64_t)M * chunks;
+    hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,
+                       wgs, M, N, K, y, y_stride, y2, n_split, res, res_stride, sumsq_parts);
+    return launch_status("gemm_skinny_reduce");
+}
+
+}  // namespace vitcop

@@ -53,6 +53,24 @@ int launch_gemm(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t
 int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                      const uint16_t* w2, uint16_t* y2, int N2, int M, int K, hipStream_t s);
 
+// The same two calls with a scratch buffer: launches with few rows (M <= 256) then stream the weights
+// through a split-K kernel (gemm_skinny.hip) whose fp32 partials live in `ws`; with ws == nullptr, too
+// small a buffer or any other shape they are the calls above.  gemm_workspace_bytes is what the
+// split-K path of one launch (N = N1 + N2 for a pair) needs, 0 if it does not apply.
+size_t gemm_workspace_bytes(int M, int N, int K);
+int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                   const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws,
+                   size_t ws_bytes, hipStream_t s);
+int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
+                        const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
+                        hipStream_t s);
+// gemm_skinny.hip
+bool gemm_skinny_applies(int M, int N, int K);
+size_t gemm_skinny_workspace_bytes(int M, int N, int K);
+int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                       const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
+                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s);
+
 // dist[b][i,j] = ||f_i - f_j||_2 (fp32) between the rows of each of `batch` matrices, from MFMA
 // inner products and given squared row norms; sq readable and dist rows writable up to the next
 // multiple of 4 entries, dist_stride % 4 == 0

@@ -120,13 +120,18 @@ def test_attn_validation():
 
 def test_project_and_select_from_sumsq_validation():
     f = lib.vitcop_project
-    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4096, 4008, None, None) == binding.VITCOP_EUNSUPPORTED
-    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4100, 4096, None, None) == binding.VITCOP_EUNSUPPORTED
-    assert f(A16, 1024, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
-    assert f(None, 4096, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
-    assert f(A16, 4096, A16, A16, 4096, A16, 8, 640, 4096, 4096, None, None) == binding.VITCOP_EINVAL
-    assert f(A16, 4096, A16, A16, 4096, None, 0, 0, 4096, 4096, None, None) == binding.VITCOP_OK
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4096, 4008, None, None, 0, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 640, 4100, 4096, None, None, 0, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(A16, 1024, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None, 0, None) == binding.VITCOP_EINVAL
+    assert f(None, 4096, A16, A16, 4096, None, 0, 640, 4096, 4096, None, None, 0, None) == binding.VITCOP_EINVAL
+    assert f(A16, 4096, A16, A16, 4096, A16, 8, 640, 4096, 4096, None, None, 0, None) == binding.VITCOP_EINVAL
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 0, 4096, 4096, None, None, 0, None) == binding.VITCOP_OK
     assert lib.vitcop_project_sumsq_parts(4096) == 32 and lib.vitcop_project_sumsq_parts(512) == 4
+    # scratch of the few-row path: two fp32 partial tiles of 128 columns per workgroup
+    assert lib.vitcop_project_workspace_bytes(128, 4096, 4096) == 2 * 256 * 128 * 128 * 4
+    assert lib.vitcop_project_workspace_bytes(640, 4096, 4096) == 0
+    assert lib.vitcop_project_workspace_bytes(128, 4096, 96) == 0
+    assert f(A16, 4096, A16, A16, 4096, None, 0, 128, 4096, 4096, None, A16 + 4, 1 << 30, None) == binding.VITCOP_EINVAL
     s = lib.vitcop_select_from_sumsq
     assert s(A16, 32, 640, 1, 640, 35, 576, 600, None, A16, None) == binding.VITCOP_EINVAL
     assert s(A16, 32, 100, 1, 640, 35, 576, 64, None, A16, None) == binding.VITCOP_EINVAL   # stride < B*T

@@ -106,7 +106,10 @@ def test_decoder_layer_deterministic_and_prefix(vc):
     cut = run_layer(vc, c, pos, 40, 260, 50)
     again = run_layer(vc, c, pos, 40, 260, 50)
     assert torch.equal(cut["y"], again["y"])
-    assert torch.equal(cut["y"][:, :40], full["y"][:, :40])
+    # (equal up to the rounding order of the projections: few rows take the split-K path)
+    a, b = host_f64(cut["y"][:, :40]), host_f64(full["y"][:, :40])
+    assert_attention_close(a, b, "rows before the visual span")
+    assert np.mean(a == b) > 0.9
 
 
 def schedule_case(seed, B, T, D, Hq, Hkv, d, F, vs, nv, n_layers):

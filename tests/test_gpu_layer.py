@@ -42,6 +42,33 @@ def test_project_matches_oracle(vc, M, N, K):
     assert np.allclose(ss, ref_ss, rtol=1e-5)
 
 
+@pytest.mark.parametrize("M,N,K", [(128, 4096, 4096), (192, 1024, 11008), (256, 2048, 1024), (1, 128, 128),
+                                   (31, 144, 192), (100, 16, 640), (250, 400, 4096), (160, 11008, 512),
+                                   (64, 4096, 2752), (33, 256, 8192)])
+def test_project_few_rows_matches_oracle(vc, M, N, K):
+    # M <= 256: the split-K kernel that streams W through registers (1..16 splits, ragged k-ranges,
+    # partial column groups, every row-block count), with residual and the norm side output
+    assert vc.lib.vitcop_project_workspace_bytes(M, N, K) > 0
+    x = I.normal_bf16(M + N + K, 0, (M, K))
+    w = I.normal_bf16(M + N + K, 1, (N, K), 0.05)
+    r = I.normal_bf16(M + N + K, 2, (M, N))
+    want = True
+    y, parts = vc.vitcop_project(dev(x), dev(w), residual=dev(r), want_sumsq=want)
+    torch.cuda.synchronize()
+    ref = O.project(x, w) + O.bf16_to_f64(r)
+    yb = host_bits(y)
+    assert_bf16_of(yb, ref, f"project {M}x{N}x{K}")
+    if want:
+        ss = parts.cpu().numpy().astype(np.float64)
+        rounded = I.bf16_bits_to_f32(yb).astype(np.float64) ** 2
+        assert parts.shape[0] == vc.vitcop_project_sumsq_parts(N)
+        for p_ in range(parts.shape[0]):            # every 128-column part on its own
+            assert np.allclose(ss[p_], rounded[:, 128 * p_:128 * p_ + 128].sum(axis=1), rtol=1e-5)
+    # the big tiles (no scratch) round the same sums: both within half an ulp of the oracle
+    y2, _ = vc.vitcop_project(dev(x), dev(w), residual=dev(r), scratch=False)
+    assert_bf16_of(host_bits(y2), ref, f"project (big tiles) {M}x{N}x{K}")
+
+
 def test_project_residual_and_strides(vc):
     M, N, K = 200, 256, 128
     x = I.normal_bf16(1, 0, (M, K)); w = I.normal_bf16(1, 1, (N, K), 0.1); r = I.normal_bf16(1, 2, (M, N))
@@ -117,7 +144,11 @@ def check_layer(vc, c, keep, residual, what):
     assert_attention_close(host_f64(st["y"]), ref["y"], what + " staged y")
     # the one-call layer is the composition of those entry points on its own keep list
     st_own = st if np.array_equal(idx, ref["keep_idx"]) else staged_layer(vc, c, idx, residual)
-    assert torch.equal(r["y"], st_own["y"]), what + ": fused call differs from the staged calls"
+    # (the one-call layer may sum a projection's k-range in other pieces than the separate call does: few
+    # rows go through split-K whose cut depends on the launch; both are fp32 sums rounded once to bf16)
+    fused, staged = host_f64(r["y"]), host_f64(st_own["y"])
+    assert_attention_close(fused, staged, what + ": fused call against the staged calls")
+    assert np.mean(fused == staged) > 0.9, what + ": fused call differs from the staged calls in many places"
     return np.array_equal(idx, ref["keep_idx"])
 
 
