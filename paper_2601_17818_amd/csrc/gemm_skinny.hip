@@ -35,18 +35,20 @@ constexpr int sk_slots() {
     return 2;
 }
 
-// Workgroup i of P owns the units [i * total / P, (i+1) * total / P) of the group-major order.
-__host__ __device__ __forceinline__ int sk_first_unit(int i, int total, int P) {
-    return (int)((int64_t)i * total / P);
-}
+// Workgroup i of P owns the units [first(i), first(i+1)) of the group-major order: total / P units
+// each, one more for the first total % P workgroups (q and r below; no division on the device).
+__host__ __device__ __forceinline__ int sk_first_unit(int i, int q, int r) { return i * q + min(i, r); }
 
 // part[2 * workgroup + segment][m][128] (fp32) = sum over the segment's k-range of x[m,k] W[n,k]
-// for the 128 columns n of the segment's group.  With w2 != nullptr the columns [n_split, N) come
+// for the 128 columns n of the segment's group.  With part == nullptr every workgroup owns exactly
+// one whole column group and writes bf16(sum + residual) to y (or y2) itself.  With w2 != nullptr the columns [n_split, N) come
 // from a second weight matrix (n_split a multiple of 128).
 template <int MB>
 __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w, int64_t w_stride,
-    const uint16_t* __restrict__ w2, int n_split, int M, int N, int K, int m_chunk, float* __restrict__ part) {
+    const uint16_t* __restrict__ w2, int n_split, int M, int N, int K, int m_chunk, int units_q, int units_r,
+    float* __restrict__ part, uint16_t* __restrict__ y, uint16_t* __restrict__ y2, int64_t y_stride,
+    const uint16_t* __restrict__ res, int64_t res_stride) {
     constexpr int NSLOT = sk_slots<MB>();
     constexpr int XROWS = MB * 32;
     constexpr int ROWS = XROWS + SK_COLS;                // slab rows: x, then the group's rows of W
@@ -61,11 +63,9 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
     const int upg = K / SK_UNIT;                         // units per column group
-    const int total = ((N + SK_COLS - 1) / SK_COLS) * upg;
-    const int first = sk_first_unit(blockIdx.x, total, gridDim.x);
-    const int last = sk_first_unit(blockIdx.x + 1, total, gridDim.x);    // exclusive; last - first <= upg
-    // blockIdx.y picks a chunk of m_chunk <= MB*32 rows (more than 192 rows go in two chunks: the
-    // accumulators of 256 rows leave too few registers for loads in flight)
+    const int first = sk_first_unit(blockIdx.x, units_q, units_r);
+    const int last = sk_first_unit(blockIdx.x + 1, units_q, units_r);    // exclusive; last - first <= upg
+    // blockIdx.y picks a chunk of m_chunk <= MB*32 rows (one chunk for every M the launcher accepts)
     const int m_base = blockIdx.y * m_chunk;
     const int m_rows = min(M - m_base, m_chunk);
     x += (int64_t)m_base * x_stride;
@@ -78,7 +78,7 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     };
 
     for (int seg = 0, u_begin = first; u_begin < last; ++seg) {
-        const int grp = u_begin / upg;
+        const int grp = (int)((unsigned)u_begin / (unsigned)upg);
         const int u0 = u_begin - grp * upg;                          // first unit inside the group
         const int nk = min(last, (grp + 1) * upg) - u_begin;         // units of this segment
         u_begin += nk;
@@ -102,17 +102,22 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
 
         // Load q of wavefront wv covers slab rows (wv*NLD+q)*8 .. +8; lane L fetches chunk L%8 (16
         // bytes) of row L/8 and stores it at chunk position (L%8) ^ (row%8).
-        // (operand base in scalar registers + a 32-bit lane offset: operands are below 2^31 elements)
+        // (operand base in scalar registers + a 32-bit lane offset: operands are below 2^31 elements;
+        // whether a load fetches x or W is uniform, so stride, row limit and row shift are picked as
+        // scalars first: a workgroup starts with one wavefront per SIMD, which issues an instruction
+        // every few cycles, so every instruction ahead of the first load delays the whole launch)
         const char* base[NLD];
         unsigned src[NLD];
         int dst[NLD];
+        const int xs32 = (int)x_stride, ws32 = (int)w_stride;
 #pragma unroll
         for (int q = 0; q < NLD; ++q) {
             const int row0 = (wv * NLD + q) * 8, row = row0 + (lane >> 3);
             const bool is_x = row0 < XROWS;                          // uniform: 8 rows never straddle
             base[q] = reinterpret_cast<const char*>(is_x ? x : wm);
-            src[q] = 2u * (unsigned)(is_x ? min(row, m_rows - 1) * (int)x_stride
-                                          : min(n0 + row - XROWS, n_rows - 1) * (int)w_stride) + 16 * (lane & 7);
+            const int stride = is_x ? xs32 : ws32, limit = is_x ? m_rows - 1 : n_rows - 1;
+            const int shift = is_x ? 0 : n0 - XROWS;
+            src[q] = 2u * (unsigned)(min(row + shift, limit) * stride) + 16 * (lane & 7);
             dst[q] = row * 128 + (((lane & 7) ^ (row & 7)) << 4);
         }
         u32x4 held[NSLOT][NLD];
@@ -212,8 +217,13 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
         // and writes it with 8 lanes per 128-byte row of the partial tile.
         lds_barrier();                                       // the last unit's slab reads are done
         char* stage = sk_lds + wv * STAGE;
-        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base) * SK_COLS;
         const int srow = lane >> 3, scol = (lane & 7) * 4;   // store side: row within a group of 8, first column
+        const int n = n0 + wv * 32 + scol;                   // column inside the selected matrix
+        // running addresses, 8 rows further per store (kept as additions: what the compiler hoists
+        // to the top of the kernel from here runs ahead of the first load)
+        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base + srow) * SK_COLS + wv * 32 + scol;
+        uint16_t* yrow = (wm == w ? y : y2) + (int64_t)(m_base + srow) * y_stride + n;
+        const uint16_t* rrow = res + (int64_t)(m_base + srow) * res_stride + n;
 #pragma unroll
         for (int j = 0; j < MB; ++j) {
             if (j * 32 >= m_rows) break;
@@ -230,8 +240,25 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
 #pragma unroll
             for (int r0 = 0; r0 < 32; r0 += 8) {
                 const int m = j * 32 + r0 + srow;
-                const float4 o = *reinterpret_cast<const float4*>(stage + (r0 + srow) * 144 + scol * 4);
-                if (m < m_rows) *reinterpret_cast<float4*>(out + (int64_t)m * SK_COLS + wv * 32 + scol) = o;
+                float4 o = *reinterpret_cast<const float4*>(stage + (r0 + srow) * 144 + scol * 4);
+                if (m < m_rows) {
+                    if (part != nullptr) {
+                        *reinterpret_cast<float4*>(out) = o;
+                    } else if (n < n_rows) {                         // direct: the segment is the whole k-range
+                        if (res) {
+                            const uint2 rr = *reinterpret_cast<const uint2*>(rrow);
+                            o.x += bf16_lo(rr.x); o.y += bf16_hi(rr.x);
+                            o.z += bf16_lo(rr.y); o.w += bf16_hi(rr.y);
+                        }
+                        uint2 pk;
+                        pk.x = pack_bf16(o.x, o.y);
+                        pk.y = pack_bf16(o.z, o.w);
+                        *reinterpret_cast<uint2*>(yrow) = pk;
+                    }
+                }
+                out += 8 * SK_COLS;
+                yrow += 8 * y_stride;
+                rrow += 8 * res_stride;
             }
         }
     }
@@ -241,7 +268,8 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
 // one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
 // group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
 __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
-    const float* __restrict__ part, int P, int M, int N, int K, uint16_t* __restrict__ y, int64_t y_stride,
+    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, uint16_t* __restrict__ y,
+    int64_t y_stride,
     uint16_t* __restrict__ y2, int n_split, const uint16_t* __restrict__ res, int64_t res_stride,
     float* __restrict__ sumsq_parts) {
     const int groups = (N + SK_COLS - 1) / SK_COLS, chunks = groups * 16;
@@ -250,18 +278,36 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
     const int n = c * 8, grp = c >> 4;
     float ss = 0.f;
     if (m < M && n < N) {
-        const int upg = K / SK_UNIT, total = groups * upg;
+        const int upg = K / SK_UNIT;
         // workgroups whose unit ranges meet [grp * upg, (grp+1) * upg)
         auto owner = [&](int u) {
-            int i = (int)((int64_t)u * P / total);
-            while (sk_first_unit(i + 1, total, P) <= u) ++i;
-            return i;
+            const int big = units_r * (units_q + 1);          // units held by the workgroups with one more
+            return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
         };
         const int i_lo = owner(grp * upg), i_hi = owner((grp + 1) * upg - 1);
         float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int i = i_lo; i <= i_hi; ++i) {
-            const int seg = sk_first_unit(i, total, P) / upg == grp ? 0 : 1;     // its first or its second group
-            const float* p = part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
+        auto tile = [&](int i) {
+            const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;   // its first or its second group
+            return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
+        };
+        // four tiles' loads in flight at a time; the additions keep the workgroup order
+        int i = i_lo;
+        for (; i + 3 <= i_hi; i += 4) {
+            float4 a[4], b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* p = tile(i + t);
+                a[t] = *reinterpret_cast<const float4*>(p);
+                b[t] = *reinterpret_cast<const float4*>(p + 4);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
+                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+            }
+        }
+        for (; i <= i_hi; ++i) {
+            const float* p = tile(i);
             const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
             v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
             v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
@@ -305,7 +351,13 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
 
 // Workgroups of the first kernel: one per CU if there is work for that many (two units each at
 // least), never fewer than column groups (so that a workgroup's share stays within two groups).
-static int skinny_row_chunks(int M) { return M > 192 ? 2 : 1; }
+static int skinny_row_chunks(int M) { return M > SK_MAX_ROWS ? 2 : 1; }
+// With this many column groups one workgroup per group already keeps most CUs streaming, at a
+// higher rate each, and the partial tiles and their reduction are saved.
+constexpr int SK_DIRECT_GROUPS = 128;
+static bool skinny_direct(int M, int N, bool want_sumsq) {
+    return !want_sumsq && (N + SK_COLS - 1) / SK_COLS * skinny_row_chunks(M) >= SK_DIRECT_GROUPS;
+}
 static int skinny_workgroups(int M, int N, int K) {
     const int groups = (N + SK_COLS - 1) / SK_COLS, total = groups * (K / SK_UNIT);
     return max(groups, min(SK_MAX_WGS / skinny_row_chunks(M), total / 2));
@@ -323,7 +375,8 @@ size_t gemm_skinny_workspace_bytes(int M, int N, int K) {
 template <int MB>
 static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
                              const uint16_t* w2, int n_split, int M, int N, int K, int wgs, int m_chunk,
-                             float* part, hipStream_t s) {
+                             int units_q, int units_r, float* part, uint16_t* y, uint16_t* y2, int64_t y_stride,
+                             const uint16_t* res, int64_t res_stride, hipStream_t s) {
     auto kern = gemm_skinny_kernel<MB>;
     constexpr size_t lds = (size_t)2 * (MB * 32 + SK_COLS) * 128;
     static bool attr_set = false;
@@ -335,7 +388,7 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t
         attr_set = true;
     }
     hipLaunchKernelGGL(kern, dim3(wgs, (M + m_chunk - 1) / m_chunk), dim3(SK_THREADS), lds, s, x, x_stride, w,
-                       w_stride, w2, n_split, M, N, K, m_chunk, part);
+                       w_stride, w2, n_split, M, N, K, m_chunk, units_q, units_r, part, y, y2, y_stride, res, res_stride);
     return launch_status("gemm_skinny");
 }
 
@@ -345,22 +398,30 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                        const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
                        const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s) {
-    const int wgs = skinny_workgroups(M, N, K);
-    float* part = static_cast<float*>(ws);
-    const int m_chunk = skinny_row_chunks(M) == 2 ? 128 : M;
+    const bool direct = skinny_direct(M, N, sumsq_parts != nullptr);
+    const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
+    float* part = direct ? nullptr : static_cast<float*>(ws);
+    const int m_chunk = skinny_row_chunks(M) == 2 ? SK_MAX_ROWS / 2 : M;
     const int mb = (m_chunk + 31) / 32;
+    const int total = (N + SK_COLS - 1) / SK_COLS * (K / SK_UNIT), units_q = total / wgs, units_r = total % wgs;
     int rc;
     if (mb <= 2)
-        rc = launch_skinny_cfg<2>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
+        rc = launch_skinny_cfg<2>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
+                                  y2, y_stride, res, res_stride, s);
     else if (mb <= 4)
-        rc = launch_skinny_cfg<4>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
+        rc = launch_skinny_cfg<4>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
+                                  y2, y_stride, res, res_stride, s);
+    else if (mb <= 6)
+        rc = launch_skinny_cfg<6>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
+                                  y2, y_stride, res, res_stride, s);
     else
-        rc = launch_skinny_cfg<6>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, part, s);
-    if (rc) return rc;
+        rc = launch_skinny_cfg<8>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
+                                  y2, y_stride, res, res_stride, s);
+    if (rc || direct) return rc;
     const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
     const int64_t threads = (int64_t)M * chunks;
     hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,
-                       wgs, M, N, K, y, y_stride, y2, n_split, res, res_stride, sumsq_parts);
+                       units_q, units_r, M, N, K, y, y_stride, y2, n_split, res, res_stride, sumsq_parts);
     return launch_status("gemm_skinny_reduce");
 }
 
