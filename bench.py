@@ -251,6 +251,26 @@ def main():
         dec["stream_frac_hbm"] = dec["stream_GBps"] / HBM_PEAK_GBPS
         dec["speedup_pruned_cache"] = dec["unpruned_us"] / dec["pruned_us"]
         kern["decode_step"] = dec
+        # projections at the row counts pruning leaves in config 2 (128 rows; 4096x4096, the MLP's
+        # 4096x11008 and 11008x4096): HBM-bound on the weights, which are rotated through more than
+        # the 256 MB of cache so that every call streams them from HBM; per call = kernel + reduction
+        few = {}
+        for (N_, K_) in ((4096, 4096), (4096, 11008), (11008, 4096)):
+            n_w = max(2, int(300e6 // (N_ * K_ * 2)) + 1)
+            w_rot = [torch.randn((N_, K_), dtype=torch.bfloat16, device="cuda") * 0.02 for _ in range(n_w)]
+            x_few = torch.randn((128, K_), dtype=torch.bfloat16, device="cuda")
+            bufs = vc.vitcop_project(x_few, w_rot[0])
+            ws_few = torch.empty(vc.lib.vitcop_project_workspace_bytes(128, N_, K_), dtype=torch.uint8, device="cuda")
+            it = [0]
+
+            def few_call():
+                it[0] += 1
+                vc.vitcop_project(x_few, w_rot[it[0] % n_w], out=bufs, scratch=ws_few)
+            us = ev_time(few_call, 4 * n_w) * 1e3
+            few[f"128x{N_}x{K_}"] = {"us": us, "weights_GBps": N_ * K_ * 2 / us / 1e3,
+                                      "frac_hbm": N_ * K_ * 2 / us / 1e3 / HBM_PEAK_GBPS}
+            del w_rot, x_few, bufs, ws_few
+        kern["few_row_projection"] = few
         # a full decoder layer (RMSNorm, rotary embedding, gated MLP of width 11008 around the same
         # attention block) with pruning on entry, at the bench shape
         Fm = 11008

@@ -288,11 +288,12 @@ def vitcop_project_sumsq_parts(N: int) -> int:
     return lib.vitcop_project_sumsq_parts(N)
 
 
-def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None, scratch: bool = True):
+def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None, scratch=True):
     """x [M,K], w [N,K] -> (y [M,N], sumsq_parts [P,M] fp32 or None).
 
     ``out`` = (y, parts) reuses buffers from an earlier call; ``scratch`` = False withholds the
-    workspace, so that a call with few rows also runs on the big tiles.
+    workspace, so that a call with few rows also runs on the big tiles; a uint8 tensor of
+    vitcop_project_workspace_bytes(M, N, K) or more is used as the workspace instead of a new one.
     """
     _dense(x, "x"); _dense(w, "w")
     M, K = x.shape
@@ -306,8 +307,11 @@ def vitcop_project(x, w, residual=None, want_sumsq: bool = False, out=None, scra
             parts = torch.empty((vitcop_project_sumsq_parts(N), M), dtype=torch.float32, device=x.device)
     if residual is not None:
         _dense(residual, "residual")
-    nb = lib.vitcop_project_workspace_bytes(M, N, K) if scratch else 0
-    ws = _ws(nb, x) if nb else None
+    nb = lib.vitcop_project_workspace_bytes(M, N, K) if scratch is not False else 0
+    if isinstance(scratch, torch.Tensor) and scratch.numel() >= nb:
+        ws = scratch
+    else:
+        ws = _ws(nb, x) if nb else None
     _check(lib.vitcop_project(_ptr(x), K, _ptr(w), _ptr(y), N, _ptr(residual), N, M, N, K,
                               _ptr(parts), _ptr(ws), nb, _stream()))
     return y, parts

@@ -611,7 +611,11 @@ size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L) {
     return n;
 }
 
-int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream) {
+// The layer.  a_pre: RMSNorm(h) * ln1 already computed ([B*T, D] dense), or null.  ln_next / a_next:
+// if given, a_next [B*T', D] also receives RMSNorm(y) * ln_next, the next layer's a_pre (fused into
+// the down projection's reduction where the few-row path runs it).
+static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_pre, const uint16_t* ln_next,
+                             uint16_t* a_next, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_decoder_layer(L);
     if (rc) return rc;
     REQUIRE(L->h && L->positions && L->ln1 && L->ln2 && L->wq && L->wk && L->wv && L->wo && L->wg && L->wu &&
@@ -652,8 +656,12 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
     int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
     int32_t* pos = L->positions_out ? L->positions_out : pos_ws;
 
-    rc = launch_rmsnorm(L->h, D, L->ln1, L->eps, a_all, D, B * T, D, s);
-    if (rc) return rc;
+    if (a_pre) {
+        a_all = const_cast<uint16_t*>(a_pre);
+    } else {
+        rc = launch_rmsnorm(L->h, D, L->ln1, L->eps, a_all, D, B * T, D, s);
+        if (rc) return rc;
+    }
     // K of every token, squared norms (before the rotary embedding) as a side output
     rc = launch_gemm_ws(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, gs, gs_bytes, s);
     if (rc) return rc;
@@ -687,15 +695,20 @@ int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size
     if (rc) return rc;
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
-    rc = launch_gemm_ws(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, nullptr, gs, gs_bytes, s);
-    if (rc) return rc;
-    rc = launch_rmsnorm(h1, D, L->ln2, L->eps, bb, D, B * Tp, D, s);
+    rc = launch_gemm_norm_ws(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, L->ln2, L->eps, bb, D, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_gemm_pair_ws(bb, D, L->wg, gate, F, L->wu, up, F, B * Tp, D, gs, gs_bytes, s);
     if (rc) return rc;
     rc = launch_silu_mul(gate, up, act, (int64_t)B * Tp * F, s);
     if (rc) return rc;
+    if (ln_next && a_next)
+        return launch_gemm_norm_ws(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, ln_next, L->eps, a_next, D, gs,
+                                   gs_bytes, s);
     return launch_gemm_ws(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, nullptr, gs, gs_bytes, s);
+}
+
+int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream) {
+    return decoder_layer_run(L, nullptr, nullptr, nullptr, ws, ws_bytes, stream);
 }
 
 static vitcop_decoder_layer_t first_decoder_layer(const vitcop_decoder_schedule_t* S) {
@@ -739,7 +752,7 @@ size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* 
         L.n_vis = L.keep;
     }
     const size_t B = S->B, T = S->T, D = S->D;
-    return layer_max + 2 * up256(B * T * D * 2) + 2 * up256(B * T * 4);
+    return layer_max + 4 * up256(B * T * D * 2) + 2 * up256(B * T * 4);      // hidden and normalised, ping-pong
 }
 
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream) {
@@ -754,11 +767,13 @@ int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws
     const size_t B = S->B, T = S->T, D = S->D;
     Carver c(ws);
     uint16_t* hbuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
+    uint16_t* abuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
     int32_t* pbuf[2] = {c.take<int32_t>(B * T * 4), c.take<int32_t>(B * T * 4)};
     void* lws = c.base + c.used;
     const size_t lws_bytes = ws_bytes - c.used;
 
     const uint16_t* h = S->h;
+    const uint16_t* a_pre = nullptr;          // RMSNorm of h with this layer's ln1, left by the layer before
     const int32_t* pos = S->positions;
     int cur_T = S->T, cur_vis = S->n_vis, stage = 0, pp = 0;
     for (int l = 0; l < S->n_layers; ++l) {
@@ -774,8 +789,10 @@ int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws
             L.positions_out = pbuf[pp];
         }
         L.y = last ? S->y_out : hbuf[l & 1];
-        rc = vitcop_decoder_layer_prefill(&L, lws, lws_bytes, stream);
+        const uint16_t* ln_next = last ? nullptr : static_cast<const uint16_t*>(S->ln1[l + 1]);
+        rc = decoder_layer_run(&L, a_pre, ln_next, abuf[l & 1], lws, lws_bytes, stream);
         if (rc) return rc;
+        a_pre = ln_next ? abuf[l & 1] : nullptr;
         if (prune_here) {
             pos = pbuf[pp];
             pp ^= 1;

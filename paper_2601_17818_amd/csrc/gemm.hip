@@ -462,6 +462,20 @@ int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint1
     return launch_gemm(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, s);
 }
 
+int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                        const uint16_t* res, int64_t res_stride, int M, int N, int K, const uint16_t* ln_w,
+                        float eps, uint16_t* norm_out, int64_t norm_stride, void* ws, size_t ws_bytes,
+                        hipStream_t s) {
+    if (M == 0 || N == 0) return VITCOP_OK;
+    const size_t need = gemm_skinny_workspace_bytes(M, N, K);
+    if (ws && need && ws_bytes >= need && gemm_skinny_fuses_norm(M, N, K))
+        return launch_gemm_skinny(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, nullptr, nullptr, nullptr, 0,
+                                  ws, s, ln_w, eps, norm_out, norm_stride);
+    int rc = launch_gemm_ws(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, nullptr, ws, ws_bytes, s);
+    if (rc) return rc;
+    return launch_rmsnorm(y, y_stride, ln_w, eps, norm_out, norm_stride, M, N, s);
+}
+
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s) {

@@ -351,6 +351,94 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
 
 // Workgroups of the first kernel: one per CU if there is work for that many (two units each at
 // least), never fewer than column groups (so that a workgroup's share stays within two groups).
+// The same reduction followed by an RMSNorm of the finished row (the next operation of a decoder
+// layer after its attention and MLP output projections): y as above, and
+// norm_out[m, :] = y[m, :] / sqrt(mean(y[m, :]^2) + eps) * ln_w, computed from the ROUNDED y exactly as
+// rmsnorm_kernel does.  One workgroup per row; a thread owns the chunks tid, tid + 256, ...
+// (N <= 8 * 256 * SK_NORM_CHUNKS).
+constexpr int SK_NORM_CHUNKS = 16;
+
+__global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
+    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, uint16_t* __restrict__ y,
+    int64_t y_stride, const uint16_t* __restrict__ res, int64_t res_stride, const uint16_t* __restrict__ ln_w,
+    float eps, uint16_t* __restrict__ norm_out, int64_t norm_stride) {
+    __shared__ float wave_part[4];
+    const int m = blockIdx.x, tid = threadIdx.x;
+    const int chunks = N / 8, upg = K / SK_UNIT;
+    auto owner = [&](int u) {
+        const int big = units_r * (units_q + 1);
+        return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
+    };
+    u32x4 held[SK_NORM_CHUNKS];          // (a native vector type: arrays of the uint4 struct end up in scratch)
+    float ss = 0.f;
+#pragma unroll
+    for (int j = 0; j < SK_NORM_CHUNKS; ++j) {
+        const int c = tid + 256 * j;
+        if (c >= chunks) break;
+        const int n = c * 8, grp = c >> 4;
+        const int i_lo = owner(grp * upg), i_hi = owner((grp + 1) * upg - 1);
+        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        auto tile = [&](int i) {
+            const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;
+            return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
+        };
+        int i = i_lo;                  // four tiles' loads in flight at a time; additions in workgroup order
+        for (; i + 3 <= i_hi; i += 4) {
+            float4 a[4], b[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* p = tile(i + t);
+                a[t] = *reinterpret_cast<const float4*>(p);
+                b[t] = *reinterpret_cast<const float4*>(p + 4);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
+                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+            }
+        }
+        for (; i <= i_hi; ++i) {
+            const float* p = tile(i);
+            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+        }
+        if (res) {
+            const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * res_stride + n);
+            v[0] += bf16_lo(r.x); v[1] += bf16_hi(r.x);
+            v[2] += bf16_lo(r.y); v[3] += bf16_hi(r.y);
+            v[4] += bf16_lo(r.z); v[5] += bf16_hi(r.z);
+            v[6] += bf16_lo(r.w); v[7] += bf16_hi(r.w);
+        }
+        uint4 o;
+        o.x = pack_bf16(v[0], v[1]);
+        o.y = pack_bf16(v[2], v[3]);
+        o.z = pack_bf16(v[4], v[5]);
+        o.w = pack_bf16(v[6], v[7]);
+        *reinterpret_cast<uint4*>(y + (int64_t)m * y_stride + n) = o;
+        held[j] = u32x4{o.x, o.y, o.z, o.w};
+        ss = sumsq8(o, ss);
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) wave_part[tid >> 6] = ss;
+    __syncthreads();
+    ss = (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+    const float r = __builtin_amdgcn_rsqf(ss / (float)N + eps);
+#pragma unroll
+    for (int j = 0; j < SK_NORM_CHUNKS; ++j) {
+        const int c = tid + 256 * j;
+        if (c >= chunks) break;
+        const uint4 v = make_uint4(held[j].x, held[j].y, held[j].z, held[j].w);
+        const uint4 g = *reinterpret_cast<const uint4*>(ln_w + 8 * c);
+        uint4 o;
+        o.x = pack_bf16(bf16_lo(v.x) * r * bf16_lo(g.x), bf16_hi(v.x) * r * bf16_hi(g.x));
+        o.y = pack_bf16(bf16_lo(v.y) * r * bf16_lo(g.y), bf16_hi(v.y) * r * bf16_hi(g.y));
+        o.z = pack_bf16(bf16_lo(v.z) * r * bf16_lo(g.z), bf16_hi(v.z) * r * bf16_hi(g.z));
+        o.w = pack_bf16(bf16_lo(v.w) * r * bf16_lo(g.w), bf16_hi(v.w) * r * bf16_hi(g.w));
+        *reinterpret_cast<uint4*>(norm_out + (int64_t)m * norm_stride + 8 * c) = o;
+    }
+}
+
 static int skinny_row_chunks(int M) { return M > SK_MAX_ROWS ? 2 : 1; }
 // With this many column groups one workgroup per group already keeps most CUs streaming, at a
 // higher rate each, and the partial tiles and their reduction are saved.
@@ -395,9 +483,16 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t
 // y = x W^T (+ res) [M,N] for M <= 256 through partial tiles in `ws` (gemm_skinny_workspace_bytes).
 // With w2: columns [n_split, N) use w2 and go to y2 (n_split a multiple of 128); both outputs have
 // row stride y_stride.
+bool gemm_skinny_fuses_norm(int M, int N, int K) {
+    return gemm_skinny_applies(M, N, K) && !skinny_direct(M, N, false) && N <= 8 * 256 * SK_NORM_CHUNKS;
+}
+
+// With ln_w != nullptr (only where gemm_skinny_fuses_norm holds, one weight matrix, no norm side
+// output) norm_out also receives RMSNorm(y) * ln_w.
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                        const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
-                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s) {
+                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
+                       const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride) {
     const bool direct = skinny_direct(M, N, sumsq_parts != nullptr);
     const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
     float* part = direct ? nullptr : static_cast<float*>(ws);
@@ -418,6 +513,11 @@ int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, u
         rc = launch_skinny_cfg<8>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
                                   y2, y_stride, res, res_stride, s);
     if (rc || direct) return rc;
+    if (ln_w != nullptr) {
+        hipLaunchKernelGGL(gemm_skinny_reduce_norm_kernel, dim3(M), dim3(256), 0, s, part, units_q, units_r, M, N, K,
+                           y, y_stride, res, res_stride, ln_w, eps, norm_out, norm_stride);
+        return launch_status("gemm_skinny_reduce_norm");
+    }
     const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
     const int64_t threads = (int64_t)M * chunks;
     hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,

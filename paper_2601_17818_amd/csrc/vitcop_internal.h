@@ -61,15 +61,24 @@ size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                    const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws,
                    size_t ws_bytes, hipStream_t s);
+// y = x W^T + res as launch_gemm_ws, and norm_out = RMSNorm(y) * ln_w (rows norm_stride apart): fused
+// into the few-row path's reduction where that applies, otherwise the projection and launch_rmsnorm.
+int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                        const uint16_t* res, int64_t res_stride, int M, int N, int K, const uint16_t* ln_w,
+                        float eps, uint16_t* norm_out, int64_t norm_stride, void* ws, size_t ws_bytes,
+                        hipStream_t s);
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s);
 // gemm_skinny.hip
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
+bool gemm_skinny_fuses_norm(int M, int N, int K);
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                        const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
-                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s);
+                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
+                       const uint16_t* ln_w = nullptr, float eps = 0.f, uint16_t* norm_out = nullptr,
+                       int64_t norm_stride = 0);
 
 // dist[b][i,j] = ||f_i - f_j||_2 (fp32) between the rows of each of `batch` matrices, from MFMA
 // inner products and given squared row norms; sq readable and dist rows writable up to the next
