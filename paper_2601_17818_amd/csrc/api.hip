@@ -258,6 +258,7 @@ static int check_layer(const vitcop_layer_t* L) {
 static size_t layer_gemm_scratch(int M_all, int M_kept, int D, int qd, int kd, int F) {
     size_t n = gemm_workspace_bytes(M_all, kd, D);                               // K
     n = std::max(n, gemm_workspace_bytes(M_kept, qd + kd, D));                   // Q and V
+    n = std::max(n, gemm_workspace_bytes(M_all, qd + 2 * kd, D));                // K, Q and V of a layer that keeps all
     n = std::max(n, gemm_workspace_bytes(M_kept, D, qd));                        // O
     if (F > 0) {
         n = std::max(n, gemm_workspace_bytes(M_kept, 2 * F, D));                 // gate and up
@@ -318,7 +319,16 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
         rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_begin), s), "hipEventRecord");
         if (rc) return rc;
     }
-    rc = launch_gemm_ws(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, gs, gs_bytes, s);
+    // (nothing to select and nobody asks for the norms: K, Q and V of all tokens go as one launch)
+    const bool kqv_together = !want_sel;
+    if (kqv_together) {
+        const uint16_t* const w3[3] = {L->wk, L->wq, L->wv};
+        uint16_t* const y3[3] = {k_all, qb, vb};
+        const int n3[3] = {kd, qd, kd};
+        rc = launch_gemm_triple_ws(L->x, D, w3, y3, n3, B * T, D, gs, gs_bytes, s);
+    } else {
+        rc = launch_gemm_ws(L->x, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, parts, gs, gs_bytes, s);
+    }
     if (rc) return rc;
     if (L->ev_kproj_end) {
         rc = hip_status(hipEventRecord(static_cast<hipEvent_t>(L->ev_kproj_end), s), "hipEventRecord");
@@ -348,8 +358,10 @@ int vitcop_layer_prefill(const vitcop_layer_t* L, void* ws, size_t ws_bytes, voi
         if (rc) return rc;
     }
     // Q and V of the survivors only
-    rc = launch_gemm_pair_ws(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
-    if (rc) return rc;
+    if (!kqv_together) {
+        rc = launch_gemm_pair_ws(xs, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
+        if (rc) return rc;
+    }
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
     return launch_gemm_ws(ob, qd, L->wo, L->y, D, L->residual ? xs : nullptr, D, B * Tp, D, qd, nullptr, gs, gs_bytes, s);
@@ -663,7 +675,16 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
         if (rc) return rc;
     }
     // K of every token, squared norms (before the rotary embedding) as a side output
-    rc = launch_gemm_ws(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, want_sel ? parts : nullptr, gs, gs_bytes, s);
+    // (nothing to select and nobody asks for the norms: K, Q and V of all tokens go as one launch)
+    const bool kqv_together = !want_sel;
+    if (kqv_together) {
+        const uint16_t* const w3[3] = {L->wk, L->wq, L->wv};
+        uint16_t* const y3[3] = {k_all, qb, vb};
+        const int n3[3] = {kd, qd, kd};
+        rc = launch_gemm_triple_ws(a_all, D, w3, y3, n3, B * T, D, gs, gs_bytes, s);
+    } else {
+        rc = launch_gemm_ws(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, parts, gs, gs_bytes, s);
+    }
     if (rc) return rc;
     if (want_sel) {
         rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T, L->vis_start,
@@ -689,8 +710,10 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
                         "copy positions");
         if (rc) return rc;
     }
-    rc = launch_gemm_pair_ws(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
-    if (rc) return rc;
+    if (!kqv_together) {
+        rc = launch_gemm_pair_ws(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
+        if (rc) return rc;
+    }
     rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
     if (rc) return rc;
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);

@@ -476,6 +476,17 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
     return launch_rmsnorm(y, y_stride, ln_w, eps, norm_out, norm_stride, M, N, s);
 }
 
+int launch_gemm_triple_ws(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
+                          const int n[3], int M, int K, void* ws, size_t ws_bytes, hipStream_t s) {
+    if (M == 0) return VITCOP_OK;
+    const size_t need = gemm_skinny_workspace_bytes(M, n[0] + n[1] + n[2], K);
+    if (ws && need && ws_bytes >= need && n[0] % 128 == 0 && n[1] % 128 == 0)
+        return launch_gemm_skinny3(x, x_stride, w, y, n, M, K, ws, s);
+    int rc = launch_gemm_ws(x, x_stride, w[0], y[0], n[0], nullptr, 0, M, n[0], K, nullptr, ws, ws_bytes, s);
+    if (rc) return rc;
+    return launch_gemm_pair_ws(x, x_stride, w[1], y[1], n[1], w[2], y[2], n[2], M, K, ws, ws_bytes, s);
+}
+
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s) {

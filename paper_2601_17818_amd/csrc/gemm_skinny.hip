@@ -35,20 +35,35 @@ constexpr int sk_slots() {
     return 2;
 }
 
+// Up to three weight matrices side by side (projections of the same input in one launch): matrix i
+// covers the columns [n_end[i-1], n_end[i]) of the launch (boundaries multiples of 128; unused
+// entries repeat N) and writes its own output with its own row stride.
+struct SkMats {
+    const uint16_t* w[3];
+    uint16_t* y[3];
+    int64_t y_stride[3];
+    int n_end[3];
+};
+struct SkPick {
+    int mi, start;
+};
+__device__ __forceinline__ SkPick sk_pick(const SkMats& mats, int n) {
+    const int mi = (n >= mats.n_end[0] ? 1 : 0) + (n >= mats.n_end[1] ? 1 : 0);
+    return {mi, mi == 0 ? 0 : (mi == 1 ? mats.n_end[0] : mats.n_end[1])};
+}
+
 // Workgroup i of P owns the units [first(i), first(i+1)) of the group-major order: total / P units
 // each, one more for the first total % P workgroups (q and r below; no division on the device).
 __host__ __device__ __forceinline__ int sk_first_unit(int i, int q, int r) { return i * q + min(i, r); }
 
 // part[2 * workgroup + segment][m][128] (fp32) = sum over the segment's k-range of x[m,k] W[n,k]
 // for the 128 columns n of the segment's group.  With part == nullptr every workgroup owns exactly
-// one whole column group and writes bf16(sum + residual) to y (or y2) itself.  With w2 != nullptr the columns [n_split, N) come
-// from a second weight matrix (n_split a multiple of 128).
+// one whole column group and writes bf16(sum + residual) to its matrix's output itself.
 template <int MB>
 __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
-    const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w, int64_t w_stride,
-    const uint16_t* __restrict__ w2, int n_split, int M, int N, int K, int m_chunk, int units_q, int units_r,
-    float* __restrict__ part, uint16_t* __restrict__ y, uint16_t* __restrict__ y2, int64_t y_stride,
-    const uint16_t* __restrict__ res, int64_t res_stride) {
+    const uint16_t* __restrict__ x, int64_t x_stride, SkMats mats, int64_t w_stride, int M, int N, int K,
+    int m_chunk, int units_q, int units_r, float* __restrict__ part, const uint16_t* __restrict__ res,
+    int64_t res_stride) {
     constexpr int NSLOT = sk_slots<MB>();
     constexpr int XROWS = MB * 32;
     constexpr int ROWS = XROWS + SK_COLS;                // slab rows: x, then the group's rows of W
@@ -82,17 +97,10 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
         const int u0 = u_begin - grp * upg;                          // first unit inside the group
         const int nk = min(last, (grp + 1) * upg) - u_begin;         // units of this segment
         u_begin += nk;
-        int n0 = grp * SK_COLS, n_rows = N;
-        const uint16_t* wm = w;
-        if (w2 != nullptr) {
-            if (n0 >= n_split) {
-                wm = w2;
-                n0 -= n_split;
-                n_rows = N - n_split;
-            } else {
-                n_rows = n_split;
-            }
-        }
+        const SkPick pick = sk_pick(mats, grp * SK_COLS);            // which matrix this group belongs to
+        const int n0 = grp * SK_COLS - pick.start;                   // first column inside that matrix
+        const int n_rows = mats.n_end[pick.mi] - pick.start;
+        const uint16_t* wm = mats.w[pick.mi];
 
         f32x16 acc[MB];
 #pragma unroll
@@ -222,7 +230,8 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
         // running addresses, 8 rows further per store (kept as additions: what the compiler hoists
         // to the top of the kernel from here runs ahead of the first load)
         float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base + srow) * SK_COLS + wv * 32 + scol;
-        uint16_t* yrow = (wm == w ? y : y2) + (int64_t)(m_base + srow) * y_stride + n;
+        const int64_t y_stride = mats.y_stride[pick.mi];
+        uint16_t* yrow = mats.y[pick.mi] + (int64_t)(m_base + srow) * y_stride + n;
         const uint16_t* rrow = res + (int64_t)(m_base + srow) * res_stride + n;
 #pragma unroll
         for (int j = 0; j < MB; ++j) {
@@ -268,10 +277,8 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
 // one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
 // group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
 __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
-    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, uint16_t* __restrict__ y,
-    int64_t y_stride,
-    uint16_t* __restrict__ y2, int n_split, const uint16_t* __restrict__ res, int64_t res_stride,
-    float* __restrict__ sumsq_parts) {
+    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, SkMats mats,
+    const uint16_t* __restrict__ res, int64_t res_stride, float* __restrict__ sumsq_parts) {
     const int groups = (N + SK_COLS - 1) / SK_COLS, chunks = groups * 16;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(id / chunks), c = (int)(id % chunks);
@@ -312,11 +319,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
             v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
             v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
         }
-        uint16_t* dst;
-        if (y2 != nullptr && n >= n_split)
-            dst = y2 + (int64_t)m * y_stride + (n - n_split);
-        else
-            dst = y + (int64_t)m * y_stride + n;
+        const SkPick pick = sk_pick(mats, n);
+        uint16_t* dst = mats.y[pick.mi] + (int64_t)m * mats.y_stride[pick.mi] + (n - pick.start);
         if (res) {
             const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * res_stride + n);
             v[0] += bf16_lo(r.x); v[1] += bf16_hi(r.x);
@@ -461,9 +465,8 @@ size_t gemm_skinny_workspace_bytes(int M, int N, int K) {
 }
 
 template <int MB>
-static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, int64_t w_stride,
-                             const uint16_t* w2, int n_split, int M, int N, int K, int wgs, int m_chunk,
-                             int units_q, int units_r, float* part, uint16_t* y, uint16_t* y2, int64_t y_stride,
+static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const SkMats& mats, int64_t w_stride, int M, int N,
+                             int K, int wgs, int m_chunk, int units_q, int units_r, float* part,
                              const uint16_t* res, int64_t res_stride, hipStream_t s) {
     auto kern = gemm_skinny_kernel<MB>;
     constexpr size_t lds = (size_t)2 * (MB * 32 + SK_COLS) * 128;
@@ -475,24 +478,22 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const uint16_t
         if (rc) return rc;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(wgs, (M + m_chunk - 1) / m_chunk), dim3(SK_THREADS), lds, s, x, x_stride, w,
-                       w_stride, w2, n_split, M, N, K, m_chunk, units_q, units_r, part, y, y2, y_stride, res, res_stride);
+    hipLaunchKernelGGL(kern, dim3(wgs, (M + m_chunk - 1) / m_chunk), dim3(SK_THREADS), lds, s, x, x_stride, mats,
+                       w_stride, M, N, K, m_chunk, units_q, units_r, part, res, res_stride);
     return launch_status("gemm_skinny");
 }
 
-// y = x W^T (+ res) [M,N] for M <= 256 through partial tiles in `ws` (gemm_skinny_workspace_bytes).
-// With w2: columns [n_split, N) use w2 and go to y2 (n_split a multiple of 128); both outputs have
-// row stride y_stride.
 bool gemm_skinny_fuses_norm(int M, int N, int K) {
     return gemm_skinny_applies(M, N, K) && !skinny_direct(M, N, false) && N <= 8 * 256 * SK_NORM_CHUNKS;
 }
 
-// With ln_w != nullptr (only where gemm_skinny_fuses_norm holds, one weight matrix, no norm side
-// output) norm_out also receives RMSNorm(y) * ln_w.
-int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
-                       const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
-                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
-                       const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride) {
+// The launch over the matrices of `mats` (N = all their columns) through partial tiles in `ws`
+// (gemm_skinny_workspace_bytes).  res and sumsq_parts only with a single matrix.  With ln_w != nullptr
+// (only where gemm_skinny_fuses_norm holds, one matrix, no norm side output) norm_out also receives
+// RMSNorm(y) * ln_w.
+static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats& mats, const uint16_t* res,
+                              int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws, hipStream_t s,
+                              const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride) {
     const bool direct = skinny_direct(M, N, sumsq_parts != nullptr);
     const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
     float* part = direct ? nullptr : static_cast<float*>(ws);
@@ -501,28 +502,45 @@ int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, u
     const int total = (N + SK_COLS - 1) / SK_COLS * (K / SK_UNIT), units_q = total / wgs, units_r = total % wgs;
     int rc;
     if (mb <= 2)
-        rc = launch_skinny_cfg<2>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
-                                  y2, y_stride, res, res_stride, s);
+        rc = launch_skinny_cfg<2>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     else if (mb <= 4)
-        rc = launch_skinny_cfg<4>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
-                                  y2, y_stride, res, res_stride, s);
+        rc = launch_skinny_cfg<4>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     else if (mb <= 6)
-        rc = launch_skinny_cfg<6>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
-                                  y2, y_stride, res, res_stride, s);
+        rc = launch_skinny_cfg<6>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     else
-        rc = launch_skinny_cfg<8>(x, x_stride, w, K, w2, n_split, M, N, K, wgs, m_chunk, units_q, units_r, part, y,
-                                  y2, y_stride, res, res_stride, s);
+        rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     if (rc || direct) return rc;
     if (ln_w != nullptr) {
         hipLaunchKernelGGL(gemm_skinny_reduce_norm_kernel, dim3(M), dim3(256), 0, s, part, units_q, units_r, M, N, K,
-                           y, y_stride, res, res_stride, ln_w, eps, norm_out, norm_stride);
+                           mats.y[0], mats.y_stride[0], res, res_stride, ln_w, eps, norm_out, norm_stride);
         return launch_status("gemm_skinny_reduce_norm");
     }
     const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
     const int64_t threads = (int64_t)M * chunks;
     hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,
-                       units_q, units_r, M, N, K, y, y_stride, y2, n_split, res, res_stride, sumsq_parts);
+                       units_q, units_r, M, N, K, mats, res, res_stride, sumsq_parts);
     return launch_status("gemm_skinny_reduce");
+}
+
+// y = x W^T (+ res) [M,N] for M <= 256.  With w2: columns [n_split, N) use w2 and go to y2 (n_split a
+// multiple of 128); both outputs have row stride y_stride.
+int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                       const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
+                       const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
+                       const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride) {
+    SkMats mats{{w, w2 ? w2 : w, w}, {y, w2 ? y2 : y, y}, {y_stride, y_stride, y_stride},
+                {w2 ? n_split : N, N, N}};
+    return launch_skinny_mats(x, x_stride, mats, res, res_stride, M, N, K, sumsq_parts, ws, s, ln_w, eps, norm_out,
+                              norm_stride);
+}
+
+// Three projections of the same input in one launch: y[i] = x w[i]^T, [M, n[i]] dense (n[0] and n[1]
+// multiples of 128).
+int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
+                        const int n[3], int M, int K, void* ws, hipStream_t s) {
+    SkMats mats{{w[0], w[1], w[2]}, {y[0], y[1], y[2]}, {n[0], n[1], n[2]}, {n[0], n[0] + n[1], n[0] + n[1] + n[2]}};
+    return launch_skinny_mats(x, x_stride, mats, nullptr, 0, M, n[0] + n[1] + n[2], K, nullptr, ws, s, nullptr, 0.f,
+                              nullptr, 0);
 }
 
 }  // namespace vitcop

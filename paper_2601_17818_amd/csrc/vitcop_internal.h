@@ -67,6 +67,10 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
                         const uint16_t* res, int64_t res_stride, int M, int N, int K, const uint16_t* ln_w,
                         float eps, uint16_t* norm_out, int64_t norm_stride, void* ws, size_t ws_bytes,
                         hipStream_t s);
+// Three projections of the same input (dense outputs [M, n[i]]): one launch on the few-row path when
+// it applies and n[0], n[1] are multiples of 128; otherwise the first alone and the other two as a pair.
+int launch_gemm_triple_ws(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
+                          const int n[3], int M, int K, void* ws, size_t ws_bytes, hipStream_t s);
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s);
@@ -74,6 +78,8 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
 bool gemm_skinny_fuses_norm(int M, int N, int K);
+int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
+                        const int n[3], int M, int K, void* ws, hipStream_t s);
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                        const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
                        const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
