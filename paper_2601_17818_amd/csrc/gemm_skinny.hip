@@ -69,14 +69,21 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     constexpr int ROWS = XROWS + SK_COLS;                // slab rows: x, then the group's rows of W
     constexpr int SLAB = ROWS * 128;                     // bytes: 64 k-values per row
     constexpr int NLD = ROWS / 8 / 4;                    // loads per wavefront per unit (8 rows each)
-    constexpr int STAGE = 32 * (128 + 16);               // epilogue staging per wavefront: 32 rows of 32 fp32, padded
+    constexpr int MI = MB / 2;                           // row blocks per wavefront (2 x 2 wavefronts: rows x columns)
+    constexpr int SROW = 256 + 16;                       // epilogue staging row: 64 fp32, padded
+    constexpr int STAGE = 32 * SROW;                     // per wavefront: one 32 x 64 block
     static_assert(NSLOT % 2 == 0, "the slab of a unit must be known at compile time");
+    static_assert(MB % 2 == 0, "two wavefronts share the rows");
     static_assert(2 * SLAB >= 4 * STAGE, "the epilogue reuses the slabs");
     extern __shared__ __attribute__((aligned(1024))) char sk_lds[];     // 2 * SLAB bytes
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, g = lane >> 5;
+    // A wavefront multiplies MI row blocks of x with 2 column blocks of W: (MI + 2) fragment reads per
+    // 2 MI multiplies; one column block against all rows would read (MB + 1) per MB, and the LDS
+    // reads of the four wavefronts are what bounds the loop at 192 and 256 rows.
+    const int wr = wv & 1, wc = wv >> 1;
     const int upg = K / SK_UNIT;                         // units per column group
     const int first = sk_first_unit(blockIdx.x, units_q, units_r);
     const int last = sk_first_unit(blockIdx.x + 1, units_q, units_r);    // exclusive; last - first <= upg
@@ -102,11 +109,13 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
         const int n_rows = mats.n_end[pick.mi] - pick.start;
         const uint16_t* wm = mats.w[pick.mi];
 
-        f32x16 acc[MB];
+        f32x16 acc[MI][2];
 #pragma unroll
-        for (int j = 0; j < MB; ++j)
+        for (int j = 0; j < MI; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
         // Load q of wavefront wv covers slab rows (wv*NLD+q)*8 .. +8; lane L fetches chunk L%8 (16
         // bytes) of row L/8 and stores it at chunk position (L%8) ^ (row%8).
@@ -146,32 +155,38 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
             for (int q = 0; q < NLD; ++q) *reinterpret_cast<u32x4*>(sk_lds + slab * SLAB + dst[q]) = held[slot][q];
         };
         // MFMA fragments: lane (l32, g) reads the 8 k-values 16*kc + 8*g .. of a row
-        bf16x8 xf[2][MB], wf[2];
+        bf16x8 xf[2][MI], wf[2][2];
         auto read_frags = [&](int buf, int slab, int kc) {
             const char* S = sk_lds + slab * SLAB;
 #pragma unroll
-            for (int j = 0; j < MB; ++j) {
-                const int row = j * 32 + l32;
+            for (int j = 0; j < MI; ++j) {
+                const int row = (wr * MI + j) * 32 + l32;
                 xf[buf][j] = *reinterpret_cast<const bf16x8*>(S + row * 128 + (((2 * kc + g) ^ (row & 7)) << 4));
             }
-            const int row = XROWS + wv * 32 + l32;
-            wf[buf] = *reinterpret_cast<const bf16x8*>(S + row * 128 + (((2 * kc + g) ^ (row & 7)) << 4));
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+                const int row = XROWS + (wc * 2 + i) * 32 + l32;
+                wf[buf][i] = *reinterpret_cast<const bf16x8*>(S + row * 128 + (((2 * kc + g) ^ (row & 7)) << 4));
+            }
         };
         auto multiply = [&](int buf) {
 #pragma unroll
-            for (int j = 0; j < MB; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf], xf[buf][j], acc[j], 0, 0, 0);
+            for (int j = 0; j < MI; ++j)
+#pragma unroll
+                for (int i = 0; i < 2; ++i)
+                    acc[j][i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[buf][i], xf[buf][j], acc[j][i], 0, 0, 0);
         };
-        // Scheduling hints: a phase is MB multiplies; each is followed by one LDS read of the next
-        // phase's fragments and, if `extra` names a class (0x200 LDS write, 0x020 global load), by
-        // one instruction of that class; what is left of the NLD extras and the last read close it.
+        // Scheduling hints: a phase is MB multiplies; the MI + 2 LDS reads of the next phase's
+        // fragments follow the first multiplies one by one and, if `extra` names a class (0x200 LDS
+        // write, 0x020 global load), every multiply is followed by one instruction of that class;
+        // what is left of the NLD extras closes the phase.
 #define VITCOP_PHASE(extra)                                              \
     _Pragma("unroll") for (int q_ = 0; q_ < MB; ++q_) {                  \
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);               \
-        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);               \
+        if (q_ < MI + 2) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0); \
         if ((extra) != 0) __builtin_amdgcn_sched_group_barrier((extra), 1, 0); \
     }                                                                    \
-    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                   \
+    if (MB < MI + 2) __builtin_amdgcn_sched_group_barrier(0x100, MI + 2 - MB, 0); \
     if ((extra) != 0) __builtin_amdgcn_sched_group_barrier((extra), NLD - MB, 0);
         // Unit t: slab t % 2, registers slot t % NSLOT.  The operands of unit t+1 go to the other
         // slab (every wavefront left it at the barrier that ended unit t-1); the loads of unit
@@ -221,35 +236,38 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
 
         // Epilogue.  A lane owns row m = 32 j + l32 and the column runs n = 8 (r/4) + 4 g + r%4 of
         // its wavefront's 32: stored from there, an instruction would touch 32 rows with 32 bytes
-        // each.  Each wavefront stages one 32 x 32 block at a time in LDS (rows padded by 16 bytes)
-        // and writes it with 8 lanes per 128-byte row of the partial tile.
+        // each.  Each wavefront stages one 32 x 64 block at a time in LDS (rows padded by 16 bytes)
+        // and writes it with 16 lanes per 256-byte row piece of the partial tile.
         lds_barrier();                                       // the last unit's slab reads are done
         char* stage = sk_lds + wv * STAGE;
-        const int srow = lane >> 3, scol = (lane & 7) * 4;   // store side: row within a group of 8, first column
-        const int n = n0 + wv * 32 + scol;                   // column inside the selected matrix
-        // running addresses, 8 rows further per store (kept as additions: what the compiler hoists
+        const int srow = lane >> 4, scol = (lane & 15) * 4;  // store side: row within a group of 4, first column
+        const int n = n0 + wc * 64 + scol;                   // column inside the selected matrix
+        const int m0 = wr * MI * 32;                         // first row of this wavefront
+        // running addresses, 4 rows further per store (kept as additions: what the compiler hoists
         // to the top of the kernel from here runs ahead of the first load)
-        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base + srow) * SK_COLS + wv * 32 + scol;
+        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base + m0 + srow) * SK_COLS + wc * 64 + scol;
         const int64_t y_stride = mats.y_stride[pick.mi];
-        uint16_t* yrow = mats.y[pick.mi] + (int64_t)(m_base + srow) * y_stride + n;
-        const uint16_t* rrow = res + (int64_t)(m_base + srow) * res_stride + n;
+        uint16_t* yrow = mats.y[pick.mi] + (int64_t)(m_base + m0 + srow) * y_stride + n;
+        const uint16_t* rrow = res + (int64_t)(m_base + m0 + srow) * res_stride + n;
 #pragma unroll
-        for (int j = 0; j < MB; ++j) {
-            if (j * 32 >= m_rows) break;
+        for (int j = 0; j < MI; ++j) {
+            if (m0 + j * 32 >= m_rows) break;
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) {
-                float4 o;
-                o.x = acc[j][4 * r4];
-                o.y = acc[j][4 * r4 + 1];
-                o.z = acc[j][4 * r4 + 2];
-                o.w = acc[j][4 * r4 + 3];
-                *reinterpret_cast<float4*>(stage + l32 * 144 + (8 * r4 + 4 * g) * 4) = o;
-            }
+            for (int i = 0; i < 2; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    float4 o;
+                    o.x = acc[j][i][4 * r4];
+                    o.y = acc[j][i][4 * r4 + 1];
+                    o.z = acc[j][i][4 * r4 + 2];
+                    o.w = acc[j][i][4 * r4 + 3];
+                    *reinterpret_cast<float4*>(stage + l32 * SROW + (32 * i + 8 * r4 + 4 * g) * 4) = o;
+                }
             // (a wavefront reads back only what it wrote itself: the LDS counter suffices, no barrier)
 #pragma unroll
-            for (int r0 = 0; r0 < 32; r0 += 8) {
-                const int m = j * 32 + r0 + srow;
-                float4 o = *reinterpret_cast<const float4*>(stage + (r0 + srow) * 144 + scol * 4);
+            for (int r0 = 0; r0 < 32; r0 += 4) {
+                const int m = m0 + j * 32 + r0 + srow;
+                float4 o = *reinterpret_cast<const float4*>(stage + (r0 + srow) * SROW + scol * 4);
                 if (m < m_rows) {
                     if (part != nullptr) {
                         *reinterpret_cast<float4*>(out) = o;
@@ -265,9 +283,9 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
                         *reinterpret_cast<uint2*>(yrow) = pk;
                     }
                 }
-                out += 8 * SK_COLS;
-                yrow += 8 * y_stride;
-                rrow += 8 * res_stride;
+                out += 4 * SK_COLS;
+                yrow += 4 * y_stride;
+                rrow += 4 * res_stride;
             }
         }
     }
