@@ -720,9 +720,7 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
     if (rc) return rc;
     rc = launch_gemm_norm_ws(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, L->ln2, L->eps, bb, D, gs, gs_bytes, s);
     if (rc) return rc;
-    rc = launch_gemm_pair_ws(bb, D, L->wg, gate, F, L->wu, up, F, B * Tp, D, gs, gs_bytes, s);
-    if (rc) return rc;
-    rc = launch_silu_mul(gate, up, act, (int64_t)B * Tp * F, s);
+    rc = launch_gemm_gated_ws(bb, D, L->wg, L->wu, F, gate, up, act, B * Tp, D, gs, gs_bytes, s);
     if (rc) return rc;
     if (ln_next && a_next)
         return launch_gemm_norm_ws(act, F, L->wd, L->y, D, h1, D, B * Tp, D, F, ln_next, L->eps, a_next, D, gs,

@@ -476,6 +476,18 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
     return launch_rmsnorm(y, y_stride, ln_w, eps, norm_out, norm_stride, M, N, s);
 }
 
+int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
+                         uint16_t* gate, uint16_t* up, uint16_t* out, int M, int K, void* ws, size_t ws_bytes,
+                         hipStream_t s) {
+    if (M == 0 || F == 0) return VITCOP_OK;
+    const size_t need = gemm_skinny_workspace_bytes(M, 2 * F, K);
+    if (ws && need && ws_bytes >= need && F % 128 == 0)
+        return launch_gemm_skinny_gated(x, x_stride, wg, wu, F, out, M, K, ws, s);
+    int rc = launch_gemm_pair_ws(x, x_stride, wg, gate, F, wu, up, F, M, K, ws, ws_bytes, s);
+    if (rc) return rc;
+    return launch_silu_mul(gate, up, out, (int64_t)M * F, s);
+}
+
 int launch_gemm_triple_ws(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
                           const int n[3], int M, int K, void* ws, size_t ws_bytes, hipStream_t s) {
     if (M == 0) return VITCOP_OK;

@@ -291,6 +291,45 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     }
 }
 
+// v[0..8) = sum, in workgroup order, of the partial tiles that hold row m, columns n .. n+8 (n a
+// multiple of 8).  Four tiles' loads are in flight at a time; the additions keep the order.
+__device__ __forceinline__ void sk_sum_tiles(const float* __restrict__ part, int units_q, int units_r, int upg,
+                                             int M, int m, int n, float (&v)[8]) {
+    const int grp = n / SK_COLS;
+    auto owner = [&](int u) {               // the workgroup whose unit range holds unit u
+        const int big = units_r * (units_q + 1);          // units held by the workgroups with one more
+        return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
+    };
+    auto tile = [&](int i) {
+        const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;   // its first or its second group
+        return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
+    };
+    const int i_hi = owner((grp + 1) * upg - 1);
+    int i = owner(grp * upg);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = 0.f;
+    for (; i + 3 <= i_hi; i += 4) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const float* p = tile(i + t);
+            a[t] = *reinterpret_cast<const float4*>(p);
+            b[t] = *reinterpret_cast<const float4*>(p + 4);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
+            v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+        }
+    }
+    for (; i <= i_hi; ++i) {
+        const float* p = tile(i);
+        const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+    }
+}
+
 // y[m, n..n+8) = bf16(sum of the partial tiles of n's column group, in workgroup order, + residual);
 // one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
 // group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
@@ -303,40 +342,8 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
     const int n = c * 8, grp = c >> 4;
     float ss = 0.f;
     if (m < M && n < N) {
-        const int upg = K / SK_UNIT;
-        // workgroups whose unit ranges meet [grp * upg, (grp+1) * upg)
-        auto owner = [&](int u) {
-            const int big = units_r * (units_q + 1);          // units held by the workgroups with one more
-            return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
-        };
-        const int i_lo = owner(grp * upg), i_hi = owner((grp + 1) * upg - 1);
-        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        auto tile = [&](int i) {
-            const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;   // its first or its second group
-            return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
-        };
-        // four tiles' loads in flight at a time; the additions keep the workgroup order
-        int i = i_lo;
-        for (; i + 3 <= i_hi; i += 4) {
-            float4 a[4], b[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float* p = tile(i + t);
-                a[t] = *reinterpret_cast<const float4*>(p);
-                b[t] = *reinterpret_cast<const float4*>(p + 4);
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
-                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
-            }
-        }
-        for (; i <= i_hi; ++i) {
-            const float* p = tile(i);
-            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
-            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
-        }
+        float v[8];
+        sk_sum_tiles(part, units_q, units_r, K / SK_UNIT, M, m, n, v);
         const SkPick pick = sk_pick(mats, n);
         uint16_t* dst = mats.y[pick.mi] + (int64_t)m * mats.y_stride[pick.mi] + (n - pick.start);
         if (res) {
@@ -387,44 +394,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
     __shared__ float wave_part[4];
     const int m = blockIdx.x, tid = threadIdx.x;
     const int chunks = N / 8, upg = K / SK_UNIT;
-    auto owner = [&](int u) {
-        const int big = units_r * (units_q + 1);
-        return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
-    };
     u32x4 held[SK_NORM_CHUNKS];          // (a native vector type: arrays of the uint4 struct end up in scratch)
     float ss = 0.f;
 #pragma unroll
     for (int j = 0; j < SK_NORM_CHUNKS; ++j) {
         const int c = tid + 256 * j;
         if (c >= chunks) break;
-        const int n = c * 8, grp = c >> 4;
-        const int i_lo = owner(grp * upg), i_hi = owner((grp + 1) * upg - 1);
-        float v[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        auto tile = [&](int i) {
-            const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;
-            return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
-        };
-        int i = i_lo;                  // four tiles' loads in flight at a time; additions in workgroup order
-        for (; i + 3 <= i_hi; i += 4) {
-            float4 a[4], b[4];
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const float* p = tile(i + t);
-                a[t] = *reinterpret_cast<const float4*>(p);
-                b[t] = *reinterpret_cast<const float4*>(p + 4);
-            }
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
-                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
-            }
-        }
-        for (; i <= i_hi; ++i) {
-            const float* p = tile(i);
-            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
-            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
-        }
+        const int n = c * 8;
+        float v[8];
+        sk_sum_tiles(part, units_q, units_r, upg, M, m, n, v);
         if (res) {
             const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * res_stride + n);
             v[0] += bf16_lo(r.x); v[1] += bf16_hi(r.x);
@@ -459,6 +437,32 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
         o.w = pack_bf16(bf16_lo(v.w) * r * bf16_lo(g.w), bf16_hi(v.w) * r * bf16_hi(g.w));
         *reinterpret_cast<uint4*>(norm_out + (int64_t)m * norm_stride + 8 * c) = o;
     }
+}
+
+// The reduction of a gate/up pair launch (columns [0, F) gate, [F, 2F) up) followed by the gated
+// activation of the MLP: out[m, n] = bf16(silu(g) * u) with g and u the bf16-rounded projections,
+// exactly what silu_mul_kernel computes from stored gate and up tensors.  One thread per 8 columns.
+__global__ __launch_bounds__(256) void gemm_skinny_reduce_silu_kernel(
+    const float* __restrict__ part, int units_q, int units_r, int M, int F, int K, uint16_t* __restrict__ out,
+    int64_t out_stride) {
+    const int chunks = F / 8, upg = K / SK_UNIT;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int m = (int)(id / chunks), c = (int)(id % chunks);
+    if (m >= M) return;
+    // bf16(sum of the partial tiles of the 8 columns from n on, in workgroup order), packed
+    auto reduced = [&](int n) {
+        float v[8];
+        sk_sum_tiles(part, units_q, units_r, upg, M, m, n, v);
+        return make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
+    };
+    const uint4 g = reduced(8 * c), u = reduced(F + 8 * c);
+    auto gated = [](uint32_t gw, uint32_t uw) {
+        const float g0 = bf16_lo(gw), g1 = bf16_hi(gw);
+        const float s0 = g0 / (1.0f + __expf(-g0)), s1 = g1 / (1.0f + __expf(-g1));
+        return pack_bf16(s0 * bf16_lo(uw), s1 * bf16_hi(uw));
+    };
+    *reinterpret_cast<uint4*>(out + (int64_t)m * out_stride + 8 * c) =
+        make_uint4(gated(g.x, u.x), gated(g.y, u.y), gated(g.z, u.z), gated(g.w, u.w));
 }
 
 static int skinny_row_chunks(int M) { return M > SK_MAX_ROWS ? 2 : 1; }
@@ -511,8 +515,9 @@ bool gemm_skinny_fuses_norm(int M, int N, int K) {
 // RMSNorm(y) * ln_w.
 static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats& mats, const uint16_t* res,
                               int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws, hipStream_t s,
-                              const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride) {
-    const bool direct = skinny_direct(M, N, sumsq_parts != nullptr);
+                              const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride,
+                              uint16_t* gated_out = nullptr) {
+    const bool direct = gated_out == nullptr && skinny_direct(M, N, sumsq_parts != nullptr);
     const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
     float* part = direct ? nullptr : static_cast<float*>(ws);
     const int m_chunk = skinny_row_chunks(M) == 2 ? SK_MAX_ROWS / 2 : M;
@@ -528,6 +533,12 @@ static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats&
     else
         rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     if (rc || direct) return rc;
+    if (gated_out != nullptr) {                  // N = 2 F: gate and up side by side
+        const int64_t threads = (int64_t)M * (N / 16);
+        hipLaunchKernelGGL(gemm_skinny_reduce_silu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                           part, units_q, units_r, M, N / 2, K, gated_out, (int64_t)(N / 2));
+        return launch_status("gemm_skinny_reduce_silu");
+    }
     if (ln_w != nullptr) {
         hipLaunchKernelGGL(gemm_skinny_reduce_norm_kernel, dim3(M), dim3(256), 0, s, part, units_q, units_r, M, N, K,
                            mats.y[0], mats.y_stride[0], res, res_stride, ln_w, eps, norm_out, norm_stride);
@@ -559,6 +570,15 @@ int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* con
     SkMats mats{{w[0], w[1], w[2]}, {y[0], y[1], y[2]}, {n[0], n[1], n[2]}, {n[0], n[0] + n[1], n[0] + n[1] + n[2]}};
     return launch_skinny_mats(x, x_stride, mats, nullptr, 0, M, n[0] + n[1] + n[2], K, nullptr, ws, s, nullptr, 0.f,
                               nullptr, 0);
+}
+
+// out = silu(x wg^T) * (x wu^T) [M, F] (F a multiple of 128): both projections in one launch, the
+// activation in its reduction.
+int launch_gemm_skinny_gated(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
+                             uint16_t* out, int M, int K, void* ws, hipStream_t s) {
+    SkMats mats{{wg, wu, wu}, {nullptr, nullptr, nullptr}, {0, 0, 0}, {F, 2 * F, 2 * F}};
+    return launch_skinny_mats(x, x_stride, mats, nullptr, 0, M, 2 * F, K, nullptr, ws, s, nullptr, 0.f, nullptr, 0,
+                              out);
 }
 
 }  // namespace vitcop

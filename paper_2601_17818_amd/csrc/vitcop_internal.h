@@ -71,6 +71,11 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
 // it applies and n[0], n[1] are multiples of 128; otherwise the first alone and the other two as a pair.
 int launch_gemm_triple_ws(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
                           const int n[3], int M, int K, void* ws, size_t ws_bytes, hipStream_t s);
+// out = silu(x wg^T) * (x wu^T) [M, F]: on the few-row path one launch with the activation in its
+// reduction; otherwise the pair of projections into gate and up [M, F] and launch_silu_mul.
+int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
+                         uint16_t* gate, uint16_t* up, uint16_t* out, int M, int K, void* ws, size_t ws_bytes,
+                         hipStream_t s);
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s);
@@ -78,6 +83,8 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
 bool gemm_skinny_fuses_norm(int M, int N, int K);
+int launch_gemm_skinny_gated(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
+                             uint16_t* out, int M, int K, void* ws, hipStream_t s);
 int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
                         const int n[3], int M, int K, void* ws, hipStream_t s);
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
