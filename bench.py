@@ -26,7 +26,7 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, vendor figure
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, vendor figure
 # HBM-side bytes per launch of the K-projection GEMM at the bench shape, from two rocprofv3 --pmc
 # runs (FETCH_SIZE, WRITE_SIZE) scaled by a plain 1 GiB copy: profiles/gemm_kproj_config3_hbm_traffic.txt
-KPROJ_MEASURED_TRAFFIC_BYTES = 790.1e6
+KPROJ_MEASURED_TRAFFIC_BYTES = 791.0e6
 
 
 def parse():
@@ -36,6 +36,7 @@ def parse():
     p.add_argument("--warmup", type=int, default=5)
     p.add_argument("--keep", type=int, default=320, help="visual budget of the timed layer (of 2880)")
     p.add_argument("--no-schedule", action="store_true", help="skip the 32-layer step-wise schedule leg")
+    p.add_argument("--schedule", action="store_true", help="run the schedule leg even with --no-extras (profiling)")
     p.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     p.add_argument("--no-extras", action="store_true", help="only the headline step and its roofline")
     p.add_argument("--calib-copy", action="store_true",
@@ -305,7 +306,7 @@ def main():
         out["kernels"] = kern
 
     # -------------------------------------- step-wise schedule (config 2, 32 layers)
-    if not args.no_schedule and not args.no_extras:
+    if args.schedule or (not args.no_schedule and not args.no_extras):
         from concurrent.futures import ThreadPoolExecutor
         h2 = I.config2_hidden()
         with ThreadPoolExecutor(max_workers=8) as ex:
