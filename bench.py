@@ -339,6 +339,25 @@ def main():
         out["decoder_schedule_config2"] = {"ms_pruned": t_dsched, "ms_unpruned": t_dunpr,
                                            "speedup": t_dunpr / t_dsched,
                                            "tokens_per_s": 640 / (t_dsched * 1e-3), "layers": 32, "F": F2}
+        # the paper's own LLaVA-1.5 schedules (App. C, Table 7: Stage I keeps ratio r1 of the 576 visual
+        # tokens before the language model, pruning on entry to layers 2 and 22 keeps r2 and r3) against
+        # the unpruned 640-token prefill, with the FLOPs ratio Eq. 9 predicts (layer cost 4 n^2 d + 16 n d^2)
+        def eq9_ratio(counts):
+            cost = lambda n: 4.0 * n * n * 4096 + 16.0 * n * 4096 * 4096
+            full = 32 * cost(640)
+            return full / (2 * cost(counts[0]) + 20 * cost(counts[1]) + 10 * cost(counts[2]))
+        paper = {}
+        for name, (r1, r2, r3) in (("retain192", (0.5, 0.4394, 0.0879)), ("retain64", (0.3, 0.1343, 0.0269))):
+            v1, v2, v3 = (int(round(576 * r)) for r in (r1, r2, r3))
+            T1 = 64 + v1
+            xp = x2[:, :T1].contiguous()          # (timing only: which visual tokens Stage I kept does not matter)
+            pp = torch.arange(T1, dtype=torch.int32, device="cuda")[None].contiguous()
+            plan = vc.DecoderSchedulePlan(xp, pp, w_dev, 32, 32, 128, 35, v1, ((2, v2), (22, v3)))
+            t_p = ev_time(plan.run, 5, warm=2)
+            paper[name] = {"visual_tokens": [v1, v2, v3], "ms": t_p, "speedup_vs_unpruned": t_dunpr / t_p,
+                           "eq9_flops_ratio": eq9_ratio((64 + v1, 64 + v2, 64 + v3))}
+            del plan, xp, pp
+        out["decoder_schedule_paper_llava15"] = paper
         del w_dev, sp, up, dsp, dup
 
     # ------------------------------------------------------ CPU oracle baseline

@@ -47,7 +47,10 @@ __device__ __forceinline__ int gm_swz(int row) {
 // EPI selects the epilogue: GM_EPI_BF16 the projection described above; GM_EPI_DIST writes,
 // in fp32, the Euclidean distance between row m of x and row n of w from their inner product
 // and the two squared row norms: dist[m,n] = sqrt(max(0, xsq[m] + wsq[n] - 2 <x_m, w_n>)).
-constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1;
+// GM_EPI_PART is split-K: blockIdx.y = split, which multiplies its share of the k-steps and writes the
+// raw fp32 accumulators to dist[split][m][n] (row stride dist_stride, slices dist_batch apart) for a
+// reduction kernel to add up.
+constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1, GM_EPI_PART = 2;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
@@ -71,6 +74,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     static_assert(SLAB % 4096 == 0 && (BM * ROWB) % 1024 == 0, "slab splits evenly over loads");
 
     extern __shared__ __attribute__((aligned(1024))) char gemm_lds[];
+    if constexpr (EPI == GM_EPI_PART) dist += blockIdx.y * dist_batch;
     if constexpr (EPI == GM_EPI_DIST) {      // blockIdx.y = image: x and w are the same feature matrix
         x += blockIdx.y * x_batch;
         w += blockIdx.y * x_batch;
@@ -109,6 +113,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         y = y2;
         n0 -= n_split;
         N -= n_split;
+        if constexpr (EPI == GM_EPI_PART) dist += n_split;       // the partials keep the launch's column index
     } else if (w2 != nullptr) {
         N = n_split;
     }
@@ -191,8 +196,13 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     //   still be in flight); barrier
     //   slice KC-1: multiply; read the fragments of slice 0 of step t+1
     // Past the end the loads repeat the last k-step into slabs nobody reads again.
-    const int nk = K / BK;
-    auto k_of = [&](int step) { return min(step, nk - 1) * BK; };
+    int nk = K / BK, k_lo = 0;
+    if constexpr (EPI == GM_EPI_PART) {      // this split's k-steps: [k_lo, k_lo + nk), never empty
+        const int all = nk;
+        k_lo = (int)((int64_t)all * blockIdx.y / gridDim.y);
+        nk = (int)((int64_t)all * (blockIdx.y + 1) / gridDim.y) - k_lo;
+    }
+    auto k_of = [&](int step) { return (k_lo + min(step, nk - 1)) * BK; };
     auto step = [&](int t, int slab) {
 #pragma unroll
         for (int kc = 0; kc < KC - 1; ++kc) {
@@ -240,6 +250,28 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no load may outlive the workgroup's LDS
 #undef VITCOP_INTERLEAVE
 
+    if constexpr (EPI == GM_EPI_PART) {
+        // lane owns row m = .. + l32 and the 4-element column runs n = .. + 8*(r/4) + 4*g + r%4
+#pragma unroll
+        for (int j = 0; j < MI; ++j) {
+            const int m = m0 + wm * TM + j * 32 + l32;
+            if (m >= M) continue;
+#pragma unroll
+            for (int i = 0; i < NI; ++i)
+#pragma unroll
+                for (int r4 = 0; r4 < 4; ++r4) {
+                    const int n = n0 + wn * TN + i * 32 + 8 * r4 + 4 * g;
+                    if (n >= N) continue;            // N % 4 == 0: the run of 4 is all in or all out
+                    float4 o;
+                    o.x = acc[i][j][4 * r4];
+                    o.y = acc[i][j][4 * r4 + 1];
+                    o.z = acc[i][j][4 * r4 + 2];
+                    o.w = acc[i][j][4 * r4 + 3];
+                    *reinterpret_cast<float4*>(dist + (int64_t)m * dist_stride + n) = o;
+                }
+        }
+        return;
+    }
     if constexpr (EPI == GM_EPI_DIST) {
         // lane owns row m = .. + l32 and the 4-element column runs n = .. + 8*(r/4) + 4*g + r%4
 #pragma unroll
@@ -449,7 +481,60 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
     return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
 }
 
-size_t gemm_workspace_bytes(int M, int N, int K) { return gemm_skinny_workspace_bytes(M, N, K); }
+// Split-K on the big tiles, for a few hundred to a thousand rows: there are then too few 256-wide
+// tiles to fill the chip, and the smaller tiles that would fill it load twice the bytes per FLOP
+// through a CU's load path, which is what bounds them.  So the tiles stay big and the k-range is cut
+// into `splits` slices (blockIdx.y) whose fp32 partials the few-row path's reduction kernels add up.
+struct SplitKPlan {
+    int bm = 0, splits = 0;          // splits == 0: does not apply
+};
+static SplitKPlan splitk_plan(int M, int N, int K) {
+    SplitKPlan p;
+    if (M <= 256 || M > 1024 || N % 16 != 0 || K % 32 != 0) return p;
+    // 256 or 192 rows per tile, whichever pads M less (192 runs at 0.8 of the rate)
+    const int t256 = (M + 255) / 256, t192 = (M + 191) / 192;
+    const int bm = (float)(t192 * 192) / 0.8f < (float)(t256 * 256) ? 192 : 256;
+    const int tiles = (bm == 192 ? t192 : t256) * ((N + 255) / 256);
+    const int splits = std::min(std::min(16, 256 / tiles), K / 32 / 8);     // at least 8 k-steps per slice
+    if (splits < 3) return p;
+    p.bm = bm;
+    p.splits = splits;
+    return p;
+}
+static size_t splitk_workspace_bytes(int M, int N, int K) {
+    const SplitKPlan p = splitk_plan(M, N, K);
+    return p.splits ? up256((size_t)p.splits * M * N * 4) : 0;
+}
+
+size_t gemm_workspace_bytes(int M, int N, int K) {
+    return std::max(gemm_skinny_workspace_bytes(M, N, K), splitk_workspace_bytes(M, N, K));
+}
+
+// y = x W^T (+ res) by split-K (splitk_plan applies, ws holds splitk_workspace_bytes); optionally the
+// norm side output or the RMSNorm of the finished rows, as in the few-row path.
+static int launch_gemm_splitk(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
+                              const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
+                              void* ws, hipStream_t s, const uint16_t* ln_w, float eps, uint16_t* norm_out,
+                              int64_t norm_stride, const uint16_t* w2 = nullptr, uint16_t* y2 = nullptr,
+                              int n_split = 0) {
+    const SplitKPlan p = splitk_plan(M, N, K);
+    float* part = static_cast<float*>(ws);
+    int rc;
+    if (p.bm == 256)
+        rc = launch_gemm_cfg<256, 256, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr,
+                                                             w2, nullptr, n_split, s, K, nullptr, nullptr, part, N,
+                                                             p.splits, 0, 0, (int64_t)M * N);
+    else
+        rc = launch_gemm_cfg<192, 256, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr,
+                                                             w2, nullptr, n_split, s, K, nullptr, nullptr, part, N,
+                                                             p.splits, 0, 0, (int64_t)M * N);
+    if (rc) return rc;
+    const SkParts parts{part, 0, p.splits, N, M};
+    const SkMats mats{{w, w2 ? w2 : w, w}, {y, w2 ? y2 : y, y}, {y_stride, y_stride, y_stride},
+                      {w2 ? n_split : N, N, N}};
+    return launch_partial_reduce(parts, N, mats, res, res_stride, sumsq_parts, ln_w, eps, norm_out, norm_stride,
+                                 nullptr, s);
+}
 
 int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                    const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws,
@@ -459,6 +544,10 @@ int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint1
     if (ws && need && ws_bytes >= need)
         return launch_gemm_skinny(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, nullptr,
                                   nullptr, 0, ws, s);
+    const size_t need_k = splitk_workspace_bytes(M, N, K);
+    if (ws && need_k && ws_bytes >= need_k)
+        return launch_gemm_splitk(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, ws, s, nullptr,
+                                  0.f, nullptr, 0);
     return launch_gemm(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, s);
 }
 
@@ -471,6 +560,10 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
     if (ws && need && ws_bytes >= need && gemm_skinny_fuses_norm(M, N, K))
         return launch_gemm_skinny(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, nullptr, nullptr, nullptr, 0,
                                   ws, s, ln_w, eps, norm_out, norm_stride);
+    const size_t need_k = splitk_workspace_bytes(M, N, K);
+    if (ws && need_k && ws_bytes >= need_k && partial_reduce_fuses_norm(N))
+        return launch_gemm_splitk(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, nullptr, ws, s, ln_w, eps,
+                                  norm_out, norm_stride);
     int rc = launch_gemm_ws(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, nullptr, ws, ws_bytes, s);
     if (rc) return rc;
     return launch_rmsnorm(y, y_stride, ln_w, eps, norm_out, norm_stride, M, N, s);
@@ -506,6 +599,10 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
     const size_t need = gemm_skinny_workspace_bytes(M, N1 + N2, K);
     if (ws && need && ws_bytes >= need && N1 == N2 && N1 % 128 == 0)
         return launch_gemm_skinny(x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, ws, s);
+    const size_t need_k = splitk_workspace_bytes(M, N1 + N2, K);
+    if (ws && need_k && ws_bytes >= need_k && N1 == N2 && N1 % 256 == 0)      // no tile straddles the two outputs
+        return launch_gemm_splitk(x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, ws, s, nullptr, 0.f,
+                                  nullptr, 0, w2, y2, N1);
     return launch_gemm_pair(x, x_stride, w1, y1, N1, w2, y2, N2, M, K, s);
 }
 

@@ -35,15 +35,6 @@ constexpr int sk_slots() {
     return 2;
 }
 
-// Up to three weight matrices side by side (projections of the same input in one launch): matrix i
-// covers the columns [n_end[i-1], n_end[i]) of the launch (boundaries multiples of 128; unused
-// entries repeat N) and writes its own output with its own row stride.
-struct SkMats {
-    const uint16_t* w[3];
-    uint16_t* y[3];
-    int64_t y_stride[3];
-    int n_end[3];
-};
 struct SkPick {
     int mi, start;
 };
@@ -291,51 +282,55 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     }
 }
 
-// v[0..8) = sum, in workgroup order, of the partial tiles that hold row m, columns n .. n+8 (n a
-// multiple of 8).  Four tiles' loads are in flight at a time; the additions keep the order.
-__device__ __forceinline__ void sk_sum_tiles(const float* __restrict__ part, int units_q, int units_r, int upg,
-                                             int M, int m, int n, float (&v)[8]) {
-    const int grp = n / SK_COLS;
-    auto owner = [&](int u) {               // the workgroup whose unit range holds unit u
-        const int big = units_r * (units_q + 1);          // units held by the workgroups with one more
-        return u < big ? u / (units_q + 1) : units_r + (u - big) / units_q;
-    };
-    auto tile = [&](int i) {
-        const int seg = sk_first_unit(i, units_q, units_r) / upg == grp ? 0 : 1;   // its first or its second group
-        return part + ((int64_t)(2 * i + seg) * M + m) * SK_COLS + (n & (SK_COLS - 1));
-    };
-    const int i_hi = owner((grp + 1) * upg - 1);
-    int i = owner(grp * upg);
+// v[0..8) = sum, in workgroup (or slice) order, of the partials of row m, columns n .. n+8 (n a
+// multiple of 8).  Four loads are in flight at a time; the additions keep the order.
+__device__ __forceinline__ void sk_sum_tiles(const SkParts& P, int m, int n, float (&v)[8]) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) v[e] = 0.f;
-    for (; i + 3 <= i_hi; i += 4) {
-        float4 a[4], b[4];
+    auto sum_range = [&](int i, int i_hi, auto tile) {
+        for (; i + 3 <= i_hi; i += 4) {
+            float4 a[4], b[4];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const float* p = tile(i + t);
-            a[t] = *reinterpret_cast<const float4*>(p);
-            b[t] = *reinterpret_cast<const float4*>(p + 4);
-        }
+            for (int t = 0; t < 4; ++t) {
+                const float* p = tile(i + t);
+                a[t] = *reinterpret_cast<const float4*>(p);
+                b[t] = *reinterpret_cast<const float4*>(p + 4);
+            }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
-            v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+            for (int t = 0; t < 4; ++t) {
+                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
+                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+            }
         }
+        for (; i <= i_hi; ++i) {
+            const float* p = tile(i);
+            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+        }
+    };
+    if (P.units_q == 0) {
+        sum_range(0, P.units_r - 1, [&](int sl) { return P.part + ((int64_t)sl * P.M + m) * P.upg + n; });
+        return;
     }
-    for (; i <= i_hi; ++i) {
-        const float* p = tile(i);
-        const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
-        v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
-        v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
-    }
+    const int grp = n / SK_COLS;
+    auto owner = [&](int u) {               // the workgroup whose unit range holds unit u
+        const int big = P.units_r * (P.units_q + 1);      // units held by the workgroups with one more
+        return u < big ? u / (P.units_q + 1) : P.units_r + (u - big) / P.units_q;
+    };
+    sum_range(owner(grp * P.upg), owner((grp + 1) * P.upg - 1), [&](int i) {
+        const int seg = sk_first_unit(i, P.units_q, P.units_r) / P.upg == grp ? 0 : 1;   // its first or its second group
+        return P.part + ((int64_t)(2 * i + seg) * P.M + m) * SK_COLS + (n & (SK_COLS - 1));
+    });
 }
 
 // y[m, n..n+8) = bf16(sum of the partial tiles of n's column group, in workgroup order, + residual);
 // one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
 // group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
 __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
-    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, SkMats mats,
-    const uint16_t* __restrict__ res, int64_t res_stride, float* __restrict__ sumsq_parts) {
+    SkParts parts, int N, SkMats mats, const uint16_t* __restrict__ res, int64_t res_stride,
+    float* __restrict__ sumsq_parts) {
+    const int M = parts.M;
     const int groups = (N + SK_COLS - 1) / SK_COLS, chunks = groups * 16;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(id / chunks), c = (int)(id % chunks);
@@ -343,7 +338,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
     float ss = 0.f;
     if (m < M && n < N) {
         float v[8];
-        sk_sum_tiles(part, units_q, units_r, K / SK_UNIT, M, m, n, v);
+        sk_sum_tiles(parts, m, n, v);
         const SkPick pick = sk_pick(mats, n);
         uint16_t* dst = mats.y[pick.mi] + (int64_t)m * mats.y_stride[pick.mi] + (n - pick.start);
         if (res) {
@@ -388,12 +383,12 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_kernel(
 constexpr int SK_NORM_CHUNKS = 16;
 
 __global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
-    const float* __restrict__ part, int units_q, int units_r, int M, int N, int K, uint16_t* __restrict__ y,
-    int64_t y_stride, const uint16_t* __restrict__ res, int64_t res_stride, const uint16_t* __restrict__ ln_w,
-    float eps, uint16_t* __restrict__ norm_out, int64_t norm_stride) {
+    SkParts parts, int N, uint16_t* __restrict__ y, int64_t y_stride, const uint16_t* __restrict__ res,
+    int64_t res_stride, const uint16_t* __restrict__ ln_w, float eps, uint16_t* __restrict__ norm_out,
+    int64_t norm_stride) {
     __shared__ float wave_part[4];
     const int m = blockIdx.x, tid = threadIdx.x;
-    const int chunks = N / 8, upg = K / SK_UNIT;
+    const int chunks = N / 8;
     u32x4 held[SK_NORM_CHUNKS];          // (a native vector type: arrays of the uint4 struct end up in scratch)
     float ss = 0.f;
 #pragma unroll
@@ -402,7 +397,7 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
         if (c >= chunks) break;
         const int n = c * 8;
         float v[8];
-        sk_sum_tiles(part, units_q, units_r, upg, M, m, n, v);
+        sk_sum_tiles(parts, m, n, v);
         if (res) {
             const uint4 r = *reinterpret_cast<const uint4*>(res + (int64_t)m * res_stride + n);
             v[0] += bf16_lo(r.x); v[1] += bf16_hi(r.x);
@@ -443,16 +438,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_norm_kernel(
 // activation of the MLP: out[m, n] = bf16(silu(g) * u) with g and u the bf16-rounded projections,
 // exactly what silu_mul_kernel computes from stored gate and up tensors.  One thread per 8 columns.
 __global__ __launch_bounds__(256) void gemm_skinny_reduce_silu_kernel(
-    const float* __restrict__ part, int units_q, int units_r, int M, int F, int K, uint16_t* __restrict__ out,
-    int64_t out_stride) {
-    const int chunks = F / 8, upg = K / SK_UNIT;
+    SkParts parts, int F, uint16_t* __restrict__ out, int64_t out_stride) {
+    const int chunks = F / 8, M = parts.M;
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int m = (int)(id / chunks), c = (int)(id % chunks);
     if (m >= M) return;
     // bf16(sum of the partial tiles of the 8 columns from n on, in workgroup order), packed
     auto reduced = [&](int n) {
         float v[8];
-        sk_sum_tiles(part, units_q, units_r, upg, M, m, n, v);
+        sk_sum_tiles(parts, m, n, v);
         return make_uint4(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]), pack_bf16(v[4], v[5]), pack_bf16(v[6], v[7]));
     };
     const uint4 g = reduced(8 * c), u = reduced(F + 8 * c);
@@ -506,8 +500,34 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const SkMats& 
 }
 
 bool gemm_skinny_fuses_norm(int M, int N, int K) {
-    return gemm_skinny_applies(M, N, K) && !skinny_direct(M, N, false) && N <= 8 * 256 * SK_NORM_CHUNKS;
+    return gemm_skinny_applies(M, N, K) && !skinny_direct(M, N, false) && partial_reduce_fuses_norm(N);
 }
+
+// Adds up the partial sums of a launch and finishes the rows: plain (+ residual, + norm side output),
+// with the RMSNorm of the finished row (ln_w), or as the gated MLP activation (gated_out; N = 2 F).
+int launch_partial_reduce(const SkParts& parts, int N, const SkMats& mats, const uint16_t* res, int64_t res_stride,
+                          float* sumsq_parts, const uint16_t* ln_w, float eps, uint16_t* norm_out,
+                          int64_t norm_stride, uint16_t* gated_out, hipStream_t s) {
+    const int M = parts.M;
+    if (gated_out != nullptr) {                  // gate and up side by side
+        const int64_t threads = (int64_t)M * (N / 16);
+        hipLaunchKernelGGL(gemm_skinny_reduce_silu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
+                           parts, N / 2, gated_out, (int64_t)(N / 2));
+        return launch_status("gemm_skinny_reduce_silu");
+    }
+    if (ln_w != nullptr) {
+        hipLaunchKernelGGL(gemm_skinny_reduce_norm_kernel, dim3(M), dim3(256), 0, s, parts, N, mats.y[0],
+                           mats.y_stride[0], res, res_stride, ln_w, eps, norm_out, norm_stride);
+        return launch_status("gemm_skinny_reduce_norm");
+    }
+    const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
+    const int64_t threads = (int64_t)M * chunks;
+    hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, parts, N,
+                       mats, res, res_stride, sumsq_parts);
+    return launch_status("gemm_skinny_reduce");
+}
+
+bool partial_reduce_fuses_norm(int N) { return N % 8 == 0 && N <= 8 * 256 * SK_NORM_CHUNKS; }
 
 // The launch over the matrices of `mats` (N = all their columns) through partial tiles in `ws`
 // (gemm_skinny_workspace_bytes).  res and sumsq_parts only with a single matrix.  With ln_w != nullptr
@@ -533,22 +553,9 @@ static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats&
     else
         rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
     if (rc || direct) return rc;
-    if (gated_out != nullptr) {                  // N = 2 F: gate and up side by side
-        const int64_t threads = (int64_t)M * (N / 16);
-        hipLaunchKernelGGL(gemm_skinny_reduce_silu_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s,
-                           part, units_q, units_r, M, N / 2, K, gated_out, (int64_t)(N / 2));
-        return launch_status("gemm_skinny_reduce_silu");
-    }
-    if (ln_w != nullptr) {
-        hipLaunchKernelGGL(gemm_skinny_reduce_norm_kernel, dim3(M), dim3(256), 0, s, part, units_q, units_r, M, N, K,
-                           mats.y[0], mats.y_stride[0], res, res_stride, ln_w, eps, norm_out, norm_stride);
-        return launch_status("gemm_skinny_reduce_norm");
-    }
-    const int chunks = (N + SK_COLS - 1) / SK_COLS * 16;
-    const int64_t threads = (int64_t)M * chunks;
-    hipLaunchKernelGGL(gemm_skinny_reduce_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, part,
-                       units_q, units_r, M, N, K, mats, res, res_stride, sumsq_parts);
-    return launch_status("gemm_skinny_reduce");
+    const SkParts parts{part, units_q, units_r, K / SK_UNIT, M};
+    return launch_partial_reduce(parts, N, mats, res, res_stride, sumsq_parts, ln_w, eps, norm_out, norm_stride,
+                                 gated_out, s);
 }
 
 // y = x W^T (+ res) [M,N] for M <= 256.  With w2: columns [n_split, N) use w2 and go to y2 (n_split a

@@ -80,6 +80,28 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s);
 // gemm_skinny.hip
+// Up to three weight matrices side by side (projections of the same input in one launch): matrix i
+// covers the columns [n_end[i-1], n_end[i]) of the launch (boundaries multiples of 128; unused
+// entries repeat N) and writes its own output with its own row stride.
+struct SkMats {
+    const uint16_t* w[3];
+    uint16_t* y[3];
+    int64_t y_stride[3];
+    int n_end[3];
+};
+// Where the partial sums of a launch live.  units_q > 0: the tiles of gemm_skinny_kernel
+// (part[2 * workgroup + segment][m][128], workgroups by sk_first_unit over groups of upg units).
+// units_q == 0: the slices of a split-K launch of the big-tile kernel, part[slice][m][n] with
+// units_r slices and row stride upg.
+struct SkParts {
+    const float* part;
+    int units_q, units_r, upg, M;
+};
+
+int launch_partial_reduce(const SkParts& parts, int N, const SkMats& mats, const uint16_t* res, int64_t res_stride,
+                          float* sumsq_parts, const uint16_t* ln_w, float eps, uint16_t* norm_out,
+                          int64_t norm_stride, uint16_t* gated_out, hipStream_t s);
+bool partial_reduce_fuses_norm(int N);
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
 bool gemm_skinny_fuses_norm(int M, int N, int K);

@@ -78,7 +78,11 @@ def run_layer(vc, c, pos, vis_start, n_vis, keep):
 @pytest.mark.parametrize("B,T,D,Hq,Hkv,d,F,vs,nv,keep", [(2, 200, 256, 4, 2, 128, 352, 20, 150, 60),
                                                        (1, 333, 512, 8, 8, 64, 704, 0, 300, 300),
                                                        (1, 420, 256, 4, 4, 64, 512, 10, 390, 0),
-                                                       (1, 700, 512, 4, 4, 128, 1408, 0, 640, 320)])
+                                                       (1, 700, 512, 4, 4, 128, 1408, 0, 640, 320),
+                                                       # 256 < rows <= 1024 and k >= 768: the split-K projections
+                                                       # (K alone with norms, Q+V and gate+up as pairs, down)
+                                                       (1, 400, 1024, 2, 2, 128, 768, 20, 300, 200),
+                                                       (1, 320, 1024, 2, 2, 128, 768, 0, 300, 300)])
 def test_decoder_layer_matches_oracle(vc, B, T, D, Hq, Hkv, d, F, vs, nv, keep):
     c = I.decoder_inputs(9300 + T, B, T, D, Hq, Hkv, d, F)
     pos = np.stack([np.sort(np.random.default_rng(10 + b).choice(2 * T, T, replace=False)) for b in range(B)])

@@ -70,6 +70,28 @@ def test_project_few_rows_matches_oracle(vc, M, N, K):
     assert_bf16_of(host_bits(y2), ref, f"project (big tiles) {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K", [(317, 4096, 4096), (640, 4096, 2048), (1000, 1024, 2048), (352, 2048, 11008),
+                                   (257, 256, 768), (1024, 4096, 1024)])
+def test_project_split_k_matches_oracle(vc, M, N, K):
+    # 256 < M <= 1024 and few column tiles: 256- or 192-row tiles with the k-range cut into slices
+    # (3..16, ragged), fp32 partials added by the reduction kernel, with residual and norm side output
+    assert vc.lib.vitcop_project_workspace_bytes(M, N, K) > 0
+    x = I.normal_bf16(M + N + K, 0, (M, K))
+    w = I.normal_bf16(M + N + K, 1, (N, K), 0.05)
+    r = I.normal_bf16(M + N + K, 2, (M, N))
+    y, parts = vc.vitcop_project(dev(x), dev(w), residual=dev(r), want_sumsq=True)
+    torch.cuda.synchronize()
+    ref = O.project(x, w) + O.bf16_to_f64(r)
+    yb = host_bits(y)
+    assert_bf16_of(yb, ref, f"project {M}x{N}x{K}")
+    ss = parts.cpu().numpy().astype(np.float64)
+    rounded = I.bf16_bits_to_f32(yb).astype(np.float64) ** 2
+    for p_ in range(parts.shape[0]):
+        assert np.allclose(ss[p_], rounded[:, 128 * p_:128 * p_ + 128].sum(axis=1), rtol=1e-5)
+    y2, _ = vc.vitcop_project(dev(x), dev(w), residual=dev(r), scratch=False)
+    assert_bf16_of(host_bits(y2), ref, f"project (one pass over k) {M}x{N}x{K}")
+
+
 def test_project_residual_and_strides(vc):
     M, N, K = 200, 256, 128
     x = I.normal_bf16(1, 0, (M, K)); w = I.normal_bf16(1, 1, (N, K), 0.1); r = I.normal_bf16(1, 2, (M, N))
