@@ -10,14 +10,18 @@
 //     of the next (two segments);
 //   * both operands are fetched with whole 128-byte lines per 8 lanes (the vector memory path
 //     moves lines, so the MFMA operand layout, 32 rows x 32 bytes per instruction, would cost four
-//     times the cycles) into registers, several units ahead of the multiply, and written to one of
+//     times the cycles) into registers, two units ahead of the multiply, and written to one of
 //     two LDS slabs one unit before their use, with the same swizzle as the big-tile GEMM; all
 //     loads are ordinary ones, so the compiler's own counting of outstanding loads places every
-//     wait;
+//     wait (mixed with direct-to-LDS loads it falls back to full drains);
+//   * the four wavefronts sit 2 x 2 over the (rows of x) x (128 columns) tile;
+//   * up to three weight matrices can sit side by side in one launch (K, Q and V; gate and up);
 //   * every segment writes an fp32 partial tile; a second kernel adds the partials of a column
-//     group in workgroup order (deterministic), adds the residual, rounds to bf16 and, for the
-//     K projection, forms the per-128-column sums of squares of the rounded outputs for the
-//     K-norm of Eq. 4.
+//     group in workgroup order (deterministic) and finishes the rows in one of three ways: residual,
+//     bf16 rounding and, for the K projection, the per-128-column sums of squares of the rounded
+//     outputs for the K-norm of Eq. 4; the same plus the RMSNorm of the finished row; or the gated
+//     activation silu(gate) * up of the MLP.  The same reductions serve the split-K launches of the
+//     big-tile kernel (gemm.hip), whose partials are whole slices.
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -29,11 +33,10 @@ constexpr int SK_UNIT = 64;           // k-values per unit (one 128-byte line pe
 constexpr int SK_MAX_ROWS = 256;
 constexpr int SK_MAX_WGS = 256;       // one per CU
 
-// units held in registers (one being stored, the others in flight): as many as the register file takes
-template <int MB>
-constexpr int sk_slots() {
-    return 2;
-}
+// Units held in registers: the one being stored to LDS and one more in flight behind it.  A deeper
+// ring does not put more bytes in flight: a CU's load queue fills, the wavefront blocks on issuing
+// the prologue's loads, and the first multiply only starts later (measured with 4, 6 and 8 slots).
+constexpr int SK_SLOTS = 2;
 
 struct SkPick {
     int mi, start;
@@ -53,9 +56,9 @@ __host__ __device__ __forceinline__ int sk_first_unit(int i, int q, int r) { ret
 template <int MB>
 __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, SkMats mats, int64_t w_stride, int M, int N, int K,
-    int m_chunk, int units_q, int units_r, float* __restrict__ part, const uint16_t* __restrict__ res,
+    int units_q, int units_r, float* __restrict__ part, const uint16_t* __restrict__ res,
     int64_t res_stride) {
-    constexpr int NSLOT = sk_slots<MB>();
+    constexpr int NSLOT = SK_SLOTS;
     constexpr int XROWS = MB * 32;
     constexpr int ROWS = XROWS + SK_COLS;                // slab rows: x, then the group's rows of W
     constexpr int SLAB = ROWS * 128;                     // bytes: 64 k-values per row
@@ -78,10 +81,7 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
     const int upg = K / SK_UNIT;                         // units per column group
     const int first = sk_first_unit(blockIdx.x, units_q, units_r);
     const int last = sk_first_unit(blockIdx.x + 1, units_q, units_r);    // exclusive; last - first <= upg
-    // blockIdx.y picks a chunk of m_chunk <= MB*32 rows (one chunk for every M the launcher accepts)
-    const int m_base = blockIdx.y * m_chunk;
-    const int m_rows = min(M - m_base, m_chunk);
-    x += (int64_t)m_base * x_stride;
+    const int m_rows = M;                                // <= MB * 32
 
     // every wavefront's LDS accesses are done, its writes visible, after this
     auto lds_barrier = [&]() {
@@ -236,10 +236,10 @@ __global__ __launch_bounds__(SK_THREADS) void gemm_skinny_kernel(
         const int m0 = wr * MI * 32;                         // first row of this wavefront
         // running addresses, 4 rows further per store (kept as additions: what the compiler hoists
         // to the top of the kernel from here runs ahead of the first load)
-        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m_base + m0 + srow) * SK_COLS + wc * 64 + scol;
+        float* out = part + ((int64_t)(2 * blockIdx.x + seg) * M + m0 + srow) * SK_COLS + wc * 64 + scol;
         const int64_t y_stride = mats.y_stride[pick.mi];
-        uint16_t* yrow = mats.y[pick.mi] + (int64_t)(m_base + m0 + srow) * y_stride + n;
-        const uint16_t* rrow = res + (int64_t)(m_base + m0 + srow) * res_stride + n;
+        uint16_t* yrow = mats.y[pick.mi] + (int64_t)(m0 + srow) * y_stride + n;
+        const uint16_t* rrow = res + (int64_t)(m0 + srow) * res_stride + n;
 #pragma unroll
         for (int j = 0; j < MI; ++j) {
             if (m0 + j * 32 >= m_rows) break;
@@ -459,16 +459,15 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_silu_kernel(
         make_uint4(gated(g.x, u.x), gated(g.y, u.y), gated(g.z, u.z), gated(g.w, u.w));
 }
 
-static int skinny_row_chunks(int M) { return M > SK_MAX_ROWS ? 2 : 1; }
 // With this many column groups one workgroup per group already keeps most CUs streaming, at a
 // higher rate each, and the partial tiles and their reduction are saved.
 constexpr int SK_DIRECT_GROUPS = 128;
 static bool skinny_direct(int M, int N, bool want_sumsq) {
-    return !want_sumsq && (N + SK_COLS - 1) / SK_COLS * skinny_row_chunks(M) >= SK_DIRECT_GROUPS;
+    return !want_sumsq && (N + SK_COLS - 1) / SK_COLS >= SK_DIRECT_GROUPS;
 }
 static int skinny_workgroups(int M, int N, int K) {
     const int groups = (N + SK_COLS - 1) / SK_COLS, total = groups * (K / SK_UNIT);
-    return max(groups, min(SK_MAX_WGS / skinny_row_chunks(M), total / 2));
+    return max(groups, min(SK_MAX_WGS, total / 2));
 }
 
 bool gemm_skinny_applies(int M, int N, int K) {
@@ -482,7 +481,7 @@ size_t gemm_skinny_workspace_bytes(int M, int N, int K) {
 
 template <int MB>
 static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const SkMats& mats, int64_t w_stride, int M, int N,
-                             int K, int wgs, int m_chunk, int units_q, int units_r, float* part,
+                             int K, int wgs, int units_q, int units_r, float* part,
                              const uint16_t* res, int64_t res_stride, hipStream_t s) {
     auto kern = gemm_skinny_kernel<MB>;
     constexpr size_t lds = (size_t)2 * (MB * 32 + SK_COLS) * 128;
@@ -494,8 +493,8 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const SkMats& 
         if (rc) return rc;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kern, dim3(wgs, (M + m_chunk - 1) / m_chunk), dim3(SK_THREADS), lds, s, x, x_stride, mats,
-                       w_stride, M, N, K, m_chunk, units_q, units_r, part, res, res_stride);
+    hipLaunchKernelGGL(kern, dim3(wgs), dim3(SK_THREADS), lds, s, x, x_stride, mats, w_stride, M, N, K, units_q,
+                       units_r, part, res, res_stride);
     return launch_status("gemm_skinny");
 }
 
@@ -540,18 +539,17 @@ static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats&
     const bool direct = gated_out == nullptr && skinny_direct(M, N, sumsq_parts != nullptr);
     const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
     float* part = direct ? nullptr : static_cast<float*>(ws);
-    const int m_chunk = skinny_row_chunks(M) == 2 ? SK_MAX_ROWS / 2 : M;
-    const int mb = (m_chunk + 31) / 32;
+    const int mb = (M + 31) / 32;
     const int total = (N + SK_COLS - 1) / SK_COLS * (K / SK_UNIT), units_q = total / wgs, units_r = total % wgs;
     int rc;
     if (mb <= 2)
-        rc = launch_skinny_cfg<2>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
+        rc = launch_skinny_cfg<2>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
     else if (mb <= 4)
-        rc = launch_skinny_cfg<4>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
+        rc = launch_skinny_cfg<4>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
     else if (mb <= 6)
-        rc = launch_skinny_cfg<6>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
+        rc = launch_skinny_cfg<6>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
     else
-        rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, m_chunk, units_q, units_r, part, res, res_stride, s);
+        rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
     if (rc || direct) return rc;
     const SkParts parts{part, units_q, units_r, K / SK_UNIT, M};
     return launch_partial_reduce(parts, N, mats, res, res_stride, sumsq_parts, ln_w, eps, norm_out, norm_stride,
