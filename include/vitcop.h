@@ -356,6 +356,35 @@ typedef struct {
 size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S);
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
 
+/* The paper's whole in-model procedure on ONE sample (Alg. 1): the decoder layers of S; on entry to
+ * layer stage2_layer the n_vis visual tokens are clustered (Alg. 2: vitcop_vic_cluster on their hidden
+ * states and grid positions vis_xy) and replaced by the per-cluster elites and one merged token per
+ * cluster (Alg. 3: vitcop_collab_prune_merge with budget stage2_budget and that layer's K-norms, Eq. 4);
+ * the stages of S (all at layers after stage2_layer) then prune by the Stage III rule.  The number of
+ * visual tokens Stage II leaves is data-dependent (<= stage2_budget when the budget is at least the
+ * number of clusters): the call reads it back and therefore SYNCHRONISES the stream once; a Stage III
+ * budget above it keeps every token.  The new visual block holds the elites in token order, then the
+ * merged tokens in cluster order; a merged token takes the position of the lowest-index token it
+ * absorbed.
+ *   S->B == 1;  S->y_out and S->positions_out (may be NULL) sized for T rows; T_final rows are written
+ *   vis_xy [n_vis,2] fp32 device;  T_final, n_stage2: host ints (n_stage2 may be NULL)
+ *   labels [n_vis], norms [n_vis] fp32, out_index [n_vis]: device outputs of Stage II, may be NULL
+ * D % 32 == 0, n_vis <= VITCOP_VIC_MAX_TOKENS.
+ */
+typedef struct {
+    vitcop_decoder_schedule_t S;
+    int stage2_layer, stage2_budget, n_centers;
+    float d_c, tau;
+    const float* vis_xy;
+    int* T_final;
+    int* n_stage2;
+    int32_t* labels;
+    float* norms;
+    int32_t* out_index;
+} vitcop_full_schedule_t;
+size_t vitcop_full_schedule_workspace_bytes(const vitcop_full_schedule_t* F);
+int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size_t ws_bytes, void* stream);
+
 /* ------------------------------------------------------------------------
  * One decoding step over the KV cache a (pruned) prefill left behind: for the new
  * token of every sample, out = softmax(scale * K q) V over ALL N cached keys.  This

@@ -15,6 +15,7 @@ from __future__ import annotations
 
 import numpy as np
 
+from . import vic_oracle as V
 from . import vitcop_oracle as O
 
 
@@ -123,3 +124,61 @@ def decoder_schedule(h_bits, layer_weights, schedule, Hq: int, Hkv: int, d: int,
             cur_vis = keep
         h = out["y_bits"]
     return {"y": out["y"], "y_bits": h, "positions": pos, "keep_lists": kept, "norms": norms}
+
+
+def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv: int, d: int, vis_start: int,
+                    n_vis: int, positions, eps: float = 1e-5, theta: float = 10000.0, labels=None, k_norms=None,
+                    keep_lists=None):
+    """The in-model procedure of Alg. 1 on ONE sample: decoder layers in sequence; on entry to layer
+    ``stage2["layer"]`` the visual tokens are clustered (Alg. 2 on their hidden states and grid positions
+    ``stage2["xy"]`` [n_vis, 2], with d_c, tau, n_centers) and replaced by the per-cluster elites and one
+    merged token per cluster (Alg. 3 with budget ``stage2["budget"]`` and that layer's K-norms, Eq. 4);
+    the Stage III rule (``schedule`` as in ``decoder_schedule``, layers after Stage II) prunes the rest.
+
+    Readings: the clustering features are the hidden states entering the layer; the K-norms are those of
+    the layer's own K projection of the normalised input, before the rotary embedding; the new visual
+    block is laid out as ``collab_prune_merge`` returns it (elites in token order, then merged tokens in
+    label order) between the unchanged text tokens; a merged token takes the position of the
+    lowest-index token it absorbed and is stored in bf16; a Stage III budget above the number of visual
+    tokens Stage II left keeps them all.
+
+    ``labels`` [n_vis] and ``k_norms`` [n_vis] replace the clustering and the norms computed here (for
+    checking a pipeline whose own, separately validated, values decide differently among near-ties).
+    Returns the final hidden state, positions, and what Stage II produced.
+    """
+    h = np.asarray(h_bits)
+    pos = np.asarray(positions)
+    assert h.shape[0] == 1, "one sample"
+    r16 = O.f64_to_bf16_bits
+    stages = dict(schedule)
+    cur_vis = n_vis
+    s2 = None
+    out = None
+    for l, w in enumerate(layer_weights):
+        if l == stage2["layer"]:
+            T = h.shape[1]
+            a = r16(rmsnorm(h, w["ln1"], eps))
+            k_all = r16(O.project(a, w["wk"])).reshape(1, T, Hkv, d)
+            norms = O.k_norms(k_all, vis_start, cur_vis)[0] if k_norms is None else np.asarray(k_norms)
+            feats = h[0, vis_start:vis_start + cur_vis]
+            if labels is None:
+                lab = V.vic_cluster(feats, stage2["xy"], stage2["d_c"], stage2["tau"], stage2["n_centers"])["labels"]
+            else:
+                lab = np.asarray(labels)
+            cm = V.collab_prune_merge(feats, lab, norms, stage2["budget"])
+            n_out = len(cm["index"])
+            new_vis = r16(cm["feats"]).reshape(n_out, h.shape[2])
+            h = np.concatenate([h[:, :vis_start], new_vis[None], h[:, vis_start + cur_vis:]], axis=1)
+            vis_pos = pos[0, vis_start + cm["index"].astype(np.int64)]
+            pos = np.concatenate([pos[:, :vis_start], vis_pos[None], pos[:, vis_start + cur_vis:]], axis=1)
+            s2 = {"labels": lab, "norms": norms, "index": cm["index"], "n_out": n_out, "elite": cm["elite"],
+                  "feats": cm["feats"]}
+            cur_vis = n_out
+        keep = min(stages.get(l, cur_vis), cur_vis)
+        forced = None if keep_lists is None else keep_lists.get(l)
+        out = decoder_layer(h, w, Hq, Hkv, d, vis_start, cur_vis, keep, pos, eps, theta, keep_idx=forced)
+        if l in stages:
+            pos = out["positions"]
+            cur_vis = keep
+        h = out["y_bits"]
+    return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2}

@@ -39,6 +39,7 @@ EXPORTS = (
     "vitcop_decoder_layer_workspace_bytes", "vitcop_decoder_layer_prefill",
     "vitcop_decode_attn_workspace_bytes", "vitcop_decode_attn",
     "vitcop_decoder_schedule_workspace_bytes", "vitcop_decoder_schedule_prefill",
+    "vitcop_full_schedule_workspace_bytes", "vitcop_full_schedule_prefill",
 )
 
 
@@ -84,6 +85,13 @@ class DecoderScheduleT(C.Structure):
                  ("h", C.c_void_p), ("positions", C.c_void_p)] +
                 [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
                 [("y_out", C.c_void_p), ("positions_out", C.c_void_p)])
+
+
+class FullScheduleT(C.Structure):
+    _fields_ = [("S", DecoderScheduleT), ("stage2_layer", C.c_int), ("stage2_budget", C.c_int),
+                ("n_centers", C.c_int), ("d_c", C.c_float), ("tau", C.c_float), ("vis_xy", C.c_void_p),
+                ("T_final", C.POINTER(C.c_int)), ("n_stage2", C.POINTER(C.c_int)),
+                ("labels", C.c_void_p), ("norms", C.c_void_p), ("out_index", C.c_void_p)]
 
 
 class ScheduleT(C.Structure):
@@ -165,6 +173,10 @@ def _load() -> C.CDLL:
     lib.vitcop_decoder_schedule_workspace_bytes.argtypes = [C.POINTER(DecoderScheduleT)]
     lib.vitcop_decoder_schedule_prefill.restype = i32
     lib.vitcop_decoder_schedule_prefill.argtypes = [C.POINTER(DecoderScheduleT), vp, sz, vp]
+    lib.vitcop_full_schedule_workspace_bytes.restype = sz
+    lib.vitcop_full_schedule_workspace_bytes.argtypes = [C.POINTER(FullScheduleT)]
+    lib.vitcop_full_schedule_prefill.restype = i32
+    lib.vitcop_full_schedule_prefill.argtypes = [C.POINTER(FullScheduleT), vp, sz, vp]
     return lib
 
 
@@ -526,6 +538,48 @@ class DecoderSchedulePlan:
     def run(self):
         _check(lib.vitcop_decoder_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
         return self.y
+
+
+class FullSchedulePlan:
+    """Pre-marshalled vitcop_full_schedule_prefill call (one sample).  ``stage2``: dict with layer, budget,
+    n_centers, d_c, tau and xy (device tensor [n_vis, 2] fp32); ``schedule``: the Stage III stages after it.
+    ``run`` returns (y [1, T_final, D], positions [1, T_final]); labels, norms, out_index and n_stage2 hold
+    what Stage II produced."""
+
+    def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, stage2: dict,
+                 schedule, eps: float = 1e-5, theta: float = 10000.0):
+        B, T, D = h.shape
+        n_layers = len(weights)
+        F = weights[0]["wg"].shape[0]
+        self.keepalive = (h, positions, weights, stage2["xy"])
+        layers = [int(s[0]) for s in schedule]
+        keeps = [int(s[1]) for s in schedule]
+        self._pl = (C.c_int * max(len(layers), 1))(*layers)
+        self._pk = (C.c_int * max(len(keeps), 1))(*keeps)
+        self._w = [(C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights]) for n in _DEC_WEIGHTS]
+        self._y = torch.empty((B, T, D), dtype=h.dtype, device=h.device)
+        self._pos = torch.empty((B, T), dtype=torch.int32, device=h.device)
+        self.labels = torch.empty((n_vis,), dtype=torch.int32, device=h.device)
+        self.norms = torch.empty((n_vis,), dtype=torch.float32, device=h.device)
+        self._out_index = torch.empty((n_vis,), dtype=torch.int32, device=h.device)
+        self._T_final, self._n2 = C.c_int(0), C.c_int(0)
+        S = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
+                             self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self._y),
+                             _ptr(self._pos))
+        self.desc = FullScheduleT(S, int(stage2["layer"]), int(stage2["budget"]), int(stage2["n_centers"]),
+                                  float(stage2["d_c"]), float(stage2["tau"]), _ptr(stage2["xy"]),
+                                  C.pointer(self._T_final), C.pointer(self._n2), _ptr(self.labels),
+                                  _ptr(self.norms), _ptr(self._out_index))
+        nb = lib.vitcop_full_schedule_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, h)
+
+    def run(self):
+        _check(lib.vitcop_full_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        self.T_final, self.n_stage2 = self._T_final.value, self._n2.value
+        self.out_index = self._out_index[: self.n_stage2]
+        return self._y[:, : self.T_final], self._pos[:, : self.T_final]
 
 
 class SchedulePlan:

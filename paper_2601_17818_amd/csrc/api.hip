@@ -255,14 +255,23 @@ static int check_layer(const vitcop_layer_t* L) {
 
 // Scratch of the few-row projection path: the largest need among a layer's projections (rows
 // before and after pruning; F = 0: no MLP).
+// The need is not monotone in the row count (different paths below 257 and below 1025 rows, slice
+// counts that drop as tiles are added), and a schedule sizes its workspace for its longest sequence:
+// so a launch of M rows reserves the largest need of any row count up to M.  The need grows with M
+// between tile boundaries, which are multiples of 64.
+static size_t gemm_scratch_upto(int M, int N, int K) {
+    size_t n = gemm_workspace_bytes(M, N, K);
+    for (int m = 64; m < M && m <= 1024; m += 64) n = std::max(n, gemm_workspace_bytes(m, N, K));
+    return n;
+}
 static size_t layer_gemm_scratch(int M_all, int M_kept, int D, int qd, int kd, int F) {
-    size_t n = gemm_workspace_bytes(M_all, kd, D);                               // K
-    n = std::max(n, gemm_workspace_bytes(M_kept, qd + kd, D));                   // Q and V
-    n = std::max(n, gemm_workspace_bytes(M_all, qd + 2 * kd, D));                // K, Q and V of a layer that keeps all
-    n = std::max(n, gemm_workspace_bytes(M_kept, D, qd));                        // O
+    size_t n = gemm_scratch_upto(M_all, kd, D);                                  // K
+    n = std::max(n, gemm_scratch_upto(M_kept, qd + kd, D));                      // Q and V
+    n = std::max(n, gemm_scratch_upto(M_all, qd + 2 * kd, D));                   // K, Q and V of a layer that keeps all
+    n = std::max(n, gemm_scratch_upto(M_kept, D, qd));                           // O
     if (F > 0) {
-        n = std::max(n, gemm_workspace_bytes(M_kept, 2 * F, D));                 // gate and up
-        n = std::max(n, gemm_workspace_bytes(M_kept, D, F));                     // down
+        n = std::max(n, gemm_scratch_upto(M_kept, 2 * F, D));                    // gate and up
+        n = std::max(n, gemm_scratch_upto(M_kept, D, F));                        // down
     }
     return n;
 }
@@ -776,6 +785,50 @@ size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* 
     return layer_max + 4 * up256(B * T * D * 2) + 2 * up256(B * T * 4);      // hidden and normalised, ping-pong
 }
 
+// State carried from layer to layer of a whole-model run, and the ping-pong buffers it lives in.
+struct DecoderRun {
+    const uint16_t* h;            // hidden state entering the next layer
+    const uint16_t* a_pre;        // its RMSNorm with that layer's ln1, if the layer before left it
+    const int32_t* pos;
+    int cur_T, cur_vis, stage, pp;
+    uint16_t* hbuf[2];
+    uint16_t* abuf[2];
+    int32_t* pbuf[2];
+    void* lws;
+    size_t lws_bytes;
+};
+
+// Layers [l_begin, l_end) of S; a Stage III budget above the visual tokens still present keeps them all.
+static int run_decoder_layers(const vitcop_decoder_schedule_t* S, int l_begin, int l_end, DecoderRun& r,
+                              void* stream) {
+    for (int l = l_begin; l < l_end; ++l) {
+        vitcop_decoder_layer_t L = first_decoder_layer(S);
+        L.T = r.cur_T; L.n_vis = r.cur_vis; L.keep = r.cur_vis;
+        L.h = r.h; L.positions = r.pos;
+        L.ln1 = S->ln1[l]; L.ln2 = S->ln2[l]; L.wq = S->wq[l]; L.wk = S->wk[l]; L.wv = S->wv[l]; L.wo = S->wo[l];
+        L.wg = S->wg[l]; L.wu = S->wu[l]; L.wd = S->wd[l];
+        const bool last = l + 1 == S->n_layers;
+        const bool prune_here = r.stage < S->n_stages && S->prune_layer[r.stage] == l;
+        if (prune_here) {
+            L.keep = std::min(S->prune_keep[r.stage++], r.cur_vis);
+            L.positions_out = r.pbuf[r.pp];
+        }
+        L.y = last ? S->y_out : r.hbuf[l & 1];
+        const uint16_t* ln_next = last ? nullptr : static_cast<const uint16_t*>(S->ln1[l + 1]);
+        int rc = decoder_layer_run(&L, r.a_pre, ln_next, r.abuf[l & 1], r.lws, r.lws_bytes, stream);
+        if (rc) return rc;
+        r.a_pre = ln_next ? r.abuf[l & 1] : nullptr;
+        if (prune_here) {
+            r.pos = r.pbuf[r.pp];
+            r.pp ^= 1;
+            r.cur_T = r.cur_T - r.cur_vis + L.keep;
+            r.cur_vis = L.keep;
+        }
+        r.h = L.y;
+    }
+    return VITCOP_OK;
+}
+
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream) {
     int rc = check_decoder_schedule(S);
     if (rc) return rc;
@@ -787,43 +840,170 @@ int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws
     hipStream_t s = static_cast<hipStream_t>(stream);
     const size_t B = S->B, T = S->T, D = S->D;
     Carver c(ws);
-    uint16_t* hbuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
-    uint16_t* abuf[2] = {c.take<uint16_t>(B * T * D * 2), c.take<uint16_t>(B * T * D * 2)};
-    int32_t* pbuf[2] = {c.take<int32_t>(B * T * 4), c.take<int32_t>(B * T * 4)};
-    void* lws = c.base + c.used;
-    const size_t lws_bytes = ws_bytes - c.used;
-
-    const uint16_t* h = S->h;
-    const uint16_t* a_pre = nullptr;          // RMSNorm of h with this layer's ln1, left by the layer before
-    const int32_t* pos = S->positions;
-    int cur_T = S->T, cur_vis = S->n_vis, stage = 0, pp = 0;
-    for (int l = 0; l < S->n_layers; ++l) {
-        vitcop_decoder_layer_t L = first_decoder_layer(S);
-        L.T = cur_T; L.n_vis = cur_vis; L.keep = cur_vis;
-        L.h = h; L.positions = pos;
-        L.ln1 = S->ln1[l]; L.ln2 = S->ln2[l]; L.wq = S->wq[l]; L.wk = S->wk[l]; L.wv = S->wv[l]; L.wo = S->wo[l];
-        L.wg = S->wg[l]; L.wu = S->wu[l]; L.wd = S->wd[l];
-        const bool last = l + 1 == S->n_layers;
-        const bool prune_here = stage < S->n_stages && S->prune_layer[stage] == l;
-        if (prune_here) {
-            L.keep = S->prune_keep[stage++];
-            L.positions_out = pbuf[pp];
-        }
-        L.y = last ? S->y_out : hbuf[l & 1];
-        const uint16_t* ln_next = last ? nullptr : static_cast<const uint16_t*>(S->ln1[l + 1]);
-        rc = decoder_layer_run(&L, a_pre, ln_next, abuf[l & 1], lws, lws_bytes, stream);
-        if (rc) return rc;
-        a_pre = ln_next ? abuf[l & 1] : nullptr;
-        if (prune_here) {
-            pos = pbuf[pp];
-            pp ^= 1;
-            cur_T = cur_T - cur_vis + L.keep;
-            cur_vis = L.keep;
-        }
-        h = L.y;
-    }
+    DecoderRun r{S->h, nullptr, S->positions, S->T, S->n_vis, 0, 0, {}, {}, {}, nullptr, 0};
+    for (int i = 0; i < 2; ++i) r.hbuf[i] = c.take<uint16_t>(B * T * D * 2);
+    for (int i = 0; i < 2; ++i) r.abuf[i] = c.take<uint16_t>(B * T * D * 2);
+    for (int i = 0; i < 2; ++i) r.pbuf[i] = c.take<int32_t>(B * T * 4);
+    r.lws = c.base + c.used;
+    r.lws_bytes = ws_bytes - c.used;
+    rc = run_decoder_layers(S, 0, S->n_layers, r, stream);
+    if (rc) return rc;
     if (S->positions_out) {
-        rc = hip_status(hipMemcpyAsync(S->positions_out, pos, (size_t)B * cur_T * 4, hipMemcpyDeviceToDevice, s),
+        rc = hip_status(hipMemcpyAsync(S->positions_out, r.pos, (size_t)B * r.cur_T * 4, hipMemcpyDeviceToDevice, s),
+                        "copy positions");
+    }
+    return rc;
+}
+
+/* ------------------------------------------- whole procedure with Stage II */
+
+// Positions of the sequence after Stage II: text before the visual block unchanged, row j of the new
+// visual block takes the position of its representative token, text after it unchanged.
+__global__ void stage2_positions_kernel(const int32_t* __restrict__ pos, const int32_t* __restrict__ out_index,
+                                        int vis_start, int n_vis, int n_out, int T_new,
+                                        int32_t* __restrict__ pos_out) {
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= T_new) return;
+    int src = j;
+    if (j >= vis_start + n_out)
+        src = j - n_out + n_vis;
+    else if (j >= vis_start)
+        src = vis_start + out_index[j - vis_start];
+    pos_out[j] = pos[src];
+}
+
+static int check_full_schedule(const vitcop_full_schedule_t* F) {
+    REQUIRE(F, VITCOP_EINVAL, "full_schedule: descriptor is null");
+    const vitcop_decoder_schedule_t* S = &F->S;
+    int rc = check_decoder_schedule(S);
+    if (rc) return rc;
+    REQUIRE(S->B == 1, VITCOP_EUNSUPPORTED, "full_schedule: B=%d (Stage II leaves a data-dependent length: one sample)",
+            S->B);
+    REQUIRE(F->stage2_layer >= 0 && F->stage2_layer < S->n_layers, VITCOP_EINVAL, "full_schedule: stage2_layer=%d",
+            F->stage2_layer);
+    REQUIRE(S->n_stages == 0 || S->prune_layer[0] > F->stage2_layer, VITCOP_EINVAL,
+            "full_schedule: Stage III layers must come after layer %d", F->stage2_layer);
+    REQUIRE(F->stage2_budget >= 0 && F->stage2_budget <= S->n_vis, VITCOP_EINVAL, "full_schedule: stage2_budget=%d",
+            F->stage2_budget);
+    return check_vic(1, S->n_vis, S->D, F->d_c, F->tau, F->n_centers);
+}
+
+// Stage II scratch: K of all tokens, norm partials, the identity keep list the norm pass writes, norms,
+// labels, cluster count, the new visual block, its representatives, its size; then the two stages' own.
+static size_t full_schedule_stage2_bytes(const vitcop_full_schedule_t* F) {
+    const vitcop_decoder_schedule_t* S = &F->S;
+    const size_t T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
+    size_t b = up256(T * D * 2) + up256(T * D * 2) + up256(T * kd * 2) +
+               up256((size_t)gemm_sumsq_parts((int)kd) * T * 4) + up256(T * 4);
+    b += 2 * up256(n * 4) + 2 * up256(16) + up256(n * D * 2) + up256(n * 4);
+    b += up256(vic_workspace_bytes(1, (int)n)) + up256(collab_workspace_bytes(1, (int)n));
+    b += up256(gemm_workspace_bytes((int)T, (int)kd, (int)D));
+    return b;
+}
+
+size_t vitcop_full_schedule_workspace_bytes(const vitcop_full_schedule_t* F) {
+    if (check_full_schedule(F) != VITCOP_OK) return 0;
+    return vitcop_decoder_schedule_workspace_bytes(&F->S) + full_schedule_stage2_bytes(F);
+}
+
+int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_full_schedule(F);
+    if (rc) return rc;
+    const vitcop_decoder_schedule_t* S = &F->S;
+    REQUIRE(S->h && S->positions && S->y_out && S->ln1 && S->ln2 && S->wq && S->wk && S->wv && S->wo && S->wg &&
+                S->wu && S->wd && F->vis_xy && F->T_final,
+            VITCOP_EINVAL, "full_schedule: null pointer");
+    const size_t need = vitcop_full_schedule_workspace_bytes(F);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "full_schedule: workspace needs %zu bytes", need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const size_t T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
+    const int vs = S->vis_start, P = gemm_sumsq_parts((int)kd), ls = F->stage2_layer;
+    Carver c(ws);
+    DecoderRun r{S->h, nullptr, S->positions, S->T, S->n_vis, 0, 0, {}, {}, {}, nullptr, 0};
+    for (int i = 0; i < 2; ++i) r.hbuf[i] = c.take<uint16_t>(T * D * 2);
+    for (int i = 0; i < 2; ++i) r.abuf[i] = c.take<uint16_t>(T * D * 2);
+    for (int i = 0; i < 2; ++i) r.pbuf[i] = c.take<int32_t>(T * 4);
+    uint16_t* h_new = c.take<uint16_t>(T * D * 2);
+    uint16_t* a_all = c.take<uint16_t>(T * D * 2);
+    uint16_t* k_all = c.take<uint16_t>(T * kd * 2);
+    float* parts = c.take<float>((size_t)P * T * 4);
+    int32_t* idx_all = c.take<int32_t>(T * 4);
+    float* norms = c.take<float>(n * 4);
+    int32_t* labels = c.take<int32_t>(n * 4);
+    int32_t* n_clusters = c.take<int32_t>(16);
+    int32_t* n_out_dev = c.take<int32_t>(16);
+    uint16_t* out_feats = c.take<uint16_t>(n * D * 2);
+    int32_t* out_index = c.take<int32_t>(n * 4);
+    void* vic_ws = c.take<char>(vic_workspace_bytes(1, (int)n));
+    void* collab_ws = c.take<char>(collab_workspace_bytes(1, (int)n));
+    const size_t gs_bytes = gemm_workspace_bytes((int)T, (int)kd, (int)D);
+    void* gs = c.take<char>(gs_bytes);
+    r.lws = c.base + c.used;
+    r.lws_bytes = ws_bytes - c.used;
+
+    rc = run_decoder_layers(S, 0, ls, r, stream);
+    if (rc) return rc;
+
+    // Stage II on entry to layer ls.  K-norms of that layer (Eq. 4): K of the normalised input with the
+    // squared norms as a side output; keeping all n_vis tokens makes the selection pass write the norms.
+    const uint16_t* a = r.a_pre;
+    if (!a) {
+        rc = launch_rmsnorm(r.h, D, S->ln1[ls], S->eps, a_all, D, (int)T, (int)D, s);
+        if (rc) return rc;
+        a = a_all;
+    }
+    rc = launch_gemm_ws(a, D, S->wk[ls], k_all, kd, nullptr, 0, (int)T, (int)kd, (int)D, parts, gs, gs_bytes, s);
+    if (rc) return rc;
+    rc = launch_select_smallest(parts, P, (int64_t)T, T, vs, 1, norms, 1, (int)T, vs, (int)n, (int)n, idx_all, s);
+    if (rc) return rc;
+    const uint16_t* feats = r.h + (size_t)vs * D;
+    if (n > 0) {
+        rc = launch_vic(feats, D, (int64_t)T * D, F->vis_xy, 1, (int)n, (int)D, F->d_c, F->tau, F->n_centers, labels,
+                        n_clusters, nullptr, nullptr, nullptr, nullptr, vic_ws, s);
+        if (rc) return rc;
+        rc = launch_collab(feats, D, (int64_t)T * D, labels, n_clusters, norms, 1, (int)n, (int)D, F->stage2_budget,
+                           out_feats, out_index, n_out_dev, nullptr, collab_ws, s);
+        if (rc) return rc;
+    }
+    int n_out = 0;
+    if (n > 0) {
+        rc = hip_status(hipMemcpyAsync(&n_out, n_out_dev, 4, hipMemcpyDeviceToHost, s), "read Stage II count");
+        if (rc) return rc;
+    }
+    rc = hip_status(hipStreamSynchronize(s), "hipStreamSynchronize");
+    if (rc) return rc;
+    REQUIRE(n_out >= 0 && (size_t)n_out <= n, VITCOP_EHIP, "full_schedule: Stage II returned %d tokens", n_out);
+    if (F->n_stage2) *F->n_stage2 = n_out;
+    auto copy = [&](void* dst, const void* src, size_t bytes) {
+        if (rc == VITCOP_OK && dst && bytes)
+            rc = hip_status(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s), "copy after Stage II");
+    };
+    copy(F->labels, labels, n * 4);
+    copy(F->norms, norms, n * 4);
+    copy(F->out_index, out_index, (size_t)n_out * 4);
+    // the new sequence: text, new visual block, text
+    const size_t T_new = T - n + (size_t)n_out, tail = T - vs - n;
+    copy(h_new, r.h, (size_t)vs * D * 2);
+    copy(h_new + (size_t)vs * D, out_feats, (size_t)n_out * D * 2);
+    copy(h_new + ((size_t)vs + n_out) * D, r.h + ((size_t)vs + n) * D, tail * D * 2);
+    if (rc) return rc;
+    int32_t* pos_new = r.pbuf[r.pp];
+    hipLaunchKernelGGL(stage2_positions_kernel, dim3((unsigned)((T_new + 255) / 256)), dim3(256), 0, s, r.pos,
+                       out_index, vs, (int)n, n_out, (int)T_new, pos_new);
+    rc = launch_status("stage2_positions");
+    if (rc) return rc;
+    r.h = h_new;
+    r.a_pre = nullptr;
+    r.pos = pos_new;
+    r.pp ^= 1;
+    r.cur_T = (int)T_new;
+    r.cur_vis = n_out;
+
+    rc = run_decoder_layers(S, ls, S->n_layers, r, stream);
+    if (rc) return rc;
+    *F->T_final = r.cur_T;
+    if (S->positions_out) {
+        rc = hip_status(hipMemcpyAsync(S->positions_out, r.pos, (size_t)r.cur_T * 4, hipMemcpyDeviceToDevice, s),
                         "copy positions");
     }
     return rc;

@@ -292,6 +292,36 @@ def test_decoder_schedule_validation():
     assert ws(C.byref(desc(layers=(), keeps=()))) > 0
 
 
+def test_full_schedule_validation():
+    assert C.sizeof(binding.FullScheduleT) == C.sizeof(binding.DecoderScheduleT) + 3 * 4 + 2 * 4 + 4 + 6 * 8
+    ptrs = (C.c_void_p * 4)(*[A16] * 4)
+    t_final = C.c_int(0)
+
+    def desc(B=1, layers=(3,), keeps=(32,), stage2_layer=1, budget=128, n_centers=20, d_c=8.0, tau=0.6, xy=A16,
+             t_ptr=True, **kw):
+        base = dict(B=B, T=640, D=4096, Hq=32, Hkv=32, d=128, F=11008, vis_start=35, n_vis=576, n_layers=4,
+                    n_stages=len(layers), eps=1e-5, theta=10000.0,
+                    prune_layer=(C.c_int * max(len(layers), 1))(*layers),
+                    prune_keep=(C.c_int * max(len(keeps), 1))(*keeps),
+                    h=A16, positions=A16, y_out=A16, positions_out=None)
+        base.update({n: C.cast(ptrs, C.POINTER(C.c_void_p)) for n in binding._DEC_WEIGHTS})
+        base.update(kw)
+        return binding.FullScheduleT(binding.DecoderScheduleT(**base), stage2_layer, budget, n_centers, d_c, tau, xy,
+                                     C.pointer(t_final) if t_ptr else None, None, None, None, None)
+
+    ws = lib.vitcop_full_schedule_workspace_bytes
+    run = lib.vitcop_full_schedule_prefill
+    need = ws(C.byref(desc()))
+    assert need > lib.vitcop_decoder_schedule_workspace_bytes(C.byref(desc().S)) + 576 * 576 * 4
+    assert run(C.byref(desc()), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    assert run(C.byref(desc(B=2)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED       # one sample
+    for bad in (desc(stage2_layer=4), desc(stage2_layer=3), desc(budget=600), desc(n_centers=600), desc(d_c=0.0),
+                desc(tau=-1.0), desc(xy=None), desc(t_ptr=False), desc(layers=(3, 2), keeps=(32, 16))):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    assert ws(C.byref(desc(stage2_layer=3))) == 0          # Stage III must come after Stage II
+    assert ws(C.byref(desc(layers=(), keeps=()))) > 0
+
+
 def test_decode_validation():
     f = lib.vitcop_decode_attn
     need = lib.vitcop_decode_attn_workspace_bytes(4, 384, 32, 32, 128)

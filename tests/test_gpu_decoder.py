@@ -6,6 +6,7 @@ import torch
 
 import vitcop_inputs as I
 from oracle import decoder_oracle as Dc
+from oracle import vic_oracle as V
 from oracle import vitcop_oracle as O
 from gpu_util import assert_attention_close, assert_selection_matches, dev, host_bits, host_f64
 
@@ -158,3 +159,59 @@ def test_decoder_schedule_matches_oracle(vc):
     ref0 = Dc.decoder_schedule(h, layers, (), Hq, Hkv, d, vs, nv, pos)
     assert_attention_close(host_f64(plan0.y), ref0["y"], "unpruned decoder schedule")
     assert np.array_equal(plan0.positions.cpu().numpy(), pos)
+
+
+def full_case(seed, vs, n, tail, D, Hq, Hkv, d, F, n_layers, grid, regions):
+    """Text tokens ~ N(0,1); visual hidden states = planted spatial regions (vic_inputs); small output
+    projections keep the residual stream close to the input, so the regions survive the first layers."""
+    T = vs + n + tail
+    layers = [I.decoder_inputs(seed + 1 + l, 1, T, D, Hq, Hkv, d, F)["w"] for l in range(n_layers)]
+    for w in layers:
+        for name in ("wo", "wd"):
+            w[name] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w[name]) * np.float32(0.25))
+    h = I.decoder_inputs(seed, 1, T, D, Hq, Hkv, d, F)["h"].copy()
+    v = I.vic_inputs(seed, n, D, grid, regions, 0.15)
+    h[0, vs:vs + n] = v["feats"]
+    return h, layers, v["pos"]
+
+
+@pytest.mark.parametrize("stage2_layer,schedule", [(1, ()), (0, ((2, 24),)), (2, ((3, 100),))])
+def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
+    # Alg. 1 end to end on one sample: decoder layers, Stage II (clustering + elites + merging) on entry
+    # to one layer, Stage III (K-norm top-k) later.  The oracle is given the GPU's labels and norms (each
+    # validated against the oracle's own below and in the Stage II tests), so its discrete steps decide
+    # on the same numbers; a Stage III keep list is read off the final positions.
+    D, Hq, Hkv, d, F, vs, n, tail = 256, 4, 2, 128, 352, 12, 150, 10
+    T = vs + n + tail
+    h, layers, xy = full_case(9900, vs, n, tail, D, Hq, Hkv, d, F, 4, 16, 6)
+    pos = (2 * np.arange(T))[None].astype(np.int32)
+    s2 = {"layer": stage2_layer, "budget": 60, "n_centers": 6, "d_c": 8.0, "tau": 0.6}
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    plan = vc.FullSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, n,
+                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)).cuda()}, schedule)
+    y, p = plan.run()
+    torch.cuda.synchronize()
+    labels, norms = plan.labels.cpu().numpy(), plan.norms.cpu().numpy()
+    # Stage II alone (no Stage III) with the oracle's own clustering and norms: same partition, close norms
+    own = Dc.vitcop_schedule(h, layers[: stage2_layer + 1], {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos)
+    assert V.same_partition(labels, own["stage2"]["labels"])
+    assert np.allclose(norms, own["stage2"]["norms"], rtol=2e-3)
+    # the whole run on the GPU's labels and norms
+    ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos, labels=labels, k_norms=norms)
+    st = ref["stage2"]
+    assert plan.n_stage2 == st["n_out"] <= s2["budget"]
+    assert np.array_equal(plan.out_index.cpu().numpy(), st["index"])
+    got_pos = p.cpu().numpy()
+    if schedule:
+        (l3, k3), = schedule
+        k3 = min(k3, st["n_out"])
+        after2 = ref["positions"][0]                    # positions after Stage II (no Stage III in `ref`)
+        assert plan.T_final == T - n + k3
+        lookup = {int(q): i for i, q in enumerate(after2)}                      # positions are unique
+        idx = np.array([lookup[int(q)] for q in got_pos[0]])
+        assert np.all(np.diff(idx) > 0) and np.array_equal(idx[:vs], np.arange(vs))
+        assert np.array_equal(idx[vs + k3:], np.arange(vs + st["n_out"], len(after2)))
+        ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
+                                 k_norms=norms, keep_lists={l3: idx[None]})
+    assert np.array_equal(got_pos, ref["positions"])
+    assert_attention_close(host_f64(y), ref["y"], "full schedule output")

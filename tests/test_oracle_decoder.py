@@ -123,3 +123,61 @@ def test_decode_attention_against_pinned_prefill_and_library():
     assert np.array_equal(o1[:, 0], f64(t["v"])[:, 0, 0])
     ones = bits(np.ones((2, 57, 2, 64)))
     assert np.allclose(Dc.decode_attention(t["q"][:, 3], t["k"], ones)[0], 1.0)
+
+
+def small_model(seed, n_layers, T, D=128, Hq=4, Hkv=2, d=64, F=96):
+    layers = [I.decoder_inputs(seed + 1 + l, 1, T, D, Hq, Hkv, d, F)["w"] for l in range(n_layers)]
+    return I.decoder_inputs(seed, 1, T, D, Hq, Hkv, d, F)["h"], layers
+
+
+def test_vitcop_schedule_with_one_token_per_cluster_is_the_plain_schedule():
+    # every token its own cluster and a budget below the number of clusters: no elites, every
+    # "merged" token is the mean of one token, in token order: Stage II changes nothing
+    h, layers = small_model(300, 3, 40)
+    pos = (3 * np.arange(40))[None]
+    s2 = {"layer": 1, "budget": 20, "xy": None, "d_c": 8.0, "tau": 0.6, "n_centers": 0}
+    got = Dc.vitcop_schedule(h, layers, s2, (), 4, 2, 64, 6, 28, pos, labels=np.arange(28))
+    want = Dc.decoder_schedule(h, layers, (), 4, 2, 64, 6, 28, pos)
+    assert got["stage2"]["n_out"] == 28 and np.array_equal(got["stage2"]["index"], np.arange(28))
+    assert np.array_equal(got["y_bits"], want["y_bits"]) and np.array_equal(got["positions"], pos)
+
+
+def test_vitcop_schedule_single_cluster_by_hand():
+    # one cluster, budget 5: the 4 smallest K-norms stay as they are (in token order), the other 20
+    # tokens become one token, their mean, at the position of the first of them; then layers 1, 2
+    # run on 6 + 5 + 6 tokens.  Rebuilt here step by step from the pinned pieces.
+    T, vs, n = 36, 6, 24
+    h, layers = small_model(310, 3, T)
+    pos = (2 * np.arange(T) + 1)[None]
+    s2 = {"layer": 1, "budget": 5, "xy": None, "d_c": 8.0, "tau": 0.6, "n_centers": 0}
+    got = Dc.vitcop_schedule(h, layers, s2, (), 4, 2, 64, vs, n, pos, labels=np.zeros(n, dtype=np.int64))
+    h1 = Dc.decoder_layer(h, layers[0], 4, 2, 64, vs, n, n, pos)["y_bits"]
+    norms = Dc.decoder_layer(h1, layers[1], 4, 2, 64, vs, n, n, pos)["norms"][0]        # layer 1's own K-norms
+    elite = np.sort(O.topk_smallest(norms, 4))
+    rest = np.setdiff1d(np.arange(n), elite)
+    merged = f64(h1[0, vs + rest]).mean(axis=0)
+    vis = np.concatenate([h1[0, vs + elite], O.f64_to_bf16_bits(merged)[None]], axis=0)
+    h_new = np.concatenate([h1[:, :vs], vis[None], h1[:, vs + n:]], axis=1)
+    pos_new = np.concatenate([pos[0, :vs], pos[0, vs + elite], pos[0, vs + rest[:1]], pos[0, vs + n:]])[None]
+    assert got["stage2"]["n_out"] == 5 and np.array_equal(got["stage2"]["index"], np.append(elite, rest[0]))
+    want = Dc.decoder_schedule(h_new, layers[1:], (), 4, 2, 64, vs, 5, pos_new)
+    assert np.array_equal(got["y_bits"], want["y_bits"]) and np.array_equal(got["positions"], pos_new)
+
+
+def test_vitcop_schedule_clusters_planted_regions_and_clamps_stage3():
+    # visual hidden states = planted spatial regions: Stage II at layer 0 sees them untouched, finds the
+    # regions, and leaves at most `budget` tokens; a Stage III budget above that keeps them all
+    n, D = 60, 128
+    v = I.vic_inputs(41, n, D, 12, 4, 0.1)
+    h, layers = small_model(320, 2, 8 + n + 4, D=D)
+    h = h.copy()
+    h[0, 8:8 + n] = v["feats"]
+    pos = np.arange(8 + n + 4)[None]
+    s2 = {"layer": 0, "budget": 20, "xy": v["pos"], "d_c": 8.0, "tau": 0.6, "n_centers": 4}
+    got = Dc.vitcop_schedule(h, layers, s2, ((1, 50),), 4, 2, 64, 8, n, pos)
+    st = got["stage2"]
+    assert np.array_equal(st["labels"], Dc.V.vic_cluster(v["feats"], v["pos"], 8.0, 0.6, 4)["labels"])
+    assert st["n_out"] <= 20 and got["y"].shape[1] == 12 + st["n_out"]
+    # the same call with the clustering and norms handed in decides the same
+    again = Dc.vitcop_schedule(h, layers, s2, ((1, 50),), 4, 2, 64, 8, n, pos, labels=st["labels"], k_norms=st["norms"])
+    assert np.array_equal(again["y_bits"], got["y_bits"])
