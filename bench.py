@@ -358,6 +358,22 @@ def main():
                            "eq9_flops_ratio": eq9_ratio((64 + v1, 64 + v2, 64 + v3))}
             del plan, xp, pp
         out["decoder_schedule_paper_llava15"] = paper
+        # the same "retain 192" setting with the paper's actual Stage II at layer 2 (clustering, elites,
+        # merging; budget 253) and Stage III at layer 22; the 288 visual hidden states are planted spatial
+        # regions so that the clustering has something to find; one host read-back inside
+        vin = I.vic_inputs(2, 288, 4096, 24, 29, 0.15)
+        xf = x2[:, :64 + 288].clone()
+        xf[0, 35:35 + 288] = dev(vin["feats"])
+        pf = torch.arange(64 + 288, dtype=torch.int32, device="cuda")[None].contiguous()
+        xy = torch.from_numpy(vin["pos"].astype(np.float32)).cuda()
+        fplan = vc.FullSchedulePlan(xf, pf, w_dev, 32, 32, 128, 35, 288,
+                                    {"layer": 2, "budget": 253, "n_centers": 29, "d_c": 8.0, "tau": 0.6, "xy": xy},
+                                    ((22, 51),))
+        t_f = ev_time(fplan.run, 5, warm=2)
+        out["full_schedule_paper_llava15_retain192"] = {
+            "ms": t_f, "speedup_vs_unpruned": t_dunpr / t_f, "visual_after_stage2": fplan.n_stage2,
+            "tokens_final": fplan.T_final}
+        del fplan, xf, pf, xy
         del w_dev, sp, up, dsp, dup
 
     # ------------------------------------------------------ CPU oracle baseline
