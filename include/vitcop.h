@@ -322,6 +322,11 @@ typedef struct {
     int32_t* keep_idx;                /* [B,T'] out, may be NULL */
     int32_t* positions_out;           /* [B,T'] out, may be NULL */
     float* norms;                     /* [B,n_vis] out, may be NULL */
+    /* KV cache of the layer for later decoding steps, may be NULL: K (after the rotary embedding) and V
+     * of the T' kept tokens go to rows [0,T') of each sample's [cache_capacity, Hkv, d] block */
+    uint16_t* k_cache;
+    uint16_t* v_cache;
+    int cache_capacity;               /* rows per sample, >= T' */
 } vitcop_decoder_layer_t;
 size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L);
 int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream);
@@ -352,6 +357,11 @@ typedef struct {
     const uint16_t* const* wd;
     uint16_t* y_out;
     int32_t* positions_out;
+    /* KV caches, may be NULL: host arrays of n_layers device pointers, each [B, cache_capacity, Hkv, d];
+     * layer l fills the rows of the tokens it kept (a pruned prefill leaves shorter caches in later layers) */
+    uint16_t* const* k_cache;
+    uint16_t* const* v_cache;
+    int cache_capacity;
 } vitcop_decoder_schedule_t;
 size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S);
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
@@ -384,6 +394,38 @@ typedef struct {
 } vitcop_full_schedule_t;
 size_t vitcop_full_schedule_workspace_bytes(const vitcop_full_schedule_t* F);
 int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size_t ws_bytes, void* stream);
+
+/* One decoding step of the whole model after a (pruned) prefill (what Table 5 times per generated token):
+ * for the new token of every sample, n_layers decoder layers; layer l projects the token (K, Q, V in one
+ * launch), applies the rotary embedding at positions[b], appends K and V to row n_cached[l] of its cache,
+ * attends over the n_cached[l] + 1 cached keys (vitcop_decode_attn's kernels) and runs the output
+ * projection and the gated MLP with their residual adds.  The caches of a pruned prefill are shorter in
+ * the layers after a pruning point, hence one length per layer.
+ *   h [B,D], positions [B];  y_out [B,D];  k_cache[l], v_cache[l] [B, cache_capacity, Hkv, d]
+ *   n_cached: host [n_layers], each < cache_capacity
+ * B <= 256 (one launch per projection on the few-row path); d in {64,128}.
+ */
+typedef struct {
+    int B, D, Hq, Hkv, d, F, n_layers, cache_capacity;
+    float eps, theta;
+    const int* n_cached;
+    const uint16_t* h;
+    const int32_t* positions;
+    const uint16_t* const* ln1;
+    const uint16_t* const* ln2;
+    const uint16_t* const* wq;
+    const uint16_t* const* wk;
+    const uint16_t* const* wv;
+    const uint16_t* const* wo;
+    const uint16_t* const* wg;
+    const uint16_t* const* wu;
+    const uint16_t* const* wd;
+    uint16_t* const* k_cache;
+    uint16_t* const* v_cache;
+    uint16_t* y_out;
+} vitcop_decoder_decode_t;
+size_t vitcop_decoder_decode_workspace_bytes(const vitcop_decoder_decode_t* S);
+int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_t ws_bytes, void* stream);
 
 /* ------------------------------------------------------------------------
  * One decoding step over the KV cache a (pruned) prefill left behind: for the new

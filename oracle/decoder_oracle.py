@@ -74,7 +74,7 @@ def decoder_layer(h_bits, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_
     m = r16(silu_mul(g, u))
     y = O.bf16_to_f64(h1) + O.project(m, w["wd"])
     return {"y": y, "y_bits": r16(y), "keep_idx": idx, "norms": norms, "positions": pos_kept,
-            "a": a, "q_rope": q_r, "k_rope": k_r, "h1": h1, "m": m}
+            "a": a, "q_rope": q_r, "k_rope": k_r, "v": v, "h1": h1, "m": m}
 
 
 def decode_attention(q_bits, k_bits, v_bits, scale: float | None = None):
@@ -105,25 +105,27 @@ def decoder_schedule(h_bits, layer_weights, schedule, Hq: int, Hkv: int, d: int,
     """Whole-model prefill (layer loop of Alg. 1, Eq. 8): decoder layers in sequence, 0-indexed, pruning on
     entry to the scheduled layers by that layer's own K-norms; the hidden state is carried in bf16.
     ``schedule``: ((layer, keep), ...); ``keep_lists``: optional {layer: keep_idx} overriding the lists
-    computed here.  Returns the final hidden state (float64, bits), positions, and per pruning layer the
-    keep list and the norms it was taken from."""
+    computed here.  Returns the final hidden state (float64, bits), positions, per pruning layer the
+    keep list and the norms it was taken from, and per layer its KV cache (K after the rotary embedding, V;
+    bf16 bits [B, T_l, Hkv, d])."""
     h = np.asarray(h_bits)
     pos = np.asarray(positions)
     stages = dict(schedule)
     cur_vis = n_vis
-    kept, norms = {}, {}
+    kept, norms, caches = {}, {}, []
     out = None
     for l, w in enumerate(layer_weights):
         keep = stages.get(l, cur_vis)
         forced = None if keep_lists is None else keep_lists.get(l)
         out = decoder_layer(h, w, Hq, Hkv, d, vis_start, cur_vis, keep, pos, eps, theta, keep_idx=forced)
+        caches.append((out["k_rope"], out["v"]))
         if l in stages:
             kept[l] = out["keep_idx"]
             norms[l] = out["norms"]
             pos = out["positions"]
             cur_vis = keep
         h = out["y_bits"]
-    return {"y": out["y"], "y_bits": h, "positions": pos, "keep_lists": kept, "norms": norms}
+    return {"y": out["y"], "y_bits": h, "positions": pos, "keep_lists": kept, "norms": norms, "caches": caches}
 
 
 def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv: int, d: int, vis_start: int,
@@ -182,3 +184,37 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
             cur_vis = keep
         h = out["y_bits"]
     return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2}
+
+
+def decode_step(h_bits, layer_weights, caches, positions, Hq: int, Hkv: int, d: int, eps: float = 1e-5,
+                theta: float = 10000.0):
+    """One decoding step of the whole model (what Table 5 times per generated token): the new token of
+    every sample, ``h_bits`` [B, D], goes through all layers; layer l attends over its cache
+    ``caches[l]`` = (K after the rotary embedding, V), bf16 bits [B, N_l, Hkv, d] (N_l differs between
+    layers after a pruned prefill), extended by the token's own K and V.  ``positions`` [B]: the position
+    id of the new token.  Rounds to bf16 where the prefill layer does.  Returns the output hidden state
+    (float64, bits) and the per-layer rows appended to the caches."""
+    h = np.asarray(h_bits)
+    B, D = h.shape
+    pos = np.asarray(positions).reshape(B, 1)
+    r16 = O.f64_to_bf16_bits
+    appended = []
+    y = None
+    for w, (k_cache, v_cache) in zip(layer_weights, caches):
+        a = r16(rmsnorm(h, w["ln1"], eps))                                      # [B, D]
+        q = r16(O.project(a, w["wq"])).reshape(B, 1, Hq, d)
+        k = r16(O.project(a, w["wk"])).reshape(B, 1, Hkv, d)
+        v = r16(O.project(a, w["wv"])).reshape(B, 1, Hkv, d)
+        q_r, k_r = r16(rope(q, pos, theta)), r16(rope(k, pos, theta))
+        keys = np.concatenate([np.asarray(k_cache), k_r], axis=1)
+        vals = np.concatenate([np.asarray(v_cache), v], axis=1)
+        attn, _ = decode_attention(q_r[:, 0], keys, vals)
+        o = r16(attn).reshape(B, Hq * d)
+        h1 = r16(O.bf16_to_f64(h) + O.project(o, w["wo"]))
+        b = r16(rmsnorm(h1, w["ln2"], eps))
+        g, u = r16(O.project(b, w["wg"])), r16(O.project(b, w["wu"]))
+        m = r16(silu_mul(g, u))
+        y = O.bf16_to_f64(h1) + O.project(m, w["wd"])
+        h = r16(y)
+        appended.append((k_r[:, 0], v[:, 0]))
+    return {"y": y, "y_bits": h, "appended": appended}

@@ -40,6 +40,7 @@ EXPORTS = (
     "vitcop_decode_attn_workspace_bytes", "vitcop_decode_attn",
     "vitcop_decoder_schedule_workspace_bytes", "vitcop_decoder_schedule_prefill",
     "vitcop_full_schedule_workspace_bytes", "vitcop_full_schedule_prefill",
+    "vitcop_decoder_decode_workspace_bytes", "vitcop_decoder_decode_step",
 )
 
 
@@ -71,7 +72,8 @@ class DecoderLayerT(C.Structure):
                 ("h", C.c_void_p), ("positions", C.c_void_p), ("ln1", C.c_void_p), ("ln2", C.c_void_p),
                 ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p), ("wo", C.c_void_p),
                 ("wg", C.c_void_p), ("wu", C.c_void_p), ("wd", C.c_void_p), ("y", C.c_void_p),
-                ("keep_idx", C.c_void_p), ("positions_out", C.c_void_p), ("norms", C.c_void_p)]
+                ("keep_idx", C.c_void_p), ("positions_out", C.c_void_p), ("norms", C.c_void_p),
+                ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cache_capacity", C.c_int)]
 
 
 _DEC_WEIGHTS = ("ln1", "ln2", "wq", "wk", "wv", "wo", "wg", "wu", "wd")
@@ -84,7 +86,16 @@ class DecoderScheduleT(C.Structure):
                  ("prune_layer", C.POINTER(C.c_int)), ("prune_keep", C.POINTER(C.c_int)),
                  ("h", C.c_void_p), ("positions", C.c_void_p)] +
                 [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
-                [("y_out", C.c_void_p), ("positions_out", C.c_void_p)])
+                [("y_out", C.c_void_p), ("positions_out", C.c_void_p),
+                 ("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("cache_capacity", C.c_int)])
+
+
+class DecoderDecodeT(C.Structure):
+    _fields_ = ([(n, C.c_int) for n in ("B", "D", "Hq", "Hkv", "d", "F", "n_layers", "cache_capacity")] +
+                [("eps", C.c_float), ("theta", C.c_float), ("n_cached", C.POINTER(C.c_int)),
+                 ("h", C.c_void_p), ("positions", C.c_void_p)] +
+                [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
+                [("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("y_out", C.c_void_p)])
 
 
 class FullScheduleT(C.Structure):
@@ -177,6 +188,10 @@ def _load() -> C.CDLL:
     lib.vitcop_full_schedule_workspace_bytes.argtypes = [C.POINTER(FullScheduleT)]
     lib.vitcop_full_schedule_prefill.restype = i32
     lib.vitcop_full_schedule_prefill.argtypes = [C.POINTER(FullScheduleT), vp, sz, vp]
+    lib.vitcop_decoder_decode_workspace_bytes.restype = sz
+    lib.vitcop_decoder_decode_workspace_bytes.argtypes = [C.POINTER(DecoderDecodeT)]
+    lib.vitcop_decoder_decode_step.restype = i32
+    lib.vitcop_decoder_decode_step.argtypes = [C.POINTER(DecoderDecodeT), vp, sz, vp]
     return lib
 
 
@@ -430,12 +445,14 @@ class DecoderLayerPlan:
     wo, wg, wu, wd."""
 
     def __init__(self, h, positions, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, keep: int,
-                 eps: float = 1e-5, theta: float = 10000.0):
+                 eps: float = 1e-5, theta: float = 10000.0, caches=None):
+        """``caches`` = (k_cache, v_cache) [B, capacity, Hkv, d]: the layer writes its KV cache there."""
         B, T, D = h.shape
         F = w["wg"].shape[0]
         Tp = T - n_vis + keep
         dev = h.device
-        self.tensors = (h, positions, w)
+        self.tensors = (h, positions, w, caches)
+        kc, vc = caches if caches is not None else (None, None)
         self.y = torch.empty((B, Tp, D), dtype=h.dtype, device=dev)
         self.keep_idx = torch.empty((B, Tp), dtype=torch.int32, device=dev)
         self.positions_out = torch.empty((B, Tp), dtype=torch.int32, device=dev)
@@ -443,7 +460,8 @@ class DecoderLayerPlan:
         self.desc = DecoderLayerT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, keep, eps, theta, _ptr(h),
                                   _ptr(positions), _ptr(w["ln1"]), _ptr(w["ln2"]), _ptr(w["wq"]), _ptr(w["wk"]),
                                   _ptr(w["wv"]), _ptr(w["wo"]), _ptr(w["wg"]), _ptr(w["wu"]), _ptr(w["wd"]),
-                                  _ptr(self.y), _ptr(self.keep_idx), _ptr(self.positions_out), _ptr(self.norms))
+                                  _ptr(self.y), _ptr(self.keep_idx), _ptr(self.positions_out), _ptr(self.norms),
+                                  _ptr(kc), _ptr(vc), kc.shape[1] if kc is not None else 0)
         nb = lib.vitcop_decoder_layer_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
@@ -454,9 +472,10 @@ class DecoderLayerPlan:
         return self.y
 
 
-def vitcop_decoder_layer_prefill(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps=1e-5, theta=10000.0):
+def vitcop_decoder_layer_prefill(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps=1e-5, theta=10000.0,
+                                 caches=None):
     """One full decoder layer with pruning on entry.  Returns dict(y, keep_idx, positions, norms)."""
-    plan = DecoderLayerPlan(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps, theta)
+    plan = DecoderLayerPlan(h, positions, w, Hq, Hkv, d, vis_start, n_vis, keep, eps, theta, caches)
     plan.run()
     return {"y": plan.y, "keep_idx": plan.keep_idx, "positions": plan.positions_out, "norms": plan.norms}
 
@@ -509,16 +528,54 @@ def vitcop_layer_prefill(x, wq, wk, wv, wo, Hq, Hkv, d, vis_start, n_vis, keep, 
             "positions": plan.positions_out}
 
 
+def _cache_arrays(caches, n_layers: int):
+    """(k pointer array, v pointer array, capacity) for a list of per-layer (k_cache, v_cache), or nulls."""
+    if caches is None:
+        return None, None, 0
+    assert len(caches) == n_layers
+    kc = (C.c_void_p * n_layers)(*[k.data_ptr() for k, _ in caches])
+    vc = (C.c_void_p * n_layers)(*[v.data_ptr() for _, v in caches])
+    return kc, vc, caches[0][0].shape[1]
+
+
+class DecoderDecodePlan:
+    """Pre-marshalled vitcop_decoder_decode_step call: one new token per sample through all layers.
+    ``caches``: per layer (k_cache, v_cache) [B, capacity, Hkv, d]; ``n_cached``: tokens each layer's cache holds."""
+
+    def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, caches, n_cached, eps: float = 1e-5,
+                 theta: float = 10000.0):
+        B, D = h.shape
+        n_layers = len(weights)
+        F = weights[0]["wg"].shape[0]
+        self.keepalive = (h, positions, weights, caches)
+        self._kc, self._vc, cap = _cache_arrays(caches, n_layers)
+        self._n = (C.c_int * n_layers)(*[int(v) for v in n_cached])
+        self._w = [(C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights]) for n in _DEC_WEIGHTS]
+        self.y = torch.empty((B, D), dtype=h.dtype, device=h.device)
+        self.desc = DecoderDecodeT(B, D, Hq, Hkv, d, F, n_layers, cap, eps, theta, self._n, _ptr(h), _ptr(positions),
+                                   *self._w, self._kc, self._vc, _ptr(self.y))
+        nb = lib.vitcop_decoder_decode_workspace_bytes(C.byref(self.desc))
+        if nb == 0:
+            raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
+        self.ws = _ws(nb, h)
+
+    def run(self):
+        _check(lib.vitcop_decoder_decode_step(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
+        return self.y
+
+
 class DecoderSchedulePlan:
     """Pre-marshalled vitcop_decoder_schedule_prefill call.  ``weights``: one dict per layer with the device
     tensors ln1, ln2, wq, wk, wv, wo, wg, wu, wd; ``schedule``: ((layer, keep), ...)."""
 
     def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, schedule,
-                 eps: float = 1e-5, theta: float = 10000.0):
+                 eps: float = 1e-5, theta: float = 10000.0, caches=None):
+        """``caches``: per layer (k_cache, v_cache) [B, capacity, Hkv, d], filled by the prefill."""
         B, T, D = h.shape
         n_layers = len(weights)
         F = weights[0]["wg"].shape[0]
-        self.keepalive = (h, positions, weights)
+        self.keepalive = (h, positions, weights, caches)
+        self._kc, self._vc, cap = _cache_arrays(caches, n_layers)
         layers = [int(s[0]) for s in schedule]
         keeps = [int(s[1]) for s in schedule]
         self._pl = (C.c_int * max(len(layers), 1))(*layers)
@@ -529,7 +586,7 @@ class DecoderSchedulePlan:
         self.positions = torch.empty((B, T_final), dtype=torch.int32, device=h.device)
         self.desc = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
                                      self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self.y),
-                                     _ptr(self.positions))
+                                     _ptr(self.positions), self._kc, self._vc, cap)
         nb = lib.vitcop_decoder_schedule_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
@@ -547,11 +604,12 @@ class FullSchedulePlan:
     what Stage II produced."""
 
     def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, stage2: dict,
-                 schedule, eps: float = 1e-5, theta: float = 10000.0):
+                 schedule, eps: float = 1e-5, theta: float = 10000.0, caches=None):
         B, T, D = h.shape
         n_layers = len(weights)
         F = weights[0]["wg"].shape[0]
-        self.keepalive = (h, positions, weights, stage2["xy"])
+        self.keepalive = (h, positions, weights, stage2["xy"], caches)
+        self._kc, self._vc, cap = _cache_arrays(caches, n_layers)
         layers = [int(s[0]) for s in schedule]
         keeps = [int(s[1]) for s in schedule]
         self._pl = (C.c_int * max(len(layers), 1))(*layers)
@@ -565,7 +623,7 @@ class FullSchedulePlan:
         self._T_final, self._n2 = C.c_int(0), C.c_int(0)
         S = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
                              self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self._y),
-                             _ptr(self._pos))
+                             _ptr(self._pos), self._kc, self._vc, cap)
         self.desc = FullScheduleT(S, int(stage2["layer"]), int(stage2["budget"]), int(stage2["n_centers"]),
                                   float(stage2["d_c"]), float(stage2["tau"]), _ptr(stage2["xy"]),
                                   C.pointer(self._T_final), C.pointer(self._n2), _ptr(self.labels),

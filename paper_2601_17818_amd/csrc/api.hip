@@ -610,6 +610,11 @@ static int check_decoder_layer(const vitcop_decoder_layer_t* L) {
             "decoder_layer: eps or theta");
     REQUIRE((long)L->B * L->T * std::max(L->D, L->F) < (1L << 31), VITCOP_EUNSUPPORTED,
             "decoder_layer: an activation tensor would reach 2^31 elements");
+    REQUIRE((L->k_cache == nullptr) == (L->v_cache == nullptr), VITCOP_EINVAL,
+            "decoder_layer: k_cache and v_cache go together");
+    REQUIRE(!L->k_cache || L->cache_capacity >= L->T - L->n_vis + L->keep, VITCOP_EINVAL,
+            "decoder_layer: cache_capacity=%d below the %d kept tokens", L->cache_capacity,
+            L->T - L->n_vis + L->keep);
     return VITCOP_OK;
 }
 
@@ -725,6 +730,15 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
     }
     rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
     if (rc) return rc;
+    if (L->k_cache && L->v_cache && Tp > 0) {        // the layer's KV cache: rows [0,T') of each sample's block
+        const size_t rowb = (size_t)Tp * kd * 2, pitch = (size_t)L->cache_capacity * kd * 2;
+        rc = hip_status(hipMemcpy2DAsync(L->k_cache, pitch, ks, rowb, rowb, B, hipMemcpyDeviceToDevice, s),
+                        "copy K to the cache");
+        if (rc) return rc;
+        rc = hip_status(hipMemcpy2DAsync(L->v_cache, pitch, vb, rowb, rowb, B, hipMemcpyDeviceToDevice, s),
+                        "copy V to the cache");
+        if (rc) return rc;
+    }
     rc = launch_attn(qb, ks, vb, ob, nullptr, B, Tp, L->Hq, L->Hkv, L->d, 1.0f / std::sqrt((float)L->d), 1, s);
     if (rc) return rc;
     rc = launch_gemm_norm_ws(ob, qd, L->wo, h1, D, hs, D, B * Tp, D, qd, L->ln2, L->eps, bb, D, gs, gs_bytes, s);
@@ -814,6 +828,11 @@ static int run_decoder_layers(const vitcop_decoder_schedule_t* S, int l_begin, i
             L.positions_out = r.pbuf[r.pp];
         }
         L.y = last ? S->y_out : r.hbuf[l & 1];
+        if (S->k_cache && S->v_cache) {
+            L.k_cache = S->k_cache[l];
+            L.v_cache = S->v_cache[l];
+            L.cache_capacity = S->cache_capacity;
+        }
         const uint16_t* ln_next = last ? nullptr : static_cast<const uint16_t*>(S->ln1[l + 1]);
         int rc = decoder_layer_run(&L, r.a_pre, ln_next, r.abuf[l & 1], r.lws, r.lws_bytes, stream);
         if (rc) return rc;
@@ -1038,6 +1057,130 @@ int vitcop_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, 
     REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "decode_attn: workspace %zu < %zu", ws_bytes, need);
     if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
     return launch_decode_attn(q, k, v, out, lse_out, B, N, Hq, Hkv, d, scale, ws, static_cast<hipStream_t>(stream));
+}
+
+/* ------------------------------------------------ whole-model decoding step */
+
+static int check_decoder_decode(const vitcop_decoder_decode_t* S) {
+    REQUIRE(S, VITCOP_EINVAL, "decoder_decode: descriptor is null");
+    REQUIRE(S->B >= 1 && S->D >= 32 && S->Hq >= 1 && S->Hkv >= 1 && S->F >= 32 && S->n_layers >= 1, VITCOP_EINVAL,
+            "decoder_decode: B=%d D=%d Hq=%d Hkv=%d F=%d n_layers=%d", S->B, S->D, S->Hq, S->Hkv, S->F, S->n_layers);
+    REQUIRE(S->B <= 256, VITCOP_EUNSUPPORTED, "decoder_decode: B=%d above 256", S->B);
+    REQUIRE(S->Hq % S->Hkv == 0, VITCOP_EINVAL, "decoder_decode: Hq=%d not a multiple of Hkv=%d", S->Hq, S->Hkv);
+    REQUIRE(S->d == 64 || S->d == 128, VITCOP_EUNSUPPORTED, "decoder_decode: d=%d (64 or 128)", S->d);
+    REQUIRE(S->D % 64 == 0 && S->F % 128 == 0 && (S->Hq * S->d) % 64 == 0, VITCOP_EUNSUPPORTED,
+            "decoder_decode: D=%d must be a multiple of 64, F=%d of 128", S->D, S->F);
+    REQUIRE(std::isfinite(S->eps) && S->eps >= 0.f && std::isfinite(S->theta) && S->theta > 1.f, VITCOP_EINVAL,
+            "decoder_decode: eps or theta");
+    REQUIRE(S->n_cached, VITCOP_EINVAL, "decoder_decode: n_cached is null");
+    for (int l = 0; l < S->n_layers; ++l) {
+        REQUIRE(S->n_cached[l] >= 0 && S->n_cached[l] < S->cache_capacity, VITCOP_EINVAL,
+                "decoder_decode: layer %d holds %d tokens, capacity %d", l, S->n_cached[l], S->cache_capacity);
+        const int rc = check_decode(S->B, S->n_cached[l] + 1, S->Hq, S->Hkv, S->d);
+        if (rc) return rc;
+    }
+    REQUIRE((long)S->cache_capacity * S->Hkv * S->d < (1L << 31), VITCOP_EUNSUPPORTED,
+            "decoder_decode: one sample's cache must stay below 2^31 elements");
+    return VITCOP_OK;
+}
+
+static size_t decoder_decode_gemm_scratch(const vitcop_decoder_decode_t* S) {
+    const int B = S->B, D = S->D, qd = S->Hq * S->d, kd = S->Hkv * S->d, F = S->F;
+    size_t n = gemm_workspace_bytes(B, qd + 2 * kd, D);
+    n = std::max(n, gemm_workspace_bytes(B, D, qd));
+    n = std::max(n, gemm_workspace_bytes(B, 2 * F, D));
+    return std::max(n, gemm_workspace_bytes(B, D, F));
+}
+
+size_t vitcop_decoder_decode_workspace_bytes(const vitcop_decoder_decode_t* S) {
+    if (check_decoder_decode(S) != VITCOP_OK) return 0;
+    const size_t B = S->B, D = S->D, qd = (size_t)S->Hq * S->d, kd = (size_t)S->Hkv * S->d, F = S->F;
+    int n_max = 0;
+    for (int l = 0; l < S->n_layers; ++l) n_max = std::max(n_max, S->n_cached[l] + 1);
+    size_t n = 6 * up256(B * D * 2);                                     // a (two), hidden (two), h1, b
+    n += 2 * up256(B * qd * 2) + 2 * up256(B * kd * 2);                  // q, attention output, new K and V
+    n += 3 * up256(B * F * 2);                                           // gate, up, activation
+    n += up256(decode_workspace_bytes((int)B, n_max, S->Hq, S->Hkv, S->d));
+    return n + up256(decoder_decode_gemm_scratch(S));
+}
+
+int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_t ws_bytes, void* stream) {
+    int rc = check_decoder_decode(S);
+    if (rc) return rc;
+    REQUIRE(S->h && S->positions && S->y_out && S->ln1 && S->ln2 && S->wq && S->wk && S->wv && S->wo && S->wg &&
+                S->wu && S->wd && S->k_cache && S->v_cache,
+            VITCOP_EINVAL, "decoder_decode: null pointer");
+    const size_t need = vitcop_decoder_decode_workspace_bytes(S);
+    REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "decoder_decode: workspace needs %zu bytes", need);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const int B = S->B, D = S->D, qd = S->Hq * S->d, kd = S->Hkv * S->d, F = S->F;
+    int n_max = 0;
+    for (int l = 0; l < S->n_layers; ++l) n_max = std::max(n_max, S->n_cached[l] + 1);
+    Carver c(ws);
+    uint16_t* abuf[2] = {c.take<uint16_t>((size_t)B * D * 2), c.take<uint16_t>((size_t)B * D * 2)};
+    uint16_t* hbuf[2] = {c.take<uint16_t>((size_t)B * D * 2), c.take<uint16_t>((size_t)B * D * 2)};
+    uint16_t* h1 = c.take<uint16_t>((size_t)B * D * 2);
+    uint16_t* bb = c.take<uint16_t>((size_t)B * D * 2);
+    uint16_t* qb = c.take<uint16_t>((size_t)B * qd * 2);
+    uint16_t* ob = c.take<uint16_t>((size_t)B * qd * 2);
+    uint16_t* k_new = c.take<uint16_t>((size_t)B * kd * 2);
+    uint16_t* v_new = c.take<uint16_t>((size_t)B * kd * 2);
+    uint16_t* gate = c.take<uint16_t>((size_t)B * F * 2);
+    uint16_t* up = c.take<uint16_t>((size_t)B * F * 2);
+    uint16_t* act = c.take<uint16_t>((size_t)B * F * 2);
+    void* dws = c.take<char>(decode_workspace_bytes(B, n_max, S->Hq, S->Hkv, S->d));
+    const size_t gs_bytes = decoder_decode_gemm_scratch(S);
+    void* gs = c.take<char>(gs_bytes);
+
+    const uint16_t* h = S->h;
+    const uint16_t* a = nullptr;            // RMSNorm of h with this layer's ln1, left by the layer before
+    const size_t rowb = (size_t)kd * 2, pitch = (size_t)S->cache_capacity * kd * 2;
+    for (int l = 0; l < S->n_layers; ++l) {
+        REQUIRE(S->ln1[l] && S->ln2[l] && S->wq[l] && S->wk[l] && S->wv[l] && S->wo[l] && S->wg[l] && S->wu[l] &&
+                    S->wd[l] && S->k_cache[l] && S->v_cache[l],
+                VITCOP_EINVAL, "decoder_decode: layer %d has a null pointer", l);
+        const int N = S->n_cached[l];
+        const bool last = l + 1 == S->n_layers;
+        if (!a) {
+            rc = launch_rmsnorm(h, D, S->ln1[l], S->eps, abuf[0], D, B, D, s);
+            if (rc) return rc;
+            a = abuf[0];
+        }
+        const uint16_t* const w3[3] = {S->wk[l], S->wq[l], S->wv[l]};
+        uint16_t* const y3[3] = {k_new, qb, v_new};
+        const int n3[3] = {kd, qd, kd};
+        rc = launch_gemm_triple_ws(a, D, w3, y3, n3, B, D, gs, gs_bytes, s);
+        if (rc) return rc;
+        rc = launch_rope(qb, k_new, S->positions, B, S->Hq, S->Hkv, S->d, S->theta, s);
+        if (rc) return rc;
+        // the new token's K and V become row N of every sample's cache
+        rc = hip_status(hipMemcpy2DAsync(S->k_cache[l] + (size_t)N * kd, pitch, k_new, rowb, rowb, B,
+                                         hipMemcpyDeviceToDevice, s), "append K");
+        if (rc) return rc;
+        rc = hip_status(hipMemcpy2DAsync(S->v_cache[l] + (size_t)N * kd, pitch, v_new, rowb, rowb, B,
+                                         hipMemcpyDeviceToDevice, s), "append V");
+        if (rc) return rc;
+        rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
+                                1.0f / std::sqrt((float)S->d), dws, s, (int64_t)S->cache_capacity * kd);
+        if (rc) return rc;
+        rc = launch_gemm_norm_ws(ob, qd, S->wo[l], h1, D, h, D, B, D, qd, S->ln2[l], S->eps, bb, D, gs, gs_bytes, s);
+        if (rc) return rc;
+        rc = launch_gemm_gated_ws(bb, D, S->wg[l], S->wu[l], F, gate, up, act, B, D, gs, gs_bytes, s);
+        if (rc) return rc;
+        uint16_t* y = last ? S->y_out : hbuf[l & 1];
+        if (!last && S->ln1[l + 1]) {
+            uint16_t* a_next = abuf[(l + 1) & 1];
+            rc = launch_gemm_norm_ws(act, F, S->wd[l], y, D, h1, D, B, D, F, S->ln1[l + 1], S->eps, a_next, D, gs,
+                                     gs_bytes, s);
+            a = a_next;
+        } else {
+            rc = launch_gemm_ws(act, F, S->wd[l], y, D, h1, D, B, D, F, nullptr, gs, gs_bytes, s);
+            a = nullptr;
+        }
+        if (rc) return rc;
+        h = y;
+    }
+    return VITCOP_OK;
 }
 
 #pragma GCC visibility pop

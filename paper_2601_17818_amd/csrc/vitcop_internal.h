@@ -146,7 +146,8 @@ int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int
 
 // ---- decoding step over the KV cache (decode.hip) ---------------------------
 size_t decode_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
+// kv_batch: elements between two samples' caches (0: dense, N * Hkv * d)
 int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
-                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s);
+                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch = 0);
 
 }  // namespace vitcop

@@ -247,12 +247,13 @@ def test_decoder_validation():
     assert lib.vitcop_silu_mul(A16, A16, A16, 12, None) == binding.VITCOP_EINVAL
     assert lib.vitcop_silu_mul(A16, A16 + 2, A16, 16, None) == binding.VITCOP_EINVAL
     assert lib.vitcop_silu_mul(None, None, None, 0, None) == binding.VITCOP_OK
-    assert C.sizeof(binding.DecoderLayerT) == 10 * 4 + 2 * 4 + 15 * 8
+    assert C.sizeof(binding.DecoderLayerT) == 10 * 4 + 2 * 4 + 15 * 8 + 2 * 8 + 8      # caches, capacity (+ padding)
 
     def desc(**kw):
         base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, F=11008, vis_start=35, n_vis=576, keep=64,
                     eps=1e-5, theta=10000.0, h=A16, positions=A16, ln1=A16, ln2=A16, wq=A16, wk=A16, wv=A16,
-                    wo=A16, wg=A16, wu=A16, wd=A16, y=A16, keep_idx=None, positions_out=None, norms=None)
+                    wo=A16, wg=A16, wu=A16, wd=A16, y=A16, keep_idx=None, positions_out=None, norms=None,
+                    k_cache=None, v_cache=None, cache_capacity=0)
         base.update(kw)
         return binding.DecoderLayerT(**base)
 
@@ -268,7 +269,8 @@ def test_decoder_validation():
 
 
 def test_decoder_schedule_validation():
-    assert C.sizeof(binding.DecoderScheduleT) == 11 * 4 + 2 * 4 + 4 + 15 * 8      # 4 bytes of padding before the pointers
+    # padding before the pointers and at the end
+    assert C.sizeof(binding.DecoderScheduleT) == 11 * 4 + 2 * 4 + 4 + 15 * 8 + 2 * 8 + 8
     ptrs = (C.c_void_p * 4)(*[A16] * 4)
 
     def desc(layers=(1, 3), keeps=(128, 32), **kw):
@@ -339,3 +341,30 @@ def test_decode_validation():
     assert call(out=A16 + 4) == binding.VITCOP_EINVAL
     assert call(B=0) == binding.VITCOP_OK
     assert lib.vitcop_decode_attn_workspace_bytes(4, 384, 32, 5, 128) == 0
+
+
+def test_decoder_decode_validation():
+    assert C.sizeof(binding.DecoderDecodeT) == 8 * 4 + 2 * 4 + 15 * 8
+    ptrs = C.cast((C.c_void_p * 3)(*[A16] * 3), C.POINTER(C.c_void_p))
+
+    def desc(n_cached=(352, 317, 115), **kw):
+        counts = (C.c_int * 3)(*n_cached) if n_cached else None
+        base = dict(B=1, D=4096, Hq=32, Hkv=32, d=128, F=11008, n_layers=3, cache_capacity=640, eps=1e-5,
+                    theta=10000.0, n_cached=counts, h=A16, positions=A16, k_cache=ptrs, v_cache=ptrs, y_out=A16)
+        base.update({n: ptrs for n in binding._DEC_WEIGHTS})
+        base.update(kw)
+        return binding.DecoderDecodeT(**base)
+
+    ws = lib.vitcop_decoder_decode_workspace_bytes
+    run = lib.vitcop_decoder_decode_step
+    need = ws(C.byref(desc()))
+    assert need >= 6 * 4096 * 2 + 3 * 11008 * 2
+    assert ws(C.byref(desc(B=4))) > need
+    assert run(C.byref(desc()), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
+    assert run(None, A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    for bad in (desc(B=0), desc(n_layers=0), desc(Hq=30), desc(n_cached=(352, 640, 115)), desc(n_cached=(-1, 1, 1)),
+                desc(theta=1.0), desc(n_cached=None), desc(h=None), desc(k_cache=None), desc(wq=None)):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
+    for bad in (desc(d=96), desc(D=4100), desc(F=11000), desc(B=300)):
+        assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED
+    assert ws(C.byref(desc(n_cached=(640, 1, 1)))) == 0        # a full cache has no row for the new token

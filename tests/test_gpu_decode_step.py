@@ -1,0 +1,112 @@
+"""GPU parity: the KV cache a prefill leaves behind and the whole-model decoding step over it."""
+import numpy as np
+import pytest
+import torch
+
+import vitcop_inputs as I
+from oracle import decoder_oracle as Dc
+from oracle import vitcop_oracle as O
+from gpu_util import assert_attention_close, dev, host_bits, host_f64
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def vc():
+    from paper_2601_17818_amd import binding
+    return binding
+
+
+def model(seed, n_layers, B, T, D, Hq, Hkv, d, F):
+    layers = [I.decoder_inputs(seed + 1 + l, B, T, D, Hq, Hkv, d, F)["w"] for l in range(n_layers)]
+    for w in layers:                       # small output projections keep the residual stream bounded
+        for name in ("wo", "wd"):
+            w[name] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w[name]) * np.float32(0.25))
+    return I.decoder_inputs(seed, B, T, D, Hq, Hkv, d, F)["h"], layers
+
+
+def cache_pair(B, cap, Hkv, d):
+    return (torch.zeros((B, cap, Hkv, d), dtype=torch.bfloat16, device="cuda"),
+            torch.zeros((B, cap, Hkv, d), dtype=torch.bfloat16, device="cuda"))
+
+
+def rope_close(got_bits, ref_bits, what):
+    """bf16 tensors that went through the fp32 rotary embedding: within one bf16 ulp of the pair's length."""
+    got, ref = O.bf16_to_f64(got_bits), O.bf16_to_f64(ref_bits)
+    scale = np.maximum(np.abs(ref).max(axis=-1, keepdims=True), 1e-6)
+    assert np.all(np.abs(got - ref) <= scale * 2.0 ** -7), what
+
+
+def test_prefill_leaves_the_kv_cache(vc):
+    # one pruning layer: K (after the rotary embedding) and V of the kept tokens, rows [0,T') of the cache
+    B, T, D, Hq, Hkv, d, F, vs, nv, keep, cap = 2, 150, 256, 4, 2, 128, 384, 10, 120, 50, 100
+    c = I.decoder_inputs(7100, B, T, D, Hq, Hkv, d, F)
+    pos = np.stack([np.sort(np.random.default_rng(5 + b).choice(3 * T, T, replace=False)) for b in range(B)])
+    kc, vcache = cache_pair(B, cap, Hkv, d)
+    w = {k: dev(v) for k, v in c["w"].items()}
+    r = vc.vitcop_decoder_layer_prefill(dev(c["h"]), torch.from_numpy(pos.astype(np.int32)).cuda(), w, Hq, Hkv, d, vs,
+                                        nv, keep, caches=(kc, vcache))
+    torch.cuda.synchronize()
+    idx = r["keep_idx"].cpu().numpy()
+    ref = Dc.decoder_layer(c["h"], c["w"], Hq, Hkv, d, vs, nv, keep, pos, keep_idx=idx)
+    Tp = T - nv + keep
+    rope_close(host_bits(kc)[:, :Tp], ref["k_rope"], "K cache")
+    v_got, v_ref = O.bf16_to_f64(host_bits(vcache)[:, :Tp]), O.bf16_to_f64(ref["v"])
+    assert np.all(np.abs(v_got - v_ref) <= np.maximum(np.abs(v_ref), 1e-3) * 2.0 ** -7)      # bf16 of an fp32 sum
+    assert not host_bits(kc)[:, Tp:].any() and not host_bits(vcache)[:, Tp:].any()           # nothing past T'
+
+
+@pytest.mark.parametrize("B,n_cached", [(1, (70, 40, 40)), (3, (33, 33, 9)), (2, (1, 200, 64))])
+def test_decode_step_matches_oracle(vc, B, n_cached):
+    # three layers whose caches have different lengths (as after a pruned prefill), capacity above them;
+    # the caches are the oracle's (any bf16 values are a valid cache)
+    D, Hq, Hkv, d, F, cap = 256, 4, 2, 128, 384, 256
+    h, layers = model(7200 + B, 3, B, 1, D, Hq, Hkv, d, F)
+    h = h[:, 0]
+    pos = np.array([500 + 7 * b for b in range(B)], dtype=np.int32)
+    caches_ref = [(I.normal_bf16(7300 + l, 0, (B, n, Hkv, d)), I.normal_bf16(7300 + l, 1, (B, n, Hkv, d)))
+                  for l, n in enumerate(n_cached)]
+    caches = []
+    for (k, v), n in zip(caches_ref, n_cached):
+        kc, vcache = cache_pair(B, cap, Hkv, d)
+        kc[:, :n] = dev(k)
+        vcache[:, :n] = dev(v)
+        caches.append((kc, vcache))
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    plan = vc.DecoderDecodePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, caches, n_cached)
+    y = plan.run()
+    torch.cuda.synchronize()
+    ref = Dc.decode_step(h, layers, caches_ref, pos, Hq, Hkv, d)
+    assert_attention_close(host_f64(y), ref["y"], "decode step output")
+    # layer 0's appended rows depend on the inputs alone: K after the rotary embedding, V
+    rope_close(host_bits(caches[0][0])[:, n_cached[0]], ref["appended"][0][0], "appended K")
+    v_got = O.bf16_to_f64(host_bits(caches[0][1])[:, n_cached[0]])
+    v_ref = O.bf16_to_f64(ref["appended"][0][1])
+    assert np.all(np.abs(v_got - v_ref) <= np.maximum(np.abs(v_ref), 1e-3) * 2.0 ** -7)
+    for (kc, vcache), (k, v), n in zip(caches, caches_ref, n_cached):      # the cached rows are untouched
+        assert np.array_equal(host_bits(kc)[:, :n], k) and np.array_equal(host_bits(vcache)[:, :n], v)
+        assert not host_bits(kc)[:, n + 1:].any()
+
+
+def test_prefill_then_decode_equals_longer_prefill(vc):
+    # GPU only: a pruned prefill of T-1 tokens with cache export, then one decoding step of token T,
+    # against the last row of the same pruned prefill over T tokens (same keep lists: the last token is text)
+    B, T, D, Hq, Hkv, d, F, vs, nv = 1, 141, 256, 4, 2, 128, 384, 8, 100
+    h, layers = model(7400, 3, B, T, D, Hq, Hkv, d, F)
+    pos = (np.arange(T) * 2)[None].astype(np.int32)
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    schedule = ((1, 30),)
+    caches = [cache_pair(B, 160, Hkv, d) for _ in range(3)]
+    head = vc.DecoderSchedulePlan(dev(h[:, :T - 1]), torch.from_numpy(pos[:, :T - 1]).cuda(), wd, Hq, Hkv, d, vs, nv,
+                                  schedule, caches=caches)
+    head.run()
+    full = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, schedule)
+    y_full = full.run()
+    torch.cuda.synchronize()
+    assert np.array_equal(full.positions.cpu().numpy()[0, :-1], head.positions.cpu().numpy()[0])
+    n_cached = (T - 1, T - 1 - nv + 30, T - 1 - nv + 30)
+    step = vc.DecoderDecodePlan(dev(h[:, T - 1]), torch.from_numpy(pos[:, T - 1]).cuda(), wd, Hq, Hkv, d, caches,
+                                n_cached)
+    y = step.run()
+    torch.cuda.synchronize()
+    assert_attention_close(host_f64(y), host_f64(y_full[:, -1]), "decode after prefill")

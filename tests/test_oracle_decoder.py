@@ -181,3 +181,25 @@ def test_vitcop_schedule_clusters_planted_regions_and_clamps_stage3():
     # the same call with the clustering and norms handed in decides the same
     again = Dc.vitcop_schedule(h, layers, s2, ((1, 50),), 4, 2, 64, 8, n, pos, labels=st["labels"], k_norms=st["norms"])
     assert np.array_equal(again["y_bits"], got["y_bits"])
+
+
+def test_decode_step_is_the_last_row_of_the_prefill():
+    # prefill of T tokens, last row == prefill of T-1 tokens (its caches) + one decoding step of token T:
+    # every operation of a layer but the attention acts on rows independently, and the last row's
+    # attention is the decoding step's (pinned above)
+    T, D, Hq, Hkv, d, F = 30, 128, 4, 2, 64, 96
+    h, layers = small_model(400, 3, T, D, Hq, Hkv, d, F)
+    pos = (2 * np.arange(T) + 5)[None]
+    full = Dc.decoder_schedule(h, layers, (), Hq, Hkv, d, 4, 20, pos)
+    head = Dc.decoder_schedule(h[:, :T - 1], layers, (), Hq, Hkv, d, 4, 20, pos[:, :T - 1])
+    step = Dc.decode_step(h[:, T - 1], layers, head["caches"], pos[:, T - 1], Hq, Hkv, d)
+    assert np.allclose(step["y"][0], full["y"][0, T - 1], rtol=1e-9, atol=1e-11)
+    assert np.array_equal(step["y_bits"][0], full["y_bits"][0, T - 1])
+    for l in range(3):
+        assert np.array_equal(step["appended"][l][0][0], full["caches"][l][0][0, T - 1])
+        assert np.array_equal(step["appended"][l][1][0], full["caches"][l][1][0, T - 1])
+    # after a pruned prefill the step attends over what each layer kept
+    pr = Dc.decoder_schedule(h[:, :T - 1], layers, ((1, 6),), Hq, Hkv, d, 4, 20, pos[:, :T - 1])
+    assert [c[0].shape[1] for c in pr["caches"]] == [29, 15, 15]
+    st = Dc.decode_step(h[:, T - 1], layers, pr["caches"], pos[:, T - 1], Hq, Hkv, d)
+    assert st["y"].shape == (1, D) and np.all(np.isfinite(st["y"]))
