@@ -374,6 +374,29 @@ def main():
             "ms": t_f, "speedup_vs_unpruned": t_dunpr / t_f, "visual_after_stage2": fplan.n_stage2,
             "tokens_final": fplan.T_final}
         del fplan, xf, pf, xy
+        # one decoding step (a new token per sample through all 32 layers) over the caches those prefills
+        # leave: per-layer cache lengths of the unpruned prefill and of the paper's two schedules (Table 5's
+        # time per generated token); a step streams every weight (12.95 GB) and every cached K and V once
+        dec = {}
+        w_bytes = 32 * (4 * 4096 * 4096 + 3 * 4096 * F2) * 2
+        lens = {"unpruned": [640] * 32}
+        for name, (r1, r2, r3) in (("retain192", (0.5, 0.4394, 0.0879)), ("retain64", (0.3, 0.1343, 0.0269))):
+            v1, v2, v3 = (int(round(576 * r)) for r in (r1, r2, r3))
+            lens[name] = [64 + v1] * 2 + [64 + v2] * 20 + [64 + v3] * 10
+        for Bd in (1, 64):
+            caches = [tuple(torch.empty((Bd, 704, 32, 128), dtype=torch.bfloat16, device="cuda").normal_(generator=gen)
+                            for _ in range(2)) for _ in range(32)]
+            hd = torch.empty((Bd, 4096), dtype=torch.bfloat16, device="cuda").normal_(generator=gen)
+            pd = torch.full((Bd,), 700, dtype=torch.int32, device="cuda")
+            for name, n_cached in lens.items():
+                dplan = vc.DecoderDecodePlan(hd, pd, w_dev, 32, 32, 128, caches, n_cached)
+                t_d = ev_time(dplan.run, 10, warm=3)
+                moved = w_bytes + sum(n + 1 for n in n_cached) * Bd * 4096 * 2 * 2
+                dec[f"batch{Bd}_{name}"] = {"ms_per_step": t_d, "tokens_per_s": Bd / (t_d * 1e-3),
+                                            "GBps": moved / t_d / 1e6, "frac_hbm": moved / t_d / 1e6 / HBM_PEAK_GBPS}
+                del dplan
+            del caches, hd, pd
+        out["decode_step_config2"] = dec
         del w_dev, sp, up, dsp, dup
 
     # ------------------------------------------------------ CPU oracle baseline

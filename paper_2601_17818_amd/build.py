@@ -19,7 +19,7 @@ CSRC = os.path.join(PKG, "csrc")
 OUT = os.path.join(PKG, "libvitcop.so")
 BUILD = os.path.join(ROOT, "_build")
 
-SOURCES = ["api.hip", "knorm_select.hip", "compact.hip", "filter.hip", "attn.hip", "gemm.hip", "gemm_skinny.hip", "vic.hip", "collab.hip", "decoder.hip", "decode.hip"]
+SOURCES = ["api.hip", "knorm_select.hip", "compact.hip", "filter.hip", "attn.hip", "gemm.hip", "gemm_skinny.hip", "gemv.hip", "vic.hip", "collab.hip", "decoder.hip", "decode.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",

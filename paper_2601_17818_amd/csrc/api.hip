@@ -1133,6 +1133,33 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
     void* gs = c.take<char>(gs_bytes);
 
     const uint16_t* h = S->h;
+    if (gemv_applies(B, D) && gemv_applies(B, qd) && gemv_applies(B, F) && S->d % 2 == 0) {
+        // a handful of rows: every product is a stream over its weights, with the norms, the rotary embedding,
+        // the cache append, the activation and the residual adds inside the streaming kernels
+        const int64_t kv_batch = (int64_t)S->cache_capacity * kd;
+        for (int l = 0; l < S->n_layers; ++l) {
+            REQUIRE(S->ln1[l] && S->ln2[l] && S->wq[l] && S->wk[l] && S->wv[l] && S->wo[l] && S->wg[l] && S->wu[l] &&
+                        S->wd[l] && S->k_cache[l] && S->v_cache[l],
+                    VITCOP_EINVAL, "decoder_decode: layer %d has a null pointer", l);
+            const int N = S->n_cached[l];
+            rc = launch_gemv_qkv_rope(h, D, S->ln1[l], S->eps, S->wq[l], S->wk[l], S->wv[l], qb,
+                                      S->k_cache[l] + (size_t)N * kd, S->v_cache[l] + (size_t)N * kd, kv_batch,
+                                      S->positions, B, S->Hq, S->Hkv, S->d, D, S->theta, s);
+            if (rc) return rc;
+            rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
+                                    1.0f / std::sqrt((float)S->d), dws, s, kv_batch);
+            if (rc) return rc;
+            rc = launch_gemv(ob, qd, nullptr, 0.f, S->wo[l], h1, D, h, D, B, D, qd, s);
+            if (rc) return rc;
+            rc = launch_gemv_gated(h1, D, S->ln2[l], S->eps, S->wg[l], S->wu[l], act, F, B, F, D, s);
+            if (rc) return rc;
+            uint16_t* y = l + 1 == S->n_layers ? S->y_out : hbuf[l & 1];
+            rc = launch_gemv(act, F, nullptr, 0.f, S->wd[l], y, D, h1, D, B, D, F, s);
+            if (rc) return rc;
+            h = y;
+        }
+        return VITCOP_OK;
+    }
     const uint16_t* a = nullptr;            // RMSNorm of h with this layer's ln1, left by the layer before
     const size_t rowb = (size_t)kd * 2, pitch = (size_t)S->cache_capacity * kd * 2;
     for (int l = 0; l < S->n_layers; ++l) {

@@ -102,6 +102,20 @@ int launch_partial_reduce(const SkParts& parts, int N, const SkMats& mats, const
                           float* sumsq_parts, const uint16_t* ln_w, float eps, uint16_t* norm_out,
                           int64_t norm_stride, uint16_t* gated_out, hipStream_t s);
 bool partial_reduce_fuses_norm(int N);
+// gemv.hip: projections of at most GV_MAX_ROWS rows as a stream over the weights (decoding steps), with
+// RMSNorm of x in the prologue (ln_w != nullptr) and the residual add, silu(gate) * up, or the rotary
+// embedding with the KV-cache append in the epilogue.  N even, W dense [N][K], K within gemv_applies.
+constexpr int GV_MAX_ROWS = 4;
+bool gemv_applies(int B, int K);
+int launch_gemv(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* w, uint16_t* y,
+                int64_t y_stride, const uint16_t* res, int64_t res_stride, int B, int N, int K, hipStream_t s);
+int launch_gemv_gated(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wg,
+                      const uint16_t* wu, uint16_t* act, int64_t act_stride, int B, int F, int K, hipStream_t s);
+int launch_gemv_qkv_rope(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wq,
+                         const uint16_t* wk, const uint16_t* wv, uint16_t* q, uint16_t* k_dst, uint16_t* v_dst,
+                         int64_t kv_batch, const int32_t* positions, int B, int Hq, int Hkv, int d, int K, float theta,
+                         hipStream_t s);
+
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
 bool gemm_skinny_fuses_norm(int M, int N, int K);

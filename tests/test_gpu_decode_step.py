@@ -37,6 +37,14 @@ def rope_close(got_bits, ref_bits, what):
     assert np.all(np.abs(got - ref) <= scale * 2.0 ** -7), what
 
 
+def v_close(got, ref):
+    """bf16 of an fp32 sum of a few hundred products against bf16 of the exact sum: one bf16 ulp of the
+    entry, with a floor for entries near zero: the normalised input is itself rounded to bf16 from fp32
+    on one side and from fp64 on the other, and one such rounding that falls the other way moves the sum
+    by 2^-8 of one product (products here are around 0.05), whatever the size of the sum."""
+    assert np.all(np.abs(got - ref) <= np.maximum(np.abs(ref), 5e-2) * 2.0 ** -7)
+
+
 def test_prefill_leaves_the_kv_cache(vc):
     # one pruning layer: K (after the rotary embedding) and V of the kept tokens, rows [0,T') of the cache
     B, T, D, Hq, Hkv, d, F, vs, nv, keep, cap = 2, 150, 256, 4, 2, 128, 384, 10, 120, 50, 100
@@ -52,16 +60,28 @@ def test_prefill_leaves_the_kv_cache(vc):
     Tp = T - nv + keep
     rope_close(host_bits(kc)[:, :Tp], ref["k_rope"], "K cache")
     v_got, v_ref = O.bf16_to_f64(host_bits(vcache)[:, :Tp]), O.bf16_to_f64(ref["v"])
-    assert np.all(np.abs(v_got - v_ref) <= np.maximum(np.abs(v_ref), 1e-3) * 2.0 ** -7)      # bf16 of an fp32 sum
+    v_close(v_got, v_ref)
     assert not host_bits(kc)[:, Tp:].any() and not host_bits(vcache)[:, Tp:].any()           # nothing past T'
 
 
-@pytest.mark.parametrize("B,n_cached", [(1, (70, 40, 40)), (3, (33, 33, 9)), (2, (1, 200, 64))])
-def test_decode_step_matches_oracle(vc, B, n_cached):
-    # three layers whose caches have different lengths (as after a pruned prefill), capacity above them;
-    # the caches are the oracle's (any bf16 values are a valid cache)
-    D, Hq, Hkv, d, F, cap = 256, 4, 2, 128, 384, 256
-    h, layers = model(7200 + B, 3, B, 1, D, Hq, Hkv, d, F)
+SMALL = (256, 4, 2, 128, 384)               # D, Hq, Hkv, d, F: below the streaming kernels' minimum width
+RAGGED = (512, 4, 2, 128, 640)              # streaming kernels, F not a whole number of column blocks
+CUT = (4160, 24, 6, 128, 2176)              # more row pairs than wavefronts: pairs cut between two of them
+GATED_CUT = (2112, 4, 2, 128, 2304)
+
+
+@pytest.mark.parametrize("B,n_cached,dims", [
+    (1, (70, 40, 40), SMALL), (2, (1, 200, 64), SMALL), (6, (50, 20), RAGGED),
+    (3, (33, 33, 9), RAGGED), (1, (5, 255), RAGGED), (4, (30, 17), CUT), (2, (17, 30), CUT), (1, (100, 10), GATED_CUT),
+    (3, (9, 64), GATED_CUT)])
+def test_decode_step_matches_oracle(vc, B, n_cached, dims):
+    # layers whose caches have different lengths (as after a pruned prefill), capacity above them;
+    # the caches are the oracle's (any bf16 values are a valid cache); one to four samples go through
+    # the weight-streaming kernels, more through the few-row matrix-core kernels
+    D, Hq, Hkv, d, F = dims
+    cap = 256
+    n_layers = len(n_cached)
+    h, layers = model(7200 + B + D, n_layers, B, 1, D, Hq, Hkv, d, F)
     h = h[:, 0]
     pos = np.array([500 + 7 * b for b in range(B)], dtype=np.int32)
     caches_ref = [(I.normal_bf16(7300 + l, 0, (B, n, Hkv, d)), I.normal_bf16(7300 + l, 1, (B, n, Hkv, d)))
@@ -82,10 +102,10 @@ def test_decode_step_matches_oracle(vc, B, n_cached):
     rope_close(host_bits(caches[0][0])[:, n_cached[0]], ref["appended"][0][0], "appended K")
     v_got = O.bf16_to_f64(host_bits(caches[0][1])[:, n_cached[0]])
     v_ref = O.bf16_to_f64(ref["appended"][0][1])
-    assert np.all(np.abs(v_got - v_ref) <= np.maximum(np.abs(v_ref), 1e-3) * 2.0 ** -7)
+    v_close(v_got, v_ref)
     for (kc, vcache), (k, v), n in zip(caches, caches_ref, n_cached):      # the cached rows are untouched
         assert np.array_equal(host_bits(kc)[:, :n], k) and np.array_equal(host_bits(vcache)[:, :n], v)
-        assert not host_bits(kc)[:, n + 1:].any()
+        assert not host_bits(kc)[:, n + 1:].any() and not host_bits(vcache)[:, n + 1:].any()
 
 
 def test_prefill_then_decode_equals_longer_prefill(vc):
