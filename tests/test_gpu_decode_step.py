@@ -68,12 +68,13 @@ SMALL = (256, 4, 2, 128, 384)               # D, Hq, Hkv, d, F: below the stream
 RAGGED = (512, 4, 2, 128, 640)              # streaming kernels, F not a whole number of column blocks
 CUT = (4160, 24, 6, 128, 2176)              # more row pairs than wavefronts: pairs cut between two of them
 GATED_CUT = (2112, 4, 2, 128, 2304)
+FULL = (4096, 32, 32, 128, 11008)           # the 7B shape bench.py times (two layers of it)
 
 
 @pytest.mark.parametrize("B,n_cached,dims", [
     (1, (70, 40, 40), SMALL), (2, (1, 200, 64), SMALL), (6, (50, 20), RAGGED),
     (3, (33, 33, 9), RAGGED), (1, (5, 255), RAGGED), (4, (30, 17), CUT), (2, (17, 30), CUT), (1, (100, 10), GATED_CUT),
-    (3, (9, 64), GATED_CUT)])
+    (3, (9, 64), GATED_CUT), (4, (200, 115), FULL), (1, (115, 200), FULL)])
 def test_decode_step_matches_oracle(vc, B, n_cached, dims):
     # layers whose caches have different lengths (as after a pruned prefill), capacity above them;
     # the caches are the oracle's (any bf16 values are a valid cache); one to four samples go through
