@@ -540,6 +540,10 @@ int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint1
                    const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws,
                    size_t ws_bytes, hipStream_t s) {
     if (M == 0 || N == 0) return VITCOP_OK;
+    // one to four rows: a stream over W with no partial sums to reduce
+    if (!sumsq_parts && gemv_applies(M, K) && N % 2 == 0 && x_stride % 8 == 0 && y_stride % 2 == 0 &&
+        (!res || res_stride % 2 == 0))
+        return launch_gemv(x, x_stride, nullptr, 0.f, w, y, y_stride, res, res_stride, M, N, K, s);
     const size_t need = gemm_skinny_workspace_bytes(M, N, K);
     if (ws && need && ws_bytes >= need)
         return launch_gemm_skinny(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, nullptr,

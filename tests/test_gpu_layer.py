@@ -70,6 +70,22 @@ def test_project_few_rows_matches_oracle(vc, M, N, K):
     assert_bf16_of(host_bits(y2), ref, f"project (big tiles) {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M", [1, 2, 3, 4])
+@pytest.mark.parametrize("N,K", [(4096, 4096), (128, 512), (400, 11008), (16512, 640), (16, 2080)])
+def test_project_one_to_four_rows_matches_oracle(vc, M, N, K):
+    # M <= 4 without the norm side output: the weight-streaming matrix-vector kernel (whole and cut row
+    # pairs, ragged last column block), with and without residual
+    x = I.normal_bf16(M + N + K, 0, (M, K))
+    w = I.normal_bf16(M + N + K, 1, (N, K), 0.05)
+    r = I.normal_bf16(M + N + K, 2, (M, N))
+    y, _ = vc.vitcop_project(dev(x), dev(w), residual=dev(r))
+    y0, _ = vc.vitcop_project(dev(x), dev(w), scratch=False)
+    torch.cuda.synchronize()
+    ref = O.project(x, w)
+    assert_bf16_of(host_bits(y), ref + O.bf16_to_f64(r), f"project {M}x{N}x{K} + residual")
+    assert_bf16_of(host_bits(y0), ref, f"project {M}x{N}x{K}")
+
+
 @pytest.mark.parametrize("M,N,K", [(317, 4096, 4096), (640, 4096, 2048), (1000, 1024, 2048), (352, 2048, 11008),
                                    (257, 256, 768), (1024, 4096, 1024)])
 def test_project_split_k_matches_oracle(vc, M, N, K):
