@@ -403,7 +403,13 @@ int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size
  * the layers after a pruning point, hence one length per layer.
  *   h [B,D], positions [B];  y_out [B,D];  k_cache[l], v_cache[l] [B, cache_capacity, Hkv, d]
  *   n_cached: host [n_layers], each < cache_capacity
- * B <= 256 (one launch per projection on the few-row path); d in {64,128}.
+ * B <= 256; d in {64,128}; D a multiple of 64, F of 128.  One to four samples run through weight-streaming
+ * matrix-vector kernels that carry the norms, the rotary embedding, the cache append, the activation and
+ * the residual adds (6 launches per layer); more samples through the few-row matrix-core projections.
+ * All pointers are device pointers except the descriptor's own arrays (n_cached and the per-layer pointer
+ * tables), which are host memory read during the call.  The call enqueues on `stream` and returns; the
+ * caller advances n_cached after each step.  Errors: VITCOP_EINVAL (null pointer, sizes, a full cache),
+ * VITCOP_EUNSUPPORTED (shape limits), VITCOP_EWORKSPACE, VITCOP_EHIP.
  */
 typedef struct {
     int B, D, Hq, Hkv, d, F, n_layers, cache_capacity;

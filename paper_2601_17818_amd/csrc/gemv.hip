@@ -18,6 +18,7 @@
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
+#include <atomic>
 #include <cmath>
 
 namespace vitcop {
@@ -299,13 +300,13 @@ static int launch_gemv_nb(GvArgs& a, hipStream_t s) {
     a.pairs_r = a.n_pairs % wgs;
     const int KG = (a.K + GV_KBLK * GV_U - 1) / (GV_KBLK * GV_U);
     const size_t lds = (size_t)NB * KG * GV_U * 64 * 16 + (size_t)(a.pairs_q + 1) * 4 * NB * 4 + GV_WAVES * NB * 4;
-    static size_t raised_to = 65536;                 // (per instantiation) dynamic LDS the kernel may use so far
-    if (lds > raised_to) {
+    static std::atomic<size_t> raised_to{65536};     // (per instantiation) dynamic LDS the kernel may use so far
+    if (lds > raised_to.load()) {
         const int rc = hip_status(hipFuncSetAttribute(reinterpret_cast<const void*>(&gemv_kernel<NB, EPI>),
                                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                                   "hipFuncSetAttribute(gemv)");
         if (rc) return rc;
-        raised_to = lds;
+        raised_to.store(lds);
     }
     hipLaunchKernelGGL((gemv_kernel<NB, EPI>), dim3(wgs), dim3(GV_THREADS), lds, s, a);
     return launch_status("gemv");

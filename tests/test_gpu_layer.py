@@ -86,6 +86,23 @@ def test_project_one_to_four_rows_matches_oracle(vc, M, N, K):
     assert_bf16_of(host_bits(y0), ref, f"project {M}x{N}x{K}")
 
 
+def test_project_one_to_four_rows_shape_sweep(vc):
+    # seeded random shapes over the streaming kernel's whole range: 1..6 pieces per row pair, fewer pairs than
+    # wavefronts, uneven pairs per workgroup (pairs cut between wavefronts), ragged last column block
+    rng = np.random.default_rng(20260117)
+    for case in range(24):
+        M = int(rng.integers(1, 5))
+        K = 32 * int(rng.integers(16, 385))                    # 512 .. 12288
+        N = 16 * int(rng.integers(1, 40 if K > 4096 else 300))
+        if case % 6 == 0:
+            N = 16 * int(rng.integers(260, 400))               # more than 8 pairs per workgroup
+        x = I.normal_bf16(9000 + case, 0, (M, K))
+        w = I.normal_bf16(9000 + case, 1, (N, K), 0.05)
+        y, _ = vc.vitcop_project(dev(x), dev(w))
+        torch.cuda.synchronize()
+        assert_bf16_of(host_bits(y), O.project(x, w), f"project {M}x{N}x{K}")
+
+
 @pytest.mark.parametrize("M,N,K", [(317, 4096, 4096), (640, 4096, 2048), (1000, 1024, 2048), (352, 2048, 11008),
                                    (257, 256, 768), (1024, 4096, 1024)])
 def test_project_split_k_matches_oracle(vc, M, N, K):
