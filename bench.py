@@ -357,6 +357,20 @@ def main():
             paper[name] = {"visual_tokens": [v1, v2, v3], "ms": t_p, "speedup_vs_unpruned": t_dunpr / t_p,
                            "eq9_flops_ratio": eq9_ratio((64 + v1, 64 + v2, 64 + v3))}
             del plan, xp, pp
+        # the same "retain 192" schedule on a batch of 8 prompts (2816 / 2536 / 920 rows per layer): the projections
+        # are then matrix-core-bound on both sides and the speedup moves towards the FLOPs ratio
+        x8 = x2.repeat(8, 1, 1).contiguous()
+        p8 = pos2.repeat(8, 1).contiguous()
+        u8 = vc.DecoderSchedulePlan(x8, p8, w_dev, 32, 32, 128, 35, 576, ())
+        t_u8 = ev_time(u8.run, 3, warm=1)
+        del u8
+        r8 = vc.DecoderSchedulePlan(x8[:, :352].contiguous(), p8[:, :352].contiguous(), w_dev, 32, 32, 128, 35, 288,
+                                    ((2, 253), (22, 51)))
+        t_r8 = ev_time(r8.run, 3, warm=1)
+        del r8, x8, p8
+        paper["retain192_batch8"] = {"ms": t_r8, "ms_unpruned": t_u8, "speedup_vs_unpruned": t_u8 / t_r8,
+                                     "unpruned_tokens_per_s": 8 * 640 / (t_u8 * 1e-3),
+                                     "eq9_flops_ratio": paper["retain192"]["eq9_flops_ratio"]}
         out["decoder_schedule_paper_llava15"] = paper
         # the same "retain 192" setting with the paper's actual Stage II at layer 2 (clustering, elites,
         # merging; budget 253) and Stage III at layer 22; the 288 visual hidden states are planted spatial
