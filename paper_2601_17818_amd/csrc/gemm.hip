@@ -438,6 +438,36 @@ static TileId choose_tile(int M, int N, int K, bool need_sumsq, int align_n) {
     return best;
 }
 
+// A launch whose tiles overflow whole rounds over the 256 CUs by a few (640 rows x 22016 columns: 3 x 86 =
+// 258 tiles of 256 x 256) would spend a whole extra round on them.  Then only the leading columns, as many
+// column tiles as fill the whole rounds, go out on the big tiles, and the few trailing columns follow as a
+// launch of their own on the few-row / split-K path, which spreads them over the chip.  Returns the number
+// of leading columns (N: no cut) and, in `id`, the tile shape for them.  The tail is priced at 0.3 of a
+// 256 x 256 tile time (its launch and its reduction).
+constexpr int GM_TAIL_MAX_TILES = 64;
+static int main_columns(TileId& id, int M, int N, int K, bool need_sumsq, int align_n) {
+    if (id == T128x32) return N;
+    float best = tile_cost(kTiles[id], M, N);
+    int best_n = N;
+    for (int i = 0; i < T128x32; ++i) {
+        const TileShape& t = kTiles[i];
+        if (need_sumsq && !t.sumsq) continue;
+        if (align_n % t.bn != 0) continue;
+        const int tiles_m = (M + t.bm - 1) / t.bm, tiles_n = (N + t.bn - 1) / t.bn;
+        const int rounds = (tiles_m * tiles_n + 255) / 256;
+        if (rounds < 2) continue;
+        const int keep_n = (rounds - 1) * 256 / tiles_m;              // column tiles that fill the whole rounds
+        if (keep_n < 1 || keep_n >= tiles_n || (tiles_n - keep_n) * tiles_m > GM_TAIL_MAX_TILES) continue;
+        const float c = (float)(rounds - 1) * (float)(t.bm * t.bn) / (65536.0f * t.rate) + 0.3f;
+        if (c < best) {
+            best = c;
+            best_n = keep_n * t.bn;
+            id = (TileId)i;
+        }
+    }
+    return best_n;
+}
+
 static int launch_tile(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                        int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N, int K,
                        float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split, hipStream_t s) {
@@ -506,8 +536,25 @@ static size_t splitk_workspace_bytes(int M, int N, int K) {
     return p.splits ? up256((size_t)p.splits * M * N * 4) : 0;
 }
 
+// scratch of the trailing columns when main_columns cuts the launch (as one matrix, or as the pair N/2 + N/2)
+static size_t tail_workspace_bytes(int M, int N, int K) {
+    size_t need = 0;
+    for (int pair = 0; pair < 2; ++pair) {
+        if (pair && N % 256 != 0) break;
+        for (int sumsq = 0; sumsq < (pair ? 1 : 2); ++sumsq) {
+            TileId id = choose_tile(M, N, K, sumsq != 0, pair ? N / 2 : 768);
+            const int n_main = main_columns(id, M, N, K, sumsq != 0, pair ? N / 2 : 768);
+            if (n_main < N)
+                need = std::max(need, std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
+                                               splitk_workspace_bytes(M, N - n_main, K)));
+        }
+    }
+    return need;
+}
+
 size_t gemm_workspace_bytes(int M, int N, int K) {
-    return std::max(gemm_skinny_workspace_bytes(M, N, K), splitk_workspace_bytes(M, N, K));
+    const size_t whole = std::max(gemm_skinny_workspace_bytes(M, N, K), splitk_workspace_bytes(M, N, K));
+    return whole ? whole : tail_workspace_bytes(M, N, K);
 }
 
 // y = x W^T (+ res) by split-K (splitk_plan applies, ws holds splitk_workspace_bytes); optionally the
@@ -552,6 +599,21 @@ int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint1
     if (ws && need_k && ws_bytes >= need_k)
         return launch_gemm_splitk(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, ws, s, nullptr,
                                   0.f, nullptr, 0);
+    if (ws) {               // a few tiles over whole rounds: leading columns on the big tiles, the rest on their own
+        TileId id = choose_tile(M, N, K, sumsq_parts != nullptr, 768);
+        const int n_main = main_columns(id, M, N, K, sumsq_parts != nullptr, 768);
+        const size_t need_tail = n_main < N ? std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
+                                                       splitk_workspace_bytes(M, N - n_main, K))
+                                            : 0;
+        if (need_tail && ws_bytes >= need_tail) {
+            int rc = launch_tile(id, x, x_stride, w, y, y_stride, res, res_stride, M, n_main, K, sumsq_parts, nullptr,
+                                 nullptr, 0, s);
+            if (rc) return rc;
+            return launch_gemm_ws(x, x_stride, w + (int64_t)n_main * K, y + n_main, y_stride,
+                                  res ? res + n_main : nullptr, res_stride, M, N - n_main, K,
+                                  sumsq_parts ? sumsq_parts + (int64_t)(n_main / GM_PART) * M : nullptr, ws, ws_bytes, s);
+        }
+    }
     return launch_gemm(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts, s);
 }
 
@@ -607,6 +669,21 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
     if (ws && need_k && ws_bytes >= need_k && N1 == N2 && N1 % 256 == 0)      // no tile straddles the two outputs
         return launch_gemm_splitk(x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, ws, s, nullptr, 0.f,
                                   nullptr, 0, w2, y2, N1);
+    if (ws && N1 == N2 && N1 % 128 == 0) {       // the same cut for the pair: the tail lies in the second matrix
+        const int N = N1 + N2;
+        TileId id = choose_tile(M, N, K, false, N1);
+        const int n_main = main_columns(id, M, N, K, false, N1);
+        const size_t need_tail = n_main < N && n_main >= N1
+                                     ? std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
+                                                splitk_workspace_bytes(M, N - n_main, K))
+                                     : 0;
+        if (need_tail && ws_bytes >= need_tail) {
+            int rc = launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, n_main, K, nullptr, w2, y2, N1, s);
+            if (rc) return rc;
+            return launch_gemm_ws(x, x_stride, w2 + (int64_t)(n_main - N1) * K, y2 + (n_main - N1), N2, nullptr, 0, M,
+                                  N - n_main, K, nullptr, ws, ws_bytes, s);
+        }
+    }
     return launch_gemm_pair(x, x_stride, w1, y1, N1, w2, y2, N2, M, K, s);
 }
 

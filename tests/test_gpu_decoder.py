@@ -83,7 +83,10 @@ def run_layer(vc, c, pos, vis_start, n_vis, keep):
                                                        # 256 < rows <= 1024 and k >= 768: the split-K projections
                                                        # (K alone with norms, Q+V and gate+up as pairs, down)
                                                        (1, 400, 1024, 2, 2, 128, 768, 20, 300, 200),
-                                                       (1, 320, 1024, 2, 2, 128, 768, 0, 300, 300)])
+                                                       (1, 320, 1024, 2, 2, 128, 768, 0, 300, 300),
+                                                       # gate+up as 3 x 86 tiles: the trailing column tile of `up`
+                                                       # goes out as a launch of its own
+                                                       (1, 640, 1024, 2, 2, 128, 11008, 35, 576, 576)])
 def test_decoder_layer_matches_oracle(vc, B, T, D, Hq, Hkv, d, F, vs, nv, keep):
     c = I.decoder_inputs(9300 + T, B, T, D, Hq, Hkv, d, F)
     pos = np.stack([np.sort(np.random.default_rng(10 + b).choice(2 * T, T, replace=False)) for b in range(B)])

@@ -125,6 +125,28 @@ def test_project_split_k_matches_oracle(vc, M, N, K):
     assert_bf16_of(host_bits(y2), ref, f"project (one pass over k) {M}x{N}x{K}")
 
 
+@pytest.mark.parametrize("M,N,K,want", [(640, 22016, 1024, True), (640, 22016, 768, False), (1000, 16640, 768, False)])
+def test_project_trailing_columns_matches_oracle(vc, M, N, K, want):
+    # a few tiles over whole rounds of 256 workgroups (3 x 86 tiles of 256 x 256): the leading columns go out on
+    # the big tiles and the trailing ones as a split-K launch of their own; both halves with residual, and the
+    # norm side output's parts continue across the cut
+    assert vc.lib.vitcop_project_workspace_bytes(M, N, K) > 0
+    x = I.normal_bf16(M + N + K, 0, (M, K))
+    w = I.normal_bf16(M + N + K, 1, (N, K), 0.05)
+    r = I.normal_bf16(M + N + K, 2, (M, N))
+    y, parts = vc.vitcop_project(dev(x), dev(w), residual=dev(r), want_sumsq=want)
+    torch.cuda.synchronize()
+    ref = O.project(x, w) + O.bf16_to_f64(r)
+    yb = host_bits(y)
+    assert_bf16_of(yb, ref, f"project {M}x{N}x{K}")
+    if want:
+        ss = parts.cpu().numpy().astype(np.float64)
+        rounded = I.bf16_bits_to_f32(yb).astype(np.float64) ** 2
+        assert parts.shape[0] == vc.vitcop_project_sumsq_parts(N)
+        for p_ in range(parts.shape[0]):
+            assert np.allclose(ss[p_], rounded[:, 128 * p_:128 * p_ + 128].sum(axis=1), rtol=1e-5)
+
+
 def test_project_residual_and_strides(vc):
     M, N, K = 200, 256, 128
     x = I.normal_bf16(1, 0, (M, K)); w = I.normal_bf16(1, 1, (N, K), 0.1); r = I.normal_bf16(1, 2, (M, N))
