@@ -18,6 +18,9 @@
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
+#include <cstdio>
+#include <cstdlib>
+
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
@@ -516,16 +519,40 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
 // through a CU's load path, which is what bounds them.  So the tiles stay big and the k-range is cut
 // into `splits` slices (blockIdx.y) whose fp32 partials the few-row path's reduction kernels add up.
 struct SplitKPlan {
-    int bm = 0, splits = 0;          // splits == 0: does not apply
+    int bm = 0, bn = 256, splits = 0;          // splits == 0: does not apply
 };
 static SplitKPlan splitk_plan(int M, int N, int K) {
     SplitKPlan p;
     if (M <= 256 || M > 1024 || N % 16 != 0 || K % 32 != 0) return p;
-    // 256 or 192 rows per tile, whichever pads M less (192 runs at 0.8 of the rate)
-    const int t256 = (M + 255) / 256, t192 = (M + 191) / 192;
+#ifdef VITCOP_SWEEP
+    if (const char* e = getenv("VITCOP_SK")) {          // "bm,bn,splits" (timing sweeps only)
+        int bm = 0, bn = 0, sp = 0;
+        if (sscanf(e, "%d,%d,%d", &bm, &bn, &sp) == 3 && sp >= 2 && sp <= 16 && K / 32 / sp >= 4) {
+            p.bm = bm; p.bn = bn; p.splits = sp;
+        }
+        return p;
+    }
+#endif
+    // 128-column tiles first: for the same number of workgroups they need half the slices of the 256-column
+    // tiles, i.e. half the fp32 partials to write and to add up, and at these sizes that traffic, not the
+    // matrix cores, sets the time (317 x 4096 x 4096: 28 us with 2 x 32 tiles x 4 slices against 36 us with
+    // 2 x 16 tiles x 8).  Rows per tile: 192 or 256, whichever leaves the shorter slice per workgroup at its
+    // measured rate.
+    const int t256 = (M + 255) / 256, t192 = (M + 191) / 192, cols = (N + 127) / 128;
+    auto slices = [&](int tiles) { return std::min(std::min(16, 256 / std::max(tiles, 1)), K / 32 / 8); };
+    const int s192 = slices(t192 * cols), s256 = slices(t256 * cols);
+    const float c192 = s192 >= 2 ? 192.0f / (0.64f * (float)s192) : 1e30f;
+    const float c256 = s256 >= 2 ? 256.0f / (0.74f * (float)s256) : 1e30f;
+    if (s192 >= 2 || s256 >= 2) {
+        p.bn = 128;
+        p.bm = c192 <= c256 ? 192 : 256;
+        p.splits = c192 <= c256 ? s192 : s256;
+        return p;
+    }
+    // 256-column tiles: 256 or 192 rows, whichever pads M less (192 runs at 0.8 of the rate)
     const int bm = (float)(t192 * 192) / 0.8f < (float)(t256 * 256) ? 192 : 256;
     const int tiles = (bm == 192 ? t192 : t256) * ((N + 255) / 256);
-    const int splits = std::min(std::min(16, 256 / tiles), K / 32 / 8);     // at least 8 k-steps per slice
+    const int splits = slices(tiles);                                       // at least 8 k-steps per slice
     if (splits < 3) return p;
     p.bm = bm;
     p.splits = splits;
@@ -567,14 +594,15 @@ static int launch_gemm_splitk(const uint16_t* x, int64_t x_stride, const uint16_
     const SplitKPlan p = splitk_plan(M, N, K);
     float* part = static_cast<float*>(ws);
     int rc;
-    if (p.bm == 256)
-        rc = launch_gemm_cfg<256, 256, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr,
-                                                             w2, nullptr, n_split, s, K, nullptr, nullptr, part, N,
-                                                             p.splits, 0, 0, (int64_t)M * N);
-    else
-        rc = launch_gemm_cfg<192, 256, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr,
-                                                             w2, nullptr, n_split, s, K, nullptr, nullptr, part, N,
-                                                             p.splits, 0, 0, (int64_t)M * N);
+#define VITCOP_SPLITK(BM, BN)                                                                                      \
+    rc = launch_gemm_cfg<BM, BN, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr, w2, \
+                                                        nullptr, n_split, s, K, nullptr, nullptr, part, N, p.splits, \
+                                                        0, 0, (int64_t)M * N)
+    if (p.bm == 256 && p.bn == 256) VITCOP_SPLITK(256, 256);
+    else if (p.bm == 192 && p.bn == 256) VITCOP_SPLITK(192, 256);
+    else if (p.bm == 256) VITCOP_SPLITK(256, 128);
+    else VITCOP_SPLITK(192, 128);
+#undef VITCOP_SPLITK
     if (rc) return rc;
     const SkParts parts{part, 0, p.splits, N, M};
     const SkMats mats{{w, w2 ? w2 : w, w}, {y, w2 ? y2 : y, y}, {y_stride, y_stride, y_stride},
