@@ -18,9 +18,6 @@
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
-#include <cstdio>
-#include <cstdlib>
-
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
@@ -524,15 +521,6 @@ struct SplitKPlan {
 static SplitKPlan splitk_plan(int M, int N, int K) {
     SplitKPlan p;
     if (M <= 256 || M > 1024 || N % 16 != 0 || K % 32 != 0) return p;
-#ifdef VITCOP_SWEEP
-    if (const char* e = getenv("VITCOP_SK")) {          // "bm,bn,splits" (timing sweeps only)
-        int bm = 0, bn = 0, sp = 0;
-        if (sscanf(e, "%d,%d,%d", &bm, &bn, &sp) == 3 && sp >= 2 && sp <= 16 && K / 32 / sp >= 4) {
-            p.bm = bm; p.bn = bn; p.splits = sp;
-        }
-        return p;
-    }
-#endif
     // 128-column tiles first: for the same number of workgroups they need half the slices of the 256-column
     // tiles, i.e. half the fp32 partials to write and to add up, and at these sizes that traffic, not the
     // matrix cores, sets the time (317 x 4096 x 4096: 28 us with 2 x 32 tiles x 4 slices against 36 us with
