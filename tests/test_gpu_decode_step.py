@@ -131,3 +131,40 @@ def test_prefill_then_decode_equals_longer_prefill(vc):
     y = step.run()
     torch.cuda.synchronize()
     assert_attention_close(host_f64(y), host_f64(y_full[:, -1]), "decode after prefill")
+
+
+def test_decode_step_in_a_hip_graph(vc):
+    # the step of one to four samples is kernel launches only (no allocation, no synchronisation, no memset):
+    # captured once and replayed, every replay gives the eager result bit for bit, with eager work in between
+    B, (D, Hq, Hkv, d, F), n_cached, cap = 2, RAGGED, (40, 17, 90), 128
+    h, layers = model(7600, 3, B, 1, D, Hq, Hkv, d, F)
+    pos = torch.tensor([300, 411], dtype=torch.int32, device="cuda")
+    caches = []
+    for l, n in enumerate(n_cached):
+        kc, vcache = cache_pair(B, cap, Hkv, d)
+        kc[:, :n] = dev(I.normal_bf16(7700 + l, 0, (B, n, Hkv, d)))
+        vcache[:, :n] = dev(I.normal_bf16(7700 + l, 1, (B, n, Hkv, d)))
+        caches.append((kc, vcache))
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    plan = vc.DecoderDecodePlan(dev(h[:, 0]), pos, wd, Hq, Hkv, d, caches, n_cached)
+    y_eager = plan.run().clone()
+    rows_eager = [kc[:, n].clone() for (kc, _), n in zip(caches, n_cached)]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            plan.run()
+    torch.cuda.current_stream().wait_stream(side)
+    for rep in range(3):
+        plan.y.zero_()
+        for (kc, vcache), n in zip(caches, n_cached):          # eager work between the replays
+            kc[:, n].zero_()
+            vcache[:, n].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(plan.y, y_eager), f"replay {rep}"
+        for (kc, _), n, row in zip(caches, n_cached, rows_eager):
+            assert torch.equal(kc[:, n], row), f"replay {rep}: appended K"
