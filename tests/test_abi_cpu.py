@@ -129,7 +129,11 @@ def test_project_and_select_from_sumsq_validation():
     assert lib.vitcop_project_sumsq_parts(4096) == 32 and lib.vitcop_project_sumsq_parts(512) == 4
     # scratch of the few-row path: two fp32 partial tiles of 128 columns per workgroup
     assert lib.vitcop_project_workspace_bytes(128, 4096, 4096) == 2 * 256 * 128 * 128 * 4
-    assert lib.vitcop_project_workspace_bytes(640, 4096, 4096) == 5 * 640 * 4096 * 4      # split-K: 48 tiles, 5 slices
+    assert lib.vitcop_project_workspace_bytes(640, 4096, 4096) == 2 * 640 * 4096 * 4      # split-K: 4 x 32 tiles, 2 slices
+    assert lib.vitcop_project_workspace_bytes(317, 4096, 4096) == 4 * 317 * 4096 * 4      # 2 x 32 tiles, 4 slices
+    # 3 x 86 tiles of 256 x 256: the last column tile goes out on its own, in 16 slices
+    assert lib.vitcop_project_workspace_bytes(640, 22016, 4096) == 16 * 640 * 256 * 4
+    assert lib.vitcop_project_workspace_bytes(1536, 8192, 4096) == 0                       # 256 tiles: one whole round
     assert lib.vitcop_project_workspace_bytes(2000, 4096, 4096) == 0
     assert lib.vitcop_project_workspace_bytes(128, 4096, 96) == 0
     assert f(A16, 4096, A16, A16, 4096, None, 0, 128, 4096, 4096, None, A16 + 4, 1 << 30, None) == binding.VITCOP_EINVAL
