@@ -531,10 +531,13 @@ static SplitKPlan splitk_plan(int M, int N, int K) {
     const int s192 = slices(t192 * cols), s256 = slices(t256 * cols);
     const float c192 = s192 >= 2 ? 192.0f / (0.64f * (float)s192) : 1e30f;
     const float c256 = s256 >= 2 ? 256.0f / (0.74f * (float)s256) : 1e30f;
-    if (s192 >= 2 || s256 >= 2) {
+    const int s128 = c192 <= c256 ? s192 : s256;
+    // (not with slices longer than 4096 of k: inside a layer the 640-row down projection, K = 11008, takes
+    // 110 us as 4 x 32 tiles x 2 slices against 91 us as 3 x 16 tiles x 5)
+    if (s128 >= 2 && K / s128 <= 4096) {
         p.bn = 128;
         p.bm = c192 <= c256 ? 192 : 256;
-        p.splits = c192 <= c256 ? s192 : s256;
+        p.splits = s128;
         return p;
     }
     // 256-column tiles: 256 or 192 rows, whichever pads M less (192 runs at 0.8 of the rate)
