@@ -511,10 +511,10 @@ int launch_gemm_pair(const uint16_t* x, int64_t x_stride, const uint16_t* w1, ui
     return launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, N1 + N2, K, nullptr, w2, y2, N1, s);
 }
 
-// Split-K on the big tiles, for a few hundred to a thousand rows: there are then too few 256-wide
-// tiles to fill the chip, and the smaller tiles that would fill it load twice the bytes per FLOP
-// through a CU's load path, which is what bounds them.  So the tiles stay big and the k-range is cut
-// into `splits` slices (blockIdx.y) whose fp32 partials the few-row path's reduction kernels add up.
+// Split-K for a few hundred to a thousand rows: there are then too few large tiles to fill the chip,
+// and 128 x 128 tiles, which would, load twice the bytes per FLOP through a CU's load path, which is
+// what bounds them.  So the tiles stay 192 or 256 rows tall and the k-range is cut into `splits` slices
+// (blockIdx.y) whose fp32 partials the few-row path's reduction kernels add up.
 struct SplitKPlan {
     int bm = 0, bn = 256, splits = 0;          // splits == 0: does not apply
 };
