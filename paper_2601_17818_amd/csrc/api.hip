@@ -1161,7 +1161,6 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
         return VITCOP_OK;
     }
     const uint16_t* a = nullptr;            // RMSNorm of h with this layer's ln1, left by the layer before
-    const size_t rowb = (size_t)kd * 2, pitch = (size_t)S->cache_capacity * kd * 2;
     for (int l = 0; l < S->n_layers; ++l) {
         REQUIRE(S->ln1[l] && S->ln2[l] && S->wq[l] && S->wk[l] && S->wv[l] && S->wo[l] && S->wg[l] && S->wu[l] &&
                     S->wd[l] && S->k_cache[l] && S->v_cache[l],
@@ -1178,14 +1177,10 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
         const int n3[3] = {kd, qd, kd};
         rc = launch_gemm_triple_ws(a, D, w3, y3, n3, B, D, gs, gs_bytes, s);
         if (rc) return rc;
-        rc = launch_rope(qb, k_new, S->positions, B, S->Hq, S->Hkv, S->d, S->theta, s);
-        if (rc) return rc;
-        // the new token's K and V become row N of every sample's cache
-        rc = hip_status(hipMemcpy2DAsync(S->k_cache[l] + (size_t)N * kd, pitch, k_new, rowb, rowb, B,
-                                         hipMemcpyDeviceToDevice, s), "append K");
-        if (rc) return rc;
-        rc = hip_status(hipMemcpy2DAsync(S->v_cache[l] + (size_t)N * kd, pitch, v_new, rowb, rowb, B,
-                                         hipMemcpyDeviceToDevice, s), "append V");
+        // the rotary embedding; the new token's K and V become row N of every sample's cache
+        rc = launch_rope_append(qb, k_new, v_new, S->positions, B, S->Hq, S->Hkv, S->d, S->theta,
+                                S->k_cache[l] + (size_t)N * kd, S->v_cache[l] + (size_t)N * kd,
+                                (int64_t)S->cache_capacity * kd, s);
         if (rc) return rc;
         rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
                                 1.0f / std::sqrt((float)S->d), dws, s, (int64_t)S->cache_capacity * kd);

@@ -124,6 +124,67 @@ int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_to
     return launch_status("rope");
 }
 
+// The decoding step's variant: one new token per sample.  q is embedded in place; k is embedded on its way
+// into the sample's next cache row (k_dst + b * kv_batch) and v is copied into its row, so the append needs
+// no copies of its own.  Threads: per token (Hq + Hkv) * d/16 rotary groups, then Hkv * d/8 chunks of v.
+__global__ __launch_bounds__(RP_THREADS) void rope_append_kernel(
+    uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
+    const int32_t* __restrict__ positions, int n_tokens, int Hq, int Hkv, int d, float neg_log2_theta_2_over_d,
+    uint16_t* __restrict__ k_dst, uint16_t* __restrict__ v_dst, int64_t kv_batch) {
+    const int groups = d / 16;
+    const int rot = (Hq + Hkv) * groups, per_token = rot + Hkv * (d / 8);
+    const int idx = blockIdx.x * RP_THREADS + threadIdx.x;
+    const int token = idx / per_token;
+    if (token >= n_tokens) return;
+    const int rem = idx - token * per_token;
+    if (rem >= rot) {                                   // a 16-byte chunk of v
+        const int c = rem - rot;
+        *reinterpret_cast<uint4*>(v_dst + token * kv_batch + 8 * c) =
+            *reinterpret_cast<const uint4*>(v + ((int64_t)token * Hkv * d) + 8 * c);
+        return;
+    }
+    const int head = rem / groups, grp = rem - head * groups;
+    const bool is_q = head < Hq;
+    const uint16_t* src = is_q ? q + ((int64_t)token * Hq + head) * d : k + ((int64_t)token * Hkv + (head - Hq)) * d;
+    uint16_t* dst = is_q ? q + ((int64_t)token * Hq + head) * d : k_dst + token * kv_batch + (head - Hq) * d;
+    const float pos = (float)positions[token];
+    const uint4 lo = *reinterpret_cast<const uint4*>(src + 8 * grp);
+    const uint4 hi = *reinterpret_cast<const uint4*>(src + d / 2 + 8 * grp);
+    const uint32_t* lw = reinterpret_cast<const uint32_t*>(&lo);
+    const uint32_t* hw = reinterpret_cast<const uint32_t*>(&hi);
+    uint32_t ol[4], oh[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        float rl[2], rh[2];
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+            const int i = 8 * grp + 2 * p + e;
+            const float inv_freq = __builtin_exp2f((float)i * neg_log2_theta_2_over_d);
+            float sn, cs;
+            sincosf(pos * inv_freq, &sn, &cs);
+            const float a = e ? bf16_hi(lw[p]) : bf16_lo(lw[p]);
+            const float b = e ? bf16_hi(hw[p]) : bf16_lo(hw[p]);
+            rl[e] = a * cs - b * sn;
+            rh[e] = b * cs + a * sn;
+        }
+        ol[p] = pack_bf16(rl[0], rl[1]);
+        oh[p] = pack_bf16(rh[0], rh[1]);
+    }
+    *reinterpret_cast<uint4*>(dst + 8 * grp) = make_uint4(ol[0], ol[1], ol[2], ol[3]);
+    *reinterpret_cast<uint4*>(dst + d / 2 + 8 * grp) = make_uint4(oh[0], oh[1], oh[2], oh[3]);
+}
+
+int launch_rope_append(uint16_t* q, const uint16_t* k, const uint16_t* v, const int32_t* positions, int n_tokens,
+                       int Hq, int Hkv, int d, float theta, uint16_t* k_dst, uint16_t* v_dst, int64_t kv_batch,
+                       hipStream_t s) {
+    const int64_t threads = (int64_t)n_tokens * ((Hq + Hkv) * (d / 16) + Hkv * (d / 8));
+    if (threads == 0) return VITCOP_OK;
+    const float c = -2.0f * std::log2(theta) / (float)d;
+    hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)((threads + RP_THREADS - 1) / RP_THREADS)), dim3(RP_THREADS),
+                       0, s, q, k, v, positions, n_tokens, Hq, Hkv, d, c, k_dst, v_dst, kv_batch);
+    return launch_status("rope_append");
+}
+
 // out = silu(gate) * up, 8 elements per thread
 __global__ __launch_bounds__(256) void silu_mul_kernel(const uint16_t* __restrict__ gate,
                                                        const uint16_t* __restrict__ up,

@@ -156,6 +156,10 @@ int launch_rmsnorm(const uint16_t* x, int64_t x_stride, const uint16_t* w, float
 // in place; q [n_tokens,Hq,d] and k [n_tokens,Hkv,d] (either may be null), positions [n_tokens]
 int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_tokens, int Hq, int Hkv, int d,
                 float theta, hipStream_t s);
+// one new token per sample: q embedded in place, k embedded into k_dst + b * kv_batch, v copied to v_dst + b * kv_batch
+int launch_rope_append(uint16_t* q, const uint16_t* k, const uint16_t* v, const int32_t* positions, int n_tokens,
+                       int Hq, int Hkv, int d, float theta, uint16_t* k_dst, uint16_t* v_dst, int64_t kv_batch,
+                       hipStream_t s);
 int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, hipStream_t s);
 
 // ---- decoding step over the KV cache (decode.hip) ---------------------------

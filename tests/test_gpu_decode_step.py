@@ -133,12 +133,14 @@ def test_prefill_then_decode_equals_longer_prefill(vc):
     assert_attention_close(host_f64(y), host_f64(y_full[:, -1]), "decode after prefill")
 
 
-def test_decode_step_in_a_hip_graph(vc):
-    # the step of one to four samples is kernel launches only (no allocation, no synchronisation, no memset):
-    # captured once and replayed, every replay gives the eager result bit for bit, with eager work in between
-    B, (D, Hq, Hkv, d, F), n_cached, cap = 2, RAGGED, (40, 17, 90), 128
-    h, layers = model(7600, 3, B, 1, D, Hq, Hkv, d, F)
-    pos = torch.tensor([300, 411], dtype=torch.int32, device="cuda")
+@pytest.mark.parametrize("B", [2, 6])
+def test_decode_step_in_a_hip_graph(vc, B):
+    # the step is kernel launches only (no allocation, synchronisation, copy or memset), on the streaming
+    # path (B <= 4) and on the few-row matrix-core path: captured once and replayed, every replay gives the
+    # eager result bit for bit, with eager work in between
+    (D, Hq, Hkv, d, F), n_cached, cap = RAGGED, (40, 17, 90), 128
+    h, layers = model(7600 + B, 3, B, 1, D, Hq, Hkv, d, F)
+    pos = torch.tensor([300 + 111 * b for b in range(B)], dtype=torch.int32, device="cuda")
     caches = []
     for l, n in enumerate(n_cached):
         kc, vcache = cache_pair(B, cap, Hkv, d)
