@@ -91,21 +91,45 @@ __global__ __launch_bounds__(SEL_THREADS) void filter_finalize_kernel(
     const int b = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int N1 = N + 1;
     const float* lg = logits + (int64_t)b * H * N1;
+    // (the workgroup is alone on its CU and everything it reads is a round trip to L2: a head's row is read
+    // once, all of its loads in flight together, and kept in registers for the second pass)
+    constexpr int FF_HELD = 16;                    // logits per lane held in registers: rows up to 1024 tokens
     for (int h = wv; h < H; h += SEL_THREADS / 64) {
         const float* row = lg + (int64_t)h * N1;
-        float m = -INFINITY;
-        for (int i = lane; i < N1; i += 64) m = fmaxf(m, row[i]);
-        m = wave_max(m);
-        float z = 0.f;
-        for (int i = lane; i < N1; i += 64) z += __expf(row[i] - m);
+        float m = -INFINITY, z = 0.f;
+        if (N1 <= 64 * FF_HELD) {
+            float held[FF_HELD];
+#pragma unroll
+            for (int j = 0; j < FF_HELD; ++j) {
+                const int i = lane + 64 * j;
+                held[j] = i < N1 ? row[i] : -INFINITY;
+            }
+#pragma unroll
+            for (int j = 0; j < FF_HELD; ++j) m = fmaxf(m, held[j]);
+            m = wave_max(m);
+#pragma unroll
+            for (int j = 0; j < FF_HELD; ++j)
+                if (lane + 64 * j < N1) z += __expf(held[j] - m);
+        } else {
+            for (int i = lane; i < N1; i += 64) m = fmaxf(m, row[i]);
+            m = wave_max(m);
+            for (int i = lane; i < N1; i += 64) z += __expf(row[i] - m);
+        }
         z = wave_sum(z);
         if (lane == 0) { head_max[h] = m; head_inv[h] = 1.0f / z; }
     }
     __syncthreads();
     for (int i = tid; i < N; i += SEL_THREADS) {
         float s = 0.f;
-        for (int h = 0; h < H; ++h)
-            s = fmaf(__expf(lg[(int64_t)h * N1 + i + 1] - head_max[h]), head_inv[h], s);
+        int h = 0;
+        for (; h + 8 <= H; h += 8) {               // eight heads' logits in flight, added in head order
+            float w[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) w[j] = lg[(int64_t)(h + j) * N1 + i + 1];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) s = fmaf(__expf(w[j] - head_max[h + j]), head_inv[h + j], s);
+        }
+        for (; h < H; ++h) s = fmaf(__expf(lg[(int64_t)h * N1 + i + 1] - head_max[h]), head_inv[h], s);
         if (scores_out) scores_out[(int64_t)b * N + i] = s;
         sel_keys[i] = ~__float_as_uint(s);         // s >= 0: complement reverses the order
     }

@@ -75,20 +75,41 @@ __global__ __launch_bounds__(SEL_THREADS) void select_smallest_kernel(
     const int Tp = T - n_vis + keep;
     int32_t* out = keep_idx + (int64_t)b * Tp;
     const float* src = parts + (int64_t)b * sample_stride + offset;
-    for (int i = tid; i < n_vis; i += SEL_THREADS) {
-        float v = src[i];
-        int p = 1;
-        for (; p + 8 <= n_parts; p += 8) {           // eight independent loads in flight, summed in order
-            float w[8];
+    // Four candidates per thread at a time, eight parts each: 32 independent loads in flight per round trip
+    // (the workgroup is alone on its CU and the reads are all latency); every candidate's parts are added in
+    // index order, so the sums do not depend on the grouping.
+    constexpr int RU = 4;
+    for (int i0 = tid; i0 < n_vis; i0 += SEL_THREADS * RU) {
+        int row[RU];
+        float v[RU];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) w[j] = src[(int64_t)(p + j) * part_stride + i];
-#pragma unroll
-            for (int j = 0; j < 8; ++j) v += w[j];
+        for (int r = 0; r < RU; ++r) {
+            row[r] = min(i0 + r * SEL_THREADS, n_vis - 1);      // past the end: a valid row, not stored
+            v[r] = src[row[r]];
         }
-        for (; p < n_parts; ++p) v += src[(int64_t)p * part_stride + i];
-        if (do_sqrt) v = sqrtf(v);
-        if (norms_out) norms_out[(int64_t)b * n_vis + i] = v;
-        sel_keys[i] = __float_as_uint(v);          // v >= 0: bit order = value order
+        int p = 1;
+        for (; p + 8 <= n_parts; p += 8) {
+            float w[RU][8];
+#pragma unroll
+            for (int r = 0; r < RU; ++r)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) w[r][j] = src[(int64_t)(p + j) * part_stride + row[r]];
+#pragma unroll
+            for (int r = 0; r < RU; ++r)
+#pragma unroll
+                for (int j = 0; j < 8; ++j) v[r] += w[r][j];
+        }
+        for (; p < n_parts; ++p)
+#pragma unroll
+            for (int r = 0; r < RU; ++r) v[r] += src[(int64_t)p * part_stride + row[r]];
+#pragma unroll
+        for (int r = 0; r < RU; ++r) {
+            const int i = i0 + r * SEL_THREADS;
+            if (i >= n_vis) continue;
+            const float val = do_sqrt ? sqrtf(v[r]) : v[r];
+            if (norms_out) norms_out[(int64_t)b * n_vis + i] = val;
+            sel_keys[i] = __float_as_uint(val);      // val >= 0: bit order = value order
+        }
     }
     // text before and after the visual span is always kept
     for (int i = tid; i < vis_start; i += SEL_THREADS) out[i] = i;
