@@ -85,23 +85,21 @@ __global__ __launch_bounds__(SEL_THREADS) void select_smallest_kernel(
 #pragma unroll
         for (int r = 0; r < RU; ++r) {
             row[r] = min(i0 + r * SEL_THREADS, n_vis - 1);      // past the end: a valid row, not stored
-            v[r] = src[row[r]];
+            v[r] = 0.f;                                         // (0 + part 0 is part 0 exactly)
         }
-        int p = 1;
-        for (; p + 8 <= n_parts; p += 8) {
-            float w[RU][8];
+        for (int p = 0; p < n_parts; p += 8) {                  // the last group may be short: its loads repeat
+            float w[RU][8];                                     // the last part and are not added
 #pragma unroll
             for (int r = 0; r < RU; ++r)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) w[r][j] = src[(int64_t)(p + j) * part_stride + row[r]];
+                for (int j = 0; j < 8; ++j)
+                    w[r][j] = src[(int64_t)min(p + j, n_parts - 1) * part_stride + row[r]];
 #pragma unroll
             for (int r = 0; r < RU; ++r)
 #pragma unroll
-                for (int j = 0; j < 8; ++j) v[r] += w[r][j];
+                for (int j = 0; j < 8; ++j)
+                    if (p + j < n_parts) v[r] += w[r][j];
         }
-        for (; p < n_parts; ++p)
-#pragma unroll
-            for (int r = 0; r < RU; ++r) v[r] += src[(int64_t)p * part_stride + row[r]];
 #pragma unroll
         for (int r = 0; r < RU; ++r) {
             const int i = i0 + r * SEL_THREADS;
