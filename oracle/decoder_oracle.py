@@ -146,7 +146,8 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
 
     ``labels`` [n_vis] and ``k_norms`` [n_vis] replace the clustering and the norms computed here (for
     checking a pipeline whose own, separately validated, values decide differently among near-ties).
-    Returns the final hidden state, positions, and what Stage II produced.
+    Returns the final hidden state, positions, what Stage II produced, and per layer the K (after the rotary
+    embedding) and V of the tokens the layer attended over (the KV cache a decoding step continues from).
     """
     h = np.asarray(h_bits)
     pos = np.asarray(positions)
@@ -156,6 +157,7 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
     cur_vis = n_vis
     s2 = None
     out = None
+    caches = []
     for l, w in enumerate(layer_weights):
         if l == stage2["layer"]:
             T = h.shape[1]
@@ -179,11 +181,12 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
         keep = min(stages.get(l, cur_vis), cur_vis)
         forced = None if keep_lists is None else keep_lists.get(l)
         out = decoder_layer(h, w, Hq, Hkv, d, vis_start, cur_vis, keep, pos, eps, theta, keep_idx=forced)
+        caches.append((out["k_rope"], out["v"]))
         if l in stages:
             pos = out["positions"]
             cur_vis = keep
         h = out["y_bits"]
-    return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2}
+    return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2, "caches": caches}
 
 
 def decode_step(h_bits, layer_weights, caches, positions, Hq: int, Hkv: int, d: int, eps: float = 1e-5,

@@ -218,3 +218,45 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
                                  k_norms=norms, keep_lists={l3: idx[None]})
     assert np.array_equal(got_pos, ref["positions"])
     assert_attention_close(host_f64(y), ref["y"], "full schedule output")
+
+
+def test_full_schedule_caches_then_decode(vc):
+    # the paper's whole procedure, then generation: prefill with Stage II on entry to layer 1 and Stage III on
+    # entry to layer 3, every layer leaving its KV cache (three different lengths), then one decoding step over
+    # those caches; oracle: the same procedure on the GPU's labels, norms and Stage III list, its caches, its step
+    D, Hq, Hkv, d, F, vs, n, tail = 256, 4, 2, 128, 384, 12, 150, 10
+    T = vs + n + tail
+    h, layers, xy = full_case(9950, vs, n, tail, D, Hq, Hkv, d, F, 4, 16, 6)
+    pos = (2 * np.arange(T))[None].astype(np.int32)
+    s2 = {"layer": 1, "budget": 60, "n_centers": 6, "d_c": 8.0, "tau": 0.6}
+    schedule = ((3, 20),)
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    cap = T + 8
+    caches = [(torch.zeros((1, cap, Hkv, d), dtype=torch.bfloat16, device="cuda"),
+               torch.zeros((1, cap, Hkv, d), dtype=torch.bfloat16, device="cuda")) for _ in layers]
+    plan = vc.FullSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, n,
+                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)).cuda()}, schedule, caches=caches)
+    y, p = plan.run()
+    torch.cuda.synchronize()
+    labels, norms = plan.labels.cpu().numpy(), plan.norms.cpu().numpy()
+    mid = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos, labels=labels, k_norms=norms)
+    n2 = mid["stage2"]["n_out"]
+    lookup = {int(q): i for i, q in enumerate(mid["positions"][0])}
+    idx = np.array([lookup[int(q)] for q in p.cpu().numpy()[0]])
+    ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
+                             k_norms=norms, keep_lists={3: idx[None]})
+    lengths = [T, T - n + n2, T - n + n2, T - n + 20]
+    assert plan.T_final == lengths[-1] and plan.n_stage2 == n2
+    for (kc, vcache), (k_ref, v_ref), L in zip(caches, ref["caches"], lengths):
+        assert k_ref.shape[1] == L
+        assert_attention_close(host_f64(kc)[:, :L], O.bf16_to_f64(k_ref), "K cache after the full schedule")
+        assert_attention_close(host_f64(vcache)[:, :L], O.bf16_to_f64(v_ref), "V cache after the full schedule")
+        assert not host_bits(kc)[:, L:].any()
+    # one decoding step from there: a new token at the next position
+    h_new = I.decoder_inputs(9960, 1, 1, D, Hq, Hkv, d, F)["h"][:, 0]
+    new_pos = np.array([2 * T], dtype=np.int32)
+    step = vc.DecoderDecodePlan(dev(h_new), torch.from_numpy(new_pos).cuda(), wd, Hq, Hkv, d, caches, lengths)
+    y1 = step.run()
+    torch.cuda.synchronize()
+    ref1 = Dc.decode_step(h_new, layers, ref["caches"], new_pos, Hq, Hkv, d)
+    assert_attention_close(host_f64(y1), ref1["y"], "decoding step after the full schedule")

@@ -140,6 +140,8 @@ def test_vitcop_schedule_with_one_token_per_cluster_is_the_plain_schedule():
     want = Dc.decoder_schedule(h, layers, (), 4, 2, 64, 6, 28, pos)
     assert got["stage2"]["n_out"] == 28 and np.array_equal(got["stage2"]["index"], np.arange(28))
     assert np.array_equal(got["y_bits"], want["y_bits"]) and np.array_equal(got["positions"], pos)
+    for (k1, v1), (k2, v2) in zip(got["caches"], want["caches"]):          # and leaves the same KV caches
+        assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
 
 
 def test_vitcop_schedule_single_cluster_by_hand():
