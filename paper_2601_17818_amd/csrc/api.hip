@@ -1146,10 +1146,13 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
                                       S->k_cache[l] + (size_t)N * kd, S->v_cache[l] + (size_t)N * kd, kv_batch,
                                       S->positions, B, S->Hq, S->Hkv, S->d, D, S->theta, s);
             if (rc) return rc;
+            // (one sample and few slices: the output projection combines them itself, no merge launch; with more
+            // samples every workgroup would repeat the combination for each of them and the launch is cheaper)
+            DecodeParts slices{nullptr, nullptr, 0};
             rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
-                                    1.0f / std::sqrt((float)S->d), dws, s, kv_batch);
+                                    1.0f / std::sqrt((float)S->d), dws, s, kv_batch, B == 1 ? &slices : nullptr);
             if (rc) return rc;
-            rc = launch_gemv(ob, qd, nullptr, 0.f, S->wo[l], h1, D, h, D, B, D, qd, s);
+            rc = launch_gemv(ob, qd, nullptr, 0.f, S->wo[l], h1, D, h, D, B, D, qd, s, &slices, S->d);
             if (rc) return rc;
             rc = launch_gemv_gated(h1, D, S->ln2[l], S->eps, S->wg[l], S->wu[l], act, F, B, F, D, s);
             if (rc) return rc;

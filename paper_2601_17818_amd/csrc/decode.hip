@@ -173,7 +173,8 @@ static void launch_partial(dim3 grid, hipStream_t s, const uint16_t* q, const ui
 
 template <int D>
 static int launch_decode_d(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
-                           int B, int N, int Hq, int Hkv, float scale, void* ws, hipStream_t s, int64_t kv_batch) {
+                           int B, int N, int Hq, int Hkv, float scale, void* ws, hipStream_t s, int64_t kv_batch,
+                           DecodeParts* hand_over) {
     const int ns = decode_splits(B, N, Hkv);
     const int kps = ((N + ns - 1) / ns + 63) / 64 * 64;
     float* po = static_cast<float*>(ws);
@@ -190,15 +191,21 @@ static int launch_decode_d(const uint16_t* q, const uint16_t* k, const uint16_t*
         int rc = launch_status("decode_partial");
         if (rc) return rc;
     }
+    if (hand_over != nullptr && ns <= DECODE_PARTS_MAX_SPLITS) {       // the caller's next kernel combines the slices
+        *hand_over = DecodeParts{po, pml, ns};
+        return VITCOP_OK;
+    }
+    if (hand_over != nullptr) *hand_over = DecodeParts{nullptr, nullptr, 0};
     hipLaunchKernelGGL((decode_merge_kernel<D>), dim3((unsigned)(B * Hq)), dim3(D), 0, s, po, pml, ns, out, lse);
     return launch_status("decode_merge");
 }
 
 int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
-                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch) {
+                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch,
+                       DecodeParts* hand_over) {
     if (kv_batch == 0) kv_batch = (int64_t)N * Hkv * d;         // dense caches
-    if (d == 64) return launch_decode_d<64>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch);
-    return launch_decode_d<128>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch);
+    if (d == 64) return launch_decode_d<64>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over);
+    return launch_decode_d<128>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over);
 }
 
 }  // namespace vitcop

@@ -54,7 +54,43 @@ struct GvArgs {
     const int32_t* positions;              // rope: [B]
     int Hq, Hkv, d;
     float rope_c;                          // -2 log2(theta) / d
+    const float* part_o;                   // x = the combination of a decoding attention's slices (x unused), or
+    const float* part_ml;                  // nullptr: part_o [B*heads][n_splits][head_dim], part_ml [..][n_splits][2]
+    int n_splits, head_dim;
 };
+
+// Eight consecutive channels (from ch0 on) of one head's attention output from its slices, as
+// decode_merge_kernel forms them: slice weights 2^(m_s - max m), sum of weighted outputs over the sum of
+// weighted sums, rounded to bf16.  The loads of up to eight slices are in flight together.
+__device__ __forceinline__ u32x4 gv_merge8(const float* __restrict__ part_o, const float* __restrict__ part_ml,
+                                           int64_t slot0, int n_splits, int head_dim, int ch0) {
+    float mn = -INFINITY, lt = 0.f, ot[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ot[e] = 0.f;
+    for (int s = 0; s < n_splits; ++s) mn = fmaxf(mn, part_ml[(slot0 + s) * 2]);
+    for (int s0 = 0; s0 < n_splits; s0 += 8) {
+        float ms[8], ls[8];
+        float4 lo[8], hi[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int64_t slot = slot0 + min(s0 + j, n_splits - 1);         // past the end: read again, not used
+            ms[j] = part_ml[slot * 2];
+            ls[j] = part_ml[slot * 2 + 1];
+            lo[j] = *reinterpret_cast<const float4*>(part_o + slot * head_dim + ch0);
+            hi[j] = *reinterpret_cast<const float4*>(part_o + slot * head_dim + ch0 + 4);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            if (s0 + j >= n_splits) continue;
+            const float a = ms[j] == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(ms[j] - mn);
+            lt += ls[j] * a;
+            ot[0] += lo[j].x * a; ot[1] += lo[j].y * a; ot[2] += lo[j].z * a; ot[3] += lo[j].w * a;
+            ot[4] += hi[j].x * a; ot[5] += hi[j].y * a; ot[6] += hi[j].z * a; ot[7] += hi[j].w * a;
+        }
+    }
+    return u32x4{pack_bf16(ot[0] / lt, ot[1] / lt), pack_bf16(ot[2] / lt, ot[3] / lt),
+                 pack_bf16(ot[4] / lt, ot[5] / lt), pack_bf16(ot[6] / lt, ot[7] / lt)};
+}
 
 // the two weight rows of pair p
 template <int EPI>
@@ -171,7 +207,15 @@ __global__ __launch_bounds__(GV_THREADS) void gemv_kernel(GvArgs a) {
             for (int j = 0; j < GV_HELD; ++j) {
                 const int c = tid + GV_THREADS * j;
                 held[b][j] = u32x4{0u, 0u, 0u, 0u};
-                if (c < kc) held[b][j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)b * a.x_stride + 8 * c);
+                if (c < kc) {
+                    if (a.part_o != nullptr) {                    // x[b] = attention output, heads side by side
+                        const int head = 8 * c / a.head_dim, heads = K / a.head_dim;
+                        held[b][j] = gv_merge8(a.part_o, a.part_ml, ((int64_t)b * heads + head) * a.n_splits,
+                                               a.n_splits, a.head_dim, 8 * c - head * a.head_dim);
+                    } else {
+                        held[b][j] = *reinterpret_cast<const u32x4*>(a.x + (int64_t)b * a.x_stride + 8 * c);
+                    }
+                }
                 ss[b] = sumsq8(make_uint4(held[b][j].x, held[b][j].y, held[b][j].z, held[b][j].w), ss[b]);
             }
         }
@@ -334,10 +378,18 @@ static GvArgs gv_args(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w,
     return a;
 }
 
-// y[b, :N] = bf16(norm?(x[b]) W^T + res[b]); N even, W [N][K] dense.
+// y[b, :N] = bf16(norm?(x[b]) W^T + res[b]); N even, W [N][K] dense.  With `attn` (and its head_dim), x[b] is the
+// output of a decoding attention still in slices (K = heads * head_dim), combined in the prologue.
 int launch_gemv(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* w, uint16_t* y,
-                int64_t y_stride, const uint16_t* res, int64_t res_stride, int B, int N, int K, hipStream_t s) {
+                int64_t y_stride, const uint16_t* res, int64_t res_stride, int B, int N, int K, hipStream_t s,
+                const DecodeParts* attn, int head_dim) {
     GvArgs a = gv_args(x, x_stride, ln_w, eps, K);
+    if (attn != nullptr && attn->part_o != nullptr) {            // x comes from the attention's slices
+        a.part_o = attn->part_o;
+        a.part_ml = attn->part_ml;
+        a.n_splits = attn->n_splits;
+        a.head_dim = head_dim;
+    }
     a.w0 = w;
     a.n_pairs = N / 2;
     a.y = y;

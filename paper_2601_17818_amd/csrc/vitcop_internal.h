@@ -102,13 +102,25 @@ int launch_partial_reduce(const SkParts& parts, int N, const SkMats& mats, const
                           float* sumsq_parts, const uint16_t* ln_w, float eps, uint16_t* norm_out,
                           int64_t norm_stride, uint16_t* gated_out, hipStream_t s);
 bool partial_reduce_fuses_norm(int N);
+// The per-slice partials of a decoding attention: part_o [B*Hq][n_splits][d] unnormalised outputs, part_ml
+// [B*Hq][n_splits][2] (running maximum in log2 units, sum).  With hand_over != nullptr and at most
+// DECODE_PARTS_MAX_SPLITS slices launch_decode_attn leaves the combination to the caller's next kernel
+// (`out` is then not written) and describes the partials there; otherwise hand_over->part_o is null.
+constexpr int DECODE_PARTS_MAX_SPLITS = 16;
+struct DecodeParts {
+    const float* part_o;
+    const float* part_ml;
+    int n_splits;
+};
+
 // gemv.hip: projections of at most GV_MAX_ROWS rows as a stream over the weights (decoding steps), with
 // RMSNorm of x in the prologue (ln_w != nullptr) and the residual add, silu(gate) * up, or the rotary
 // embedding with the KV-cache append in the epilogue.  N even, W dense [N][K], K within gemv_applies.
 constexpr int GV_MAX_ROWS = 4;
 bool gemv_applies(int B, int K);
 int launch_gemv(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* w, uint16_t* y,
-                int64_t y_stride, const uint16_t* res, int64_t res_stride, int B, int N, int K, hipStream_t s);
+                int64_t y_stride, const uint16_t* res, int64_t res_stride, int B, int N, int K, hipStream_t s,
+                const DecodeParts* attn = nullptr, int head_dim = 0);
 int launch_gemv_gated(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wg,
                       const uint16_t* wu, uint16_t* act, int64_t act_stride, int B, int F, int K, hipStream_t s);
 int launch_gemv_qkv_rope(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wq,
@@ -166,6 +178,7 @@ int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int
 size_t decode_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
 // kv_batch: elements between two samples' caches (0: dense, N * Hkv * d)
 int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
-                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch = 0);
+                       int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch = 0,
+                       DecodeParts* hand_over = nullptr);
 
 }  // namespace vitcop
