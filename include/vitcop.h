@@ -8,7 +8,9 @@
  *  - Plain C ABI.  bf16 tensors are passed as uint16_t bit patterns.
  *  - Every tensor pointer is a DEVICE pointer owned by the caller, 16-byte
  *    aligned unless stated otherwise, rows contiguous, token-major.
- *  - The library allocates no device memory and keeps no state between calls.
+ *  - The library allocates no device memory and carries no data from one call to
+ *    the next (the only thing it remembers is that a kernel's shared-memory limit
+ *    has been raised, a once-per-process flag that any thread may set again).
  *    Scratch memory comes from the caller through `ws` / `ws_bytes`; the size
  *    needed is returned by the matching *_workspace_bytes query.  The contents
  *    of `ws` need not be initialised and are undefined afterwards.
@@ -362,6 +364,12 @@ typedef struct {
     uint16_t* const* k_cache;
     uint16_t* const* v_cache;
     int cache_capacity;
+    /* Record of the Stage III decisions, may be NULL: host arrays of n_stages device pointers (single entries
+     * may be NULL too).  Stage s writes the fp32 K-norms its selection ranked, [B, visual tokens present on
+     * entry to its layer], and its keep list, [B, tokens the layer keeps] int32 indices into the sequence
+     * that entered the layer. */
+    float* const* stage_norms;
+    int32_t* const* stage_keep_idx;
 } vitcop_decoder_schedule_t;
 size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S);
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream);

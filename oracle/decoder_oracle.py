@@ -158,6 +158,7 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
     s2 = None
     out = None
     caches = []
+    stage3 = {}          # per Stage III layer: the norms ranked there and the keep list taken
     for l, w in enumerate(layer_weights):
         if l == stage2["layer"]:
             T = h.shape[1]
@@ -183,10 +184,11 @@ def vitcop_schedule(h_bits, layer_weights, stage2: dict, schedule, Hq: int, Hkv:
         out = decoder_layer(h, w, Hq, Hkv, d, vis_start, cur_vis, keep, pos, eps, theta, keep_idx=forced)
         caches.append((out["k_rope"], out["v"]))
         if l in stages:
+            stage3[l] = {"norms": out["norms"], "keep_idx": out["keep_idx"]}
             pos = out["positions"]
             cur_vis = keep
         h = out["y_bits"]
-    return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2, "caches": caches}
+    return {"y": out["y"], "y_bits": h, "positions": pos, "stage2": s2, "stage3": stage3, "caches": caches}
 
 
 def decode_step(h_bits, layer_weights, caches, positions, Hq: int, Hkv: int, d: int, eps: float = 1e-5,

@@ -87,7 +87,8 @@ class DecoderScheduleT(C.Structure):
                  ("h", C.c_void_p), ("positions", C.c_void_p)] +
                 [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
                 [("y_out", C.c_void_p), ("positions_out", C.c_void_p),
-                 ("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("cache_capacity", C.c_int)])
+                 ("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("cache_capacity", C.c_int),
+                 ("stage_norms", C.POINTER(C.c_void_p)), ("stage_keep_idx", C.POINTER(C.c_void_p))])
 
 
 class DecoderDecodeT(C.Structure):
@@ -584,9 +585,15 @@ class DecoderSchedulePlan:
         T_final = T - n_vis + (keeps[-1] if keeps else n_vis)
         self.y = torch.empty((B, T_final, D), dtype=h.dtype, device=h.device)
         self.positions = torch.empty((B, T_final), dtype=torch.int32, device=h.device)
+        # record of every stage's decision: the norms it ranked and the keep list it took
+        present = [n_vis] + keeps[:-1]
+        self.stage_norms = [torch.empty((B, n), dtype=torch.float32, device=h.device) for n in present]
+        self.stage_keep_idx = [torch.empty((B, T - n_vis + k), dtype=torch.int32, device=h.device) for k in keeps]
+        self._sn = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self.stage_norms])
+        self._sk = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self.stage_keep_idx])
         self.desc = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
                                      self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self.y),
-                                     _ptr(self.positions), self._kc, self._vc, cap)
+                                     _ptr(self.positions), self._kc, self._vc, cap, self._sn, self._sk)
         nb = lib.vitcop_decoder_schedule_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
@@ -601,7 +608,7 @@ class FullSchedulePlan:
     """Pre-marshalled vitcop_full_schedule_prefill call (one sample).  ``stage2``: dict with layer, budget,
     n_centers, d_c, tau and xy (device tensor [n_vis, 2] fp32); ``schedule``: the Stage III stages after it.
     ``run`` returns (y [1, T_final, D], positions [1, T_final]); labels, norms, out_index and n_stage2 hold
-    what Stage II produced."""
+    what Stage II produced, stage_norms[s] and stage_keep_idx[s] what Stage III stage s ranked and kept."""
 
     def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, stage2: dict,
                  schedule, eps: float = 1e-5, theta: float = 10000.0, caches=None):
@@ -621,9 +628,15 @@ class FullSchedulePlan:
         self.norms = torch.empty((n_vis,), dtype=torch.float32, device=h.device)
         self._out_index = torch.empty((n_vis,), dtype=torch.int32, device=h.device)
         self._T_final, self._n2 = C.c_int(0), C.c_int(0)
+        # record of every Stage III decision (one sample; sized for the counts before Stage II, cut in run)
+        self._keeps, self._T, self._n_vis = keeps, T, n_vis
+        self._stage_norms = [torch.empty((n_vis,), dtype=torch.float32, device=h.device) for _ in keeps]
+        self._stage_keep_idx = [torch.empty((T,), dtype=torch.int32, device=h.device) for _ in keeps]
+        self._sn = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self._stage_norms])
+        self._sk = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self._stage_keep_idx])
         S = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
                              self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self._y),
-                             _ptr(self._pos), self._kc, self._vc, cap)
+                             _ptr(self._pos), self._kc, self._vc, cap, self._sn, self._sk)
         self.desc = FullScheduleT(S, int(stage2["layer"]), int(stage2["budget"]), int(stage2["n_centers"]),
                                   float(stage2["d_c"]), float(stage2["tau"]), _ptr(stage2["xy"]),
                                   C.pointer(self._T_final), C.pointer(self._n2), _ptr(self.labels),
@@ -637,6 +650,14 @@ class FullSchedulePlan:
         _check(lib.vitcop_full_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
         self.T_final, self.n_stage2 = self._T_final.value, self._n2.value
         self.out_index = self._out_index[: self.n_stage2]
+        # stage s ranked the visual tokens present on entry and kept min(budget, present) of them
+        present, text = self.n_stage2, self._T - self._n_vis
+        self.stage_norms, self.stage_keep_idx = [], []
+        for s, budget in enumerate(self._keeps):
+            kept = min(budget, present)
+            self.stage_norms.append(self._stage_norms[s][:present])
+            self.stage_keep_idx.append(self._stage_keep_idx[s][: text + kept])
+            present = kept
         return self._y[:, : self.T_final], self._pos[:, : self.T_final]
 
 

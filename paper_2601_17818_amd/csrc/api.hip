@@ -194,7 +194,7 @@ int vitcop_prefill_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v,
     REQUIRE(Hq % Hkv == 0, VITCOP_EINVAL, "prefill_attn: Hq=%d not a multiple of Hkv=%d", Hq, Hkv);
     REQUIRE(causal == 0 || causal == 1, VITCOP_EINVAL, "prefill_attn: causal=%d", causal);
     REQUIRE(std::isfinite(scale) && scale >= 0.f, VITCOP_EINVAL, "prefill_attn: scale");
-    REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "prefill_attn: d=%d", d);
+    REQUIRE(d == 64 || d == 128, VITCOP_EUNSUPPORTED, "prefill_attn: d=%d (64 or 128)", d);
     REQUIRE(Hq <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "prefill_attn: Hq or B above 65535");
     REQUIRE(N <= (1 << 22), VITCOP_EUNSUPPORTED, "prefill_attn: N=%d above 2^22", N);
     if (B == 0 || N == 0) return VITCOP_OK;
@@ -824,6 +824,8 @@ static int run_decoder_layers(const vitcop_decoder_schedule_t* S, int l_begin, i
         const bool last = l + 1 == S->n_layers;
         const bool prune_here = r.stage < S->n_stages && S->prune_layer[r.stage] == l;
         if (prune_here) {
+            if (S->stage_norms) L.norms = S->stage_norms[r.stage];
+            if (S->stage_keep_idx) L.keep_idx = S->stage_keep_idx[r.stage];
             L.keep = std::min(S->prune_keep[r.stage++], r.cur_vis);
             L.positions_out = r.pbuf[r.pp];
         }
@@ -1033,7 +1035,7 @@ int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size
 static int check_decode(int B, int N, int Hq, int Hkv, int d) {
     REQUIRE(B >= 0 && N >= 1 && Hq >= 1 && Hkv >= 1, VITCOP_EINVAL, "decode_attn: B=%d N=%d Hq=%d Hkv=%d", B, N, Hq, Hkv);
     REQUIRE(Hq % Hkv == 0, VITCOP_EINVAL, "decode_attn: Hq=%d not a multiple of Hkv=%d", Hq, Hkv);
-    REQUIRE(d == 64 || d == 128, VITCOP_EINVAL, "decode_attn: d=%d", d);
+    REQUIRE(d == 64 || d == 128, VITCOP_EUNSUPPORTED, "decode_attn: d=%d (64 or 128)", d);
     REQUIRE(Hkv <= 65535 && B <= 65535, VITCOP_EUNSUPPORTED, "decode_attn: Hkv or B above 65535");
     REQUIRE((long)N * Hkv * d < (1L << 31), VITCOP_EUNSUPPORTED, "decode_attn: one sample's cache must stay below 2^31 elements");
     return VITCOP_OK;

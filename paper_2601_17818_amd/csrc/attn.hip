@@ -14,6 +14,7 @@
 //    O^T += V^T P^T — they never leave registers;
 //  * V is written to LDS transposed (channel-major) with the keys of each
 //    group of 32 permuted so that the 8 keys a lane needs are contiguous.
+#include <atomic>
 #include <type_traits>
 
 #include "vitcop_internal.h"
@@ -711,9 +712,9 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
         return launch_status("attn<64>");
     }
     if (N >= AW_MIN_N) {
-        static bool attr_set = false;
+        static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
         constexpr int lds = AW_STAGES * AW_STAGE;
-        if (!attr_set) {
+        if (!attr_set.load(std::memory_order_acquire)) {
             int rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<true>,
                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds),
                                 "hipFuncSetAttribute(attn_wide)");
@@ -722,7 +723,7 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, lds),
                             "hipFuncSetAttribute(attn_wide)");
             if (rc) return rc;
-            attr_set = true;
+            attr_set.store(true, std::memory_order_release);
         }
         const int n_qb = (N + AW_BM - 1) / AW_BM;
         const long n_heads = (long)Hq * B;

@@ -14,6 +14,7 @@
 //
 // Everything is integer work on the given labels and fp32 norms except the means, so the
 // result is deterministic; ties in the norm go to the lower index.
+#include <atomic>
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -171,14 +172,14 @@ int launch_collab(const uint16_t* feats, int64_t row_stride, int64_t batch_strid
         int rc = launch_status("collab_rank");
         if (rc) return rc;
     }
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         int rc = hip_status(hipFuncSetAttribute((const void*)collab_plan_kernel,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize,
                                                 2 * VITCOP_VIC_MAX_TOKENS * 4 + 16),
                             "hipFuncSetAttribute(collab_plan)");
         if (rc) return rc;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(collab_plan_kernel, dim3(B), dim3(CB_PLAN_THREADS), (size_t)2 * n * 4 + 16, s, labels, elite,
                        n_clusters, n, assign, out_index, n_out);

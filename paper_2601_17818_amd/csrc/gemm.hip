@@ -15,6 +15,7 @@
 // k-step; MFMA fragments of the next 16-wide slice are read while the current
 // slice is multiplied.  Workgroups are renumbered so that each XCD (own L2)
 // works on a compact patch of output tiles.
+#include <atomic>
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -374,13 +375,13 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
     if (w_stride == 0) w_stride = K;
     auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, EPI>;
     constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK>();
-    static bool attr_set = false;        // per kernel instantiation; setting it twice is harmless
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // per kernel instantiation; a second thread repeating the call is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         int rc = hip_status(hipFuncSetAttribute((const void*)kern,
                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds),
                             "hipFuncSetAttribute(gemm)");
         if (rc) return rc;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
     // tile rows per group: a patch of about 32 tiles (one XCD's worth of workgroups) near square

@@ -22,6 +22,7 @@
 //     outputs for the K-norm of Eq. 4; the same plus the RMSNorm of the finished row; or the gated
 //     activation silu(gate) * up of the MLP.  The same reductions serve the split-K launches of the
 //     big-tile kernel (gemm.hip), whose partials are whole slices.
+#include <atomic>
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -485,13 +486,13 @@ static int launch_skinny_cfg(const uint16_t* x, int64_t x_stride, const SkMats& 
                              const uint16_t* res, int64_t res_stride, hipStream_t s) {
     auto kern = gemm_skinny_kernel<MB>;
     constexpr size_t lds = (size_t)2 * (MB * 32 + SK_COLS) * 128;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         int rc = hip_status(hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                                 (int)lds),
                             "hipFuncSetAttribute(gemm_skinny)");
         if (rc) return rc;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(kern, dim3(wgs), dim3(SK_THREADS), lds, s, x, x_stride, mats, w_stride, M, N, K, units_q,
                        units_r, part, res, res_stride);

@@ -17,6 +17,7 @@
 // (tokens in decreasing density take their parent's label) is replaced by
 // pointer jumping, which reaches the same labels: a parent is strictly denser
 // than its child, so the parent chains have no cycles.
+#include <atomic>
 #include "vitcop_internal.h"
 #include "device_utils.h"
 #include "select_device.h"
@@ -209,14 +210,14 @@ int launch_vic(const uint16_t* feats, int64_t row_stride, int64_t batch_stride, 
     rc = launch_status("vic_parent");
     if (rc) return rc;
     const size_t lds = (size_t)3 * n * 4 + 16;
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
+    if (!attr_set.load(std::memory_order_acquire)) {
         rc = hip_status(hipFuncSetAttribute((const void*)vic_label_kernel,
                                             hipFuncAttributeMaxDynamicSharedMemorySize,
                                             3 * VITCOP_VIC_MAX_TOKENS * 4 + 16),
                         "hipFuncSetAttribute(vic_label)");
         if (rc) return rc;
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(vic_label_kernel, dim3(B), dim3(SEL_THREADS), lds, s, gamma, parent, n, n_centers, labels,
                        n_clusters, (int64_t)n);

@@ -27,12 +27,29 @@ def host_f64(t: torch.Tensor) -> np.ndarray:
     return t.cpu().numpy().astype(np.float64)
 
 
-def assert_attention_close(got_f64: np.ndarray, ref_f64: np.ndarray, what=""):
-    scale = max(1.0, float(np.abs(ref_f64).max()))
+def _assert_close(got_f64, ref_f64, max_abs, what):
     err = np.abs(got_f64 - ref_f64)
-    assert err.max() <= ATTN_MAX_ABS * scale, f"{what}: max-abs {err.max():.4g} (scale {scale:.3g})"
+    assert err.max() <= max_abs, f"{what}: max-abs {err.max():.4g} (bound {max_abs:.3g})"
     denom = max(float(np.abs(ref_f64).mean()), 1e-30)
     assert err.mean() / denom <= ATTN_MEAN_REL, f"{what}: mean-rel {err.mean() / denom:.4g}"
+
+
+def assert_attention_close(got_f64: np.ndarray, ref_f64: np.ndarray, what=""):
+    """Outputs of the attention entry points (prefill and decoding): the stated tolerance, 2e-2 max-abs
+    and 1e-2 mean-relative, unscaled while the reference stays below 8 in magnitude (every input drawn
+    as the workloads are, q, k, v ~ N(0,1), does).  From 8 on, one bf16 rounding of the output alone
+    exceeds 2e-2 (half an ulp in [8,16) is 0.031), so the max-abs bound doubles with each binade of the
+    reference maximum above [4,8): 4e-2 in [8,16), 8e-2 in [16,32)."""
+    m = float(np.abs(ref_f64).max())
+    binades = max(0.0, np.floor(np.log2(max(m, 1e-30))) - 2.0)
+    _assert_close(got_f64, ref_f64, ATTN_MAX_ABS * 2.0 ** binades, what)
+
+
+def assert_stream_close(got_f64: np.ndarray, ref_f64: np.ndarray, what=""):
+    """Projected and residual-stream outputs (a layer's y, a schedule's hidden state, cache rows): the
+    same bounds with the max-abs one scaled by max(1, |ref|_inf).  These tensors reach magnitudes of
+    20 and more, where one bf16 rounding of the output alone is 0.06, so an absolute 2e-2 cannot hold."""
+    _assert_close(got_f64, ref_f64, ATTN_MAX_ABS * max(1.0, float(np.abs(ref_f64).max())), what)
 
 
 def assert_selection_matches(gpu_idx: np.ndarray, gpu_scores: np.ndarray, ref_scores: np.ndarray,

@@ -12,7 +12,9 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 HEADER = os.path.join(ROOT, "include", "vitcop.h")
 
-binding = pytest.importorskip("paper_2601_17818_amd.binding")
+# a missing library is a failure here, not a skip: the boundary is what these tests are about
+from paper_2601_17818_amd import binding  # noqa: E402
+
 lib = binding.lib
 
 A16 = 0x1000   # a fake, 16-byte aligned, non-null "device pointer" (never dereferenced)
@@ -109,7 +111,7 @@ def test_attn_validation():
         return f(q, k, v, out, None, B, N, Hq, Hkv, d, scale, causal, None, 0, None)
 
     assert call(Hq=28, Hkv=5) == binding.VITCOP_EINVAL
-    assert call(d=96) == binding.VITCOP_EINVAL
+    assert call(d=96) == binding.VITCOP_EUNSUPPORTED
     assert call(d=64, N=0) == binding.VITCOP_OK                  # d = 64 passes validation
     assert call(causal=2) == binding.VITCOP_EINVAL
     assert call(scale=-1.0) == binding.VITCOP_EINVAL
@@ -274,7 +276,7 @@ def test_decoder_validation():
 
 def test_decoder_schedule_validation():
     # padding before the pointers and at the end
-    assert C.sizeof(binding.DecoderScheduleT) == 11 * 4 + 2 * 4 + 4 + 15 * 8 + 2 * 8 + 8
+    assert C.sizeof(binding.DecoderScheduleT) == 11 * 4 + 2 * 4 + 4 + 15 * 8 + 2 * 8 + 8 + 2 * 8    # + stage records
     ptrs = (C.c_void_p * 4)(*[A16] * 4)
 
     def desc(layers=(1, 3), keeps=(128, 32), **kw):
@@ -339,7 +341,7 @@ def test_decode_validation():
     assert call(ws_bytes=need - 1) == binding.VITCOP_EWORKSPACE
     assert call(N=0) == binding.VITCOP_EINVAL
     assert call(Hq=30) == binding.VITCOP_EINVAL
-    assert call(d=96) == binding.VITCOP_EINVAL
+    assert call(d=96) == binding.VITCOP_EUNSUPPORTED
     assert call(scale=-1.0) == binding.VITCOP_EINVAL
     assert call(k=None) == binding.VITCOP_EINVAL
     assert call(out=A16 + 4) == binding.VITCOP_EINVAL

@@ -33,7 +33,8 @@ def test_causal_sizes(vc, N):
     assert np.abs(lse - ref_lse).max() < 1e-3
 
 
-# the 256-query kernel takes over at N >= 320: block edges, ragged tails, several blocks
+# lengths around the point where the 256-query kernel takes over (N >= 512): block edges, ragged tails,
+# several blocks
 @pytest.mark.parametrize("N", [320, 321, 384, 500, 511, 512, 513, 640, 784, 1024, 1025, 1087, 1280, 1500, 2100])
 def test_causal_long(vc, N):
     t = I.qkv_tensors(150 + N, 1, N, 2, 2, 128)

@@ -8,7 +8,7 @@ import vitcop_inputs as I
 from oracle import decoder_oracle as Dc
 from oracle import vic_oracle as V
 from oracle import vitcop_oracle as O
-from gpu_util import assert_attention_close, assert_selection_matches, dev, host_bits, host_f64
+from gpu_util import assert_stream_close, assert_selection_matches, dev, host_bits, host_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -103,7 +103,7 @@ def test_decoder_layer_matches_oracle(vc, B, T, D, Hq, Hkv, d, F, vs, nv, keep):
     if not np.array_equal(idx, ref["keep_idx"]):
         ref = Dc.decoder_layer(c["h"], c["w"], Hq, Hkv, d, vs, nv, keep, pos, keep_idx=idx)
     assert np.array_equal(r["positions"].cpu().numpy(), np.take_along_axis(pos, idx.astype(np.int64), axis=1))
-    assert_attention_close(host_f64(r["y"]), ref["y"], "decoder layer output")
+    assert_stream_close(host_f64(r["y"]), ref["y"], "decoder layer output")
 
 
 def test_decoder_layer_deterministic_and_prefix(vc):
@@ -116,7 +116,7 @@ def test_decoder_layer_deterministic_and_prefix(vc):
     assert torch.equal(cut["y"], again["y"])
     # (equal up to the rounding order of the projections: few rows take the split-K path)
     a, b = host_f64(cut["y"][:, :40]), host_f64(full["y"][:, :40])
-    assert_attention_close(a, b, "rows before the visual span")
+    assert_stream_close(a, b, "rows before the visual span")
     assert np.mean(a == b) > 0.9
 
 
@@ -153,14 +153,19 @@ def test_decoder_schedule_matches_oracle(vc):
     plan = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, schedule)
     plan.run()
     torch.cuda.synchronize()
+    for s_, (l, k) in enumerate(schedule):        # every stage's record: the norms it ranked, the list it took
+        got_n, got_idx = plan.stage_norms[s_].cpu().numpy(), plan.stage_keep_idx[s_].cpu().numpy()
+        assert np.allclose(got_n, ref["norms"][l], rtol=2e-3)
+        assert_selection_matches(got_idx[0, vs:vs + k] - vs, got_n[0], ref["norms"][l][0], k, False, f"stage {s_}")
+        assert np.array_equal(got_idx, ref["keep_lists"][l])
     assert np.array_equal(plan.positions.cpu().numpy(), ref["positions"])
-    assert_attention_close(host_f64(plan.y), ref["y"], "decoder schedule output")
+    assert_stream_close(host_f64(plan.y), ref["y"], "decoder schedule output")
     # the unpruned schedule has no decisions
     plan0 = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, ())
     plan0.run()
     torch.cuda.synchronize()
     ref0 = Dc.decoder_schedule(h, layers, (), Hq, Hkv, d, vs, nv, pos)
-    assert_attention_close(host_f64(plan0.y), ref0["y"], "unpruned decoder schedule")
+    assert_stream_close(host_f64(plan0.y), ref0["y"], "unpruned decoder schedule")
     assert np.array_equal(plan0.positions.cpu().numpy(), pos)
 
 
@@ -183,7 +188,8 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
     # Alg. 1 end to end on one sample: decoder layers, Stage II (clustering + elites + merging) on entry
     # to one layer, Stage III (K-norm top-k) later.  The oracle is given the GPU's labels and norms (each
     # validated against the oracle's own below and in the Stage II tests), so its discrete steps decide
-    # on the same numbers; a Stage III keep list is read off the final positions.
+    # on the same numbers; the Stage III keep list and the norms it was taken from come out of the call
+    # and are checked against the rule on the oracle's norms before the oracle continues with that list.
     D, Hq, Hkv, d, F, vs, n, tail = 256, 4, 2, 128, 352, 12, 150, 10
     T = vs + n + tail
     h, layers, xy = full_case(9900, vs, n, tail, D, Hq, Hkv, d, F, 4, 16, 6)
@@ -208,16 +214,23 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
     if schedule:
         (l3, k3), = schedule
         k3 = min(k3, st["n_out"])
-        after2 = ref["positions"][0]                    # positions after Stage II (no Stage III in `ref`)
         assert plan.T_final == T - n + k3
-        lookup = {int(q): i for i, q in enumerate(after2)}                      # positions are unique
-        idx = np.array([lookup[int(q)] for q in got_pos[0]])
-        assert np.all(np.diff(idx) > 0) and np.array_equal(idx[:vs], np.arange(vs))
-        assert np.array_equal(idx[vs + k3:], np.arange(vs + st["n_out"], len(after2)))
+        # Stage III: the oracle's own decision on the sequence Stage II left, from its own K-norms of layer l3
+        free = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
+                                  k_norms=norms)
+        norms3 = plan.stage_norms[0].cpu().numpy()
+        idx = plan.stage_keep_idx[0].cpu().numpy()
+        want3 = free["stage3"][l3]
+        assert norms3.shape == want3["norms"][0].shape == (st["n_out"],)
+        assert np.allclose(norms3, want3["norms"][0], rtol=2e-3)
+        assert_selection_matches(idx[vs:vs + k3] - vs, norms3, want3["norms"][0], k3, False, "Stage III keep list")
+        assert np.array_equal(idx[:vs], np.arange(vs))
+        assert np.array_equal(idx[vs + k3:], np.arange(vs + st["n_out"], T - n + st["n_out"]))
+        # the list is the rule's outside the band of near-ties: the oracle goes on with it
         ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
                                  k_norms=norms, keep_lists={l3: idx[None]})
     assert np.array_equal(got_pos, ref["positions"])
-    assert_attention_close(host_f64(y), ref["y"], "full schedule output")
+    assert_stream_close(host_f64(y), ref["y"], "full schedule output")
 
 
 def test_full_schedule_caches_then_decode(vc):
@@ -241,16 +254,22 @@ def test_full_schedule_caches_then_decode(vc):
     labels, norms = plan.labels.cpu().numpy(), plan.norms.cpu().numpy()
     mid = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos, labels=labels, k_norms=norms)
     n2 = mid["stage2"]["n_out"]
-    lookup = {int(q): i for i, q in enumerate(mid["positions"][0])}
-    idx = np.array([lookup[int(q)] for q in p.cpu().numpy()[0]])
+    # Stage III list: checked against the rule on the oracle's own norms of that layer before the oracle uses it
+    free = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
+                              k_norms=norms)
+    norms3, idx = plan.stage_norms[0].cpu().numpy(), plan.stage_keep_idx[0].cpu().numpy()
+    assert np.allclose(norms3, free["stage3"][3]["norms"][0], rtol=2e-3)
+    assert_selection_matches(idx[vs:vs + 20] - vs, norms3, free["stage3"][3]["norms"][0], 20, False, "Stage III")
+    assert np.array_equal(idx[:vs], np.arange(vs)) and np.array_equal(idx[vs + 20:], np.arange(vs + n2, T - n + n2))
     ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
                              k_norms=norms, keep_lists={3: idx[None]})
+    assert np.array_equal(p.cpu().numpy(), ref["positions"])
     lengths = [T, T - n + n2, T - n + n2, T - n + 20]
     assert plan.T_final == lengths[-1] and plan.n_stage2 == n2
     for (kc, vcache), (k_ref, v_ref), L in zip(caches, ref["caches"], lengths):
         assert k_ref.shape[1] == L
-        assert_attention_close(host_f64(kc)[:, :L], O.bf16_to_f64(k_ref), "K cache after the full schedule")
-        assert_attention_close(host_f64(vcache)[:, :L], O.bf16_to_f64(v_ref), "V cache after the full schedule")
+        assert_stream_close(host_f64(kc)[:, :L], O.bf16_to_f64(k_ref), "K cache after the full schedule")
+        assert_stream_close(host_f64(vcache)[:, :L], O.bf16_to_f64(v_ref), "V cache after the full schedule")
         assert not host_bits(kc)[:, L:].any()
     # one decoding step from there: a new token at the next position
     h_new = I.decoder_inputs(9960, 1, 1, D, Hq, Hkv, d, F)["h"][:, 0]
@@ -259,4 +278,4 @@ def test_full_schedule_caches_then_decode(vc):
     y1 = step.run()
     torch.cuda.synchronize()
     ref1 = Dc.decode_step(h_new, layers, ref["caches"], new_pos, Hq, Hkv, d)
-    assert_attention_close(host_f64(y1), ref1["y"], "decoding step after the full schedule")
+    assert_stream_close(host_f64(y1), ref1["y"], "decoding step after the full schedule")

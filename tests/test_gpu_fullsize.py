@@ -21,10 +21,11 @@ def vc():
     return binding
 
 
-def test_config3_bench_layer_keep320(vc):
-    # the bench workload itself: B 4, T 2944, keep 320 of 2880 -> T' 384
+@pytest.mark.parametrize("keep", [720, 320, 160])
+def test_config3_bench_layer(vc, keep):
+    # the bench workload itself: B 4, T 2944, keep 720 / 320 / 160 of 2880 -> T' 784 / 384 / 224
     c = I.config3()
-    check_layer(vc, c, 320, False, "config 3 keep 320")
+    check_layer(vc, c, keep, False, f"config 3 keep {keep}")
 
 
 @pytest.mark.parametrize("B,N,Hq,Hkv,seed", [(4, 2944, 32, 32, 3001), (1, 6400, 28, 4, 4001)])
@@ -61,10 +62,45 @@ def test_config4_video_knorm_select_and_filter(vc):
     assert np.array_equal(kidx[0, c["keep"]:], np.arange(6272, 6400))
 
 
+def test_config4_video_layer_end_to_end(vc):
+    # the video workload as one chain: Stage I per frame (32 x 196 patches, keep 58) -> compaction of the frame
+    # features -> 1856 visual + 128 text tokens into a GQA 28/4 layer at D 3584 -> K-norm keep 627 -> attention
+    fr = I.config4_frames()
+    keep1 = fr["keep"]
+    scores, idx = vc.vitcop_filter_visual(dev(fr["q_cls"]), dev(fr["k"]), keep1)
+    S, S_idx = O.filter_visual(fr["q_cls"], fr["k"], keep1)
+    scores, idx = scores.cpu().numpy(), idx.cpu().numpy()
+    assert np.allclose(scores, S, rtol=2e-4, atol=1e-7)
+    for b in range(fr["B"]):
+        assert_selection_matches(idx[b], scores[b], S[b], keep1, True, f"frame {b}")
+    # the survivors' features, gathered on the GPU with the oracle's lists (bit-exact against the oracle's gather)
+    patches = np.ascontiguousarray(fr["feats"][:, 1:, :])
+    kept, = vc.vitcop_compact([dev(patches)], torch.from_numpy(S_idx.astype(np.int32)).cuda())
+    torch.cuda.synchronize()
+    want = O.compact(patches, S_idx)
+    got = kept.view(torch.int16).cpu().numpy().view(np.uint16)
+    assert np.array_equal(got, want)
+    n1 = fr["B"] * keep1
+    assert n1 == 1856
+    c = I.config4_layer(n_vis=n1, vis_feats=I.bf16_bits_to_f32(want).reshape(n1, fr["C"]))
+    assert (c["T"], c["D"], c["Hq"], c["Hkv"]) == (1984, 3584, 28, 4)
+    check_layer(vc, c, 627, False, "config 4: filter, then keep 627 of 1856")
+
+
+def test_config4_video_layer_no_filter(vc):
+    # the same layer on all 6272 visual tokens (no Stage I): keep 627 -> T' 755
+    c = I.config4_layer()
+    assert (c["T"], c["n_vis"], c["keep"]) == (6400, 6272, 627)
+    check_layer(vc, c, c["keep"], False, "config 4: keep 627 of 6272")
+
+
 def test_config2_schedule_prefix_full_width(vc):
     # first four layers of the config-2 schedule at full width (D 4096, 32 x 128), budgets
     # 576 -> 192 -> 128 -> 64 brought forward to layers 1, 2, 3; each layer teacher-forced on
-    # the oracle's input for that layer
+    # the oracle's input for that layer.  The cuts of this workload fall among near-ties (hundreds of
+    # log-normal norms around each cut), so every layer is compared through the separate entry points
+    # driven by the ORACLE's keep list, and the one-call layer against those entry points on its own
+    # list (check_layer): no comparison depends on the two lists being equal.
     h2 = I.config2_hidden()
     sched = ((1, 192), (2, 128), (3, 64))
     ws = [I.config2_layer_weights(l) for l in range(4)]
@@ -74,19 +110,8 @@ def test_config2_schedule_prefix_full_width(vc):
     budgets, cur_vis = dict(sched), 576
     for l, lay in enumerate(ref["layers"]):
         keep = budgets.get(l, cur_vis)
-        w = {n: dev(ws[l][n]) for n in ("wq", "wk", "wv", "wo")}
-        r = vc.vitcop_layer_prefill(dev(lay["x_in"]), w["wq"], w["wk"], w["wv"], w["wo"], 32, 32, 128, 35,
-                                    cur_vis, keep, residual=True)
-        torch.cuda.synchronize()
-        nxt = ref["layers"][l + 1]["x_in"] if l + 1 < 4 else ref["h"]
-        same = True
-        if lay["keep_idx"] is not None:
-            idx, nr = r["keep_idx"].cpu().numpy(), r["norms"].cpu().numpy()
-            assert_selection_matches(idx[0, 35:35 + keep] - 35, nr[0], lay["norms"][0], keep, False, f"layer {l}")
-            vis = idx[0, 35:35 + keep] - 35
-            # surviving rows carry small gains: none of the planted 4x outliers of the input survive layer 1
-            same = np.array_equal(idx, lay["keep_idx"])
-        if same:
-            assert_attention_close(host_f64(r["y"]), O.bf16_to_f64(nxt), f"schedule layer {l}")
+        c = {"B": 1, "T": lay["x_in"].shape[1], "D": 4096, "Hq": 32, "Hkv": 32, "d": 128, "vis_start": 35,
+             "n_vis": cur_vis, "x": lay["x_in"], **{n: ws[l][n] for n in ("wq", "wk", "wv", "wo")}}
+        check_layer(vc, c, keep, True, f"config 2 layer {l}")
         cur_vis = keep
     assert ref["h"].shape == (1, 128, 4096)

@@ -5,7 +5,7 @@ import torch
 
 import vitcop_inputs as I
 from oracle import vitcop_oracle as O
-from gpu_util import assert_attention_close, assert_selection_matches, dev, host_bits, host_f64
+from gpu_util import assert_attention_close, assert_stream_close, assert_selection_matches, dev, host_bits, host_f64
 
 pytestmark = pytest.mark.gpu
 
@@ -219,13 +219,13 @@ def check_layer(vc, c, keep, residual, what):
     st = staged_layer(vc, c, ref["keep_idx"], residual)
     assert_bf16_of(host_bits(st["k"]).reshape(ref["k"].shape), O.project(c["x"], c["wk"]).reshape(ref["k"].shape), what)
     assert_attention_close(host_f64(st["o"]).reshape(ref["attn"].shape), ref["attn"], what + " attn")
-    assert_attention_close(host_f64(st["y"]), ref["y"], what + " staged y")
+    assert_stream_close(host_f64(st["y"]), ref["y"], what + " staged y")
     # the one-call layer is the composition of those entry points on its own keep list
     st_own = st if np.array_equal(idx, ref["keep_idx"]) else staged_layer(vc, c, idx, residual)
     # (the one-call layer may sum a projection's k-range in other pieces than the separate call does: few
     # rows go through split-K whose cut depends on the launch; both are fp32 sums rounded once to bf16)
     fused, staged = host_f64(r["y"]), host_f64(st_own["y"])
-    assert_attention_close(fused, staged, what + ": fused call against the staged calls")
+    assert_stream_close(fused, staged, what + ": fused call against the staged calls")
     assert np.mean(fused == staged) > 0.9, what + ": fused call differs from the staged calls in many places"
     return np.array_equal(idx, ref["keep_idx"])
 
@@ -257,23 +257,34 @@ def test_config0_layer(vc):
     check_layer(vc, c, 64, False, "config 0")
     r = run_layer(vc, c, 576)
     u = O.unpruned_layer(c["x"], c["wq"], c["wk"], c["wv"], c["wo"], 32, 32, 128)
-    assert_attention_close(host_f64(r["y"]), u["y"], "config 0 unpruned")
+    assert_stream_close(host_f64(r["y"]), u["y"], "config 0 unpruned")
     assert np.array_equal(r["keep_idx"].cpu().numpy(), np.arange(640)[None])
+
+
+def schedule_small_case(seed, B, T, D, Hq, Hkv, d, vs, nv, n_layers):
+    cfg = I.layer_inputs(seed, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.02)
+    gain, _ = I.lognormal_gains(seed, B, nv)
+    xf = I.bf16_bits_to_f32(cfg["x"]).copy()
+    xf[:, vs:vs + nv] *= gain[:, :, None]
+    ws = [I.layer_inputs(5000 + seed + l, 1, 1, D, Hq, Hkv, d, 0, 0, w_std=0.02) for l in range(n_layers)]
+    for w in ws:
+        w["wo"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w["wo"]) * np.float32(0.125))
+    return I.f32_to_bf16_bits(xf), ws
 
 
 def test_schedule_small(vc):
     B, T, D, Hq, Hkv, d, vs, nv = 1, 180, 256, 4, 2, 128, 10, 150
     sched = ((1, 90), (3, 40), (4, 12))
     n_layers = 6
-    cfg = I.layer_inputs(1234, B, T, D, Hq, Hkv, d, vs, nv, w_std=0.02)
-    gain, _ = I.lognormal_gains(1234, B, nv)
-    xf = I.bf16_bits_to_f32(cfg["x"]).copy()
-    xf[:, vs:vs + nv] *= gain[:, :, None]
-    x = I.f32_to_bf16_bits(xf)
-    ws = [I.layer_inputs(5000 + l, 1, 1, D, Hq, Hkv, d, 0, 0, w_std=0.02) for l in range(n_layers)]
-    for w in ws:
-        w["wo"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w["wo"]) * np.float32(0.125))
-    ref = O.schedule_prefill(x, lambda l: ws[l], n_layers, sched, Hq, Hkv, d, vs, nv)
+    # seeds are searched, on the oracle alone, for a run whose three cuts have no near-tie: both sides
+    # must then take the same decisions, and every comparison below is unconditional
+    for seed in range(1234, 1234 + 400):
+        x, ws = schedule_small_case(seed, B, T, D, Hq, Hkv, d, vs, nv, n_layers)
+        ref = O.schedule_prefill(x, lambda l: ws[l], n_layers, sched, Hq, Hkv, d, vs, nv)
+        if all(O.tie_band(ref["layers"][l]["norms"][0], k, False, 4e-3).sum() <= 1 for l, k in sched):
+            break
+    else:
+        raise AssertionError("no seed with gap-free cuts")
     dws = [{n: dev(w[n]) for n in ("wq", "wk", "wv", "wo")} for w in ws]
 
     # (1) teacher-forced: every layer run on the oracle's input for that layer
@@ -291,21 +302,14 @@ def test_schedule_small(vc):
             for b in range(B):
                 assert_selection_matches(idx[b, vs:vs + keep] - vs, nr[b], lay["norms"][b], keep, False,
                                          f"layer {l}")
-            if not np.array_equal(idx, lay["keep_idx"]):
-                cur_vis = keep
-                continue            # a near-tie at the cut: outputs are for a different, equally valid set
-        assert_attention_close(host_f64(r["y"]), O.bf16_to_f64(nxt), f"schedule layer {l}")
+            assert np.array_equal(idx, lay["keep_idx"]), f"layer {l}: gap-free cut, the lists must agree"
+        assert_stream_close(host_f64(r["y"]), O.bf16_to_f64(nxt), f"schedule layer {l}")
         cur_vis = keep
 
     # (2) free-running schedule through the one C call
     y, pos = vc.vitcop_schedule_prefill(dev(x), dws, Hq, Hkv, d, vs, nv, sched)
     torch.cuda.synchronize()
     pos = pos.cpu().numpy()
-    assert y.shape == (B, T - nv + 12, D) and np.all(np.diff(pos, axis=1) > 0)
-    assert np.array_equal(pos[:, :vs], np.arange(vs)[None]) and np.array_equal(pos[:, vs + 12:], np.arange(vs + nv, T)[None])
-    if np.array_equal(pos, ref["positions"]):
-        assert_attention_close(host_f64(y), O.bf16_to_f64(ref["h"]), "schedule end to end")
-    else:
-        # survivors may differ only by near-ties; most must agree
-        common = len(set(pos[0].tolist()) & set(ref["positions"][0].tolist()))
-        assert common >= pos.shape[1] - 3
+    assert y.shape == (B, T - nv + 12, D)
+    assert np.array_equal(pos, ref["positions"]), "free-running schedule: survivors differ from the oracle's"
+    assert_stream_close(host_f64(y), O.bf16_to_f64(ref["h"]), "schedule end to end")

@@ -204,4 +204,54 @@ def test_decode_step_is_the_last_row_of_the_prefill():
     pr = Dc.decoder_schedule(h[:, :T - 1], layers, ((1, 6),), Hq, Hkv, d, 4, 20, pos[:, :T - 1])
     assert [c[0].shape[1] for c in pr["caches"]] == [29, 15, 15]
     st = Dc.decode_step(h[:, T - 1], layers, pr["caches"], pos[:, T - 1], Hq, Hkv, d)
-    assert st["y"].shape == (1, D) and np.all(np.isfinite(st["y"]))
+    # ... and is again the last row of the same pruned prefill run over all T tokens: the K-norms of the
+    # visual tokens do not depend on the text token after them, so both runs prune the same tokens
+    full_pr = Dc.decoder_schedule(h, layers, ((1, 6),), Hq, Hkv, d, 4, 20, pos)
+    assert np.array_equal(full_pr["keep_lists"][1][0, :-1], pr["keep_lists"][1][0])
+    assert np.allclose(st["y"][0], full_pr["y"][0, -1], rtol=1e-9, atol=1e-11)
+    assert np.array_equal(st["y_bits"][0], full_pr["y_bits"][0, -1])
+    for l in range(3):
+        assert np.array_equal(st["appended"][l][0][0], full_pr["caches"][l][0][0, -1])
+        assert np.array_equal(st["appended"][l][1][0], full_pr["caches"][l][1][0, -1])
+
+
+def test_decoder_schedule_with_pruning_is_a_chain_of_pruned_layers():
+    # 5 layers, pruning on entry to layers 1 (20 -> 12 visual tokens) and 3 (12 -> 5).  Rebuilt by hand from
+    # single layers: each stage ranks only the tokens still present, by the K-norms of ITS layer's input;
+    # positions compose; the layers in between keep everything.  The keep lists themselves are re-derived
+    # by a sort on norms recomputed from the layer input (RMSNorm, K projection, Eq. 4).
+    T, vs, n, D, Hq, Hkv, d, F = 34, 6, 20, 128, 4, 2, 64, 96
+    h, layers = small_model(330, 5, T, D, Hq, Hkv, d, F)
+    pos = (3 * np.arange(T) + 2)[None]
+    got = Dc.decoder_schedule(h, layers, ((1, 12), (3, 5)), Hq, Hkv, d, vs, n, pos)
+
+    def own_list(h_in, w, n_now, keep):
+        a = O.f64_to_bf16_bits(Dc.rmsnorm(h_in, w["ln1"], 1e-5))
+        k = O.f64_to_bf16_bits(O.project(a, w["wk"]))[0, vs:vs + n_now]
+        nrm = np.sqrt((f64(k) ** 2).sum(axis=1))
+        kept = np.sort(np.lexsort((np.arange(n_now), nrm))[:keep])
+        t_now = h_in.shape[1]
+        return nrm, np.concatenate([np.arange(vs), vs + kept, np.arange(vs + n_now, t_now)])[None]
+
+    cur, p_cur, n_now, caches = h, pos, n, []
+    for l, w in enumerate(layers):
+        keep = {1: 12, 3: 5}.get(l, n_now)
+        nrm, idx = own_list(cur, w, n_now, keep)
+        out = Dc.decoder_layer(cur, w, Hq, Hkv, d, vs, n_now, keep, p_cur, keep_idx=idx)
+        if l in (1, 3):
+            assert np.allclose(got["norms"][l][0], nrm, rtol=1e-12) and got["norms"][l].shape == (1, n_now)
+            assert np.array_equal(got["keep_lists"][l], idx)
+            p_cur = np.take_along_axis(p_cur, idx, axis=1)
+        caches.append((out["k_rope"], out["v"]))
+        cur, n_now = out["y_bits"], keep
+    assert np.array_equal(got["y_bits"], cur) and np.array_equal(got["positions"], p_cur)
+    assert [c[0].shape[1] for c in got["caches"]] == [34, 26, 26, 19, 19]
+    for (k1, v1), (k2, v2) in zip(got["caches"], caches):
+        assert np.array_equal(k1, k2) and np.array_equal(v1, v2)
+    # positions compose: the second list indexes the sequence the first one left
+    i1, i3 = got["keep_lists"][1][0], got["keep_lists"][3][0]
+    assert np.array_equal(got["positions"][0], pos[0][i1][i3])
+    assert set(i1[i3][vs:vs + 5]) <= set(i1[vs:vs + 12]) and len(i3) == 19
+    # text tokens always survive, with their positions
+    assert np.array_equal(got["positions"][0, :vs], pos[0, :vs])
+    assert np.array_equal(got["positions"][0, vs + 5:], pos[0, vs + n:])
