@@ -5,7 +5,8 @@ import torch
 
 import vitcop_inputs as I
 from oracle import vitcop_oracle as O
-from gpu_util import assert_attention_close, assert_stream_close, assert_selection_matches, dev, host_bits, host_f64
+from gpu_util import (assert_attention_close, assert_stream_close, assert_selection_matches, dev, host_bits,
+                      host_f64, v_scale_of)
 
 pytestmark = pytest.mark.gpu
 
@@ -218,7 +219,8 @@ def check_layer(vc, c, keep, residual, what):
     # the separate entry points, driven by the ORACLE's keep list, reproduce the oracle's layer
     st = staged_layer(vc, c, ref["keep_idx"], residual)
     assert_bf16_of(host_bits(st["k"]).reshape(ref["k"].shape), O.project(c["x"], c["wk"]).reshape(ref["k"].shape), what)
-    assert_attention_close(host_f64(st["o"]).reshape(ref["attn"].shape), ref["attn"], what + " attn")
+    assert_attention_close(host_f64(st["o"]).reshape(ref["attn"].shape), ref["attn"], what + " attn",
+                           v_scale=v_scale_of(ref["v"]), peaked=True)
     assert_stream_close(host_f64(st["y"]), ref["y"], what + " staged y")
     # the one-call layer is the composition of those entry points on its own keep list
     st_own = st if np.array_equal(idx, ref["keep_idx"]) else staged_layer(vc, c, idx, residual)
