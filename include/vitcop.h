@@ -69,6 +69,21 @@ int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k,
                          float* scores_out, int32_t* idx_out,
                          void* ws, size_t ws_bytes, void* stream);
 
+/* The same call for callers that cannot allocate device memory or hand over a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): arguments, outputs and kernels are
+ * those of vitcop_filter_visual, and the logits live in a scratch array inside the library's own device
+ * image, VITCOP_FILTER_STATIC_MAX_BYTES per GPU, held until the process ends.  The call allocates nothing.
+ * Limit: B * H * (N+1) * 4 bytes must fit the array, else VITCOP_EUNSUPPORTED (use vitcop_filter_visual).
+ * Every call on a GPU shares that GPU's array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls on one stream are ordered and safe.  Nothing in it needs clearing: each call
+ * writes every entry it later reads.  Other errors as vitcop_filter_visual, plus VITCOP_EHIP if the array's
+ * device address cannot be obtained.
+ */
+#define VITCOP_FILTER_STATIC_MAX_BYTES (4u << 20)
+int vitcop_filter_visual_static(const uint16_t* q_cls, const uint16_t* k,
+                                int B, int N, int H, int d, int keep, float scale,
+                                float* scores_out, int32_t* idx_out, void* stream);
+
 /* ------------------------------------------------------------------------
  * K-norm saliency and selection (Sec. 3.2.2, Eq. 4; Alg. 1 Stage III; "a
  * smaller norm corresponds to higher importance", Sec. 2.2).

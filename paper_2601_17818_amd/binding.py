@@ -41,6 +41,7 @@ EXPORTS = (
     "vitcop_decoder_schedule_workspace_bytes", "vitcop_decoder_schedule_prefill",
     "vitcop_full_schedule_workspace_bytes", "vitcop_full_schedule_prefill",
     "vitcop_decoder_decode_workspace_bytes", "vitcop_decoder_decode_step",
+    "vitcop_filter_visual_static",
 )
 
 
@@ -131,6 +132,8 @@ def _load() -> C.CDLL:
     lib.vitcop_filter_visual_workspace_bytes.argtypes = [i32] * 4
     lib.vitcop_filter_visual.restype = i32
     lib.vitcop_filter_visual.argtypes = [vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp, sz, vp]
+    lib.vitcop_filter_visual_static.restype = i32
+    lib.vitcop_filter_visual_static.argtypes = [vp, vp, i32, i32, i32, i32, i32, f32, vp, vp, vp]
     lib.vitcop_knorm_select_workspace_bytes.restype = sz
     lib.vitcop_knorm_select_workspace_bytes.argtypes = [i32, i32]
     lib.vitcop_knorm_select.restype = i32
@@ -251,6 +254,19 @@ def vitcop_filter_visual(q_cls, k, keep: int, scale: float = 0.0, want_scores: b
     _check(lib.vitcop_filter_visual(_ptr(q_cls), _ptr(k), B, N, H, d, keep, scale, _ptr(scores),
                                     _ptr(idx), _ptr(ws), ws.numel(), _stream()))
     return (scores, idx, ws) if out is not None else (scores, idx)
+
+
+VITCOP_FILTER_STATIC_MAX_BYTES = 4 << 20
+
+
+def vitcop_filter_visual_static(q_cls, k, keep: int, scores, idx, scale: float = 0.0) -> None:
+    """vitcop_filter_visual without any allocation: ``scores`` [B,N] fp32 (or None) and ``idx`` [B,keep] int32
+    are the caller's tensors, the logits go to the library's built-in scratch (B*H*(N+1)*4 bytes at most
+    VITCOP_FILTER_STATIC_MAX_BYTES)."""
+    _dense(q_cls, "q_cls"); _dense(k, "k")
+    B, N1, H, d = k.shape
+    _check(lib.vitcop_filter_visual_static(_ptr(q_cls), _ptr(k), B, N1 - 1, H, d, keep, scale, _ptr(scores),
+                                           _ptr(idx), _stream()))
 
 
 def vitcop_knorm_select(k, vis_start: int, n_vis: int, keep: int, *, norms=None, flags: int = 0,

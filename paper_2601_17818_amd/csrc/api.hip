@@ -64,9 +64,9 @@ size_t vitcop_filter_visual_workspace_bytes(int B, int N, int H, int d) {
     return up256((size_t)B * H * ((size_t)N + 1) * sizeof(float));
 }
 
-int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
-                         int keep, float scale, float* scores_out, int32_t* idx_out, void* ws,
-                         size_t ws_bytes, void* stream) {
+// Everything vitcop_filter_visual checks apart from the workspace.
+static int check_filter(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d, int keep,
+                        float scale, const int32_t* idx_out) {
     REQUIRE(B >= 0 && N >= 1 && H >= 1, VITCOP_EINVAL, "filter_visual: B=%d N=%d H=%d", B, N, H);
     REQUIRE(keep >= 0 && keep <= N, VITCOP_EINVAL, "filter_visual: keep=%d outside [0,%d]", keep, N);
     REQUIRE(d == 64 || d == 128, VITCOP_EUNSUPPORTED, "filter_visual: d=%d (64 or 128)", d);
@@ -78,11 +78,35 @@ int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k, int B, int N,
     if (B == 0) return VITCOP_OK;
     REQUIRE(q_cls && k && (idx_out || keep == 0), VITCOP_EINVAL, "filter_visual: null pointer");
     REQUIRE(aligned16(q_cls) && aligned16(k), VITCOP_EINVAL, "filter_visual: q_cls/k not 16-byte aligned");
+    return VITCOP_OK;
+}
+
+int vitcop_filter_visual(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
+                         int keep, float scale, float* scores_out, int32_t* idx_out, void* ws,
+                         size_t ws_bytes, void* stream) {
+    int rc = check_filter(q_cls, k, B, N, H, d, keep, scale, idx_out);
+    if (rc || B == 0) return rc;
     REQUIRE(ws && ws_bytes >= vitcop_filter_visual_workspace_bytes(B, N, H, d), VITCOP_EWORKSPACE,
             "filter_visual: workspace needs %zu bytes", vitcop_filter_visual_workspace_bytes(B, N, H, d));
     if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
     return launch_filter(q_cls, k, B, N, H, d, keep, scale, scores_out, idx_out,
                          static_cast<float*>(ws), static_cast<hipStream_t>(stream));
+}
+
+int vitcop_filter_visual_static(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
+                                int keep, float scale, float* scores_out, int32_t* idx_out, void* stream) {
+    int rc = check_filter(q_cls, k, B, N, H, d, keep, scale, idx_out);
+    if (rc || B == 0) return rc;
+    const size_t need = (size_t)B * H * ((size_t)N + 1) * sizeof(float);
+    REQUIRE(need <= VITCOP_FILTER_STATIC_MAX_BYTES, VITCOP_EUNSUPPORTED,
+            "filter_visual_static: B*H*(N+1)*4 = %zu bytes of logits exceed the built-in scratch of %u bytes "
+            "(use vitcop_filter_visual with a workspace)", need, (unsigned)VITCOP_FILTER_STATIC_MAX_BYTES);
+    float* logits = nullptr;
+    rc = filter_static_scratch(&logits);       // no allocation: the address of the library's own array
+    if (rc) return rc;
+    if (scale == 0.f) scale = 1.0f / std::sqrt((float)d);
+    return launch_filter(q_cls, k, B, N, H, d, keep, scale, scores_out, idx_out, logits,
+                         static_cast<hipStream_t>(stream));
 }
 
 /* --------------------------------------------------------- knorm + select */

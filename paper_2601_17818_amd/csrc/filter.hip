@@ -10,6 +10,8 @@
 //                          normaliser, head-summed softmax weight per patch,
 //                          then the same radix selection as the K-norm path
 //                          on complemented keys (largest first).
+#include <mutex>
+
 #include "vitcop_internal.h"
 #include "device_utils.h"
 #include "select_device.h"
@@ -171,6 +173,34 @@ int launch_filter(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H,
     hipLaunchKernelGGL(filter_finalize_kernel, dim3(B), dim3(SEL_THREADS), smem, s, logits_ws, N,
                        H, keep, scores_out, idx_out);
     return launch_status("filter_finalize");
+}
+
+// ---- scratch for callers that cannot allocate ---------------------------------
+// The logits of one call, in device memory that belongs to the library's code object: every GPU the
+// library runs on holds its own copy of this array, at its own address, until the process ends.
+static __device__ __align__(256) unsigned char scratch[FILTER_STATIC_SCRATCH_BYTES];
+
+constexpr int FILTER_MAX_DEVICES = 64;
+static std::mutex scratch_mutex;
+static void* scratch_ptr[FILTER_MAX_DEVICES];      // device address of `scratch` on each device, once looked up
+
+// The address of the current device's copy of `scratch` (looked up once per device, with that device
+// current; the array's name itself is only a host-side handle and must never reach a kernel).
+int filter_static_scratch(float** out) {
+    int dev = -1;
+    int rc = hip_status(hipGetDevice(&dev), "hipGetDevice");
+    if (rc) return rc;
+    if (dev < 0 || dev >= FILTER_MAX_DEVICES) return fail(VITCOP_EUNSUPPORTED, "filter_visual_static: device %d", dev);
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (!scratch_ptr[dev]) {
+        void* p = nullptr;
+        rc = hip_status(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)), "hipGetSymbolAddress(scratch)");
+        if (rc) return rc;
+        if (!p) return fail(VITCOP_EHIP, "filter_visual_static: no address for the scratch array");
+        scratch_ptr[dev] = p;
+    }
+    *out = static_cast<float*>(scratch_ptr[dev]);
+    return VITCOP_OK;
 }
 
 }  // namespace vitcop

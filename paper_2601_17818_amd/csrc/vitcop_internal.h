@@ -38,6 +38,9 @@ int launch_compact(const vitcop_gather_t* t, int n, const int32_t* idx, int B, i
 int launch_filter(const uint16_t* q_cls, const uint16_t* k, int B, int N, int H, int d,
                   int keep, float scale, float* scores_out, int32_t* idx_out,
                   float* logits_ws, hipStream_t s);
+// Device address of the library-owned scratch array of FILTER_STATIC_SCRATCH_BYTES on the current device.
+constexpr size_t FILTER_STATIC_SCRATCH_BYTES = VITCOP_FILTER_STATIC_MAX_BYTES;
+int filter_static_scratch(float** out);
 
 // ---- attention (attn.hip) -------------------------------------------------
 int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,

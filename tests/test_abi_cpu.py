@@ -64,6 +64,22 @@ def test_filter_validation():
     assert f(None, None, 0, 10, 2, 64, 5, 0.0, None, None, None, 0, None) == binding.VITCOP_OK
 
 
+def test_filter_static_validation():
+    # the variant without workspace: the same argument checks, then the size limit of its built-in scratch,
+    # all before any HIP call
+    f = lib.vitcop_filter_visual_static
+    assert f(A16, A16, 1, 10, 2, 64, 11, 0.0, None, A16, None) == binding.VITCOP_EINVAL
+    assert f(A16, A16, 1, 10, 2, 32, 5, 0.0, None, A16, None) == binding.VITCOP_EUNSUPPORTED
+    assert f(None, A16, 1, 10, 2, 64, 5, 0.0, None, A16, None) == binding.VITCOP_EINVAL
+    assert f(None, None, 0, 10, 2, 64, 5, 0.0, None, None, None) == binding.VITCOP_OK
+    text = open(HEADER).read()
+    limit = re.search(r"#define\s+VITCOP_FILTER_STATIC_MAX_BYTES\s+\((\d+)u\s*<<\s*(\d+)\)", text)
+    assert int(limit.group(1)) << int(limit.group(2)) == binding.VITCOP_FILTER_STATIC_MAX_BYTES == 4 << 20
+    # 64 x 16 x 1025 x 4 bytes of logits do not fit, 64 x 16 x 1024 x 4 would (rejected here for N > limit instead)
+    assert f(A16, A16, 64, 1024, 16, 64, 5, 0.0, None, A16, None) == binding.VITCOP_EUNSUPPORTED
+    assert "scratch" in binding.vitcop_last_error()
+
+
 def test_knorm_select_validation():
     f = lib.vitcop_knorm_select
 
