@@ -96,7 +96,9 @@ def main():
         5 * B, tiles["N"], tiles["H"], tiles["d"]), dtype=torch.uint8, device="cuda"))
     f_cmp = vc.vitcop_compact([f_feat], f_bufs[1])
 
-    plans = {k: vc.LayerPlan(x, wq, wk, wv, wo, Hq, Hkv, d, vs, nv, k, want_norms=False)
+    # original position ids of the tokens: gathered with the hidden states and K (the survivors keep them)
+    pos3 = torch.arange(T, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+    plans = {k: vc.LayerPlan(x, wq, wk, wv, wo, Hq, Hkv, d, vs, nv, k, want_norms=False, positions=pos3)
              for k in sorted(set(c3["keeps"]) | {args.keep, nv})}
     plan = plans[args.keep]
     Tp = T - nv + args.keep
@@ -147,6 +149,23 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["algorithmic_flops_per_launch"] = kproj_flops
     roofline["algorithmic_bytes_per_launch"] = 2.0 * (B * T * D + kd * D + B * T * kd)
+    # measured ceilings beside the vendor peaks: the SAME kernel and launch on all-zero operands (what the
+    # matrix cores sustain when the data toggles no bits: the clock the chip holds under this kernel is
+    # power-limited and depends on the operands), and a plain 1 GiB device-to-device copy for HBM
+    xz, wz = torch.zeros_like(x).reshape(B * T, D), torch.zeros_like(wk)
+    zbuf = vc.vitcop_project(xz, wz, want_sumsq=True)
+    t_kproj_zero = ev_time(lambda: vc.vitcop_project(xz, wz, want_sumsq=True, out=zbuf), reps)
+    del xz, wz, zbuf
+    csrc_ = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    cdst_ = torch.empty_like(csrc_)
+    t_copy = ev_time(lambda: cdst_.copy_(csrc_), 10)
+    del csrc_, cdst_
+    roofline["peak_measured"] = {
+        "mfma_TFLOPs_same_kernel_zero_operands": kproj_flops / (t_kproj_zero * 1e-3) / 1e12,
+        "kproj_gemm_zero_operands_ms": t_kproj_zero,
+        "kproj_gemm_random_operands_back_to_back_ms": t_kproj_alone,
+        "hbm_copy_GBps": 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9,
+    }
     if args.traffic is not None:
         roofline["traffic"] = args.traffic
     if args.calib_copy:
@@ -281,7 +300,7 @@ def main():
               "wg": torch.randn((Fm, D), dtype=torch.bfloat16, device="cuda") * 0.02,
               "wu": torch.randn((Fm, D), dtype=torch.bfloat16, device="cuda") * 0.02,
               "wd": torch.randn((D, Fm), dtype=torch.bfloat16, device="cuda") * 0.02}
-        dpos = torch.arange(T, dtype=torch.int32, device="cuda").repeat(B, 1).contiguous()
+        dpos = pos3
         dec_ms = {}
         for k_ in sorted(set(c3["keeps"]) | {args.keep, nv}):
             dp = vc.DecoderLayerPlan(x, dpos, dw, Hq, Hkv, d, vs, nv, k_)
@@ -299,6 +318,87 @@ def main():
         out["speedup_vs_unpruned"] = {f"keep{k_}": layer_ms[nv] / v_ for k_, v_ in layer_ms.items() if k_ != nv}
         out["layer_tokens_per_s"] = {("unpruned" if k_ == nv else f"keep{k_}"): B * T / (v_ * 1e-3)
                                      for k_, v_ in layer_ms.items()}
+        # ---- the other workload configs at their own shapes: single-call latency (L) ----
+        def layer_line(c, keeps, what):
+            xs_ = dev(c["x"])
+            ws_ = [dev(c[n]) for n in ("wq", "wk", "wv", "wo")]
+            ps_ = torch.arange(c["T"], dtype=torch.int32, device="cuda").repeat(c["B"], 1).contiguous()
+            ms = {}
+            for k_ in keeps:
+                pl_ = vc.LayerPlan(xs_, *ws_, c["Hq"], c["Hkv"], c["d"], c["vis_start"], c["n_vis"], k_,
+                                   want_norms=False, positions=ps_)
+                ms["unpruned" if k_ == c["n_vis"] else f"keep{k_}"] = ev_time(pl_.run, 20, warm=5)
+                del pl_
+            return {"workload": what, "layer_ms": ms,
+                    "speedup_vs_unpruned": {k_: ms["unpruned"] / v_ for k_, v_ in ms.items() if k_ != "unpruned"},
+                    "tokens_per_s": {k_: c["B"] * c["T"] / (v_ * 1e-3) for k_, v_ in ms.items()}}
+
+        # config 0: one LLaVA-1.5-shaped sample, 640 tokens, keep 64 of 576 (launch-latency bound)
+        c0 = I.config0()
+        cfg0 = layer_line(c0, (64, 576), "config0: B=1, T=640 (35 + 576 + 29), keep 64 of 576, D=4096, 32x128 MHA")
+        # compaction alone at that shape: hidden states, K and positions of the 128 survivors
+        x0 = dev(c0["x"])
+        k0 = torch.randn((1, 640, 32, 128), dtype=torch.bfloat16, device="cuda")
+        p0 = torch.arange(640, dtype=torch.int32, device="cuda")[None].contiguous()
+        i0 = torch.cat([torch.arange(35), 35 + torch.arange(64) * 9, torch.arange(611, 640)]).to(torch.int32).cuda()[None]
+        o0 = vc.vitcop_compact([x0, k0, p0], i0)
+        t_c0 = ev_time(lambda: vc.vitcop_compact([x0, k0, p0], i0, outs_in=o0), 50, warm=10)
+        cfg0["compact_us"] = t_c0 * 1e3
+        cfg0["compact_GBps"] = 128 * (2 * (8192 + 8192 + 4) + 4) / (t_c0 * 1e-3) / 1e9
+        nb0 = torch.empty((1, 576), dtype=torch.float32, device="cuda")
+        ib0 = torch.empty((1, 128), dtype=torch.int32, device="cuda")
+        t_k0 = ev_time(lambda: vc.vitcop_knorm_select(k0, 35, 576, 64, norms=nb0, idx_out=ib0), 50, warm=10)
+        cfg0["knorm_select_us"] = t_k0 * 1e3
+        cfg0["knorm_select_GBps"] = (576 * (8192 + 4) + 128 * 4) / (t_k0 * 1e-3) / 1e9
+        del x0, k0, p0, o0
+        out["config0"] = cfg0
+        # config 1 at its own batch: 8 images x 577 tokens, keep 288 of 576
+        c1 = I.config1()
+        q1, k1 = dev(c1["q_cls"]), dev(c1["k"])
+        b1 = vc.vitcop_filter_visual(q1, k1, c1["keep"])
+        b1 = (b1[0], b1[1], torch.empty(vc.lib.vitcop_filter_visual_workspace_bytes(8, 576, 16, 64),
+                                       dtype=torch.uint8, device="cuda"))
+        t_f1 = ev_time(lambda: vc.vitcop_filter_visual(q1, k1, c1["keep"], out=b1), 50, warm=10)
+        out["config1"] = {"workload": "config1: 8 images x 577 tokens x 1024 (16x64), keep 288 of 576",
+                          "filter_us": t_f1 * 1e3,
+                          "filter_GBps": 8 * (577 * 1024 * 2 + 288 * 4) / (t_f1 * 1e-3) / 1e9,
+                          "images_per_s": 8 / (t_f1 * 1e-3)}
+        del q1, k1, b1
+        # config 4: the video layer (GQA 28/4, D 3584).  (a) K-norm alone: 6272 -> 627 visual tokens;
+        # (b) the chain: Stage I per frame (32 x 196 -> 58), compaction of the frame features, then the
+        # layer on 1856 visual + 128 text tokens with keep 627; both against the unpruned 6400-token layer
+        c4 = I.config4_layer()
+        cfg4 = layer_line(c4, (627, 6272), "config4: B=1, T=6400 (32 frames x 196 + 128 text), keep 627 of 6272, "
+                                           "D=3584, 28/4 GQA x128")
+        fr = I.config4_frames()
+        q4, k4, feat4 = dev(fr["q_cls"]), dev(fr["k"]), dev(np.ascontiguousarray(fr["feats"][:, 1:, :]))
+        fo4 = vc.vitcop_filter_visual(q4, k4, fr["keep"])
+        fb4 = (fo4[0], fo4[1], torch.empty(vc.lib.vitcop_filter_visual_workspace_bytes(32, 196, 16, 64),
+                                          dtype=torch.uint8, device="cuda"))
+        fc4 = vc.vitcop_compact([feat4], fb4[1])
+        torch.cuda.synchronize()
+        kept_bits = fc4[0].view(torch.int16).cpu().numpy().view(np.uint16).reshape(32 * fr["keep"], fr["C"])
+        c4f = I.config4_layer(n_vis=32 * fr["keep"], vis_feats=I.bf16_bits_to_f32(kept_bits))
+        x4f = dev(c4f["x"])
+        w4 = [dev(c4f[n]) for n in ("wq", "wk", "wv", "wo")]
+        p4f = torch.arange(c4f["T"], dtype=torch.int32, device="cuda")[None].contiguous()
+        pl4 = vc.LayerPlan(x4f, *w4, 28, 4, 128, 0, c4f["n_vis"], 627, want_norms=False, positions=p4f)
+
+        def chain4():
+            vc.vitcop_filter_visual(q4, k4, fr["keep"], out=fb4)
+            vc.vitcop_compact([feat4], fb4[1], outs_in=fc4)
+            pl4.run()
+        t_fl4 = ev_time(lambda: vc.vitcop_filter_visual(q4, k4, fr["keep"], out=fb4), 50, warm=10)
+        t_l4 = ev_time(pl4.run, 20, warm=5)
+        t_ch4 = ev_time(chain4, 20, warm=5)
+        cfg4["filter_then_knorm"] = {
+            "visual_tokens": [6272, 32 * fr["keep"], 627], "filter_us": t_fl4 * 1e3,
+            "filter_GBps": 32 * (197 * 1024 * 2 + fr["keep"] * 4) / (t_fl4 * 1e-3) / 1e9,
+            "layer_ms": t_l4, "chain_ms": t_ch4,
+            "speedup_vs_unpruned": cfg4["layer_ms"]["unpruned"] / t_ch4,
+            "tokens_per_s": 6400 / (t_ch4 * 1e-3)}
+        del pl4, x4f, w4, q4, k4, feat4
+        out["config4"] = cfg4
         out["knorm_select_GBps"] = kern["knorm_select_stream_GBps"]
         out["attn_bf16_TFLOPs"] = kern["attn_unpruned_TFLOPs"]
         out["attn_frac_of_peak"] = kern["attn_unpruned_frac_mfma"]
