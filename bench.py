@@ -42,6 +42,10 @@ def parse():
     p.add_argument("--calib-copy", action="store_true",
                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3's "
                         "FETCH_SIZE / WRITE_SIZE counters)")
+    p.add_argument("--mfma-kernels", type=int, default=0, metavar="N",
+                   help="profiling mode: only N launches each of the matrix-core kernels at their bench shapes "
+                        "(K projection on random and on zero operands, attention at 4 x 2944 and at the video "
+                        "shape, the Stage II clustering with its Gram launch), then one JSON line of their times")
     p.add_argument("--traffic", type=float, default=None,
                    help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs), "
                         "echoed in roofline.traffic")
@@ -102,6 +106,37 @@ def main():
              for k in sorted(set(c3["keeps"]) | {args.keep, nv})}
     plan = plans[args.keep]
     Tp = T - nv + args.keep
+
+    if args.mfma_kernels > 0:
+        n_ = args.mfma_kernels
+        kd_ = Hkv * d
+        res = {}
+        x2d = x.reshape(B * T, D)
+        kb_ = vc.vitcop_project(x2d, wk, want_sumsq=True)
+        res["kproj_random_ms"] = ev_time(lambda: vc.vitcop_project(x2d, wk, want_sumsq=True, out=kb_), n_)
+        res["kproj_TFLOPs"] = 2.0 * B * T * kd_ * D / res["kproj_random_ms"] / 1e9
+        for name, b_a, n_a, hq_a, hkv_a in (("attn_4x2944_mha32", B, T, Hq, Hkv), ("attn_1x6400_gqa28_4", 1, 6400, 28, 4)):
+            qq = torch.randn((b_a, n_a, hq_a, d), dtype=torch.bfloat16, device="cuda")
+            kk = torch.randn((b_a, n_a, hkv_a, d), dtype=torch.bfloat16, device="cuda")
+            vv = torch.randn((b_a, n_a, hkv_a, d), dtype=torch.bfloat16, device="cuda")
+            oo = torch.empty_like(qq)
+            res[name + "_ms"] = ev_time(lambda: vc.vitcop_prefill_attn(qq, kk, vv, out=oo), n_, warm=3)
+            res[name + "_TFLOPs"] = 4.0 * d * hq_a * b_a * n_a * (n_a + 1) / 2 / res[name + "_ms"] / 1e9
+            del qq, kk, vv, oo
+        cases = [I.vic_inputs(I.seed_for(1, 50 + j), 288, 4096, grid=24, n_regions=8, noise=0.2) for j in range(8)]
+        vf = dev(np.stack([c["feats"] for c in cases]))
+        vp = torch.from_numpy(np.stack([c["pos"] for c in cases])).cuda()
+        res["vic_cluster_8x288x4096_ms"] = ev_time(lambda: vc.vitcop_vic_cluster(vf, vp, 8.0, 0.6, 29), n_)
+        res["gram_GFLOP"] = 2.0 * 8 * 288 * 288 * 4096 / 1e9
+        xz, wz = torch.zeros_like(x2d), torch.zeros_like(wk)
+        res["kproj_zero_ms"] = ev_time(lambda: vc.vitcop_project(xz, wz, want_sumsq=True, out=kb_), n_)
+        if args.calib_copy:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"mode": "mfma-kernels", "launches_each": n_, **res}))
+        return
 
     def step(kproj_events=None):
         vc.vitcop_filter_visual(f_q, f_k, f_keep, out=f_bufs)

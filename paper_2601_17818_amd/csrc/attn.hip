@@ -215,8 +215,8 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 // Wide variant for long sequences: a workgroup owns 256 queries, each of its 4
 // wavefronts 64 of them (two 32-query blocks), so every K and V^T fragment read
 // from LDS feeds two MFMAs.  K and V tiles (64 keys) arrive by direct
-// global -> LDS loads into two stages; both stay row-major in LDS with their
-// 16-byte chunks XOR-swizzled; V^T fragments come from the transposing LDS read
+// global -> LDS loads into a ring of four stages; both stay row-major in LDS,
+// padded per KiB; V^T fragments come from the transposing LDS read
 // (ds_read_b64_tr_b16), so nothing is staged in or shuffled through registers.
 // The running maximum is only refreshed when it grew by more than 2^8 (the
 // accumulators are rescaled then); the normalisation at the end makes the
@@ -246,17 +246,10 @@ __device__ __forceinline__ s16x4 lds_read_tr16(unsigned addr) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(uintptr_t)addr);
 }
 
-// 16 bytes per lane, global -> LDS, without passing through registers: lane L's data lands at
-// lds_base + 16*L (lds_base is wave-uniform and travels in M0).  Written as inline assembly on
-// purpose: for the builtin the compiler makes every later LDS read wait for ALL such loads in
-// flight, which would undo the prefetch; completion is tracked here by explicit vmcnt waits
-// before the barrier that publishes a tile.
-__device__ __forceinline__ void load_to_lds_16(const void* gptr, unsigned lds_base) {
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off"
-                 :
-                 : "s"(lds_base), "v"(gptr)
-                 : "memory");
-}
+// K and V reach LDS by buffer loads with the LDS modifier (16 bytes per lane, global -> LDS without passing
+// through registers: lane L's data lands at M0 + 16*L).  They are written as inline assembly on purpose: for
+// the builtins the compiler makes every later LDS read wait for ALL such loads in flight, which would undo
+// the prefetch; completion is tracked by explicit vmcnt waits before the barrier that publishes a tile.
 
 template <int I, int N, typename F>
 __device__ __forceinline__ void static_for(F&& f) {
@@ -365,8 +358,8 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         hb = first + ((gsz & 7) == 0 ? (j & 7) * (gsz >> 3) + (j >> 3) : j);
         qb = CAUSAL ? n_qb - 1 - r : r;
     }
-    const int h = hb % Hq, b = hb / Hq;
-    const int hk = h / (Hq / Hkv);
+    const int h = __builtin_amdgcn_readfirstlane(hb % Hq), b = __builtin_amdgcn_readfirstlane(hb / Hq);
+    const int hk = __builtin_amdgcn_readfirstlane(h / (Hq / Hkv));
     // Query blocks are aligned to the END of the sequence: a ragged block is then the first one,
     // which has the fewest keys to waste wavefronts on (query indices below 0 do not exist).
     const int q0 = N - (n_qb - qb) * AW_BM, wq0 = q0 + 64 * wv;
@@ -408,39 +401,46 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     const char* kbase = reinterpret_cast<const char*>(k + (int64_t)b * N * kv_rs + hk * AT_D);
     const char* vbase = reinterpret_cast<const char*>(v + (int64_t)b * N * kv_rs + hk * AT_D);
 
-    // direct-to-LDS loads: load i (0..3) of this wavefront is KiB group 4*wv+i of the K tile and
-    // of the V tile: rows {grp, grp+16, grp+32, grp+48}; lane L carries row grp + 16*(L/16),
-    // 16-byte chunk L%16.  Byte offsets of tile 0 are kept per lane; a tile further on adds a
-    // uniform stride.  Only the last tile of a ragged sequence needs its rows clamped.
+    // Direct-to-LDS loads.  A tile (64 keys) is 16 KiB groups for K and 16 for V: group g holds rows
+    // {g, g+16, g+32, g+48}; a wavefront fetches groups 4*wv .. 4*wv+3 of both, one buffer load of 16 bytes
+    // per lane each: lane L carries row g + 16*(L/16), 16-byte chunk L%16.  The address of a load is split so
+    // that nothing per-lane ever changes: the descriptor holds the base of this (sample, KV head), the scalar
+    // offset the tile and the row group, and ONE vector register the lane's row and chunk.  A load is then
+    // three instructions and no vector arithmetic.
+    // Rows past the end of the sequence are out of the descriptor's range and arrive as zeros (the scores of
+    // those keys are masked, and their zero V rows meet zero probabilities).
     const unsigned lds_base0 = __builtin_amdgcn_readfirstlane(
         (unsigned)(uintptr_t)(__attribute__((address_space(3))) char*)aw_lds);
-    const int64_t tile_stride = (int64_t)AW_BN * kv_rs * 2;
-    const int last_full_tile = N / AW_BN;                 // tiles [0, last_full_tile) lie inside the sequence
-    int64_t src_off[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-        src_off[i] = (int64_t)(4 * wv + i + 16 * (lane >> 4)) * kv_rs * 2 + ((lane & 15) << 4);
-    auto issue_tile = [&](int t) __attribute__((always_inline)) {
+    const unsigned row_bytes = (unsigned)(kv_rs * 2);
+    const unsigned tile_stride = AW_BN * row_bytes;
+    const unsigned n_rec = (unsigned)(N - 1) * row_bytes + AT_D * 2;      // through the last row of THIS head
+    auto make_desc = [&](const char* base) __attribute__((always_inline)) {
+        const uint64_t a = reinterpret_cast<uint64_t>(base);
+        u32x4 d;                          // raw buffer: base address, no stride, byte range, 32-bit data format
+        d.x = __builtin_amdgcn_readfirstlane((unsigned)a);
+        d.y = __builtin_amdgcn_readfirstlane((unsigned)(a >> 32) & 0xFFFFu);
+        d.z = n_rec;
+        d.w = 0x00020000u;
+        return d;
+    };
+    const u32x4 k_desc = make_desc(kbase), v_desc = make_desc(vbase);
+    const unsigned lane_off = (unsigned)(4 * wv + 16 * (lane >> 4)) * row_bytes + ((unsigned)(lane & 15) << 4);
+    // load j of tile t: row group 4*wv + j/2 of K (j even) or V (j odd)
+    auto issue_one = [&](int t, int j) __attribute__((always_inline)) {
+        const int i = j >> 1;
         const unsigned stage = lds_base0 + (t % AW_STAGES) * AW_STAGE;
-        const char* kt_base = kbase + t * tile_stride;
-        const char* vt_base = vbase + t * tile_stride;
-        if (t < last_full_tile) {
+        const unsigned dst = (j & 1) ? stage + AW_KTILE + (4 * wv + i) * AW_VGRP : stage + (4 * wv + i) * AW_KGRP;
+        const unsigned off = (unsigned)t * tile_stride + (unsigned)i * row_bytes;
+        if (j & 1)
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(lane_off), "s"(v_desc), "s"(off) : "memory");
+        else
+            asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                         :: "s"(dst), "v"(lane_off), "s"(k_desc), "s"(off) : "memory");
+    };
+    auto issue_tile = [&](int t) __attribute__((always_inline)) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int grp = 4 * wv + i;
-                load_to_lds_16(kt_base + src_off[i], stage + grp * AW_KGRP);
-                load_to_lds_16(vt_base + src_off[i], stage + AW_KTILE + grp * AW_VGRP);
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int grp = 4 * wv + i;
-                const int64_t key = min(t * AW_BN + grp + 16 * (lane >> 4), N - 1);
-                const int64_t off = key * kv_rs * 2 + ((lane & 15) << 4);
-                load_to_lds_16(kbase + off, stage + grp * AW_KGRP);
-                load_to_lds_16(vbase + off, stage + AW_KTILE + grp * AW_VGRP);
-            }
-        }
+        for (int j = 0; j < 8; ++j) issue_one(t, j);
     };
 
     // Software pipeline over "stages" of 32 keys (two per tile).  For stage c, with both query
@@ -634,6 +634,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // loads of tile t+2 may still be in flight) and tile t-1 is dead everywhere: its last
     // fragments were requested in the previous block and have arrived (lgkmcnt), so the fetch
     // of tile t+3 may overwrite its stage.
+    // (The eight loads of a tile go out together right after the barrier.  Spread over the MFMA slots of the
+    // pipeline blocks they were measured 15 % slower: a wavefront sits on each such load for a hundred cycles
+    // or more, and in a burst those waits overlap.)
     auto tile_sync = [&](int t) __attribute__((always_inline)) {
         if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -671,7 +674,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         }
         values_only(1, 0);                                              // drain: PV of the last stage
     }
-    for (; t < ntiles; ++t) tile_sync(t);                              // keep feeding the other wavefronts
+    for (; t < ntiles; ++t) tile_sync(t);                       // keep feeding the other wavefronts
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
@@ -711,7 +714,9 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
                            causal);
         return launch_status("attn<64>");
     }
-    if (N >= AW_MIN_N) {
+    // the wide kernel addresses K and V of one (sample, KV head) with 32-bit byte offsets
+    const bool wide_ok = ((int64_t)N + AW_BN) * Hkv * AT_D * 2 < ((int64_t)1 << 32);
+    if (N >= AW_MIN_N && wide_ok) {
         static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
         constexpr int lds = AW_STAGES * AW_STAGE;
         if (!attr_set.load(std::memory_order_acquire)) {
