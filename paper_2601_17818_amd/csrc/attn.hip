@@ -218,9 +218,9 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 // global -> LDS loads into a ring of four stages; both stay row-major in LDS,
 // padded per KiB; V^T fragments come from the transposing LDS read
 // (ds_read_b64_tr_b16), so nothing is staged in or shuffled through registers.
-// The running maximum is only refreshed when it grew by more than 2^8 (the
-// accumulators are rescaled then); the normalisation at the end makes the
-// result independent of which reference maximum was used.
+// The reference of the exponentials is only raised when a score exceeds it by
+// more than 2^8 (the accumulators are rescaled then); the normalisation at the
+// end makes the result independent of which reference was used.
 // ---------------------------------------------------------------------------
 constexpr int AW_BM = 256;
 constexpr int AW_BN = 64;
@@ -265,20 +265,24 @@ __device__ __forceinline__ void static_for(F&& f) {
 // matrix pipe and the vector pipe stay busy together; the order keeps every instruction a
 // few issue slots away from the producer of its operands.
 //   kinds: MASK (diagonal and ragged tiles only) score := -inf where the key is not visible;
-//   MAX5 five 3-input maxima of the 16 scores; MAX3 their reduction to one; SWAP exchange
-//   between the two wavefront halves (they hold different keys of the same query); REF0..REF6
-//   new reference maximum and alpha = exp2(old - new); FMA argument of an exponential; EXP;
-//   ADD2 sum of two neighbours, added to one of two running partial sums (few values stay
-//   live); CVT pack two probabilities to bf16; TREE the two partial sums combined and the
-//   update of the running denominator.
-enum SmKind : int { SM_MASK, SM_MAX5, SM_MAX3, SM_SWAP, SM_REF, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
+//   MAX5 five 3-input maxima of the lane's 16 scores; MAX3 their reduction to one; FMA argument of
+//   an exponential, score * scale - reference; EXP; ADD2 sum of two neighbours, added to one of
+//   two running partial sums (few values stay live); CVT pack two probabilities to bf16; TREE the
+//   two partial sums combined, then the update of the running denominator.
+//   (A dot-product instruction with (1, 1) would sum a packed pair in one go, but it was measured
+//   slower: it does not run beside the MFMAs the way plain vector instructions do.)
+// The list has two parts.  Part 1 (masks and maxima) fills the first `check` runs; after them the
+// block compares each lane's maximum with a threshold and, rarely, raises references (see there).
+// Part 2 (everything that needs the reference) fills the remaining runs.
+enum SmKind : int { SM_MASK, SM_MAX5, SM_MAX3, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, SM_TREE };
 struct SmOp {
     int kind, u, i;
 };
-constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3 + 1 + 7) + 2 * (16 + 16 + 8 + 8 + 2);
+constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3) + 2 * (16 + 16 + 8 + 8 + 2);
 struct SmTable {
     SmOp op[SM_NOPS];
     int start[33];       // run r is op[start[r]] .. op[start[r+1]-1]
+    int check;           // the reference check sits between run check-1 and run check
 };
 constexpr SmTable make_sm_table(bool masked) {
     SmTable t{};
@@ -289,9 +293,7 @@ constexpr SmTable make_sm_table(bool masked) {
     for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 0, i};
     for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 1, i};
     for (int i = 0; i < 3; ++i) { t.op[n++] = {SM_MAX3, 0, i}; t.op[n++] = {SM_MAX3, 1, i}; }
-    t.op[n++] = {SM_SWAP, 0, 0};
-    t.op[n++] = {SM_SWAP, 1, 0};
-    for (int i = 0; i < 7; ++i) { t.op[n++] = {SM_REF, 0, i}; t.op[n++] = {SM_REF, 1, i}; }
+    const int n1 = n;
     // part 2 in groups of four scores (group g: query block g / 4, scores 4 (g % 4) ..+3),
     // software pipelined: arguments of group ph, exponentials of group ph-1, sums and packing
     // of group ph-2; the tree of a query block follows two phases after its last pair sums
@@ -311,17 +313,30 @@ constexpr SmTable make_sm_table(bool masked) {
             for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, 1, i};
     }
     // split into 32 runs of about equal issue time (a mask is a compare and a select, an
-    // exponential takes twice as long as a plain instruction, a pair sum from the third on is two adds)
-    int total = 0;
+    // exponential takes twice as long as a plain instruction, a pair sum from the third on is two
+    // adds); part 1 gets whole runs
     auto weight = [](const SmOp& o) {
         return (o.kind == SM_MASK || o.kind == SM_EXP || (o.kind == SM_ADD2 && o.i >= 2)) ? 2 : 1;
     };
-    for (int k = 0; k < n; ++k) total += weight(t.op[k]);
+    int w1 = 0, w2 = 0;
+    for (int k = 0; k < n1; ++k) w1 += weight(t.op[k]);
+    for (int k = n1; k < n; ++k) w2 += weight(t.op[k]);
+    const int w_check = 6;       // compare, branch and the registers the rare path sets up
+    int runs1 = ((w1 + w_check) * 32 + (w1 + w_check + w2) / 2) / (w1 + w_check + w2);
+    if (runs1 < 1) runs1 = 1;
+    t.check = runs1;
     int acc = 0, r = 0;
     t.start[0] = 0;
-    for (int k = 0; k < n; ++k) {
+    for (int k = 0; k < n1; ++k) {
         acc += weight(t.op[k]);
-        while (r < 31 && acc * 32 >= total * (r + 1)) t.start[++r] = k + 1;
+        while (r < runs1 - 1 && acc * runs1 >= w1 * (r + 1)) t.start[++r] = k + 1;
+    }
+    while (r < runs1) t.start[++r] = n1;
+    acc = 0;
+    const int runs2 = 32 - runs1;
+    for (int k = n1; k < n; ++k) {
+        acc += weight(t.op[k]);
+        while (r < 31 && acc * runs2 >= w2 * (r - runs1 + 1)) t.start[++r] = k + 1;
     }
     while (r < 32) t.start[++r] = n;
     return t;
@@ -390,7 +405,10 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[u][i][r] = 0.f;
-    float m_ref[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    // per query: reference of the exponentials (log2 units), the raw score above which it must be
+    // raised, (reference + gap) / scale, and the running denominator
+    // (the threshold starts finite so that "maximum - threshold" is never inf - inf)
+    float m_ref[2] = {-INFINITY, -INFINITY}, thr[2] = {-3.0e38f, -3.0e38f}, l_run[2] = {0.f, 0.f};
 
     const int kend = CAUSAL ? min(N, q0 + AW_BM) : N;
     const int ntiles = (kend + AW_BN - 1) / AW_BN;                 // tiles the workgroup streams
@@ -528,34 +546,25 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             }
         }
         // state of the vector work (see SmKind)
-        float m5[2][5], m3[2][3], mx[2], ref[2][4], alpha[2] = {1.f, 1.f};
+        float m5[2][5], m3[2][3], alpha[2] = {1.f, 1.f};
         float e[2][16], ps[2][2];
         uint32_t pk[2][8];
+        bool moved = false;          // wave-uniform: some query of this wavefront raised its reference
         auto vector_op = [&](auto kc, auto uc, auto ic) __attribute__((always_inline)) {
             constexpr int kind = kc.value, u = uc.value, i = ic.value;
             const f32x16& sv = s[par][u];
             if constexpr (kind == SM_MASK) {
                 if (8 * (i >> 2) + (i & 3) > lim[u]) s[par][u][i] = -INFINITY;
             } else if constexpr (kind == SM_MAX5) {
+                // (the empty asm pins the instruction to its run: nothing else needs the maxima before
+                // the check, so the compiler would otherwise gather them all right in front of it)
                 m5[u][i] = fmaxf(fmaxf(sv[3 * i], sv[3 * i + 1]), sv[3 * i + 2]);
+                asm volatile("" : "+v"(m5[u][i]));
             } else if constexpr (kind == SM_MAX3) {
                 if constexpr (i == 0) m3[u][0] = fmaxf(fmaxf(m5[u][0], m5[u][1]), m5[u][2]);
                 if constexpr (i == 1) m3[u][1] = fmaxf(fmaxf(m5[u][3], m5[u][4]), sv[15]);
-                if constexpr (i == 2) m3[u][2] = fmaxf(m3[u][0], m3[u][1]);
-            } else if constexpr (kind == SM_SWAP) {
-                const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(m3[u][2]),
-                                                                 __float_as_uint(m3[u][2]), false, false);
-                mx[u] = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-            } else if constexpr (kind == SM_REF) {
-                // the reference maximum of a query moves only when it is exceeded by more than
-                // the gap; alpha = exp2(old - new) (1 if kept; exp2(-inf) = 0 at the start)
-                if constexpr (i == 0) ref[u][0] = mx[u] * scale_log2e;
-                if constexpr (i == 1) ref[u][1] = fmaxf(m_ref[u], ref[u][0]);
-                if constexpr (i == 2) ref[u][2] = m_ref[u] + AW_RESCALE_GAP;
-                if constexpr (i == 3) ref[u][3] = (ref[u][1] > ref[u][2]) ? ref[u][1] : m_ref[u];
-                if constexpr (i == 4) ref[u][0] = m_ref[u] - ref[u][3];
-                if constexpr (i == 5) alpha[u] = __builtin_amdgcn_exp2f(ref[u][0]);
-                if constexpr (i == 6) m_ref[u] = ref[u][3];
+                if constexpr (i == 2) m3[u][2] = fmaxf(m3[u][0], m3[u][1]) - thr[u];   // excess over the threshold
+                asm volatile("" : "+v"(m3[u][i]));
             } else if constexpr (kind == SM_FMA) {
                 e[u][i] = fmaf(sv[i], scale_log2e, -m_ref[u]);
             } else if constexpr (kind == SM_EXP) {
@@ -571,6 +580,29 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                 if constexpr (i == 1) l_run[u] = fmaf(l_run[u], alpha[u], ps[u][0]);
             }
         };
+        // The reference of a query moves only when its scores exceed it by more than the gap, which is
+        // rare (and always the case in a wavefront's first stage): the common path only compares the
+        // lane's own maximum with the threshold.  When any lane is over, the whole wavefront takes the
+        // long way: maxima exchanged between the two wavefront halves (they hold different keys of the
+        // same query, so both decide alike), new reference, alpha = exp2(old - new) (exp2(-inf) = 0 at
+        // the start) for the rescaling at the end of the block, new threshold.
+        auto check_reference = [&]() __attribute__((always_inline)) {
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(m3[0][2], m3[1][2]) > 0.f) != 0, 0)) {
+                moved = true;
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const float own = fmaxf(m3[u][0], m3[u][1]);
+                    const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(own), __float_as_uint(own),
+                                                                     false, false);
+                    const float mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+                    const float top = fmaxf(m_ref[u], mx * scale_log2e);
+                    const float ref_new = (top > m_ref[u] + AW_RESCALE_GAP) ? top : m_ref[u];
+                    alpha[u] = __builtin_amdgcn_exp2f(m_ref[u] - ref_new);
+                    m_ref[u] = ref_new;
+                    thr[u] = fmaxf((ref_new + AW_RESCALE_GAP) / scale_log2e, -3.0e38f);
+                }
+            }
+        };
         // S(c+1) accumulators
 #pragma unroll
         for (int u = 0; u < 2; ++u)
@@ -578,7 +610,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             for (int r = 0; r < 16; ++r) s[par ^ 1][u][r] = 0.f;
         // 32 slots: one MFMA (the 16 of S(c+1) first, so that they are complete when the next
         // block reads them, then the 16 of PV(c-1)), one fragment request, one run of vector work
-        static_for<0, 32>([&](auto slot) {
+        auto run_slot = [&](auto slot) __attribute__((always_inline)) {
             constexpr int i = slot.value;
             if constexpr (i < 16) {
                 constexpr int dc = i >> 1, u = i & 1;
@@ -592,11 +624,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                                                                        pf[par ^ 1][u][tt], o[u][db], 0, 0, 0);
                 }
             }
-            if constexpr (i < 8) {
-                kfr[par ^ 1][i] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + i * 32);
-            } else if constexpr (i < 24) {
-                constexpr int n = (i - 8) >> 1, off = (n >> 2) * 256 + (n & 3) * 64;
-                if constexpr ((i & 1) == 0) vlo[par ^ 1][n] = lds_read_tr16(Vs + off);                 // keys of slots 0..3
+            // fragment requests at an even pace, 2 KiB per four slots (a K fragment is 1 KiB per wavefront,
+            // a V^T half 512 B): bunched together they saturate LDS for the four wavefronts in lock-step,
+            // right when the tile loads issued after the barrier are writing into it
+            if constexpr ((i & 3) == 0) {
+                kfr[par ^ 1][i >> 2] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + (i >> 2) * 32);
+            } else if constexpr ((i & 1) == 1) {
+                constexpr int n = i >> 2, off = (n >> 2) * 256 + (n & 3) * 64;
+                if constexpr ((i & 2) == 0) vlo[par ^ 1][n] = lds_read_tr16(Vs + off);                 // keys of slots 0..3
                 else vhi[par ^ 1][n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);                          // keys of slots 4..7
             }
             static_for<SM_TABLE.start[i], SM_TABLE.start[i + 1]>([&](auto k) {
@@ -605,7 +640,11 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
                           std::integral_constant<int, op.i>{});
             });
             __builtin_amdgcn_sched_barrier(0);
-        });
+        };
+        static_for<0, SM_TABLE.check>(run_slot);
+        check_reference();
+        __builtin_amdgcn_sched_barrier(0);
+        static_for<SM_TABLE.check, 32>(run_slot);
         // the probabilities are consumed in the next block; without this pin the compiler sinks
         // their computation past the end of this block, away from the MFMAs it must hide behind
         asm volatile("" ::"v"(pk[0][0]), "v"(pk[0][1]), "v"(pk[0][2]), "v"(pk[0][3]), "v"(pk[0][4]), "v"(pk[0][5]),
@@ -621,7 +660,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             }
         // rare: some query moved its reference.  PV(c-1) above still belongs to the old one and
         // has been issued; PV(c) comes in the next block.
-        if (__builtin_amdgcn_ballot_w64(alpha[0] != 1.0f || alpha[1] != 1.0f) != 0) {
+        if (__builtin_expect(moved, 0)) {
 #pragma unroll
             for (int u = 0; u < 2; ++u)
 #pragma unroll
@@ -634,9 +673,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // loads of tile t+2 may still be in flight) and tile t-1 is dead everywhere: its last
     // fragments were requested in the previous block and have arrived (lgkmcnt), so the fetch
     // of tile t+3 may overwrite its stage.
-    // (The eight loads of a tile go out together right after the barrier.  Spread over the MFMA slots of the
-    // pipeline blocks they were measured 15 % slower: a wavefront sits on each such load for a hundred cycles
-    // or more, and in a burst those waits overlap.)
+    // (The eight loads of a tile go out together right after the barrier.  Inside the pipeline blocks they were
+    // measured 7 to 15 % slower, whether spread one by one over the MFMA slots or as one burst per wavefront,
+    // each wavefront in a slot of its own.)
     auto tile_sync = [&](int t) __attribute__((always_inline)) {
         if (t + 2 < ntiles) asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
         else asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
@@ -674,7 +713,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         }
         values_only(1, 0);                                              // drain: PV of the last stage
     }
-    for (; t < ntiles; ++t) tile_sync(t);                       // keep feeding the other wavefronts
+    for (; t < ntiles; ++t) tile_sync(t);                     // keep feeding the other wavefronts
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll

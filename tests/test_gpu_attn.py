@@ -66,6 +66,23 @@ def test_long_large_logits(vc):
     assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
 
 
+@pytest.mark.parametrize("N,d", [(1500, 128), (300, 128), (700, 64)])
+def test_rising_scores_move_the_reference(vc, N, d):
+    # scores that climb along the keys by several hundred in the exponent: the kernels raise their reference
+    # maximum again and again (and rescale what they have accumulated), also inside diagonal tiles; softmax
+    # weight sits on the last visible keys, so every row checks the state after all those moves
+    g = np.random.default_rng(77 + N)
+    q = np.ones((1, N, 2, d), np.float32) + 0.05 * g.standard_normal((1, N, 2, d)).astype(np.float32)
+    ramp = (np.arange(N, dtype=np.float32) / N * 6.0)[None, :, None, None]
+    k = ramp * np.ones((1, N, 2, d), np.float32) + 0.05 * g.standard_normal((1, N, 2, d)).astype(np.float32)
+    t = {"q": I.f32_to_bf16_bits(q), "k": I.f32_to_bf16_bits(k), "v": I.normal_bf16(78 + N, 3, (1, N, 2, d))}
+    out, lse = run(vc, t)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
+    assert ref_lse.max() - ref_lse.min() > 40.0                  # the logits do span hundreds of bits
+    assert_attention_close(out, ref, f"rising scores N={N} d={d}")
+    assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
+
+
 @pytest.mark.parametrize("N", [5, 64, 130, 257])
 def test_non_causal(vc, N):
     t = I.qkv_tensors(200 + N, 1, N, 2, 2, 128)
