@@ -173,7 +173,6 @@ def main():
     reps = max(5, args.steps)
     kd, qd = Hkv * d, Hq * d
     kbuf = vc.vitcop_project(x.reshape(B * T, D), wk, want_sumsq=True)
-    t_kproj_alone = ev_time(lambda: vc.vitcop_project(x.reshape(B * T, D), wk, want_sumsq=True, out=kbuf), reps)
     kproj_flops = 2.0 * B * T * kd * D
     roofline = {
         "kernel": "gemm_kernel<256,256> (K projection with squared-norm epilogue)",
@@ -184,25 +183,30 @@ def main():
     roofline["frac"] = roofline["achieved"] / roofline["peak"]
     roofline["algorithmic_flops_per_launch"] = kproj_flops
     roofline["algorithmic_bytes_per_launch"] = 2.0 * (B * T * D + kd * D + B * T * kd)
-    # measured ceilings beside the vendor peaks: the SAME kernel and launch on all-zero operands (what the
-    # matrix cores sustain when the data toggles no bits: the clock the chip holds under this kernel is
-    # power-limited and depends on the operands), and a plain 1 GiB device-to-device copy for HBM
-    xz, wz = torch.zeros_like(x).reshape(B * T, D), torch.zeros_like(wk)
-    zbuf = vc.vitcop_project(xz, wz, want_sumsq=True)
-    t_kproj_zero = ev_time(lambda: vc.vitcop_project(xz, wz, want_sumsq=True, out=zbuf), reps)
-    del xz, wz, zbuf
-    csrc_ = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
-    cdst_ = torch.empty_like(csrc_)
-    t_copy = ev_time(lambda: cdst_.copy_(csrc_), 10)
-    del csrc_, cdst_
-    roofline["peak_measured"] = {
-        "mfma_TFLOPs_same_kernel_zero_operands": kproj_flops / (t_kproj_zero * 1e-3) / 1e12,
-        "kproj_gemm_zero_operands_ms": t_kproj_zero,
-        "kproj_gemm_random_operands_back_to_back_ms": t_kproj_alone,
-        "hbm_copy_GBps": 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9,
-    }
     if args.traffic is not None:
         roofline["traffic"] = args.traffic
+    t_kproj_alone = None
+    if not args.no_extras:
+        # (left out with --no-extras so that a profile of that command holds the K projection only as it
+        # runs inside the steps)
+        t_kproj_alone = ev_time(lambda: vc.vitcop_project(x.reshape(B * T, D), wk, want_sumsq=True, out=kbuf), reps)
+        # measured ceilings beside the vendor peaks: the SAME kernel and launch on all-zero operands (what the
+        # matrix cores sustain when the data toggles no bits: the clock the chip holds under this kernel is
+        # power-limited and depends on the operands), and a plain 1 GiB device-to-device copy for HBM
+        xz, wz = torch.zeros_like(x).reshape(B * T, D), torch.zeros_like(wk)
+        zbuf = vc.vitcop_project(xz, wz, want_sumsq=True)
+        t_kproj_zero = ev_time(lambda: vc.vitcop_project(xz, wz, want_sumsq=True, out=zbuf), reps)
+        del xz, wz, zbuf
+        csrc_ = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+        cdst_ = torch.empty_like(csrc_)
+        t_copy = ev_time(lambda: cdst_.copy_(csrc_), 10)
+        del csrc_, cdst_
+        roofline["peak_measured"] = {
+            "mfma_TFLOPs_same_kernel_zero_operands": kproj_flops / (t_kproj_zero * 1e-3) / 1e12,
+            "kproj_gemm_zero_operands_ms": t_kproj_zero,
+            "kproj_gemm_random_operands_back_to_back_ms": t_kproj_alone,
+            "hbm_copy_GBps": 2.0 * (1 << 30) / (t_copy * 1e-3) / 1e9,
+        }
     if args.calib_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
         dst = torch.empty_like(src)
