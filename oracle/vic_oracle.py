@@ -89,16 +89,22 @@ def density(d_feat, d_c: float) -> np.ndarray:
 
 
 def parents(d_feat, d_spatial, rho, tau: float):
-    """Eq. 3 / Alg. 2 Step 2.  Returns (delta [n] with inf where no candidate, N [n] int32 with -1)."""
+    """Eq. 3 (Alg. 2 Step 2): delta_i = the smallest feature distance from token i to a token that is strictly
+    denser and spatially within tau of it; N_i = that token (the lowest index among equal distances).
+    Returns (delta [n], inf where no token qualifies; N [n] int32, -1 there)."""
+    d_feat = np.asarray(d_feat, dtype=np.float64)
+    d_spatial = np.asarray(d_spatial, dtype=np.float64)
+    rho = np.asarray(rho, dtype=np.float64)
     n = len(rho)
     delta = np.full(n, np.inf, dtype=np.float64)
     parent = np.full(n, -1, dtype=np.int32)
     for i in range(n):
-        for j in range(n):
-            if rho[j] > rho[i] and d_spatial[i][j] <= tau:
-                if d_feat[i][j] < delta[i]:
-                    delta[i] = d_feat[i][j]
-                    parent[i] = j
+        allowed = (rho > rho[i]) & (d_spatial[i] <= tau)          # the set the minimum of Eq. 3 runs over
+        if not allowed.any():
+            continue
+        masked = np.where(allowed, d_feat[i], np.inf)
+        parent[i] = int(np.argmin(masked))                         # first occurrence of the minimum
+        delta[i] = masked[parent[i]]
     return delta, parent
 
 

@@ -83,17 +83,20 @@ def test_spatial_threshold_is_inclusive_and_density_strict():
 
 
 def test_parents_against_independent_brute_force():
+    # the definition walked pair by pair: a candidate replaces the current one only if it is strictly nearer
     c = I.vic_inputs(23, 60, 32, n_regions=5)
     d, ds = V.feature_distances(c["feats"]), V.spatial_distances(c["pos"])
     rho = V.density(d, 8.0)
     delta, parent = V.parents(d, ds, rho, 0.6)
+    n_with = 0
     for i in range(60):
-        cand = np.where((rho > rho[i]) & (ds[i] <= 0.6))[0]
-        if len(cand) == 0:
-            assert parent[i] == -1 and np.isinf(delta[i])
-        else:
-            j = cand[np.argmin(d[i, cand])]                # first minimum = lower index
-            assert parent[i] == j and delta[i] == d[i, j]
+        best, arg = float("inf"), -1
+        for j in range(60):
+            if rho[j] > rho[i] and ds[i][j] <= 0.6 and d[i][j] < best:
+                best, arg = d[i][j], j
+        assert parent[i] == arg and (delta[i] == best or (arg < 0 and np.isinf(delta[i])))
+        n_with += arg >= 0
+    assert 0 < n_with < 60                                  # both branches were exercised
 
 
 def test_equal_distance_candidates_go_to_the_lower_index():
