@@ -518,15 +518,32 @@ def main():
         xf = x2[:, :64 + 288].clone()
         xf[0, 35:35 + 288] = dev(vin["feats"])
         pf = torch.arange(64 + 288, dtype=torch.int32, device="cuda")[None].contiguous()
-        xy = torch.from_numpy(vin["pos"].astype(np.float32)).cuda()
+        xy = torch.from_numpy(vin["pos"].astype(np.float32)[None]).cuda()
         fplan = vc.FullSchedulePlan(xf, pf, w_dev, 32, 32, 128, 35, 288,
                                     {"layer": 2, "budget": 253, "n_centers": 29, "d_c": 8.0, "tau": 0.6, "xy": xy},
                                     ((22, 51),))
         t_f = ev_time(fplan.run, 5, warm=2)
         out["full_schedule_paper_llava15_retain192"] = {
-            "ms": t_f, "speedup_vs_unpruned": t_dunpr / t_f, "visual_after_stage2": fplan.n_stage2,
+            "ms": t_f, "speedup_vs_unpruned": t_dunpr / t_f, "visual_after_stage2": fplan.n_stage2[0],
             "tokens_final": fplan.T_final}
         del fplan, xf, pf, xy
+        # the same on a batch of 8 prompts whose images differ (8 seeds of planted regions): Stage II leaves a
+        # different number of visual tokens per sample, the batch runs right-padded to the longest
+        xf8 = x2[:, :64 + 288].repeat(8, 1, 1).contiguous()
+        xy8 = []
+        for b in range(8):
+            vin = I.vic_inputs(2 + b, 288, 4096, 24, 29, 0.15)
+            xf8[b, 35:35 + 288] = dev(vin["feats"])
+            xy8.append(vin["pos"].astype(np.float32))
+        pf8 = torch.arange(64 + 288, dtype=torch.int32, device="cuda")[None].repeat(8, 1).contiguous()
+        fplan8 = vc.FullSchedulePlan(xf8, pf8, w_dev, 32, 32, 128, 35, 288,
+                                     {"layer": 2, "budget": 253, "n_centers": 29, "d_c": 8.0, "tau": 0.6,
+                                      "xy": torch.from_numpy(np.stack(xy8)).cuda()}, ((22, 51),))
+        t_f8 = ev_time(fplan8.run, 3, warm=1)
+        out["full_schedule_paper_llava15_retain192"]["batch8"] = {
+            "ms": t_f8, "speedup_vs_unpruned": paper["retain192_batch8"]["ms_unpruned"] / t_f8,
+            "visual_after_stage2": fplan8.n_stage2, "tokens_final": fplan8.T_final}
+        del fplan8, xf8, pf8, xy8
         # one decoding step (a new token per sample through all 32 layers) over the caches those prefills
         # leave: per-layer cache lengths of the unpruned prefill and of the paper's two schedules (Table 5's
         # time per generated token); a step streams every weight (12.95 GB) and every cached K and V once

@@ -344,6 +344,15 @@ typedef struct {
     uint16_t* k_cache;
     uint16_t* v_cache;
     int cache_capacity;               /* rows per sample, >= T' */
+    /* A right-padded batch, may be NULL (then every sample has n_vis visual tokens).  n_vis_samples [B]
+     * int32 device: sample b holds n_vis_samples[b] <= n_vis visual tokens at [vis_start, vis_start +
+     * n_vis_samples[b]), its remaining text follows them directly, and the last n_vis - n_vis_samples[b] of
+     * its T rows are padding (any finite values; under the causal mask no real token attends to them).
+     * Sample b then keeps min(keep, n_vis_samples[b]) visual tokens; its output is again right-padded to
+     * T' = T - n_vis + keep rows (padding rows repeat the last input row), and n_vis_samples_out [B]
+     * (may be NULL) receives the new counts.  Rows of `norms` past a sample's count are written as 0. */
+    const int32_t* n_vis_samples;
+    int32_t* n_vis_samples_out;
 } vitcop_decoder_layer_t;
 size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L);
 int vitcop_decoder_layer_prefill(const vitcop_decoder_layer_t* L, void* ws, size_t ws_bytes, void* stream);
@@ -389,19 +398,27 @@ typedef struct {
 size_t vitcop_decoder_schedule_workspace_bytes(const vitcop_decoder_schedule_t* S);
 int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws, size_t ws_bytes, void* stream);
 
-/* The paper's whole in-model procedure on ONE sample (Alg. 1): the decoder layers of S; on entry to
- * layer stage2_layer the n_vis visual tokens are clustered (Alg. 2: vitcop_vic_cluster on their hidden
- * states and grid positions vis_xy) and replaced by the per-cluster elites and one merged token per
- * cluster (Alg. 3: vitcop_collab_prune_merge with budget stage2_budget and that layer's K-norms, Eq. 4);
- * the stages of S (all at layers after stage2_layer) then prune by the Stage III rule.  The number of
- * visual tokens Stage II leaves is data-dependent (<= stage2_budget when the budget is at least the
- * number of clusters): the call reads it back and therefore SYNCHRONISES the stream once; a Stage III
- * budget above it keeps every token.  The new visual block holds the elites in token order, then the
- * merged tokens in cluster order; a merged token takes the position of the lowest-index token it
- * absorbed.
- *   S->B == 1;  S->y_out and S->positions_out (may be NULL) sized for T rows; T_final rows are written
- *   vis_xy [n_vis,2] fp32 device;  T_final, n_stage2: host ints (n_stage2 may be NULL)
- *   labels [n_vis], norms [n_vis] fp32, out_index [n_vis]: device outputs of Stage II, may be NULL
+/* The paper's whole in-model procedure (Alg. 1) on a batch: the decoder layers of S; on entry to
+ * layer stage2_layer the n_vis visual tokens of every sample are clustered (Alg. 2: vitcop_vic_cluster on
+ * their hidden states and grid positions vis_xy) and replaced by the per-cluster elites and one merged
+ * token per cluster (Alg. 3: vitcop_collab_prune_merge with budget stage2_budget and that layer's K-norms,
+ * Eq. 4); the stages of S (all at layers after stage2_layer) then prune by the Stage III rule.  The number
+ * of visual tokens Stage II leaves is data-dependent (<= stage2_budget when the budget is at least the
+ * number of clusters) and differs between samples: the call reads the B counts back and therefore
+ * SYNCHRONISES the stream once, and from there on the batch is RIGHT-PADDED to its longest sample (see
+ * vitcop_decoder_layer_t.n_vis_samples): the real tokens of a sample are a prefix of its rows, so under the
+ * causal mask padding changes no real token's result.  A Stage III budget above a sample's count keeps all
+ * of that sample's tokens.  The new visual block holds the elites in token order, then the merged tokens
+ * in cluster order; a merged token takes the position of the lowest-index token it absorbed; padding rows
+ * hold zeros (position 0) after Stage II and copies of a row of the same sample after Stage III.
+ *   S->y_out [B,T,D] and S->positions_out [B,T] (may be NULL) are sized for T rows per sample and written
+ *   densely as [B,T_final,...]; sample b's real rows are the first T_final_samples[b] of its T_final.
+ *   KV caches (S->k_cache, S->v_cache): layer l writes rows [0, padded length) of every sample, of which
+ *   the first cache_len_samples[l*B + b] are real; decoding over them needs equal lengths per layer.
+ *   vis_xy [B,n_vis,2] fp32 device;  T_final: host int;  n_stage2, T_final_samples: host arrays of B ints,
+ *   cache_len_samples: host array of n_layers*B ints (the three may be NULL)
+ *   labels [B,n_vis], norms [B,n_vis] fp32, out_index [B,n_vis] (row b: n_stage2[b] entries): device
+ *   outputs of Stage II, may be NULL
  * D % 32 == 0, n_vis <= VITCOP_VIC_MAX_TOKENS.
  */
 typedef struct {
@@ -414,6 +431,8 @@ typedef struct {
     int32_t* labels;
     float* norms;
     int32_t* out_index;
+    int* T_final_samples;
+    int* cache_len_samples;
 } vitcop_full_schedule_t;
 size_t vitcop_full_schedule_workspace_bytes(const vitcop_full_schedule_t* F);
 int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size_t ws_bytes, void* stream);
@@ -431,8 +450,14 @@ int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size
  * the residual adds (6 launches per layer); more samples through the few-row matrix-core projections.
  * All pointers are device pointers except the descriptor's own arrays (n_cached and the per-layer pointer
  * tables), which are host memory read during the call.  The call enqueues on `stream` and returns; the
- * caller advances n_cached after each step.  Errors: VITCOP_EINVAL (null pointer, sizes, a full cache),
- * VITCOP_EUNSUPPORTED (shape limits), VITCOP_EWORKSPACE, VITCOP_EHIP.
+ * caller advances n_cached after each step.
+ * Caches of different lengths within a batch (what vitcop_full_schedule_prefill leaves when Stage II kept
+ * different numbers of tokens per sample): n_cached_samples, DEVICE int32 [n_layers, B], may be NULL; sample
+ * b's cache in layer l then holds n_cached_samples[l*B + b] rows, its new K and V go to that row and it
+ * attends over that many rows + 1; n_cached[l] (host) must be the largest of layer l's entries (it sizes the
+ * launch and is checked against the capacity; an entry above it is clamped).  The caller advances both.
+ * Errors: VITCOP_EINVAL (null pointer, sizes, a full cache), VITCOP_EUNSUPPORTED (shape limits),
+ * VITCOP_EWORKSPACE, VITCOP_EHIP.
  */
 typedef struct {
     int B, D, Hq, Hkv, d, F, n_layers, cache_capacity;
@@ -452,6 +477,7 @@ typedef struct {
     uint16_t* const* k_cache;
     uint16_t* const* v_cache;
     uint16_t* y_out;
+    const int32_t* n_cached_samples;
 } vitcop_decoder_decode_t;
 size_t vitcop_decoder_decode_workspace_bytes(const vitcop_decoder_decode_t* S);
 int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_t ws_bytes, void* stream);

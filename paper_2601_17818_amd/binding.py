@@ -74,7 +74,8 @@ class DecoderLayerT(C.Structure):
                 ("wq", C.c_void_p), ("wk", C.c_void_p), ("wv", C.c_void_p), ("wo", C.c_void_p),
                 ("wg", C.c_void_p), ("wu", C.c_void_p), ("wd", C.c_void_p), ("y", C.c_void_p),
                 ("keep_idx", C.c_void_p), ("positions_out", C.c_void_p), ("norms", C.c_void_p),
-                ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cache_capacity", C.c_int)]
+                ("k_cache", C.c_void_p), ("v_cache", C.c_void_p), ("cache_capacity", C.c_int),
+                ("n_vis_samples", C.c_void_p), ("n_vis_samples_out", C.c_void_p)]
 
 
 _DEC_WEIGHTS = ("ln1", "ln2", "wq", "wk", "wv", "wo", "wg", "wu", "wd")
@@ -97,14 +98,16 @@ class DecoderDecodeT(C.Structure):
                 [("eps", C.c_float), ("theta", C.c_float), ("n_cached", C.POINTER(C.c_int)),
                  ("h", C.c_void_p), ("positions", C.c_void_p)] +
                 [(n, C.POINTER(C.c_void_p)) for n in _DEC_WEIGHTS] +
-                [("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("y_out", C.c_void_p)])
+                [("k_cache", C.POINTER(C.c_void_p)), ("v_cache", C.POINTER(C.c_void_p)), ("y_out", C.c_void_p),
+                 ("n_cached_samples", C.c_void_p)])
 
 
 class FullScheduleT(C.Structure):
     _fields_ = [("S", DecoderScheduleT), ("stage2_layer", C.c_int), ("stage2_budget", C.c_int),
                 ("n_centers", C.c_int), ("d_c", C.c_float), ("tau", C.c_float), ("vis_xy", C.c_void_p),
                 ("T_final", C.POINTER(C.c_int)), ("n_stage2", C.POINTER(C.c_int)),
-                ("labels", C.c_void_p), ("norms", C.c_void_p), ("out_index", C.c_void_p)]
+                ("labels", C.c_void_p), ("norms", C.c_void_p), ("out_index", C.c_void_p),
+                ("T_final_samples", C.POINTER(C.c_int)), ("cache_len_samples", C.POINTER(C.c_int))]
 
 
 class ScheduleT(C.Structure):
@@ -557,20 +560,29 @@ def _cache_arrays(caches, n_layers: int):
 
 class DecoderDecodePlan:
     """Pre-marshalled vitcop_decoder_decode_step call: one new token per sample through all layers.
-    ``caches``: per layer (k_cache, v_cache) [B, capacity, Hkv, d]; ``n_cached``: tokens each layer's cache holds."""
+    ``caches``: per layer (k_cache, v_cache) [B, capacity, Hkv, d]; ``n_cached``: tokens each layer's cache holds,
+    one int per layer, or one list of B ints per layer when the samples' caches differ in length (those go to
+    the device as an int32 tensor [n_layers, B], ``n_cached_samples``)."""
 
     def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, caches, n_cached, eps: float = 1e-5,
                  theta: float = 10000.0):
         B, D = h.shape
         n_layers = len(weights)
         F = weights[0]["wg"].shape[0]
-        self.keepalive = (h, positions, weights, caches)
         self._kc, self._vc, cap = _cache_arrays(caches, n_layers)
+        self.n_cached_samples = None
+        if len(n_cached) and hasattr(n_cached[0], "__len__"):
+            per = [[int(v) for v in row] for row in n_cached]
+            if any(len(row) != B for row in per):
+                raise ValueError("n_cached: one entry per sample in every layer")
+            self.n_cached_samples = torch.tensor(per, dtype=torch.int32, device=h.device)
+            n_cached = [max(row) for row in per]
+        self.keepalive = (h, positions, weights, caches, self.n_cached_samples)
         self._n = (C.c_int * n_layers)(*[int(v) for v in n_cached])
         self._w = [(C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights]) for n in _DEC_WEIGHTS]
         self.y = torch.empty((B, D), dtype=h.dtype, device=h.device)
         self.desc = DecoderDecodeT(B, D, Hq, Hkv, d, F, n_layers, cap, eps, theta, self._n, _ptr(h), _ptr(positions),
-                                   *self._w, self._kc, self._vc, _ptr(self.y))
+                                   *self._w, self._kc, self._vc, _ptr(self.y), _ptr(self.n_cached_samples))
         nb = lib.vitcop_decoder_decode_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
@@ -621,42 +633,50 @@ class DecoderSchedulePlan:
 
 
 class FullSchedulePlan:
-    """Pre-marshalled vitcop_full_schedule_prefill call (one sample).  ``stage2``: dict with layer, budget,
-    n_centers, d_c, tau and xy (device tensor [n_vis, 2] fp32); ``schedule``: the Stage III stages after it.
-    ``run`` returns (y [1, T_final, D], positions [1, T_final]); labels, norms, out_index and n_stage2 hold
-    what Stage II produced, stage_norms[s] and stage_keep_idx[s] what Stage III stage s ranked and kept."""
+    """Pre-marshalled vitcop_full_schedule_prefill call on a batch.  ``stage2``: dict with layer, budget,
+    n_centers, d_c, tau and xy (device tensor [B, n_vis, 2] fp32); ``schedule``: the Stage III stages after it.
+    ``run`` returns (y [B, T_final, D], positions [B, T_final]), right-padded: sample b's real rows are the
+    first T_final_samples[b].  labels [B, n_vis], norms [B, n_vis], out_index [B, max count] and n_stage2 (list)
+    hold what Stage II produced; stage_norms[s] [B, present] and stage_keep_idx[s] [B, kept rows] what Stage III
+    stage s ranked and kept (padded like the batch); cache_len[l][b] the real rows of layer l's cache."""
 
     def __init__(self, h, positions, weights, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, stage2: dict,
                  schedule, eps: float = 1e-5, theta: float = 10000.0, caches=None):
         B, T, D = h.shape
         n_layers = len(weights)
         F = weights[0]["wg"].shape[0]
-        self.keepalive = (h, positions, weights, stage2["xy"], caches)
+        xy = stage2["xy"]
+        if tuple(xy.shape) != (B, n_vis, 2):
+            raise ValueError(f"stage2['xy'] must be [B, n_vis, 2] = {(B, n_vis, 2)}, got {tuple(xy.shape)}")
+        self.keepalive = (h, positions, weights, xy, caches)
         self._kc, self._vc, cap = _cache_arrays(caches, n_layers)
         layers = [int(s[0]) for s in schedule]
         keeps = [int(s[1]) for s in schedule]
         self._pl = (C.c_int * max(len(layers), 1))(*layers)
         self._pk = (C.c_int * max(len(keeps), 1))(*keeps)
         self._w = [(C.c_void_p * n_layers)(*[w[n].data_ptr() for w in weights]) for n in _DEC_WEIGHTS]
-        self._y = torch.empty((B, T, D), dtype=h.dtype, device=h.device)
-        self._pos = torch.empty((B, T), dtype=torch.int32, device=h.device)
-        self.labels = torch.empty((n_vis,), dtype=torch.int32, device=h.device)
-        self.norms = torch.empty((n_vis,), dtype=torch.float32, device=h.device)
-        self._out_index = torch.empty((n_vis,), dtype=torch.int32, device=h.device)
-        self._T_final, self._n2 = C.c_int(0), C.c_int(0)
-        # record of every Stage III decision (one sample; sized for the counts before Stage II, cut in run)
-        self._keeps, self._T, self._n_vis = keeps, T, n_vis
-        self._stage_norms = [torch.empty((n_vis,), dtype=torch.float32, device=h.device) for _ in keeps]
-        self._stage_keep_idx = [torch.empty((T,), dtype=torch.int32, device=h.device) for _ in keeps]
+        self._y = torch.empty((B * T * D,), dtype=h.dtype, device=h.device)
+        self._pos = torch.empty((B * T,), dtype=torch.int32, device=h.device)
+        self.labels = torch.empty((B, n_vis), dtype=torch.int32, device=h.device)
+        self.norms = torch.empty((B, n_vis), dtype=torch.float32, device=h.device)
+        self._out_index = torch.empty((B, n_vis), dtype=torch.int32, device=h.device)
+        self._T_final = C.c_int(0)
+        self._n2 = (C.c_int * B)()
+        self._T_samples = (C.c_int * B)()
+        self._cache_len = (C.c_int * (n_layers * B))()
+        # record of every Stage III decision (sized for the counts before Stage II, cut in run)
+        self._keeps, self._B, self._T, self._D, self._n_vis, self._n_layers = keeps, B, T, D, n_vis, n_layers
+        self._stage_norms = [torch.empty((B * n_vis,), dtype=torch.float32, device=h.device) for _ in keeps]
+        self._stage_keep_idx = [torch.empty((B * T,), dtype=torch.int32, device=h.device) for _ in keeps]
         self._sn = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self._stage_norms])
         self._sk = (C.c_void_p * max(len(keeps), 1))(*[t.data_ptr() for t in self._stage_keep_idx])
         S = DecoderScheduleT(B, T, D, Hq, Hkv, d, F, vis_start, n_vis, n_layers, len(layers), eps, theta,
                              self._pl, self._pk, _ptr(h), _ptr(positions), *self._w, _ptr(self._y),
                              _ptr(self._pos), self._kc, self._vc, cap, self._sn, self._sk)
         self.desc = FullScheduleT(S, int(stage2["layer"]), int(stage2["budget"]), int(stage2["n_centers"]),
-                                  float(stage2["d_c"]), float(stage2["tau"]), _ptr(stage2["xy"]),
-                                  C.pointer(self._T_final), C.pointer(self._n2), _ptr(self.labels),
-                                  _ptr(self.norms), _ptr(self._out_index))
+                                  float(stage2["d_c"]), float(stage2["tau"]), _ptr(xy),
+                                  C.pointer(self._T_final), self._n2, _ptr(self.labels),
+                                  _ptr(self.norms), _ptr(self._out_index), self._T_samples, self._cache_len)
         nb = lib.vitcop_full_schedule_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())
@@ -664,17 +684,22 @@ class FullSchedulePlan:
 
     def run(self):
         _check(lib.vitcop_full_schedule_prefill(C.byref(self.desc), _ptr(self.ws), self.ws.numel(), _stream()))
-        self.T_final, self.n_stage2 = self._T_final.value, self._n2.value
-        self.out_index = self._out_index[: self.n_stage2]
-        # stage s ranked the visual tokens present on entry and kept min(budget, present) of them
-        present, text = self.n_stage2, self._T - self._n_vis
+        B, T, D = self._B, self._T, self._D
+        self.T_final = self._T_final.value
+        self.n_stage2 = list(self._n2)
+        self.T_final_samples = list(self._T_samples)
+        self.cache_len = [[self._cache_len[l * B + b] for b in range(B)] for l in range(self._n_layers)]
+        self.out_index = self._out_index[:, : max(self.n_stage2)]
+        # stage s ranked the visual tokens present on entry (of the longest sample) and kept min(budget, present)
+        present, text = max(self.n_stage2), T - self._n_vis
         self.stage_norms, self.stage_keep_idx = [], []
         for s, budget in enumerate(self._keeps):
             kept = min(budget, present)
-            self.stage_norms.append(self._stage_norms[s][:present])
-            self.stage_keep_idx.append(self._stage_keep_idx[s][: text + kept])
+            self.stage_norms.append(self._stage_norms[s][: B * present].view(B, present))
+            self.stage_keep_idx.append(self._stage_keep_idx[s][: B * (text + kept)].view(B, text + kept))
             present = kept
-        return self._y[:, : self.T_final], self._pos[:, : self.T_final]
+        Tf = self.T_final
+        return self._y[: B * Tf * D].view(B, Tf, D), self._pos[: B * Tf].view(B, Tf)
 
 
 class SchedulePlan:

@@ -2,6 +2,7 @@
 // then kernel launches on the caller's stream.  See include/vitcop.h for the
 // contract of each entry point.
 #include <algorithm>
+#include <vector>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -726,7 +727,7 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
     if (rc) return rc;
     if (want_sel) {
         rc = launch_select_smallest(parts, P, (int64_t)B * T, T, L->vis_start, 1, L->norms, B, T, L->vis_start,
-                                    L->n_vis, L->keep, idx, s);
+                                    L->n_vis, L->keep, idx, s, L->n_vis_samples, L->n_vis_samples_out);
         if (rc) return rc;
     }
     const uint16_t *hs = L->h, *as = a_all;
@@ -834,6 +835,13 @@ struct DecoderRun {
     int32_t* pbuf[2];
     void* lws;
     size_t lws_bytes;
+    // a right-padded batch (after Stage II): the samples' visual counts on the device while they differ,
+    // their host mirror, two buffers for the counts after a pruning layer, and the real cache lengths
+    const int32_t* nv_dev = nullptr;
+    int* nv_host = nullptr;
+    int32_t* nvbuf[2] = {nullptr, nullptr};
+    int nvpp = 0;
+    int* cache_len = nullptr;     // host, [n_layers * B], may be null
 };
 
 // Layers [l_begin, l_end) of S; a Stage III budget above the visual tokens still present keeps them all.
@@ -852,6 +860,10 @@ static int run_decoder_layers(const vitcop_decoder_schedule_t* S, int l_begin, i
             if (S->stage_keep_idx) L.keep_idx = S->stage_keep_idx[r.stage];
             L.keep = std::min(S->prune_keep[r.stage++], r.cur_vis);
             L.positions_out = r.pbuf[r.pp];
+            if (r.nv_dev) {
+                L.n_vis_samples = r.nv_dev;
+                L.n_vis_samples_out = r.nvbuf[r.nvpp];
+            }
         }
         L.y = last ? S->y_out : r.hbuf[l & 1];
         if (S->k_cache && S->v_cache) {
@@ -866,9 +878,21 @@ static int run_decoder_layers(const vitcop_decoder_schedule_t* S, int l_begin, i
         if (prune_here) {
             r.pos = r.pbuf[r.pp];
             r.pp ^= 1;
+            if (r.nv_dev && L.keep < r.cur_vis) {      // the selection ran and wrote the new counts
+                bool differ = false;
+                for (int b = 0; b < S->B; ++b) {
+                    r.nv_host[b] = std::min(r.nv_host[b], L.keep);
+                    differ |= r.nv_host[b] != L.keep;
+                }
+                r.nv_dev = differ ? r.nvbuf[r.nvpp] : nullptr;
+                r.nvpp ^= 1;
+            }
             r.cur_T = r.cur_T - r.cur_vis + L.keep;
             r.cur_vis = L.keep;
         }
+        if (r.cache_len)
+            for (int b = 0; b < S->B; ++b)
+                r.cache_len[(size_t)l * S->B + b] = r.cur_T - (r.nv_dev ? r.cur_vis - r.nv_host[b] : 0);
         r.h = L.y;
     }
     return VITCOP_OK;
@@ -902,19 +926,31 @@ int vitcop_decoder_schedule_prefill(const vitcop_decoder_schedule_t* S, void* ws
 
 /* ------------------------------------------- whole procedure with Stage II */
 
-// Positions of the sequence after Stage II: text before the visual block unchanged, row j of the new
-// visual block takes the position of its representative token, text after it unchanged.
-__global__ void stage2_positions_kernel(const int32_t* __restrict__ pos, const int32_t* __restrict__ out_index,
-                                        int vis_start, int n_vis, int n_out, int T_new,
-                                        int32_t* __restrict__ pos_out) {
-    const int j = blockIdx.x * blockDim.x + threadIdx.x;
-    if (j >= T_new) return;
-    int src = j;
-    if (j >= vis_start + n_out)
-        src = j - n_out + n_vis;
-    else if (j >= vis_start)
-        src = vis_start + out_index[j - vis_start];
-    pos_out[j] = pos[src];
+// The sequences after Stage II, right-padded to T_new rows: text before the visual block unchanged, row j of
+// the new visual block = row j of Stage II's output with the position of its representative token, the text
+// after it, then zero rows (position 0) up to the longest sample.  One workgroup per output row.
+__global__ __launch_bounds__(256) void stage2_splice_kernel(
+    const uint16_t* __restrict__ h, const uint16_t* __restrict__ out_feats, const int32_t* __restrict__ pos,
+    const int32_t* __restrict__ out_index, const int32_t* __restrict__ n_out, int T, int D, int vis_start,
+    int n_vis, int T_new, uint16_t* __restrict__ h_new, int32_t* __restrict__ pos_new) {
+    const int j = blockIdx.x, b = blockIdx.y;
+    const int no = n_vis > 0 ? n_out[b] : 0;
+    const uint16_t* src = nullptr;
+    int pos_src = -1;
+    if (j < vis_start) {
+        src = h + ((int64_t)b * T + j) * D;
+        pos_src = j;
+    } else if (j < vis_start + no) {
+        src = out_feats + ((int64_t)b * n_vis + (j - vis_start)) * D;
+        pos_src = vis_start + out_index[(int64_t)b * n_vis + (j - vis_start)];
+    } else if (j < T - n_vis + no) {
+        pos_src = j - no + n_vis;
+        src = h + ((int64_t)b * T + pos_src) * D;
+    }
+    uint4* dst = reinterpret_cast<uint4*>(h_new + ((int64_t)b * T_new + j) * D);
+    const uint4* s4 = reinterpret_cast<const uint4*>(src);
+    for (int c = threadIdx.x; c < D / 8; c += blockDim.x) dst[c] = src ? s4[c] : make_uint4(0, 0, 0, 0);
+    if (threadIdx.x == 0) pos_new[(int64_t)b * T_new + j] = pos_src >= 0 ? pos[(int64_t)b * T + pos_src] : 0;
 }
 
 static int check_full_schedule(const vitcop_full_schedule_t* F) {
@@ -922,27 +958,26 @@ static int check_full_schedule(const vitcop_full_schedule_t* F) {
     const vitcop_decoder_schedule_t* S = &F->S;
     int rc = check_decoder_schedule(S);
     if (rc) return rc;
-    REQUIRE(S->B == 1, VITCOP_EUNSUPPORTED, "full_schedule: B=%d (Stage II leaves a data-dependent length: one sample)",
-            S->B);
     REQUIRE(F->stage2_layer >= 0 && F->stage2_layer < S->n_layers, VITCOP_EINVAL, "full_schedule: stage2_layer=%d",
             F->stage2_layer);
     REQUIRE(S->n_stages == 0 || S->prune_layer[0] > F->stage2_layer, VITCOP_EINVAL,
             "full_schedule: Stage III layers must come after layer %d", F->stage2_layer);
     REQUIRE(F->stage2_budget >= 0 && F->stage2_budget <= S->n_vis, VITCOP_EINVAL, "full_schedule: stage2_budget=%d",
             F->stage2_budget);
-    return check_vic(1, S->n_vis, S->D, F->d_c, F->tau, F->n_centers);
+    return check_vic(S->B, S->n_vis, S->D, F->d_c, F->tau, F->n_centers);
 }
 
-// Stage II scratch: K of all tokens, norm partials, the identity keep list the norm pass writes, norms,
-// labels, cluster count, the new visual block, its representatives, its size; then the two stages' own.
+// Stage II scratch: the spliced hidden states, the normalised input, K of all tokens, norm partials, the
+// identity keep list the norm pass writes, norms, labels, cluster counts, the new visual blocks, their
+// representatives, their sizes (twice more for the counts after later stages); then the two stages' own.
 static size_t full_schedule_stage2_bytes(const vitcop_full_schedule_t* F) {
     const vitcop_decoder_schedule_t* S = &F->S;
-    const size_t T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
-    size_t b = up256(T * D * 2) + up256(T * D * 2) + up256(T * kd * 2) +
-               up256((size_t)gemm_sumsq_parts((int)kd) * T * 4) + up256(T * 4);
-    b += 2 * up256(n * 4) + 2 * up256(16) + up256(n * D * 2) + up256(n * 4);
-    b += up256(vic_workspace_bytes(1, (int)n)) + up256(collab_workspace_bytes(1, (int)n));
-    b += up256(gemm_workspace_bytes((int)T, (int)kd, (int)D));
+    const size_t B = S->B, T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
+    size_t b = up256(B * T * D * 2) + up256(B * T * D * 2) + up256(B * T * kd * 2) +
+               up256((size_t)gemm_sumsq_parts((int)kd) * B * T * 4) + up256(B * T * 4);
+    b += 2 * up256(B * n * 4) + 4 * up256(B * 4) + up256(B * n * D * 2) + up256(B * n * 4);
+    b += up256(vic_workspace_bytes((int)B, (int)n)) + up256(collab_workspace_bytes((int)B, (int)n));
+    b += up256(gemm_workspace_bytes((int)(B * T), (int)kd, (int)D));
     return b;
 }
 
@@ -961,30 +996,32 @@ int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size
     const size_t need = vitcop_full_schedule_workspace_bytes(F);
     REQUIRE(ws && ws_bytes >= need, VITCOP_EWORKSPACE, "full_schedule: workspace needs %zu bytes", need);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    const size_t T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
+    const size_t B = S->B, T = S->T, D = S->D, n = S->n_vis, kd = (size_t)S->Hkv * S->d;
     const int vs = S->vis_start, P = gemm_sumsq_parts((int)kd), ls = F->stage2_layer;
     Carver c(ws);
     DecoderRun r{S->h, nullptr, S->positions, S->T, S->n_vis, 0, 0, {}, {}, {}, nullptr, 0};
-    for (int i = 0; i < 2; ++i) r.hbuf[i] = c.take<uint16_t>(T * D * 2);
-    for (int i = 0; i < 2; ++i) r.abuf[i] = c.take<uint16_t>(T * D * 2);
-    for (int i = 0; i < 2; ++i) r.pbuf[i] = c.take<int32_t>(T * 4);
-    uint16_t* h_new = c.take<uint16_t>(T * D * 2);
-    uint16_t* a_all = c.take<uint16_t>(T * D * 2);
-    uint16_t* k_all = c.take<uint16_t>(T * kd * 2);
-    float* parts = c.take<float>((size_t)P * T * 4);
-    int32_t* idx_all = c.take<int32_t>(T * 4);
-    float* norms = c.take<float>(n * 4);
-    int32_t* labels = c.take<int32_t>(n * 4);
-    int32_t* n_clusters = c.take<int32_t>(16);
-    int32_t* n_out_dev = c.take<int32_t>(16);
-    uint16_t* out_feats = c.take<uint16_t>(n * D * 2);
-    int32_t* out_index = c.take<int32_t>(n * 4);
-    void* vic_ws = c.take<char>(vic_workspace_bytes(1, (int)n));
-    void* collab_ws = c.take<char>(collab_workspace_bytes(1, (int)n));
-    const size_t gs_bytes = gemm_workspace_bytes((int)T, (int)kd, (int)D);
+    for (int i = 0; i < 2; ++i) r.hbuf[i] = c.take<uint16_t>(B * T * D * 2);
+    for (int i = 0; i < 2; ++i) r.abuf[i] = c.take<uint16_t>(B * T * D * 2);
+    for (int i = 0; i < 2; ++i) r.pbuf[i] = c.take<int32_t>(B * T * 4);
+    uint16_t* h_new = c.take<uint16_t>(B * T * D * 2);
+    uint16_t* a_all = c.take<uint16_t>(B * T * D * 2);
+    uint16_t* k_all = c.take<uint16_t>(B * T * kd * 2);
+    float* parts = c.take<float>((size_t)P * B * T * 4);
+    int32_t* idx_all = c.take<int32_t>(B * T * 4);
+    float* norms = c.take<float>(B * n * 4);
+    int32_t* labels = c.take<int32_t>(B * n * 4);
+    int32_t* n_clusters = c.take<int32_t>(B * 4);
+    int32_t* n_out_dev = c.take<int32_t>(B * 4);
+    for (int i = 0; i < 2; ++i) r.nvbuf[i] = c.take<int32_t>(B * 4);
+    uint16_t* out_feats = c.take<uint16_t>(B * n * D * 2);
+    int32_t* out_index = c.take<int32_t>(B * n * 4);
+    void* vic_ws = c.take<char>(vic_workspace_bytes((int)B, (int)n));
+    void* collab_ws = c.take<char>(collab_workspace_bytes((int)B, (int)n));
+    const size_t gs_bytes = gemm_workspace_bytes((int)(B * T), (int)kd, (int)D);
     void* gs = c.take<char>(gs_bytes);
     r.lws = c.base + c.used;
     r.lws_bytes = ws_bytes - c.used;
+    r.cache_len = F->cache_len_samples;
 
     rc = run_decoder_layers(S, 0, ls, r, stream);
     if (rc) return rc;
@@ -993,62 +1030,70 @@ int vitcop_full_schedule_prefill(const vitcop_full_schedule_t* F, void* ws, size
     // squared norms as a side output; keeping all n_vis tokens makes the selection pass write the norms.
     const uint16_t* a = r.a_pre;
     if (!a) {
-        rc = launch_rmsnorm(r.h, D, S->ln1[ls], S->eps, a_all, D, (int)T, (int)D, s);
+        rc = launch_rmsnorm(r.h, D, S->ln1[ls], S->eps, a_all, D, (int)(B * T), (int)D, s);
         if (rc) return rc;
         a = a_all;
     }
-    rc = launch_gemm_ws(a, D, S->wk[ls], k_all, kd, nullptr, 0, (int)T, (int)kd, (int)D, parts, gs, gs_bytes, s);
+    rc = launch_gemm_ws(a, D, S->wk[ls], k_all, kd, nullptr, 0, (int)(B * T), (int)kd, (int)D, parts, gs, gs_bytes, s);
     if (rc) return rc;
-    rc = launch_select_smallest(parts, P, (int64_t)T, T, vs, 1, norms, 1, (int)T, vs, (int)n, (int)n, idx_all, s);
+    rc = launch_select_smallest(parts, P, (int64_t)(B * T), T, vs, 1, norms, (int)B, (int)T, vs, (int)n, (int)n,
+                                idx_all, s);
     if (rc) return rc;
     const uint16_t* feats = r.h + (size_t)vs * D;
+    std::vector<int> n_out(B, 0);
     if (n > 0) {
-        rc = launch_vic(feats, D, (int64_t)T * D, F->vis_xy, 1, (int)n, (int)D, F->d_c, F->tau, F->n_centers, labels,
-                        n_clusters, nullptr, nullptr, nullptr, nullptr, vic_ws, s);
+        rc = launch_vic(feats, D, (int64_t)T * D, F->vis_xy, (int)B, (int)n, (int)D, F->d_c, F->tau, F->n_centers,
+                        labels, n_clusters, nullptr, nullptr, nullptr, nullptr, vic_ws, s);
         if (rc) return rc;
-        rc = launch_collab(feats, D, (int64_t)T * D, labels, n_clusters, norms, 1, (int)n, (int)D, F->stage2_budget,
-                           out_feats, out_index, n_out_dev, nullptr, collab_ws, s);
+        rc = launch_collab(feats, D, (int64_t)T * D, labels, n_clusters, norms, (int)B, (int)n, (int)D,
+                           F->stage2_budget, out_feats, out_index, n_out_dev, nullptr, collab_ws, s);
         if (rc) return rc;
-    }
-    int n_out = 0;
-    if (n > 0) {
-        rc = hip_status(hipMemcpyAsync(&n_out, n_out_dev, 4, hipMemcpyDeviceToHost, s), "read Stage II count");
+        rc = hip_status(hipMemcpyAsync(n_out.data(), n_out_dev, B * 4, hipMemcpyDeviceToHost, s),
+                        "read Stage II counts");
         if (rc) return rc;
     }
     rc = hip_status(hipStreamSynchronize(s), "hipStreamSynchronize");
     if (rc) return rc;
-    REQUIRE(n_out >= 0 && (size_t)n_out <= n, VITCOP_EHIP, "full_schedule: Stage II returned %d tokens", n_out);
-    if (F->n_stage2) *F->n_stage2 = n_out;
+    int n_max = 0;
+    bool differ = false;
+    for (size_t b = 0; b < B; ++b) {
+        REQUIRE(n_out[b] >= 0 && (size_t)n_out[b] <= n, VITCOP_EHIP, "full_schedule: Stage II returned %d tokens",
+                n_out[b]);
+        n_max = std::max(n_max, n_out[b]);
+        differ |= n_out[b] != n_out[0];
+        if (F->n_stage2) F->n_stage2[b] = n_out[b];
+    }
     auto copy = [&](void* dst, const void* src, size_t bytes) {
         if (rc == VITCOP_OK && dst && bytes)
             rc = hip_status(hipMemcpyAsync(dst, src, bytes, hipMemcpyDeviceToDevice, s), "copy after Stage II");
     };
-    copy(F->labels, labels, n * 4);
-    copy(F->norms, norms, n * 4);
-    copy(F->out_index, out_index, (size_t)n_out * 4);
-    // the new sequence: text, new visual block, text
-    const size_t T_new = T - n + (size_t)n_out, tail = T - vs - n;
-    copy(h_new, r.h, (size_t)vs * D * 2);
-    copy(h_new + (size_t)vs * D, out_feats, (size_t)n_out * D * 2);
-    copy(h_new + ((size_t)vs + n_out) * D, r.h + ((size_t)vs + n) * D, tail * D * 2);
+    copy(F->labels, labels, B * n * 4);
+    copy(F->norms, norms, B * n * 4);
+    copy(F->out_index, out_index, B * n * 4);
     if (rc) return rc;
+    // the new sequences: text, new visual block, text, padding up to the longest sample
+    const size_t T_new = T - n + (size_t)n_max;
     int32_t* pos_new = r.pbuf[r.pp];
-    hipLaunchKernelGGL(stage2_positions_kernel, dim3((unsigned)((T_new + 255) / 256)), dim3(256), 0, s, r.pos,
-                       out_index, vs, (int)n, n_out, (int)T_new, pos_new);
-    rc = launch_status("stage2_positions");
+    hipLaunchKernelGGL(stage2_splice_kernel, dim3((unsigned)T_new, (unsigned)B), dim3(256), 0, s, r.h, out_feats,
+                       r.pos, out_index, n_out_dev, (int)T, (int)D, vs, (int)n, (int)T_new, h_new, pos_new);
+    rc = launch_status("stage2_splice");
     if (rc) return rc;
     r.h = h_new;
     r.a_pre = nullptr;
     r.pos = pos_new;
     r.pp ^= 1;
     r.cur_T = (int)T_new;
-    r.cur_vis = n_out;
+    r.cur_vis = n_max;
+    r.nv_host = n_out.data();
+    r.nv_dev = differ ? n_out_dev : nullptr;
 
     rc = run_decoder_layers(S, ls, S->n_layers, r, stream);
     if (rc) return rc;
     *F->T_final = r.cur_T;
+    if (F->T_final_samples)
+        for (size_t b = 0; b < B; ++b) F->T_final_samples[b] = r.cur_T - (r.nv_dev ? r.cur_vis - n_out[b] : 0);
     if (S->positions_out) {
-        rc = hip_status(hipMemcpyAsync(S->positions_out, r.pos, (size_t)r.cur_T * 4, hipMemcpyDeviceToDevice, s),
+        rc = hip_status(hipMemcpyAsync(S->positions_out, r.pos, B * (size_t)r.cur_T * 4, hipMemcpyDeviceToDevice, s),
                         "copy positions");
     }
     return rc;
@@ -1168,15 +1213,18 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
                         S->wd[l] && S->k_cache[l] && S->v_cache[l],
                     VITCOP_EINVAL, "decoder_decode: layer %d has a null pointer", l);
             const int N = S->n_cached[l];
+            // per-sample cache lengths: the append row and the keys attended over come from the device array
+            const int32_t* ncs = S->n_cached_samples ? S->n_cached_samples + (size_t)l * B : nullptr;
+            const size_t row0 = ncs ? 0 : (size_t)N * kd;
             rc = launch_gemv_qkv_rope(h, D, S->ln1[l], S->eps, S->wq[l], S->wk[l], S->wv[l], qb,
-                                      S->k_cache[l] + (size_t)N * kd, S->v_cache[l] + (size_t)N * kd, kv_batch,
-                                      S->positions, B, S->Hq, S->Hkv, S->d, D, S->theta, s);
+                                      S->k_cache[l] + row0, S->v_cache[l] + row0, kv_batch,
+                                      S->positions, B, S->Hq, S->Hkv, S->d, D, S->theta, s, ncs);
             if (rc) return rc;
             // (one sample and few slices: the output projection combines them itself, no merge launch; with more
             // samples every workgroup would repeat the combination for each of them and the launch is cheaper)
             DecodeParts slices{nullptr, nullptr, 0};
             rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
-                                    1.0f / std::sqrt((float)S->d), dws, s, kv_batch, B == 1 ? &slices : nullptr);
+                                    1.0f / std::sqrt((float)S->d), dws, s, kv_batch, B == 1 ? &slices : nullptr, ncs);
             if (rc) return rc;
             rc = launch_gemv(ob, qd, nullptr, 0.f, S->wo[l], h1, D, h, D, B, D, qd, s, &slices, S->d);
             if (rc) return rc;
@@ -1207,12 +1255,13 @@ int vitcop_decoder_decode_step(const vitcop_decoder_decode_t* S, void* ws, size_
         rc = launch_gemm_triple_ws(a, D, w3, y3, n3, B, D, gs, gs_bytes, s);
         if (rc) return rc;
         // the rotary embedding; the new token's K and V become row N of every sample's cache
+        const int32_t* ncs = S->n_cached_samples ? S->n_cached_samples + (size_t)l * B : nullptr;
+        const size_t row0 = ncs ? 0 : (size_t)N * kd;
         rc = launch_rope_append(qb, k_new, v_new, S->positions, B, S->Hq, S->Hkv, S->d, S->theta,
-                                S->k_cache[l] + (size_t)N * kd, S->v_cache[l] + (size_t)N * kd,
-                                (int64_t)S->cache_capacity * kd, s);
+                                S->k_cache[l] + row0, S->v_cache[l] + row0, (int64_t)S->cache_capacity * kd, s, ncs);
         if (rc) return rc;
         rc = launch_decode_attn(qb, S->k_cache[l], S->v_cache[l], ob, nullptr, B, N + 1, S->Hq, S->Hkv, S->d,
-                                1.0f / std::sqrt((float)S->d), dws, s, (int64_t)S->cache_capacity * kd);
+                                1.0f / std::sqrt((float)S->d), dws, s, (int64_t)S->cache_capacity * kd, nullptr, ncs);
         if (rc) return rc;
         rc = launch_gemm_norm_ws(ob, qd, S->wo[l], h1, D, h, D, B, D, qd, S->ln2[l], S->eps, bb, D, gs, gs_bytes, s);
         if (rc) return rc;

@@ -21,7 +21,8 @@ template <int D, int G>
 __global__ __launch_bounds__(DC_THREADS) void decode_partial_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     float* __restrict__ part_o, float* __restrict__ part_ml, int N, int Hq, int Hkv, int g0,
-    float scale_log2e, int keys_per_split, int n_splits, int64_t kv_batch) {
+    float scale_log2e, int keys_per_split, int n_splits, int64_t kv_batch,
+    const int32_t* __restrict__ n_cached_samples) {
     constexpr int LPK = D / 8;                       // lanes per key row
     constexpr int KPW = 64 / LPK;                    // keys per wavefront instruction
     const int split = blockIdx.x, hk = blockIdx.y, b = blockIdx.z;
@@ -46,11 +47,14 @@ __global__ __launch_bounds__(DC_THREADS) void decode_partial_kernel(
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
-    const int key_begin = split * keys_per_split, key_end = min(N, key_begin + keys_per_split);
+    // caches of different lengths: sample b attends over its n_cached_samples[b] rows and the appended one;
+    // slices past them see no live key and hand on an empty partial (max -inf, sum 0)
+    const int n_keys = n_cached_samples ? min(max(n_cached_samples[b], 0) + 1, N) : N;
+    const int key_begin = split * keys_per_split, key_end = min(n_keys, key_begin + keys_per_split);
     const int64_t row = (int64_t)Hkv * D;
     const uint16_t* kb = k + b * kv_batch + hk * D + 8 * c;      // kv_batch: elements between two samples' caches
     const uint16_t* vb = v + b * kv_batch + hk * D + 8 * c;
-    for (int key0 = key_begin + wv * KPW; key0 < key_end; key0 += 4 * KPW) {
+    for (int key0 = key_begin + wv * KPW; key0 < key_end; key0 += 4 * KPW) {     // (empty if key_end <= key_begin)
         const int key = key0 + kq;
         const bool live = key < key_end;
         const int kc = min(key, key_end - 1);
@@ -166,15 +170,15 @@ size_t decode_workspace_bytes(int B, int N, int Hq, int Hkv, int d) {
 template <int D, int G>
 static void launch_partial(dim3 grid, hipStream_t s, const uint16_t* q, const uint16_t* k, const uint16_t* v,
                            float* po, float* pml, int N, int Hq, int Hkv, int g0, float sl2, int kps, int ns,
-                           int64_t kv_batch) {
+                           int64_t kv_batch, const int32_t* ncs) {
     hipLaunchKernelGGL((decode_partial_kernel<D, G>), grid, dim3(DC_THREADS), 0, s, q, k, v, po, pml, N, Hq, Hkv, g0,
-                       sl2, kps, ns, kv_batch);
+                       sl2, kps, ns, kv_batch, ncs);
 }
 
 template <int D>
 static int launch_decode_d(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
                            int B, int N, int Hq, int Hkv, float scale, void* ws, hipStream_t s, int64_t kv_batch,
-                           DecodeParts* hand_over) {
+                           DecodeParts* hand_over, const int32_t* ncs) {
     const int ns = decode_splits(B, N, Hkv);
     const int kps = ((N + ns - 1) / ns + 63) / 64 * 64;
     float* po = static_cast<float*>(ws);
@@ -184,10 +188,10 @@ static int launch_decode_d(const uint16_t* q, const uint16_t* k, const uint16_t*
     dim3 grid(ns, Hkv, B);
     for (int g0 = 0; g0 < group; g0 += DC_MAX_G) {
         const int g = std::min(DC_MAX_G, group - g0);
-        if (g == 1) launch_partial<D, 1>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch);
-        else if (g == 2) launch_partial<D, 2>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch);
-        else if (g <= 4) launch_partial<D, 4>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch);
-        else launch_partial<D, 8>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch);
+        if (g == 1) launch_partial<D, 1>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch, ncs);
+        else if (g == 2) launch_partial<D, 2>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch, ncs);
+        else if (g <= 4) launch_partial<D, 4>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch, ncs);
+        else launch_partial<D, 8>(grid, s, q, k, v, po, pml, N, Hq, Hkv, g0, sl2, kps, ns, kv_batch, ncs);
         int rc = launch_status("decode_partial");
         if (rc) return rc;
     }
@@ -202,10 +206,13 @@ static int launch_decode_d(const uint16_t* q, const uint16_t* k, const uint16_t*
 
 int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
                        int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch,
-                       DecodeParts* hand_over) {
+                       DecodeParts* hand_over, const int32_t* n_cached_samples) {
     if (kv_batch == 0) kv_batch = (int64_t)N * Hkv * d;         // dense caches
-    if (d == 64) return launch_decode_d<64>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over);
-    return launch_decode_d<128>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over);
+    if (d == 64)
+        return launch_decode_d<64>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over,
+                                   n_cached_samples);
+    return launch_decode_d<128>(q, k, v, out, lse, B, N, Hq, Hkv, scale, ws, s, kv_batch, hand_over,
+                                n_cached_samples);
 }
 
 }  // namespace vitcop

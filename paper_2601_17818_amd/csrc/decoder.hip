@@ -125,28 +125,30 @@ int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_to
 }
 
 // The decoding step's variant: one new token per sample.  q is embedded in place; k is embedded on its way
-// into the sample's next cache row (k_dst + b * kv_batch) and v is copied into its row, so the append needs
-// no copies of its own.  Threads: per token (Hq + Hkv) * d/16 rotary groups, then Hkv * d/8 chunks of v.
+// into the sample's next cache row (k_dst + b * kv_batch, plus rows[b] rows when the samples' caches have
+// different lengths) and v is copied into its row, so the append needs no copies of its own.  Threads: per token (Hq + Hkv) * d/16 rotary groups, then Hkv * d/8 chunks of v.
 __global__ __launch_bounds__(RP_THREADS) void rope_append_kernel(
     uint16_t* __restrict__ q, const uint16_t* __restrict__ k, const uint16_t* __restrict__ v,
     const int32_t* __restrict__ positions, int n_tokens, int Hq, int Hkv, int d, float neg_log2_theta_2_over_d,
-    uint16_t* __restrict__ k_dst, uint16_t* __restrict__ v_dst, int64_t kv_batch) {
+    uint16_t* __restrict__ k_dst, uint16_t* __restrict__ v_dst, int64_t kv_batch,
+    const int32_t* __restrict__ rows) {
     const int groups = d / 16;
     const int rot = (Hq + Hkv) * groups, per_token = rot + Hkv * (d / 8);
     const int idx = blockIdx.x * RP_THREADS + threadIdx.x;
     const int token = idx / per_token;
     if (token >= n_tokens) return;
     const int rem = idx - token * per_token;
+    const int64_t cache_off = token * kv_batch + (rows ? (int64_t)rows[token] * Hkv * d : 0);
     if (rem >= rot) {                                   // a 16-byte chunk of v
         const int c = rem - rot;
-        *reinterpret_cast<uint4*>(v_dst + token * kv_batch + 8 * c) =
+        *reinterpret_cast<uint4*>(v_dst + cache_off + 8 * c) =
             *reinterpret_cast<const uint4*>(v + ((int64_t)token * Hkv * d) + 8 * c);
         return;
     }
     const int head = rem / groups, grp = rem - head * groups;
     const bool is_q = head < Hq;
     const uint16_t* src = is_q ? q + ((int64_t)token * Hq + head) * d : k + ((int64_t)token * Hkv + (head - Hq)) * d;
-    uint16_t* dst = is_q ? q + ((int64_t)token * Hq + head) * d : k_dst + token * kv_batch + (head - Hq) * d;
+    uint16_t* dst = is_q ? q + ((int64_t)token * Hq + head) * d : k_dst + cache_off + (head - Hq) * d;
     const float pos = (float)positions[token];
     const uint4 lo = *reinterpret_cast<const uint4*>(src + 8 * grp);
     const uint4 hi = *reinterpret_cast<const uint4*>(src + d / 2 + 8 * grp);
@@ -176,12 +178,12 @@ __global__ __launch_bounds__(RP_THREADS) void rope_append_kernel(
 
 int launch_rope_append(uint16_t* q, const uint16_t* k, const uint16_t* v, const int32_t* positions, int n_tokens,
                        int Hq, int Hkv, int d, float theta, uint16_t* k_dst, uint16_t* v_dst, int64_t kv_batch,
-                       hipStream_t s) {
+                       hipStream_t s, const int32_t* rows) {
     const int64_t threads = (int64_t)n_tokens * ((Hq + Hkv) * (d / 16) + Hkv * (d / 8));
     if (threads == 0) return VITCOP_OK;
     const float c = -2.0f * std::log2(theta) / (float)d;
     hipLaunchKernelGGL(rope_append_kernel, dim3((unsigned)((threads + RP_THREADS - 1) / RP_THREADS)), dim3(RP_THREADS),
-                       0, s, q, k, v, positions, n_tokens, Hq, Hkv, d, c, k_dst, v_dst, kv_batch);
+                       0, s, q, k, v, positions, n_tokens, Hq, Hkv, d, c, k_dst, v_dst, kv_batch, rows);
     return launch_status("rope_append");
 }
 

@@ -51,6 +51,7 @@ struct GvArgs {
     uint16_t* k_dst;                       // rope: row of the K cache that receives sample 0's k
     uint16_t* v_dst;
     int64_t kv_batch;                      // elements between two samples' rows
+    const int32_t* kv_rows;                // rope: sample b's row lies kv_rows[b] rows further on, or nullptr
     const int32_t* positions;              // rope: [B]
     int Hq, Hkv, d;
     float rope_c;                          // -2 log2(theta) / d
@@ -143,12 +144,14 @@ __device__ __forceinline__ void gv_finish(const GvArgs& a, int p, int b, float v
             float sn, cs;
             sincosf((float)a.positions[b] * inv_freq, &sn, &cs);
             const uint32_t o = pack_bf16(lo * cs - hi * sn, hi * cs + lo * sn);
-            uint16_t* dst = is_q ? a.y + (int64_t)b * a.y_stride : a.k_dst + (int64_t)b * a.kv_batch;
+            const int64_t extra = a.kv_rows ? (int64_t)a.kv_rows[b] * a.Hkv * a.d : 0;
+            uint16_t* dst = is_q ? a.y + (int64_t)b * a.y_stride : a.k_dst + (int64_t)b * a.kv_batch + extra;
             dst[head * a.d + i] = (uint16_t)(o & 0xFFFFu);
             dst[head * a.d + i + half] = (uint16_t)(o >> 16);
         } else {
             const int n = 2 * (p - pq - pk);
-            *reinterpret_cast<uint32_t*>(a.v_dst + (int64_t)b * a.kv_batch + n) = pack_bf16(v0, v1);
+            const int64_t extra = a.kv_rows ? (int64_t)a.kv_rows[b] * a.Hkv * a.d : 0;
+            *reinterpret_cast<uint32_t*>(a.v_dst + (int64_t)b * a.kv_batch + extra + n) = pack_bf16(v0, v1);
         }
     }
 }
@@ -412,11 +415,12 @@ int launch_gemv_gated(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w,
 }
 
 // q, k, v of one new token per sample from norm?(x[b]): q [B][Hq*d] with the rotary embedding at
-// positions[b]; k (embedded) and v go to k_dst / v_dst + b * kv_batch, the sample's next cache row.
+// positions[b]; k (embedded) and v go to k_dst / v_dst + b * kv_batch (+ kv_rows[b] rows), the sample's next
+// cache row.
 int launch_gemv_qkv_rope(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wq,
                          const uint16_t* wk, const uint16_t* wv, uint16_t* q, uint16_t* k_dst, uint16_t* v_dst,
                          int64_t kv_batch, const int32_t* positions, int B, int Hq, int Hkv, int d, int K, float theta,
-                         hipStream_t s) {
+                         hipStream_t s, const int32_t* kv_rows) {
     GvArgs a = gv_args(x, x_stride, ln_w, eps, K);
     a.w0 = wq;
     a.w1 = wk;
@@ -427,6 +431,7 @@ int launch_gemv_qkv_rope(const uint16_t* x, int64_t x_stride, const uint16_t* ln
     a.k_dst = k_dst;
     a.v_dst = v_dst;
     a.kv_batch = kv_batch;
+    a.kv_rows = kv_rows;
     a.positions = positions;
     a.Hq = Hq;
     a.Hkv = Hkv;

@@ -67,13 +67,19 @@ __global__ __launch_bounds__(KN_THREADS) void knorm_generic_kernel(
 
 __global__ __launch_bounds__(SEL_THREADS) void select_smallest_kernel(
     const float* __restrict__ parts, int n_parts, int64_t part_stride, int64_t sample_stride,
-    int64_t offset, int do_sqrt, float* __restrict__ norms_out, int T, int vis_start, int n_vis,
-    int keep, int32_t* __restrict__ keep_idx) {
+    int64_t offset, int do_sqrt, float* __restrict__ norms_out, int T, int vis_start, int n_vis_max,
+    int keep_max, int32_t* __restrict__ keep_idx, const int32_t* __restrict__ n_vis_samples,
+    int32_t* __restrict__ n_vis_samples_out) {
     extern __shared__ unsigned sel_keys[];
     __shared__ SelectShared sh;
     const int b = blockIdx.x, tid = threadIdx.x;
-    const int Tp = T - n_vis + keep;
+    const int Tp = T - n_vis_max + keep_max;
     int32_t* out = keep_idx + (int64_t)b * Tp;
+    // A right-padded batch: this sample has n_vis of the n_vis_max visual tokens, its text follows them
+    // directly, and the last n_vis_max - n_vis rows of its T are padding.  It keeps min(keep_max, n_vis).
+    const int n_vis = n_vis_samples ? min(max(n_vis_samples[b], 0), n_vis_max) : n_vis_max;
+    const int keep = min(keep_max, n_vis);
+    const int T_real = T - (n_vis_max - n_vis);
     const float* src = parts + (int64_t)b * sample_stride + offset;
     // Four candidates per thread at a time, eight parts each: 32 independent loads in flight per round trip
     // (the workgroup is alone on its CU and the reads are all latency); every candidate's parts are added in
@@ -105,13 +111,17 @@ __global__ __launch_bounds__(SEL_THREADS) void select_smallest_kernel(
             const int i = i0 + r * SEL_THREADS;
             if (i >= n_vis) continue;
             const float val = do_sqrt ? sqrtf(v[r]) : v[r];
-            if (norms_out) norms_out[(int64_t)b * n_vis + i] = val;
+            if (norms_out) norms_out[(int64_t)b * n_vis_max + i] = val;
             sel_keys[i] = __float_as_uint(val);      // val >= 0: bit order = value order
         }
     }
-    // text before and after the visual span is always kept
+    if (norms_out)
+        for (int i = n_vis + tid; i < n_vis_max; i += SEL_THREADS) norms_out[(int64_t)b * n_vis_max + i] = 0.f;
+    // text before and after the visual span is always kept; padding rows of the output name the last row
     for (int i = tid; i < vis_start; i += SEL_THREADS) out[i] = i;
-    for (int i = vis_start + n_vis + tid; i < T; i += SEL_THREADS) out[i - n_vis + keep] = i;
+    for (int i = vis_start + n_vis + tid; i < T_real; i += SEL_THREADS) out[i - n_vis + keep] = i;
+    for (int j = T_real - n_vis + keep + tid; j < Tp; j += SEL_THREADS) out[j] = T - 1;
+    if (n_vis_samples_out && tid == 0) n_vis_samples_out[b] = keep;
     __syncthreads();
     block_select_emit(sel_keys, n_vis, keep, out + vis_start, vis_start, sh);
 }
@@ -145,7 +155,8 @@ int launch_knorm(const uint16_t* k, int64_t row_stride, int64_t batch_stride, in
 int launch_select_smallest(const float* parts, int n_parts, int64_t part_stride,
                            int64_t sample_stride, int64_t offset, int do_sqrt,
                            float* norms_out, int B, int T, int vis_start, int n_vis,
-                           int keep, int32_t* keep_idx, hipStream_t s) {
+                           int keep, int32_t* keep_idx, hipStream_t s, const int32_t* n_vis_samples,
+                           int32_t* n_vis_samples_out) {
     if (B == 0 || T - n_vis + keep == 0) return VITCOP_OK;
     const size_t smem = (size_t)(n_vis > 0 ? n_vis : 1) * sizeof(unsigned);
     if (smem > 48 * 1024) {
@@ -157,7 +168,7 @@ int launch_select_smallest(const float* parts, int n_parts, int64_t part_stride,
     }
     hipLaunchKernelGGL(select_smallest_kernel, dim3(B), dim3(SEL_THREADS), smem, s, parts,
                        n_parts, part_stride, sample_stride, offset, do_sqrt, norms_out, T,
-                       vis_start, n_vis, keep, keep_idx);
+                       vis_start, n_vis, keep, keep_idx, n_vis_samples, n_vis_samples_out);
     return launch_status("select_smallest");
 }
 

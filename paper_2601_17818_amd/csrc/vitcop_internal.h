@@ -28,7 +28,8 @@ int launch_knorm(const uint16_t* k, int64_t row_stride, int64_t batch_stride, in
 int launch_select_smallest(const float* parts, int n_parts, int64_t part_stride,
                            int64_t sample_stride, int64_t offset, int do_sqrt,
                            float* norms_out, int B, int T, int vis_start, int n_vis,
-                           int keep, int32_t* keep_idx, hipStream_t s);
+                           int keep, int32_t* keep_idx, hipStream_t s,
+                           const int32_t* n_vis_samples = nullptr, int32_t* n_vis_samples_out = nullptr);
 
 // ---- compaction (compact.hip) --------------------------------------------
 int launch_compact(const vitcop_gather_t* t, int n, const int32_t* idx, int B, int T_out,
@@ -129,7 +130,7 @@ int launch_gemv_gated(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w,
 int launch_gemv_qkv_rope(const uint16_t* x, int64_t x_stride, const uint16_t* ln_w, float eps, const uint16_t* wq,
                          const uint16_t* wk, const uint16_t* wv, uint16_t* q, uint16_t* k_dst, uint16_t* v_dst,
                          int64_t kv_batch, const int32_t* positions, int B, int Hq, int Hkv, int d, int K, float theta,
-                         hipStream_t s);
+                         hipStream_t s, const int32_t* kv_rows = nullptr);
 
 bool gemm_skinny_applies(int M, int N, int K);
 size_t gemm_skinny_workspace_bytes(int M, int N, int K);
@@ -172,16 +173,18 @@ int launch_rmsnorm(const uint16_t* x, int64_t x_stride, const uint16_t* w, float
 int launch_rope(uint16_t* q, uint16_t* k, const int32_t* positions, int64_t n_tokens, int Hq, int Hkv, int d,
                 float theta, hipStream_t s);
 // one new token per sample: q embedded in place, k embedded into k_dst + b * kv_batch, v copied to v_dst + b * kv_batch
+// (rows, nullable: sample b's row lies rows[b] cache rows further on)
 int launch_rope_append(uint16_t* q, const uint16_t* k, const uint16_t* v, const int32_t* positions, int n_tokens,
                        int Hq, int Hkv, int d, float theta, uint16_t* k_dst, uint16_t* v_dst, int64_t kv_batch,
-                       hipStream_t s);
+                       hipStream_t s, const int32_t* rows = nullptr);
 int launch_silu_mul(const uint16_t* gate, const uint16_t* up, uint16_t* out, int64_t n_elems, hipStream_t s);
 
 // ---- decoding step over the KV cache (decode.hip) ---------------------------
 size_t decode_workspace_bytes(int B, int N, int Hq, int Hkv, int d);
-// kv_batch: elements between two samples' caches (0: dense, N * Hkv * d)
+// kv_batch: elements between two samples' caches (0: dense, N * Hkv * d); n_cached_samples (nullable, device
+// [B]): sample b attends over its first n_cached_samples[b] + 1 <= N rows only
 int launch_decode_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse, int B,
                        int N, int Hq, int Hkv, int d, float scale, void* ws, hipStream_t s, int64_t kv_batch = 0,
-                       DecodeParts* hand_over = nullptr);
+                       DecodeParts* hand_over = nullptr, const int32_t* n_cached_samples = nullptr);
 
 }  // namespace vitcop

@@ -269,7 +269,7 @@ def test_decoder_validation():
     assert lib.vitcop_silu_mul(A16, A16, A16, 12, None) == binding.VITCOP_EINVAL
     assert lib.vitcop_silu_mul(A16, A16 + 2, A16, 16, None) == binding.VITCOP_EINVAL
     assert lib.vitcop_silu_mul(None, None, None, 0, None) == binding.VITCOP_OK
-    assert C.sizeof(binding.DecoderLayerT) == 10 * 4 + 2 * 4 + 15 * 8 + 2 * 8 + 8      # caches, capacity (+ padding)
+    assert C.sizeof(binding.DecoderLayerT) == 10 * 4 + 2 * 4 + 15 * 8 + 2 * 8 + 8 + 2 * 8      # caches, capacity (+ padding), per-sample counts
 
     def desc(**kw):
         base = dict(B=1, T=640, D=4096, Hq=32, Hkv=32, d=128, F=11008, vis_start=35, n_vis=576, keep=64,
@@ -317,7 +317,7 @@ def test_decoder_schedule_validation():
 
 
 def test_full_schedule_validation():
-    assert C.sizeof(binding.FullScheduleT) == C.sizeof(binding.DecoderScheduleT) + 3 * 4 + 2 * 4 + 4 + 6 * 8
+    assert C.sizeof(binding.FullScheduleT) == C.sizeof(binding.DecoderScheduleT) + 3 * 4 + 2 * 4 + 4 + 8 * 8
     ptrs = (C.c_void_p * 4)(*[A16] * 4)
     t_final = C.c_int(0)
 
@@ -331,14 +331,15 @@ def test_full_schedule_validation():
         base.update({n: C.cast(ptrs, C.POINTER(C.c_void_p)) for n in binding._DEC_WEIGHTS})
         base.update(kw)
         return binding.FullScheduleT(binding.DecoderScheduleT(**base), stage2_layer, budget, n_centers, d_c, tau, xy,
-                                     C.pointer(t_final) if t_ptr else None, None, None, None, None)
+                                     C.pointer(t_final) if t_ptr else None, None, None, None, None, None, None)
 
     ws = lib.vitcop_full_schedule_workspace_bytes
     run = lib.vitcop_full_schedule_prefill
     need = ws(C.byref(desc()))
     assert need > lib.vitcop_decoder_schedule_workspace_bytes(C.byref(desc().S)) + 576 * 576 * 4
     assert run(C.byref(desc()), A16, need - 1, None) == binding.VITCOP_EWORKSPACE
-    assert run(C.byref(desc(B=2)), A16, 1 << 40, None) == binding.VITCOP_EUNSUPPORTED       # one sample
+    assert ws(C.byref(desc(B=2))) > need + 2 * 640 * 4096 * 2                               # a batch needs more
+    assert run(C.byref(desc(B=2)), A16, need, None) == binding.VITCOP_EWORKSPACE
     for bad in (desc(stage2_layer=4), desc(stage2_layer=3), desc(budget=600), desc(n_centers=600), desc(d_c=0.0),
                 desc(tau=-1.0), desc(xy=None), desc(t_ptr=False), desc(layers=(3, 2), keeps=(32, 16))):
         assert run(C.byref(bad), A16, 1 << 40, None) == binding.VITCOP_EINVAL
@@ -366,7 +367,7 @@ def test_decode_validation():
 
 
 def test_decoder_decode_validation():
-    assert C.sizeof(binding.DecoderDecodeT) == 8 * 4 + 2 * 4 + 15 * 8
+    assert C.sizeof(binding.DecoderDecodeT) == 8 * 4 + 2 * 4 + 15 * 8 + 8       # + per-sample cache lengths
     ptrs = C.cast((C.c_void_p * 3)(*[A16] * 3), C.POINTER(C.c_void_p))
 
     def desc(n_cached=(352, 317, 115), **kw):

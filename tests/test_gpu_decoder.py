@@ -197,10 +197,10 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
     s2 = {"layer": stage2_layer, "budget": 60, "n_centers": 6, "d_c": 8.0, "tau": 0.6}
     wd = [{k: dev(v) for k, v in w.items()} for w in layers]
     plan = vc.FullSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, n,
-                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)).cuda()}, schedule)
+                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)[None]).cuda()}, schedule)
     y, p = plan.run()
     torch.cuda.synchronize()
-    labels, norms = plan.labels.cpu().numpy(), plan.norms.cpu().numpy()
+    labels, norms = plan.labels[0].cpu().numpy(), plan.norms[0].cpu().numpy()
     # Stage II alone (no Stage III) with the oracle's own clustering and norms: same partition, close norms
     own = Dc.vitcop_schedule(h, layers[: stage2_layer + 1], {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos)
     assert V.same_partition(labels, own["stage2"]["labels"])
@@ -208,8 +208,9 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
     # the whole run on the GPU's labels and norms
     ref = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos, labels=labels, k_norms=norms)
     st = ref["stage2"]
-    assert plan.n_stage2 == st["n_out"] <= s2["budget"]
-    assert np.array_equal(plan.out_index.cpu().numpy(), st["index"])
+    assert plan.n_stage2 == [st["n_out"]] and st["n_out"] <= s2["budget"]
+    assert plan.T_final_samples == [plan.T_final]
+    assert np.array_equal(plan.out_index[0].cpu().numpy(), st["index"])
     got_pos = p.cpu().numpy()
     if schedule:
         (l3, k3), = schedule
@@ -218,8 +219,8 @@ def test_full_schedule_matches_oracle(vc, stage2_layer, schedule):
         # Stage III: the oracle's own decision on the sequence Stage II left, from its own K-norms of layer l3
         free = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
                                   k_norms=norms)
-        norms3 = plan.stage_norms[0].cpu().numpy()
-        idx = plan.stage_keep_idx[0].cpu().numpy()
+        norms3 = plan.stage_norms[0][0].cpu().numpy()
+        idx = plan.stage_keep_idx[0][0].cpu().numpy()
         want3 = free["stage3"][l3]
         assert norms3.shape == want3["norms"][0].shape == (st["n_out"],)
         assert np.allclose(norms3, want3["norms"][0], rtol=2e-3)
@@ -248,16 +249,17 @@ def test_full_schedule_caches_then_decode(vc):
     caches = [(torch.zeros((1, cap, Hkv, d), dtype=torch.bfloat16, device="cuda"),
                torch.zeros((1, cap, Hkv, d), dtype=torch.bfloat16, device="cuda")) for _ in layers]
     plan = vc.FullSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, n,
-                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)).cuda()}, schedule, caches=caches)
+                               {**s2, "xy": torch.from_numpy(xy.astype(np.float32)[None]).cuda()}, schedule,
+                               caches=caches)
     y, p = plan.run()
     torch.cuda.synchronize()
-    labels, norms = plan.labels.cpu().numpy(), plan.norms.cpu().numpy()
+    labels, norms = plan.labels[0].cpu().numpy(), plan.norms[0].cpu().numpy()
     mid = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, (), Hq, Hkv, d, vs, n, pos, labels=labels, k_norms=norms)
     n2 = mid["stage2"]["n_out"]
     # Stage III list: checked against the rule on the oracle's own norms of that layer before the oracle uses it
     free = Dc.vitcop_schedule(h, layers, {**s2, "xy": xy}, schedule, Hq, Hkv, d, vs, n, pos, labels=labels,
                               k_norms=norms)
-    norms3, idx = plan.stage_norms[0].cpu().numpy(), plan.stage_keep_idx[0].cpu().numpy()
+    norms3, idx = plan.stage_norms[0][0].cpu().numpy(), plan.stage_keep_idx[0][0].cpu().numpy()
     assert np.allclose(norms3, free["stage3"][3]["norms"][0], rtol=2e-3)
     assert_selection_matches(idx[vs:vs + 20] - vs, norms3, free["stage3"][3]["norms"][0], 20, False, "Stage III")
     assert np.array_equal(idx[:vs], np.arange(vs)) and np.array_equal(idx[vs + 20:], np.arange(vs + n2, T - n + n2))
@@ -265,7 +267,8 @@ def test_full_schedule_caches_then_decode(vc):
                              k_norms=norms, keep_lists={3: idx[None]})
     assert np.array_equal(p.cpu().numpy(), ref["positions"])
     lengths = [T, T - n + n2, T - n + n2, T - n + 20]
-    assert plan.T_final == lengths[-1] and plan.n_stage2 == n2
+    assert plan.T_final == lengths[-1] and plan.n_stage2 == [n2]
+    assert plan.cache_len == [[L] for L in lengths]
     for (kc, vcache), (k_ref, v_ref), L in zip(caches, ref["caches"], lengths):
         assert k_ref.shape[1] == L
         assert_stream_close(host_f64(kc)[:, :L], O.bf16_to_f64(k_ref), "K cache after the full schedule")
@@ -279,3 +282,98 @@ def test_full_schedule_caches_then_decode(vc):
     torch.cuda.synchronize()
     ref1 = Dc.decode_step(h_new, layers, ref["caches"], new_pos, Hq, Hkv, d)
     assert_stream_close(host_f64(y1), ref1["y"], "decoding step after the full schedule")
+
+
+@pytest.mark.parametrize("seeds", [(9900, 9968, 9934), (9900, 9968, 9934, 9951, 10002, 10036)])
+def test_full_schedule_batch_with_different_counts(vc, seeds):
+    # Alg. 1 on a batch whose samples leave Stage II with different numbers of visual tokens: the library pads the
+    # batch on the right; every sample's real rows must equal the one-sample procedure of the oracle (which knows
+    # nothing of batches or padding).  First Stage III budget lies between the samples' counts (one sample keeps
+    # all it has, the batch stays ragged), the second below all of them (the batch is dense again).
+    D, Hq, Hkv, d, F, vs, n, tail = 256, 4, 2, 128, 384, 12, 150, 10
+    T, B, n_layers = vs + n + tail, len(seeds), 5
+    layers = None
+    hs, xys = [], []
+    for b, seed in enumerate(seeds):
+        h_b, layers_b, xy_b = full_case(seed, vs, n, tail, D, Hq, Hkv, d, F, n_layers, 16, 6)
+        layers = layers or layers_b                       # one model: the first sample's weights
+        hs.append(h_b)
+        xys.append(xy_b)
+    h = np.concatenate(hs, axis=0)
+    pos = np.stack([2 * np.arange(T) + 3 * b for b in range(B)]).astype(np.int32)
+    s2 = {"layer": 1, "budget": 60, "n_centers": 6, "d_c": 8.0, "tau": 0.6}
+    own = [Dc.vitcop_schedule(h[b:b + 1], layers[:2], {**s2, "xy": xys[b]}, (), Hq, Hkv, d, vs, n, pos[b:b + 1])
+           for b in range(B)]
+    counts = [o["stage2"]["n_out"] for o in own]
+    assert len(set(counts)) == 3, counts                  # the case is about different counts
+    k3a, k3b = sorted(set(counts))[1], 20
+    schedule = ((2, k3a), (4, k3b))
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    cap = T + 4
+    caches = [(torch.zeros((B, cap, Hkv, d), dtype=torch.bfloat16, device="cuda"),
+               torch.zeros((B, cap, Hkv, d), dtype=torch.bfloat16, device="cuda")) for _ in layers]
+    xy_dev = torch.from_numpy(np.stack(xys).astype(np.float32)).cuda()
+    plan = vc.FullSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, n, {**s2, "xy": xy_dev},
+                               schedule, caches=caches)
+    y, p = plan.run()
+    torch.cuda.synchronize()
+    assert plan.n_stage2 == counts
+    n_max = max(counts)
+    T2 = T - n + n_max                                    # padded length after Stage II
+    kept_a = [min(k3a, c) for c in counts]
+    assert plan.T_final == T - n + k3b and plan.T_final_samples == [T - n + k3b] * B
+    want_len = [[T] * B, [T - n + c for c in counts], [T - n + k for k in kept_a], [T - n + k for k in kept_a],
+                [T - n + k3b] * B]
+    assert plan.cache_len == want_len
+    y_host, p_host = host_f64(y), p.cpu().numpy()
+    # then one decoding step over those caches of different lengths (2 to 4 samples: the streaming matrix-vector
+    # kernels; more: the few-row projections), every sample against the oracle's one-sample step
+    h_new = I.decoder_inputs(9960, B, 1, D, Hq, Hkv, d, F)["h"][:, 0]
+    new_pos = (2 * T + 5 * np.arange(B)).astype(np.int32)
+    step = vc.DecoderDecodePlan(dev(h_new), torch.from_numpy(new_pos).cuda(), wd, Hq, Hkv, d, caches, plan.cache_len)
+    y1 = host_f64(step.run())
+    torch.cuda.synchronize()
+    for b in range(B):
+        labels, norms = plan.labels[b].cpu().numpy(), plan.norms[b].cpu().numpy()
+        assert V.same_partition(labels, own[b]["stage2"]["labels"]), f"sample {b}"
+        assert np.allclose(norms, own[b]["stage2"]["norms"], rtol=2e-3)
+        one = dict(h_bits=h[b:b + 1], layer_weights=layers, stage2={**s2, "xy": xys[b]}, schedule=schedule, Hq=Hq,
+                   Hkv=Hkv, d=d, vis_start=vs, n_vis=n, positions=pos[b:b + 1], labels=labels, k_norms=norms)
+        free = Dc.vitcop_schedule(**one)
+        c = counts[b]
+        assert np.array_equal(plan.out_index[b, :c].cpu().numpy(), free["stage2"]["index"])
+        # first Stage III stage: candidates are this sample's c tokens, it keeps min(k3a, c) of them
+        ka = kept_a[b]
+        got_n = plan.stage_norms[0][b].cpu().numpy()
+        got_idx = plan.stage_keep_idx[0][b].cpu().numpy()
+        want = free["stage3"][2]
+        assert np.allclose(got_n[:c], want["norms"][0], rtol=2e-3) and not got_n[c:].any()
+        assert_selection_matches(got_idx[vs:vs + ka] - vs, got_n[:c], want["norms"][0], ka, False, f"sample {b} stage a")
+        assert np.array_equal(got_idx[:vs], np.arange(vs))
+        assert np.array_equal(got_idx[vs + ka:vs + ka + tail], np.arange(vs + c, vs + c + tail))
+        assert (got_idx[vs + ka + tail:] == T2 - 1).all()                      # padding rows
+        list_a = got_idx[None, :vs + ka + tail]
+        # second stage: the oracle continues with the first list, then its own norms decide
+        mid = Dc.vitcop_schedule(**one, keep_lists={2: list_a})
+        got_n = plan.stage_norms[1][b].cpu().numpy()
+        got_idx = plan.stage_keep_idx[1][b].cpu().numpy()
+        want = mid["stage3"][4]
+        assert np.allclose(got_n[:ka], want["norms"][0], rtol=2e-3) and not got_n[ka:].any()
+        assert_selection_matches(got_idx[vs:vs + k3b] - vs, got_n[:ka], want["norms"][0], k3b, False,
+                                 f"sample {b} stage b")
+        assert np.array_equal(got_idx[:vs], np.arange(vs))
+        assert np.array_equal(got_idx[vs + k3b:], np.arange(vs + ka, vs + ka + tail))
+        ref = Dc.vitcop_schedule(**one, keep_lists={2: list_a, 4: got_idx[None]})
+        assert np.array_equal(p_host[b], ref["positions"][0])
+        assert_stream_close(y_host[b:b + 1], ref["y"], f"sample {b} of the batch")
+        for l, ((kc, vcache), (k_ref, v_ref)) in enumerate(zip(caches, ref["caches"])):
+            L = want_len[l][b]
+            assert k_ref.shape[1] == L
+            assert_stream_close(host_f64(kc[b:b + 1, :L]), O.bf16_to_f64(k_ref), f"K cache, sample {b}, layer {l}")
+            assert_stream_close(host_f64(vcache[b:b + 1, :L]), O.bf16_to_f64(v_ref), f"V cache, sample {b}, layer {l}")
+        ref1 = Dc.decode_step(h_new[b:b + 1], layers, ref["caches"], new_pos[b:b + 1], Hq, Hkv, d)
+        assert_stream_close(y1[b:b + 1], ref1["y"], f"decoding step, sample {b}")
+        for l, ((kc, vcache), (k_row, v_row)) in enumerate(zip(caches, ref1["appended"])):
+            L = want_len[l][b]                            # the step appended at the sample's own row
+            assert_stream_close(host_f64(kc[b:b + 1, L]), O.bf16_to_f64(k_row), f"appended K, sample {b}, layer {l}")
+            assert_stream_close(host_f64(vcache[b:b + 1, L]), O.bf16_to_f64(v_row), f"appended V, sample {b}, layer {l}")
