@@ -115,3 +115,31 @@ def test_config2_schedule_prefix_full_width(vc):
         check_layer(vc, c, keep, True, f"config 2 layer {l}")
         cur_vis = keep
     assert ref["h"].shape == (1, 128, 4096)
+
+
+def test_config2_schedule_all_32_layers(vc):
+    # the whole config-2 schedule at full width: 32 layers (D 4096, 32 x 128), 576 visual tokens -> 192 on entry
+    # to layer 2, -> 128 at layer 8, -> 64 at layer 16; every layer teacher-forced on the oracle's input for that
+    # layer and compared through check_layer (separate entry points on the oracle's keep list, the one-call
+    # layer against them on its own list), so no comparison depends on how near-ties at a cut were decided
+    h2 = I.config2_hidden()
+    cache = {}
+
+    def weights(l):
+        if l not in cache:
+            w = I.config2_layer_weights(l)
+            w["wo"] = I.f32_to_bf16_bits(I.bf16_bits_to_f32(w["wo"]) * np.float32(0.125))
+            cache[l] = w
+        return cache[l]
+
+    ref = O.schedule_prefill(h2["x"], weights, 32, I.CONFIG2_SCHEDULE, 32, 32, 128, 35, 576)
+    budgets, cur_vis = dict(I.CONFIG2_SCHEDULE), 576
+    for l, lay in enumerate(ref["layers"]):
+        keep = budgets.get(l, cur_vis)
+        w = weights(l)
+        c = {"B": 1, "T": lay["x_in"].shape[1], "D": 4096, "Hq": 32, "Hkv": 32, "d": 128, "vis_start": 35,
+             "n_vis": cur_vis, "x": lay["x_in"], **{n: w[n] for n in ("wq", "wk", "wv", "wo")}}
+        check_layer(vc, c, keep, True, f"config 2 layer {l}")
+        cur_vis = keep
+        del cache[l]
+    assert ref["h"].shape == (1, 64 + 64, 4096) and cur_vis == 64
