@@ -51,7 +51,11 @@ __device__ __forceinline__ int gm_swz(int row) {
 // GM_EPI_PART is split-K: blockIdx.y = split, which multiplies its share of the k-steps and writes the
 // raw fp32 accumulators to dist[split][m][n] (row stride dist_stride, slices dist_batch apart) for a
 // reduction kernel to add up.
-constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1, GM_EPI_PART = 2;
+// GM_EPI_GATED is the MLP's first half in one launch: a tile's first BN/2 columns are rows of w (gate), its
+// last BN/2 the same rows of w2 (up); N counts the columns of each; the epilogue rounds both to bf16 as the
+// two separate projections would, and stores y[m,n] = silu(gate[m,n]) * up[m,n] (WAVES_N == 2: the gate
+// columns of a tile belong to the wavefronts with wn = 0, the up columns to wn = 1).
+constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1, GM_EPI_PART = 2, GM_EPI_GATED = 3;
 
 template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
@@ -108,8 +112,10 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         tile_n = in / gsz;
     }
     const int m0 = tile_m * BM;
-    int n0 = tile_n * BN;
-    if (w2 != nullptr && n0 >= n_split) {                // second projection (uniform per workgroup)
+    int n0 = tile_n * (EPI == GM_EPI_GATED ? BN / 2 : BN);
+    if constexpr (EPI == GM_EPI_GATED) {
+        static_assert(EPI != GM_EPI_GATED || WAVES_N == 2, "gate and up halves go to the two wavefront columns");
+    } else if (w2 != nullptr && n0 >= n_split) {         // second projection (uniform per workgroup)
         w = w2;
         y = y2;
         n0 -= n_split;
@@ -137,16 +143,20 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         const int chunk = (lane % CHUNKS) ^ gm_swz<BK>(row);
         if (row < BM)
             goff[q] = 2u * (unsigned)(min(m0 + row, M - 1) * (int)x_stride + chunk * 8);
+        else if (EPI == GM_EPI_GATED)     // slab rows [BM, BM + BN/2): gate rows n0.., then the same rows of up
+            goff[q] = 2u * (unsigned)(min(n0 + (row - BM) % (BN / 2), N - 1) * (int)w_stride + chunk * 8);
         else
             goff[q] = 2u * (unsigned)(min(n0 + row - BM, N - 1) * (int)w_stride + chunk * 8);
     }
     auto issue_loads = [&](int slab, int k0) {
         const char* xb = reinterpret_cast<const char*>(x + k0);
         const char* wb = reinterpret_cast<const char*>(w + k0);
+        const char* ub = reinterpret_cast<const char*>((EPI == GM_EPI_GATED ? w2 : w) + k0);
 #pragma unroll
         for (int q = 0; q < NDMA; ++q) {
             const bool is_x = (wv * NDMA + q) * ROWS_PER_LOAD < BM;            // wave-uniform
-            const char* src = (is_x ? xb : wb) + goff[q];
+            const bool is_up = EPI == GM_EPI_GATED && (wv * NDMA + q) * ROWS_PER_LOAD >= BM + BN / 2;
+            const char* src = (is_x ? xb : is_up ? ub : wb) + goff[q];
             char* dst = gemm_lds + slab * SLAB + (wv * NDMA + q) * 1024;
             __builtin_amdgcn_global_load_lds(
                 (const __attribute__((address_space(1))) void*)src,
@@ -347,6 +357,38 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
             }
         }
     }
+    if constexpr (EPI == GM_EPI_GATED) {
+        // gate block of these rows: staged by wavefront (wm, 0); up block: by (wm, 1).  Each of the two takes
+        // half of the block's columns: 16-byte chunks of gate and up in, one chunk of silu(gate) * up out.
+        static_assert((BM * ROWB) % (ROWS_PER_LOAD * ROWB) == 0 && (BN / 2) % ROWS_PER_LOAD == 0, "whole loads per half");
+        __builtin_amdgcn_s_waitcnt(0xC07F);               // lgkmcnt(0): this wavefront's staging writes are done
+        __builtin_amdgcn_s_barrier();
+        asm volatile("" ::: "memory");
+        const char* gate_stage = gemm_lds + wm * (TM * STAGE_ROW);
+        const char* up_stage = gemm_lds + (wm + WAVES_M) * (TM * STAGE_ROW);
+        constexpr int HALF_LANES = TN / 16;               // 16-byte chunks per half row
+        constexpr int ROWS_PER_PASS = 64 / HALF_LANES;
+        const int hrow = lane / HALF_LANES, hchunk = lane % HALF_LANES + wn * HALF_LANES;
+        const int nn = n0 + hchunk * 8;
+        if (nn < N) {                                     // N % 8 == 0: the chunk is all in or all out
+#pragma unroll
+            for (int r0 = 0; r0 < TM; r0 += ROWS_PER_PASS) {
+                const int row = r0 + hrow;
+                const int m = m0 + wm * TM + row;
+                const u32x4 gv = *reinterpret_cast<const u32x4*>(gate_stage + row * STAGE_ROW + hchunk * 16);
+                const u32x4 uv = *reinterpret_cast<const u32x4*>(up_stage + row * STAGE_ROW + hchunk * 16);
+                u32x4 ov;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float g0 = bf16_lo(gv[e]), g1 = bf16_hi(gv[e]);
+                    const float s0 = g0 / (1.0f + __expf(-g0)), s1 = g1 / (1.0f + __expf(-g1));
+                    ov[e] = pack_bf16(s0 * bf16_lo(uv[e]), s1 * bf16_hi(uv[e]));
+                }
+                if (m < M) *reinterpret_cast<u32x4*>(y + (int64_t)m * y_stride + nn) = ov;
+            }
+        }
+        return;
+    }
     // (a wavefront reads back only what it wrote itself: no barrier, the LDS counter suffices)
     constexpr int LANES_PER_ROW = TN / 8;                 // 16-byte chunks per staged row
     constexpr int ROWS_PER_STORE = 64 / LANES_PER_ROW;
@@ -383,7 +425,8 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
         if (rc) return rc;
         attr_set.store(true, std::memory_order_release);
     }
-    const int tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+    const int tiles_m = (M + BM - 1) / BM;
+    const int tiles_n = EPI == GM_EPI_GATED ? (N + BN / 2 - 1) / (BN / 2) : (N + BN - 1) / BN;
     // tile rows per group: a patch of about 32 tiles (one XCD's worth of workgroups) near square
     int group_m = 1;
     while (group_m * 2 <= tiles_m && group_m * group_m * 2 <= 32) group_m *= 2;
@@ -655,6 +698,23 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
     return launch_rmsnorm(y, y_stride, ln_w, eps, norm_out, norm_stride, M, N, s);
 }
 
+// out = silu(x Wg^T) * (x Wu^T) as ONE launch of the big tiles: a tile's columns are half gate, half up, and the
+// epilogue applies the activation (GM_EPI_GATED), so gate and up never reach memory.
+static int launch_tile_gated(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu,
+                             uint16_t* out, int M, int F, int K, hipStream_t s) {
+#define VITCOP_GATED(BM, BN) \
+    return launch_gemm_cfg<BM, BN, 2, 2, 32, GM_EPI_GATED>(x, x_stride, wg, out, F, nullptr, 0, M, F, K, nullptr, wu, \
+                                                           nullptr, 0, s)
+    switch (id) {
+        case T256x256: VITCOP_GATED(256, 256);
+        case T192x256: VITCOP_GATED(192, 256);
+        case T256x128: VITCOP_GATED(256, 128);
+        case T192x128: VITCOP_GATED(192, 128);
+        default: VITCOP_GATED(128, 128);
+    }
+#undef VITCOP_GATED
+}
+
 int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
                          uint16_t* gate, uint16_t* up, uint16_t* out, int M, int K, void* ws, size_t ws_bytes,
                          hipStream_t s) {
@@ -662,6 +722,16 @@ int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg
     const size_t need = gemm_skinny_workspace_bytes(M, 2 * F, K);
     if (ws && need && ws_bytes >= need && F % 128 == 0)
         return launch_gemm_skinny_gated(x, x_stride, wg, wu, F, out, M, K, ws, s);
+    // more rows than the few-row kernel takes: the big tiles with the activation in their epilogue, unless the
+    // launch is one that gets cut (k-slices for a few hundred rows, trailing columns on a path of their own):
+    // those produce gate and up separately
+    if (F % 8 == 0 && splitk_plan(M, 2 * F, K).splits == 0) {
+        TileId id = choose_tile(M, 2 * F, K, false, 768);
+        const bool two_by_two = id == T256x256 || id == T192x256 || id == T256x128 || id == T192x128 || id == T128x128;
+        TileId cut_id = id;
+        const bool cut = ws && F % 128 == 0 && main_columns(cut_id, M, 2 * F, K, false, F) < 2 * F;
+        if (two_by_two && !cut) return launch_tile_gated(id, x, x_stride, wg, wu, out, M, F, K, s);
+    }
     int rc = launch_gemm_pair_ws(x, x_stride, wg, gate, F, wu, up, F, M, K, ws, ws_bytes, s);
     if (rc) return rc;
     return launch_silu_mul(gate, up, out, (int64_t)M * F, s);

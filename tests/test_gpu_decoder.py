@@ -86,7 +86,13 @@ def run_layer(vc, c, pos, vis_start, n_vis, keep):
                                                        (1, 320, 1024, 2, 2, 128, 768, 0, 300, 300),
                                                        # gate+up as 3 x 86 tiles: the trailing column tile of `up`
                                                        # goes out as a launch of its own
-                                                       (1, 640, 1024, 2, 2, 128, 11008, 35, 576, 576)])
+                                                       (1, 640, 1024, 2, 2, 128, 11008, 35, 576, 576),
+                                                       # gate+up on the big tiles with the activation in their
+                                                       # epilogue: 300 rows x 2 x 86 tiles of 192 x 256; 1400 rows
+                                                       # on smaller tiles, whole and with a ragged last column tile
+                                                       (1, 400, 1024, 2, 2, 128, 11008, 20, 300, 200),
+                                                       (2, 700, 512, 4, 4, 128, 1408, 0, 640, 640),
+                                                       (2, 700, 512, 4, 4, 128, 1376, 0, 640, 600)])
 def test_decoder_layer_matches_oracle(vc, B, T, D, Hq, Hkv, d, F, vs, nv, keep):
     c = I.decoder_inputs(9300 + T, B, T, D, Hq, Hkv, d, F)
     pos = np.stack([np.sort(np.random.default_rng(10 + b).choice(2 * T, T, replace=False)) for b in range(B)])
