@@ -367,13 +367,14 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         const char* gate_stage = gemm_lds + wm * (TM * STAGE_ROW);
         const char* up_stage = gemm_lds + (wm + WAVES_M) * (TM * STAGE_ROW);
         constexpr int HALF_LANES = TN / 16;               // 16-byte chunks per half row
-        constexpr int ROWS_PER_PASS = 64 / HALF_LANES;
+        constexpr int ROWS_PER_PASS = 64 / HALF_LANES;    // (96-column blocks: 10 rows, the last 4 lanes idle)
         const int hrow = lane / HALF_LANES, hchunk = lane % HALF_LANES + wn * HALF_LANES;
         const int nn = n0 + hchunk * 8;
-        if (nn < N) {                                     // N % 8 == 0: the chunk is all in or all out
+        if (nn < N && hrow < ROWS_PER_PASS) {             // N % 8 == 0: the chunk is all in or all out
 #pragma unroll
             for (int r0 = 0; r0 < TM; r0 += ROWS_PER_PASS) {
                 const int row = r0 + hrow;
+                if (TM % ROWS_PER_PASS != 0 && row >= TM) break;
                 const int m = m0 + wm * TM + row;
                 const u32x4 gv = *reinterpret_cast<const u32x4*>(gate_stage + row * STAGE_ROW + hchunk * 16);
                 const u32x4 uv = *reinterpret_cast<const u32x4*>(up_stage + row * STAGE_ROW + hchunk * 16);
@@ -444,10 +445,11 @@ struct TileShape {
     float rate;
     bool sumsq;        // wavefront tile is 128 columns wide: can emit the norm partials
 };
-enum TileId { T256x256, T192x256, T256x128, T192x128, T128x128, T128x128R, T128x32, T_COUNT };
+enum TileId { T256x256, T192x256, T256x128, T192x128, T128x128, T128x128R, T128x32, T192x192G, T_COUNT };
 static const TileShape kTiles[T_COUNT] = {
     {256, 256, 1.00f, true},  {192, 256, 0.80f, true},  {256, 128, 0.74f, false}, {192, 128, 0.64f, false},
     {128, 128, 0.71f, false}, {128, 128, 0.69f, true},  {128, 32, 0.0f, false},
+    {192, 192, 0.72f, false},     // gate/up launches only (96 gate + 96 up columns): its epilogue exists in that form alone
 };
 
 // Estimated time of the launch in units of (one 256x256 tile at full rate): rounds over the
@@ -710,6 +712,7 @@ static int launch_tile_gated(TileId id, const uint16_t* x, int64_t x_stride, con
         case T192x256: VITCOP_GATED(192, 256);
         case T256x128: VITCOP_GATED(256, 128);
         case T192x128: VITCOP_GATED(192, 128);
+        case T192x192G: VITCOP_GATED(192, 192);
         default: VITCOP_GATED(128, 128);
     }
 #undef VITCOP_GATED
@@ -730,6 +733,10 @@ int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg
         const bool two_by_two = id == T256x256 || id == T192x256 || id == T256x128 || id == T192x128 || id == T128x128;
         TileId cut_id = id;
         const bool cut = ws && F % 128 == 0 && main_columns(cut_id, M, 2 * F, K, false, F) < 2 * F;
+        // a few hundred rows leave the 256-column tiles a third of the CUs short (317 x 22016: 172 tiles);
+        // 192 x 192 tiles (230) fill them
+        if (two_by_two && !cut && tile_cost(kTiles[T192x192G], M, 2 * F) < tile_cost(kTiles[id], M, 2 * F))
+            id = T192x192G;
         if (two_by_two && !cut) return launch_tile_gated(id, x, x_stride, wg, wu, out, M, F, K, s);
     }
     int rc = launch_gemm_pair_ws(x, x_stride, wg, gate, F, wu, up, F, M, K, ws, ws_bytes, s);
