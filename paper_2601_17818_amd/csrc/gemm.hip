@@ -22,15 +22,15 @@
 namespace vitcop {
 
 constexpr int GM_THREADS = 256;
-constexpr int GM_SLABS = 4;          // ring of k-slabs in LDS: three k-steps of loads in flight
+constexpr int GM_SLABS = 4;          // ring of k-slabs in LDS: three k-steps of loads in flight (k-steps of 32)
 constexpr int GM_PART = 128;         // columns per sum-of-squares partial
 constexpr int GM_XCDS = 8;
 
 // LDS: the slab ring, reused by the epilogue as one staging region per wavefront of
 // (BM / WAVES_M) rows of (BN / WAVES_N) bf16 + 16 bytes of padding.
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int NS = GM_SLABS>
 constexpr size_t gemm_lds_bytes() {
-    constexpr size_t ring = (size_t)GM_SLABS * (BM + BN) * BK * 2;
+    constexpr size_t ring = (size_t)NS * (BM + BN) * BK * 2;
     constexpr size_t stage = (size_t)4 * (BM / WAVES_M) * ((BN / WAVES_N) * 2 + 16);
     return ring > stage ? ring : stage;
 }
@@ -57,7 +57,12 @@ __device__ __forceinline__ int gm_swz(int row) {
 // columns of a tile belong to the wavefronts with wn = 0, the up columns to wn = 1).
 constexpr int GM_EPI_BF16 = 0, GM_EPI_DIST = 1, GM_EPI_PART = 2, GM_EPI_GATED = 3;
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
+// BK, NS: k-step and slabs in the ring.  With k-steps of 64 a slab row is a whole 128-byte line, so one direct
+// load moves 8 whole lines where k-steps of 32 move 16 half lines (and fetch every line twice, one k-step
+// apart): the CU's load path, which is what bounds the tiles of 128 and 192 columns, carries twice the useful
+// bytes.  Tiles whose three 64-wide slabs do not fit in LDS (256 x 256, 192 x 256) stay at 32 with four slabs;
+// with two slabs of 64 they were slower.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16, int NS = GM_SLABS>
 __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     const uint16_t* __restrict__ x, int64_t x_stride, const uint16_t* __restrict__ w,
     uint16_t* __restrict__ y, int64_t y_stride, const uint16_t* __restrict__ res,
@@ -198,12 +203,12 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
     }
     constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
 
-    // Pipeline over k-steps of BK.  Slab t % 4 holds k-step t; the loads of k-step t+3 are
+    // Pipeline over k-steps of BK.  Slab t % NS holds k-step t; the loads of k-step t+NS-1 are
     // issued during step t into the slab that step t-1 used (every wavefront left it before
     // the barrier of step t-1).  Step t, slice by slice (a slice = 16 of k):
-    //   slice 0: multiply; read the fragments of slice 1; issue the loads of step t+3
+    //   slice 0: multiply; read the fragments of slice 1; issue the loads of step t+NS-1
     //   slices 1 .. KC-2: multiply; read the fragments of the next slice
-    //   wait until this wavefront's loads of step t+1 have landed (two younger steps may
+    //   wait until this wavefront's loads of step t+1 have landed (NS-2 younger steps may
     //   still be in flight); barrier
     //   slice KC-1: multiply; read the fragments of slice 0 of step t+1
     // Past the end the loads repeat the last k-step into slabs nobody reads again.
@@ -218,7 +223,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
         for (int kc = 0; kc < KC - 1; ++kc) {
             read_frags((kc + 1) & 1, slab, kc + 1);
-            if (kc == 0) issue_loads((slab + 3) & 3, k_of(t + 3));
+            if (kc == 0) issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1));
             multiply(kc & 1);
             if constexpr (NMFMA >= NFRAG + NDMA) {
                 VITCOP_INTERLEAVE(0x100, NFRAG)
@@ -231,33 +236,31 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
             }
         }
         // (a plain s_barrier: __syncthreads would also drain the two younger steps' loads)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
-        read_frags(KC & 1, (slab + 1) & 3, 0);
+        read_frags(KC & 1, (slab + 1) % NS, 0);
         multiply((KC - 1) & 1);
         if constexpr (NMFMA >= NFRAG) {
             VITCOP_INTERLEAVE(0x100, NFRAG)
             __builtin_amdgcn_sched_group_barrier(0x008, NMFMA - NFRAG, 0);
         }
     };
-    issue_loads(0, k_of(0));
-    issue_loads(1, k_of(1));
-    issue_loads(2, k_of(2));
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * NDMA) : "memory");
+    static_assert(NS >= 3 && (NS - 2) * NDMA <= 63, "the wait counter holds 63 loads");
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i) issue_loads(i, k_of(i));
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA) : "memory");
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
     read_frags(0, 0, 0);
     int t = 0;
-    for (; t + 3 < nk; t += 4) {
-        step(t, 0);
-        step(t + 1, 1);
-        step(t + 2, 2);
-        step(t + 3, 3);
+    for (; t + NS - 1 < nk; t += NS) {
+#pragma unroll
+        for (int i = 0; i < NS; ++i) step(t + i, i);
     }
-    if (t < nk) step(t, 0);
-    if (t + 1 < nk) step(t + 1, 1);
-    if (t + 2 < nk) step(t + 2, 2);
+#pragma unroll
+    for (int i = 0; i < NS - 1; ++i)
+        if (t + i < nk) step(t + i, i);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");    // no load may outlive the workgroup's LDS
 #undef VITCOP_INTERLEAVE
 
@@ -408,7 +411,7 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 
 int gemm_sumsq_parts(int N) { return (N + GM_PART - 1) / GM_PART; }
 
-template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16>
+template <int BM, int BN, int WAVES_M, int WAVES_N, int BK, int EPI = GM_EPI_BF16, int NS = GM_SLABS>
 static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                            int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N,
                            int K, float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split,
@@ -416,8 +419,9 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
                            const float* wsq = nullptr, float* dist = nullptr, int64_t dist_stride = 0,
                            int batch = 1, int64_t x_batch = 0, int64_t sq_batch = 0, int64_t dist_batch = 0) {
     if (w_stride == 0) w_stride = K;
-    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, EPI>;
-    constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK>();
+    auto kern = gemm_kernel<BM, BN, WAVES_M, WAVES_N, BK, EPI, NS>;
+    constexpr size_t lds = gemm_lds_bytes<BM, BN, WAVES_M, WAVES_N, BK, NS>();
+    static_assert(lds <= 160 * 1024, "LDS of a CU");
     static std::atomic<bool> attr_set{false};   // per kernel instantiation; a second thread repeating the call is harmless
     if (!attr_set.load(std::memory_order_acquire)) {
         int rc = hip_status(hipFuncSetAttribute((const void*)kern,
@@ -435,6 +439,17 @@ static int launch_gemm_cfg(const uint16_t* x, int64_t x_stride, const uint16_t* 
                        y_stride, res, res_stride, M, N, K, sumsq_parts, tiles_m, tiles_n, group_m, w2,
                        y2, n_split, w_stride, xsq, wsq, dist, dist_stride, x_batch, sq_batch, dist_batch);
     return launch_status("gemm");
+}
+
+// The k-step of a launch: 64 where three (or four) slabs of that width fit in LDS and K allows it, else 32.
+template <int BM, int BN, int WAVES_M, int WAVES_N, int EPI, typename... Args>
+static int launch_gemm_k(int K, Args... args) {
+    constexpr size_t slab64 = (size_t)(BM + BN) * 128;
+    if constexpr (3 * slab64 <= 160 * 1024) {
+        constexpr int NS = 4 * slab64 <= 160 * 1024 ? 4 : 3;
+        if (K % 64 == 0) return launch_gemm_cfg<BM, BN, WAVES_M, WAVES_N, 64, EPI, NS>(args...);
+    }
+    return launch_gemm_cfg<BM, BN, WAVES_M, WAVES_N, 32, EPI>(args...);
 }
 
 // Tile shapes.  The wavefront tile sets the LDS bytes read per MFMA, so big tiles are the
@@ -517,17 +532,19 @@ static int main_columns(TileId& id, int M, int N, int K, bool need_sumsq, int al
 static int launch_tile(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y,
                        int64_t y_stride, const uint16_t* res, int64_t res_stride, int M, int N, int K,
                        float* sumsq_parts, const uint16_t* w2, uint16_t* y2, int n_split, hipStream_t s) {
-#define VITCOP_TILE(BM, BN, WM, WN, BK) \
-    return launch_gemm_cfg<BM, BN, WM, WN, BK>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, \
-                                               sumsq_parts, w2, y2, n_split, s)
+#define VITCOP_TILE(BM, BN, WM, WN) \
+    return launch_gemm_k<BM, BN, WM, WN, GM_EPI_BF16>(K, x, x_stride, w, y, y_stride, res, res_stride, M, N, K, \
+                                                      sumsq_parts, w2, y2, n_split, s)
     switch (id) {
-        case T256x256: VITCOP_TILE(256, 256, 2, 2, 32);
-        case T192x256: VITCOP_TILE(192, 256, 2, 2, 32);
-        case T256x128: VITCOP_TILE(256, 128, 2, 2, 32);
-        case T192x128: VITCOP_TILE(192, 128, 2, 2, 32);
-        case T128x128: VITCOP_TILE(128, 128, 2, 2, 32);
-        case T128x128R: VITCOP_TILE(128, 128, 4, 1, 32);
-        default: VITCOP_TILE(128, 32, 4, 1, 64);
+        case T256x256: VITCOP_TILE(256, 256, 2, 2);
+        case T192x256: VITCOP_TILE(192, 256, 2, 2);
+        case T256x128: VITCOP_TILE(256, 128, 2, 2);
+        case T192x128: VITCOP_TILE(192, 128, 2, 2);
+        case T128x128: VITCOP_TILE(128, 128, 2, 2);
+        case T128x128R: VITCOP_TILE(128, 128, 4, 1);
+        default:
+            return launch_gemm_cfg<128, 32, 4, 1, 64>(x, x_stride, w, y, y_stride, res, res_stride, M, N, K, sumsq_parts,
+                                                      w2, y2, n_split, s);
     }
 #undef VITCOP_TILE
 }
@@ -631,10 +648,10 @@ static int launch_gemm_splitk(const uint16_t* x, int64_t x_stride, const uint16_
     const SplitKPlan p = splitk_plan(M, N, K);
     float* part = static_cast<float*>(ws);
     int rc;
-#define VITCOP_SPLITK(BM, BN)                                                                                      \
-    rc = launch_gemm_cfg<BM, BN, 2, 2, 32, GM_EPI_PART>(x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr, w2, \
-                                                        nullptr, n_split, s, K, nullptr, nullptr, part, N, p.splits, \
-                                                        0, 0, (int64_t)M * N)
+#define VITCOP_SPLITK(BM, BN)                                                                                    \
+    rc = launch_gemm_k<BM, BN, 2, 2, GM_EPI_PART>(K, x, x_stride, w, nullptr, 0, nullptr, 0, M, N, K, nullptr, w2,   \
+                                                  nullptr, n_split, s, K, nullptr, nullptr, part, N, p.splits, 0, 0, \
+                                                  (int64_t)M * N)
     if (p.bm == 256 && p.bn == 256) VITCOP_SPLITK(256, 256);
     else if (p.bm == 192 && p.bn == 256) VITCOP_SPLITK(192, 256);
     else if (p.bm == 256) VITCOP_SPLITK(256, 128);
@@ -705,8 +722,8 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
 static int launch_tile_gated(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu,
                              uint16_t* out, int M, int F, int K, hipStream_t s) {
 #define VITCOP_GATED(BM, BN) \
-    return launch_gemm_cfg<BM, BN, 2, 2, 32, GM_EPI_GATED>(x, x_stride, wg, out, F, nullptr, 0, M, F, K, nullptr, wu, \
-                                                           nullptr, 0, s)
+    return launch_gemm_k<BM, BN, 2, 2, GM_EPI_GATED>(K, x, x_stride, wg, out, F, nullptr, 0, M, F, K, nullptr, wu, \
+                                                     nullptr, 0, s)
     switch (id) {
         case T256x256: VITCOP_GATED(256, 256);
         case T192x256: VITCOP_GATED(192, 256);
@@ -792,9 +809,9 @@ int launch_pairwise_dist(const uint16_t* f, int64_t row_stride, int64_t batch_st
                          int64_t sq_batch, float* dist, int64_t dist_stride, int64_t dist_batch, int n, int K,
                          int batch, hipStream_t s) {
     if (n == 0 || batch == 0) return VITCOP_OK;
-    return launch_gemm_cfg<128, 128, 2, 2, 32, GM_EPI_DIST>(f, row_stride, f, nullptr, 0, nullptr, 0, n, n, K,
-                                                            nullptr, nullptr, nullptr, 0, s, row_stride, sq, sq, dist,
-                                                            dist_stride, batch, batch_stride, sq_batch, dist_batch);
+    return launch_gemm_k<128, 128, 2, 2, GM_EPI_DIST>(K, f, row_stride, f, nullptr, 0, nullptr, 0, n, n, K, nullptr,
+                                                      nullptr, nullptr, 0, s, row_stride, sq, sq, dist, dist_stride, batch,
+                                                      batch_stride, sq_batch, dist_batch);
 }
 
 }  // namespace vitcop
