@@ -462,9 +462,9 @@ struct TileShape {
 };
 enum TileId { T256x256, T192x256, T256x128, T192x128, T128x128, T128x128R, T128x32, T192x192G, T_COUNT };
 static const TileShape kTiles[T_COUNT] = {
-    {256, 256, 1.00f, true},  {192, 256, 0.80f, true},  {256, 128, 0.74f, false}, {192, 128, 0.64f, false},
-    {128, 128, 0.71f, false}, {128, 128, 0.69f, true},  {128, 32, 0.0f, false},
-    {192, 192, 0.72f, false},     // gate/up launches only (96 gate + 96 up columns): its epilogue exists in that form alone
+    {256, 256, 1.00f, true},  {192, 256, 0.90f, true},  {256, 128, 0.88f, false}, {192, 128, 0.89f, false},
+    {128, 128, 0.76f, false}, {128, 128, 0.74f, true},  {128, 32, 0.0f, false},
+    {192, 192, 0.88f, false},     // gate/up launches only (96 gate + 96 up columns): its epilogue exists in that form alone
 };
 
 // Estimated time of the launch in units of (one 256x256 tile at full rate): rounds over the
@@ -592,8 +592,8 @@ static SplitKPlan splitk_plan(int M, int N, int K) {
     const int t256 = (M + 255) / 256, t192 = (M + 191) / 192, cols = (N + 127) / 128;
     auto slices = [&](int tiles) { return std::min(std::min(16, 256 / std::max(tiles, 1)), K / 32 / 8); };
     const int s192 = slices(t192 * cols), s256 = slices(t256 * cols);
-    const float c192 = s192 >= 2 ? 192.0f / (0.64f * (float)s192) : 1e30f;
-    const float c256 = s256 >= 2 ? 256.0f / (0.74f * (float)s256) : 1e30f;
+    const float c192 = s192 >= 2 ? 192.0f / (0.89f * (float)s192) : 1e30f;
+    const float c256 = s256 >= 2 ? 256.0f / (0.88f * (float)s256) : 1e30f;
     const int s128 = c192 <= c256 ? s192 : s256;
     // (not with slices longer than 4096 of k: inside a layer the 640-row down projection, K = 11008, takes
     // 110 us as 4 x 32 tiles x 2 slices against 91 us as 3 x 16 tiles x 5)
@@ -603,8 +603,8 @@ static SplitKPlan splitk_plan(int M, int N, int K) {
         p.splits = s128;
         return p;
     }
-    // 256-column tiles: 256 or 192 rows, whichever pads M less (192 runs at 0.8 of the rate)
-    const int bm = (float)(t192 * 192) / 0.8f < (float)(t256 * 256) ? 192 : 256;
+    // 256-column tiles: 256 or 192 rows, whichever pads M less (192 runs at 0.9 of the rate)
+    const int bm = (float)(t192 * 192) / 0.9f < (float)(t256 * 256) ? 192 : 256;
     const int tiles = (bm == 192 ? t192 : t256) * ((N + 255) / 256);
     const int splits = slices(tiles);                                       // at least 8 k-steps per slice
     if (splits < 3) return p;
