@@ -37,10 +37,13 @@ constexpr size_t gemm_lds_bytes() {
 
 // A slab row holds BK bf16 (64 or 128 bytes, unpadded because direct loads write 1 KiB runs).
 // 16-byte chunk c of row r lives at chunk position c ^ swz(r), which makes the MFMA fragment
-// reads (32 consecutive rows, same chunk) bank-conflict free.
+// reads (32 consecutive rows, same chunk) bank-conflict free: LDS serves a 16-byte read 16 lanes at a
+// time, so 16 consecutive rows must fall on the 16 different 16-byte units of a 256-byte bank row.  With
+// 64-byte rows the unit is 4*(r & 3) + position, so the position must differ among r, r+4, r+8, r+12;
+// with 128-byte rows it is 8*(r & 1) + position, so it must differ among the eight rows of equal parity.
 template <int BK>
 __device__ __forceinline__ int gm_swz(int row) {
-    return BK == 32 ? (row >> 2) & 3 : row & 7;
+    return BK == 32 ? (row >> 2) & 3 : (row >> 1) & 7;
 }
 
 // y = x W^T (+ residual).  With w2 != nullptr the columns [n_split, N) come from a second weight
