@@ -206,11 +206,14 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         __builtin_amdgcn_sched_group_barrier((mask), 1, 0);          \
     }
     constexpr int NFRAG = MI + NI, NMFMA = MI * NI;
-    // With two slices per k-step (k-steps of 32) and enough MFMAs to pair them with, a step's loads go out in
-    // two halves, one per slice, the second after the barrier into the same slab: one CU's 4 x NDMA loads of
-    // a step otherwise saturate its load unit for the whole first slice, and a wavefront stuck on issuing
-    // one cannot issue MFMAs meanwhile (8 % fewer cycles on the 256 x 256 tile).
+    // A step's loads go out in equal shares, one per slice, the last share after the barrier (into the same
+    // slab, free since the barrier of the step before): issued together, one CU's 4 x NDMA loads saturate its
+    // load unit for the whole first slice, and a wavefront stuck on issuing one cannot issue MFMAs meanwhile
+    // (8 % fewer cycles on the 256 x 256 tile, 3-6 % more throughput on the smaller ones).  SPLIT: the form
+    // with two slices and enough MFMAs to pair every fragment read and load with one (scheduling hints).
     constexpr bool SPLIT = KC == 2 && NDMA % 2 == 0 && NMFMA >= NFRAG + NDMA;
+    constexpr bool SPREAD = !SPLIT && NDMA >= KC;
+    constexpr int LAST_PART = NDMA - ((KC - 1) * NDMA + KC - 1) / KC;      // loads issued after the barrier
 
     // Pipeline over k-steps of BK.  Slab t % NS holds k-step t; the loads of k-step t+NS-1 are
     // issued during step t into the slab that step t-1 used (every wavefront left it before
@@ -232,7 +235,9 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
 #pragma unroll
         for (int kc = 0; kc < KC - 1; ++kc) {
             read_frags((kc + 1) & 1, slab, kc + 1);
-            if (kc == 0) {
+            if constexpr (SPREAD) {
+                issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1), kc, KC);
+            } else if (kc == 0) {
                 if constexpr (SPLIT) issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1), 0, 2);
                 else issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1));
             }
@@ -249,12 +254,13 @@ __global__ __launch_bounds__(GM_THREADS) void gemm_kernel(
         }
         // (a plain s_barrier: __syncthreads would also drain the two younger steps' loads)
         // (younger loads that may stay in flight: the steps t+2 .. t+NS-2 and what this step has issued so far)
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA - (SPLIT ? NDMA / 2 : 0)) : "memory");
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((NS - 2) * NDMA - (SPLIT ? NDMA / 2 : SPREAD ? LAST_PART : 0)) : "memory");
         __builtin_amdgcn_s_barrier();
         asm volatile("" ::: "memory");
         read_frags(KC & 1, (slab + 1) % NS, 0);
         // second half of this step's loads: same slab (free since the barrier of the step before)
         if constexpr (SPLIT) issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1), 1, 2);
+        if constexpr (SPREAD) issue_loads((slab + NS - 1) % NS, k_of(t + NS - 1), KC - 1, KC);
         multiply((KC - 1) & 1);
         if constexpr (NMFMA >= NFRAG) {
             VITCOP_INTERLEAVE(0x100, NFRAG)
