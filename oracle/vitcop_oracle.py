@@ -162,7 +162,7 @@ def k_norms(k, vis_start: int, n_vis: int) -> np.ndarray:
     kk = bf16_to_f64(k)
     B, T = kk.shape[0], kk.shape[1]
     assert 0 <= vis_start and vis_start + n_vis <= T
-    rows = kk[:, vis_start:vis_start + n_vis].reshape(B, n_vis, -1)
+    rows = kk[:, vis_start:vis_start + n_vis].reshape(B, n_vis, kk.shape[2] * kk.shape[3])    # (n_vis may be 0)
     return np.sqrt((rows * rows).sum(axis=2))
 
 

@@ -465,13 +465,17 @@ class DecoderLayerPlan:
     wo, wg, wu, wd."""
 
     def __init__(self, h, positions, w: dict, Hq: int, Hkv: int, d: int, vis_start: int, n_vis: int, keep: int,
-                 eps: float = 1e-5, theta: float = 10000.0, caches=None):
-        """``caches`` = (k_cache, v_cache) [B, capacity, Hkv, d]: the layer writes its KV cache there."""
+                 eps: float = 1e-5, theta: float = 10000.0, caches=None, n_vis_samples=None):
+        """``caches`` = (k_cache, v_cache) [B, capacity, Hkv, d]: the layer writes its KV cache there.
+        ``n_vis_samples``: int32 device tensor [B] for a right-padded batch (sample b has that many of the
+        n_vis visual tokens, its text follows them, the rest of its rows is padding); ``n_vis_out`` then holds
+        the counts after the layer."""
         B, T, D = h.shape
         F = w["wg"].shape[0]
         Tp = T - n_vis + keep
         dev = h.device
-        self.tensors = (h, positions, w, caches)
+        self.tensors = (h, positions, w, caches, n_vis_samples)
+        self.n_vis_out = torch.empty((B,), dtype=torch.int32, device=dev) if n_vis_samples is not None else None
         kc, vc = caches if caches is not None else (None, None)
         self.y = torch.empty((B, Tp, D), dtype=h.dtype, device=dev)
         self.keep_idx = torch.empty((B, Tp), dtype=torch.int32, device=dev)
@@ -481,7 +485,8 @@ class DecoderLayerPlan:
                                   _ptr(positions), _ptr(w["ln1"]), _ptr(w["ln2"]), _ptr(w["wq"]), _ptr(w["wk"]),
                                   _ptr(w["wv"]), _ptr(w["wo"]), _ptr(w["wg"]), _ptr(w["wu"]), _ptr(w["wd"]),
                                   _ptr(self.y), _ptr(self.keep_idx), _ptr(self.positions_out), _ptr(self.norms),
-                                  _ptr(kc), _ptr(vc), kc.shape[1] if kc is not None else 0)
+                                  _ptr(kc), _ptr(vc), kc.shape[1] if kc is not None else 0, _ptr(n_vis_samples),
+                                  _ptr(self.n_vis_out))
         nb = lib.vitcop_decoder_layer_workspace_bytes(C.byref(self.desc))
         if nb == 0:
             raise VitcopError(VITCOP_EINVAL, vitcop_last_error())

@@ -383,3 +383,45 @@ def test_full_schedule_batch_with_different_counts(vc, seeds):
             L = want_len[l][b]                            # the step appended at the sample's own row
             assert_stream_close(host_f64(kc[b:b + 1, L]), O.bf16_to_f64(k_row), f"appended K, sample {b}, layer {l}")
             assert_stream_close(host_f64(vcache[b:b + 1, L]), O.bf16_to_f64(v_row), f"appended V, sample {b}, layer {l}")
+
+
+def test_decoder_layer_right_padded_batch(vc):
+    # a right-padded batch given directly to the layer: samples with all, some, one and none of the n_vis visual
+    # tokens; every sample's real rows must equal the layer run on that sample alone (the oracle, on the sample's
+    # own rows, with its own count and min(keep, count) survivors)
+    B, D, Hq, Hkv, d, F, vs, nv, tail, keep = 4, 256, 4, 2, 128, 384, 7, 90, 9, 40
+    counts = [90, 55, 1, 0]
+    T = vs + nv + tail
+    c = I.decoder_inputs(9700, B, T, D, Hq, Hkv, d, F)
+    h = c["h"].copy()
+    pos = np.stack([3 * np.arange(T) + b for b in range(B)]).astype(np.int32)
+    for b, n_b in enumerate(counts):                     # text directly after the sample's own visual tokens
+        real = vs + n_b + tail
+        h[b, vs + n_b:real] = c["h"][b, vs + nv:]
+        h[b, real:] = 0                                  # padding rows
+        pos[b, vs + n_b:real] = pos[b, vs + nv:].copy()
+        pos[b, real:] = 0
+    wd = {k: dev(v) for k, v in c["w"].items()}
+    plan = vc.DecoderLayerPlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, keep,
+                               n_vis_samples=torch.tensor(counts, dtype=torch.int32, device="cuda"))
+    plan.run()
+    torch.cuda.synchronize()
+    y, idx, p_out = host_f64(plan.y), plan.keep_idx.cpu().numpy(), plan.positions_out.cpu().numpy()
+    norms = plan.norms.cpu().numpy()
+    assert plan.n_vis_out.cpu().tolist() == [min(keep, n_b) for n_b in counts]
+    assert y.shape[1] == T - nv + keep
+    for b, n_b in enumerate(counts):
+        real, k_b = vs + n_b + tail, min(keep, n_b)
+        out_real = vs + k_b + tail
+        ref = Dc.decoder_layer(h[b:b + 1, :real], c["w"], Hq, Hkv, d, vs, n_b, k_b, pos[b:b + 1, :real])
+        assert np.allclose(norms[b, :n_b], ref["norms"][0], rtol=2e-3) and not norms[b, n_b:].any()
+        if k_b:
+            assert_selection_matches(idx[b, vs:vs + k_b] - vs, norms[b, :n_b], ref["norms"][0], k_b, False, f"sample {b}")
+        assert np.array_equal(idx[b, :vs], np.arange(vs))
+        assert np.array_equal(idx[b, vs + k_b:out_real], np.arange(vs + n_b, real))
+        assert (idx[b, out_real:] == T - 1).all()
+        if not np.array_equal(idx[b, :out_real], ref["keep_idx"][0]):
+            ref = Dc.decoder_layer(h[b:b + 1, :real], c["w"], Hq, Hkv, d, vs, n_b, k_b, pos[b:b + 1, :real],
+                                   keep_idx=idx[b:b + 1, :out_real])
+        assert np.array_equal(p_out[b, :out_real], ref["positions"][0])
+        assert_stream_close(y[b:b + 1, :out_real], ref["y"], f"right-padded batch, sample {b}")
