@@ -529,13 +529,32 @@ static TileId choose_tile(int M, int N, int K, bool need_sumsq, int align_n) {
 // 258 tiles of 256 x 256) would spend a whole extra round on them.  Then only the leading columns, as many
 // column tiles as fill the whole rounds, go out on the big tiles, and the few trailing columns follow as a
 // launch of their own on the few-row / split-K path, which spreads them over the chip.  Returns the number
-// of leading columns (N: no cut) and, in `id`, the tile shape for them.  The tail is priced at 0.3 of a
-// 256 x 256 tile time (its launch and its reduction).
+// of leading columns (N: no cut) and, in `id`, the tile shape for them.  A small tail (at most 64 tiles'
+// worth) is priced at 0.3 of a 256 x 256 tile time (its launch and its reduction); a larger one goes out on
+// whichever tile shape suits its own size and is priced as that launch plus the boundary between the two
+// (5120 x 4096: 320 tiles of 256 x 256 are 1.25 rounds; 240 of them and then 160 tiles of 256 x 128 are
+// one round each at their rates, 1.57 tile times instead of 2).
 constexpr int GM_TAIL_MAX_TILES = 64;
-static int main_columns(TileId& id, int M, int N, int K, bool need_sumsq, int align_n) {
+constexpr float GM_TAIL_BOUNDARY = 0.08f;
+static float plain_cost(int M, int N, bool need_sumsq, int align_n) {
+    float best = 1e30f;
+    for (int i = 0; i < T128x32; ++i) {
+        const TileShape& t = kTiles[i];
+        if (need_sumsq && !t.sumsq) continue;
+        if (align_n % t.bn != 0) continue;
+        best = std::min(best, tile_cost(t, M, N));
+    }
+    return best;
+}
+static int main_columns(TileId& id, int M, int N, int K, bool need_sumsq, int align_n, float* cost_out = nullptr) {
     if (id == T128x32) return N;
     float best = tile_cost(kTiles[id], M, N);
     int best_n = N;
+    struct Report {              // the cost of the plan that is returned
+        float* out;
+        const float& v;
+        ~Report() { if (out) *out = v; }
+    } report{cost_out, best};
     for (int i = 0; i < T128x32; ++i) {
         const TileShape& t = kTiles[i];
         if (need_sumsq && !t.sumsq) continue;
@@ -544,8 +563,14 @@ static int main_columns(TileId& id, int M, int N, int K, bool need_sumsq, int al
         const int rounds = (tiles_m * tiles_n + 255) / 256;
         if (rounds < 2) continue;
         const int keep_n = (rounds - 1) * 256 / tiles_m;              // column tiles that fill the whole rounds
-        if (keep_n < 1 || keep_n >= tiles_n || (tiles_n - keep_n) * tiles_m > GM_TAIL_MAX_TILES) continue;
-        const float c = (float)(rounds - 1) * (float)(t.bm * t.bn) / (65536.0f * t.rate) + 0.3f;
+        if (keep_n < 1 || keep_n >= tiles_n) continue;
+        const bool small_tail = (tiles_n - keep_n) * tiles_m <= GM_TAIL_MAX_TILES;
+        // (a large tail is priced as a plain launch: with at most 1024 rows it would be cut into k-slices instead;
+        // and the tail of a pair must start where the second matrix does, or stay inside it: it is one launch)
+        if (!small_tail && (M <= 1024 || (align_n != 768 && keep_n * t.bn < align_n))) continue;
+        const float tail = small_tail ? 0.3f
+                                      : plain_cost(M, N - keep_n * t.bn, need_sumsq, 768) + GM_TAIL_BOUNDARY;
+        const float c = (float)(rounds - 1) * (float)(t.bm * t.bn) / (65536.0f * t.rate) + tail;
         if (c < best) {
             best = c;
             best_n = keep_n * t.bn;
@@ -713,7 +738,7 @@ int launch_gemm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint1
         const size_t need_tail = n_main < N ? std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
                                                        splitk_workspace_bytes(M, N - n_main, K))
                                             : 0;
-        if (need_tail && ws_bytes >= need_tail) {
+        if (n_main < N && ws_bytes >= need_tail) {
             int rc = launch_tile(id, x, x_stride, w, y, y_stride, res, res_stride, M, n_main, K, sumsq_parts, nullptr,
                                  nullptr, 0, s);
             if (rc) return rc;
@@ -745,11 +770,12 @@ int launch_gemm_norm_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w, 
 
 // out = silu(x Wg^T) * (x Wu^T) as ONE launch of the big tiles: a tile's columns are half gate, half up, and the
 // epilogue applies the activation (GM_EPI_GATED), so gate and up never reach memory.
+// (F columns of an output whose rows are out_stride apart)
 static int launch_tile_gated(TileId id, const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu,
-                             uint16_t* out, int M, int F, int K, hipStream_t s) {
+                             uint16_t* out, int64_t out_stride, int M, int F, int K, hipStream_t s) {
 #define VITCOP_GATED(BM, BN) \
-    return launch_gemm_k<BM, BN, 2, 2, GM_EPI_GATED>(K, x, x_stride, wg, out, F, nullptr, 0, M, F, K, nullptr, wu, \
-                                                     nullptr, 0, s)
+    return launch_gemm_k<BM, BN, 2, 2, GM_EPI_GATED>(K, x, x_stride, wg, out, out_stride, nullptr, 0, M, F, K, nullptr, \
+                                                     wu, nullptr, 0, s)
     switch (id) {
         case T256x256: VITCOP_GATED(256, 256);
         case T192x256: VITCOP_GATED(192, 256);
@@ -769,18 +795,57 @@ int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg
     if (ws && need && ws_bytes >= need && F % 128 == 0)
         return launch_gemm_skinny_gated(x, x_stride, wg, wu, F, out, M, K, ws, s);
     // more rows than the few-row kernel takes: the big tiles with the activation in their epilogue, unless the
-    // launch is one that gets cut (k-slices for a few hundred rows, trailing columns on a path of their own):
-    // those produce gate and up separately
+    // launch is one that gets cut into k-slices or sends a few trailing tiles down a path of their own (a few
+    // hundred rows): those produce gate and up separately.  A large tail (many rows, whole rounds plus a part
+    // of one) stays on this path: first the columns that fill the whole rounds, then the rest on the tiles
+    // that suit it.
     if (F % 8 == 0 && splitk_plan(M, 2 * F, K).splits == 0) {
-        TileId id = choose_tile(M, 2 * F, K, false, 768);
-        const bool two_by_two = id == T256x256 || id == T192x256 || id == T256x128 || id == T192x128 || id == T128x128;
-        TileId cut_id = id;
-        const bool cut = ws && F % 128 == 0 && main_columns(cut_id, M, 2 * F, K, false, F) < 2 * F;
-        // a few hundred rows leave the 256-column tiles a third of the CUs short (317 x 22016: 172 tiles);
-        // 192 x 192 tiles (230) fill them
-        if (two_by_two && !cut && tile_cost(kTiles[T192x192G], M, 2 * F) < tile_cost(kTiles[id], M, 2 * F))
-            id = T192x192G;
-        if (two_by_two && !cut) return launch_tile_gated(id, x, x_stride, wg, wu, out, M, F, K, s);
+        const uint16_t *g_w = wg, *u_w = wu;
+        uint16_t* o = out;
+        int f_left = F;
+        bool fused = true;
+        while (f_left > 0) {
+            TileId id = choose_tile(M, 2 * f_left, K, false, 768);
+            if (id == T128x128R) id = T128x128;
+            const bool first = f_left == F;              // only the whole launch may still go the separate way
+            if (!(id == T256x256 || id == T192x256 || id == T256x128 || id == T192x128 || id == T128x128)) {
+                if (first) {
+                    fused = false;
+                    break;
+                }
+                id = T128x128;
+            }
+            TileId cut_id = id;
+            float cut_cost = 0.f;
+            int n_main = ws && f_left % 128 == 0 ? main_columns(cut_id, M, 2 * f_left, K, false, 768, &cut_cost)
+                                                 : 2 * f_left;
+            // (the 192 x 192 tiles exist in this form only: a cut must beat them too)
+            if (cut_id == T128x128R || cut_cost >= tile_cost(kTiles[T192x192G], M, 2 * f_left)) n_main = 2 * f_left;
+            int f_now = f_left;
+            if (n_main < 2 * f_left) {
+                const TileShape& t = kTiles[cut_id];
+                const int tail_tiles = (2 * f_left - n_main + t.bn - 1) / t.bn * ((M + t.bm - 1) / t.bm);
+                if (tail_tiles <= GM_TAIL_MAX_TILES && first) {  // the small-tail cut: separate gate and up
+                    fused = false;
+                    break;
+                }
+                if (tail_tiles > GM_TAIL_MAX_TILES) {
+                    id = cut_id;
+                    f_now = n_main / 2;
+                }
+            } else if (tile_cost(kTiles[T192x192G], M, 2 * f_left) < tile_cost(kTiles[id], M, 2 * f_left)) {
+                // a few hundred rows leave the 256-column tiles a third of the CUs short (317 x 22016: 172
+                // tiles); 192 x 192 tiles (230) fill them
+                id = T192x192G;
+            }
+            int rc = launch_tile_gated(id, x, x_stride, g_w, u_w, o, F, M, f_now, K, s);
+            if (rc) return rc;
+            g_w += (int64_t)f_now * K;
+            u_w += (int64_t)f_now * K;
+            o += f_now;
+            f_left -= f_now;
+        }
+        if (fused) return VITCOP_OK;
     }
     int rc = launch_gemm_pair_ws(x, x_stride, wg, gate, F, wu, up, F, M, K, ws, ws_bytes, s);
     if (rc) return rc;
@@ -813,11 +878,11 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
         const int N = N1 + N2;
         TileId id = choose_tile(M, N, K, false, N1);
         const int n_main = main_columns(id, M, N, K, false, N1);
-        const size_t need_tail = n_main < N && n_main >= N1
-                                     ? std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
+        const bool cut = n_main < N && n_main >= N1;
+        const size_t need_tail = cut ? std::max(gemm_skinny_workspace_bytes(M, N - n_main, K),
                                                 splitk_workspace_bytes(M, N - n_main, K))
                                      : 0;
-        if (need_tail && ws_bytes >= need_tail) {
+        if (cut && ws_bytes >= need_tail) {
             int rc = launch_tile(id, x, x_stride, w1, y1, N1, nullptr, 0, M, n_main, K, nullptr, w2, y2, N1, s);
             if (rc) return rc;
             return launch_gemm_ws(x, x_stride, w2 + (int64_t)(n_main - N1) * K, y2 + (n_main - N1), N2, nullptr, 0, M,
