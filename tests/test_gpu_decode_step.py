@@ -170,3 +170,43 @@ def test_decode_step_in_a_hip_graph(vc, B):
         assert torch.equal(plan.y, y_eager), f"replay {rep}"
         for (kc, _), n, row in zip(caches, n_cached, rows_eager):
             assert torch.equal(kc[:, n], row), f"replay {rep}: appended K"
+
+
+@pytest.mark.parametrize("B,dims,lengths", [
+    (3, RAGGED, ((40, 0, 17), (9, 33, 33))),                       # weight-streaming kernels; an empty cache
+    (2, CUT, ((64, 65), (1, 200))),
+    (6, RAGGED, ((50, 3, 0, 50, 21, 64), (20, 20, 19, 1, 7, 0)))])  # few-row matrix-core kernels
+def test_decode_step_per_sample_cache_lengths(vc, B, dims, lengths):
+    # every sample with a cache length of its own in every layer (what a batched Stage II leaves behind):
+    # sample b's row of the output, and the rows it appends, against the oracle run on that sample alone
+    D, Hq, Hkv, d, F = dims
+    cap = 256
+    n_layers = len(lengths)
+    h, layers = model(7500 + B + D, n_layers, B, 1, D, Hq, Hkv, d, F)
+    h = h[:, 0]
+    pos = np.array([300 + 11 * b for b in range(B)], dtype=np.int32)
+    filled = [(I.normal_bf16(7600 + l, 0, (B, cap, Hkv, d)), I.normal_bf16(7600 + l, 1, (B, cap, Hkv, d)))
+              for l in range(n_layers)]
+    caches = []
+    for (k, v), ns in zip(filled, lengths):
+        kc, vcache = cache_pair(B, cap, Hkv, d)
+        for b, n in enumerate(ns):
+            kc[b, :n] = dev(k[b, :n])
+            vcache[b, :n] = dev(v[b, :n])
+        caches.append((kc, vcache))
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    plan = vc.DecoderDecodePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, caches,
+                                [list(ns) for ns in lengths])
+    y = host_f64(plan.run())
+    torch.cuda.synchronize()
+    for b in range(B):
+        own = [(k[b:b + 1, :ns[b]], v[b:b + 1, :ns[b]]) for (k, v), ns in zip(filled, lengths)]
+        ref = Dc.decode_step(h[b:b + 1], layers, own, pos[b:b + 1], Hq, Hkv, d)
+        assert_stream_close(y[b:b + 1], ref["y"], f"decode step output, sample {b}")
+        n0 = lengths[0][b]
+        rope_close(host_bits(caches[0][0])[b, n0], ref["appended"][0][0][0], f"appended K, sample {b}")
+        v_close(O.bf16_to_f64(host_bits(caches[0][1])[b, n0]), O.bf16_to_f64(ref["appended"][0][1][0]))
+        for (kc, vcache), (k, v), ns in zip(caches, filled, lengths):    # cached rows untouched, nothing past the new one
+            n = ns[b]
+            assert np.array_equal(host_bits(kc)[b, :n], k[b, :n]) and np.array_equal(host_bits(vcache)[b, :n], v[b, :n])
+            assert not host_bits(kc)[b, n + 1:].any() and not host_bits(vcache)[b, n + 1:].any()
