@@ -212,9 +212,11 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 }
 
 // ---------------------------------------------------------------------------
-// Wide variant for long sequences: a workgroup owns 256 queries, each of its 4
-// wavefronts 64 of them (two 32-query blocks), so every K and V^T fragment read
-// from LDS feeds two MFMAs.  K and V tiles (64 keys) arrive by direct
+// The kernel for head dimension 128 (the one above remains for 64, and for K/V spans beyond 32-bit byte
+// offsets).  A workgroup of 4 wavefronts owns 128 U queries, each wavefront U blocks of 32: with U = 2 (long
+// sequences) every K and V^T fragment read from LDS feeds two MFMAs; with U = 1 (the few hundred tokens that
+// survive pruning) a wavefront's chain per key tile is half as long and there are twice the workgroups.
+// K and V tiles (64 keys) arrive by direct
 // global -> LDS loads into a ring of four stages; both stay row-major in LDS,
 // padded per KiB; V^T fragments come from the transposing LDS read
 // (ds_read_b64_tr_b16), so nothing is staged in or shuffled through registers.
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(AT_THREADS) void attn_kernel(
 // more than 2^8 (the accumulators are rescaled then); the normalisation at the
 // end makes the result independent of which reference was used.
 // ---------------------------------------------------------------------------
-constexpr int AW_BM = 256;
+constexpr int AW_BM = 256;            // queries per workgroup with two query blocks per wavefront (128 with one)
 constexpr int AW_BN = 64;
 // LDS layout of a 64-key tile (rows of 256 B): one direct-to-LDS load writes 1 KiB = the four
 // rows {i, i+16, i+32, i+48}, so row r sits at (r % 16) * (1024 + pad) + (r / 16) * 256.
@@ -259,9 +261,9 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
-// Vector work of the softmax of one 32-key stage (both query blocks), as a list of single
-// instructions in issue order.  The pipeline block below cuts the list into 32 runs and puts
-// one run behind each of its 32 MFMAs, with scheduling barriers in between, so that the
+// Vector work of the softmax of one 32-key stage (all query blocks of the wavefront), as a list of single
+// instructions in issue order.  The pipeline block below cuts the list into as many runs as it has MFMAs
+// (16 per query block) and puts one run behind each, with scheduling barriers in between, so that the
 // matrix pipe and the vector pipe stay busy together; the order keeps every instruction a
 // few issue slots away from the producer of its operands.
 //   kinds: MASK (diagonal and ragged tiles only) score := -inf where the key is not visible;
@@ -278,41 +280,45 @@ enum SmKind : int { SM_MASK, SM_MAX5, SM_MAX3, SM_FMA, SM_EXP, SM_ADD2, SM_CVT, 
 struct SmOp {
     int kind, u, i;
 };
-constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3) + 2 * (16 + 16 + 8 + 8 + 2);
+constexpr int SM_NOPS = 2 * 16 + 2 * (5 + 3) + 2 * (16 + 16 + 8 + 8 + 2);      // for two query blocks
 struct SmTable {
     SmOp op[SM_NOPS];
     int start[33];       // run r is op[start[r]] .. op[start[r+1]-1]
     int check;           // the reference check sits between run check-1 and run check
+    int slots;           // runs = MFMAs of a pipeline block: 16 per query block
 };
-constexpr SmTable make_sm_table(bool masked) {
+// U query blocks per wavefront (1 or 2)
+constexpr SmTable make_sm_table(bool masked, int U) {
     SmTable t{};
     int n = 0;
+    const int slots = 16 * U;
+    t.slots = slots;
     if (masked)
-        for (int i = 0; i < 16; ++i) { t.op[n++] = {SM_MASK, 0, i}; t.op[n++] = {SM_MASK, 1, i}; }
-    // part 1, the two query blocks interleaved
-    for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 0, i};
-    for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, 1, i};
-    for (int i = 0; i < 3; ++i) { t.op[n++] = {SM_MAX3, 0, i}; t.op[n++] = {SM_MAX3, 1, i}; }
+        for (int i = 0; i < 16; ++i)
+            for (int u = 0; u < U; ++u) t.op[n++] = {SM_MASK, u, i};
+    // part 1, the query blocks interleaved
+    for (int u = 0; u < U; ++u)
+        for (int i = 0; i < 5; ++i) t.op[n++] = {SM_MAX5, u, i};
+    for (int i = 0; i < 3; ++i)
+        for (int u = 0; u < U; ++u) t.op[n++] = {SM_MAX3, u, i};
     const int n1 = n;
     // part 2 in groups of four scores (group g: query block g / 4, scores 4 (g % 4) ..+3),
     // software pipelined: arguments of group ph, exponentials of group ph-1, sums and packing
     // of group ph-2; the tree of a query block follows two phases after its last pair sums
-    for (int ph = 0; ph < 13; ++ph) {
-        if (ph < 8)
+    for (int ph = 0; ph < 4 * U + 5; ++ph) {
+        if (ph < 4 * U)
             for (int i = 0; i < 4; ++i) t.op[n++] = {SM_FMA, ph / 4, 4 * (ph % 4) + i};
-        if (ph >= 1 && ph < 9)
+        if (ph >= 1 && ph < 4 * U + 1)
             for (int i = 0; i < 4; ++i) t.op[n++] = {SM_EXP, (ph - 1) / 4, 4 * ((ph - 1) % 4) + i};
-        if (ph >= 2 && ph < 10) {
+        if (ph >= 2 && ph < 4 * U + 2) {
             const int g = ph - 2;
             for (int i = 0; i < 2; ++i) t.op[n++] = {SM_ADD2, g / 4, 2 * (g % 4) + i};
             for (int i = 0; i < 2; ++i) t.op[n++] = {SM_CVT, g / 4, 2 * (g % 4) + i};
         }
-        if (ph == 7)                                // query block 0: pair sums done in phase 5
-            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, 0, i};
-        if (ph == 11)                               // query block 1: pair sums done in phase 9
-            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, 1, i};
+        if (ph >= 7 && (ph - 7) % 4 == 0 && (ph - 7) / 4 < U)       // query block u: pair sums done in phase 4u + 5
+            for (int i = 0; i < 2; ++i) t.op[n++] = {SM_TREE, (ph - 7) / 4, i};
     }
-    // split into 32 runs of about equal issue time (a mask is a compare and a select, an
+    // split into `slots` runs of about equal issue time (a mask is a compare and a select, an
     // exponential takes twice as long as a plain instruction, a pair sum from the third on is two
     // adds); part 1 gets whole runs
     auto weight = [](const SmOp& o) {
@@ -322,7 +328,7 @@ constexpr SmTable make_sm_table(bool masked) {
     for (int k = 0; k < n1; ++k) w1 += weight(t.op[k]);
     for (int k = n1; k < n; ++k) w2 += weight(t.op[k]);
     const int w_check = 6;       // compare, branch and the registers the rare path sets up
-    int runs1 = ((w1 + w_check) * 32 + (w1 + w_check + w2) / 2) / (w1 + w_check + w2);
+    int runs1 = ((w1 + w_check) * slots + (w1 + w_check + w2) / 2) / (w1 + w_check + w2);
     if (runs1 < 1) runs1 = 1;
     t.check = runs1;
     int acc = 0, r = 0;
@@ -333,23 +339,25 @@ constexpr SmTable make_sm_table(bool masked) {
     }
     while (r < runs1) t.start[++r] = n1;
     acc = 0;
-    const int runs2 = 32 - runs1;
+    const int runs2 = slots - runs1;
     for (int k = n1; k < n; ++k) {
         acc += weight(t.op[k]);
-        while (r < 31 && acc * runs2 >= w2 * (r - runs1 + 1)) t.start[++r] = k + 1;
+        while (r < slots - 1 && acc * runs2 >= w2 * (r - runs1 + 1)) t.start[++r] = k + 1;
     }
-    while (r < 32) t.start[++r] = n;
+    while (r < slots) t.start[++r] = n;
     return t;
 }
-constexpr SmTable SM_TABLE_PLAIN = make_sm_table(false);
-constexpr SmTable SM_TABLE_MASKED = make_sm_table(true);
+template <int U, bool MASKED>
+constexpr SmTable SM_TABLE_OF = make_sm_table(MASKED, U);
 
-template <bool CAUSAL>
+template <bool CAUSAL, int U>
 __global__ __launch_bounds__(256) void attn_wide_kernel(
     const uint16_t* __restrict__ q, const uint16_t* __restrict__ k,
     const uint16_t* __restrict__ v, uint16_t* __restrict__ out, float* __restrict__ lse,
     int N, int Hq, int Hkv, float scale_log2e, int n_qb, int n_heads, int group) {
     extern __shared__ __attribute__((aligned(1024))) char aw_lds[];
+    static_assert(U == 1 || U == 2, "query blocks per wavefront");
+    constexpr int BM = 128 * U, QW = 32 * U;       // queries per workgroup and per wavefront
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -377,13 +385,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     const int hk = __builtin_amdgcn_readfirstlane(h / (Hq / Hkv));
     // Query blocks are aligned to the END of the sequence: a ragged block is then the first one,
     // which has the fewest keys to waste wavefronts on (query indices below 0 do not exist).
-    const int q0 = N - (n_qb - qb) * AW_BM, wq0 = q0 + 64 * wv;
+    const int q0 = N - (n_qb - qb) * BM, wq0 = q0 + QW * wv;
     const int64_t q_rs = (int64_t)Hq * AT_D, kv_rs = (int64_t)Hkv * AT_D;
 
-    // Q^T fragments of the two query blocks
-    bf16x8 qf[2][8];
+    // Q^T fragments of the query blocks
+    bf16x8 qf[U][8];
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int query = max(wq0 + 32 * u + l32, 0);
         const uint16_t* qp = q + ((int64_t)b * N + query) * q_rs + h * AT_D + 8 * g;
 #pragma unroll
@@ -394,13 +402,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // the softmax for the 256 vector registers (they would be evicted and copied back before
     // every use).
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int dc = 0; dc < 8; ++dc) asm volatile("" : "+a"(qf[u][dc]));
 
-    f32x16 o[2][4];
+    f32x16 o[U][4];
 #pragma unroll
-    for (int u = 0; u < 2; ++u)
+    for (int u = 0; u < U; ++u)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -408,12 +416,18 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // per query: reference of the exponentials (log2 units), the raw score above which it must be
     // raised, (reference + gap) / scale, and the running denominator
     // (the threshold starts finite so that "maximum - threshold" is never inf - inf)
-    float m_ref[2] = {-INFINITY, -INFINITY}, thr[2] = {-3.0e38f, -3.0e38f}, l_run[2] = {0.f, 0.f};
+    float m_ref[U], thr[U], l_run[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        m_ref[u] = -INFINITY;
+        thr[u] = -3.0e38f;
+        l_run[u] = 0.f;
+    }
 
-    const int kend = CAUSAL ? min(N, q0 + AW_BM) : N;
+    const int kend = CAUSAL ? min(N, q0 + BM) : N;
     const int ntiles = (kend + AW_BN - 1) / AW_BN;                 // tiles the workgroup streams
-    const int wave_kend = CAUSAL ? wq0 + 64 : N;                   // keys this wavefront needs
-    const int my_tiles = wq0 + 64 > 0 ? (wave_kend + AW_BN - 1) / AW_BN : 0;
+    const int wave_kend = CAUSAL ? wq0 + QW : N;                   // keys this wavefront needs
+    const int my_tiles = wq0 + QW > 0 ? (wave_kend + AW_BN - 1) / AW_BN : 0;
     // tiles whose 64 keys are visible to all 64 queries and lie inside the sequence: no masking
     const int full_tiles = min(CAUSAL ? max(wq0, 0) / AW_BN : N / AW_BN, min(N / AW_BN, my_tiles));
     const char* kbase = reinterpret_cast<const char*>(k + (int64_t)b * N * kv_rs + hk * AT_D);
@@ -461,14 +475,14 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         for (int j = 0; j < 8; ++j) issue_one(t, j);
     };
 
-    // Software pipeline over "stages" of 32 keys (two per tile).  For stage c, with both query
-    // blocks: S(c) = 16 MFMAs, softmax(c) = vector work, PV(c) = 16 MFMAs.  One straight-line
+    // Software pipeline over "stages" of 32 keys (two per tile).  For stage c, with all U query
+    // blocks: S(c) = 8 U MFMAs, softmax(c) = vector work, PV(c) = 8 U MFMAs.  One straight-line
     // block per stage holds softmax(c) next to the MFMAs of PV(c-1) and S(c+1), which do not
     // depend on it; the two MFMA streams are interleaved so that no accumulator is touched
     // twice in a row.  Score accumulators and probability fragments are double buffered by
     // stage parity.
-    f32x16 s[2][2];                  // [parity][query block]
-    bf16x8 pf[2][2][2];              // [parity][query block][16-key half]
+    f32x16 s[2][U];                  // [parity][query block]
+    bf16x8 pf[2][U][2];              // [parity][query block][16-key half]
 
     // lane roles for the transposing V^T read: lane = 16*h16 + 4*e + a supplies the address of
     // key (.. + e), channels 16*(h16&1) + 4*a .. +3; it receives channel (lane & 31), 4 keys
@@ -498,14 +512,15 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     auto scores_only = [&](int par, int t, int kt) __attribute__((always_inline)) {   // prologue: S of the first stage
         const unsigned Ks = k_lane + (t % AW_STAGES) * AW_STAGE + kt * 512;
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[par][u][r] = 0.f;
 #pragma unroll
         for (int dc = 0; dc < 8; ++dc) {
             const bf16x8 a = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + dc * 32);
-            s[par][0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[0][dc], s[par][0], 0, 0, 0);
-            s[par][1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[1][dc], s[par][1], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                s[par][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[u][dc], s[par][u], 0, 0, 0);
         }
     };
     auto values_only = [&](int par, int set) __attribute__((always_inline)) {   // drain: PV of the last stage
@@ -514,8 +529,9 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
             typedef __attribute__((ext_vector_type(8))) short s16x8;
             const s16x8 both = __builtin_shufflevector(vlo[set][n.value], vhi[set][n.value], 0, 1, 2, 3, 4, 5, 6, 7);
             const bf16x8 a = __builtin_bit_cast(bf16x8, both);
-            o[0][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][0][tt], o[0][db], 0, 0, 0);
-            o[1][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][1][tt], o[1][db], 0, 0, 0);
+#pragma unroll
+            for (int u = 0; u < U; ++u)
+                o[u][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, pf[par][u][tt], o[u][db], 0, 0, 0);
         });
     };
 
@@ -525,7 +541,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     // stage c+2 = (tile t+1, half par) and the V rows of stage c = (tile t, half par).
     auto stage_block = [&](int par, int t, auto masked_c, bool has_prev) __attribute__((always_inline)) {
         constexpr bool MASKED = decltype(masked_c)::value;
-        constexpr const SmTable& SM_TABLE = MASKED ? SM_TABLE_MASKED : SM_TABLE_PLAIN;
+        constexpr int SLOTS = 16 * U;
         const int key0 = t * AW_BN + 32 * par;
         // The fragments requested a whole block ago have long arrived; saying so here (a wait on
         // the LDS counter alone) spares the block partial waits: with its own 24 requests queued
@@ -537,18 +553,20 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         asm("" : "+v"(Vs));
         // diagonal and ragged tiles: key key0 + 4g + 8(r/4) + r%4 of register r is visible to
         // the lane's query iff it is <= min(query, N-1), i.e. iff 8(r/4) + r%4 <= lim
-        int lim[2] = {0, 0};
+        int lim[U] = {};
         if constexpr (MASKED) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < U; ++u) {
                 const int query = max(wq0 + 32 * u + l32, 0);      // rows below 0 are never stored
                 lim[u] = (CAUSAL ? min(query, N - 1) : N - 1) - key0 - 4 * g;
             }
         }
         // state of the vector work (see SmKind)
-        float m5[2][5], m3[2][3], alpha[2] = {1.f, 1.f};
-        float e[2][16], ps[2][2];
-        uint32_t pk[2][8];
+        float m5[U][5], m3[U][3], alpha[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) alpha[u] = 1.f;
+        float e[U][16], ps[U][2];
+        uint32_t pk[U][8];
         bool moved = false;          // wave-uniform: some query of this wavefront raised its reference
         auto vector_op = [&](auto kc, auto uc, auto ic) __attribute__((always_inline)) {
             constexpr int kind = kc.value, u = uc.value, i = ic.value;
@@ -587,10 +605,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         // same query, so both decide alike), new reference, alpha = exp2(old - new) (exp2(-inf) = 0 at
         // the start) for the rescaling at the end of the block, new threshold.
         auto check_reference = [&]() __attribute__((always_inline)) {
-            if (__builtin_expect(__builtin_amdgcn_ballot_w64(fmaxf(m3[0][2], m3[1][2]) > 0.f) != 0, 0)) {
+            float excess = m3[0][2];
+#pragma unroll
+            for (int u = 1; u < U; ++u) excess = fmaxf(excess, m3[u][2]);
+            if (__builtin_expect(__builtin_amdgcn_ballot_w64(excess > 0.f) != 0, 0)) {
                 moved = true;
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < U; ++u) {
                     const float own = fmaxf(m3[u][0], m3[u][1]);
                     const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(own), __float_as_uint(own),
                                                                      false, false);
@@ -605,53 +626,55 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         };
         // S(c+1) accumulators
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int r = 0; r < 16; ++r) s[par ^ 1][u][r] = 0.f;
-        // 32 slots: one MFMA (the 16 of S(c+1) first, so that they are complete when the next
+        // 16 U slots: one MFMA (those of S(c+1) first, so that they are complete when the next
         // block reads them, then the 16 of PV(c-1)), one fragment request, one run of vector work
         auto run_slot = [&](auto slot) __attribute__((always_inline)) {
             constexpr int i = slot.value;
-            if constexpr (i < 16) {
-                constexpr int dc = i >> 1, u = i & 1;
+            if constexpr (i < 8 * U) {
+                constexpr int dc = i / U, u = i % U;
                 s[par ^ 1][u] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[par][dc], qf[u][dc], s[par ^ 1][u], 0, 0, 0);
             } else {
                 if (has_prev) {
-                    constexpr int n = (i - 16) >> 1, u = i & 1, tt = n >> 2, db = n & 3;
+                    constexpr int n = (i - 8 * U) / U, u = i % U, tt = n >> 2, db = n & 3;
                     typedef __attribute__((ext_vector_type(8))) short s16x8;
                     const s16x8 both = __builtin_shufflevector(vlo[par][n], vhi[par][n], 0, 1, 2, 3, 4, 5, 6, 7);
                     o[u][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both),
                                                                        pf[par ^ 1][u][tt], o[u][db], 0, 0, 0);
                 }
             }
-            // fragment requests at an even pace, 2 KiB per four slots (a K fragment is 1 KiB per wavefront,
+            // fragment requests at an even pace, 2 KiB per 2 U slots (a K fragment is 1 KiB per wavefront,
             // a V^T half 512 B): bunched together they saturate LDS for the four wavefronts in lock-step,
             // right when the tile loads issued after the barrier are writing into it
-            if constexpr ((i & 3) == 0) {
-                kfr[par ^ 1][i >> 2] = *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + (i >> 2) * 32);
-            } else if constexpr ((i & 1) == 1) {
-                constexpr int n = i >> 2, off = (n >> 2) * 256 + (n & 3) * 64;
-                if constexpr ((i & 2) == 0) vlo[par ^ 1][n] = lds_read_tr16(Vs + off);                 // keys of slots 0..3
+            if constexpr (i % (2 * U) == 0)
+                kfr[par ^ 1][i / (2 * U)] =
+                    *(const __attribute__((address_space(3))) bf16x8*)(uintptr_t)(Ks + (i / (2 * U)) * 32);
+            if constexpr (U == 1 || (i & 1) == 1) {
+                constexpr int half = i / U, n = half >> 1, off = (n >> 2) * 256 + (n & 3) * 64;
+                if constexpr ((half & 1) == 0) vlo[par ^ 1][n] = lds_read_tr16(Vs + off);              // keys of slots 0..3
                 else vhi[par ^ 1][n] = lds_read_tr16(Vs + off + 8 * AW_VGRP);                          // keys of slots 4..7
             }
-            static_for<SM_TABLE.start[i], SM_TABLE.start[i + 1]>([&](auto k) {
-                constexpr SmOp op = SM_TABLE.op[k.value];
+            static_for<SM_TABLE_OF<U, MASKED>.start[i], SM_TABLE_OF<U, MASKED>.start[i + 1]>([&](auto k) {
+                constexpr SmOp op = SM_TABLE_OF<U, MASKED>.op[k.value];
                 vector_op(std::integral_constant<int, op.kind>{}, std::integral_constant<int, op.u>{},
                           std::integral_constant<int, op.i>{});
             });
             __builtin_amdgcn_sched_barrier(0);
         };
-        static_for<0, SM_TABLE.check>(run_slot);
+        static_for<0, SM_TABLE_OF<U, MASKED>.check>(run_slot);
         check_reference();
         __builtin_amdgcn_sched_barrier(0);
-        static_for<SM_TABLE.check, 32>(run_slot);
+        static_for<SM_TABLE_OF<U, MASKED>.check, SLOTS>(run_slot);
         // the probabilities are consumed in the next block; without this pin the compiler sinks
         // their computation past the end of this block, away from the MFMAs it must hide behind
-        asm volatile("" ::"v"(pk[0][0]), "v"(pk[0][1]), "v"(pk[0][2]), "v"(pk[0][3]), "v"(pk[0][4]), "v"(pk[0][5]),
-                     "v"(pk[0][6]), "v"(pk[0][7]), "v"(pk[1][0]), "v"(pk[1][1]), "v"(pk[1][2]), "v"(pk[1][3]),
-                     "v"(pk[1][4]), "v"(pk[1][5]), "v"(pk[1][6]), "v"(pk[1][7]), "v"(l_run[0]), "v"(l_run[1]));
 #pragma unroll
-        for (int u = 0; u < 2; ++u)
+        for (int u = 0; u < U; ++u)
+            asm volatile("" ::"v"(pk[u][0]), "v"(pk[u][1]), "v"(pk[u][2]), "v"(pk[u][3]), "v"(pk[u][4]), "v"(pk[u][5]),
+                         "v"(pk[u][6]), "v"(pk[u][7]), "v"(l_run[u]));
+#pragma unroll
+        for (int u = 0; u < U; ++u)
 #pragma unroll
             for (int tt = 0; tt < 2; ++tt) {
                 u32x4 w;
@@ -662,7 +685,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
         // has been issued; PV(c) comes in the next block.
         if (__builtin_expect(moved, 0)) {
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < U; ++u)
 #pragma unroll
                 for (int db = 0; db < 4; ++db)
 #pragma unroll
@@ -717,7 +740,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
+    for (int u = 0; u < U; ++u) {
         const int query = wq0 + 32 * u + l32;                          // < N by construction
         const float l_tot = l_run[u] + __shfl_xor(l_run[u], 32, 64);
         if (query >= 0) {
@@ -739,7 +762,32 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(
     }
 }
 
-constexpr int AW_MIN_N = 512;      // below this the 128-query kernel is faster (measured at batch 1 to 8)
+constexpr int AW_U2_MIN_N = 512;   // a wavefront takes two query blocks from this length on,
+constexpr int AW_U2_MIN_WGS = 256;  // if that still leaves more workgroups than this
+
+template <bool CAUSAL, int U>
+static int launch_attn_wide(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out, float* lse,
+                            int B, int N, int Hq, int Hkv, float sl2, hipStream_t s) {
+    static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
+    constexpr int lds = AW_STAGES * AW_STAGE;
+    if (!attr_set.load(std::memory_order_acquire)) {
+        const int rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<CAUSAL, U>,
+                                                      hipFuncAttributeMaxDynamicSharedMemorySize, lds),
+                                  "hipFuncSetAttribute(attn_wide)");
+        if (rc) return rc;
+        attr_set.store(true, std::memory_order_release);
+    }
+    constexpr int BM = 128 * U;
+    const int n_qb = (N + BM - 1) / BM;
+    const long n_heads = (long)Hq * B;
+    if (n_heads * n_qb > 0x7fffffffL) return fail(VITCOP_EUNSUPPORTED, "attention: grid too large");
+    // (sample, head) pairs in flight together: few, so that their query blocks share K/V
+    // in L2, but enough to fill the 256 CUs twice over (measured: 32 from N = 2048 up)
+    const int group = std::max(32, (512 / n_qb + 7) / 8 * 8);
+    hipLaunchKernelGGL((attn_wide_kernel<CAUSAL, U>), dim3((unsigned)(n_heads * n_qb)), dim3(256), lds, s, q, k, v,
+                       out, lse, N, Hq, Hkv, sl2, n_qb, (int)n_heads, group);
+    return launch_status("attn_wide");
+}
 
 int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_t* out,
                 float* lse, int B, int N, int Hq, int Hkv, int d, float scale, int causal,
@@ -755,34 +803,17 @@ int launch_attn(const uint16_t* q, const uint16_t* k, const uint16_t* v, uint16_
     }
     // the wide kernel addresses K and V of one (sample, KV head) with 32-bit byte offsets
     const bool wide_ok = ((int64_t)N + AW_BN) * Hkv * AT_D * 2 < ((int64_t)1 << 32);
-    if (N >= AW_MIN_N && wide_ok) {
-        static std::atomic<bool> attr_set{false};   // set once; a second thread repeating the call is harmless
-        constexpr int lds = AW_STAGES * AW_STAGE;
-        if (!attr_set.load(std::memory_order_acquire)) {
-            int rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<true>,
-                                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-                                "hipFuncSetAttribute(attn_wide)");
-            if (rc) return rc;
-            rc = hip_status(hipFuncSetAttribute((const void*)attn_wide_kernel<false>,
-                                                hipFuncAttributeMaxDynamicSharedMemorySize, lds),
-                            "hipFuncSetAttribute(attn_wide)");
-            if (rc) return rc;
-            attr_set.store(true, std::memory_order_release);
-        }
-        const int n_qb = (N + AW_BM - 1) / AW_BM;
-        const long n_heads = (long)Hq * B;
-        if (n_heads * n_qb > 0x7fffffffL) return fail(VITCOP_EUNSUPPORTED, "attention: grid too large");
-        // (sample, head) pairs in flight together: few, so that their query blocks share K/V
-        // in L2, but enough to fill the 256 CUs twice over (measured: 32 from N = 2048 up)
-        const int group = std::max(32, (512 / n_qb + 7) / 8 * 8);
-        dim3 grid((unsigned)(n_heads * n_qb));
-        if (causal)
-            hipLaunchKernelGGL(attn_wide_kernel<true>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
-                               Hkv, sl2, n_qb, (int)n_heads, group);
-        else
-            hipLaunchKernelGGL(attn_wide_kernel<false>, grid, dim3(256), lds, s, q, k, v, out, lse, N, Hq,
-                               Hkv, sl2, n_qb, (int)n_heads, group);
-        return launch_status("attn_wide");
+    if (wide_ok) {
+        // Two query blocks per wavefront halve the LDS reads per MFMA, which is what long sequences need; one
+        // block halves the chain of MFMAs a wavefront runs per key tile and doubles the workgroups, which is
+        // what the lengths that survive pruning need (a few hundred tokens: one to six key tiles per workgroup,
+        // latency and not throughput): below 512 tokens, or while 256-query workgroups would not fill the CUs.
+        const long wgs2 = (long)Hq * B * ((N + AW_BM - 1) / AW_BM);
+        if (N >= AW_U2_MIN_N && wgs2 > AW_U2_MIN_WGS)
+            return causal ? launch_attn_wide<true, 2>(q, k, v, out, lse, B, N, Hq, Hkv, sl2, s)
+                          : launch_attn_wide<false, 2>(q, k, v, out, lse, B, N, Hq, Hkv, sl2, s);
+        return causal ? launch_attn_wide<true, 1>(q, k, v, out, lse, B, N, Hq, Hkv, sl2, s)
+                      : launch_attn_wide<false, 1>(q, k, v, out, lse, B, N, Hq, Hkv, sl2, s);
     }
     dim3 grid(Hq, B, (N + AT_BM - 1) / AT_BM);
     hipLaunchKernelGGL(attn_kernel<128>, grid, dim3(AT_THREADS), 0, s, q, k, v, out, lse, N, Hq, Hkv, sl2,

@@ -33,14 +33,27 @@ def test_causal_sizes(vc, N):
     assert np.abs(lse - ref_lse).max() < 1e-3
 
 
-# lengths around the point where the 256-query kernel takes over (N >= 512): block edges, ragged tails,
-# several blocks
+# with few heads a wavefront owns one 32-query block at every length: block edges (128 queries per workgroup),
+# ragged tails, several blocks, more key tiles than the ring has stages
 @pytest.mark.parametrize("N", [320, 321, 384, 500, 511, 512, 513, 640, 784, 1024, 1025, 1087, 1280, 1500, 2100])
 def test_causal_long(vc, N):
     t = I.qkv_tensors(150 + N, 1, N, 2, 2, 128)
     out, lse = run(vc, t)
     ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
     assert_attention_close(out, ref, f"N={N}")
+    assert np.abs(lse - ref_lse).max() < 1e-3
+
+
+# enough (sample, head) pairs that 256-query workgroups fill the chip: from 512 tokens on a wavefront then owns
+# two 32-query blocks.  Block edges, ragged first blocks, GQA, and the case just below the switch (one block)
+@pytest.mark.parametrize("B,N,Hq,Hkv,causal", [
+    (5, 512, 28, 4, True), (5, 513, 28, 4, True), (3, 777, 24, 24, True), (2, 1025, 28, 4, True),
+    (2, 1300, 24, 8, True), (2, 1300, 24, 8, False), (5, 511, 28, 4, True), (1, 1025, 28, 4, True)])
+def test_many_heads_two_query_blocks_per_wavefront(vc, B, N, Hq, Hkv, causal):
+    t = I.qkv_tensors(170 + N + B, B, N, Hq, Hkv, 128)
+    out, lse = run(vc, t, causal=causal)
+    ref, ref_lse = O.attention(t["q"], t["k"], t["v"], None, causal)
+    assert_attention_close(out, ref, f"B={B} N={N} {Hq}/{Hkv} causal={causal}")
     assert np.abs(lse - ref_lse).max() < 1e-3
 
 
@@ -66,16 +79,17 @@ def test_long_large_logits(vc):
     assert np.abs(lse - ref_lse).max() < 2e-3 * max(1.0, np.abs(ref_lse).max())
 
 
-@pytest.mark.parametrize("N,d", [(1500, 128), (300, 128), (700, 64)])
-def test_rising_scores_move_the_reference(vc, N, d):
+@pytest.mark.parametrize("N,d,H", [(1500, 128, 2), (300, 128, 2), (700, 64, 2), (1040, 128, 56)])
+def test_rising_scores_move_the_reference(vc, N, d, H):
     # scores that climb along the keys by several hundred in the exponent: the kernels raise their reference
     # maximum again and again (and rescale what they have accumulated), also inside diagonal tiles; softmax
     # weight sits on the last visible keys, so every row checks the state after all those moves
+    # (56 heads: two query blocks per wavefront, each with a reference of its own)
     g = np.random.default_rng(77 + N)
-    q = np.ones((1, N, 2, d), np.float32) + 0.05 * g.standard_normal((1, N, 2, d)).astype(np.float32)
+    q = np.ones((1, N, H, d), np.float32) + 0.05 * g.standard_normal((1, N, H, d)).astype(np.float32)
     ramp = (np.arange(N, dtype=np.float32) / N * 6.0)[None, :, None, None]
-    k = ramp * np.ones((1, N, 2, d), np.float32) + 0.05 * g.standard_normal((1, N, 2, d)).astype(np.float32)
-    t = {"q": I.f32_to_bf16_bits(q), "k": I.f32_to_bf16_bits(k), "v": I.normal_bf16(78 + N, 3, (1, N, 2, d))}
+    k = ramp * np.ones((1, N, H, d), np.float32) + 0.05 * g.standard_normal((1, N, H, d)).astype(np.float32)
+    t = {"q": I.f32_to_bf16_bits(q), "k": I.f32_to_bf16_bits(k), "v": I.normal_bf16(78 + N, 3, (1, N, H, d))}
     out, lse = run(vc, t)
     ref, ref_lse = O.attention(t["q"], t["k"], t["v"])
     assert ref_lse.max() - ref_lse.min() > 40.0                  # the logits do span hundreds of bits
