@@ -44,8 +44,9 @@ def parse():
                         "FETCH_SIZE / WRITE_SIZE counters)")
     p.add_argument("--mfma-kernels", type=int, default=0, metavar="N",
                    help="profiling mode: only N launches each of the matrix-core kernels at their bench shapes "
-                        "(K projection on random and on zero operands, attention at 4 x 2944 and at the video "
-                        "shape, the Stage II clustering with its Gram launch), then one JSON line of their times")
+                        "(K projection on random and on zero operands, attention at 4 x 2944, at the video shape "
+                        "and at the pruned 4 x 384, the Stage II clustering with its Gram launch), then one JSON "
+                        "line of their times")
     p.add_argument("--traffic", type=float, default=None,
                    help="measured HBM bytes per launch of the dominant kernel (from rocprofv3 --pmc runs), "
                         "echoed in roofline.traffic")
@@ -115,7 +116,8 @@ def main():
         kb_ = vc.vitcop_project(x2d, wk, want_sumsq=True)
         res["kproj_random_ms"] = ev_time(lambda: vc.vitcop_project(x2d, wk, want_sumsq=True, out=kb_), n_)
         res["kproj_TFLOPs"] = 2.0 * B * T * kd_ * D / res["kproj_random_ms"] / 1e9
-        for name, b_a, n_a, hq_a, hkv_a in (("attn_4x2944_mha32", B, T, Hq, Hkv), ("attn_1x6400_gqa28_4", 1, 6400, 28, 4)):
+        for name, b_a, n_a, hq_a, hkv_a in (("attn_4x2944_mha32", B, T, Hq, Hkv), ("attn_1x6400_gqa28_4", 1, 6400, 28, 4),
+                                             ("attn_4x384_mha32", B, Tp, Hq, Hkv)):
             qq = torch.randn((b_a, n_a, hq_a, d), dtype=torch.bfloat16, device="cuda")
             kk = torch.randn((b_a, n_a, hkv_a, d), dtype=torch.bfloat16, device="cuda")
             vv = torch.randn((b_a, n_a, hkv_a, d), dtype=torch.bfloat16, device="cuda")
