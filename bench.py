@@ -33,7 +33,9 @@ def parse():
     p = argparse.ArgumentParser()
     p.add_argument("--gpus", type=int, default=1)
     p.add_argument("--steps", type=int, default=30)
-    p.add_argument("--warmup", type=int, default=5)
+    p.add_argument("--warmup", type=int, default=30,
+                   help="untimed steps before the timed ones; the default spans the clock transient of the first "
+                        "15 ms or so under load after idle (steps 5 to 20 run up to 15 %% slower than the steady state)")
     p.add_argument("--keep", type=int, default=320, help="visual budget of the timed layer (of 2880)")
     p.add_argument("--no-schedule", action="store_true", help="skip the 32-layer step-wise schedule leg")
     p.add_argument("--schedule", action="store_true", help="run the schedule leg even with --no-extras (profiling)")
