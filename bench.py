@@ -477,8 +477,8 @@ def main():
         pos2 = torch.arange(640, dtype=torch.int32, device="cuda")[None].contiguous()
         dsp = vc.DecoderSchedulePlan(x2, pos2, w_dev, 32, 32, 128, 35, 576, I.CONFIG2_SCHEDULE)
         dup = vc.DecoderSchedulePlan(x2, pos2, w_dev, 32, 32, 128, 35, 576, ())
-        t_dsched = ev_time(dsp.run, 5, warm=2)
-        t_dunpr = ev_time(dup.run, 5, warm=2)
+        t_dsched = ev_time(dsp.run, 6, warm=3)
+        t_dunpr = ev_time(dup.run, 6, warm=3)
         out["decoder_schedule_config2"] = {"ms_pruned": t_dsched, "ms_unpruned": t_dunpr,
                                            "speedup": t_dunpr / t_dsched,
                                            "tokens_per_s": 640 / (t_dsched * 1e-3), "layers": 32, "F": F2}
@@ -496,7 +496,7 @@ def main():
             xp = x2[:, :T1].contiguous()          # (timing only: which visual tokens Stage I kept does not matter)
             pp = torch.arange(T1, dtype=torch.int32, device="cuda")[None].contiguous()
             plan = vc.DecoderSchedulePlan(xp, pp, w_dev, 32, 32, 128, 35, v1, ((2, v2), (22, v3)))
-            t_p = ev_time(plan.run, 5, warm=2)
+            t_p = ev_time(plan.run, 6, warm=3)
             paper[name] = {"visual_tokens": [v1, v2, v3], "ms": t_p, "speedup_vs_unpruned": t_dunpr / t_p,
                            "eq9_flops_ratio": eq9_ratio((64 + v1, 64 + v2, 64 + v3))}
             del plan, xp, pp
