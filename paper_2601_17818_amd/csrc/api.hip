@@ -289,10 +289,15 @@ static size_t gemm_scratch_upto(int M, int N, int K) {
     for (int m = 64; m < M && m <= 1024; m += 64) n = std::max(n, gemm_workspace_bytes(m, N, K));
     return n;
 }
-static size_t layer_gemm_scratch(int M_all, int M_kept, int D, int qd, int kd, int F) {
+static size_t layer_gemm_scratch(int M_all, int M_kept, int D, int qd, int kd, int F, int d = 0) {
     size_t n = gemm_scratch_upto(M_all, kd, D);                                  // K
     n = std::max(n, gemm_scratch_upto(M_kept, qd + kd, D));                      // Q and V
     n = std::max(n, gemm_scratch_upto(M_all, qd + 2 * kd, D));                   // K, Q and V of a layer that keeps all
+    if (d > 0) {                                                                 // the same with the rotary embedding
+        n = std::max(n, gemm_qkv_workspace_bytes(M_all, qd / d, kd / d, d, D));
+        for (int m = 64; m < M_all && m <= 1024; m += 64)
+            n = std::max(n, gemm_qkv_workspace_bytes(m, qd / d, kd / d, d, D));
+    }
     n = std::max(n, gemm_scratch_upto(M_kept, D, qd));                           // O
     if (F > 0) {
         n = std::max(n, gemm_scratch_upto(M_kept, 2 * F, D));                    // gate and up
@@ -658,7 +663,7 @@ size_t vitcop_decoder_layer_workspace_bytes(const vitcop_decoder_layer_t* L) {
     n += up256(B * Tp * qd * 2);                                        // attention output
     n += 2 * up256(B * Tp * D * 2);                                     // h1, b
     n += 3 * up256(B * Tp * F * 2);                                     // gate, up, silu(gate) * up
-    n += layer_gemm_scratch((int)(B * T), (int)(B * Tp), (int)D, (int)qd, (int)kd, (int)F);
+    n += layer_gemm_scratch((int)(B * T), (int)(B * Tp), (int)D, (int)qd, (int)kd, (int)F, L->d);
     return n;
 }
 
@@ -702,7 +707,7 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
     uint16_t* gate = c.take<uint16_t>((size_t)B * Tp * F * 2);
     uint16_t* up = c.take<uint16_t>((size_t)B * Tp * F * 2);
     uint16_t* act = c.take<uint16_t>((size_t)B * Tp * F * 2);
-    const size_t gs_bytes = layer_gemm_scratch(B * T, B * Tp, D, qd, kd, F);
+    const size_t gs_bytes = layer_gemm_scratch(B * T, B * Tp, D, qd, kd, F, L->d);
     void* gs = c.take<char>(gs_bytes);
     int32_t* idx = L->keep_idx ? L->keep_idx : idx_ws;
     int32_t* pos = L->positions_out ? L->positions_out : pos_ws;
@@ -714,13 +719,12 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
         if (rc) return rc;
     }
     // K of every token, squared norms (before the rotary embedding) as a side output
-    // (nothing to select and nobody asks for the norms: K, Q and V of all tokens go as one launch)
+    // (nothing to select and nobody asks for the norms: K, Q and V of all tokens go together, and the rotary
+    // embedding of q and k with them)
     const bool kqv_together = !want_sel;
     if (kqv_together) {
-        const uint16_t* const w3[3] = {L->wk, L->wq, L->wv};
-        uint16_t* const y3[3] = {k_all, qb, vb};
-        const int n3[3] = {kd, qd, kd};
-        rc = launch_gemm_triple_ws(a_all, D, w3, y3, n3, B * T, D, gs, gs_bytes, s);
+        rc = launch_gemm_qkv_rope_ws(a_all, D, L->wk, L->wq, L->wv, k_all, qb, vb, L->Hq, L->Hkv, L->d, L->positions,
+                                     L->theta, B * T, D, gs, gs_bytes, s);
     } else {
         rc = launch_gemm_ws(a_all, D, L->wk, k_all, kd, nullptr, 0, B * T, kd, D, parts, gs, gs_bytes, s);
     }
@@ -753,8 +757,10 @@ static int decoder_layer_run(const vitcop_decoder_layer_t* L, const uint16_t* a_
         rc = launch_gemm_pair_ws(as, D, L->wq, qb, qd, L->wv, vb, kd, B * Tp, D, gs, gs_bytes, s);
         if (rc) return rc;
     }
-    rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
-    if (rc) return rc;
+    if (!kqv_together) {
+        rc = launch_rope(qb, ks, ps, (int64_t)B * Tp, L->Hq, L->Hkv, L->d, L->theta, s);
+        if (rc) return rc;
+    }
     if (L->k_cache && L->v_cache && Tp > 0) {        // the layer's KV cache: rows [0,T') of each sample's block
         const size_t rowb = (size_t)Tp * kd * 2, pitch = (size_t)L->cache_capacity * kd * 2;
         rc = hip_status(hipMemcpy2DAsync(L->k_cache, pitch, ks, rowb, rowb, B, hipMemcpyDeviceToDevice, s),

@@ -695,7 +695,7 @@ static int launch_gemm_splitk(const uint16_t* x, int64_t x_stride, const uint16_
                               const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
                               void* ws, hipStream_t s, const uint16_t* ln_w, float eps, uint16_t* norm_out,
                               int64_t norm_stride, const uint16_t* w2 = nullptr, uint16_t* y2 = nullptr,
-                              int n_split = 0) {
+                              int n_split = 0, SkParts* parts_out = nullptr) {
     const SplitKPlan p = splitk_plan(M, N, K);
     float* part = static_cast<float*>(ws);
     int rc;
@@ -710,6 +710,10 @@ static int launch_gemm_splitk(const uint16_t* x, int64_t x_stride, const uint16_
 #undef VITCOP_SPLITK
     if (rc) return rc;
     const SkParts parts{part, 0, p.splits, N, M};
+    if (parts_out) {                             // the caller finishes the rows itself
+        *parts_out = parts;
+        return VITCOP_OK;
+    }
     const SkMats mats{{w, w2 ? w2 : w, w}, {y, w2 ? y2 : y, y}, {y_stride, y_stride, y_stride},
                       {w2 ? n_split : N, N, N}};
     return launch_partial_reduce(parts, N, mats, res, res_stride, sumsq_parts, ln_w, eps, norm_out, norm_stride,
@@ -890,6 +894,60 @@ int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1,
         }
     }
     return launch_gemm_pair(x, x_stride, w1, y1, N1, w2, y2, N2, M, K, s);
+}
+
+// Which way launch_gemm_qkv_rope_ws goes at M rows: 1 the three matrices in one few-row launch, 2 split-K of K
+// and of the Q/V pair with their partial sums side by side in ws, 0 the plain sequence.
+static int qkv_path(int M, int qd, int kd, int d, int K) {
+    if (d != 64 && d != 128) return 0;
+    if (gemm_skinny_workspace_bytes(M, kd + qd + kd, K) && kd % 128 == 0 && qd % 128 == 0) return 1;
+    if (splitk_workspace_bytes(M, kd, K) && splitk_workspace_bytes(M, qd + kd, K) && qd == kd && kd % 256 == 0)
+        return 2;
+    return 0;
+}
+
+size_t gemm_qkv_workspace_bytes(int M, int Hq, int Hkv, int d, int K) {
+    const int qd = Hq * d, kd = Hkv * d;
+    size_t need = std::max(gemm_workspace_bytes(M, kd, K), gemm_workspace_bytes(M, qd + kd, K));
+    need = std::max(need, gemm_workspace_bytes(M, kd + qd + kd, K));
+    if (qkv_path(M, qd, kd, d, K) == 2)
+        need = std::max(need, splitk_workspace_bytes(M, kd, K) + splitk_workspace_bytes(M, qd + kd, K));
+    return need;
+}
+
+int launch_gemm_qkv_rope_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wk, const uint16_t* wq,
+                            const uint16_t* wv, uint16_t* k, uint16_t* q, uint16_t* v, int Hq, int Hkv, int d,
+                            const int32_t* positions, float theta, int M, int K, void* ws, size_t ws_bytes,
+                            hipStream_t s) {
+    if (M == 0) return VITCOP_OK;
+    const int qd = Hq * d, kd = Hkv * d;
+    const uint16_t* const w3[3] = {wk, wq, wv};
+    uint16_t* const y3[3] = {k, q, v};
+    const int n3[3] = {kd, qd, kd};
+    const int path = ws ? qkv_path(M, qd, kd, d, K) : 0;
+    if (path == 1 && ws_bytes >= gemm_skinny_workspace_bytes(M, kd + qd + kd, K)) {
+        SkParts parts{};
+        int rc = launch_gemm_skinny3(x, x_stride, w3, y3, n3, M, K, ws, s, &parts);
+        if (rc) return rc;
+        if (parts.part == nullptr) return launch_rope(q, k, positions, M, Hq, Hkv, d, theta, s);   // written directly
+        const QkvParts P{{parts, parts, parts}, {0, kd, kd + qd}};
+        return launch_qkv_finish(P, k, q, v, Hq, Hkv, d, positions, theta, s);
+    }
+    const size_t need_k = splitk_workspace_bytes(M, kd, K), need_qv = splitk_workspace_bytes(M, qd + kd, K);
+    if (path == 2 && ws_bytes >= need_k + need_qv) {
+        SkParts pk{}, pqv{};
+        int rc = launch_gemm_splitk(x, x_stride, wk, k, kd, nullptr, 0, M, kd, K, nullptr, ws, s, nullptr, 0.f, nullptr,
+                                    0, nullptr, nullptr, 0, &pk);
+        if (rc) return rc;
+        rc = launch_gemm_splitk(x, x_stride, wq, q, qd, nullptr, 0, M, qd + kd, K, nullptr,
+                                static_cast<char*>(ws) + need_k, s, nullptr, 0.f, nullptr, 0, wv, v, qd, &pqv);
+        if (rc) return rc;
+        const QkvParts P{{pk, pqv, pqv}, {0, 0, qd}};
+        return launch_qkv_finish(P, k, q, v, Hq, Hkv, d, positions, theta, s);
+    }
+    const int rc = launch_gemm_triple_ws(x, x_stride, w3, y3, n3, M, K, ws, ws_bytes, s);
+    if (rc) return rc;
+    return launch_rope(q, k, positions, M, Hq, Hkv, d, theta, s);
 }
 
 // dist[b][i,j] = ||f_i - f_j||_2 in fp32 between the rows of each of `batch` bf16 matrices

@@ -23,6 +23,7 @@
 //     activation silu(gate) * up of the MLP.  The same reductions serve the split-K launches of the
 //     big-tile kernel (gemm.hip), whose partials are whole slices.
 #include <atomic>
+#include <cmath>
 #include "vitcop_internal.h"
 #include "device_utils.h"
 
@@ -325,6 +326,55 @@ __device__ __forceinline__ void sk_sum_tiles(const SkParts& P, int m, int n, flo
     });
 }
 
+// The same for two column chunks of one 128-column group at once, n .. n+8 and n+delta .. n+delta+8: both
+// chunks' loads of four tiles are in flight together.
+__device__ __forceinline__ void sk_sum_tiles2(const SkParts& P, int m, int n, int delta, float (&v)[8], float (&w)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) v[e] = w[e] = 0.f;
+    auto sum_range = [&](int i, int i_hi, auto tile) {
+        for (; i + 3 <= i_hi; i += 4) {
+            float4 a[4], b[4], c[4], d[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const float* p = tile(i + t);
+                a[t] = *reinterpret_cast<const float4*>(p);
+                b[t] = *reinterpret_cast<const float4*>(p + 4);
+                c[t] = *reinterpret_cast<const float4*>(p + delta);
+                d[t] = *reinterpret_cast<const float4*>(p + delta + 4);
+            }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                v[0] += a[t].x; v[1] += a[t].y; v[2] += a[t].z; v[3] += a[t].w;
+                v[4] += b[t].x; v[5] += b[t].y; v[6] += b[t].z; v[7] += b[t].w;
+                w[0] += c[t].x; w[1] += c[t].y; w[2] += c[t].z; w[3] += c[t].w;
+                w[4] += d[t].x; w[5] += d[t].y; w[6] += d[t].z; w[7] += d[t].w;
+            }
+        }
+        for (; i <= i_hi; ++i) {
+            const float* p = tile(i);
+            const float4 a = *reinterpret_cast<const float4*>(p), b = *reinterpret_cast<const float4*>(p + 4);
+            const float4 c = *reinterpret_cast<const float4*>(p + delta), d = *reinterpret_cast<const float4*>(p + delta + 4);
+            v[0] += a.x; v[1] += a.y; v[2] += a.z; v[3] += a.w;
+            v[4] += b.x; v[5] += b.y; v[6] += b.z; v[7] += b.w;
+            w[0] += c.x; w[1] += c.y; w[2] += c.z; w[3] += c.w;
+            w[4] += d.x; w[5] += d.y; w[6] += d.z; w[7] += d.w;
+        }
+    };
+    if (P.units_q == 0) {
+        sum_range(0, P.units_r - 1, [&](int sl) { return P.part + ((int64_t)sl * P.M + m) * P.upg + n; });
+        return;
+    }
+    const int grp = n / SK_COLS;
+    auto owner = [&](int u) {
+        const int big = P.units_r * (P.units_q + 1);
+        return u < big ? u / (P.units_q + 1) : P.units_r + (u - big) / P.units_q;
+    };
+    sum_range(owner(grp * P.upg), owner((grp + 1) * P.upg - 1), [&](int i) {
+        const int seg = sk_first_unit(i, P.units_q, P.units_r) / P.upg == grp ? 0 : 1;
+        return P.part + ((int64_t)(2 * i + seg) * P.M + m) * SK_COLS + (n & (SK_COLS - 1));
+    });
+}
+
 // y[m, n..n+8) = bf16(sum of the partial tiles of n's column group, in workgroup order, + residual);
 // one thread per 8 columns, 16 consecutive lanes per 128-column group, which also yields that
 // group's sum of squares of the rounded outputs.  P = workgroups of the first kernel.
@@ -460,6 +510,83 @@ __global__ __launch_bounds__(256) void gemm_skinny_reduce_silu_kernel(
         make_uint4(gated(g.x, u.x), gated(g.y, u.y), gated(g.z, u.z), gated(g.w, u.w));
 }
 
+// q, k and v of a decoder layer straight from the partial sums of their projections (up to three sets of
+// partials: the three matrices of one few-row launch, or K from one split-K launch and Q, V from another),
+// with the rotary embedding of q and k: what the plain reductions followed by rope_kernel compute, value for
+// value (sum in slice order, rounded to bf16, turned in fp32 at positions[m], rounded), in one launch.
+// A thread owns 16 columns: of a q or k head the 8 low channels from 8 j on and the 8 high channels they pair
+// with (the angles are computed once per pair, as in rope_kernel); of v 16 consecutive columns.
+__global__ __launch_bounds__(256) void qkv_finish_kernel(
+    QkvParts P, uint16_t* __restrict__ k, uint16_t* __restrict__ q, uint16_t* __restrict__ v, int Hq, int Hkv,
+    int d, const int32_t* __restrict__ positions, float rope_c) {
+    const int g16 = d / 16, M = P.parts[0].M;
+    const int units = (Hq + 2 * Hkv) * g16;
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int m = (int)(id / units);
+    if (m >= M) return;
+    int unit = (int)(id - (int64_t)m * units);
+    int mat = 0;                                         // 0 k, 1 q, 2 v
+    if (unit >= Hkv * g16) {
+        unit -= Hkv * g16;
+        mat = 1;
+        if (unit >= Hq * g16) {
+            unit -= Hq * g16;
+            mat = 2;
+        }
+    }
+    const int head = unit / g16, j = unit - head * g16;
+    const int c0 = mat == 2 ? 16 * unit : head * d + 8 * j;
+    const int c1 = mat == 2 ? c0 + 8 : c0 + d / 2;
+    const SkParts& parts = mat == 0 ? P.parts[0] : (mat == 1 ? P.parts[1] : P.parts[2]);
+    const int col0 = mat == 0 ? P.col0[0] : (mat == 1 ? P.col0[1] : P.col0[2]);
+    // the angles first (they depend on the position alone): the partial sums' loads are in flight meanwhile
+    float sn[8], cs[8];
+    if (mat != 2) {
+        const float pos = (float)positions[m];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float inv_freq = __builtin_exp2f((float)(8 * j + e) * rope_c);
+            sincosf(pos * inv_freq, &sn[e], &cs[e]);
+        }
+    }
+    float a[8], bvals[8];
+    sk_sum_tiles2(parts, m, col0 + c0, c1 - c0, a, bvals);
+    uint32_t lw[4], hw[4];
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        lw[p] = pack_bf16(a[2 * p], a[2 * p + 1]);
+        hw[p] = pack_bf16(bvals[2 * p], bvals[2 * p + 1]);
+    }
+    const int width = mat == 1 ? Hq * d : Hkv * d;
+    uint16_t* dst = (mat == 0 ? k : (mat == 1 ? q : v)) + (int64_t)m * width;
+    if (mat != 2) {
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            float rl[2], rh[2];
+#pragma unroll
+            for (int e = 0; e < 2; ++e) {
+                const float lo = e ? bf16_hi(lw[p]) : bf16_lo(lw[p]);
+                const float hi = e ? bf16_hi(hw[p]) : bf16_lo(hw[p]);
+                rl[e] = lo * cs[2 * p + e] - hi * sn[2 * p + e];
+                rh[e] = hi * cs[2 * p + e] + lo * sn[2 * p + e];
+            }
+            lw[p] = pack_bf16(rl[0], rl[1]);
+            hw[p] = pack_bf16(rh[0], rh[1]);
+        }
+    }
+    *reinterpret_cast<uint4*>(dst + c0) = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+    *reinterpret_cast<uint4*>(dst + c1) = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+}
+
+int launch_qkv_finish(const QkvParts& P, uint16_t* k, uint16_t* q, uint16_t* v, int Hq, int Hkv, int d,
+                      const int32_t* positions, float theta, hipStream_t s) {
+    const int64_t threads = (int64_t)P.parts[0].M * (Hq + 2 * Hkv) * (d / 16);
+    if (threads == 0) return VITCOP_OK;
+    hipLaunchKernelGGL(qkv_finish_kernel, dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, s, P, k, q, v, Hq,
+                       Hkv, d, positions, -2.0f * std::log2(theta) / (float)d);
+    return launch_status("qkv_finish");
+}
+
 // With this many column groups one workgroup per group already keeps most CUs streaming, at a
 // higher rate each, and the partial tiles and their reduction are saved.
 constexpr int SK_DIRECT_GROUPS = 128;
@@ -536,7 +663,7 @@ bool partial_reduce_fuses_norm(int N) { return N % 8 == 0 && N <= 8 * 256 * SK_N
 static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats& mats, const uint16_t* res,
                               int64_t res_stride, int M, int N, int K, float* sumsq_parts, void* ws, hipStream_t s,
                               const uint16_t* ln_w, float eps, uint16_t* norm_out, int64_t norm_stride,
-                              uint16_t* gated_out = nullptr) {
+                              uint16_t* gated_out = nullptr, SkParts* parts_out = nullptr) {
     const bool direct = gated_out == nullptr && skinny_direct(M, N, sumsq_parts != nullptr);
     const int wgs = direct ? (N + SK_COLS - 1) / SK_COLS : skinny_workgroups(M, N, K);
     float* part = direct ? nullptr : static_cast<float*>(ws);
@@ -551,8 +678,10 @@ static int launch_skinny_mats(const uint16_t* x, int64_t x_stride, const SkMats&
         rc = launch_skinny_cfg<6>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
     else
         rc = launch_skinny_cfg<8>(x, x_stride, mats, K, M, N, K, wgs, units_q, units_r, part, res, res_stride, s);
+    if (parts_out) *parts_out = SkParts{direct ? nullptr : part, units_q, units_r, K / SK_UNIT, M};
     if (rc || direct) return rc;
     const SkParts parts{part, units_q, units_r, K / SK_UNIT, M};
+    if (parts_out) return VITCOP_OK;             // the caller finishes the rows itself
     return launch_partial_reduce(parts, N, mats, res, res_stride, sumsq_parts, ln_w, eps, norm_out, norm_stride,
                                  gated_out, s);
 }
@@ -572,10 +701,10 @@ int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, u
 // Three projections of the same input in one launch: y[i] = x w[i]^T, [M, n[i]] dense (n[0] and n[1]
 // multiples of 128).
 int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
-                        const int n[3], int M, int K, void* ws, hipStream_t s) {
+                        const int n[3], int M, int K, void* ws, hipStream_t s, SkParts* parts_out) {
     SkMats mats{{w[0], w[1], w[2]}, {y[0], y[1], y[2]}, {n[0], n[1], n[2]}, {n[0], n[0] + n[1], n[0] + n[1] + n[2]}};
     return launch_skinny_mats(x, x_stride, mats, nullptr, 0, M, n[0] + n[1] + n[2], K, nullptr, ws, s, nullptr, 0.f,
-                              nullptr, 0);
+                              nullptr, 0, nullptr, parts_out);
 }
 
 // out = silu(x wg^T) * (x wu^T) [M, F] (F a multiple of 128): both projections in one launch, the

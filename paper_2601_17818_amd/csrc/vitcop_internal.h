@@ -83,6 +83,15 @@ int launch_gemm_gated_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wg
 int launch_gemm_pair_ws(const uint16_t* x, int64_t x_stride, const uint16_t* w1, uint16_t* y1, int N1,
                         const uint16_t* w2, uint16_t* y2, int N2, int M, int K, void* ws, size_t ws_bytes,
                         hipStream_t s);
+// k, q, v = x Wk^T, x Wq^T, x Wv^T (dense [M, Hkv d], [M, Hq d], [M, Hkv d]) with the rotary embedding of q
+// and k at positions[m]: where the projections leave partial sums (few rows, or split-K of K and of the Q/V
+// pair) one launch adds them up and turns q and k; otherwise launch_gemm_triple_ws and rope_kernel.
+// gemm_qkv_workspace_bytes: what ws must hold for every path this may take at M rows.
+size_t gemm_qkv_workspace_bytes(int M, int Hq, int Hkv, int d, int K);
+int launch_gemm_qkv_rope_ws(const uint16_t* x, int64_t x_stride, const uint16_t* wk, const uint16_t* wq,
+                            const uint16_t* wv, uint16_t* k, uint16_t* q, uint16_t* v, int Hq, int Hkv, int d,
+                            const int32_t* positions, float theta, int M, int K, void* ws, size_t ws_bytes,
+                            hipStream_t s);
 // gemm_skinny.hip
 // Up to three weight matrices side by side (projections of the same input in one launch): matrix i
 // covers the columns [n_end[i-1], n_end[i]) of the launch (boundaries multiples of 128; unused
@@ -101,6 +110,16 @@ struct SkParts {
     const float* part;
     int units_q, units_r, upg, M;
 };
+// k, q and v of a layer (in this order) as partial sums: for each the launch it belongs to and its first
+// column there.
+struct QkvParts {
+    SkParts parts[3];
+    int col0[3];
+};
+// k, q, v [M, Hkv d], [M, Hq d], [M, Hkv d] (dense) = the partial sums added in slice order and rounded to
+// bf16, q and k then turned by the rotary embedding at positions[m] (rope_kernel's arithmetic).
+int launch_qkv_finish(const QkvParts& P, uint16_t* k, uint16_t* q, uint16_t* v, int Hq, int Hkv, int d,
+                      const int32_t* positions, float theta, hipStream_t s);
 
 int launch_partial_reduce(const SkParts& parts, int N, const SkMats& mats, const uint16_t* res, int64_t res_stride,
                           float* sumsq_parts, const uint16_t* ln_w, float eps, uint16_t* norm_out,
@@ -137,8 +156,10 @@ size_t gemm_skinny_workspace_bytes(int M, int N, int K);
 bool gemm_skinny_fuses_norm(int M, int N, int K);
 int launch_gemm_skinny_gated(const uint16_t* x, int64_t x_stride, const uint16_t* wg, const uint16_t* wu, int F,
                              uint16_t* out, int M, int K, void* ws, hipStream_t s);
+// (parts_out != nullptr: the rows are left as partial sums, described there, for the caller to finish;
+// parts_out->part == nullptr afterwards means the launch wrote its outputs directly.)
 int launch_gemm_skinny3(const uint16_t* x, int64_t x_stride, const uint16_t* const w[3], uint16_t* const y[3],
-                        const int n[3], int M, int K, void* ws, hipStream_t s);
+                        const int n[3], int M, int K, void* ws, hipStream_t s, SkParts* parts_out = nullptr);
 int launch_gemm_skinny(const uint16_t* x, int64_t x_stride, const uint16_t* w, uint16_t* y, int64_t y_stride,
                        const uint16_t* res, int64_t res_stride, int M, int N, int K, float* sumsq_parts,
                        const uint16_t* w2, uint16_t* y2, int n_split, void* ws, hipStream_t s,
