@@ -175,6 +175,35 @@ def test_decoder_schedule_matches_oracle(vc):
     assert np.array_equal(plan0.positions.cpu().numpy(), pos)
 
 
+@pytest.mark.parametrize("B,T,D,Hq,Hkv", [
+    (1, 400, 1024, 2, 2),      # 256 < rows <= 768: K and the Q/V pair as split-K launches, finished in one launch
+    (2, 180, 1024, 2, 2),      # the same with two samples' rows (and positions) side by side
+    (1, 200, 1024, 2, 2),      # few rows: the three matrices in one launch, finished in one launch
+    (2, 100, 512, 4, 4),
+    (1, 400, 1024, 4, 2)])     # grouped-query heads: the plain sequence (projections, then the rotary kernel)
+def test_layers_that_keep_all_tokens_finish_qkv_in_one_launch(vc, B, T, D, Hq, Hkv):
+    # layers of a schedule that prune nothing project K, Q and V together and, where those projections leave
+    # partial sums, add them up, round them and turn q and k by the rotary embedding in a single launch: the
+    # caches (K after the embedding, V) of both layers and the output against the oracle
+    d, F, vs, nv = 128, 768, 10, T - 40
+    h, layers = schedule_case(9700 + T + D + Hq, B, T, D, Hq, Hkv, d, F, vs, nv, 2)
+    pos = np.stack([np.sort(np.random.default_rng(40 + b).choice(4 * T, T, replace=False)) for b in range(B)]).astype(np.int32)
+    wd = [{k: dev(v) for k, v in w.items()} for w in layers]
+    caches = [(torch.zeros((B, T, Hkv, d), dtype=torch.bfloat16, device="cuda"),
+               torch.zeros((B, T, Hkv, d), dtype=torch.bfloat16, device="cuda")) for _ in range(2)]
+    plan = vc.DecoderSchedulePlan(dev(h), torch.from_numpy(pos).cuda(), wd, Hq, Hkv, d, vs, nv, (), caches=caches)
+    plan.run()
+    torch.cuda.synchronize()
+    ref = Dc.decoder_schedule(h, layers, (), Hq, Hkv, d, vs, nv, pos)
+    # layer 0's K and V depend on the inputs alone: within one bf16 ulp of the head's largest entry (K: the
+    # turn mixes a pair; both: a normalised input that rounds the other way on one side moves the fp32 sum
+    # by 2^-8 of one product, whatever the size of the sum)
+    for which, what in ((0, "K cache"), (1, "V cache")):
+        got, want = O.bf16_to_f64(host_bits(caches[0][which])), O.bf16_to_f64(ref["caches"][0][which])
+        assert np.all(np.abs(got - want) <= np.maximum(np.abs(want).max(axis=-1, keepdims=True), 1e-6) * 2.0 ** -7), what
+    assert_stream_close(host_f64(plan.y), ref["y"], "two layers that keep all tokens")
+
+
 def full_case(seed, vs, n, tail, D, Hq, Hkv, d, F, n_layers, grid, regions):
     """Text tokens ~ N(0,1); visual hidden states = planted spatial regions (vic_inputs); small output
     projections keep the residual stream close to the input, so the regions survive the first layers."""
